@@ -1,0 +1,171 @@
+/*
+ * q8nmt.h -- C ABI of the MI355X (gfx950) library for 8-bit GRU-NMT decoding.
+ *
+ * The library implements the hot path of "Pieces of Eight: 8-bit Neural Machine
+ * Translation" (Quinn & Ballesteros): Section 3's product -- weights and inputs as
+ * 8-bit integers, integer accumulation, 32-bit float result, one routine for matrix
+ * x vector and matrix x narrow matrix, bias / sigmoid / tanh kept in float -- driving
+ * Section 2's model: bidirectional GRU encoder (Eq. 1), conditional GRU decoder with
+ * attention (Eq. 3-6) and the two-layer output network with softmax (Eq. 2).
+ *
+ * Quantization (Section 3 leaves the scheme open; this is the fixed reading):
+ * symmetric max-abs, scale = max|v| / 127, code = clamp(rint(v * (127 / max|v|)),
+ * -127, 127) with round-half-to-even, all in IEEE fp32; if max|v| < 2^-100 the scale
+ * is 1 and every code 0.  One scale per weight matrix, one per activation vector
+ * (per column of a narrow matrix).  Accumulation is exact int32.  The float result is
+ * y_i = (float)acc_i * (s_w * s_x), then + bias_i as a separate fp32 add.
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer unless its name ends in _host.  All device
+ *    buffers, the workspace included, are owned by the caller and only borrowed for
+ *    the duration of the enqueued work.  Structs passed by pointer are read during
+ *    the call and need not outlive it.
+ *  - Matrices are row-major with the reduction dimension contiguous.  int8 weight
+ *    matrices: base 16-byte aligned, ld % 16 == 0, pad columns [cols, ld) zero.
+ *    fp32 vectors: 16-byte aligned base, leading dimensions % 4 == 0.  Batches are
+ *    vector-major: [n x dim], each vector contiguous.
+ *  - Calls enqueue work on the stream given to q8_create and return without waiting,
+ *    except q8_quantize_matrix (load time; it returns the scale to the host).
+ *  - Every function returns a q8_status.  Argument errors are detected before
+ *    anything is launched; nothing aborts or throws.  q8_last_error gives text.
+ *  - Limits: 1 <= cols <= ld <= 16384 for products (the int32 sum cannot overflow
+ *    below 133143 columns); narrow products take n <= 8 vectors in one pass over the
+ *    weights and 8 < n <= 1024 on the MFMA path; GRU / decoder / output calls take
+ *    1 <= n <= 8 hypotheses; source length l <= 1024; top-k <= 16.
+ *  - Non-finite inputs give unspecified results (no fault).
+ *  - A context is tied to one stream and one workspace and is not thread-safe.  Calls
+ *    that use the workspace (everything but q8_gemv and n <= 8 q8_gemm_narrow) must
+ *    not overlap on the GPU; on one stream they cannot.
+ *  - Taps: optional (NULL) device outputs of the integer tensors of a product, so that
+ *    results can be checked bit for bit: xq [n x cols] int8 (ld = cols), xscale [n],
+ *    acc [n x rows] int32.
+ */
+#ifndef Q8NMT_H
+#define Q8NMT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int q8_status;
+enum {
+    Q8_OK = 0,
+    Q8_ERR_NULL = 1,       /* a required pointer is NULL */
+    Q8_ERR_SHAPE = 2,      /* a dimension is non-positive, inconsistent or above a limit */
+    Q8_ERR_ALIGN = 3,      /* base pointer or leading dimension violates the alignment rule */
+    Q8_ERR_WORKSPACE = 4,  /* the context's workspace is too small for this call */
+    Q8_ERR_DEVICE = 5      /* a HIP call failed; see q8_last_error */
+};
+
+typedef struct q8_ctx q8_ctx;
+
+/* An int8 weight matrix: device data, host-side scale (known at load time). */
+typedef struct {
+    const int8_t *data;
+    int rows, cols, ld;
+    float scale;
+} q8_mat;
+
+typedef struct {
+    int8_t *xq;
+    float *xscale;
+    int32_t *acc;
+} q8_taps;
+
+/* One GRU cell.  Gate row blocks in the order r, z, n; biases [3H] may be NULL. */
+typedef struct {
+    q8_mat Wx;             /* [3H x I] */
+    q8_mat Wh;             /* [3H x H] */
+    const float *bx, *bh;
+} q8_gru_weights;
+
+/* The conditional GRU of Eq. 3-6: GRU r, attention (u and v; w enters through P), GRU q. */
+typedef struct {
+    q8_gru_weights r;      /* Wx [3H x E], Wh [3H x H] */
+    q8_mat att_U;          /* u: [A x H] */
+    const float *att_v;    /* v: [A] fp32 */
+    q8_gru_weights q;      /* Wx [3H x C], Wh [3H x H] */
+} q8_cgru_weights;
+
+/* First layer of the output network g of Eq. 2. */
+typedef struct {
+    q8_mat W_s, W_y, W_c;  /* [R x H], [R x E], [R x C] */
+    const float *b_t;      /* [R] or NULL */
+} q8_readout_weights;
+
+/* Bytes of workspace that make every call below succeed for n <= max_n vectors,
+ * source length <= max_l, matrices of at most max_rows rows and max_ld columns. */
+size_t q8_workspace_bytes(int max_n, int max_l, int max_rows, int max_ld);
+
+/* Creates a context bound to hip_stream (a hipStream_t; NULL = the default stream)
+ * and to the caller's device workspace (256-byte aligned).  Allocates host memory
+ * only.  The first 4 KiB of the workspace are zeroed on the stream here and are kept
+ * zero between calls by the kernels that use them as arrival counters. */
+q8_status q8_create(q8_ctx **out, void *hip_stream, void *workspace, size_t workspace_bytes);
+q8_status q8_destroy(q8_ctx *ctx);
+const char *q8_last_error(const q8_ctx *ctx);
+
+/* Section 3, weights ("models as is", Section 1): W fp32 [rows x cols] (ld_in floats)
+ * -> Wq int8 [rows x ld_out] with zeroed pad columns, one scale for the matrix written
+ * to *scale_out_host.  Synchronous: waits for the stream. */
+q8_status q8_quantize_matrix(q8_ctx *ctx, const float *W, int rows, int cols, int ld_in,
+                             int8_t *Wq_out, int ld_out, float *scale_out_host);
+
+/* Section 3, matrix x vector: y[rows] = (float)(Wq . quantize(x)) * (s_w * s_x) + bias.
+ * bias [rows] may be NULL.  One launch; x is quantized inside the kernel. */
+q8_status q8_gemv(q8_ctx *ctx, const q8_mat *W, const float *x, const float *bias, float *y,
+                  const q8_taps *taps);
+
+/* Section 3, matrix x narrow matrix (the same routine, P small): n vectors X [n x ldx]
+ * -> Y [n x ldy], each vector with its own scale; bit-identical to n q8_gemv calls.
+ * n <= 8: one streaming pass over W.  n > 8: vectors are quantized into the workspace
+ * and the product runs on the int8 matrix cores. */
+q8_status q8_gemm_narrow(q8_ctx *ctx, const q8_mat *W, const float *X, int n, int ldx,
+                         const float *bias, float *Y, int ldy, const q8_taps *taps);
+
+/* GRU cell of Eq. 1 / Eq. 3-4 for n vectors: gx = Wx q(x) + bx, gh = Wh q(h) + bh,
+ * r = sigmoid(gx_r + gh_r), z = sigmoid(gx_z + gh_z), n = tanh(gx_n + r * gh_n),
+ * h' = (1 - z) * n + z * h (h in fp32).  x [n x I], h_prev [n x H], h_out [n x H]
+ * (must not alias h_prev).  taps: NULL or two entries, [0] for the Wx product and
+ * [1] for the Wh product. */
+q8_status gru_step_q8(q8_ctx *ctx, const q8_gru_weights *g, const float *x, const float *h_prev,
+                      int n, float *h_out, const q8_taps *taps2);
+
+/* One conditional-GRU decoder step (Eq. 3-6) for n_beam hypotheses of one sentence:
+ * s' = r(y, s_prev); a = u q(s'); e_i = v . tanh(P_i + a); alpha = softmax(e);
+ * H_t = sum_i alpha_i h_i; s = q(H_t, s').  P [l x A] is w(h_i) + b_att for every
+ * source position (q8_gemm_narrow over enc_h), enc_h [l x C].  y_emb [n x E],
+ * s_prev [n x H] -> s_out [n x H], ctx_out [n x C]; alpha_out [n x l] and
+ * s_mid_out [n x H] may be NULL.  taps5: NULL or five entries for the products
+ * r.Wx(y), r.Wh(s_prev), att_U(s'), q.Wx(H_t), q.Wh(s'). */
+q8_status cgru_decoder_step_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h,
+                               int l, const float *y_emb, const float *s_prev, int n_beam,
+                               float *s_out, float *ctx_out, float *alpha_out, float *s_mid_out,
+                               const q8_taps *taps5);
+
+/* Output network g of Eq. 2 for n_beam hypotheses.  If ro != NULL:
+ * t = tanh(((W_s q(s) + W_y q(y_emb)) + W_c q(ctx)) + b_t), else t = t_in [n x R].
+ * logits = W_out q(t) + b_out; lse = log sum exp(logits); the k best entries per
+ * hypothesis, ordered by (logit descending, index ascending), are returned as
+ * topk_idx [n x k] and topk_logp [n x k] = logit - lse.  logits [n x rows(W_out)],
+ * lse [n] and t_out [n x R] may be NULL.  taps4: NULL or four entries for the products
+ * W_s(s), W_y(y), W_c(ctx), W_out(t) (the first three unused when ro == NULL). */
+q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                           const float *s, const float *y_emb, const float *ctx_vec, const float *t_in,
+                           int n_beam, int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx,
+                           float *t_out, const q8_taps *taps4);
+
+/* Bidirectional GRU encoder of Eq. 1 over l embedding vectors X [l x E]:
+ * enc_h [l x 2H], backward state in columns [0,H), forward state in [H,2H); both
+ * recurrences start from zero.  The input products for all positions run as one
+ * narrow/MFMA product per direction, the l recurrent steps run in sequence. */
+q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights *bwd,
+                    const float *X, int l, float *enc_h);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,262 @@
+"""ctypes binding of libq8nmt.so: argument marshalling only.
+
+Every function below has the name of the C entry point it calls (see include/q8nmt.h
+for semantics, layouts and limits).  Tensors are torch CUDA tensors used as plain
+device buffers; results come back in freshly allocated (or caller-supplied) tensors.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
+
+__all__ = ["Q8Error", "Context", "Mat", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
+           "q8_quantize_matrix", "q8_gemv", "q8_gemm_narrow", "gru_step_q8", "cgru_decoder_step_q8",
+           "output_logits_q8", "q8_encode", "q8_workspace_bytes", "LIB_PATH"]
+LIB_PATH = _LIB_PATH
+
+STATUS = {0: "Q8_OK", 1: "Q8_ERR_NULL", 2: "Q8_ERR_SHAPE", 3: "Q8_ERR_ALIGN", 4: "Q8_ERR_WORKSPACE", 5: "Q8_ERR_DEVICE"}
+
+
+class Q8Error(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("%s: %s" % (STATUS.get(code, code), text))
+        self.code = code
+
+
+class _Mat(C.Structure):
+    _fields_ = [("data", C.c_void_p), ("rows", C.c_int), ("cols", C.c_int), ("ld", C.c_int), ("scale", C.c_float)]
+
+
+class _Taps(C.Structure):
+    _fields_ = [("xq", C.c_void_p), ("xscale", C.c_void_p), ("acc", C.c_void_p)]
+
+
+class _Gru(C.Structure):
+    _fields_ = [("Wx", _Mat), ("Wh", _Mat), ("bx", C.c_void_p), ("bh", C.c_void_p)]
+
+
+class _Cgru(C.Structure):
+    _fields_ = [("r", _Gru), ("att_U", _Mat), ("att_v", C.c_void_p), ("q", _Gru)]
+
+
+class _Readout(C.Structure):
+    _fields_ = [("W_s", _Mat), ("W_y", _Mat), ("W_c", _Mat), ("b_t", C.c_void_p)]
+
+
+_lib = None
+
+
+def load_library():
+    """Loads the built HIP library; there is no fallback if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError("libq8nmt.so is not built: run `python -m paper_1804_05038_amd.build` "
+                              "(or __graft_entry__.build()) first; there is no CPU fallback")
+        lib = C.CDLL(_LIB_PATH)
+        lib.q8_workspace_bytes.restype = C.c_size_t
+        lib.q8_workspace_bytes.argtypes = [C.c_int] * 4
+        lib.q8_last_error.restype = C.c_char_p
+        lib.q8_last_error.argtypes = [C.c_void_p]
+        lib.q8_create.argtypes = [C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p, C.c_size_t]
+        lib.q8_destroy.argtypes = [C.c_void_p]
+        vp, ci = C.c_void_p, C.c_int
+        lib.q8_quantize_matrix.argtypes = [vp, vp, ci, ci, ci, vp, ci, C.POINTER(C.c_float)]
+        lib.q8_gemv.argtypes = [vp, C.POINTER(_Mat), vp, vp, vp, C.POINTER(_Taps)]
+        lib.q8_gemm_narrow.argtypes = [vp, C.POINTER(_Mat), vp, ci, ci, vp, vp, ci, C.POINTER(_Taps)]
+        lib.gru_step_q8.argtypes = [vp, C.POINTER(_Gru), vp, vp, ci, vp, C.POINTER(_Taps)]
+        lib.cgru_decoder_step_q8.argtypes = [vp, C.POINTER(_Cgru), vp, vp, ci, vp, vp, ci, vp, vp, vp, vp, C.POINTER(_Taps)]
+        lib.output_logits_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, vp, ci, ci,
+                                         vp, vp, vp, vp, vp, C.POINTER(_Taps)]
+        lib.q8_encode.argtypes = [vp, C.POINTER(_Gru), C.POINTER(_Gru), vp, ci, vp]
+        _lib = lib
+    return _lib
+
+
+def q8_workspace_bytes(max_n=8, max_l=64, max_rows=65536, max_ld=2048):
+    return load_library().q8_workspace_bytes(max_n, max_l, max_rows, max_ld)
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _dev_f32(t, device):
+    if t is None:
+        return None
+    return torch.as_tensor(t, dtype=torch.float32).to(device).contiguous()
+
+
+class Context:
+    """q8_create / q8_destroy: a stream and a caller-owned workspace."""
+
+    def __init__(self, device="cuda:0", workspace_bytes=None, stream=None):
+        self.lib = load_library()
+        self.device = torch.device(device)
+        if workspace_bytes is None:
+            workspace_bytes = q8_workspace_bytes()
+        self.workspace = torch.empty(workspace_bytes, dtype=torch.uint8, device=self.device)
+        self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
+        h = C.c_void_p()
+        st = self.lib.q8_create(C.byref(h), C.c_void_p(self.stream.cuda_stream), _ptr(self.workspace),
+                                C.c_size_t(workspace_bytes))
+        if st != 0:
+            raise Q8Error(st, "q8_create failed")
+        self.handle = h
+
+    def check(self, st):
+        if st != 0:
+            raise Q8Error(st, self.lib.q8_last_error(self.handle).decode())
+
+    def close(self):
+        if getattr(self, "handle", None):
+            self.lib.q8_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def f32(self, a):
+        return _dev_f32(a, self.device)
+
+    def empty(self, *shape, dtype=torch.float32):
+        return torch.empty(*shape, dtype=dtype, device=self.device)
+
+
+class Mat:
+    """q8_mat: int8 device matrix [rows x ld] plus its host-side scale."""
+
+    def __init__(self, data, cols, scale):
+        self.data = data
+        self.rows, self.ld = data.shape
+        self.cols = cols
+        self.scale = float(scale)
+        self.c = _Mat(data.data_ptr(), self.rows, cols, self.ld, self.scale)
+
+
+class _TapSet:
+    def __init__(self, ctx, specs):
+        """specs: list of (n, cols, rows) per product."""
+        self.arr = (_Taps * len(specs))()
+        self.t = []
+        for i, (n, cols, rows) in enumerate(specs):
+            xq = ctx.empty(n, cols, dtype=torch.int8)
+            xs = ctx.empty(n)
+            acc = ctx.empty(n, rows, dtype=torch.int32)
+            self.arr[i] = _Taps(xq.data_ptr(), xs.data_ptr(), acc.data_ptr())
+            self.t.append({"xq": xq, "xscale": xs, "acc": acc})
+
+
+def q8_quantize_matrix(ctx, W, ld_out=None):
+    W = ctx.f32(W)
+    rows, cols = W.shape
+    ld_out = (cols + 15) // 16 * 16 if ld_out is None else ld_out
+    Wq = ctx.empty(rows, ld_out, dtype=torch.int8)
+    scale = C.c_float()
+    ctx.check(ctx.lib.q8_quantize_matrix(ctx.handle, _ptr(W), rows, cols, W.stride(0), _ptr(Wq), ld_out, C.byref(scale)))
+    return Mat(Wq, cols, scale.value)
+
+
+def q8_gemv(ctx, W, x, bias=None, y=None, taps=False):
+    y = ctx.empty(W.rows) if y is None else y
+    ts = _TapSet(ctx, [(1, W.cols, W.rows)]) if taps else None
+    ctx.check(ctx.lib.q8_gemv(ctx.handle, C.byref(W.c), _ptr(x), _ptr(bias), _ptr(y), ts.arr if ts else None))
+    return (y, ts.t[0]) if taps else y
+
+
+def q8_gemm_narrow(ctx, W, X, bias=None, Y=None, taps=False):
+    n = X.shape[0]
+    Y = ctx.empty(n, W.rows) if Y is None else Y
+    ts = _TapSet(ctx, [(n, W.cols, W.rows)]) if taps else None
+    ctx.check(ctx.lib.q8_gemm_narrow(ctx.handle, C.byref(W.c), _ptr(X), n, X.stride(0), _ptr(bias), _ptr(Y),
+                                     Y.stride(0), ts.arr if ts else None))
+    return (Y, ts.t[0]) if taps else Y
+
+
+class GruWeights:
+    def __init__(self, Wx, Wh, bx=None, bh=None):
+        self.Wx, self.Wh, self.bx, self.bh = Wx, Wh, bx, bh
+        self.H = Wh.cols
+        self.c = _Gru(Wx.c, Wh.c, bx.data_ptr() if bx is not None else None, bh.data_ptr() if bh is not None else None)
+
+
+class CgruWeights:
+    def __init__(self, r, att_U, att_v, q):
+        self.r, self.att_U, self.att_v, self.q = r, att_U, att_v, q
+        self.c = _Cgru(r.c, att_U.c, att_v.data_ptr(), q.c)
+
+
+class ReadoutWeights:
+    def __init__(self, W_s, W_y, W_c, b_t=None):
+        self.W_s, self.W_y, self.W_c, self.b_t = W_s, W_y, W_c, b_t
+        self.c = _Readout(W_s.c, W_y.c, W_c.c, b_t.data_ptr() if b_t is not None else None)
+
+
+def gru_step_q8(ctx, g, x, h_prev, h_out=None, taps=False):
+    n = x.shape[0]
+    h_out = ctx.empty(n, g.H) if h_out is None else h_out
+    ts = _TapSet(ctx, [(n, g.Wx.cols, g.Wx.rows), (n, g.Wh.cols, g.Wh.rows)]) if taps else None
+    ctx.check(ctx.lib.gru_step_q8(ctx.handle, C.byref(g.c), _ptr(x), _ptr(h_prev), n, _ptr(h_out), ts.arr if ts else None))
+    return (h_out, ts.t) if taps else h_out
+
+
+def cgru_decoder_step_q8(ctx, w, P, enc_h, y_emb, s_prev, out=None, taps=False):
+    """Returns dict(s, ctx, alpha, s_mid) (+ 'taps': five entries)."""
+    n, l = y_emb.shape[0], P.shape[0]
+    H, Cd = w.r.H, w.q.Wx.cols
+    o = out or {}
+    s_out = o.get("s", None)
+    s_out = ctx.empty(n, H) if s_out is None else s_out
+    c_out = o.get("ctx", None)
+    c_out = ctx.empty(n, Cd) if c_out is None else c_out
+    alpha = o["alpha"] if "alpha" in o else ctx.empty(n, l)
+    s_mid = o["s_mid"] if "s_mid" in o else ctx.empty(n, H)
+    ts = None
+    if taps:
+        A = w.att_U.rows
+        ts = _TapSet(ctx, [(n, w.r.Wx.cols, 3 * H), (n, H, 3 * H), (n, H, A), (n, Cd, 3 * H), (n, H, 3 * H)])
+    ctx.check(ctx.lib.cgru_decoder_step_q8(ctx.handle, C.byref(w.c), _ptr(P), _ptr(enc_h), l, _ptr(y_emb), _ptr(s_prev), n,
+                                           _ptr(s_out), _ptr(c_out), _ptr(alpha), _ptr(s_mid), ts.arr if ts else None))
+    r = {"s": s_out, "ctx": c_out, "alpha": alpha, "s_mid": s_mid}
+    if taps:
+        r["taps"] = ts.t
+    return r
+
+
+def output_logits_q8(ctx, ro, W_out, b_out, s=None, y_emb=None, ctx_vec=None, t_in=None, k=12,
+                     want_logits=True, taps=False):
+    """Returns dict(logits?, lse, topk_logp, topk_idx, t?) (+ 'taps': four entries)."""
+    n = (t_in if ro is None else s).shape[0]
+    V, R = W_out.rows, W_out.cols
+    logits = ctx.empty(n, V) if want_logits else None
+    lse = ctx.empty(n)
+    lp = ctx.empty(n, k)
+    idx = ctx.empty(n, k, dtype=torch.int32)
+    t_out = ctx.empty(n, R) if ro is not None else None
+    ts = None
+    if taps:
+        if ro is not None:
+            specs = [(n, ro.W_s.cols, R), (n, ro.W_y.cols, R), (n, ro.W_c.cols, R), (n, R, V)]
+        else:
+            specs = [(1, 1, 1)] * 3 + [(n, R, V)]
+        ts = _TapSet(ctx, specs)
+    ctx.check(ctx.lib.output_logits_q8(ctx.handle, C.byref(ro.c) if ro is not None else None, C.byref(W_out.c), _ptr(b_out),
+                                       _ptr(s), _ptr(y_emb), _ptr(ctx_vec), _ptr(t_in), n, k, _ptr(logits), _ptr(lse),
+                                       _ptr(lp), _ptr(idx), _ptr(t_out), ts.arr if ts else None))
+    r = {"logits": logits, "lse": lse, "topk_logp": lp, "topk_idx": idx, "t": t_out}
+    if taps:
+        r["taps"] = ts.t
+    return r
+
+
+def q8_encode(ctx, fwd, bwd, X, enc_h=None):
+    l = X.shape[0]
+    enc_h = ctx.empty(l, 2 * fwd.H) if enc_h is None else enc_h
+    ctx.check(ctx.lib.q8_encode(ctx.handle, C.byref(fwd.c), C.byref(bwd.c), _ptr(X), l, _ptr(enc_h)))
+    return enc_h

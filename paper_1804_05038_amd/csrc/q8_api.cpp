@@ -1,0 +1,308 @@
+// q8_api.cpp -- the C ABI declared in q8nmt.h: argument validation, workspace carving
+// and the sequence of launches that makes up each call.  All arithmetic is in the
+// kernels (q8_kernels.hip).
+#include "q8_internal.h"
+
+#include <new>
+#include <stdlib.h>
+#include <string.h>
+
+namespace {
+
+const int kMaxLd = 16384, kMaxNarrow = 8, kMaxMfmaN = 1024, kMaxL = 1024, kMaxK = 16, kMaxVocab = 131072;
+
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Bump allocator over the caller's workspace (after the header).
+struct Carver {
+    char *base;
+    size_t cap, off;
+    bool ok;
+    explicit Carver(q8_ctx *c) : base(c->ws), cap(c->ws_bytes), off(Q8_WS_HEADER), ok(true) {}
+    template <class T> T *take(size_t count)
+    {
+        size_t bytes = up256(count * sizeof(T));
+        if (off + bytes > cap) { ok = false; return nullptr; }
+        T *p = (T *)(base + off);
+        off += bytes;
+        return p;
+    }
+};
+
+q8_status check_mat(q8_ctx *ctx, const q8_mat *W, const char *name)
+{
+    if (!W || !W->data) return q8_fail(ctx, Q8_ERR_NULL, "%s: NULL matrix", name);
+    if (W->rows <= 0 || W->cols <= 0 || W->ld < W->cols || W->ld > kMaxLd)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "%s: bad shape %d x %d (ld %d)", name, W->rows, W->cols, W->ld);
+    if (!aligned16(W->data) || W->ld % 16 != 0)
+        return q8_fail(ctx, Q8_ERR_ALIGN, "%s: int8 matrix needs a 16-byte aligned base and ld %% 16 == 0", name);
+    return Q8_OK;
+}
+
+q8_status check_vecs(q8_ctx *ctx, const float *p, int ld, int cols, const char *name)
+{
+    if (!p) return q8_fail(ctx, Q8_ERR_NULL, "%s: NULL", name);
+    if (ld < cols) return q8_fail(ctx, Q8_ERR_SHAPE, "%s: leading dimension %d < %d", name, ld, cols);
+    if (!aligned16(p) || ld % 4 != 0)
+        return q8_fail(ctx, Q8_ERR_ALIGN, "%s: fp32 vectors need a 16-byte aligned base and ld %% 4 == 0", name);
+    return Q8_OK;
+}
+
+q8_status check_gru(q8_ctx *ctx, const q8_gru_weights *g, const char *name)
+{
+    if (!g) return q8_fail(ctx, Q8_ERR_NULL, "%s: NULL", name);
+    q8_status st = check_mat(ctx, &g->Wx, name);
+    if (!st) st = check_mat(ctx, &g->Wh, name);
+    if (st) return st;
+    const int H = g->Wh.cols;
+    if (g->Wh.rows != 3 * H || g->Wx.rows != 3 * H)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "%s: expected Wx [3H x I], Wh [3H x H]", name);
+    return Q8_OK;
+}
+
+#define TRY(expr) do { q8_status st_ = (expr); if (st_) return st_; } while (0)
+
+}  // namespace
+
+extern "C" {
+
+size_t q8_workspace_bytes(int max_n, int max_l, int max_rows, int max_ld)
+{
+    if (max_n < 1) max_n = 1;
+    if (max_l < 1) max_l = 1;
+    if (max_rows < 1) max_rows = 1;
+    if (max_ld < 16) max_ld = 16;
+    const size_t nv = (size_t)(max_n > max_l ? max_n : max_l);
+    size_t b = Q8_WS_HEADER;
+    b += up256(nv * (size_t)max_ld) + up256(nv * 4);              // quantized vectors + scales (MFMA path)
+    b += 2 * up256((size_t)max_l * max_rows * 4);                 // encoder input pre-activations, both directions
+    b += 8 * up256((size_t)max_n * max_rows * 4);                 // per-hypothesis vectors of a decoder step
+    b += up256((size_t)max_n * max_l * 4);                        // attention energies
+    const size_t nblk = (size_t)q8i_out_blocks(max_rows);
+    b += up256(nblk * max_n * 4) + up256(nblk * max_n * 8) + 2 * up256(nblk * max_n * kMaxK * 4);
+    return b + 65536;
+}
+
+q8_status q8_create(q8_ctx **out, void *hip_stream, void *workspace, size_t workspace_bytes)
+{
+    if (!out) return Q8_ERR_NULL;
+    *out = nullptr;
+    if (!workspace) return Q8_ERR_NULL;
+    if (((uintptr_t)workspace & 255) != 0) return Q8_ERR_ALIGN;
+    if (workspace_bytes < Q8_WS_HEADER) return Q8_ERR_WORKSPACE;
+    q8_ctx *c = new (std::nothrow) q8_ctx;
+    if (!c) return Q8_ERR_DEVICE;
+    c->stream = (hipStream_t)hip_stream;
+    c->ws = (char *)workspace;
+    c->ws_bytes = workspace_bytes;
+    c->err[0] = 0;
+    q8_status st = q8i_fill_u32(c, c->ws, Q8_WS_HEADER / 4, 0u);
+    if (st) { delete c; return st; }
+    *out = c;
+    return Q8_OK;
+}
+
+q8_status q8_destroy(q8_ctx *ctx)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    delete ctx;
+    return Q8_OK;
+}
+
+const char *q8_last_error(const q8_ctx *ctx) { return ctx ? ctx->err : "NULL context"; }
+
+q8_status q8_quantize_matrix(q8_ctx *ctx, const float *W, int rows, int cols, int ld_in, int8_t *Wq_out, int ld_out,
+                             float *scale_out_host)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!W || !Wq_out || !scale_out_host) return q8_fail(ctx, Q8_ERR_NULL, "q8_quantize_matrix: NULL argument");
+    if (rows <= 0 || cols <= 0 || ld_in < cols || ld_out < cols || ld_out > kMaxLd)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "q8_quantize_matrix: bad shape %d x %d (ld_in %d, ld_out %d)", rows, cols, ld_in, ld_out);
+    if (!aligned16(Wq_out) || ld_out % 16 != 0)
+        return q8_fail(ctx, Q8_ERR_ALIGN, "q8_quantize_matrix: output needs a 16-byte aligned base and ld_out %% 16 == 0");
+    return q8i_quantize_matrix(ctx, W, rows, cols, ld_in, Wq_out, ld_out, scale_out_host);
+}
+
+q8_status q8_gemm_narrow(q8_ctx *ctx, const q8_mat *W, const float *X, int n, int ldx, const float *bias, float *Y,
+                         int ldy, const q8_taps *taps)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    TRY(check_mat(ctx, W, "W"));
+    if (n <= 0 || n > kMaxMfmaN) return q8_fail(ctx, Q8_ERR_SHAPE, "n = %d outside [1, %d]", n, kMaxMfmaN);
+    TRY(check_vecs(ctx, X, n == 1 ? W->cols + ((4 - W->cols % 4) % 4) : ldx, W->cols, "X"));
+    if (!Y) return q8_fail(ctx, Q8_ERR_NULL, "Y: NULL");
+    if (n > 1 && ldy < W->rows) return q8_fail(ctx, Q8_ERR_SHAPE, "ldy %d < rows %d", ldy, W->rows);
+    if (n <= kMaxNarrow) {
+        if ((size_t)n * W->ld > 65536) return q8_fail(ctx, Q8_ERR_SHAPE, "n * ld = %zu exceeds 65536", (size_t)n * W->ld);
+        q8i_gemv_desc d = {W, X, ldx, bias, Y, ldy, taps};
+        return q8i_gemv_jobs(ctx, &d, 1, n);
+    }
+    Carver cv(ctx);
+    int8_t *xq = cv.take<int8_t>((size_t)n * W->ld);
+    float *xs = cv.take<float>(n);
+    if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "q8_gemm_narrow: workspace too small");
+    return q8i_gemm_mfma(ctx, W, X, n, ldx, bias, Y, ldy, taps, xq, xs);
+}
+
+q8_status q8_gemv(q8_ctx *ctx, const q8_mat *W, const float *x, const float *bias, float *y, const q8_taps *taps)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!W) return q8_fail(ctx, Q8_ERR_NULL, "W: NULL");
+    return q8_gemm_narrow(ctx, W, x, 1, (W->cols + 3) & ~3, bias, y, W->rows, taps);
+}
+
+q8_status gru_step_q8(q8_ctx *ctx, const q8_gru_weights *g, const float *x, const float *h_prev, int n, float *h_out,
+                      const q8_taps *taps2)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    TRY(check_gru(ctx, g, "gru"));
+    if (n <= 0 || n > kMaxNarrow) return q8_fail(ctx, Q8_ERR_SHAPE, "n = %d outside [1, %d]", n, kMaxNarrow);
+    const int I = g->Wx.cols, H = g->Wh.cols;
+    if (n > 1 && (I % 4 || H % 4)) return q8_fail(ctx, Q8_ERR_ALIGN, "batched vectors need dims %% 4 == 0");
+    TRY(check_vecs(ctx, x, (I + 3) & ~3, I, "x"));
+    TRY(check_vecs(ctx, h_prev, (H + 3) & ~3, H, "h_prev"));
+    if (!h_out) return q8_fail(ctx, Q8_ERR_NULL, "h_out: NULL");
+    if (h_out == h_prev) return q8_fail(ctx, Q8_ERR_SHAPE, "h_out must not alias h_prev");
+    if ((size_t)n * (g->Wx.ld + g->Wh.ld) > 65536) return q8_fail(ctx, Q8_ERR_SHAPE, "n * (ld_x + ld_h) exceeds 65536");
+    q8i_gru_desc d = {g, x, I, h_prev, H, nullptr, 0, h_out, H, taps2};
+    return q8i_gru(ctx, &d, 1, n, Q8I_GRU_FULL);
+}
+
+q8_status cgru_decoder_step_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h, int l,
+                               const float *y_emb, const float *s_prev, int n_beam, float *s_out, float *ctx_out,
+                               float *alpha_out, float *s_mid_out, const q8_taps *taps5)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!w) return q8_fail(ctx, Q8_ERR_NULL, "weights: NULL");
+    TRY(check_gru(ctx, &w->r, "r"));
+    TRY(check_gru(ctx, &w->q, "q"));
+    TRY(check_mat(ctx, &w->att_U, "att_U"));
+    const int n = n_beam, H = w->r.Wh.cols, E = w->r.Wx.cols, C = w->q.Wx.cols, A = w->att_U.rows;
+    if (n <= 0 || n > kMaxNarrow) return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam = %d outside [1, %d]", n, kMaxNarrow);
+    if (l <= 0 || l > kMaxL) return q8_fail(ctx, Q8_ERR_SHAPE, "l = %d outside [1, %d]", l, kMaxL);
+    if (w->q.Wh.cols != H || w->att_U.cols != H) return q8_fail(ctx, Q8_ERR_SHAPE, "hidden sizes of r, q and att_U differ");
+    if (E % 4 || H % 4 || C % 4 || A % 4) return q8_fail(ctx, Q8_ERR_ALIGN, "E, H, C, A must be multiples of 4");
+    if (!w->att_v || !P || !enc_h || !y_emb || !s_prev || !s_out || !ctx_out)
+        return q8_fail(ctx, Q8_ERR_NULL, "cgru_decoder_step_q8: NULL argument");
+    if (!aligned16(P) || !aligned16(enc_h) || !aligned16(y_emb) || !aligned16(s_prev) || !aligned16(s_out) || !aligned16(ctx_out))
+        return q8_fail(ctx, Q8_ERR_ALIGN, "cgru_decoder_step_q8: fp32 buffers need 16-byte alignment");
+    if (s_out == s_prev) return q8_fail(ctx, Q8_ERR_SHAPE, "s_out must not alias s_prev");
+    if ((size_t)n * (w->r.Wx.ld + w->r.Wh.ld) > 65536 || (size_t)n * w->q.Wx.ld > 65536)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam * row length exceeds 65536");
+
+    Carver cv(ctx);
+    float *s_mid = s_mid_out ? s_mid_out : cv.take<float>((size_t)n * H);
+    float *a = cv.take<float>((size_t)n * A);
+    float *ghq = cv.take<float>((size_t)n * 3 * H);
+    float *e = cv.take<float>((size_t)n * l);
+    if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "cgru_decoder_step_q8: workspace too small");
+
+    // Eq. 3: s' = r(y, s_prev)
+    q8i_gru_desc dr = {&w->r, y_emb, E, s_prev, H, nullptr, 0, s_mid, H, taps5};
+    TRY(q8i_gru(ctx, &dr, 1, n, Q8I_GRU_FULL));
+    // everything that depends on s' alone: u(s') of Eq. 6 and the recurrent half of GRU q
+    q8_mat qWh = w->q.Wh;
+    q8i_gemv_desc dj[2] = {{&w->att_U, s_mid, H, nullptr, a, A, taps5 ? taps5 + 2 : nullptr},
+                           {&qWh, s_mid, H, w->q.bh, ghq, 3 * H, taps5 ? taps5 + 4 : nullptr}};
+    TRY(q8i_gemv_jobs(ctx, dj, 2, n));
+    // Eq. 5-6: energies, weights, context
+    TRY(q8i_attention(ctx, P, enc_h, l, A, C, a, w->att_v, n, e, alpha_out, ctx_out));
+    // Eq. 4: s = q(H_t, s')
+    q8_taps tq[2];
+    if (taps5) { tq[0] = taps5[3]; tq[1].xq = nullptr; tq[1].xscale = nullptr; tq[1].acc = nullptr; }
+    q8i_gru_desc dq = {&w->q, ctx_out, C, s_mid, H, ghq, 3 * H, s_out, H, taps5 ? tq : nullptr};
+    return q8i_gru(ctx, &dq, 1, n, Q8I_GRU_GH_PRE);
+}
+
+q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                           const float *s, const float *y_emb, const float *ctx_vec, const float *t_in, int n_beam,
+                           int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx, float *t_out,
+                           const q8_taps *taps4)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    TRY(check_mat(ctx, W_out, "W_out"));
+    const int n = n_beam, R = W_out->cols, V = W_out->rows;
+    if (n <= 0 || n > kMaxNarrow) return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam = %d outside [1, %d]", n, kMaxNarrow);
+    if (k <= 0 || k > kMaxK || k > V) return q8_fail(ctx, Q8_ERR_SHAPE, "k = %d outside [1, min(%d, rows)]", k, kMaxK);
+    if (V > kMaxVocab) return q8_fail(ctx, Q8_ERR_SHAPE, "W_out has more than %d rows", kMaxVocab);
+    if (W_out->ld > 8192) return q8_fail(ctx, Q8_ERR_SHAPE, "W_out: ld above 8192");
+    if (R % 4) return q8_fail(ctx, Q8_ERR_ALIGN, "R must be a multiple of 4");
+    if (!topk_logp || !topk_idx) return q8_fail(ctx, Q8_ERR_NULL, "top-k outputs: NULL");
+    Carver cv(ctx);
+    const float *T = t_in;
+    if (ro) {
+        TRY(check_mat(ctx, &ro->W_s, "W_s"));
+        TRY(check_mat(ctx, &ro->W_y, "W_y"));
+        TRY(check_mat(ctx, &ro->W_c, "W_c"));
+        if (ro->W_s.rows != R || ro->W_y.rows != R || ro->W_c.rows != R)
+            return q8_fail(ctx, Q8_ERR_SHAPE, "readout matrices must have %d rows", R);
+        if (ro->W_s.cols % 4 || ro->W_y.cols % 4 || ro->W_c.cols % 4)
+            return q8_fail(ctx, Q8_ERR_ALIGN, "H, E, C must be multiples of 4");
+        if (!s || !y_emb || !ctx_vec) return q8_fail(ctx, Q8_ERR_NULL, "s, y_emb, ctx: NULL");
+        if (!aligned16(s) || !aligned16(y_emb) || !aligned16(ctx_vec))
+            return q8_fail(ctx, Q8_ERR_ALIGN, "s, y_emb, ctx need 16-byte alignment");
+        if ((size_t)n * (ro->W_s.ld + ro->W_y.ld + ro->W_c.ld) > 65536)
+            return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam * (H + E + C) exceeds 65536");
+        float *t = t_out ? t_out : cv.take<float>((size_t)n * R);
+        if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
+        TRY(q8i_readout(ctx, ro, s, y_emb, ctx_vec, n, t, taps4));
+        T = t;
+    } else {
+        TRY(check_vecs(ctx, t_in, R, R, "t_in"));
+    }
+    const size_t nblk = (size_t)q8i_out_blocks(V);
+    float *pm = cv.take<float>(nblk * n);
+    double *ps = cv.take<double>(nblk * n);
+    float *cvl = cv.take<float>(nblk * n * k);
+    int *cid = cv.take<int>(nblk * n * k);
+    if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
+    return q8i_output(ctx, W_out, b_out, T, R, n, k, logits, lse, topk_logp, topk_idx, taps4 ? taps4 + 3 : nullptr,
+                      pm, ps, cvl, cid);
+}
+
+q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights *bwd, const float *X, int l,
+                    float *enc_h)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    TRY(check_gru(ctx, fwd, "fwd"));
+    TRY(check_gru(ctx, bwd, "bwd"));
+    const int E = fwd->Wx.cols, H = fwd->Wh.cols, C = 2 * H;
+    if (bwd->Wx.cols != E || bwd->Wh.cols != H) return q8_fail(ctx, Q8_ERR_SHAPE, "directions differ in shape");
+    if (l <= 0 || l > kMaxL) return q8_fail(ctx, Q8_ERR_SHAPE, "l = %d outside [1, %d]", l, kMaxL);
+    if (E % 4 || H % 4) return q8_fail(ctx, Q8_ERR_ALIGN, "E and H must be multiples of 4");
+    TRY(check_vecs(ctx, X, E, E, "X"));
+    if (!enc_h) return q8_fail(ctx, Q8_ERR_NULL, "enc_h: NULL");
+    if (!aligned16(enc_h)) return q8_fail(ctx, Q8_ERR_ALIGN, "enc_h needs 16-byte alignment");
+
+    Carver cv(ctx);
+    int8_t *xq = cv.take<int8_t>((size_t)l * fwd->Wx.ld);
+    float *xs = cv.take<float>(l);
+    float *gxf = cv.take<float>((size_t)l * 3 * H);
+    float *gxb = cv.take<float>((size_t)l * 3 * H);
+    float *zero = cv.take<float>(H);
+    if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "q8_encode: workspace too small");
+    TRY(q8i_fill_u32(ctx, zero, H, 0u));
+
+    // input products for every position at once (the same per-vector quantization as l separate products)
+    if (l <= kMaxNarrow) {
+        q8i_gemv_desc d[2] = {{&fwd->Wx, X, E, fwd->bx, gxf, 3 * H, nullptr}, {&bwd->Wx, X, E, bwd->bx, gxb, 3 * H, nullptr}};
+        TRY(q8i_gemv_jobs(ctx, d, 2, l));
+    } else {
+        TRY(q8i_gemm_mfma(ctx, &fwd->Wx, X, l, E, fwd->bx, gxf, 3 * H, nullptr, xq, xs));
+        TRY(q8i_gemm_mfma(ctx, &bwd->Wx, X, l, E, bwd->bx, gxb, 3 * H, nullptr, xq, xs));
+    }
+    // l sequential recurrent steps, both directions in each launch
+    for (int t = 0; t < l; ++t) {
+        const int pf = t, pb = l - 1 - t;
+        q8i_gru_desc d[2];
+        d[0] = {fwd, nullptr, 0, t == 0 ? zero : enc_h + (size_t)(pf - 1) * C + H, H, gxf + (size_t)pf * 3 * H, 3 * H,
+                enc_h + (size_t)pf * C + H, H, nullptr};
+        d[1] = {bwd, nullptr, 0, t == 0 ? zero : enc_h + (size_t)(pb + 1) * C, H, gxb + (size_t)pb * 3 * H, 3 * H,
+                enc_h + (size_t)pb * C, H, nullptr};
+        TRY(q8i_gru(ctx, d, 2, 1, Q8I_GRU_GX_PRE));
+    }
+    return Q8_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,237 @@
+// q8_device.h -- wave64 device helpers shared by the gfx950 kernels: cross-lane
+// reductions on DPP / swizzle, block-level activation quantization into LDS, and the
+// int8 row-streaming dot product (16-byte loads + 4-way int8 dot instructions).
+//
+// The arithmetic follows Section 3 of "Pieces of Eight: 8-bit Neural Machine
+// Translation": both operands 8-bit integers, integer accumulation, float result.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+#define Q8_WAVE 64
+
+// ---------------------------------------------------------------- cross-lane ----
+
+template <int CTRL>
+__device__ __forceinline__ int dpp_mov_i(int v)
+{
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+
+#define DPP_XOR1 0xB1         // quad_perm [1,0,3,2]
+#define DPP_XOR2 0x4E         // quad_perm [2,3,0,1]
+#define DPP_HALF_MIRROR 0x141 // lane <-> 7 - lane within 8
+#define DPP_MIRROR 0x140      // lane <-> 15 - lane within 16
+#define SWZ_XOR16 0x401F      // ds_swizzle bit mode: and 0x1f, or 0, xor 0x10
+
+// Sum over groups of `lpr` consecutive lanes (lpr in {16, 32, 64}, wave-uniform).
+// Every lane of a group ends up holding the group's sum.
+__device__ __forceinline__ int group_sum_i(int v, int lpr)
+{
+    v += dpp_mov_i<DPP_XOR1>(v);
+    v += dpp_mov_i<DPP_XOR2>(v);
+    v += dpp_mov_i<DPP_HALF_MIRROR>(v);
+    v += dpp_mov_i<DPP_MIRROR>(v);
+    if (lpr >= 32) v += __builtin_amdgcn_ds_swizzle(v, SWZ_XOR16);
+    if (lpr >= 64) v = __builtin_amdgcn_readlane(v, 0) + __builtin_amdgcn_readlane(v, 32);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max_f(float v)
+{
+    v = fmaxf(v, __int_as_float(dpp_mov_i<DPP_XOR1>(__float_as_int(v))));
+    v = fmaxf(v, __int_as_float(dpp_mov_i<DPP_XOR2>(__float_as_int(v))));
+    v = fmaxf(v, __int_as_float(dpp_mov_i<DPP_HALF_MIRROR>(__float_as_int(v))));
+    v = fmaxf(v, __int_as_float(dpp_mov_i<DPP_MIRROR>(__float_as_int(v))));
+    v = fmaxf(v, __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), SWZ_XOR16)));
+    return fmaxf(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0)),
+                 __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32)));
+}
+
+__device__ __forceinline__ double wave_sum_d(double v)
+{
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) v += __shfl_xor(v, s, 64);
+    return v;
+}
+
+__device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
+{
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+        unsigned long long o = __shfl_xor(v, s, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// Order-preserving key: larger value first, then lower index.  -0.0 is folded into +0.0
+// so that equal floats compare equal.
+__device__ __forceinline__ unsigned long long topk_key(float val, int idx)
+{
+    unsigned u = __float_as_uint(val + 0.0f);
+    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+    return ((unsigned long long)u << 32) | (unsigned)(0x7fffffff - idx);
+}
+__device__ __forceinline__ int topk_key_idx(unsigned long long k) { return 0x7fffffff - (int)(k & 0xffffffffu); }
+__device__ __forceinline__ float topk_key_val(unsigned long long k)
+{
+    unsigned u = (unsigned)(k >> 32);
+    u = (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u;
+    return __uint_as_float(u);
+}
+
+// ------------------------------------------------------ activation quantization ----
+
+// Scale and reciprocal of the symmetric max-abs quantizer: scale = m / 127,
+// inv = 127 / m, or (1, 0) when m < 2^-100.
+__device__ __forceinline__ void q8_scale_of(float m, float &scale, float &inv)
+{
+    if (m < 0x1p-100f) {
+        scale = 1.0f;
+        inv = 0.0f;
+    } else {
+        scale = m / 127.0f;
+        inv = 127.0f / m;
+    }
+}
+
+__device__ __forceinline__ int q8_code(float v, float inv)
+{
+    float r = __builtin_rintf(v * inv);   // round half to even
+    r = fminf(fmaxf(r, -127.0f), 127.0f);
+    return (int)r;
+}
+
+__device__ __forceinline__ int q8_pack4(float a, float b, float c, float d, float inv)
+{
+    return (q8_code(a, inv) & 0xff) | ((q8_code(b, inv) & 0xff) << 8) | ((q8_code(c, inv) & 0xff) << 16) |
+           ((q8_code(d, inv) & 0xff) << 24);
+}
+
+// Quantizes n (<= NMAX) fp32 vectors X[j * ldx + k], k < K, into LDS bytes
+// xq[j * ld + k] (ld % 16 == 0, bytes [K, ld) zeroed) and their scales into s_scale[j].
+// s_red needs NMAX * (blockDim.x / 64) floats.  Ends with a block barrier.
+template <int NMAX>
+__device__ __forceinline__ void block_quantize(const float *__restrict__ X, int n, int K, int ldx, int ld,
+                                               int8_t *xq, float *s_scale, float *s_red)
+{
+    const int tid = threadIdx.x, nt = blockDim.x, nw = nt >> 6, wave = tid >> 6, lane = tid & 63;
+    float m[NMAX];
+#pragma unroll
+    for (int j = 0; j < NMAX; ++j) {
+        m[j] = 0.0f;
+        if (j < n) {
+            const float *x = X + (size_t)j * ldx;
+            for (int k = tid * 4; k < K; k += nt * 4) {
+                if (k + 4 <= K) {
+                    float4 v = *(const float4 *)(x + k);
+                    m[j] = fmaxf(m[j], fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+                } else {
+                    for (int t = k; t < K; ++t) m[j] = fmaxf(m[j], fabsf(x[t]));
+                }
+            }
+            m[j] = wave_max_f(m[j]);
+            if (lane == 0) s_red[j * nw + wave] = m[j];
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NMAX; ++j) {
+        if (j < n) {
+            float mm = 0.0f;
+            for (int w = 0; w < nw; ++w) mm = fmaxf(mm, s_red[j * nw + w]);
+            float scale, inv;
+            q8_scale_of(mm, scale, inv);
+            if (tid == 0) s_scale[j] = scale;
+            const float *x = X + (size_t)j * ldx;
+            for (int k = tid * 4; k < ld; k += nt * 4) {
+                int packed;
+                if (k + 4 <= K) {
+                    float4 v = *(const float4 *)(x + k);
+                    packed = q8_pack4(v.x, v.y, v.z, v.w, inv);
+                } else {
+                    float a = k < K ? x[k] : 0.0f, b = k + 1 < K ? x[k + 1] : 0.0f;
+                    float c = k + 2 < K ? x[k + 2] : 0.0f, d = k + 3 < K ? x[k + 3] : 0.0f;
+                    packed = q8_pack4(a, b, c, d, inv);
+                }
+                *(int *)(xq + (size_t)j * ld + k) = packed;
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// ------------------------------------------------------------ row streaming dot ----
+
+__device__ __forceinline__ int dot16(v4i w, v4i x, int acc)
+{
+    acc = __builtin_amdgcn_sdot4(w.x, x.x, acc, false);
+    acc = __builtin_amdgcn_sdot4(w.y, x.y, acc, false);
+    acc = __builtin_amdgcn_sdot4(w.z, x.z, acc, false);
+    acc = __builtin_amdgcn_sdot4(w.w, x.w, acc, false);
+    return acc;
+}
+
+// Integer dot products of U weight rows with N quantized vectors held in LDS.
+//   wrow[u]: this lane's row base pointer (NULL = no row: contributes zeros).  Lanes are
+//            split into groups of `lpr` consecutive lanes; all lanes of a group pass
+//            the same row, different groups may pass different rows.
+//   lir:     lane index within its group; the lane covers bytes [(c*lpr + lir)*16, +16)
+//            of the row for c = 0, 1, ...
+//   xq:      LDS, vector j at xq + j * ld (same ld as the weight rows).
+// On return acc[u][j] holds, in every lane of a group, the full int32 sum for that
+// group's row u and vector j.
+template <int N, int U>
+__device__ __forceinline__ void wave_dot(const int8_t *const (&wrow)[U], int ld, int lpr, int lir,
+                                         const int8_t *xq, int (&acc)[U][N])
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int j = 0; j < N; ++j) acc[u][j] = 0;
+    const int step = lpr * 16;
+    int off = lir * 16;
+    v4i w[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        w[u] = (v4i){0, 0, 0, 0};
+        if (wrow[u] != nullptr && off < ld) w[u] = *(const v4i *)(wrow[u] + off);
+    }
+    while (off < ld) {                       // uniform trip count would be nicer; lanes past ld idle
+        const int offn = off + step;
+        v4i wn[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            wn[u] = (v4i){0, 0, 0, 0};
+            if (wrow[u] != nullptr && offn < ld) wn[u] = *(const v4i *)(wrow[u] + offn);
+        }
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const v4i x = *(const v4i *)(xq + (size_t)j * ld + off);
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc[u][j] = dot16(w[u], x, acc[u][j]);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) w[u] = wn[u];
+        off = offn;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int j = 0; j < N; ++j) acc[u][j] = group_sum_i(acc[u][j], lpr);
+}
+
+// Group width for rows of `ld` bytes: the smallest of 16, 32, 64 lanes whose single
+// 16-byte-per-lane pass covers the row, 64 for longer rows.
+static inline int q8_lanes_per_row(int ld)
+{
+    return ld <= 256 ? 16 : (ld <= 512 ? 32 : 64);
+}
+
+// fp32 nonlinearities of the gates, evaluated in double and rounded once.
+__device__ __forceinline__ float sigmoid_rn(float a) { return (float)(1.0 / (1.0 + exp(-(double)a))); }
+__device__ __forceinline__ float tanh_rn(float a) { return (float)tanh((double)a); }

@@ -1,0 +1,71 @@
+// q8_internal.h -- host-side context and the launcher interface between the C ABI
+// (q8_api.cpp) and the kernels (q8_kernels.hip).  Not part of the public interface.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdio.h>
+
+#include "q8nmt.h"
+#ifdef __HIPCC__
+#include "q8_device.h"
+#endif
+
+// Workspace header: arrival counters [0, 2048), scratch slots (max bits, scale) at 2048.
+#define Q8_WS_HEADER 4096
+#define Q8_WS_SCRATCH_SLOT 2048
+
+struct q8_ctx {
+    hipStream_t stream;
+    char *ws;
+    size_t ws_bytes;
+    char err[256];
+};
+
+static inline q8_status q8_fail(q8_ctx *ctx, q8_status code, const char *fmt, ...)
+{
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+struct q8i_gemv_desc {
+    const q8_mat *W;
+    const float *X;
+    int ldx;
+    const float *bias;
+    float *Y;
+    int ldy;
+    const q8_taps *taps;
+};
+
+struct q8i_gru_desc {
+    const q8_gru_weights *g;
+    const float *x;      int ldx;
+    const float *h_prev; int ldh;
+    const float *g_pre;  int ldg;
+    float *h_out;        int ldo;
+    const q8_taps *taps; // NULL or [2]
+};
+
+enum { Q8I_GRU_FULL = 0, Q8I_GRU_GX_PRE = 1, Q8I_GRU_GH_PRE = 2 };
+
+q8_status q8i_fill_u32(q8_ctx *ctx, void *p, int n, unsigned v);   // fill kernel (safe under graph capture)
+q8_status q8i_quantize_matrix(q8_ctx *ctx, const float *W, int rows, int cols, int ld_in, int8_t *Wq, int ld_out,
+                              float *scale_host);
+q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n);
+q8_status q8i_gemm_mfma(q8_ctx *ctx, const q8_mat *W, const float *X, int n, int ldx, const float *bias, float *Y,
+                        int ldy, const q8_taps *taps, int8_t *xq, float *xscale);
+q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode);
+q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, int A, int C, const float *a,
+                        const float *v, int n, float *e, float *alpha, float *cvec);
+q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,
+                      float *t_out, const q8_taps *taps3);
+int q8i_out_blocks(int V);
+q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const float *T, int ldt, int n, int k,
+                     float *logits, float *lse, float *topk_logp, int32_t *topk_idx, const q8_taps *taps,
+                     float *part_max, double *part_sum, float *cand_val, int *cand_idx);

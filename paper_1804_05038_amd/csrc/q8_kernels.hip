@@ -1,0 +1,836 @@
+// q8_kernels.hip -- gfx950 kernels of the 8-bit GRU-NMT decoding path and their host
+// launchers.  Section 3 of "Pieces of Eight: 8-bit Neural Machine Translation" gives the
+// product (8-bit operands, integer accumulation, float result); Section 2 (Eq. 1-6) the
+// model the products drive.  The kernels fuse the float epilogues (bias, gates,
+// attention, softmax, top-k) into the weight-streaming passes.
+#include "q8_internal.h"
+
+#include <math.h>
+
+// =============================================================== weight quantization ==
+
+// max |W| over a [rows x cols] matrix into *out_bits (bit pattern of a non-negative
+// float, combined with an unsigned atomic max; *out_bits must start at 0).
+__global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ W, int rows, int cols, int ld,
+                                                     unsigned *out_bits)
+{
+    __shared__ float s_red[4];
+    float m = 0.0f;
+    const size_t total = (size_t)rows * cols;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+        const size_t r = e / cols, c = e - r * cols;
+        m = fmaxf(m, fabsf(W[r * ld + c]));
+    }
+    m = wave_max_f(m);
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+        atomicMax(out_bits, __float_as_uint(m));
+    }
+}
+
+__global__ __launch_bounds__(256) void quantize_matrix_kernel(const float *__restrict__ W, int rows, int cols, int ld_in,
+                                                              int8_t *__restrict__ Wq, int ld_out,
+                                                              const unsigned *max_bits, float *scale_out)
+{
+    float scale, inv;
+    q8_scale_of(__uint_as_float(*max_bits), scale, inv);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = scale;
+    const int groups = ld_out / 4;
+    const size_t total = (size_t)rows * groups;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+        const size_t r = e / groups;
+        const int k = (int)(e - r * groups) * 4;
+        const float *w = W + r * ld_in;
+        float a = k < cols ? w[k] : 0.0f, b = k + 1 < cols ? w[k + 1] : 0.0f;
+        float c = k + 2 < cols ? w[k + 2] : 0.0f, d = k + 3 < cols ? w[k + 3] : 0.0f;
+        *(int *)(Wq + r * ld_out + k) = q8_pack4(a, b, c, d, inv);
+    }
+}
+
+__global__ void fill_u32_kernel(unsigned *p, int n, unsigned v)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// ====================================================== streaming matrix x vector(s) ==
+
+struct GemvJob {
+    const int8_t *W;
+    const float *X;
+    const float *bias;
+    float *Y;
+    int8_t *tap_xq;
+    float *tap_xscale;
+    int32_t *tap_acc;
+    int rows, cols, ld, ldx, ldy, lpr, block0, rpb;
+    float w_scale;
+};
+#define Q8_MAX_JOBS 3
+struct GemvJobs {
+    GemvJob j[Q8_MAX_JOBS];
+    int njobs;
+};
+
+// Up to Q8_MAX_JOBS independent products in one launch, each with N <= 8 vectors.  A
+// block belongs to one job, quantizes that job's vectors into LDS and streams its
+// slice of rows: 16 bytes per lane per row pass, 4-way int8 dots, DPP reduction.
+template <int N>
+__global__ __launch_bounds__(256) void gemv_jobs_kernel(GemvJobs jobs)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    __shared__ float s_scale[8];
+    __shared__ float s_red[8 * 4];
+    int ji = 0;
+    for (int t = 1; t < jobs.njobs; ++t)
+        if ((int)blockIdx.x >= jobs.j[t].block0) ji = t;
+    const GemvJob &J = jobs.j[ji];
+    const int blk = blockIdx.x - J.block0;
+    const int ld = J.ld;
+
+    block_quantize<N>(J.X, N, J.cols, J.ldx, ld, smem, s_scale, s_red);
+
+    if (blk == 0) {
+        if (J.tap_xq)
+            for (int e = threadIdx.x; e < N * J.cols; e += blockDim.x) {
+                const int j = e / J.cols, k = e - j * J.cols;
+                J.tap_xq[e] = smem[j * ld + k];
+            }
+        if (J.tap_xscale && threadIdx.x < N) J.tap_xscale[threadIdx.x] = s_scale[threadIdx.x];
+    }
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lpr = J.lpr, lir = lane & (lpr - 1), sg = lane / lpr, rpp = 64 / lpr;
+    constexpr int U = 4;
+    const int r_begin = blk * J.rpb;
+    const int r_end = min(J.rows, r_begin + J.rpb);
+    float cj = 0.0f;                          // lane lir < N owns vector lir in the epilogue
+    if (lir < N) cj = J.w_scale * s_scale[lir];
+
+    for (int r = r_begin + wave * rpp * U; r < r_end; r += 4 * rpp * U) {
+        const int8_t *wrow[U];
+        int row[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            row[u] = r + u * rpp + sg;
+            wrow[u] = row[u] < r_end ? J.W + (size_t)row[u] * ld : nullptr;
+        }
+        int acc[U][N];
+        wave_dot<N, U>(wrow, ld, lpr, lir, smem, acc);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int a = 0;
+#pragma unroll
+            for (int j = 0; j < N; ++j) a = (lir == j) ? acc[u][j] : a;
+            if (lir < N && row[u] < r_end) {
+                float y = (float)a * cj;
+                if (J.bias) y = y + J.bias[row[u]];
+                J.Y[(size_t)lir * J.ldy + row[u]] = y;
+                if (J.tap_acc) J.tap_acc[(size_t)lir * J.rows + row[u]] = a;
+            }
+        }
+    }
+}
+
+// ================================================ narrow product on the matrix cores ==
+
+// One block per vector: quantize X[j] into global xq[j * ld ..] (pad zeroed), scale[j].
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const float *__restrict__ X, int K, int ldx, int ld,
+                                                            int8_t *xq, float *xscale, int8_t *tap_xq)
+{
+    __shared__ float s_scale[1];
+    __shared__ float s_red[4];
+    const int j = blockIdx.x;
+    block_quantize<1>(X + (size_t)j * ldx, 1, K, ldx, ld, xq + (size_t)j * ld, s_scale, s_red);
+    if (threadIdx.x == 0) xscale[j] = s_scale[0];
+    if (tap_xq) {
+        __threadfence_block();
+        for (int k = threadIdx.x; k < K; k += blockDim.x) tap_xq[(size_t)j * K + k] = xq[(size_t)j * ld + k];
+    }
+}
+
+struct MfmaArgs {
+    const int8_t *W;
+    const int8_t *xq;      // [n x ld] int8, global
+    const float *xscale;   // [n]
+    const float *bias;
+    float *Y;
+    int32_t *tap_acc;
+    int rows, ld, n, ldy;
+    float w_scale;
+};
+
+// Y[j, row] for 16-row x 16-vector tiles on v_mfma_i32_16x16x64_i8.  Operand A = 16
+// weight rows x 64 k (lane: row lane%16, 16 consecutive k at 16*(lane/16)); operand B =
+// 64 k x 16 vectors with the same k split, so any internal k order cancels.  Result:
+// lane holds rows 4*(lane/16)+r, r = 0..3, of vector lane%16.
+template <int NT>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaArgs a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int r0 = (blockIdx.x * 4 + wave) * 16;
+    if (r0 >= a.rows) return;
+    const int ld = a.ld;
+    const bool row_ok = r0 + i < a.rows;
+    const int8_t *wp = a.W + (size_t)(r0 + i) * ld + 16 * g;
+    for (int ct = 0; ct * 16 < a.n; ct += NT) {
+        v4i acc[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = (v4i){0, 0, 0, 0};
+        for (int k0 = 0; k0 < ld; k0 += 64) {
+            const bool k_ok = k0 + 16 * g < ld;
+            v4i av = (v4i){0, 0, 0, 0};
+            if (row_ok && k_ok) av = *(const v4i *)(wp + k0);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int col = (ct + t) * 16 + i;
+                v4i bv = (v4i){0, 0, 0, 0};
+                if (col < a.n && k_ok) bv = *(const v4i *)(a.xq + (size_t)col * ld + k0 + 16 * g);
+                acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bv, acc[t], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int col = (ct + t) * 16 + i;
+            if (col >= a.n) continue;
+            const float c = a.w_scale * a.xscale[col];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = r0 + 4 * g + r;
+                if (row < a.rows) {
+                    float y = (float)acc[t][r] * c;
+                    if (a.bias) y = y + a.bias[row];
+                    a.Y[(size_t)col * a.ldy + row] = y;
+                    if (a.tap_acc) a.tap_acc[(size_t)col * a.rows + row] = acc[t][r];
+                }
+            }
+        }
+    }
+}
+
+// ========================================================================= GRU cell ==
+
+#define GRU_FULL 0     // both products computed here
+#define GRU_GX_PRE 1   // gx = Wx q(x) + bx supplied in g_pre (encoder: all positions at once)
+#define GRU_GH_PRE 2   // gh = Wh q(h) + bh supplied in g_pre (decoder GRU q: depends on s' only)
+
+struct GruJob {
+    const int8_t *Wx, *Wh;
+    const float *bx, *bh;
+    const float *x, *h_prev, *g_pre;
+    float *h_out;
+    q8_taps tx, th;
+    int I, ldwx, H, ldwh, ldx, ldh, ldo, ldg, lpr;
+    float sx_w, sh_w;
+};
+struct GruJobs {
+    GruJob j[2];
+};
+
+template <int N, int MODE>
+__global__ __launch_bounds__(256) void gru_kernel(GruJobs jobs)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    __shared__ float s_scale[16];
+    __shared__ float s_red[8 * 4];
+    const GruJob &J = jobs.j[blockIdx.y];
+    const int H = J.H;
+    int8_t *xq = smem;
+    int8_t *hq = smem + (MODE == GRU_GX_PRE ? 0 : N * J.ldwx);
+    if (MODE != GRU_GX_PRE) block_quantize<N>(J.x, N, J.I, J.ldx, J.ldwx, xq, s_scale, s_red);
+    if (MODE != GRU_GH_PRE) block_quantize<N>(J.h_prev, N, H, J.ldh, J.ldwh, hq, s_scale + 8, s_red);
+
+    if (blockIdx.x == 0) {
+        if (MODE != GRU_GX_PRE) {
+            if (J.tx.xq)
+                for (int e = threadIdx.x; e < N * J.I; e += blockDim.x) J.tx.xq[e] = xq[(e / J.I) * J.ldwx + e % J.I];
+            if (J.tx.xscale && threadIdx.x < N) J.tx.xscale[threadIdx.x] = s_scale[threadIdx.x];
+        }
+        if (MODE != GRU_GH_PRE) {
+            if (J.th.xq)
+                for (int e = threadIdx.x; e < N * H; e += blockDim.x) J.th.xq[e] = hq[(e / H) * J.ldwh + e % H];
+            if (J.th.xscale && threadIdx.x < N) J.th.xscale[threadIdx.x] = s_scale[8 + threadIdx.x];
+        }
+    }
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lpr = J.lpr, lir = lane & (lpr - 1), sg = lane / lpr, upw = 64 / lpr;
+    float cx = 0.0f, ch = 0.0f;
+    if (lir < N) {
+        if (MODE != GRU_GX_PRE) cx = J.sx_w * s_scale[lir];
+        if (MODE != GRU_GH_PRE) ch = J.sh_w * s_scale[8 + lir];
+    }
+
+    for (int u0 = (blockIdx.x * 4 + wave) * upw; u0 < H; u0 += gridDim.x * 4 * upw) {
+        const int unit = u0 + sg;
+        const bool ok = unit < H;
+        int ax[3][N], ah[3][N];
+        if (MODE != GRU_GX_PRE) {
+            const int8_t *wrow[3];
+#pragma unroll
+            for (int gt = 0; gt < 3; ++gt) wrow[gt] = ok ? J.Wx + (size_t)(gt * H + unit) * J.ldwx : nullptr;
+            wave_dot<N, 3>(wrow, J.ldwx, lpr, lir, xq, ax);
+        }
+        if (MODE != GRU_GH_PRE) {
+            const int8_t *wrow[3];
+#pragma unroll
+            for (int gt = 0; gt < 3; ++gt) wrow[gt] = ok ? J.Wh + (size_t)(gt * H + unit) * J.ldwh : nullptr;
+            wave_dot<N, 3>(wrow, J.ldwh, lpr, lir, hq, ah);
+        }
+        if (ok && lir < N) {
+            const int j = lir;
+            float gx[3], gh[3];
+#pragma unroll
+            for (int gt = 0; gt < 3; ++gt) {
+                const int row = gt * H + unit;
+                if (MODE == GRU_GX_PRE) {
+                    gx[gt] = J.g_pre[(size_t)j * J.ldg + row];
+                } else {
+                    int a = 0;
+#pragma unroll
+                    for (int jj = 0; jj < N; ++jj) a = (j == jj) ? ax[gt][jj] : a;
+                    float y = (float)a * cx;
+                    if (J.bx) y = y + J.bx[row];
+                    gx[gt] = y;
+                    if (J.tx.acc) J.tx.acc[(size_t)j * 3 * H + row] = a;
+                }
+                if (MODE == GRU_GH_PRE) {
+                    gh[gt] = J.g_pre[(size_t)j * J.ldg + row];
+                } else {
+                    int a = 0;
+#pragma unroll
+                    for (int jj = 0; jj < N; ++jj) a = (j == jj) ? ah[gt][jj] : a;
+                    float y = (float)a * ch;
+                    if (J.bh) y = y + J.bh[row];
+                    gh[gt] = y;
+                    if (J.th.acc) J.th.acc[(size_t)j * 3 * H + row] = a;
+                }
+            }
+            const float pr = gx[0] + gh[0];
+            const float r = sigmoid_rn(pr);
+            const float pz = gx[1] + gh[1];
+            const float z = sigmoid_rn(pz);
+            const float rn = r * gh[2];
+            const float pn = gx[2] + rn;
+            const float nn = tanh_rn(pn);
+            const float omz = 1.0f - z;
+            const float t1 = omz * nn;
+            const float t2 = z * J.h_prev[(size_t)j * J.ldh + unit];
+            J.h_out[(size_t)j * J.ldo + unit] = t1 + t2;
+        }
+    }
+}
+
+// ======================================================================== attention ==
+
+struct AttArgs {
+    const float *P, *enc_h, *a, *v;
+    float *e, *alpha, *ctx;
+    unsigned *counters;     // one arrival counter per hypothesis, zero on entry and on exit
+    int l, A, C;
+};
+
+// Block (i, b): energy e[b, i] = sum_j v_j tanh(P[i, j] + a[b, j]) (Eq. 6).  The last
+// block to arrive for hypothesis b turns the energies into weights and the context
+// vector H_t (Eq. 5).
+__global__ __launch_bounds__(256) void attention_kernel(AttArgs a)
+{
+    __shared__ double s_red[4];
+    __shared__ float s_alpha[1024];
+    __shared__ int s_last;
+    const int i = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const float *Pi = a.P + (size_t)i * a.A;
+    const float *ab = a.a + (size_t)b * a.A;
+    double acc = 0.0;
+    for (int j = tid; j < a.A; j += blockDim.x) {
+        const float pre = Pi[j] + ab[j];
+        const float th = tanh_rn(pre);
+        acc += (double)a.v[j] * (double)th;
+    }
+    acc = wave_sum_d(acc);
+    if ((tid & 63) == 0) s_red[tid >> 6] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        const double tot = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+        a.e[(size_t)b * a.l + i] = (float)tot;
+        __threadfence();
+        const unsigned prev = atomicAdd(&a.counters[b], 1u);
+        s_last = (prev == (unsigned)a.l - 1u);
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    // softmax over the l energies of hypothesis b
+    const volatile float *e = a.e + (size_t)b * a.l;
+    if (tid == 0) {
+        float mx = e[0];
+        for (int t = 1; t < a.l; ++t) mx = fmaxf(mx, e[t]);
+        double Z = 0.0;
+        for (int t = 0; t < a.l; ++t) Z += exp((double)e[t] - (double)mx);
+        for (int t = 0; t < a.l; ++t) s_alpha[t] = (float)(exp((double)e[t] - (double)mx) / Z);
+        a.counters[b] = 0;
+    }
+    __syncthreads();
+    if (a.alpha)
+        for (int t = tid; t < a.l; t += blockDim.x) a.alpha[(size_t)b * a.l + t] = s_alpha[t];
+    for (int c = tid; c < a.C; c += blockDim.x) {
+        double s = 0.0;
+        for (int t = 0; t < a.l; ++t) s += (double)s_alpha[t] * (double)a.enc_h[(size_t)t * a.C + c];
+        a.ctx[(size_t)b * a.C + c] = (float)s;
+    }
+}
+
+// ========================================================================== readout ==
+
+struct ReadoutArgs {
+    const int8_t *Ws, *Wy, *Wc;
+    const float *b_t, *s, *y, *c;
+    float *t_out;
+    q8_taps ts, ty, tc;
+    int R, H, E, C, lds, ldy, ldc, lpr;
+    float ss_w, sy_w, sc_w;
+};
+
+// t = tanh(((W_s q(s) + W_y q(y)) + W_c q(ctx)) + b_t): first layer of g (Eq. 2).
+template <int N>
+__global__ __launch_bounds__(256) void readout_kernel(ReadoutArgs a)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    __shared__ float s_scale[24];
+    __shared__ float s_red[8 * 4];
+    int8_t *sq = smem, *yq = sq + N * a.lds, *cq = yq + N * a.ldy;
+    block_quantize<N>(a.s, N, a.H, a.H, a.lds, sq, s_scale, s_red);
+    block_quantize<N>(a.y, N, a.E, a.E, a.ldy, yq, s_scale + 8, s_red);
+    block_quantize<N>(a.c, N, a.C, a.C, a.ldc, cq, s_scale + 16, s_red);
+    if (blockIdx.x == 0) {
+        const q8_taps *tp[3] = {&a.ts, &a.ty, &a.tc};
+        const int8_t *src[3] = {sq, yq, cq};
+        const int dim[3] = {a.H, a.E, a.C}, ldq[3] = {a.lds, a.ldy, a.ldc};
+        for (int m = 0; m < 3; ++m) {
+            if (tp[m]->xq)
+                for (int e = threadIdx.x; e < N * dim[m]; e += blockDim.x)
+                    tp[m]->xq[e] = src[m][(e / dim[m]) * ldq[m] + e % dim[m]];
+            if (tp[m]->xscale && threadIdx.x < N) tp[m]->xscale[threadIdx.x] = s_scale[8 * m + threadIdx.x];
+        }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lpr = a.lpr, lir = lane & (lpr - 1), sg = lane / lpr, upw = 64 / lpr;
+    float cs = 0.0f, cy = 0.0f, cc = 0.0f;
+    if (lir < N) {
+        cs = a.ss_w * s_scale[lir];
+        cy = a.sy_w * s_scale[8 + lir];
+        cc = a.sc_w * s_scale[16 + lir];
+    }
+    for (int u0 = (blockIdx.x * 4 + wave) * upw; u0 < a.R; u0 += gridDim.x * 4 * upw) {
+        const int unit = u0 + sg;
+        const bool ok = unit < a.R;
+        int as[1][N], ay[1][N], ac[1][N];
+        const int8_t *w1[1];
+        w1[0] = ok ? a.Ws + (size_t)unit * a.lds : nullptr;
+        wave_dot<N, 1>(w1, a.lds, lpr, lir, sq, as);
+        w1[0] = ok ? a.Wy + (size_t)unit * a.ldy : nullptr;
+        wave_dot<N, 1>(w1, a.ldy, lpr, lir, yq, ay);
+        w1[0] = ok ? a.Wc + (size_t)unit * a.ldc : nullptr;
+        wave_dot<N, 1>(w1, a.ldc, lpr, lir, cq, ac);
+        if (ok && lir < N) {
+            int vs = 0, vy = 0, vc = 0;
+#pragma unroll
+            for (int jj = 0; jj < N; ++jj) {
+                vs = (lir == jj) ? as[0][jj] : vs;
+                vy = (lir == jj) ? ay[0][jj] : vy;
+                vc = (lir == jj) ? ac[0][jj] : vc;
+            }
+            const float u1 = (float)vs * cs, u2 = (float)vy * cy, u3 = (float)vc * cc;
+            float p = u1 + u2;
+            p = p + u3;
+            if (a.b_t) p = p + a.b_t[unit];
+            a.t_out[(size_t)lir * a.R + unit] = tanh_rn(p);
+            if (a.ts.acc) a.ts.acc[(size_t)lir * a.R + unit] = vs;
+            if (a.ty.acc) a.ty.acc[(size_t)lir * a.R + unit] = vy;
+            if (a.tc.acc) a.tc.acc[(size_t)lir * a.R + unit] = vc;
+        }
+    }
+}
+
+// ===================================================== vocabulary layer: logits pass ==
+
+#define OUT_RB 128   // vocabulary rows per block: 4 waves x 2 tiles of 16 rows
+
+struct OutArgs {
+    const int8_t *W;
+    const float *T, *bias;
+    float *logits;
+    float *part_max;
+    double *part_sum;
+    float *cand_val;
+    int *cand_idx;
+    q8_taps taps;
+    int V, K, ld, ldt, n, k, ldl;
+    float w_scale;
+};
+
+// One pass over W_out for all n <= 8 hypotheses on the int8 matrix cores (operand layout
+// as in gemm_mfma_kernel), fused with bias, the per-block softmax partials (max, sum of
+// exp) and the per-block k best logits of every hypothesis.
+__global__ __launch_bounds__(256) void out_logits_kernel(OutArgs a)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    __shared__ float s_scale[8];
+    __shared__ float s_red[8 * 4];
+    __shared__ float s_log[8][OUT_RB];
+    const int ld = a.ld, n = a.n;
+    block_quantize<8>(a.T, n, a.K, a.ldt, ld, smem, s_scale, s_red);
+    if (blockIdx.x == 0) {
+        if (a.taps.xq)
+            for (int e = threadIdx.x; e < n * a.K; e += blockDim.x) a.taps.xq[e] = smem[(e / a.K) * ld + e % a.K];
+        if (a.taps.xscale && threadIdx.x < n) a.taps.xscale[threadIdx.x] = s_scale[threadIdx.x];
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int brow0 = blockIdx.x * OUT_RB;
+    const float cj = i < n ? a.w_scale * s_scale[i] : 0.0f;
+    const int8_t *xb = smem + (size_t)i * ld + 16 * g;
+
+    for (int tile = wave; tile < OUT_RB / 16; tile += 4) {
+        const int r0 = brow0 + tile * 16;
+        const bool row_ok = r0 + i < a.V;
+        const int8_t *wp = a.W + (size_t)(r0 + i) * ld + 16 * g;
+        v4i acc = (v4i){0, 0, 0, 0};
+        for (int k0 = 0; k0 < ld; k0 += 256) {
+            v4i av[4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                av[s] = (v4i){0, 0, 0, 0};
+                if (row_ok && k0 + 64 * s + 16 * g < ld) av[s] = *(const v4i *)(wp + k0 + 64 * s);
+            }
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                v4i bv = (v4i){0, 0, 0, 0};
+                if (i < n && k0 + 64 * s + 16 * g < ld) bv = *(const v4i *)(xb + k0 + 64 * s);
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[s], bv, acc, 0, 0, 0);
+            }
+        }
+        if (i < n) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = r0 + 4 * g + r;
+                float y = -INFINITY;
+                if (row < a.V) {
+                    y = (float)acc[r] * cj;
+                    if (a.bias) y = y + a.bias[row];
+                    if (a.logits) a.logits[(size_t)i * a.ldl + row] = y;
+                    if (a.taps.acc) a.taps.acc[(size_t)i * a.V + row] = acc[r];
+                }
+                s_log[i][row - brow0] = y;
+            }
+        }
+    }
+    __syncthreads();
+
+    for (int j = wave; j < n; j += 4) {
+        const float v0 = s_log[j][lane], v1 = s_log[j][lane + 64];
+        const float m = wave_max_f(fmaxf(v0, v1));
+        double s = 0.0;
+        if (brow0 + lane < a.V) s += exp((double)v0 - (double)m);
+        if (brow0 + lane + 64 < a.V) s += exp((double)v1 - (double)m);
+        s = wave_sum_d(s);
+        if (lane == 0) {
+            a.part_max[(size_t)blockIdx.x * n + j] = m;
+            a.part_sum[(size_t)blockIdx.x * n + j] = s;
+        }
+        unsigned long long k0 = brow0 + lane < a.V ? topk_key(v0, brow0 + lane) : 0ull;
+        unsigned long long k1 = brow0 + lane + 64 < a.V ? topk_key(v1, brow0 + lane + 64) : 0ull;
+        for (int r = 0; r < a.k; ++r) {
+            const unsigned long long best = wave_max_u64(k0 > k1 ? k0 : k1);
+            if (lane == 0) {
+                const size_t o = ((size_t)blockIdx.x * n + j) * a.k + r;
+                a.cand_val[o] = best ? topk_key_val(best) : -INFINITY;
+                a.cand_idx[o] = best ? topk_key_idx(best) : -1;
+            }
+            if (best) {
+                if (k0 == best) k0 = 0ull;
+                if (k1 == best) k1 = 0ull;
+            }
+        }
+    }
+}
+
+struct MergeArgs {
+    const float *part_max;
+    const double *part_sum;
+    const float *cand_val;
+    const int *cand_idx;
+    float *lse, *topk_logp;
+    int *topk_idx;
+    int nblk, n, k;
+};
+
+// One wave per hypothesis: log-sum-exp from the per-block partials, then a k-way merge
+// of the per-block candidate lists (each sorted), only the list heads competing.
+__global__ __launch_bounds__(64) void out_merge_kernel(MergeArgs a)
+{
+    __shared__ unsigned long long s_head[1024];
+    __shared__ unsigned char s_ptr[1024];
+    const int j = blockIdx.x, lane = threadIdx.x, n = a.n, k = a.k;
+    float m = -INFINITY;
+    for (int b = lane; b < a.nblk; b += 64) m = fmaxf(m, a.part_max[(size_t)b * n + j]);
+    m = wave_max_f(m);
+    double S = 0.0;
+    for (int b = lane; b < a.nblk; b += 64)
+        S += a.part_sum[(size_t)b * n + j] * exp((double)a.part_max[(size_t)b * n + j] - (double)m);
+    S = wave_sum_d(S);
+    const float lse = (float)((double)m + log(S));
+    if (lane == 0 && a.lse) a.lse[j] = lse;
+
+    for (int b = lane; b < a.nblk; b += 64) {
+        const size_t o = ((size_t)b * n + j) * k;
+        const int idx = a.cand_idx[o];
+        s_head[b] = idx >= 0 ? topk_key(a.cand_val[o], idx) : 0ull;
+        s_ptr[b] = 0;
+    }
+    __syncthreads();
+    for (int r = 0; r < k; ++r) {
+        unsigned long long best = 0ull;
+        for (int b = lane; b < a.nblk; b += 64) best = s_head[b] > best ? s_head[b] : best;
+        best = wave_max_u64(best);
+        const int idx = best ? topk_key_idx(best) : -1;
+        if (lane == 0) {
+            a.topk_idx[(size_t)j * k + r] = idx;
+            a.topk_logp[(size_t)j * k + r] = best ? topk_key_val(best) - lse : -INFINITY;
+        }
+        if (best) {
+            const int b = idx / OUT_RB;
+            if ((b & 63) == lane) {
+                const int p = ++s_ptr[b];
+                unsigned long long nk = 0ull;
+                if (p < k) {
+                    const size_t o = ((size_t)b * n + j) * k + p;
+                    const int ni = a.cand_idx[o];
+                    nk = ni >= 0 ? topk_key(a.cand_val[o], ni) : 0ull;
+                }
+                s_head[b] = nk;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// =================================================================== host launchers ==
+
+static q8_status launch_check(q8_ctx *ctx, const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+    return Q8_OK;
+}
+
+q8_status q8i_quantize_matrix(q8_ctx *ctx, const float *W, int rows, int cols, int ld_in, int8_t *Wq, int ld_out,
+                              float *scale_host)
+{
+    unsigned *slot = (unsigned *)(ctx->ws + Q8_WS_SCRATCH_SLOT);
+    float *scale_dev = (float *)(slot + 1);
+    const size_t total = (size_t)rows * cols;
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(absmax_kernel, dim3(blocks), dim3(256), 0, ctx->stream, W, rows, cols, ld_in, slot);
+    hipLaunchKernelGGL(quantize_matrix_kernel, dim3(blocks), dim3(256), 0, ctx->stream, W, rows, cols, ld_in, Wq,
+                       ld_out, slot, scale_dev);
+    q8_status st = launch_check(ctx, "q8_quantize_matrix");
+    if (st) return st;
+    hipError_t e = hipMemcpyAsync(scale_host, scale_dev, sizeof(float), hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, ctx->stream, slot, 2, 0u);
+        e = hipStreamSynchronize(ctx->stream);
+    }
+    if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "q8_quantize_matrix: %s", hipGetErrorString(e));
+    return Q8_OK;
+}
+
+q8_status q8i_fill_u32(q8_ctx *ctx, void *p, int n, unsigned v)
+{
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, (unsigned *)p, n, v);
+    return launch_check(ctx, "fill");
+}
+
+template <int N>
+static void launch_gemv_n(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t smem)
+{
+    hipLaunchKernelGGL(gemv_jobs_kernel<N>, dim3(blocks), dim3(256), smem, ctx->stream, jobs);
+}
+
+// Fills the launch geometry of a job: rows per block so that large matrices spread
+// over about 1024 blocks and every block runs whole 4-wave row passes.
+static int gemv_job_geometry(GemvJob &J, int block0)
+{
+    J.lpr = q8_lanes_per_row(J.ld);
+    const int pass = 4 * (64 / J.lpr) * 4;            // rows covered by one block iteration
+    int rpb = (J.rows + 1023) / 1024;
+    rpb = (rpb + pass - 1) / pass * pass;
+    J.rpb = rpb;
+    J.block0 = block0;
+    return (J.rows + rpb - 1) / rpb;
+}
+
+q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
+{
+    GemvJobs jobs;
+    jobs.njobs = njobs;
+    int blocks = 0, max_ld = 0;
+    for (int t = 0; t < njobs; ++t) {
+        GemvJob &J = jobs.j[t];
+        J.W = d[t].W->data; J.X = d[t].X; J.bias = d[t].bias; J.Y = d[t].Y;
+        J.tap_xq = d[t].taps ? d[t].taps->xq : nullptr;
+        J.tap_xscale = d[t].taps ? d[t].taps->xscale : nullptr;
+        J.tap_acc = d[t].taps ? d[t].taps->acc : nullptr;
+        J.rows = d[t].W->rows; J.cols = d[t].W->cols; J.ld = d[t].W->ld;
+        J.ldx = d[t].ldx; J.ldy = d[t].ldy; J.w_scale = d[t].W->scale;
+        blocks += gemv_job_geometry(J, blocks);
+        if (J.ld > max_ld) max_ld = J.ld;
+    }
+    const size_t smem = (size_t)n * max_ld;
+    switch (n) {
+    case 1: launch_gemv_n<1>(ctx, jobs, blocks, smem); break;
+    case 2: launch_gemv_n<2>(ctx, jobs, blocks, smem); break;
+    case 3: launch_gemv_n<3>(ctx, jobs, blocks, smem); break;
+    case 4: launch_gemv_n<4>(ctx, jobs, blocks, smem); break;
+    case 5: launch_gemv_n<5>(ctx, jobs, blocks, smem); break;
+    case 6: launch_gemv_n<6>(ctx, jobs, blocks, smem); break;
+    case 7: launch_gemv_n<7>(ctx, jobs, blocks, smem); break;
+    default: launch_gemv_n<8>(ctx, jobs, blocks, smem); break;
+    }
+    return launch_check(ctx, "gemv");
+}
+
+q8_status q8i_gemm_mfma(q8_ctx *ctx, const q8_mat *W, const float *X, int n, int ldx, const float *bias, float *Y,
+                        int ldy, const q8_taps *taps, int8_t *xq, float *xscale)
+{
+    hipLaunchKernelGGL(quantize_rows_kernel, dim3(n), dim3(256), 0, ctx->stream, X, W->cols, ldx, W->ld, xq, xscale,
+                       taps ? taps->xq : nullptr);
+    if (taps && taps->xscale) {
+        hipError_t e = hipMemcpyAsync(taps->xscale, xscale, sizeof(float) * n, hipMemcpyDeviceToDevice, ctx->stream);
+        if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "tap copy: %s", hipGetErrorString(e));
+    }
+    MfmaArgs a;
+    a.W = W->data; a.xq = xq; a.xscale = xscale; a.bias = bias; a.Y = Y;
+    a.tap_acc = taps ? taps->acc : nullptr;
+    a.rows = W->rows; a.ld = W->ld; a.n = n; a.ldy = ldy; a.w_scale = W->scale;
+    const int blocks = (W->rows + 63) / 64;
+    const int tiles = (n + 15) / 16;
+    if (tiles == 1) hipLaunchKernelGGL(gemm_mfma_kernel<1>, dim3(blocks), dim3(256), 0, ctx->stream, a);
+    else if (tiles == 2) hipLaunchKernelGGL(gemm_mfma_kernel<2>, dim3(blocks), dim3(256), 0, ctx->stream, a);
+    else hipLaunchKernelGGL(gemm_mfma_kernel<4>, dim3(blocks), dim3(256), 0, ctx->stream, a);
+    return launch_check(ctx, "gemm_mfma");
+}
+
+template <int N>
+static void launch_gru_n(q8_ctx *ctx, const GruJobs &jobs, int njobs, int mode, int blocks, size_t smem)
+{
+    dim3 grid(blocks, njobs);
+    if (mode == GRU_FULL) hipLaunchKernelGGL((gru_kernel<N, GRU_FULL>), grid, dim3(256), smem, ctx->stream, jobs);
+    else if (mode == GRU_GX_PRE) hipLaunchKernelGGL((gru_kernel<N, GRU_GX_PRE>), grid, dim3(256), smem, ctx->stream, jobs);
+    else hipLaunchKernelGGL((gru_kernel<N, GRU_GH_PRE>), grid, dim3(256), smem, ctx->stream, jobs);
+}
+
+q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode)
+{
+    GruJobs jobs;
+    int blocks = 0;
+    size_t smem = 0;
+    for (int t = 0; t < njobs; ++t) {
+        GruJob &J = jobs.j[t];
+        const q8_gru_weights *g = d[t].g;
+        J.Wx = g->Wx.data; J.Wh = g->Wh.data; J.bx = g->bx; J.bh = g->bh;
+        J.x = d[t].x; J.h_prev = d[t].h_prev; J.g_pre = d[t].g_pre; J.h_out = d[t].h_out;
+        q8_taps none = {nullptr, nullptr, nullptr};
+        J.tx = d[t].taps ? d[t].taps[0] : none;
+        J.th = d[t].taps ? d[t].taps[1] : none;
+        J.I = g->Wx.cols; J.ldwx = g->Wx.ld; J.H = g->Wh.cols; J.ldwh = g->Wh.ld;
+        J.ldx = d[t].ldx; J.ldh = d[t].ldh; J.ldo = d[t].ldo; J.ldg = d[t].ldg;
+        J.sx_w = g->Wx.scale; J.sh_w = g->Wh.scale;
+        int ldmin = mode == GRU_GX_PRE ? J.ldwh : (mode == GRU_GH_PRE ? J.ldwx : (J.ldwx < J.ldwh ? J.ldwx : J.ldwh));
+        J.lpr = q8_lanes_per_row(ldmin);
+        const int upb = 4 * (64 / J.lpr);
+        const int b = (J.H + upb - 1) / upb;
+        if (b > blocks) blocks = b;
+        size_t s = (size_t)n * ((mode == GRU_GX_PRE ? 0 : J.ldwx) + (mode == GRU_GH_PRE ? 0 : J.ldwh));
+        if (s > smem) smem = s;
+    }
+    switch (n) {
+    case 1: launch_gru_n<1>(ctx, jobs, njobs, mode, blocks, smem); break;
+    case 2: launch_gru_n<2>(ctx, jobs, njobs, mode, blocks, smem); break;
+    case 3: launch_gru_n<3>(ctx, jobs, njobs, mode, blocks, smem); break;
+    case 4: launch_gru_n<4>(ctx, jobs, njobs, mode, blocks, smem); break;
+    case 5: launch_gru_n<5>(ctx, jobs, njobs, mode, blocks, smem); break;
+    case 6: launch_gru_n<6>(ctx, jobs, njobs, mode, blocks, smem); break;
+    case 7: launch_gru_n<7>(ctx, jobs, njobs, mode, blocks, smem); break;
+    default: launch_gru_n<8>(ctx, jobs, njobs, mode, blocks, smem); break;
+    }
+    return launch_check(ctx, "gru");
+}
+
+q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, int A, int C, const float *a,
+                        const float *v, int n, float *e, float *alpha, float *cvec)
+{
+    AttArgs t;
+    t.P = P; t.enc_h = enc_h; t.a = a; t.v = v; t.e = e; t.alpha = alpha; t.ctx = cvec;
+    t.counters = (unsigned *)ctx->ws;
+    t.l = l; t.A = A; t.C = C;
+    hipLaunchKernelGGL(attention_kernel, dim3(l, n), dim3(256), 0, ctx->stream, t);
+    return launch_check(ctx, "attention");
+}
+
+q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,
+                      float *t_out, const q8_taps *taps3)
+{
+    ReadoutArgs a;
+    a.Ws = ro->W_s.data; a.Wy = ro->W_y.data; a.Wc = ro->W_c.data; a.b_t = ro->b_t;
+    a.s = s; a.y = y; a.c = c; a.t_out = t_out;
+    q8_taps none = {nullptr, nullptr, nullptr};
+    a.ts = taps3 ? taps3[0] : none; a.ty = taps3 ? taps3[1] : none; a.tc = taps3 ? taps3[2] : none;
+    a.R = ro->W_s.rows; a.H = ro->W_s.cols; a.E = ro->W_y.cols; a.C = ro->W_c.cols;
+    a.lds = ro->W_s.ld; a.ldy = ro->W_y.ld; a.ldc = ro->W_c.ld;
+    int ldmin = a.lds < a.ldy ? a.lds : a.ldy;
+    if (a.ldc < ldmin) ldmin = a.ldc;
+    a.lpr = q8_lanes_per_row(ldmin);
+    a.ss_w = ro->W_s.scale; a.sy_w = ro->W_y.scale; a.sc_w = ro->W_c.scale;
+    const int upb = 4 * (64 / a.lpr);
+    const int blocks = (a.R + upb - 1) / upb;
+    const size_t smem = (size_t)n * (a.lds + a.ldy + a.ldc);
+    switch (n) {
+    case 1: hipLaunchKernelGGL(readout_kernel<1>, dim3(blocks), dim3(256), smem, ctx->stream, a); break;
+    case 2: hipLaunchKernelGGL(readout_kernel<2>, dim3(blocks), dim3(256), smem, ctx->stream, a); break;
+    case 3: hipLaunchKernelGGL(readout_kernel<3>, dim3(blocks), dim3(256), smem, ctx->stream, a); break;
+    case 4: hipLaunchKernelGGL(readout_kernel<4>, dim3(blocks), dim3(256), smem, ctx->stream, a); break;
+    case 5: hipLaunchKernelGGL(readout_kernel<5>, dim3(blocks), dim3(256), smem, ctx->stream, a); break;
+    case 6: hipLaunchKernelGGL(readout_kernel<6>, dim3(blocks), dim3(256), smem, ctx->stream, a); break;
+    case 7: hipLaunchKernelGGL(readout_kernel<7>, dim3(blocks), dim3(256), smem, ctx->stream, a); break;
+    default: hipLaunchKernelGGL(readout_kernel<8>, dim3(blocks), dim3(256), smem, ctx->stream, a); break;
+    }
+    return launch_check(ctx, "readout");
+}
+
+int q8i_out_blocks(int V) { return (V + OUT_RB - 1) / OUT_RB; }
+
+q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const float *T, int ldt, int n, int k,
+                     float *logits, float *lse, float *topk_logp, int32_t *topk_idx, const q8_taps *taps,
+                     float *part_max, double *part_sum, float *cand_val, int *cand_idx)
+{
+    OutArgs a;
+    a.W = W->data; a.T = T; a.bias = bias; a.logits = logits;
+    a.part_max = part_max; a.part_sum = part_sum; a.cand_val = cand_val; a.cand_idx = cand_idx;
+    q8_taps none = {nullptr, nullptr, nullptr};
+    a.taps = taps ? *taps : none;
+    a.V = W->rows; a.K = W->cols; a.ld = W->ld; a.ldt = ldt; a.n = n; a.k = k; a.ldl = W->rows;
+    a.w_scale = W->scale;
+    const int nblk = q8i_out_blocks(a.V);
+    hipLaunchKernelGGL(out_logits_kernel, dim3(nblk), dim3(256), (size_t)n * a.ld, ctx->stream, a);
+    MergeArgs m;
+    m.part_max = part_max; m.part_sum = part_sum; m.cand_val = cand_val; m.cand_idx = cand_idx;
+    m.lse = lse; m.topk_logp = topk_logp; m.topk_idx = topk_idx;
+    m.nblk = nblk; m.n = n; m.k = k;
+    hipLaunchKernelGGL(out_merge_kernel, dim3(n), dim3(64), 0, ctx->stream, m);
+    return launch_check(ctx, "output");
+}
