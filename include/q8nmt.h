@@ -165,6 +165,15 @@ q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_m
 q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights *bwd,
                     const float *X, int l, float *enc_h);
 
+/* Measurement helper (not an operation of the paper): between q8_profile_begin and
+ * q8_profile_end, up to max_samples launches of the vocabulary-layer kernel of
+ * output_logits_q8 carry a pair of HIP events that take the kernel's own begin and
+ * end timestamps.  q8_profile_end waits for the stream and returns the average
+ * kernel duration in milliseconds and the number of samples (host pointers, may be
+ * NULL).  Not for use under stream capture. */
+q8_status q8_profile_begin(q8_ctx *ctx, int max_samples);
+q8_status q8_profile_end(q8_ctx *ctx, float *avg_ms_host, int *samples_host);
+
 #ifdef __cplusplus
 }
 #endif

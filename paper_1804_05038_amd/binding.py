@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 
 __all__ = ["Q8Error", "Context", "Mat", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
            "q8_quantize_matrix", "q8_gemv", "q8_gemm_narrow", "gru_step_q8", "cgru_decoder_step_q8",
-           "output_logits_q8", "q8_encode", "q8_workspace_bytes", "LIB_PATH"]
+           "output_logits_q8", "q8_encode", "q8_workspace_bytes", "q8_profile_begin", "q8_profile_end", "LIB_PATH"]
 LIB_PATH = _LIB_PATH
 
 STATUS = {0: "Q8_OK", 1: "Q8_ERR_NULL", 2: "Q8_ERR_SHAPE", 3: "Q8_ERR_ALIGN", 4: "Q8_ERR_WORKSPACE", 5: "Q8_ERR_DEVICE"}
@@ -72,6 +72,8 @@ def load_library():
         lib.output_logits_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, vp, ci, ci,
                                          vp, vp, vp, vp, vp, C.POINTER(_Taps)]
         lib.q8_encode.argtypes = [vp, C.POINTER(_Gru), C.POINTER(_Gru), vp, ci, vp]
+        lib.q8_profile_begin.argtypes = [vp, ci]
+        lib.q8_profile_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int)]
         _lib = lib
     return _lib
 
@@ -140,6 +142,19 @@ class Mat:
         self.c = _Mat(data.data_ptr(), self.rows, cols, self.ld, self.scale)
 
 
+class _Bound:
+    """A call with its arguments already marshalled: launch() re-issues it on the same
+    buffers (what a decode loop or a captured graph needs); results live in .out."""
+
+    def __init__(self, ctx, fn, args, out):
+        self.ctx, self.fn, self.args, self.out = ctx, fn, args, out
+
+    def launch(self):
+        st = self.fn(*self.args)
+        if st != 0:
+            self.ctx.check(st)
+
+
 class _TapSet:
     def __init__(self, ctx, specs):
         """specs: list of (n, cols, rows) per product."""
@@ -206,7 +221,7 @@ def gru_step_q8(ctx, g, x, h_prev, h_out=None, taps=False):
     return (h_out, ts.t) if taps else h_out
 
 
-def cgru_decoder_step_q8(ctx, w, P, enc_h, y_emb, s_prev, out=None, taps=False):
+def cgru_decoder_step_q8(ctx, w, P, enc_h, y_emb, s_prev, out=None, taps=False, bind=False):
     """Returns dict(s, ctx, alpha, s_mid) (+ 'taps': five entries)."""
     n, l = y_emb.shape[0], P.shape[0]
     H, Cd = w.r.H, w.q.Wx.cols
@@ -221,16 +236,20 @@ def cgru_decoder_step_q8(ctx, w, P, enc_h, y_emb, s_prev, out=None, taps=False):
     if taps:
         A = w.att_U.rows
         ts = _TapSet(ctx, [(n, w.r.Wx.cols, 3 * H), (n, H, 3 * H), (n, H, A), (n, Cd, 3 * H), (n, H, 3 * H)])
-    ctx.check(ctx.lib.cgru_decoder_step_q8(ctx.handle, C.byref(w.c), _ptr(P), _ptr(enc_h), l, _ptr(y_emb), _ptr(s_prev), n,
-                                           _ptr(s_out), _ptr(c_out), _ptr(alpha), _ptr(s_mid), ts.arr if ts else None))
+    args = (ctx.handle, C.byref(w.c), _ptr(P), _ptr(enc_h), l, _ptr(y_emb), _ptr(s_prev), n,
+            _ptr(s_out), _ptr(c_out), _ptr(alpha), _ptr(s_mid), ts.arr if ts else None)
     r = {"s": s_out, "ctx": c_out, "alpha": alpha, "s_mid": s_mid}
     if taps:
         r["taps"] = ts.t
+    if bind:
+        r["keep"] = (w, P, enc_h, y_emb, s_prev)
+        return _Bound(ctx, ctx.lib.cgru_decoder_step_q8, args, r)
+    ctx.check(ctx.lib.cgru_decoder_step_q8(*args))
     return r
 
 
 def output_logits_q8(ctx, ro, W_out, b_out, s=None, y_emb=None, ctx_vec=None, t_in=None, k=12,
-                     want_logits=True, taps=False):
+                     want_logits=True, taps=False, bind=False):
     """Returns dict(logits?, lse, topk_logp, topk_idx, t?) (+ 'taps': four entries)."""
     n = (t_in if ro is None else s).shape[0]
     V, R = W_out.rows, W_out.cols
@@ -246,12 +265,16 @@ def output_logits_q8(ctx, ro, W_out, b_out, s=None, y_emb=None, ctx_vec=None, t_
         else:
             specs = [(1, 1, 1)] * 3 + [(n, R, V)]
         ts = _TapSet(ctx, specs)
-    ctx.check(ctx.lib.output_logits_q8(ctx.handle, C.byref(ro.c) if ro is not None else None, C.byref(W_out.c), _ptr(b_out),
-                                       _ptr(s), _ptr(y_emb), _ptr(ctx_vec), _ptr(t_in), n, k, _ptr(logits), _ptr(lse),
-                                       _ptr(lp), _ptr(idx), _ptr(t_out), ts.arr if ts else None))
+    args = (ctx.handle, C.byref(ro.c) if ro is not None else None, C.byref(W_out.c), _ptr(b_out),
+            _ptr(s), _ptr(y_emb), _ptr(ctx_vec), _ptr(t_in), n, k, _ptr(logits), _ptr(lse),
+            _ptr(lp), _ptr(idx), _ptr(t_out), ts.arr if ts else None)
     r = {"logits": logits, "lse": lse, "topk_logp": lp, "topk_idx": idx, "t": t_out}
     if taps:
         r["taps"] = ts.t
+    if bind:
+        r["keep"] = (ro, W_out, b_out, s, y_emb, ctx_vec, t_in)
+        return _Bound(ctx, ctx.lib.output_logits_q8, args, r)
+    ctx.check(ctx.lib.output_logits_q8(*args))
     return r
 
 
@@ -260,3 +283,13 @@ def q8_encode(ctx, fwd, bwd, X, enc_h=None):
     enc_h = ctx.empty(l, 2 * fwd.H) if enc_h is None else enc_h
     ctx.check(ctx.lib.q8_encode(ctx.handle, C.byref(fwd.c), C.byref(bwd.c), _ptr(X), l, _ptr(enc_h)))
     return enc_h
+
+
+def q8_profile_begin(ctx, max_samples):
+    ctx.check(ctx.lib.q8_profile_begin(ctx.handle, max_samples))
+
+
+def q8_profile_end(ctx):
+    ms, n = C.c_float(), C.c_int()
+    ctx.check(ctx.lib.q8_profile_end(ctx.handle, C.byref(ms), C.byref(n)))
+    return ms.value, n.value

@@ -97,6 +97,8 @@ q8_status q8_create(q8_ctx **out, void *hip_stream, void *workspace, size_t work
     c->ws = (char *)workspace;
     c->ws_bytes = workspace_bytes;
     c->err[0] = 0;
+    c->prof_ev = nullptr;
+    c->prof_cap = c->prof_n = 0;
     q8_status st = q8i_fill_u32(c, c->ws, Q8_WS_HEADER / 4, 0u);
     if (st) { delete c; return st; }
     *out = c;
@@ -106,8 +108,52 @@ q8_status q8_create(q8_ctx **out, void *hip_stream, void *workspace, size_t work
 q8_status q8_destroy(q8_ctx *ctx)
 {
     if (!ctx) return Q8_ERR_NULL;
+    if (ctx->prof_ev) q8_profile_end(ctx, nullptr, nullptr);
     delete ctx;
     return Q8_OK;
+}
+
+q8_status q8_profile_begin(q8_ctx *ctx, int max_samples)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (max_samples <= 0 || max_samples > 65536) return q8_fail(ctx, Q8_ERR_SHAPE, "max_samples outside [1, 65536]");
+    if (ctx->prof_ev) q8_profile_end(ctx, nullptr, nullptr);
+    ctx->prof_ev = (hipEvent_t *)calloc(2 * (size_t)max_samples, sizeof(hipEvent_t));
+    if (!ctx->prof_ev) return q8_fail(ctx, Q8_ERR_DEVICE, "out of host memory");
+    for (int i = 0; i < 2 * max_samples; ++i)
+        if (hipEventCreate(&ctx->prof_ev[i]) != hipSuccess) {
+            for (int t = 0; t < i; ++t) (void)hipEventDestroy(ctx->prof_ev[t]);
+            free(ctx->prof_ev);
+            ctx->prof_ev = nullptr;
+            return q8_fail(ctx, Q8_ERR_DEVICE, "hipEventCreate failed");
+        }
+    ctx->prof_cap = max_samples;
+    ctx->prof_n = 0;
+    return Q8_OK;
+}
+
+q8_status q8_profile_end(q8_ctx *ctx, float *avg_ms_host, int *samples_host)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!ctx->prof_ev) return q8_fail(ctx, Q8_ERR_SHAPE, "q8_profile_end without q8_profile_begin");
+    q8_status st = Q8_OK;
+    double sum = 0.0;
+    int n = 0;
+    if (hipStreamSynchronize(ctx->stream) != hipSuccess) st = q8_fail(ctx, Q8_ERR_DEVICE, "stream synchronize failed");
+    for (int i = 0; i < ctx->prof_n && st == Q8_OK; ++i) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]) == hipSuccess) {
+            sum += ms;
+            ++n;
+        }
+    }
+    for (int i = 0; i < 2 * ctx->prof_cap; ++i) (void)hipEventDestroy(ctx->prof_ev[i]);
+    free(ctx->prof_ev);
+    ctx->prof_ev = nullptr;
+    ctx->prof_cap = ctx->prof_n = 0;
+    if (avg_ms_host) *avg_ms_host = n ? (float)(sum / n) : 0.0f;
+    if (samples_host) *samples_host = n;
+    return st;
 }
 
 const char *q8_last_error(const q8_ctx *ctx) { return ctx ? ctx->err : "NULL context"; }

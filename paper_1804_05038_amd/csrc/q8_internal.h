@@ -20,6 +20,9 @@ struct q8_ctx {
     char *ws;
     size_t ws_bytes;
     char err[256];
+    // kernel timing (q8_profile_begin / q8_profile_end): event pairs attached to dispatches
+    hipEvent_t *prof_ev;
+    int prof_cap, prof_n;
 };
 
 static inline q8_status q8_fail(q8_ctx *ctx, q8_status code, const char *fmt, ...)

@@ -5,6 +5,7 @@
 // attention, softmax, top-k) into the weight-streaming passes.
 #include "q8_internal.h"
 
+#include <hip/hip_ext.h>
 #include <math.h>
 
 // =============================================================== weight quantization ==
@@ -826,7 +827,14 @@ q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const floa
     a.V = W->rows; a.K = W->cols; a.ld = W->ld; a.ldt = ldt; a.n = n; a.k = k; a.ldl = W->rows;
     a.w_scale = W->scale;
     const int nblk = q8i_out_blocks(a.V);
-    hipLaunchKernelGGL(out_logits_kernel, dim3(nblk), dim3(256), (size_t)n * a.ld, ctx->stream, a);
+    if (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) {
+        // timed dispatch: the two events take the kernel's own begin and end timestamps
+        hipEvent_t e0 = ctx->prof_ev[2 * ctx->prof_n], e1 = ctx->prof_ev[2 * ctx->prof_n + 1];
+        ++ctx->prof_n;
+        hipExtLaunchKernelGGL(out_logits_kernel, dim3(nblk), dim3(256), (size_t)n * a.ld, ctx->stream, e0, e1, 0, a);
+    } else {
+        hipLaunchKernelGGL(out_logits_kernel, dim3(nblk), dim3(256), (size_t)n * a.ld, ctx->stream, a);
+    }
     MergeArgs m;
     m.part_max = part_max; m.part_sum = part_sum; m.cand_val = cand_val; m.cand_idx = cand_idx;
     m.lse = lse; m.topk_logp = topk_logp; m.topk_idx = topk_idx;
