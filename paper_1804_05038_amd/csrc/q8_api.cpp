@@ -9,7 +9,7 @@
 
 namespace {
 
-const int kMaxLd = 16384, kMaxNarrow = 8, kMaxMfmaN = 1024, kMaxL = 1024, kMaxK = 16, kMaxVocab = 131072;
+const int kMaxLd = 16384, kMaxNarrow = 8, kMaxMfmaN = 1024, kMaxL = 1024, kMaxK = 16;
 
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -231,7 +231,7 @@ q8_status cgru_decoder_step_q8(q8_ctx *ctx, const q8_cgru_weights *w, const floa
     if (E % 4 || H % 4 || C % 4 || A % 4) return q8_fail(ctx, Q8_ERR_ALIGN, "E, H, C, A must be multiples of 4");
     if (!w->att_v || !P || !enc_h || !y_emb || !s_prev || !s_out || !ctx_out)
         return q8_fail(ctx, Q8_ERR_NULL, "cgru_decoder_step_q8: NULL argument");
-    if (!aligned16(P) || !aligned16(enc_h) || !aligned16(y_emb) || !aligned16(s_prev) || !aligned16(s_out) || !aligned16(ctx_out))
+    if (!aligned16(w->att_v) || !aligned16(P) || !aligned16(enc_h) || !aligned16(y_emb) || !aligned16(s_prev) || !aligned16(s_out) || !aligned16(ctx_out))
         return q8_fail(ctx, Q8_ERR_ALIGN, "cgru_decoder_step_q8: fp32 buffers need 16-byte alignment");
     if (s_out == s_prev) return q8_fail(ctx, Q8_ERR_SHAPE, "s_out must not alias s_prev");
     if ((size_t)n * (w->r.Wx.ld + w->r.Wh.ld) > 65536 || (size_t)n * w->q.Wx.ld > 65536)
@@ -271,8 +271,9 @@ q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_m
     const int n = n_beam, R = W_out->cols, V = W_out->rows;
     if (n <= 0 || n > kMaxNarrow) return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam = %d outside [1, %d]", n, kMaxNarrow);
     if (k <= 0 || k > kMaxK || k > V) return q8_fail(ctx, Q8_ERR_SHAPE, "k = %d outside [1, min(%d, rows)]", k, kMaxK);
-    if (V > kMaxVocab) return q8_fail(ctx, Q8_ERR_SHAPE, "W_out has more than %d rows", kMaxVocab);
-    if (W_out->ld > 8192) return q8_fail(ctx, Q8_ERR_SHAPE, "W_out: ld above 8192");
+    if (q8i_out_blocks(V) > 1024 || (size_t)q8i_out_blocks(V) * k > (size_t)q8i_out_max_keys())
+        return q8_fail(ctx, Q8_ERR_SHAPE, "W_out: rows x k too large for the top-k merge (%d rows, k %d)", V, k);
+    if (W_out->ld > 4096) return q8_fail(ctx, Q8_ERR_SHAPE, "W_out: ld above 4096");
     if (R % 4) return q8_fail(ctx, Q8_ERR_ALIGN, "R must be a multiple of 4");
     if (!topk_logp || !topk_idx) return q8_fail(ctx, Q8_ERR_NULL, "top-k outputs: NULL");
     Carver cv(ctx);

@@ -1,0 +1,282 @@
+// q8_decoder.hip -- the float part of the attention of Eq. 5-6 and the first layer of the
+// output network g of Eq. 2 ("Pieces of Eight: 8-bit Neural Machine Translation").
+#include "q8_internal.h"
+
+// ======================================================================== attention ==
+
+struct AttArgs {
+    const float *P, *enc_h, *a, *v;
+    float *e, *alpha, *ctx;
+    unsigned *counters;     // one arrival counter per hypothesis, zero on entry and on exit
+    int l, A, C;
+};
+
+// Block (i, b): energy e[b, i] = sum_j v_j tanh(P[i, j] + a[b, j]) (Eq. 6).  The last
+// block to arrive for hypothesis b turns the energies into weights and the context
+// vector H_t (Eq. 5).  Sums run in double; every stored value is rounded once to fp32.
+__global__ __launch_bounds__(256) void attention_kernel(AttArgs a)
+{
+    __shared__ double s_red[4];
+    __shared__ float s_alpha[1024];
+    __shared__ int s_last;
+    const int i = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float *Pi = a.P + (size_t)i * a.A;
+    const float *ab = a.a + (size_t)b * a.A;
+    double acc = 0.0;
+    if ((a.A & 3) == 0) {
+        for (int j = tid * 4; j < a.A; j += 1024) {
+            const float4 p = *(const float4 *)(Pi + j), q = *(const float4 *)(ab + j), vv = *(const float4 *)(a.v + j);
+            acc += (double)vv.x * (double)tanh_rn(p.x + q.x);
+            acc += (double)vv.y * (double)tanh_rn(p.y + q.y);
+            acc += (double)vv.z * (double)tanh_rn(p.z + q.z);
+            acc += (double)vv.w * (double)tanh_rn(p.w + q.w);
+        }
+    } else {
+        for (int j = tid; j < a.A; j += 256) acc += (double)a.v[j] * (double)tanh_rn(Pi[j] + ab[j]);
+    }
+    acc = wave_sum_d(acc);
+    if (lane == 0) s_red[wave] = acc;
+    __syncthreads();
+    if (tid == 0) {
+        const double tot = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+        a.e[(size_t)b * a.l + i] = (float)tot;
+        __threadfence();
+        const unsigned prev = atomicAdd(&a.counters[b], 1u);
+        s_last = (prev == (unsigned)a.l - 1u);
+    }
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+
+    // softmax over the l energies of hypothesis b: one wave, lane t holds e[t], e[t+64], ...
+    const int l = a.l;
+    if (wave == 0) {
+        const float *e = a.e + (size_t)b * l;
+        float mx = -INFINITY;
+        for (int t = lane; t < l; t += 64) {
+            const float ev = __builtin_nontemporal_load(e + t);
+            s_alpha[t] = ev;
+            mx = fmaxf(mx, ev);
+        }
+        mx = wave_max_f(mx);
+        double Z = 0.0;
+        for (int t = lane; t < l; t += 64) Z += exp((double)s_alpha[t] - (double)mx);
+        Z = wave_sum_d(Z);
+        for (int t = lane; t < l; t += 64) {
+            const float al = (float)(exp((double)s_alpha[t] - (double)mx) / Z);
+            s_alpha[t] = al;
+            if (a.alpha) a.alpha[(size_t)b * l + t] = al;
+        }
+        if (lane == 0) a.counters[b] = 0;
+    }
+    __syncthreads();
+    // context: each thread owns groups of four adjacent columns
+    if ((a.C & 3) == 0) {
+        for (int c = tid * 4; c < a.C; c += 1024) {
+            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+            const float *h = a.enc_h + c;
+#pragma unroll 6
+            for (int t = 0; t < l; ++t) {
+                const float4 hv = *(const float4 *)(h + (size_t)t * a.C);
+                const double al = (double)s_alpha[t];
+                s0 += al * (double)hv.x; s1 += al * (double)hv.y; s2 += al * (double)hv.z; s3 += al * (double)hv.w;
+            }
+            *(float4 *)(a.ctx + (size_t)b * a.C + c) = make_float4((float)s0, (float)s1, (float)s2, (float)s3);
+        }
+    } else {
+        for (int c = tid; c < a.C; c += 256) {
+            double s = 0.0;
+            for (int t = 0; t < l; ++t) s += (double)s_alpha[t] * (double)a.enc_h[(size_t)t * a.C + c];
+            a.ctx[(size_t)b * a.C + c] = (float)s;
+        }
+    }
+}
+
+// ========================================================================== readout ==
+
+struct ReadoutArgs {
+    const int8_t *Ws, *Wy, *Wc;
+    const float *b_t, *s, *y, *c;
+    float *t_out;
+    q8_taps ts, ty, tc;
+    int R, H, E, C, lds, ldy, ldc, lpr;
+    float ss_w, sy_w, sc_w;
+};
+
+template <int N>
+__device__ __forceinline__ void readout_x_taps(const ReadoutArgs &a, const int8_t *sq, const int8_t *yq, const int8_t *cq,
+                                               const float *s_scale)
+{
+    const q8_taps *tp[3] = {&a.ts, &a.ty, &a.tc};
+    const int8_t *src[3] = {sq, yq, cq};
+    const int dim[3] = {a.H, a.E, a.C}, ldq[3] = {a.lds, a.ldy, a.ldc};
+    for (int m = 0; m < 3; ++m) {
+        if (tp[m]->xq)
+            for (int e = threadIdx.x; e < N * dim[m]; e += blockDim.x)
+                tp[m]->xq[e] = src[m][(e / dim[m]) * ldq[m] + e % dim[m]];
+        if (tp[m]->xscale && threadIdx.x < N) tp[m]->xscale[threadIdx.x] = s_scale[8 * m + threadIdx.x];
+    }
+}
+
+// t = tanh(((W_s q(s) + W_y q(y)) + W_c q(ctx)) + b_t): first layer of g (Eq. 2).  General shapes.
+template <int N>
+__global__ __launch_bounds__(256) void readout_kernel(ReadoutArgs a)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    __shared__ float s_scale[24];
+    __shared__ float s_red[8 * 4];
+    int8_t *sq = smem, *yq = sq + N * a.lds, *cq = yq + N * a.ldy;
+    block_quantize<N>(a.s, N, a.H, a.H, a.lds, sq, s_scale, s_red);
+    block_quantize<N>(a.y, N, a.E, a.E, a.ldy, yq, s_scale + 8, s_red);
+    block_quantize<N>(a.c, N, a.C, a.C, a.ldc, cq, s_scale + 16, s_red);
+    if (blockIdx.x == 0) readout_x_taps<N>(a, sq, yq, cq, s_scale);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lpr = a.lpr, lir = lane & (lpr - 1), sg = lane / lpr, upw = 64 / lpr;
+    float cs = 0.0f, cy = 0.0f, cc = 0.0f;
+    if (lir < N) {
+        cs = a.ss_w * s_scale[lir];
+        cy = a.sy_w * s_scale[8 + lir];
+        cc = a.sc_w * s_scale[16 + lir];
+    }
+    for (int u0 = (blockIdx.x * 4 + wave) * upw; u0 < a.R; u0 += gridDim.x * 4 * upw) {
+        const int unit = u0 + sg;
+        const bool ok = unit < a.R;
+        int as[1][N], ay[1][N], ac[1][N];
+        const int8_t *w1[1];
+        w1[0] = ok ? a.Ws + (size_t)unit * a.lds : nullptr;
+        wave_dot<N, 1>(w1, a.lds, lpr, lir, sq, as);
+        w1[0] = ok ? a.Wy + (size_t)unit * a.ldy : nullptr;
+        wave_dot<N, 1>(w1, a.ldy, lpr, lir, yq, ay);
+        w1[0] = ok ? a.Wc + (size_t)unit * a.ldc : nullptr;
+        wave_dot<N, 1>(w1, a.ldc, lpr, lir, cq, ac);
+        if (ok && lir < N) {
+            int vs = 0, vy = 0, vc = 0;
+#pragma unroll
+            for (int jj = 0; jj < N; ++jj) {
+                vs = (lir == jj) ? as[0][jj] : vs;
+                vy = (lir == jj) ? ay[0][jj] : vy;
+                vc = (lir == jj) ? ac[0][jj] : vc;
+            }
+            const float u1 = (float)vs * cs, u2 = (float)vy * cy, u3 = (float)vc * cc;
+            float p = u1 + u2;
+            p = p + u3;
+            if (a.b_t) p = p + a.b_t[unit];
+            a.t_out[(size_t)lir * a.R + unit] = tanh_rn(p);
+            if (a.ts.acc) a.ts.acc[(size_t)lir * a.R + unit] = vs;
+            if (a.ty.acc) a.ty.acc[(size_t)lir * a.R + unit] = vy;
+            if (a.tc.acc) a.tc.acc[(size_t)lir * a.R + unit] = vc;
+        }
+    }
+}
+
+// Rows of at most 1024 * CH bytes, dims % 4 == 0, one output unit per wave: everything is
+// requested up front, then quantized and dotted.
+template <int N, int CH>
+__global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    __shared__ float s_scale[24];
+    __shared__ float s_red[8 * 4];
+    int8_t *sq = smem, *yq = sq + N * a.lds, *cq = yq + N * a.ldy;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int unit = blockIdx.x * 4 + wave;
+    const bool ok = unit < a.R;
+
+    XRegs<N, CH> rs, ry, rc;
+    x_load<N, CH>(rs, a.s, N, a.H, a.H);
+    x_load<N, CH>(ry, a.y, N, a.E, a.E);
+    x_load<N, CH>(rc, a.c, N, a.C, a.C);
+    v4i ws[1][CH], wy[1][CH], wc[1][CH];
+    {
+        const int8_t *w1[1];
+        w1[0] = ok ? a.Ws + (size_t)unit * a.lds : nullptr;
+        rows_load<1, CH>(ws, w1, a.lds, lane);
+        w1[0] = ok ? a.Wy + (size_t)unit * a.ldy : nullptr;
+        rows_load<1, CH>(wy, w1, a.ldy, lane);
+        w1[0] = ok ? a.Wc + (size_t)unit * a.ldc : nullptr;
+        rows_load<1, CH>(wc, w1, a.ldc, lane);
+    }
+    float bt = 0.f;
+    if (ok && a.b_t) bt = a.b_t[unit];
+    x_finish<N, CH>(rs, N, a.lds, sq, s_scale, s_red);
+    x_finish<N, CH>(ry, N, a.ldy, yq, s_scale + 8, s_red);
+    x_finish<N, CH>(rc, N, a.ldc, cq, s_scale + 16, s_red);
+    if (blockIdx.x == 0) readout_x_taps<N>(a, sq, yq, cq, s_scale);
+
+    int as[1][N], ay[1][N], ac[1][N];
+    rows_dot<N, 1, CH>(ws, a.lds, lane, sq, as);
+    rows_dot<N, 1, CH>(wy, a.ldy, lane, yq, ay);
+    rows_dot<N, 1, CH>(wc, a.ldc, lane, cq, ac);
+    if (ok && lane < N) {
+        int vs = 0, vy = 0, vc = 0;
+#pragma unroll
+        for (int jj = 0; jj < N; ++jj) {
+            vs = (lane == jj) ? as[0][jj] : vs;
+            vy = (lane == jj) ? ay[0][jj] : vy;
+            vc = (lane == jj) ? ac[0][jj] : vc;
+        }
+        const float cs = a.ss_w * s_scale[lane], cy = a.sy_w * s_scale[8 + lane], cc = a.sc_w * s_scale[16 + lane];
+        const float u1 = (float)vs * cs, u2 = (float)vy * cy, u3 = (float)vc * cc;
+        float p = u1 + u2;
+        p = p + u3;
+        if (a.b_t) p = p + bt;
+        a.t_out[(size_t)lane * a.R + unit] = tanh_rn(p);
+        if (a.ts.acc) a.ts.acc[(size_t)lane * a.R + unit] = vs;
+        if (a.ty.acc) a.ty.acc[(size_t)lane * a.R + unit] = vy;
+        if (a.tc.acc) a.tc.acc[(size_t)lane * a.R + unit] = vc;
+    }
+}
+
+// =================================================================== host launchers ==
+
+q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, int A, int C, const float *a,
+                        const float *v, int n, float *e, float *alpha, float *cvec)
+{
+    AttArgs t;
+    t.P = P; t.enc_h = enc_h; t.a = a; t.v = v; t.e = e; t.alpha = alpha; t.ctx = cvec;
+    t.counters = (unsigned *)ctx->ws;
+    t.l = l; t.A = A; t.C = C;
+    hipLaunchKernelGGL(attention_kernel, dim3(l, n), dim3(256), 0, ctx->stream, t);
+    return q8i_launch_check(ctx, "attention");
+}
+
+template <int N>
+static void launch_readout_n(q8_ctx *ctx, const ReadoutArgs &a, int blocks, size_t smem, int ch)
+{
+    if (ch == 1) hipLaunchKernelGGL((readout_fast_kernel<N, 1>), dim3(blocks), dim3(256), smem, ctx->stream, a);
+    else if (ch == 2) hipLaunchKernelGGL((readout_fast_kernel<N, 2>), dim3(blocks), dim3(256), smem, ctx->stream, a);
+    else hipLaunchKernelGGL(readout_kernel<N>, dim3(blocks), dim3(256), smem, ctx->stream, a);
+}
+
+q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,
+                      float *t_out, const q8_taps *taps3)
+{
+    ReadoutArgs a;
+    a.Ws = ro->W_s.data; a.Wy = ro->W_y.data; a.Wc = ro->W_c.data; a.b_t = ro->b_t;
+    a.s = s; a.y = y; a.c = c; a.t_out = t_out;
+    q8_taps none = {nullptr, nullptr, nullptr};
+    a.ts = taps3 ? taps3[0] : none; a.ty = taps3 ? taps3[1] : none; a.tc = taps3 ? taps3[2] : none;
+    a.R = ro->W_s.rows; a.H = ro->W_s.cols; a.E = ro->W_y.cols; a.C = ro->W_c.cols;
+    a.lds = ro->W_s.ld; a.ldy = ro->W_y.ld; a.ldc = ro->W_c.ld;
+    int ldmin = a.lds < a.ldy ? a.lds : a.ldy, ldmax = a.lds > a.ldy ? a.lds : a.ldy;
+    if (a.ldc < ldmin) ldmin = a.ldc;
+    if (a.ldc > ldmax) ldmax = a.ldc;
+    a.lpr = q8_lanes_per_row(ldmin);
+    a.ss_w = ro->W_s.scale; a.sy_w = ro->W_y.scale; a.sc_w = ro->W_c.scale;
+    int ch = q8_fast_ch(ldmax);                 // dims % 4 == 0 is checked by the caller
+    if (ch == 4) ch = 0;
+    const int upb = ch ? 4 : 4 * (64 / a.lpr);
+    const int blocks = (a.R + upb - 1) / upb;
+    const size_t smem = (size_t)n * (a.lds + a.ldy + a.ldc);
+    switch (n) {
+    case 1: launch_readout_n<1>(ctx, a, blocks, smem, ch); break;
+    case 2: launch_readout_n<2>(ctx, a, blocks, smem, ch); break;
+    case 3: launch_readout_n<3>(ctx, a, blocks, smem, ch); break;
+    case 4: launch_readout_n<4>(ctx, a, blocks, smem, ch); break;
+    case 5: launch_readout_n<5>(ctx, a, blocks, smem, ch); break;
+    case 6: launch_readout_n<6>(ctx, a, blocks, smem, ch); break;
+    case 7: launch_readout_n<7>(ctx, a, blocks, smem, ch); break;
+    default: launch_readout_n<8>(ctx, a, blocks, smem, ch); break;
+    }
+    return q8i_launch_check(ctx, "readout");
+}

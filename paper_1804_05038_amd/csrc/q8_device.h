@@ -58,14 +58,32 @@ __device__ __forceinline__ double wave_sum_d(double v)
     return v;
 }
 
+template <int CTRL>
+__device__ __forceinline__ unsigned long long dpp_max_u64(unsigned long long v)
+{
+    const unsigned lo = dpp_mov_i<CTRL>((int)(unsigned)v), hi = dpp_mov_i<CTRL>((int)(unsigned)(v >> 32));
+    const unsigned long long o = ((unsigned long long)hi << 32) | lo;
+    return o > v ? o : v;
+}
+
+// Maximum of a 64-bit key over the wave, result in every lane.
 __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
 {
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) {
-        unsigned long long o = __shfl_xor(v, s, 64);
+    v = dpp_max_u64<DPP_XOR1>(v);
+    v = dpp_max_u64<DPP_XOR2>(v);
+    v = dpp_max_u64<DPP_HALF_MIRROR>(v);
+    v = dpp_max_u64<DPP_MIRROR>(v);
+    {
+        const unsigned lo = __builtin_amdgcn_ds_swizzle((int)(unsigned)v, SWZ_XOR16);
+        const unsigned hi = __builtin_amdgcn_ds_swizzle((int)(unsigned)(v >> 32), SWZ_XOR16);
+        const unsigned long long o = ((unsigned long long)hi << 32) | lo;
         v = o > v ? o : v;
     }
-    return v;
+    const unsigned long long a = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), 0) << 32) |
+                                 (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, 0);
+    const unsigned long long b = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(v >> 32), 32) << 32) |
+                                 (unsigned)__builtin_amdgcn_readlane((int)(unsigned)v, 32);
+    return a > b ? a : b;
 }
 
 // Order-preserving key: larger value first, then lower index.  -0.0 is folded into +0.0
@@ -224,6 +242,111 @@ __device__ __forceinline__ void wave_dot(const int8_t *const (&wrow)[U], int ld,
 #pragma unroll
         for (int j = 0; j < N; ++j) acc[u][j] = group_sum_i(acc[u][j], lpr);
 }
+
+// ------------------------------------------------ fast path: everything in registers ----
+//
+// For the latency-bound products of a decoder step the order of issue decides the time:
+// the fp32 activations are requested first (short, L2-resident), then every weight byte
+// the wave will need, and only then does the block wait, reduce max|x| and write the int8
+// codes to LDS -- the weight loads stay in flight behind that work.  Requires 256-thread
+// blocks, K % 4 == 0, ld <= 1024 * CH.
+
+template <int N, int CH>
+struct XRegs {
+    float4 v[N][CH];
+};
+
+template <int N, int CH>
+__device__ __forceinline__ void x_load(XRegs<N, CH> &R, const float *__restrict__ X, int n, int K, int ldx)
+{
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+#pragma unroll
+        for (int t = 0; t < CH; ++t) {
+            const int k = (t * 256 + (int)threadIdx.x) * 4;
+            R.v[j][t] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (j < n && k < K) R.v[j][t] = *(const float4 *)(X + (size_t)j * ldx + k);
+        }
+}
+
+// Turns the staged vectors into int8 codes in LDS (xq[j * ld + k], bytes [K, ld) zero) and
+// scales in s_scale[j].  s_red: N * 4 floats.  Ends with a block barrier.
+template <int N, int CH>
+__device__ __forceinline__ void x_finish(const XRegs<N, CH> &R, int n, int ld, int8_t *xq, float *s_scale, float *s_red)
+{
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        float m = 0.0f;
+#pragma unroll
+        for (int t = 0; t < CH; ++t) {
+            const float4 v = R.v[j][t];
+            m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+        }
+        m = wave_max_f(m);
+        if (lane == 0) s_red[j * 4 + wave] = m;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        if (j < n) {
+            const float mm = fmaxf(fmaxf(s_red[j * 4], s_red[j * 4 + 1]), fmaxf(s_red[j * 4 + 2], s_red[j * 4 + 3]));
+            float scale, inv;
+            q8_scale_of(mm, scale, inv);
+            if (tid == 0) s_scale[j] = scale;
+#pragma unroll
+            for (int t = 0; t < CH; ++t) {
+                const int k = (t * 256 + tid) * 4;
+                const float4 v = R.v[j][t];      // zero beyond K, so pad bytes come out zero
+                if (k < ld) *(int *)(xq + (size_t)j * ld + k) = q8_pack4(v.x, v.y, v.z, v.w, inv);
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// Requests U weight rows for this wave: lane covers bytes [(c * 64 + lane) * 16, +16) of a row.
+template <int U, int CH>
+__device__ __forceinline__ void rows_load(v4i (&w)[U][CH], const int8_t *const (&wrow)[U], int ld, int lane)
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int off = (c * 64 + lane) * 16;
+            w[u][c] = (v4i){0, 0, 0, 0};
+            if (wrow[u] != nullptr && off < ld) w[u][c] = *(const v4i *)(wrow[u] + off);
+        }
+}
+
+// Dots the staged rows with the N quantized vectors in LDS; every lane gets every sum.
+template <int N, int U, int CH>
+__device__ __forceinline__ void rows_dot(const v4i (&w)[U][CH], int ld, int lane, const int8_t *xq, int (&acc)[U][N])
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int j = 0; j < N; ++j) acc[u][j] = 0;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int off = (c * 64 + lane) * 16;
+        if (off < ld) {
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                const v4i x = *(const v4i *)(xq + (size_t)j * ld + off);
+#pragma unroll
+                for (int u = 0; u < U; ++u) acc[u][j] = dot16(w[u][c], x, acc[u][j]);
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int j = 0; j < N; ++j) acc[u][j] = group_sum_i(acc[u][j], 64);
+}
+
+// Chunks per lane of the fast path for a row of ld bytes (0 = not covered).
+static inline int q8_fast_ch(int ld) { return ld <= 1024 ? 1 : (ld <= 2048 ? 2 : (ld <= 4096 ? 4 : 0)); }
 
 // Group width for rows of `ld` bytes: the smallest of 16, 32, 64 lanes whose single
 // 16-byte-per-lane pass covers the row, 64 for longer rows.

@@ -1,0 +1,284 @@
+// q8_gru.hip -- the GRU cell that Eq. 1 (encoder) and Eq. 3-4 (decoder r and q) of "Pieces
+// of Eight: 8-bit Neural Machine Translation" apply, with Section 3's 8-bit products:
+// one launch computes both products of a cell for the block's hidden units and fuses
+// dequantization, bias, sigmoid / tanh and the state mix.
+#include "q8_internal.h"
+
+#define GRU_FULL 0     // both products computed here
+#define GRU_GX_PRE 1   // gx = Wx q(x) + bx supplied in g_pre (encoder: all positions at once)
+#define GRU_GH_PRE 2   // gh = Wh q(h) + bh supplied in g_pre (decoder GRU q: depends on s' only)
+
+struct GruJob {
+    const int8_t *Wx, *Wh;
+    const float *bx, *bh;
+    const float *x, *h_prev, *g_pre;
+    float *h_out;
+    q8_taps tx, th;
+    int I, ldwx, H, ldwh, ldx, ldh, ldo, ldg, lpr;
+    float sx_w, sh_w;
+};
+struct GruJobs {
+    GruJob j[2];
+};
+
+template <int N, int MODE>
+__device__ __forceinline__ void gru_x_taps(const GruJob &J, const int8_t *xq, const int8_t *hq, const float *s_scale)
+{
+    if (MODE != GRU_GX_PRE) {
+        if (J.tx.xq)
+            for (int e = threadIdx.x; e < N * J.I; e += blockDim.x) J.tx.xq[e] = xq[(e / J.I) * J.ldwx + e % J.I];
+        if (J.tx.xscale && threadIdx.x < N) J.tx.xscale[threadIdx.x] = s_scale[threadIdx.x];
+    }
+    if (MODE != GRU_GH_PRE) {
+        if (J.th.xq)
+            for (int e = threadIdx.x; e < N * J.H; e += blockDim.x) J.th.xq[e] = hq[(e / J.H) * J.ldwh + e % J.H];
+        if (J.th.xscale && threadIdx.x < N) J.th.xscale[threadIdx.x] = s_scale[8 + threadIdx.x];
+    }
+}
+
+// Gates of one hidden unit from its six pre-activations (fp32, one operation per
+// statement, transcendental functions in double rounded once).
+__device__ __forceinline__ float gru_gates(const float (&gx)[3], const float (&gh)[3], float h_prev)
+{
+    const float pr = gx[0] + gh[0];
+    const float r = sigmoid_rn(pr);
+    const float pz = gx[1] + gh[1];
+    const float z = sigmoid_rn(pz);
+    const float rn = r * gh[2];
+    const float pn = gx[2] + rn;
+    const float nn = tanh_rn(pn);
+    const float omz = 1.0f - z;
+    const float t1 = omz * nn;
+    const float t2 = z * h_prev;
+    return t1 + t2;
+}
+
+// General shapes.
+template <int N, int MODE>
+__global__ __launch_bounds__(256) void gru_kernel(GruJobs jobs)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    __shared__ float s_scale[16];
+    __shared__ float s_red[8 * 4];
+    const GruJob &J = jobs.j[blockIdx.y];
+    const int H = J.H;
+    int8_t *xq = smem;
+    int8_t *hq = smem + (MODE == GRU_GX_PRE ? 0 : N * J.ldwx);
+    if (MODE != GRU_GX_PRE) block_quantize<N>(J.x, N, J.I, J.ldx, J.ldwx, xq, s_scale, s_red);
+    if (MODE != GRU_GH_PRE) block_quantize<N>(J.h_prev, N, H, J.ldh, J.ldwh, hq, s_scale + 8, s_red);
+    if (blockIdx.x == 0) gru_x_taps<N, MODE>(J, xq, hq, s_scale);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lpr = J.lpr, lir = lane & (lpr - 1), sg = lane / lpr, upw = 64 / lpr;
+    float cx = 0.0f, ch = 0.0f;
+    if (lir < N) {
+        if (MODE != GRU_GX_PRE) cx = J.sx_w * s_scale[lir];
+        if (MODE != GRU_GH_PRE) ch = J.sh_w * s_scale[8 + lir];
+    }
+
+    for (int u0 = (blockIdx.x * 4 + wave) * upw; u0 < H; u0 += gridDim.x * 4 * upw) {
+        const int unit = u0 + sg;
+        const bool ok = unit < H;
+        int ax[3][N], ah[3][N];
+        if (MODE != GRU_GX_PRE) {
+            const int8_t *wrow[3];
+#pragma unroll
+            for (int gt = 0; gt < 3; ++gt) wrow[gt] = ok ? J.Wx + (size_t)(gt * H + unit) * J.ldwx : nullptr;
+            wave_dot<N, 3>(wrow, J.ldwx, lpr, lir, xq, ax);
+        }
+        if (MODE != GRU_GH_PRE) {
+            const int8_t *wrow[3];
+#pragma unroll
+            for (int gt = 0; gt < 3; ++gt) wrow[gt] = ok ? J.Wh + (size_t)(gt * H + unit) * J.ldwh : nullptr;
+            wave_dot<N, 3>(wrow, J.ldwh, lpr, lir, hq, ah);
+        }
+        if (ok && lir < N) {
+            const int j = lir;
+            float gx[3], gh[3];
+#pragma unroll
+            for (int gt = 0; gt < 3; ++gt) {
+                const int row = gt * H + unit;
+                if (MODE == GRU_GX_PRE) {
+                    gx[gt] = J.g_pre[(size_t)j * J.ldg + row];
+                } else {
+                    int a = 0;
+#pragma unroll
+                    for (int jj = 0; jj < N; ++jj) a = (j == jj) ? ax[gt][jj] : a;
+                    float y = (float)a * cx;
+                    if (J.bx) y = y + J.bx[row];
+                    gx[gt] = y;
+                    if (J.tx.acc) J.tx.acc[(size_t)j * 3 * H + row] = a;
+                }
+                if (MODE == GRU_GH_PRE) {
+                    gh[gt] = J.g_pre[(size_t)j * J.ldg + row];
+                } else {
+                    int a = 0;
+#pragma unroll
+                    for (int jj = 0; jj < N; ++jj) a = (j == jj) ? ah[gt][jj] : a;
+                    float y = (float)a * ch;
+                    if (J.bh) y = y + J.bh[row];
+                    gh[gt] = y;
+                    if (J.th.acc) J.th.acc[(size_t)j * 3 * H + row] = a;
+                }
+            }
+            J.h_out[(size_t)j * J.ldo + unit] = gru_gates(gx, gh, J.h_prev[(size_t)j * J.ldh + unit]);
+        }
+    }
+}
+
+// Rows of at most 1024 * CH bytes, I % 4 == 0, H % 4 == 0, one hidden unit per wave
+// (grid.x * 4 >= H).  Activations, the unit's six (or three) weight rows and the
+// epilogue's operands are all requested before the block first waits.
+template <int N, int MODE, int CH>
+__global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    __shared__ float s_scale[16];
+    __shared__ float s_red[8 * 4];
+    const GruJob &J = jobs.j[blockIdx.y];
+    const int H = J.H;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int unit = blockIdx.x * 4 + wave;
+    const bool ok = unit < H;
+    int8_t *xq = smem;
+    int8_t *hq = smem + (MODE == GRU_GX_PRE ? 0 : N * J.ldwx);
+
+    XRegs<N, CH> xr, hr;
+    if (MODE != GRU_GX_PRE) x_load<N, CH>(xr, J.x, N, J.I, J.ldx);
+    if (MODE != GRU_GH_PRE) x_load<N, CH>(hr, J.h_prev, N, H, J.ldh);
+    v4i wx[3][CH], wh[3][CH];
+    if (MODE != GRU_GX_PRE) {
+        const int8_t *wrow[3];
+#pragma unroll
+        for (int gt = 0; gt < 3; ++gt) wrow[gt] = ok ? J.Wx + (size_t)(gt * H + unit) * J.ldwx : nullptr;
+        rows_load<3, CH>(wx, wrow, J.ldwx, lane);
+    }
+    if (MODE != GRU_GH_PRE) {
+        const int8_t *wrow[3];
+#pragma unroll
+        for (int gt = 0; gt < 3; ++gt) wrow[gt] = ok ? J.Wh + (size_t)(gt * H + unit) * J.ldwh : nullptr;
+        rows_load<3, CH>(wh, wrow, J.ldwh, lane);
+    }
+    // epilogue operands of lane j < N: biases, supplied pre-activations, previous state
+    float pre[3] = {0.f, 0.f, 0.f}, bxv[3] = {0.f, 0.f, 0.f}, bhv[3] = {0.f, 0.f, 0.f}, hp = 0.f;
+    if (ok && lane < N) {
+#pragma unroll
+        for (int gt = 0; gt < 3; ++gt) {
+            const int row = gt * H + unit;
+            if (MODE != GRU_FULL) pre[gt] = J.g_pre[(size_t)lane * J.ldg + row];
+            if (MODE != GRU_GX_PRE && J.bx) bxv[gt] = J.bx[row];
+            if (MODE != GRU_GH_PRE && J.bh) bhv[gt] = J.bh[row];
+        }
+        hp = J.h_prev[(size_t)lane * J.ldh + unit];
+    }
+
+    if (MODE != GRU_GX_PRE) x_finish<N, CH>(xr, N, J.ldwx, xq, s_scale, s_red);
+    if (MODE != GRU_GH_PRE) x_finish<N, CH>(hr, N, J.ldwh, hq, s_scale + 8, s_red);
+    if (blockIdx.x == 0) gru_x_taps<N, MODE>(J, xq, hq, s_scale);
+
+    int ax[3][N], ah[3][N];
+    if (MODE != GRU_GX_PRE) rows_dot<N, 3, CH>(wx, J.ldwx, lane, xq, ax);
+    if (MODE != GRU_GH_PRE) rows_dot<N, 3, CH>(wh, J.ldwh, lane, hq, ah);
+    if (ok && lane < N) {
+        const int j = lane;
+        float cx = 0.f, ch = 0.f;
+        if (MODE != GRU_GX_PRE) cx = J.sx_w * s_scale[j];
+        if (MODE != GRU_GH_PRE) ch = J.sh_w * s_scale[8 + j];
+        float gx[3], gh[3];
+#pragma unroll
+        for (int gt = 0; gt < 3; ++gt) {
+            const int row = gt * H + unit;
+            if (MODE == GRU_GX_PRE) {
+                gx[gt] = pre[gt];
+            } else {
+                int a = 0;
+#pragma unroll
+                for (int jj = 0; jj < N; ++jj) a = (j == jj) ? ax[gt][jj] : a;
+                float y = (float)a * cx;
+                if (J.bx) y = y + bxv[gt];
+                gx[gt] = y;
+                if (J.tx.acc) J.tx.acc[(size_t)j * 3 * H + row] = a;
+            }
+            if (MODE == GRU_GH_PRE) {
+                gh[gt] = pre[gt];
+            } else {
+                int a = 0;
+#pragma unroll
+                for (int jj = 0; jj < N; ++jj) a = (j == jj) ? ah[gt][jj] : a;
+                float y = (float)a * ch;
+                if (J.bh) y = y + bhv[gt];
+                gh[gt] = y;
+                if (J.th.acc) J.th.acc[(size_t)j * 3 * H + row] = a;
+            }
+        }
+        J.h_out[(size_t)j * J.ldo + unit] = gru_gates(gx, gh, hp);
+    }
+}
+
+// =================================================================== host launcher ==
+
+template <int N, int MODE>
+static void launch_gru_nm(q8_ctx *ctx, const GruJobs &jobs, int njobs, int blocks, size_t smem, int ch)
+{
+    dim3 grid(blocks, njobs);
+    if (ch == 1) hipLaunchKernelGGL((gru_fast_kernel<N, MODE, 1>), grid, dim3(256), smem, ctx->stream, jobs);
+    else if (ch == 2) hipLaunchKernelGGL((gru_fast_kernel<N, MODE, 2>), grid, dim3(256), smem, ctx->stream, jobs);
+    else hipLaunchKernelGGL((gru_kernel<N, MODE>), grid, dim3(256), smem, ctx->stream, jobs);
+}
+
+template <int N>
+static void launch_gru_n(q8_ctx *ctx, const GruJobs &jobs, int njobs, int mode, int blocks, size_t smem, int ch)
+{
+    if (mode == GRU_FULL) launch_gru_nm<N, GRU_FULL>(ctx, jobs, njobs, blocks, smem, ch);
+    else if (mode == GRU_GX_PRE) launch_gru_nm<N, GRU_GX_PRE>(ctx, jobs, njobs, blocks, smem, ch);
+    else launch_gru_nm<N, GRU_GH_PRE>(ctx, jobs, njobs, blocks, smem, ch);
+}
+
+q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode)
+{
+    GruJobs jobs;
+    size_t smem = 0;
+    int max_ld = 0, maxH = 0;
+    bool fast = true;
+    for (int t = 0; t < njobs; ++t) {
+        GruJob &J = jobs.j[t];
+        const q8_gru_weights *g = d[t].g;
+        J.Wx = g->Wx.data; J.Wh = g->Wh.data; J.bx = g->bx; J.bh = g->bh;
+        J.x = d[t].x; J.h_prev = d[t].h_prev; J.g_pre = d[t].g_pre; J.h_out = d[t].h_out;
+        q8_taps none = {nullptr, nullptr, nullptr};
+        J.tx = d[t].taps ? d[t].taps[0] : none;
+        J.th = d[t].taps ? d[t].taps[1] : none;
+        J.I = g->Wx.cols; J.ldwx = g->Wx.ld; J.H = g->Wh.cols; J.ldwh = g->Wh.ld;
+        J.ldx = d[t].ldx; J.ldh = d[t].ldh; J.ldo = d[t].ldo; J.ldg = d[t].ldg;
+        J.sx_w = g->Wx.scale; J.sh_w = g->Wh.scale;
+        const int lx = mode == GRU_GX_PRE ? 0 : J.ldwx, lh = mode == GRU_GH_PRE ? 0 : J.ldwh;
+        if (lx > max_ld) max_ld = lx;
+        if (lh > max_ld) max_ld = lh;
+        if (J.H > maxH) maxH = J.H;
+        if ((mode != GRU_GX_PRE && J.I % 4) || J.H % 4) fast = false;
+        int ldmin = mode == GRU_GX_PRE ? J.ldwh : (mode == GRU_GH_PRE ? J.ldwx : (J.ldwx < J.ldwh ? J.ldwx : J.ldwh));
+        J.lpr = q8_lanes_per_row(ldmin);
+        const size_t s = (size_t)n * (lx + lh);
+        if (s > smem) smem = s;
+    }
+    int ch = fast ? q8_fast_ch(max_ld) : 0;
+    if (ch == 4) ch = 0;                           // rows beyond 2048 bytes take the general kernel
+    int blocks = 0;
+    for (int t = 0; t < njobs; ++t) {
+        const GruJob &J = jobs.j[t];
+        const int upb = ch ? 4 : 4 * (64 / J.lpr);
+        const int b = (J.H + upb - 1) / upb;
+        if (b > blocks) blocks = b;
+    }
+    switch (n) {
+    case 1: launch_gru_n<1>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
+    case 2: launch_gru_n<2>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
+    case 3: launch_gru_n<3>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
+    case 4: launch_gru_n<4>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
+    case 5: launch_gru_n<5>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
+    case 6: launch_gru_n<6>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
+    case 7: launch_gru_n<7>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
+    default: launch_gru_n<8>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
+    }
+    return q8i_launch_check(ctx, "gru");
+}

@@ -1,0 +1,390 @@
+// q8_products.hip -- Section 3 of "Pieces of Eight: 8-bit Neural Machine Translation" as
+// gfx950 kernels: weight quantization, the streaming int8 matrix x vector / narrow-matrix
+// product (16-byte loads, 4-way int8 dots, DPP reductions), and the narrow product on the
+// int8 matrix cores for more than 8 vectors.
+#include "q8_internal.h"
+
+// =============================================================== weight quantization ==
+
+// max |W| over a [rows x cols] matrix into *out_bits (bit pattern of a non-negative
+// float, combined with an unsigned atomic max; *out_bits must start at 0).
+__global__ __launch_bounds__(256) void absmax_kernel(const float *__restrict__ W, int rows, int cols, int ld,
+                                                     unsigned *out_bits)
+{
+    __shared__ float s_red[4];
+    float m = 0.0f;
+    const size_t total = (size_t)rows * cols;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+        const size_t r = e / cols, c = e - r * cols;
+        m = fmaxf(m, fabsf(W[r * ld + c]));
+    }
+    m = wave_max_f(m);
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        m = fmaxf(fmaxf(s_red[0], s_red[1]), fmaxf(s_red[2], s_red[3]));
+        atomicMax(out_bits, __float_as_uint(m));
+    }
+}
+
+__global__ __launch_bounds__(256) void quantize_matrix_kernel(const float *__restrict__ W, int rows, int cols, int ld_in,
+                                                              int8_t *__restrict__ Wq, int ld_out,
+                                                              const unsigned *max_bits, float *scale_out)
+{
+    float scale, inv;
+    q8_scale_of(__uint_as_float(*max_bits), scale, inv);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *scale_out = scale;
+    const int groups = ld_out / 4;
+    const size_t total = (size_t)rows * groups;
+    for (size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (size_t)gridDim.x * blockDim.x) {
+        const size_t r = e / groups;
+        const int k = (int)(e - r * groups) * 4;
+        const float *w = W + r * ld_in;
+        float a = k < cols ? w[k] : 0.0f, b = k + 1 < cols ? w[k + 1] : 0.0f;
+        float c = k + 2 < cols ? w[k + 2] : 0.0f, d = k + 3 < cols ? w[k + 3] : 0.0f;
+        *(int *)(Wq + r * ld_out + k) = q8_pack4(a, b, c, d, inv);
+    }
+}
+
+__global__ void fill_u32_kernel(unsigned *p, int n, unsigned v)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// ====================================================== streaming matrix x vector(s) ==
+
+struct GemvJob {
+    const int8_t *W;
+    const float *X;
+    const float *bias;
+    float *Y;
+    int8_t *tap_xq;
+    float *tap_xscale;
+    int32_t *tap_acc;
+    int rows, cols, ld, ldx, ldy, lpr, block0, rpb;
+    float w_scale;
+};
+#define Q8_MAX_JOBS 3
+struct GemvJobs {
+    GemvJob j[Q8_MAX_JOBS];
+    int njobs;
+};
+
+__device__ __forceinline__ int pick_job(const GemvJobs &jobs)
+{
+    int ji = 0;
+    for (int t = 1; t < jobs.njobs; ++t)
+        if ((int)blockIdx.x >= jobs.j[t].block0) ji = t;
+    return ji;
+}
+
+template <int N>
+__device__ __forceinline__ void write_x_taps(const GemvJob &J, const int8_t *xq, const float *s_scale)
+{
+    if (J.tap_xq)
+        for (int e = threadIdx.x; e < N * J.cols; e += blockDim.x) {
+            const int j = e / J.cols, k = e - j * J.cols;
+            J.tap_xq[e] = xq[j * J.ld + k];
+        }
+    if (J.tap_xscale && threadIdx.x < N) J.tap_xscale[threadIdx.x] = s_scale[threadIdx.x];
+}
+
+// General shapes.  Up to Q8_MAX_JOBS independent products in one launch, each with
+// N <= 8 vectors.  A block belongs to one job, quantizes that job's vectors into LDS
+// and streams its slice of rows.
+template <int N>
+__global__ __launch_bounds__(256) void gemv_jobs_kernel(GemvJobs jobs)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    __shared__ float s_scale[8];
+    __shared__ float s_red[8 * 4];
+    const GemvJob &J = jobs.j[pick_job(jobs)];
+    const int blk = blockIdx.x - J.block0;
+    const int ld = J.ld;
+
+    block_quantize<N>(J.X, N, J.cols, J.ldx, ld, smem, s_scale, s_red);
+    if (blk == 0) write_x_taps<N>(J, smem, s_scale);
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lpr = J.lpr, lir = lane & (lpr - 1), sg = lane / lpr, rpp = 64 / lpr;
+    constexpr int U = 4;
+    const int r_begin = blk * J.rpb;
+    const int r_end = min(J.rows, r_begin + J.rpb);
+    float cj = 0.0f;                          // lane lir < N owns vector lir in the epilogue
+    if (lir < N) cj = J.w_scale * s_scale[lir];
+
+    for (int r = r_begin + wave * rpp * U; r < r_end; r += 4 * rpp * U) {
+        const int8_t *wrow[U];
+        int row[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            row[u] = r + u * rpp + sg;
+            wrow[u] = row[u] < r_end ? J.W + (size_t)row[u] * ld : nullptr;
+        }
+        int acc[U][N];
+        wave_dot<N, U>(wrow, ld, lpr, lir, smem, acc);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int a = 0;
+#pragma unroll
+            for (int j = 0; j < N; ++j) a = (lir == j) ? acc[u][j] : a;
+            if (lir < N && row[u] < r_end) {
+                float y = (float)a * cj;
+                if (J.bias) y = y + J.bias[row[u]];
+                J.Y[(size_t)lir * J.ldy + row[u]] = y;
+                if (J.tap_acc) J.tap_acc[(size_t)lir * J.rows + row[u]] = a;
+            }
+        }
+    }
+}
+
+// Rows of at most 1024 * CH bytes and cols % 4 == 0: activations and the first two rows of
+// every wave are requested before anything is waited for; the row loop is double-buffered.
+template <int N, int CH>
+__global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    __shared__ float s_scale[8];
+    __shared__ float s_red[8 * 4];
+    const GemvJob &J = jobs.j[pick_job(jobs)];
+    const int blk = blockIdx.x - J.block0;
+    const int ld = J.ld;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr int U = 2;
+    const int r_begin = blk * J.rpb;
+    const int r_end = min(J.rows, r_begin + J.rpb);
+
+    XRegs<N, CH> xr;
+    x_load<N, CH>(xr, J.X, N, J.cols, J.ldx);
+    int r = r_begin + wave * U;
+    v4i w[U][CH];
+    {
+        const int8_t *wrow[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) wrow[u] = r + u < r_end ? J.W + (size_t)(r + u) * ld : nullptr;
+        rows_load<U, CH>(w, wrow, ld, lane);
+    }
+    x_finish<N, CH>(xr, N, ld, smem, s_scale, s_red);
+    if (blk == 0) write_x_taps<N>(J, smem, s_scale);
+    float cj = 0.0f;
+    if (lane < N) cj = J.w_scale * s_scale[lane];
+
+    while (r < r_end) {
+        const int rn = r + 4 * U;
+        v4i wn[U][CH];
+        {
+            const int8_t *wrow[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) wrow[u] = rn + u < r_end ? J.W + (size_t)(rn + u) * ld : nullptr;
+            rows_load<U, CH>(wn, wrow, ld, lane);
+        }
+        int acc[U][N];
+        rows_dot<N, U, CH>(w, ld, lane, smem, acc);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int a = 0;
+#pragma unroll
+            for (int j = 0; j < N; ++j) a = (lane == j) ? acc[u][j] : a;
+            if (lane < N && r + u < r_end) {
+                float y = (float)a * cj;
+                if (J.bias) y = y + J.bias[r + u];
+                J.Y[(size_t)lane * J.ldy + r + u] = y;
+                if (J.tap_acc) J.tap_acc[(size_t)lane * J.rows + r + u] = a;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int c = 0; c < CH; ++c) w[u][c] = wn[u][c];
+        r = rn;
+    }
+}
+
+// ================================================ narrow product on the matrix cores ==
+
+// One block per vector: quantize X[j] into global xq[j * ld ..] (pad zeroed), scale[j].
+__global__ __launch_bounds__(256) void quantize_rows_kernel(const float *__restrict__ X, int K, int ldx, int ld,
+                                                            int8_t *xq, float *xscale, int8_t *tap_xq)
+{
+    __shared__ float s_scale[1];
+    __shared__ float s_red[4];
+    const int j = blockIdx.x;
+    block_quantize<1>(X + (size_t)j * ldx, 1, K, ldx, ld, xq + (size_t)j * ld, s_scale, s_red);
+    if (threadIdx.x == 0) xscale[j] = s_scale[0];
+    if (tap_xq) {
+        __threadfence_block();
+        for (int k = threadIdx.x; k < K; k += blockDim.x) tap_xq[(size_t)j * K + k] = xq[(size_t)j * ld + k];
+    }
+}
+
+struct MfmaArgs {
+    const int8_t *W;
+    const int8_t *xq;      // [n x ld] int8, global
+    const float *xscale;   // [n]
+    const float *bias;
+    float *Y;
+    int32_t *tap_acc;
+    int rows, ld, n, ldy;
+    float w_scale;
+};
+
+// Y[j, row] for 16-row x 16-vector tiles on v_mfma_i32_16x16x64_i8.  Operand A = 16
+// weight rows x 64 k (lane: row lane%16, 16 consecutive k at 16*(lane/16)); operand B =
+// 64 k x 16 vectors with the same k split, so any internal k order cancels.  Result:
+// lane holds rows 4*(lane/16)+r, r = 0..3, of vector lane%16.
+template <int NT>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaArgs a)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int r0 = (blockIdx.x * 4 + wave) * 16;
+    if (r0 >= a.rows) return;
+    const int ld = a.ld;
+    const bool row_ok = r0 + i < a.rows;
+    const int8_t *wp = a.W + (size_t)(r0 + i) * ld + 16 * g;
+    for (int ct = 0; ct * 16 < a.n; ct += NT) {
+        v4i acc[NT];
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[t] = (v4i){0, 0, 0, 0};
+        for (int k0 = 0; k0 < ld; k0 += 64) {
+            const bool k_ok = k0 + 16 * g < ld;
+            v4i av = (v4i){0, 0, 0, 0};
+            if (row_ok && k_ok) av = *(const v4i *)(wp + k0);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int col = (ct + t) * 16 + i;
+                v4i bv = (v4i){0, 0, 0, 0};
+                if (col < a.n && k_ok) bv = *(const v4i *)(a.xq + (size_t)col * ld + k0 + 16 * g);
+                acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bv, acc[t], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int col = (ct + t) * 16 + i;
+            if (col >= a.n) continue;
+            const float c = a.w_scale * a.xscale[col];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = r0 + 4 * g + r;
+                if (row < a.rows) {
+                    float y = (float)acc[t][r] * c;
+                    if (a.bias) y = y + a.bias[row];
+                    a.Y[(size_t)col * a.ldy + row] = y;
+                    if (a.tap_acc) a.tap_acc[(size_t)col * a.rows + row] = acc[t][r];
+                }
+            }
+        }
+    }
+}
+
+// =================================================================== host launchers ==
+
+q8_status q8i_launch_check(q8_ctx *ctx, const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+    return Q8_OK;
+}
+
+q8_status q8i_quantize_matrix(q8_ctx *ctx, const float *W, int rows, int cols, int ld_in, int8_t *Wq, int ld_out,
+                              float *scale_host)
+{
+    unsigned *slot = (unsigned *)(ctx->ws + Q8_WS_SCRATCH_SLOT);
+    float *scale_dev = (float *)(slot + 1);
+    const size_t total = (size_t)rows * cols;
+    int blocks = (int)((total + 255) / 256);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(absmax_kernel, dim3(blocks), dim3(256), 0, ctx->stream, W, rows, cols, ld_in, slot);
+    hipLaunchKernelGGL(quantize_matrix_kernel, dim3(blocks), dim3(256), 0, ctx->stream, W, rows, cols, ld_in, Wq,
+                       ld_out, slot, scale_dev);
+    q8_status st = q8i_launch_check(ctx, "q8_quantize_matrix");
+    if (st) return st;
+    hipError_t e = hipMemcpyAsync(scale_host, scale_dev, sizeof(float), hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, ctx->stream, slot, 2, 0u);
+        e = hipStreamSynchronize(ctx->stream);
+    }
+    if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "q8_quantize_matrix: %s", hipGetErrorString(e));
+    return Q8_OK;
+}
+
+q8_status q8i_fill_u32(q8_ctx *ctx, void *p, int n, unsigned v)
+{
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, (unsigned *)p, n, v);
+    return q8i_launch_check(ctx, "fill");
+}
+
+template <int N>
+static void launch_gemv_n(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t smem, int ch)
+{
+    if (ch == 1) hipLaunchKernelGGL((gemv_fast_kernel<N, 1>), dim3(blocks), dim3(256), smem, ctx->stream, jobs);
+    else if (ch == 2) hipLaunchKernelGGL((gemv_fast_kernel<N, 2>), dim3(blocks), dim3(256), smem, ctx->stream, jobs);
+    else if (ch == 4) hipLaunchKernelGGL((gemv_fast_kernel<N, 4>), dim3(blocks), dim3(256), smem, ctx->stream, jobs);
+    else hipLaunchKernelGGL(gemv_jobs_kernel<N>, dim3(blocks), dim3(256), smem, ctx->stream, jobs);
+}
+
+q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
+{
+    GemvJobs jobs;
+    jobs.njobs = njobs;
+    int max_ld = 0;
+    bool fast = true;
+    for (int t = 0; t < njobs; ++t) {
+        GemvJob &J = jobs.j[t];
+        J.W = d[t].W->data; J.X = d[t].X; J.bias = d[t].bias; J.Y = d[t].Y;
+        J.tap_xq = d[t].taps ? d[t].taps->xq : nullptr;
+        J.tap_xscale = d[t].taps ? d[t].taps->xscale : nullptr;
+        J.tap_acc = d[t].taps ? d[t].taps->acc : nullptr;
+        J.rows = d[t].W->rows; J.cols = d[t].W->cols; J.ld = d[t].W->ld;
+        J.ldx = d[t].ldx; J.ldy = d[t].ldy; J.w_scale = d[t].W->scale;
+        if (J.ld > max_ld) max_ld = J.ld;
+        if (J.cols % 4 != 0) fast = false;
+    }
+    const int ch = fast ? q8_fast_ch(max_ld) : 0;
+    int blocks = 0;
+    for (int t = 0; t < njobs; ++t) {
+        GemvJob &J = jobs.j[t];
+        J.lpr = q8_lanes_per_row(J.ld);
+        // rows covered by one block iteration; large matrices spread over at most ~2048 blocks
+        const int pass = ch ? 4 * 2 : 4 * (64 / J.lpr) * 4;
+        int rpb = (J.rows + 2047) / 2048;
+        rpb = (rpb + pass - 1) / pass * pass;
+        J.rpb = rpb;
+        J.block0 = blocks;
+        blocks += (J.rows + rpb - 1) / rpb;
+    }
+    const size_t smem = (size_t)n * max_ld;
+    switch (n) {
+    case 1: launch_gemv_n<1>(ctx, jobs, blocks, smem, ch); break;
+    case 2: launch_gemv_n<2>(ctx, jobs, blocks, smem, ch); break;
+    case 3: launch_gemv_n<3>(ctx, jobs, blocks, smem, ch); break;
+    case 4: launch_gemv_n<4>(ctx, jobs, blocks, smem, ch); break;
+    case 5: launch_gemv_n<5>(ctx, jobs, blocks, smem, ch); break;
+    case 6: launch_gemv_n<6>(ctx, jobs, blocks, smem, ch); break;
+    case 7: launch_gemv_n<7>(ctx, jobs, blocks, smem, ch); break;
+    default: launch_gemv_n<8>(ctx, jobs, blocks, smem, ch); break;
+    }
+    return q8i_launch_check(ctx, "gemv");
+}
+
+q8_status q8i_gemm_mfma(q8_ctx *ctx, const q8_mat *W, const float *X, int n, int ldx, const float *bias, float *Y,
+                        int ldy, const q8_taps *taps, int8_t *xq, float *xscale)
+{
+    hipLaunchKernelGGL(quantize_rows_kernel, dim3(n), dim3(256), 0, ctx->stream, X, W->cols, ldx, W->ld, xq, xscale,
+                       taps ? taps->xq : nullptr);
+    if (taps && taps->xscale) {
+        hipError_t e = hipMemcpyAsync(taps->xscale, xscale, sizeof(float) * n, hipMemcpyDeviceToDevice, ctx->stream);
+        if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "tap copy: %s", hipGetErrorString(e));
+    }
+    MfmaArgs a;
+    a.W = W->data; a.xq = xq; a.xscale = xscale; a.bias = bias; a.Y = Y;
+    a.tap_acc = taps ? taps->acc : nullptr;
+    a.rows = W->rows; a.ld = W->ld; a.n = n; a.ldy = ldy; a.w_scale = W->scale;
+    const int blocks = (W->rows + 63) / 64;
+    const int tiles = (n + 15) / 16;
+    if (tiles == 1) hipLaunchKernelGGL(gemm_mfma_kernel<1>, dim3(blocks), dim3(256), 0, ctx->stream, a);
+    else if (tiles == 2) hipLaunchKernelGGL(gemm_mfma_kernel<2>, dim3(blocks), dim3(256), 0, ctx->stream, a);
+    else hipLaunchKernelGGL(gemm_mfma_kernel<4>, dim3(blocks), dim3(256), 0, ctx->stream, a);
+    return q8i_launch_check(ctx, "gemm_mfma");
+}
