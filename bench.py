@@ -103,6 +103,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--quick", action="store_true", help="beam-5 timed region and kernel timing only (profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (one sentence per GPU is how the path would shard); "
@@ -143,7 +144,7 @@ def main():
     eager5 = time_loop(torch, step5, args.steps, args.warmup)
     best5, mode = eager5, "eager"
     graph_ms = None
-    if not args.no_graph:
+    if not args.no_graph and not args.quick:
         try:
             g = torch.cuda.CUDAGraph()
             side = torch.cuda.Stream()
@@ -169,7 +170,7 @@ def main():
         except Exception as e:  # graph capture is an optimisation of the launch path only
             graph_ms = "unavailable: %s" % (str(e).splitlines()[0][:120])
 
-    eager1 = time_loop(torch, step1, args.steps, args.warmup)
+    eager1 = time_loop(torch, step1, args.steps, args.warmup) if not args.quick else float("nan")
 
     # ---- dominant kernel: the vocabulary projection (25.6 MB of int8 weights per launch) ----
     q.q8_profile_begin(ctx, args.steps)
@@ -182,14 +183,19 @@ def main():
 
     # ---- per-call numbers (median of 9 repetitions, the paper's protocol) ----
     calls = {}
-    med, mn = median_of(torch, c1_1.launch); calls["cgru_step_beam1_us"] = [med * 1e6, mn * 1e6]
-    med, mn = median_of(torch, c1_5.launch); calls["cgru_step_beam5_us"] = [med * 1e6, mn * 1e6]
-    med, mn = median_of(torch, c2_1.launch); calls["output_layer_beam1_us"] = [med * 1e6, mn * 1e6]
-    med, mn = median_of(torch, c2_5.launch); calls["output_layer_beam5_us"] = [med * 1e6, mn * 1e6]
+    if args.quick:
+        args.no_cpu_baseline = True
+        median_of_ = lambda torch, fn: (float("nan"), float("nan"))
+    else:
+        median_of_ = median_of
+    med, mn = median_of_(torch, c1_1.launch); calls["cgru_step_beam1_us"] = [med * 1e6, mn * 1e6]
+    med, mn = median_of_(torch, c1_5.launch); calls["cgru_step_beam5_us"] = [med * 1e6, mn * 1e6]
+    med, mn = median_of_(torch, c2_1.launch); calls["output_layer_beam1_us"] = [med * 1e6, mn * 1e6]
+    med, mn = median_of_(torch, c2_5.launch); calls["output_layer_beam5_us"] = [med * 1e6, mn * 1e6]
     x = ctx.f32(rng.standard_normal(1024).astype(np.float32))
     Wh = m["cgru"].r.Wh
     yv = ctx.empty(Wh.rows)
-    med, mn = median_of(torch, lambda: q.q8_gemv(ctx, Wh, x, None, yv))
+    med, mn = median_of_(torch, lambda: q.q8_gemv(ctx, Wh, x, None, yv))
     calls["gemv_3072x1024_us"] = [med * 1e6, mn * 1e6]
 
     cpu = None if args.no_cpu_baseline else cpu_baseline(p, l, beam)

@@ -79,8 +79,8 @@ size_t q8_workspace_bytes(int max_n, int max_l, int max_rows, int max_ld)
     b += 2 * up256((size_t)max_l * max_rows * 4);                 // encoder input pre-activations, both directions
     b += 8 * up256((size_t)max_n * max_rows * 4);                 // per-hypothesis vectors of a decoder step
     b += up256((size_t)max_n * max_l * 4);                        // attention energies
-    const size_t nblk = (size_t)q8i_out_blocks(max_rows);
-    b += up256(nblk * max_n * 4) + up256(nblk * max_n * 8) + 2 * up256(nblk * max_n * kMaxK * 4);
+    const size_t ngrp = (size_t)q8i_out_tiles(max_rows);
+    b += up256(ngrp * max_n * 4) + up256(ngrp * max_n * 8);
     return b + 65536;
 }
 
@@ -271,8 +271,7 @@ q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_m
     const int n = n_beam, R = W_out->cols, V = W_out->rows;
     if (n <= 0 || n > kMaxNarrow) return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam = %d outside [1, %d]", n, kMaxNarrow);
     if (k <= 0 || k > kMaxK || k > V) return q8_fail(ctx, Q8_ERR_SHAPE, "k = %d outside [1, min(%d, rows)]", k, kMaxK);
-    if (q8i_out_blocks(V) > 1024 || (size_t)q8i_out_blocks(V) * k > (size_t)q8i_out_max_keys())
-        return q8_fail(ctx, Q8_ERR_SHAPE, "W_out: rows x k too large for the top-k merge (%d rows, k %d)", V, k);
+    if (V > q8i_out_max_rows()) return q8_fail(ctx, Q8_ERR_SHAPE, "W_out: more than %d rows", q8i_out_max_rows());
     if (W_out->ld > 4096) return q8_fail(ctx, Q8_ERR_SHAPE, "W_out: ld above 4096");
     if (R % 4) return q8_fail(ctx, Q8_ERR_ALIGN, "R must be a multiple of 4");
     if (!topk_logp || !topk_idx) return q8_fail(ctx, Q8_ERR_NULL, "top-k outputs: NULL");
@@ -298,14 +297,12 @@ q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_m
     } else {
         TRY(check_vecs(ctx, t_in, R, R, "t_in"));
     }
-    const size_t nblk = (size_t)q8i_out_blocks(V);
-    float *pm = cv.take<float>(nblk * n);
-    double *ps = cv.take<double>(nblk * n);
-    float *cvl = cv.take<float>(nblk * n * k);
-    int *cid = cv.take<int>(nblk * n * k);
+    const size_t ngrp = (size_t)q8i_out_tiles(V);
+    float *pm = cv.take<float>(ngrp * n);
+    double *ps = cv.take<double>(ngrp * n);
+    float *lg = logits ? logits : cv.take<float>((size_t)n * V);    // the selection reads the logits back
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
-    return q8i_output(ctx, W_out, b_out, T, R, n, k, logits, lse, topk_logp, topk_idx, taps4 ? taps4 + 3 : nullptr,
-                      pm, ps, cvl, cid);
+    return q8i_output(ctx, W_out, b_out, T, R, n, k, lg, lse, topk_logp, topk_idx, taps4 ? taps4 + 3 : nullptr, pm, ps);
 }
 
 q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights *bwd, const float *X, int l,

@@ -11,42 +11,41 @@ struct AttArgs {
     int l, A, C;
 };
 
-// Block (i, b): energy e[b, i] = sum_j v_j tanh(P[i, j] + a[b, j]) (Eq. 6).  The last
-// block to arrive for hypothesis b turns the energies into weights and the context
-// vector H_t (Eq. 5).  Sums run in double; every stored value is rounded once to fp32.
-__global__ __launch_bounds__(256) void attention_kernel(AttArgs a)
+// Block (i, b), 1024 threads: energy e[b, i] = sum_j v_j tanh(P[i, j] + a[b, j]) (Eq. 6).
+// The last block to arrive for hypothesis b turns the energies into weights and the
+// context vector H_t (Eq. 5).  Sums run in double; every stored value is rounded once.
+#define ATT_THREADS 1024
+__global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
 {
-    __shared__ double s_red[4];
+    __shared__ double s_red[ATT_THREADS / 64];
     __shared__ float s_alpha[1024];
     __shared__ int s_last;
     const int i = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    Q8_STAMP(0);
     const float *Pi = a.P + (size_t)i * a.A;
     const float *ab = a.a + (size_t)b * a.A;
     double acc = 0.0;
-    if ((a.A & 3) == 0) {
-        for (int j = tid * 4; j < a.A; j += 1024) {
-            const float4 p = *(const float4 *)(Pi + j), q = *(const float4 *)(ab + j), vv = *(const float4 *)(a.v + j);
-            acc += (double)vv.x * (double)tanh_rn(p.x + q.x);
-            acc += (double)vv.y * (double)tanh_rn(p.y + q.y);
-            acc += (double)vv.z * (double)tanh_rn(p.z + q.z);
-            acc += (double)vv.w * (double)tanh_rn(p.w + q.w);
-        }
-    } else {
-        for (int j = tid; j < a.A; j += 256) acc += (double)a.v[j] * (double)tanh_rn(Pi[j] + ab[j]);
-    }
+    for (int j = tid; j < a.A; j += ATT_THREADS) acc += (double)a.v[j] * (double)tanh_rn(Pi[j] + ab[j]);
     acc = wave_sum_d(acc);
     if (lane == 0) s_red[wave] = acc;
+    Q8_STAMP(1);
     __syncthreads();
     if (tid == 0) {
-        const double tot = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
-        a.e[(size_t)b * a.l + i] = (float)tot;
-        __threadfence();
-        const unsigned prev = atomicAdd(&a.counters[b], 1u);
+        double tot = 0.0;
+#pragma unroll
+        for (int w = 0; w < ATT_THREADS / 64; ++w) tot += s_red[w];
+        // Publish the energy with a device-coherent store, wait until it has been performed,
+        // then count the arrival with a device-coherent atomic: the block that sees the last
+        // count can read every energy with device-coherent loads, no cache flush needed.
+        __hip_atomic_store(&a.e[(size_t)b * a.l + i], (float)tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): the store above has been performed
+        const unsigned prev = __hip_atomic_fetch_add(&a.counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_last = (prev == (unsigned)a.l - 1u);
     }
     __syncthreads();
+    Q8_STAMP(2);
     if (!s_last) return;
-    __threadfence();
+    if (tid == 0 && b == 0) q8_trace_stamp(16);
 
     // softmax over the l energies of hypothesis b: one wave, lane t holds e[t], e[t+64], ...
     const int l = a.l;
@@ -54,7 +53,7 @@ __global__ __launch_bounds__(256) void attention_kernel(AttArgs a)
         const float *e = a.e + (size_t)b * l;
         float mx = -INFINITY;
         for (int t = lane; t < l; t += 64) {
-            const float ev = __builtin_nontemporal_load(e + t);
+            const float ev = __hip_atomic_load(e + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             s_alpha[t] = ev;
             mx = fmaxf(mx, ev);
         }
@@ -67,30 +66,34 @@ __global__ __launch_bounds__(256) void attention_kernel(AttArgs a)
             s_alpha[t] = al;
             if (a.alpha) a.alpha[(size_t)b * l + t] = al;
         }
-        if (lane == 0) a.counters[b] = 0;
+        if (lane == 0) __hip_atomic_store(&a.counters[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
-    // context: each thread owns groups of four adjacent columns
-    if ((a.C & 3) == 0) {
-        for (int c = tid * 4; c < a.C; c += 1024) {
-            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    if (tid == 0 && b == 0) q8_trace_stamp(17);
+    // context: a thread owns two adjacent columns and walks the source positions in order
+    if ((a.C & 1) == 0) {
+        for (int c = tid * 2; c < a.C; c += 2 * ATT_THREADS) {
+            double s0 = 0.0, s1 = 0.0;
             const float *h = a.enc_h + c;
-#pragma unroll 6
+#pragma unroll 10
             for (int t = 0; t < l; ++t) {
-                const float4 hv = *(const float4 *)(h + (size_t)t * a.C);
+                const float2 hv = *(const float2 *)(h + (size_t)t * a.C);
                 const double al = (double)s_alpha[t];
-                s0 += al * (double)hv.x; s1 += al * (double)hv.y; s2 += al * (double)hv.z; s3 += al * (double)hv.w;
+                s0 += al * (double)hv.x;
+                s1 += al * (double)hv.y;
             }
-            *(float4 *)(a.ctx + (size_t)b * a.C + c) = make_float4((float)s0, (float)s1, (float)s2, (float)s3);
+            *(float2 *)(a.ctx + (size_t)b * a.C + c) = make_float2((float)s0, (float)s1);
         }
     } else {
-        for (int c = tid; c < a.C; c += 256) {
+        for (int c = tid; c < a.C; c += ATT_THREADS) {
             double s = 0.0;
             for (int t = 0; t < l; ++t) s += (double)s_alpha[t] * (double)a.enc_h[(size_t)t * a.C + c];
             a.ctx[(size_t)b * a.C + c] = (float)s;
         }
     }
+    if (tid == 0 && b == 0) q8_trace_stamp(18);
 }
+Q8_TRACE_READER(q8_trace_decoder)
 
 // ========================================================================== readout ==
 
@@ -236,7 +239,7 @@ q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, 
     t.P = P; t.enc_h = enc_h; t.a = a; t.v = v; t.e = e; t.alpha = alpha; t.ctx = cvec;
     t.counters = (unsigned *)ctx->ws;
     t.l = l; t.A = A; t.C = C;
-    hipLaunchKernelGGL(attention_kernel, dim3(l, n), dim3(256), 0, ctx->stream, t);
+    hipLaunchKernelGGL(attention_kernel, dim3(l, n), dim3(ATT_THREADS), 0, ctx->stream, t);
     return q8i_launch_check(ctx, "attention");
 }
 

@@ -13,6 +13,17 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 
 #define Q8_WAVE 64
 
+#ifdef Q8_TRACE   // phase timing experiment only: never defined in the product build
+static __device__ long long q8_trace_buf[64];
+#define Q8_STAMP(slot) do { if (threadIdx.x == 0 && blockIdx.x == (gridDim.x >> 1) && blockIdx.y == 0) q8_trace_buf[slot] = clock64(); } while (0)
+__device__ __forceinline__ void q8_trace_stamp(int slot) { q8_trace_buf[slot] = clock64(); }
+#define Q8_TRACE_READER(name) extern "C" void name(long long *host) { (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(q8_trace_buf), sizeof(long long) * 64); }
+#else
+#define Q8_STAMP(slot) do {} while (0)
+#define Q8_TRACE_READER(name)
+__device__ __forceinline__ void q8_trace_stamp(int) {}
+#endif
+
 // ---------------------------------------------------------------- cross-lane ----
 
 template <int CTRL>
@@ -51,11 +62,32 @@ __device__ __forceinline__ float wave_max_f(float v)
                  __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32)));
 }
 
+template <int CTRL>
+__device__ __forceinline__ double dpp_mov_d(double v)
+{
+    const long long b = __double_as_longlong(v);
+    const unsigned lo = dpp_mov_i<CTRL>((int)(unsigned)b), hi = dpp_mov_i<CTRL>((int)(unsigned)(b >> 32));
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
+// Sum of a double over the wave (fixed tree order), result in every lane.
 __device__ __forceinline__ double wave_sum_d(double v)
 {
-#pragma unroll
-    for (int s = 1; s < 64; s <<= 1) v += __shfl_xor(v, s, 64);
-    return v;
+    v += dpp_mov_d<DPP_XOR1>(v);
+    v += dpp_mov_d<DPP_XOR2>(v);
+    v += dpp_mov_d<DPP_HALF_MIRROR>(v);
+    v += dpp_mov_d<DPP_MIRROR>(v);
+    {
+        const long long b = __double_as_longlong(v);
+        const unsigned lo = __builtin_amdgcn_ds_swizzle((int)(unsigned)b, SWZ_XOR16);
+        const unsigned hi = __builtin_amdgcn_ds_swizzle((int)(unsigned)(b >> 32), SWZ_XOR16);
+        v += __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+    }
+    const long long b = __double_as_longlong(v);
+    const unsigned lo0 = __builtin_amdgcn_readlane((int)(unsigned)b, 0), hi0 = __builtin_amdgcn_readlane((int)(unsigned)(b >> 32), 0);
+    const unsigned lo1 = __builtin_amdgcn_readlane((int)(unsigned)b, 32), hi1 = __builtin_amdgcn_readlane((int)(unsigned)(b >> 32), 32);
+    return __longlong_as_double((long long)(((unsigned long long)hi0 << 32) | lo0)) +
+           __longlong_as_double((long long)(((unsigned long long)hi1 << 32) | lo1));
 }
 
 template <int CTRL>
@@ -269,36 +301,65 @@ __device__ __forceinline__ void x_load(XRegs<N, CH> &R, const float *__restrict_
         }
 }
 
+// Wave maxima of N independent values, the cross-lane steps of all N interleaved so that
+// their latencies overlap.
+template <int N>
+__device__ __forceinline__ void wave_max_multi(float (&m)[N])
+{
+#pragma unroll
+    for (int j = 0; j < N; ++j) m[j] = fmaxf(m[j], __int_as_float(dpp_mov_i<DPP_XOR1>(__float_as_int(m[j]))));
+#pragma unroll
+    for (int j = 0; j < N; ++j) m[j] = fmaxf(m[j], __int_as_float(dpp_mov_i<DPP_XOR2>(__float_as_int(m[j]))));
+#pragma unroll
+    for (int j = 0; j < N; ++j) m[j] = fmaxf(m[j], __int_as_float(dpp_mov_i<DPP_HALF_MIRROR>(__float_as_int(m[j]))));
+#pragma unroll
+    for (int j = 0; j < N; ++j) m[j] = fmaxf(m[j], __int_as_float(dpp_mov_i<DPP_MIRROR>(__float_as_int(m[j]))));
+#pragma unroll
+    for (int j = 0; j < N; ++j) m[j] = fmaxf(m[j], __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(m[j]), SWZ_XOR16)));
+#pragma unroll
+    for (int j = 0; j < N; ++j)
+        m[j] = fmaxf(__int_as_float(__builtin_amdgcn_readlane(__float_as_int(m[j]), 0)),
+                     __int_as_float(__builtin_amdgcn_readlane(__float_as_int(m[j]), 32)));
+}
+
 // Turns the staged vectors into int8 codes in LDS (xq[j * ld + k], bytes [K, ld) zero) and
-// scales in s_scale[j].  s_red: N * 4 floats.  Ends with a block barrier.
+// scales in s_scale[j].  s_red: N * 4 floats.  Ends with a block barrier.  The two
+// divisions per vector are done once per wave, by lane j for vector j, and broadcast.
 template <int N, int CH>
 __device__ __forceinline__ void x_finish(const XRegs<N, CH> &R, int n, int ld, int8_t *xq, float *s_scale, float *s_red)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    float m[N];
 #pragma unroll
     for (int j = 0; j < N; ++j) {
-        float m = 0.0f;
+        m[j] = 0.0f;
 #pragma unroll
         for (int t = 0; t < CH; ++t) {
             const float4 v = R.v[j][t];
-            m = fmaxf(m, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+            m[j] = fmaxf(m[j], fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
         }
-        m = wave_max_f(m);
-        if (lane == 0) s_red[j * 4 + wave] = m;
+    }
+    wave_max_multi<N>(m);
+    if (lane == 0) {
+#pragma unroll
+        for (int j = 0; j < N; ++j) s_red[j * 4 + wave] = m[j];
     }
     __syncthreads();
+    float scale = 1.0f, inv = 0.0f;
+    if (lane < N) {
+        const float mm = fmaxf(fmaxf(s_red[lane * 4], s_red[lane * 4 + 1]), fmaxf(s_red[lane * 4 + 2], s_red[lane * 4 + 3]));
+        q8_scale_of(mm, scale, inv);
+        if (wave == 0) s_scale[lane] = scale;
+    }
 #pragma unroll
     for (int j = 0; j < N; ++j) {
         if (j < n) {
-            const float mm = fmaxf(fmaxf(s_red[j * 4], s_red[j * 4 + 1]), fmaxf(s_red[j * 4 + 2], s_red[j * 4 + 3]));
-            float scale, inv;
-            q8_scale_of(mm, scale, inv);
-            if (tid == 0) s_scale[j] = scale;
+            const float invj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(inv), j));
 #pragma unroll
             for (int t = 0; t < CH; ++t) {
                 const int k = (t * 256 + tid) * 4;
                 const float4 v = R.v[j][t];      // zero beyond K, so pad bytes come out zero
-                if (k < ld) *(int *)(xq + (size_t)j * ld + k) = q8_pack4(v.x, v.y, v.z, v.w, inv);
+                if (k < ld) *(int *)(xq + (size_t)j * ld + k) = q8_pack4(v.x, v.y, v.z, v.w, invj);
             }
         }
     }
@@ -356,5 +417,10 @@ static inline int q8_lanes_per_row(int ld)
 }
 
 // fp32 nonlinearities of the gates, evaluated in double and rounded once.
+#ifdef Q8_EXPERIMENT_F32MATH   // timing experiment only: never defined in the product build
+__device__ __forceinline__ float sigmoid_rn(float a) { return 1.0f / (1.0f + __expf(-a)); }
+__device__ __forceinline__ float tanh_rn(float a) { return 1.0f - 2.0f / (1.0f + __expf(2.0f * a)); }
+#else
 __device__ __forceinline__ float sigmoid_rn(float a) { return (float)(1.0 / (1.0 + exp(-(double)a))); }
 __device__ __forceinline__ float tanh_rn(float a) { return (float)tanh((double)a); }
+#endif

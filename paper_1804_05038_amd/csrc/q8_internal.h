@@ -68,9 +68,9 @@ q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, 
                         const float *v, int n, float *e, float *alpha, float *cvec);
 q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,
                       float *t_out, const q8_taps *taps3);
-int q8i_out_blocks(int V);
-int q8i_out_max_keys(void);
+int q8i_out_tiles(int V);
+int q8i_out_max_rows(void);
 q8_status q8i_launch_check(q8_ctx *ctx, const char *what);
 q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const float *T, int ldt, int n, int k,
                      float *logits, float *lse, float *topk_logp, int32_t *topk_idx, const q8_taps *taps,
-                     float *part_max, double *part_sum, float *cand_val, int *cand_idx);
+                     float *part_max, double *part_sum);

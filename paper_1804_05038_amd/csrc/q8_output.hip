@@ -1,63 +1,70 @@
 // q8_output.hip -- second layer of the output network g of Eq. 2 ("Pieces of Eight: 8-bit
 // Neural Machine Translation"): the vocabulary projection as Section 3's narrow product
-// on the int8 matrix cores, fused with bias, log-sum-exp partials and a per-block top-k;
-// a small second kernel merges the partials.
+// on the int8 matrix cores, fused with bias and log-sum-exp partials; a second kernel
+// finishes the log-sum-exp and selects the k best entries of every hypothesis.
 #include "q8_internal.h"
 
 #include <hip/hip_ext.h>
 
-#define OUT_TPW 3                    // 16-row tiles per wave
-#define OUT_RB (4 * OUT_TPW * 16)    // vocabulary rows per block
+#define OUT_TILE 16                  // vocabulary rows per matrix-core tile = one selection group
+#define OUT_SB 16                    // tiles per super-block of the threshold search
+#define OUT_BLOCKS 512               // blocks of 4 waves; tile t belongs to block t % OUT_BLOCKS
+#define OUT_MAX_TILES 4096           // 65536 vocabulary rows
 
 struct OutArgs {
     const int8_t *W;
     const float *T, *bias;
-    float *logits;
-    float *part_max;
-    double *part_sum;
-    float *cand_val;
-    int *cand_idx;
+    float *logits;          // [n x ldl], always written
+    float *part_max;        // [tiles x n]
+    double *part_sum;       // [tiles x n]: sum of exp(logit - part_max)
     q8_taps taps;
-    int V, K, ld, ldt, n, k, ldl;
+    int V, K, ld, ldt, n, ldl, ntiles;
     float w_scale;
 };
 
 // One pass over W_out for all n <= 8 hypotheses.  Operand A of v_mfma_i32_16x16x64_i8 =
 // 16 weight rows x 64 k (lane: row lane%16, 16 consecutive k at 16*(lane/16)), operand B =
 // the quantized hidden vectors with the same k split; the result leaves rows
-// 4*(lane/16)+r, r = 0..3, of hypothesis lane%16 in the lane.  Work is cut into items of
-// 16 rows x 512 k; the loads of item i+1 are in flight while item i is multiplied.
+// 4*(lane/16)+r, r = 0..3, of hypothesis lane%16 in the lane.  Tiles of 16 rows are dealt
+// round-robin to blocks and, within a block, to waves, so every CU streams the same
+// number of bytes.  Work is cut into items of 16 rows x 512 k; two items are in flight
+// per wave.  Each tile's (max, sum of exp) per hypothesis is reduced in registers.
 template <int CH>
 __global__ __launch_bounds__(256) void out_logits_kernel(OutArgs a)
 {
     extern __shared__ __align__(16) int8_t smem[];
     __shared__ float s_scale[8];
     __shared__ float s_red[8 * 4];
-    __shared__ float s_log[8][OUT_RB];
     const int ld = a.ld, n = a.n;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 15, g = lane >> 4;
-    const int brow0 = blockIdx.x * OUT_RB;
     const int kchunks = (ld + 511) / 512;
-    const int items = OUT_TPW * kchunks;
+    // tiles of this wave: blockIdx + (wave + 4 q) * gridDim, q = 0, 1, ...
+    const int tstride = 4 * gridDim.x;
+    const int tile0 = blockIdx.x + wave * gridDim.x;
+    const int ntw = tile0 < a.ntiles ? (a.ntiles - tile0 + tstride - 1) / tstride : 0;
+    const int items = ntw * kchunks;
 
+    Q8_STAMP(0);
     XRegs<8, CH> xr;
     x_load<8, CH>(xr, a.T, n, a.K, a.ldt);
 
     auto load_item = [&](int it, v4i (&av)[8]) {
-        const int tile = it / kchunks, kc = it - tile * kchunks;
-        const int row = brow0 + (wave * OUT_TPW + tile) * 16 + i;
+        const int q = it / kchunks, kc = it - q * kchunks;
+        const int row = (tile0 + q * tstride) * OUT_TILE + i;
         const int8_t *wp = a.W + (size_t)row * ld + kc * 512 + 16 * g;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
             av[s] = (v4i){0, 0, 0, 0};
-            if (row < a.V && kc * 512 + 64 * s + 16 * g < ld) av[s] = *(const v4i *)(wp + 64 * s);
+            if (it < items && row < a.V && kc * 512 + 64 * s + 16 * g < ld) av[s] = *(const v4i *)(wp + 64 * s);
         }
     };
-    v4i cur[8], nxt[8];
-    load_item(0, cur);
+    v4i bufA[8], bufB[8];
+    load_item(0, bufA);
+    load_item(1, bufB);
 
     x_finish<8, CH>(xr, n, ld, smem, s_scale, s_red);
+    Q8_STAMP(1);
     if (blockIdx.x == 0) {
         if (a.taps.xq)
             for (int e = threadIdx.x; e < n * a.K; e += blockDim.x) a.taps.xq[e] = smem[(e / a.K) * ld + e % a.K];
@@ -65,166 +72,221 @@ __global__ __launch_bounds__(256) void out_logits_kernel(OutArgs a)
     }
     const float cj = i < n ? a.w_scale * s_scale[i] : 0.0f;
     const int8_t *xb = smem + (size_t)i * ld + 16 * g;
+    const bool vec_ok = ((a.ldl & 3) == 0) && (((uintptr_t)a.logits & 15) == 0);
 
     v4i acc = (v4i){0, 0, 0, 0};
-    for (int it = 0; it < items; ++it) {
-        if (it + 1 < items) load_item(it + 1, nxt);
-        const int tile = it / kchunks, kc = it - tile * kchunks;
+    auto compute_item = [&](int it, const v4i (&av)[8]) {
+        const int q = it / kchunks, kc = it - q * kchunks;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
             v4i bv = (v4i){0, 0, 0, 0};
             if (i < n && kc * 512 + 64 * s + 16 * g < ld) bv = *(const v4i *)(xb + kc * 512 + 64 * s);
-            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(cur[s], bv, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[s], bv, acc, 0, 0, 0);
         }
-        if (kc == kchunks - 1) {
-            const int r0 = brow0 + (wave * OUT_TPW + tile) * 16;
-            if (i < n) {
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = r0 + 4 * g + r;
-                    float y = -INFINITY;
-                    if (row < a.V) {
-                        y = (float)acc[r] * cj;
-                        if (a.bias) y = y + a.bias[row];
-                        if (a.logits) a.logits[(size_t)i * a.ldl + row] = y;
-                        if (a.taps.acc) a.taps.acc[(size_t)i * a.V + row] = acc[r];
-                    }
-                    s_log[i][row - brow0] = y;
-                }
-            }
-            acc = (v4i){0, 0, 0, 0};
-        }
-#pragma unroll
-        for (int s = 0; s < 8; ++s) cur[s] = nxt[s];
-    }
-    __syncthreads();
-
-    // per hypothesis: block maximum, sum of exp, and the k best (value, row) pairs
-    for (int j = wave; j < n; j += 4) {
-        float v[OUT_RB / 64];
+        if (kc != kchunks - 1) return;
+        const int tile = tile0 + q * tstride;
+        const int row0 = tile * OUT_TILE + 4 * g;
+        float y[4];
         float m = -INFINITY;
 #pragma unroll
-        for (int t = 0; t < OUT_RB / 64; ++t) {
-            v[t] = s_log[j][lane + 64 * t];
-            m = fmaxf(m, v[t]);
+        for (int r = 0; r < 4; ++r) {
+            y[r] = -INFINITY;
+            if (i < n && row0 + r < a.V) {
+                y[r] = (float)acc[r] * cj;
+                if (a.bias) y[r] = y[r] + a.bias[row0 + r];
+                if (a.taps.acc) a.taps.acc[(size_t)i * a.V + row0 + r] = acc[r];
+            }
+            m = fmaxf(m, y[r]);
         }
-        m = wave_max_f(m);
-        double s = 0.0;
-        unsigned long long key[OUT_RB / 64];
+        if (i < n) {
+            if (vec_ok && row0 + 3 < a.V) {
+                *(float4 *)(a.logits + (size_t)i * a.ldl + row0) = make_float4(y[0], y[1], y[2], y[3]);
+            } else {
 #pragma unroll
-        for (int t = 0; t < OUT_RB / 64; ++t) {
-            const int row = brow0 + lane + 64 * t;
-            key[t] = 0ull;
-            if (row < a.V) {
-                s += exp((double)v[t] - (double)m);
-                key[t] = topk_key(v[t], row);
+                for (int r = 0; r < 4; ++r)
+                    if (row0 + r < a.V) a.logits[(size_t)i * a.ldl + row0 + r] = y[r];
             }
         }
-        s = wave_sum_d(s);
-        if (lane == 0) {
-            a.part_max[(size_t)blockIdx.x * n + j] = m;
-            a.part_sum[(size_t)blockIdx.x * n + j] = s;
+        // (max, sum of exp) of the tile's 16 rows per hypothesis: lanes i, i+16, i+32, i+48
+        m = fmaxf(m, __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(m), SWZ_XOR16)));
+        m = fmaxf(m, __shfl_xor(m, 32, 64));
+        double sd = 0.0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if (y[r] > -INFINITY) sd += (double)__expf(y[r] - m);
+        sd += __shfl_xor(sd, 16, 64);
+        sd += __shfl_xor(sd, 32, 64);
+        if (i < n && g == 0) {
+            a.part_max[(size_t)tile * n + i] = m;
+            a.part_sum[(size_t)tile * n + i] = sd;
         }
-        for (int r = 0; r < a.k; ++r) {
-            unsigned long long best = key[0];
-#pragma unroll
-            for (int t = 1; t < OUT_RB / 64; ++t) best = key[t] > best ? key[t] : best;
-            best = wave_max_u64(best);
-            if (lane == 0) {
-                const size_t o = ((size_t)blockIdx.x * n + j) * a.k + r;
-                a.cand_val[o] = best ? topk_key_val(best) : -INFINITY;
-                a.cand_idx[o] = best ? topk_key_idx(best) : -1;
-            }
-#pragma unroll
-            for (int t = 0; t < OUT_RB / 64; ++t)
-                if (key[t] == best) key[t] = 0ull;
+        acc = (v4i){0, 0, 0, 0};
+    };
+    for (int it = 0; it < items; it += 2) {
+        compute_item(it, bufA);
+        load_item(it + 2, bufA);
+        if (it + 1 < items) {
+            compute_item(it + 1, bufB);
+            load_item(it + 3, bufB);
         }
     }
+    Q8_STAMP(3);
 }
+Q8_TRACE_READER(q8_trace_output)
 
-struct MergeArgs {
+struct SelectArgs {
     const float *part_max;
     const double *part_sum;
-    const float *cand_val;
-    const int *cand_idx;
+    const float *logits;
     float *lse, *topk_logp;
     int *topk_idx;
-    int nblk, n, k;
+    int ntiles, n, k, V, ldl;
 };
 
-#define MERGE_MAX_KEYS 7168   // candidate keys held in LDS (56 KiB)
+#define SEL_CAP 2048          // survivors held in LDS
 
-// One block per hypothesis.  All threads load the block partials and candidate lists;
-// wave 0 then merges the (sorted) lists k times, only the list heads competing.
-__global__ __launch_bounds__(256) void out_merge_kernel(MergeArgs a)
+// One block of 256 threads per hypothesis; thread t owns super-block t (16 tiles, 256 rows).
+// (1) log-sum-exp from the tile partials.  (2) T = the k-th largest super-block maximum
+// (by rank counting): at least k logits are >= T, so each of the k best logits is >= T and
+// lies in a tile whose maximum is >= T.  (3) Those tiles are read back, logits >= T
+// collected (a few dozen unless many logits tie) and ranked by (value descending, index
+// ascending).  If ties overflow the survivor list, k exact rounds of arg-max over the
+// whole row run instead.
+__global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
 {
-    __shared__ unsigned long long s_key[MERGE_MAX_KEYS];
-    __shared__ unsigned short s_ptr[1024];
-    __shared__ float s_m[4];
-    __shared__ double s_s[4];
+    __shared__ unsigned long long s_sbkey[256];
+    __shared__ unsigned short s_q[OUT_MAX_TILES];
+    __shared__ unsigned long long s_key[SEL_CAP];
+    __shared__ float s_f[4];
+    __shared__ double s_d[4];
+    __shared__ unsigned long long s_u[4];
+    __shared__ float s_T;
+    __shared__ int s_nq, s_ns;
     const int j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = a.n, k = a.k;
-    const int nblk = a.nblk;
-    for (int e = tid; e < nblk * k; e += 256) {
-        const int b = e / k, r = e - b * k;
-        const size_t o = ((size_t)b * n + j) * k + r;
-        const int idx = a.cand_idx[o];
-        s_key[e] = idx >= 0 ? topk_key(a.cand_val[o], idx) : 0ull;
-    }
-    for (int b = tid; b < nblk; b += 256) s_ptr[b] = 0;
-    float pm[4];
-    double ps[4];
-    float m = -INFINITY;
+    const int ntiles = a.ntiles, nsb = (ntiles + OUT_SB - 1) / OUT_SB;
+    if (tid == 0) { s_nq = 0; s_ns = 0; s_T = -INFINITY; }
+    Q8_STAMP(8);
+
+    float pm[OUT_SB];
+    double ps[OUT_SB];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-        const int b = tid + 256 * t;
+    for (int t = 0; t < OUT_SB; ++t) {
+        const int tile = tid * OUT_SB + t;
         pm[t] = -INFINITY;
         ps[t] = 0.0;
-        if (b < nblk) {
-            pm[t] = a.part_max[(size_t)b * n + j];
-            ps[t] = a.part_sum[(size_t)b * n + j];
+        if (tile < ntiles) {
+            pm[t] = a.part_max[(size_t)tile * n + j];
+            ps[t] = a.part_sum[(size_t)tile * n + j];
         }
-        m = fmaxf(m, pm[t]);
     }
-    m = wave_max_f(m);
-    if (lane == 0) s_m[wave] = m;
+    float bm = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < OUT_SB; ++t) bm = fmaxf(bm, pm[t]);
+    s_sbkey[tid] = tid < nsb ? topk_key(bm, tid) : 0ull;
+    float m = wave_max_f(bm);
+    if (lane == 0) s_f[wave] = m;
     __syncthreads();
-    m = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+    m = fmaxf(fmaxf(s_f[0], s_f[1]), fmaxf(s_f[2], s_f[3]));
     double S = 0.0;
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
-        if (tid + 256 * t < nblk) S += ps[t] * exp((double)pm[t] - (double)m);
+    for (int t = 0; t < OUT_SB; ++t)
+        if (pm[t] > -INFINITY) S += ps[t] * (double)__expf(pm[t] - m);
     S = wave_sum_d(S);
-    if (lane == 0) s_s[wave] = S;
+    if (lane == 0) s_d[wave] = S;
+    // rank of this super-block's maximum among all of them
+    if (tid < nsb) {
+        const unsigned long long key = s_sbkey[tid];
+        int rank = 0;
+        for (int u = 0; u < nsb; ++u) rank += (s_sbkey[u] > key);
+        if (rank == k - 1) s_T = bm;
+    }
     __syncthreads();
-    if (wave != 0) return;
-    S = (s_s[0] + s_s[1]) + (s_s[2] + s_s[3]);
+    S = (s_d[0] + s_d[1]) + (s_d[2] + s_d[3]);
     const float lse = (float)((double)m + log(S));
-    if (lane == 0 && a.lse) a.lse[j] = lse;
+    if (tid == 0 && a.lse) a.lse[j] = lse;
+    const float T = s_T;                        // -inf when there are fewer than k super-blocks
+    Q8_STAMP(10);
 
+    // ---- tiles that can hold a logit >= T
+#pragma unroll
+    for (int t = 0; t < OUT_SB; ++t)
+        if (tid * OUT_SB + t < ntiles && pm[t] >= T) s_q[atomicAdd(&s_nq, 1)] = (unsigned short)(tid * OUT_SB + t);
+    __syncthreads();
+    Q8_STAMP(11);
+    const int total = s_nq * OUT_TILE;
+    const float *lg = a.logits + (size_t)j * a.ldl;
+    bool overflow = false;
+    if (total <= 16 * SEL_CAP) {
+        for (int c0 = tid; c0 < total; c0 += 1024) {
+            float v[4];
+            int row[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int c = c0 + 256 * t;
+                row[t] = -1;
+                v[t] = -INFINITY;
+                if (c < total) {
+                    const int r = (int)s_q[c / OUT_TILE] * OUT_TILE + c % OUT_TILE;
+                    if (r < a.V) { row[t] = r; v[t] = lg[r]; }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                if (row[t] >= 0 && v[t] >= T) {
+                    const int pos = atomicAdd(&s_ns, 1);
+                    if (pos < SEL_CAP) s_key[pos] = topk_key(v[t], row[t]);
+                }
+        }
+        __syncthreads();
+        Q8_STAMP(12);
+        overflow = s_ns > SEL_CAP;
+    } else {
+        overflow = true;
+    }
+
+    if (!overflow) {
+        // rank every survivor among the survivors; ranks below k are the answer
+        const int ns = s_ns;
+        for (int t = tid; t < ns; t += 256) {
+            const unsigned long long key = s_key[t];
+            int rank = 0;
+            for (int u = 0; u < ns; ++u) rank += (s_key[u] > key);
+            if (rank < k) {
+                a.topk_idx[(size_t)j * k + rank] = topk_key_idx(key);
+                a.topk_logp[(size_t)j * k + rank] = topk_key_val(key) - lse;
+            }
+        }
+        Q8_STAMP(13);
+        return;
+    }
+
+    // ---- heavily tied logits: k exact rounds of arg-max over the whole row
+    unsigned long long prev = ~0ull;
     for (int r = 0; r < k; ++r) {
         unsigned long long best = 0ull;
-        for (int b = lane; b < nblk; b += 64) {
-            const int p = s_ptr[b];
-            const unsigned long long hk = p < k ? s_key[b * k + p] : 0ull;
-            best = hk > best ? hk : best;
+        for (int row = tid; row < a.V; row += 256) {
+            const unsigned long long key = topk_key(lg[row], row);
+            if (key < prev && key > best) best = key;
         }
         best = wave_max_u64(best);
-        const int idx = best ? topk_key_idx(best) : -1;
-        if (lane == 0) {
-            a.topk_idx[(size_t)j * k + r] = idx;
-            a.topk_logp[(size_t)j * k + r] = best ? topk_key_val(best) - lse : -INFINITY;
+        __syncthreads();
+        if (lane == 0) s_u[wave] = best;
+        __syncthreads();
+        best = s_u[0];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) best = s_u[w] > best ? s_u[w] : best;
+        if (tid == 0) {
+            a.topk_idx[(size_t)j * k + r] = topk_key_idx(best);
+            a.topk_logp[(size_t)j * k + r] = topk_key_val(best) - lse;
         }
-        if (best) {
-            const int b = idx / OUT_RB;
-            if ((b & 63) == lane) s_ptr[b] = s_ptr[b] + 1;
-        }
+        prev = best;
     }
 }
 
 // =================================================================== host launcher ==
 
-int q8i_out_blocks(int V) { return (V + OUT_RB - 1) / OUT_RB; }
-int q8i_out_max_keys(void) { return MERGE_MAX_KEYS; }
+int q8i_out_tiles(int V) { return (V + OUT_TILE - 1) / OUT_TILE; }
+int q8i_out_max_rows(void) { return OUT_MAX_TILES * OUT_TILE; }
 
 template <int CH>
 static void launch_out(q8_ctx *ctx, const OutArgs &a, int nblk, size_t smem)
@@ -241,25 +303,26 @@ static void launch_out(q8_ctx *ctx, const OutArgs &a, int nblk, size_t smem)
 
 q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const float *T, int ldt, int n, int k,
                      float *logits, float *lse, float *topk_logp, int32_t *topk_idx, const q8_taps *taps,
-                     float *part_max, double *part_sum, float *cand_val, int *cand_idx)
+                     float *part_max, double *part_sum)
 {
     OutArgs a;
     a.W = W->data; a.T = T; a.bias = bias; a.logits = logits;
-    a.part_max = part_max; a.part_sum = part_sum; a.cand_val = cand_val; a.cand_idx = cand_idx;
+    a.part_max = part_max; a.part_sum = part_sum;
     q8_taps none = {nullptr, nullptr, nullptr};
     a.taps = taps ? *taps : none;
-    a.V = W->rows; a.K = W->cols; a.ld = W->ld; a.ldt = ldt; a.n = n; a.k = k; a.ldl = W->rows;
+    a.V = W->rows; a.K = W->cols; a.ld = W->ld; a.ldt = ldt; a.n = n; a.ldl = W->rows;
     a.w_scale = W->scale;
-    const int nblk = q8i_out_blocks(a.V);
+    a.ntiles = q8i_out_tiles(a.V);
+    const int nblk = a.ntiles < 4 * OUT_BLOCKS ? (a.ntiles + 3) / 4 : OUT_BLOCKS;
     const size_t smem = (size_t)n * a.ld;
     const int ch = q8_fast_ch(a.ld);
     if (ch == 1) launch_out<1>(ctx, a, nblk, smem);
     else if (ch == 2) launch_out<2>(ctx, a, nblk, smem);
     else launch_out<4>(ctx, a, nblk, smem);
-    MergeArgs m;
-    m.part_max = part_max; m.part_sum = part_sum; m.cand_val = cand_val; m.cand_idx = cand_idx;
-    m.lse = lse; m.topk_logp = topk_logp; m.topk_idx = topk_idx;
-    m.nblk = nblk; m.n = n; m.k = k;
-    hipLaunchKernelGGL(out_merge_kernel, dim3(n), dim3(256), 0, ctx->stream, m);
+    SelectArgs s;
+    s.part_max = part_max; s.part_sum = part_sum; s.logits = logits;
+    s.lse = lse; s.topk_logp = topk_logp; s.topk_idx = topk_idx;
+    s.ntiles = a.ntiles; s.n = n; s.k = k; s.V = a.V; s.ldl = a.ldl;
+    hipLaunchKernelGGL(out_select_kernel, dim3(n), dim3(256), 0, ctx->stream, s);
     return q8i_launch_check(ctx, "output");
 }

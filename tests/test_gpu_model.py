@@ -194,3 +194,14 @@ def test_encoder(q, ctx, oracle, l, E, H):
         prev = enc[i + 1, :H] if i < l - 1 else z
         assert_close(enc[i, :H], m.enc_bwd.step(p["X"][i], prev), "backward state %d" % i)
     assert_close(enc, ref, "encoder states (free-running)")
+
+
+def test_output_layer_all_logits_equal_takes_the_exact_fallback(q, ctx, oracle):
+    """Every logit ties: the survivor list of the pruned selection overflows and the exact rounds run."""
+    V, R = 5000, 32
+    W = np.zeros((V, R), np.float32); W[0, 0] = 1.0     # scale needs a non-zero entry; t has a zero there
+    t = np.ones((2, R), np.float32); t[:, 0] = 0.0
+    Wm = gpu_mat(q, ctx, W)
+    r = q.output_logits_q8(ctx, None, Wm, None, t_in=ctx.f32(t), k=12)
+    assert np_(r["topk_idx"]).tolist() == [list(range(12))] * 2
+    np.testing.assert_allclose(np_(r["topk_logp"]), -np.log(V), rtol=1e-6)
