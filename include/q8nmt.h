@@ -165,6 +165,62 @@ q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_m
 q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights *bwd,
                     const float *X, int l, float *enc_h);
 
+/* ---- search (Section 3 only says the beam is smaller than 8; these are the rules) ----
+ * Token 0 is both begin- and end-of-sentence.  A search starts with one live hypothesis
+ * (score 0, previous token 0) and `beam` slots.  Each step every live hypothesis offers its
+ * k best continuations (k >= beam), scored cumulative + log-probability (one fp32 add);
+ * the b_live best candidates are kept, ordered by (score descending, parent ascending,
+ * token ascending); a kept candidate that ends in token 0 is finished (the best finished
+ * one is remembered, ties to the earlier) and b_live drops by one, the others become the
+ * live hypotheses.  The search is over when b_live is 0 or max_steps steps were made; the
+ * result is the best finished hypothesis, else the best live one.  Scores are not
+ * length-normalised.  The state lives on the device; slots that are not live carry score
+ * -inf and a copy of slot 0 so that the decoder kernels always see finite data. */
+
+/* Bytes of device memory of a search state for up to max_steps target tokens. */
+size_t q8_beam_state_bytes(int max_steps);
+
+/* Starts a search: writes the state, y_emb [beam x E] = E_tgt[0] and s [beam x H] = s0. */
+q8_status q8_beam_init(q8_ctx *ctx, void *state, int beam, int max_steps, const float *s0, const float *E_tgt,
+                       int E, int H, float *y_emb, float *s);
+
+/* One search step from the top-k of output_logits_q8 (topk_logp, topk_idx [n_beam x k]) and
+ * the decoder states s_step [n_beam x H] of this step: updates the state and writes the
+ * inputs of the next step, s_next [n_beam x H] (must not alias s_step) and y_emb
+ * [n_beam x E] = E_tgt[new tokens].  Does nothing once the search is over. */
+q8_status q8_beam_update(q8_ctx *ctx, void *state, const float *topk_logp, const int32_t *topk_idx, int n_beam,
+                         int k, const float *s_step, int H, const float *E_tgt, int E, float *y_emb, float *s_next);
+
+/* Waits for the stream and copies the result to the host: tokens (without the final
+ * token 0), their number, the cumulative log-probability, the steps made, and whether
+ * the search is over.  Host pointers; any may be NULL. */
+q8_status q8_beam_result(q8_ctx *ctx, const void *state, int max_steps, int32_t *tokens_host, int *len_host,
+                         float *score_host, int *steps_host, int *done_host);
+
+/* The whole model of Section 2. */
+typedef struct {
+    const float *E_src, *E_tgt;      /* fp32 embedding tables [V_src x E], [V_tgt x E]: gather only */
+    int V_src, V_tgt, E;
+    q8_gru_weights enc_fwd, enc_bwd; /* Eq. 1 */
+    q8_mat att_W;                    /* w of Eq. 6: [A x C] */
+    const float *att_b;              /* its bias [A] or NULL */
+    q8_cgru_weights dec;             /* Eq. 3-6 */
+    q8_readout_weights ro;           /* Eq. 2, first layer */
+    q8_mat W_out;                    /* Eq. 2, second layer [V_tgt x R] */
+    const float *b_out;
+} q8_model;
+
+/* Workspace bytes that q8_translate needs on top of q8_workspace_bytes(beam, max_l, ...). */
+size_t q8_translate_bytes(const q8_model *m, int max_l, int beam, int k, int max_steps);
+
+/* Translates one sentence: embedding lookup, encoder (Eq. 1), attention pre-computation
+ * w(h_i), initial decoder state = backward encoder state at the first position, then up
+ * to max_steps steps of cgru_decoder_step_q8 + output_logits_q8 + q8_beam_update, all
+ * enqueued without reading anything back except a 4-byte "search over" flag every 8
+ * steps.  src_tokens: l device int32 ids in [0, V_src).  Results as q8_beam_result. */
+q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens, int l, int beam, int k,
+                       int max_steps, int32_t *tokens_host, int *len_host, float *score_host, int *steps_host);
+
 /* Measurement helper (not an operation of the paper): between q8_profile_begin and
  * q8_profile_end, up to max_samples launches of the vocabulary-layer kernel of
  * output_logits_q8 carry a pair of HIP events that take the kernel's own begin and

@@ -14,7 +14,8 @@ _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 
 __all__ = ["Q8Error", "Context", "Mat", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
            "q8_quantize_matrix", "q8_gemv", "q8_gemm_narrow", "gru_step_q8", "cgru_decoder_step_q8",
-           "output_logits_q8", "q8_encode", "q8_workspace_bytes", "q8_profile_begin", "q8_profile_end", "LIB_PATH"]
+           "output_logits_q8", "q8_encode", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
+           "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "LIB_PATH"]
 LIB_PATH = _LIB_PATH
 
 STATUS = {0: "Q8_OK", 1: "Q8_ERR_NULL", 2: "Q8_ERR_SHAPE", 3: "Q8_ERR_ALIGN", 4: "Q8_ERR_WORKSPACE", 5: "Q8_ERR_DEVICE"}
@@ -46,6 +47,12 @@ class _Readout(C.Structure):
     _fields_ = [("W_s", _Mat), ("W_y", _Mat), ("W_c", _Mat), ("b_t", C.c_void_p)]
 
 
+class _Model(C.Structure):
+    _fields_ = [("E_src", C.c_void_p), ("E_tgt", C.c_void_p), ("V_src", C.c_int), ("V_tgt", C.c_int), ("E", C.c_int),
+                ("enc_fwd", _Gru), ("enc_bwd", _Gru), ("att_W", _Mat), ("att_b", C.c_void_p),
+                ("dec", _Cgru), ("ro", _Readout), ("W_out", _Mat), ("b_out", C.c_void_p)]
+
+
 _lib = None
 
 
@@ -72,6 +79,15 @@ def load_library():
         lib.output_logits_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, vp, ci, ci,
                                          vp, vp, vp, vp, vp, C.POINTER(_Taps)]
         lib.q8_encode.argtypes = [vp, C.POINTER(_Gru), C.POINTER(_Gru), vp, ci, vp]
+        lib.q8_beam_state_bytes.restype = C.c_size_t
+        lib.q8_beam_state_bytes.argtypes = [ci]
+        lib.q8_beam_init.argtypes = [vp, vp, ci, ci, vp, vp, ci, ci, vp, vp]
+        lib.q8_beam_update.argtypes = [vp, vp, vp, vp, ci, ci, vp, ci, vp, ci, vp, vp]
+        ip = C.POINTER(C.c_int)
+        lib.q8_beam_result.argtypes = [vp, vp, ci, vp, ip, C.POINTER(C.c_float), ip, ip]
+        lib.q8_translate_bytes.restype = C.c_size_t
+        lib.q8_translate_bytes.argtypes = [C.POINTER(_Model), ci, ci, ci, ci]
+        lib.q8_translate.argtypes = [vp, C.POINTER(_Model), vp, ci, ci, ci, ci, vp, ip, C.POINTER(C.c_float), ip]
         lib.q8_profile_begin.argtypes = [vp, ci]
         lib.q8_profile_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int)]
         _lib = lib
@@ -293,3 +309,68 @@ def q8_profile_end(ctx):
     ms, n = C.c_float(), C.c_int()
     ctx.check(ctx.lib.q8_profile_end(ctx.handle, C.byref(ms), C.byref(n)))
     return ms.value, n.value
+
+
+class Model:
+    """q8_model: every tensor of the translation model, already on the device."""
+
+    def __init__(self, E_src, E_tgt, enc_fwd, enc_bwd, att_W, att_b, dec, ro, W_out, b_out):
+        self.keep = (E_src, E_tgt, enc_fwd, enc_bwd, att_W, att_b, dec, ro, W_out, b_out)
+        self.E_src, self.E_tgt, self.dec, self.ro, self.W_out, self.b_out = E_src, E_tgt, dec, ro, W_out, b_out
+        self.enc_fwd, self.enc_bwd, self.att_W, self.att_b = enc_fwd, enc_bwd, att_W, att_b
+        self.c = _Model(E_src.data_ptr(), E_tgt.data_ptr(), E_src.shape[0], E_tgt.shape[0], E_src.shape[1],
+                        enc_fwd.c, enc_bwd.c, att_W.c, att_b.data_ptr() if att_b is not None else None,
+                        dec.c, ro.c, W_out.c, b_out.data_ptr() if b_out is not None else None)
+
+    @classmethod
+    def from_params(cls, ctx, p):
+        """Quantizes a dict of fp32 arrays (keys as in workloads.synth.full_model) on the device."""
+        mat = lambda k: q8_quantize_matrix(ctx, p[k])
+        gru = lambda pre: GruWeights(mat(pre + ".Wx"), mat(pre + ".Wh"), ctx.f32(p[pre + ".bx"]), ctx.f32(p[pre + ".bh"]))
+        dec = CgruWeights(gru("dec_r"), mat("att.U"), ctx.f32(p["att.v"]), gru("dec_q"))
+        ro = ReadoutWeights(mat("ro.Ws"), mat("ro.Wy"), mat("ro.Wc"), ctx.f32(p["ro.b"]))
+        return cls(ctx.f32(p["E_src"]), ctx.f32(p["E_tgt"]), gru("enc_fwd"), gru("enc_bwd"), mat("att.W"),
+                   ctx.f32(p["att.b"]), dec, ro, mat("out.W"), ctx.f32(p["out.b"]))
+
+
+def q8_translate_bytes(model, max_l, beam, k, max_steps):
+    return load_library().q8_translate_bytes(C.byref(model.c), max_l, beam, k, max_steps)
+
+
+def q8_translate(ctx, model, src_tokens, beam=5, k=12, max_steps=100):
+    """Returns (tokens ndarray, score, steps)."""
+    import numpy as np
+    src = torch.as_tensor(np.asarray(src_tokens, dtype=np.int32)).to(ctx.device) if not isinstance(src_tokens, torch.Tensor) else src_tokens
+    out = (C.c_int32 * max_steps)()
+    n, steps, score = C.c_int(), C.c_int(), C.c_float()
+    ctx.check(ctx.lib.q8_translate(ctx.handle, C.byref(model.c), _ptr(src), src.shape[0], beam, k, max_steps,
+                                   out, C.byref(n), C.byref(score), C.byref(steps)))
+    return np.array(out[:n.value], dtype=np.int32), np.float32(score.value), steps.value
+
+
+def q8_beam_state_bytes(max_steps):
+    return load_library().q8_beam_state_bytes(max_steps)
+
+
+def q8_beam_init(ctx, state, beam, max_steps, s0, E_tgt, y_emb, s):
+    ctx.check(ctx.lib.q8_beam_init(ctx.handle, _ptr(state), beam, max_steps, _ptr(s0), _ptr(E_tgt), E_tgt.shape[1],
+                                   s.shape[1], _ptr(y_emb), _ptr(s)))
+
+
+def q8_beam_update(ctx, state, topk_logp, topk_idx, s_step, E_tgt, y_emb, s_next, bind=False):
+    n, k = topk_logp.shape
+    args = (ctx.handle, _ptr(state), _ptr(topk_logp), _ptr(topk_idx), n, k, _ptr(s_step), s_step.shape[1],
+            _ptr(E_tgt), E_tgt.shape[1], _ptr(y_emb), _ptr(s_next))
+    if bind:
+        return _Bound(ctx, ctx.lib.q8_beam_update, args, {"keep": (state, topk_logp, topk_idx, s_step, E_tgt, y_emb, s_next)})
+    ctx.check(ctx.lib.q8_beam_update(*args))
+
+
+def q8_beam_result(ctx, state, max_steps):
+    """Returns (tokens, score, steps, done)."""
+    import numpy as np
+    out = (C.c_int32 * max_steps)()
+    n, steps, done, score = C.c_int(), C.c_int(), C.c_int(), C.c_float()
+    ctx.check(ctx.lib.q8_beam_result(ctx.handle, _ptr(state), max_steps, out, C.byref(n), C.byref(score), C.byref(steps),
+                                     C.byref(done)))
+    return np.array(out[:n.value], dtype=np.int32), np.float32(score.value), steps.value, bool(done.value)

@@ -19,7 +19,7 @@ struct Carver {
     char *base;
     size_t cap, off;
     bool ok;
-    explicit Carver(q8_ctx *c) : base(c->ws), cap(c->ws_bytes), off(Q8_WS_HEADER), ok(true) {}
+    explicit Carver(q8_ctx *c) : base(c->ws), cap(c->ws_bytes - c->ws_reserved_top), off(Q8_WS_HEADER), ok(true) {}
     template <class T> T *take(size_t count)
     {
         size_t bytes = up256(count * sizeof(T));
@@ -99,6 +99,7 @@ q8_status q8_create(q8_ctx **out, void *hip_stream, void *workspace, size_t work
     c->err[0] = 0;
     c->prof_ev = nullptr;
     c->prof_cap = c->prof_n = 0;
+    c->ws_reserved_top = 0;
     q8_status st = q8i_fill_u32(c, c->ws, Q8_WS_HEADER / 4, 0u);
     if (st) { delete c; return st; }
     *out = c;
@@ -347,6 +348,113 @@ q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights
         TRY(q8i_gru(ctx, d, 2, 1, Q8I_GRU_GX_PRE));
     }
     return Q8_OK;
+}
+
+size_t q8_beam_state_bytes(int max_steps) { return q8i_beam_state_bytes(max_steps < 1 ? 1 : max_steps); }
+
+q8_status q8_beam_init(q8_ctx *ctx, void *state, int beam, int max_steps, const float *s0, const float *E_tgt, int E,
+                       int H, float *y_emb, float *s)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!state || !s0 || !E_tgt || !y_emb || !s) return q8_fail(ctx, Q8_ERR_NULL, "q8_beam_init: NULL argument");
+    if (beam <= 0 || beam > Q8_MAX_BEAM || max_steps <= 0 || E <= 0 || H <= 0)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "q8_beam_init: beam %d (max %d), max_steps %d", beam, Q8_MAX_BEAM, max_steps);
+    return q8i_beam_init(ctx, state, beam, max_steps, s0, E_tgt, E, H, y_emb, s);
+}
+
+q8_status q8_beam_update(q8_ctx *ctx, void *state, const float *topk_logp, const int32_t *topk_idx, int n_beam, int k,
+                         const float *s_step, int H, const float *E_tgt, int E, float *y_emb, float *s_next)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!state || !topk_logp || !topk_idx || !s_step || !E_tgt || !y_emb || !s_next)
+        return q8_fail(ctx, Q8_ERR_NULL, "q8_beam_update: NULL argument");
+    if (n_beam <= 0 || n_beam > Q8_MAX_BEAM || k < n_beam || k > kMaxK || E <= 0 || H <= 0)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "q8_beam_update: need 1 <= n_beam <= %d and n_beam <= k <= %d", Q8_MAX_BEAM, kMaxK);
+    if (s_next == s_step) return q8_fail(ctx, Q8_ERR_SHAPE, "s_next must not alias s_step");
+    return q8i_beam_update(ctx, state, topk_logp, topk_idx, n_beam, k, s_step, H, E_tgt, E, y_emb, s_next);
+}
+
+q8_status q8_beam_result(q8_ctx *ctx, const void *state, int max_steps, int32_t *tokens_host, int *len_host,
+                         float *score_host, int *steps_host, int *done_host)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!state) return q8_fail(ctx, Q8_ERR_NULL, "q8_beam_result: NULL state");
+    if (max_steps <= 0) return q8_fail(ctx, Q8_ERR_SHAPE, "max_steps must be positive");
+    return q8i_beam_read(ctx, state, max_steps, tokens_host, len_host, score_host, steps_host, done_host);
+}
+
+namespace {
+struct TranslateBufs {
+    size_t X, enc_h, P, y, s0, s1, cv, lp, idx, tok, state, total;
+};
+TranslateBufs translate_layout(const q8_model *m, int l, int beam, int k, int max_steps)
+{
+    const size_t E = m->E, H = m->dec.r.Wh.cols, C = m->dec.q.Wx.cols, A = m->dec.att_U.rows;
+    TranslateBufs b;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += up256(bytes); return at; };
+    b.X = take((size_t)l * E * 4); b.enc_h = take((size_t)l * C * 4); b.P = take((size_t)l * A * 4);
+    b.y = take((size_t)beam * E * 4); b.s0 = take((size_t)beam * H * 4); b.s1 = take((size_t)beam * H * 4);
+    b.cv = take((size_t)beam * C * 4); b.lp = take((size_t)beam * k * 4); b.idx = take((size_t)beam * k * 4);
+    b.tok = take((size_t)l * 4);
+    b.state = take(q8i_beam_state_bytes(max_steps));
+    b.total = o;
+    return b;
+}
+}  // namespace
+
+size_t q8_translate_bytes(const q8_model *m, int max_l, int beam, int k, int max_steps)
+{
+    if (!m || max_l < 1 || beam < 1 || k < 1 || max_steps < 1) return 0;
+    return translate_layout(m, max_l, beam, k, max_steps).total;
+}
+
+q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens, int l, int beam, int k,
+                       int max_steps, int32_t *tokens_host, int *len_host, float *score_host, int *steps_host)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!m || !src_tokens || !m->E_src || !m->E_tgt) return q8_fail(ctx, Q8_ERR_NULL, "q8_translate: NULL argument");
+    TRY(check_gru(ctx, &m->enc_fwd, "enc_fwd"));
+    TRY(check_gru(ctx, &m->dec.r, "dec.r"));
+    TRY(check_gru(ctx, &m->dec.q, "dec.q"));
+    TRY(check_mat(ctx, &m->att_W, "att_W"));
+    TRY(check_mat(ctx, &m->dec.att_U, "att_U"));
+    const int E = m->E, H = m->dec.r.Wh.cols, C = m->dec.q.Wx.cols, A = m->dec.att_U.rows;
+    if (l <= 0 || l > kMaxL) return q8_fail(ctx, Q8_ERR_SHAPE, "l = %d outside [1, %d]", l, kMaxL);
+    if (beam <= 0 || beam > Q8_MAX_BEAM || k < beam || k > kMaxK || max_steps <= 0)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "need 1 <= beam <= %d, beam <= k <= %d, max_steps > 0", Q8_MAX_BEAM, kMaxK);
+    if (m->enc_fwd.Wx.cols != E || m->dec.r.Wx.cols != E || 2 * m->enc_fwd.Wh.cols != C || m->att_W.cols != C ||
+        m->att_W.rows != A || m->enc_fwd.Wh.cols != H)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "q8_translate: model dimensions are inconsistent");
+    if (ctx->ws_reserved_top) return q8_fail(ctx, Q8_ERR_WORKSPACE, "q8_translate is not re-entrant");
+    const TranslateBufs b = translate_layout(m, l, beam, k, max_steps);
+    if (b.total + Q8_WS_HEADER > ctx->ws_bytes) return q8_fail(ctx, Q8_ERR_WORKSPACE, "q8_translate: workspace too small");
+    char *top = ctx->ws + ((ctx->ws_bytes - b.total) & ~(size_t)255);
+    float *X = (float *)(top + b.X), *enc_h = (float *)(top + b.enc_h), *P = (float *)(top + b.P);
+    float *y = (float *)(top + b.y), *s[2] = {(float *)(top + b.s0), (float *)(top + b.s1)};
+    float *cv = (float *)(top + b.cv), *lp = (float *)(top + b.lp);
+    int32_t *idx = (int32_t *)(top + b.idx);
+    void *state = top + b.state;
+    ctx->ws_reserved_top = ctx->ws_bytes - (size_t)(top - ctx->ws);
+
+    q8_status st = q8i_gather_rows(ctx, m->E_src, src_tokens, l, E, X);                        // x_i of Eq. 1
+    if (!st) st = q8_encode(ctx, &m->enc_fwd, &m->enc_bwd, X, l, enc_h);                       // Eq. 1
+    if (!st) st = q8_gemm_narrow(ctx, &m->att_W, enc_h, l, C, m->att_b, P, A, nullptr);        // w(h_i) of Eq. 6
+    // initial decoder state: the backward encoder state at the first source position
+    if (!st) st = q8i_beam_init(ctx, state, beam, max_steps, enc_h, m->E_tgt, E, H, y, s[0]);
+    int cur = 0, done = 0;
+    for (int t = 0; t < max_steps && !st && !done; ++t) {
+        st = cgru_decoder_step_q8(ctx, &m->dec, P, enc_h, l, y, s[cur], beam, s[cur ^ 1], cv, nullptr, nullptr, nullptr);
+        if (!st) st = output_logits_q8(ctx, &m->ro, &m->W_out, m->b_out, s[cur ^ 1], y, cv, nullptr, beam, k,
+                                       nullptr, nullptr, lp, idx, nullptr, nullptr);
+        // the update gathers the surviving states from s[cur ^ 1] into s[cur]
+        if (!st) st = q8i_beam_update(ctx, state, lp, idx, beam, k, s[cur ^ 1], H, m->E_tgt, E, y, s[cur]);
+        if (!st && (t % 8 == 7))
+            st = q8i_beam_read(ctx, state, max_steps, nullptr, nullptr, nullptr, nullptr, &done);
+    }
+    if (!st) st = q8i_beam_read(ctx, state, max_steps, tokens_host, len_host, score_host, steps_host, nullptr);
+    ctx->ws_reserved_top = 0;
+    return st;
 }
 
 }  // extern "C"

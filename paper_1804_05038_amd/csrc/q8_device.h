@@ -299,6 +299,8 @@ __device__ __forceinline__ void x_load(XRegs<N, CH> &R, const float *__restrict_
             R.v[j][t] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (j < n && k < K) R.v[j][t] = *(const float4 *)(X + (size_t)j * ldx + k);
         }
+    // loads return in issue order: nothing issued later may be moved ahead of these
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 // Wave maxima of N independent values, the cross-lane steps of all N interleaved so that

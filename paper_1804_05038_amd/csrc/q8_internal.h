@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
 
 #include "q8nmt.h"
 #ifdef __HIPCC__
@@ -12,6 +14,7 @@
 #endif
 
 // Workspace header: arrival counters [0, 2048), scratch slots (max bits, scale) at 2048.
+#define Q8_MAX_BEAM 8
 #define Q8_WS_HEADER 4096
 #define Q8_WS_SCRATCH_SLOT 2048
 
@@ -23,6 +26,9 @@ struct q8_ctx {
     // kernel timing (q8_profile_begin / q8_profile_end): event pairs attached to dispatches
     hipEvent_t *prof_ev;
     int prof_cap, prof_n;
+    // bytes at the top of the workspace held by a composite call (q8_translate) while it
+    // issues other calls, which carve from the bottom
+    size_t ws_reserved_top;
 };
 
 static inline q8_status q8_fail(q8_ctx *ctx, q8_status code, const char *fmt, ...)
@@ -74,3 +80,12 @@ q8_status q8i_launch_check(q8_ctx *ctx, const char *what);
 q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const float *T, int ldt, int n, int k,
                      float *logits, float *lse, float *topk_logp, int32_t *topk_idx, const q8_taps *taps,
                      float *part_max, double *part_sum);
+
+size_t q8i_beam_state_bytes(int max_steps);
+q8_status q8i_gather_rows(q8_ctx *ctx, const float *table, const int *idx, int n, int dim, float *out);
+q8_status q8i_beam_init(q8_ctx *ctx, void *state, int beam, int max_steps, const float *s0, const float *E_tgt, int E,
+                        int H, float *y_emb, float *s);
+q8_status q8i_beam_update(q8_ctx *ctx, void *state, const float *topk_logp, const int *topk_idx, int n, int k,
+                          const float *s_step, int H, const float *E_tgt, int E, float *y_emb, float *s_next);
+q8_status q8i_beam_read(q8_ctx *ctx, const void *state, int max_steps, int32_t *tokens_host, int *len_host,
+                        float *score_host, int *steps_host, int *done_host);

@@ -15,8 +15,8 @@ struct OutArgs {
     const int8_t *W;
     const float *T, *bias;
     float *logits;          // [n x ldl], always written
-    float *part_max;        // [tiles x n]
-    double *part_sum;       // [tiles x n]: sum of exp(logit - part_max)
+    float *part_max;        // [n x tiles]
+    double *part_sum;       // [n x tiles]: sum of exp(logit - part_max)
     q8_taps taps;
     int V, K, ld, ldt, n, ldl, ntiles;
     float w_scale;
@@ -117,8 +117,8 @@ __global__ __launch_bounds__(256) void out_logits_kernel(OutArgs a)
         sd += __shfl_xor(sd, 16, 64);
         sd += __shfl_xor(sd, 32, 64);
         if (i < n && g == 0) {
-            a.part_max[(size_t)tile * n + i] = m;
-            a.part_sum[(size_t)tile * n + i] = sd;
+            a.part_max[(size_t)i * a.ntiles + tile] = m;
+            a.part_sum[(size_t)i * a.ntiles + tile] = sd;
         }
         acc = (v4i){0, 0, 0, 0};
     };
@@ -175,8 +175,8 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
         pm[t] = -INFINITY;
         ps[t] = 0.0;
         if (tile < ntiles) {
-            pm[t] = a.part_max[(size_t)tile * n + j];
-            ps[t] = a.part_sum[(size_t)tile * n + j];
+            pm[t] = a.part_max[(size_t)j * ntiles + tile];
+            ps[t] = a.part_sum[(size_t)j * ntiles + tile];
         }
     }
     float bm = -INFINITY;

@@ -1,0 +1,53 @@
+"""CPU checks of the boundary: the library loads without a GPU, exports every function that
+include/q8nmt.h declares, and its pure-host helpers behave."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "q8nmt.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_1804_05038_amd as q
+    if not os.path.exists(q.LIB_PATH):
+        from paper_1804_05038_amd import build
+        build.build()
+    return q.load_library()
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    names = re.findall(r"^\s*(?:q8_status|size_t|const char \*)\s*\*?\s*(\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_header_declares_the_north_star_entry_points():
+    names = declared_functions()
+    for f in ("q8_quantize_matrix", "q8_gemv", "q8_gemm_narrow", "gru_step_q8", "cgru_decoder_step_q8",
+              "output_logits_q8", "q8_encode", "q8_beam_update", "q8_translate", "q8_create", "q8_destroy"):
+        assert f in names
+
+
+def test_library_exports_every_declared_function(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_host_side_helpers(lib):
+    import paper_1804_05038_amd as q
+    small, big = q.q8_workspace_bytes(1, 1, 16, 16), q.q8_workspace_bytes(8, 64, 65536, 2048)
+    assert 4096 < small < big < 1 << 30
+    assert q.q8_beam_state_bytes(100) > q.q8_beam_state_bytes(10) > 0
+    # a NULL context or output is an error code, not a crash, and nothing is launched
+    out = ctypes.c_void_p()
+    assert lib.q8_create(None, None, None, 0) == 1
+    assert lib.q8_create(ctypes.byref(out), None, None, 0) == 1 and out.value is None
+    assert lib.q8_create(ctypes.byref(out), None, ctypes.c_void_p(4096 + 8), 1 << 20) == 3      # misaligned workspace
+    assert lib.q8_create(ctypes.byref(out), None, ctypes.c_void_p(4096), 16) == 4               # too small
+    assert lib.q8_destroy(None) == 1
+    assert lib.q8_gemv(None, None, None, None, None, None) == 1
+    assert lib.q8_last_error(None) == b"NULL context"

@@ -1,0 +1,89 @@
+"""GPU parity: q8_beam_* and q8_translate (encoder, attention pre-computation, decoder steps,
+output layer and beam search chained on the device) against the oracle's translate."""
+import numpy as np
+import pytest
+import torch
+
+from parity import assert_close, assert_same, np_
+from workloads import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def q():
+    import paper_1804_05038_amd as q
+    return q
+
+
+@pytest.fixture(scope="module")
+def ctx(q):
+    return q.Context()
+
+
+def _check_sentence(q, ctx, m_gpu, m_ref, src, beam, k, max_steps):
+    toks, score, steps = q.q8_translate(ctx, m_gpu, src, beam=beam, k=k, max_steps=max_steps)
+    r_toks, r_score, r_steps = m_ref.translate(src, beam=beam, topk=k, max_steps=max_steps)
+    assert toks.tolist() == r_toks.tolist(), (src.tolist(), toks.tolist(), r_toks.tolist())
+    assert steps == r_steps
+    assert abs(float(score) - float(r_score)) <= 1e-5 * max(1.0, abs(float(r_score)))
+    return len(toks), steps
+
+
+@pytest.mark.parametrize("V,E,H,A,R,beam,k", [(13, 16, 24, 20, 12, 1, 4), (13, 16, 24, 20, 12, 5, 6),
+                                              (50, 32, 48, 40, 24, 3, 5), (200, 64, 64, 32, 48, 5, 12),
+                                              (7, 8, 8, 8, 8, 5, 7), (40, 36, 40, 28, 20, 8, 12)])
+def test_translate_small_models(q, ctx, oracle, V, E, H, A, R, beam, k):
+    """Small vocabularies make the end token likely: hypotheses finish, the beam shrinks, searches end early."""
+    p = synth.full_model(seed=V + beam, V=V, E=E, H=H, A=A, R=R, w_std=0.3, b_std=0.1)
+    p["out.b"][0] += 1.5                 # make the end token frequent enough to finish hypotheses
+    m_ref = oracle.OracleModel(p)
+    m_gpu = q.Model.from_params(ctx, p)
+    rng = np.random.default_rng(V)
+    finished = 0
+    for i in range(6):
+        src = rng.integers(1, V, size=int(rng.integers(1, 12))).astype(np.int32)
+        n, steps = _check_sentence(q, ctx, m_gpu, m_ref, src, beam, k, max_steps=15)
+        finished += n < steps            # the result is a hypothesis that ended before the last step
+    assert finished > 0 or V > 100       # the finishing path was exercised
+
+
+def test_translate_full_size_model(q, ctx, oracle):
+    """The benchmark's model (embedding 512, hidden 1024, vocabulary 50000), beam 5, a few steps."""
+    p = synth.full_model(seed=4)
+    m_ref = oracle.OracleModel(p)
+    m_gpu = q.Model.from_params(ctx, p)
+    src = synth.sentences(seed=4, n=3, V=50000, min_len=10, max_len=14)[0]
+    _check_sentence(q, ctx, m_gpu, m_ref, src, beam=5, k=12, max_steps=6)
+    _check_sentence(q, ctx, m_gpu, m_ref, src[:3], beam=1, k=12, max_steps=4)
+
+
+def test_beam_update_rules(q, ctx):
+    """Hand-made top-k tables: ordering by (score, parent, token), finishing on token 0, dead slots."""
+    n, k, E, H, T = 4, 4, 8, 8, 6
+    E_tgt = ctx.f32(np.arange(10 * E, dtype=np.float32).reshape(10, E))
+    s0 = ctx.f32(np.full(H, 7.0, np.float32))
+    state = torch.zeros(q.q8_beam_state_bytes(T), dtype=torch.uint8, device=ctx.device)
+    y, s, s_next = ctx.empty(n, E), ctx.empty(n, H), ctx.empty(n, H)
+    q.q8_beam_init(ctx, state, n, T, s0, E_tgt, y, s)
+    assert (np_(y) == np_(E_tgt)[0]).all() and (np_(s) == 7.0).all()
+    # step 0: one live hypothesis; candidates (logp, token): equal scores tie-break on token id
+    lp = ctx.f32(np.array([[-1.0, -1.0, -2.0, -3.0]] + [[-0.1] * 4] * 3, np.float32))
+    ix = torch.tensor([[5, 3, 0, 9]] + [[1, 2, 3, 4]] * 3, dtype=torch.int32, device=ctx.device)
+    s_step = ctx.f32(np.arange(n * H, dtype=np.float32).reshape(n, H))
+    q.q8_beam_update(ctx, state, lp, ix, s_step, E_tgt, y, s_next)
+    toks, score, steps, done = q.q8_beam_result(ctx, state, T)
+    # kept: token 3 (-1), token 5 (-1), token 0 (-2, finishes), token 9 (-3); dead slots ignored
+    assert steps == 1 and not done
+    assert toks.tolist() == [] and score == np.float32(-2.0)            # the finished hypothesis is the result
+    assert np_(y)[:3].tolist() == np_(E_tgt)[[3, 5, 9]].tolist()
+    assert (np_(s_next)[:3] == np_(s_step)[0]).all()                      # all survivors descend from slot 0
+    # step 1: three live, beam has 3 slots left; parent order breaks ties between equal scores
+    lp = ctx.f32(np.array([[-1.0, -5, -6, -7], [-1.0, -5, -6, -7], [0.5, -5, -6, -7], [9, 9, 9, 9]], np.float32))
+    ix = torch.tensor([[4, 1, 2, 3], [4, 1, 2, 3], [0, 1, 2, 3], [1, 1, 1, 1]], dtype=torch.int32, device=ctx.device)
+    q.q8_beam_update(ctx, state, lp, ix, s_step, E_tgt, y, s)
+    toks, score, steps, done = q.q8_beam_result(ctx, state, T)
+    # scores: parent0 -2, parent1 -2, parent2 -2.5 (token 0: finishes, but -2.5 < -2 keeps the old result)
+    assert steps == 2 and not done and toks.tolist() == [] and score == np.float32(-2.0)
+    assert np_(y)[:2].tolist() == np_(E_tgt)[[4, 4]].tolist()
+    assert (np_(s)[0] == np_(s_step)[0]).all() and (np_(s)[1] == np_(s_step)[1]).all()
