@@ -352,9 +352,11 @@ def q8_beam_state_bytes(max_steps):
     return load_library().q8_beam_state_bytes(max_steps)
 
 
-def q8_beam_init(ctx, state, beam, max_steps, s0, E_tgt, y_emb, s):
-    ctx.check(ctx.lib.q8_beam_init(ctx.handle, _ptr(state), beam, max_steps, _ptr(s0), _ptr(E_tgt), E_tgt.shape[1],
-                                   s.shape[1], _ptr(y_emb), _ptr(s)))
+def q8_beam_init(ctx, state, beam, max_steps, s0, E_tgt, y_emb, s, bind=False):
+    args = (ctx.handle, _ptr(state), beam, max_steps, _ptr(s0), _ptr(E_tgt), E_tgt.shape[1], s.shape[1], _ptr(y_emb), _ptr(s))
+    if bind:
+        return _Bound(ctx, ctx.lib.q8_beam_init, args, {"keep": (state, s0, E_tgt, y_emb, s)})
+    ctx.check(ctx.lib.q8_beam_init(*args))
 
 
 def q8_beam_update(ctx, state, topk_logp, topk_idx, s_step, E_tgt, y_emb, s_next, bind=False):
