@@ -62,11 +62,14 @@ enum {
 
 typedef struct q8_ctx q8_ctx;
 
-/* An int8 weight matrix: device data, host-side scale (known at load time). */
+/* An int8 weight matrix: device data, host-side scale (known at load time).  `tiles` is
+ * an optional second copy of the same codes in the matrix-core streaming order made by
+ * q8_pack_tiles (NULL = none); output_logits_q8 reads it instead of `data` when present. */
 typedef struct {
     const int8_t *data;
     int rows, cols, ld;
     float scale;
+    const int8_t *tiles;
 } q8_mat;
 
 typedef struct {
@@ -113,6 +116,16 @@ const char *q8_last_error(const q8_ctx *ctx);
  * to *scale_out_host.  Synchronous: waits for the stream. */
 q8_status q8_quantize_matrix(q8_ctx *ctx, const float *W, int rows, int cols, int ld_in,
                              int8_t *Wq_out, int ld_out, float *scale_out_host);
+
+/* Load-time re-ordering of a quantized matrix for the vocabulary layer (a layout choice of
+ * this library, not an operation of the paper): rows are grouped in tiles of 16 and each
+ * 16 x 64-byte block is stored as one contiguous KiB in the lane order of
+ * v_mfma_i32_16x16x64_i8's A operand (lane = 16 * (k / 16 % 4) + row % 16, 16 bytes per lane),
+ * so that every wave-wide load of the streaming pass is one contiguous KiB.  Rows past
+ * `rows` in the last tile are zero.  Requires ld % 64 == 0; tiles_out holds
+ * q8_tiles_bytes(rows, ld) bytes, 16-byte aligned.  Enqueued on the stream. */
+size_t q8_tiles_bytes(int rows, int ld);
+q8_status q8_pack_tiles(q8_ctx *ctx, const q8_mat *W, int8_t *tiles_out);
 
 /* Section 3, matrix x vector: y[rows] = (float)(Wq . quantize(x)) * (s_w * s_x) + bias.
  * bias [rows] may be NULL.  One launch; x is quantized inside the kernel. */

@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 
 __all__ = ["Q8Error", "Context", "Mat", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
-           "q8_quantize_matrix", "q8_gemv", "q8_gemm_narrow", "gru_step_q8", "cgru_decoder_step_q8",
+           "q8_quantize_matrix", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "gru_step_q8", "cgru_decoder_step_q8",
            "output_logits_q8", "q8_encode", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
            "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "LIB_PATH"]
 LIB_PATH = _LIB_PATH
@@ -28,7 +28,8 @@ class Q8Error(RuntimeError):
 
 
 class _Mat(C.Structure):
-    _fields_ = [("data", C.c_void_p), ("rows", C.c_int), ("cols", C.c_int), ("ld", C.c_int), ("scale", C.c_float)]
+    _fields_ = [("data", C.c_void_p), ("rows", C.c_int), ("cols", C.c_int), ("ld", C.c_int), ("scale", C.c_float),
+                ("tiles", C.c_void_p)]
 
 
 class _Taps(C.Structure):
@@ -72,6 +73,9 @@ def load_library():
         lib.q8_destroy.argtypes = [C.c_void_p]
         vp, ci = C.c_void_p, C.c_int
         lib.q8_quantize_matrix.argtypes = [vp, vp, ci, ci, ci, vp, ci, C.POINTER(C.c_float)]
+        lib.q8_tiles_bytes.restype = C.c_size_t
+        lib.q8_tiles_bytes.argtypes = [ci, ci]
+        lib.q8_pack_tiles.argtypes = [vp, C.POINTER(_Mat), vp]
         lib.q8_gemv.argtypes = [vp, C.POINTER(_Mat), vp, vp, vp, C.POINTER(_Taps)]
         lib.q8_gemm_narrow.argtypes = [vp, C.POINTER(_Mat), vp, ci, ci, vp, vp, ci, C.POINTER(_Taps)]
         lib.gru_step_q8.argtypes = [vp, C.POINTER(_Gru), vp, vp, ci, vp, C.POINTER(_Taps)]
@@ -150,12 +154,13 @@ class Context:
 class Mat:
     """q8_mat: int8 device matrix [rows x ld] plus its host-side scale."""
 
-    def __init__(self, data, cols, scale):
+    def __init__(self, data, cols, scale, tiles=None):
         self.data = data
         self.rows, self.ld = data.shape
         self.cols = cols
         self.scale = float(scale)
-        self.c = _Mat(data.data_ptr(), self.rows, cols, self.ld, self.scale)
+        self.tiles = tiles
+        self.c = _Mat(data.data_ptr(), self.rows, cols, self.ld, self.scale, tiles.data_ptr() if tiles is not None else None)
 
 
 class _Bound:
@@ -192,6 +197,14 @@ def q8_quantize_matrix(ctx, W, ld_out=None):
     scale = C.c_float()
     ctx.check(ctx.lib.q8_quantize_matrix(ctx.handle, _ptr(W), rows, cols, W.stride(0), _ptr(Wq), ld_out, C.byref(scale)))
     return Mat(Wq, cols, scale.value)
+
+
+def q8_pack_tiles(ctx, W):
+    """Returns a Mat sharing W's codes plus their copy in the matrix-core streaming order."""
+    nbytes = ctx.lib.q8_tiles_bytes(W.rows, W.ld)
+    tiles = ctx.empty(nbytes, dtype=torch.int8)
+    ctx.check(ctx.lib.q8_pack_tiles(ctx.handle, C.byref(W.c), _ptr(tiles)))
+    return Mat(W.data, W.cols, W.scale, tiles)
 
 
 def q8_gemv(ctx, W, x, bias=None, y=None, taps=False):
@@ -329,8 +342,11 @@ class Model:
         gru = lambda pre: GruWeights(mat(pre + ".Wx"), mat(pre + ".Wh"), ctx.f32(p[pre + ".bx"]), ctx.f32(p[pre + ".bh"]))
         dec = CgruWeights(gru("dec_r"), mat("att.U"), ctx.f32(p["att.v"]), gru("dec_q"))
         ro = ReadoutWeights(mat("ro.Ws"), mat("ro.Wy"), mat("ro.Wc"), ctx.f32(p["ro.b"]))
+        out_W = mat("out.W")
+        if out_W.ld % 64 == 0:          # the streaming order of the vocabulary layer needs whole 64-byte k steps
+            out_W = q8_pack_tiles(ctx, out_W)
         return cls(ctx.f32(p["E_src"]), ctx.f32(p["E_tgt"]), gru("enc_fwd"), gru("enc_bwd"), mat("att.W"),
-                   ctx.f32(p["att.b"]), dec, ro, mat("out.W"), ctx.f32(p["out.b"]))
+                   ctx.f32(p["att.b"]), dec, ro, out_W, ctx.f32(p["out.b"]))
 
 
 def q8_translate_bytes(model, max_l, beam, k, max_steps):

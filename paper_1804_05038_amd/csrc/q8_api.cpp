@@ -171,6 +171,22 @@ q8_status q8_quantize_matrix(q8_ctx *ctx, const float *W, int rows, int cols, in
     return q8i_quantize_matrix(ctx, W, rows, cols, ld_in, Wq_out, ld_out, scale_out_host);
 }
 
+size_t q8_tiles_bytes(int rows, int ld)
+{
+    if (rows <= 0 || ld <= 0) return 0;
+    return q8i_tiles_bytes(rows, ld);
+}
+
+q8_status q8_pack_tiles(q8_ctx *ctx, const q8_mat *W, int8_t *tiles_out)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    TRY(check_mat(ctx, W, "W"));
+    if (!tiles_out) return q8_fail(ctx, Q8_ERR_NULL, "tiles_out: NULL");
+    if (W->ld % 64 != 0) return q8_fail(ctx, Q8_ERR_ALIGN, "q8_pack_tiles needs ld %% 64 == 0");
+    if (!aligned16(tiles_out)) return q8_fail(ctx, Q8_ERR_ALIGN, "tiles_out needs 16-byte alignment");
+    return q8i_pack_tiles(ctx, W, tiles_out);
+}
+
 q8_status q8_gemm_narrow(q8_ctx *ctx, const q8_mat *W, const float *X, int n, int ldx, const float *bias, float *Y,
                          int ldy, const q8_taps *taps)
 {
@@ -275,6 +291,7 @@ q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_m
     if (V > q8i_out_max_rows()) return q8_fail(ctx, Q8_ERR_SHAPE, "W_out: more than %d rows", q8i_out_max_rows());
     if (W_out->ld > 4096) return q8_fail(ctx, Q8_ERR_SHAPE, "W_out: ld above 4096");
     if (R % 4) return q8_fail(ctx, Q8_ERR_ALIGN, "R must be a multiple of 4");
+    if (W_out->tiles && !aligned16(W_out->tiles)) return q8_fail(ctx, Q8_ERR_ALIGN, "W_out.tiles needs 16-byte alignment");
     if (!topk_logp || !topk_idx) return q8_fail(ctx, Q8_ERR_NULL, "top-k outputs: NULL");
     Carver cv(ctx);
     const float *T = t_in;

@@ -341,12 +341,15 @@ __device__ __forceinline__ void x_finish(const XRegs<N, CH> &R, int n, int ld, i
             m[j] = fmaxf(m[j], fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
         }
     }
+    Q8_STAMP(20);
     wave_max_multi<N>(m);
+    Q8_STAMP(21);
     if (lane == 0) {
 #pragma unroll
         for (int j = 0; j < N; ++j) s_red[j * 4 + wave] = m[j];
     }
     __syncthreads();
+    Q8_STAMP(22);
     float scale = 1.0f, inv = 0.0f;
     if (lane < N) {
         const float mm = fmaxf(fmaxf(s_red[lane * 4], s_red[lane * 4 + 1]), fmaxf(s_red[lane * 4 + 2], s_red[lane * 4 + 3]));
@@ -365,6 +368,7 @@ __device__ __forceinline__ void x_finish(const XRegs<N, CH> &R, int n, int ld, i
             }
         }
     }
+    Q8_STAMP(23);
     __syncthreads();
 }
 

@@ -75,6 +75,8 @@ q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, 
 q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,
                       float *t_out, const q8_taps *taps3);
 int q8i_out_tiles(int V);
+size_t q8i_tiles_bytes(int rows, int ld);
+q8_status q8i_pack_tiles(q8_ctx *ctx, const q8_mat *W, int8_t *tiles);
 int q8i_out_max_rows(void);
 q8_status q8i_launch_check(q8_ctx *ctx, const char *what);
 q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const float *T, int ldt, int n, int k,

@@ -11,8 +11,26 @@
 #define OUT_BLOCKS 512               // blocks of 4 waves; tile t belongs to block t % OUT_BLOCKS
 #define OUT_MAX_TILES 4096           // 65536 vocabulary rows
 
+// tiles[((t * ksteps + s) * 64 + lane) * 16 ..] = W[(16 t + lane % 16) * ld + 64 s + 16 * (lane / 16) ..], 16 bytes
+__global__ __launch_bounds__(256) void pack_tiles_kernel(const int8_t *__restrict__ W, int rows, int ld,
+                                                         int8_t *__restrict__ tiles, size_t chunks)
+{
+    const int ksteps = ld / 64;
+    for (size_t o = (size_t)blockIdx.x * blockDim.x + threadIdx.x; o < chunks; o += (size_t)gridDim.x * blockDim.x) {
+        const int lane = (int)(o & 63);
+        const size_t blk = o >> 6;
+        const int s = (int)(blk % ksteps);
+        const size_t t = blk / ksteps;
+        const size_t row = t * 16 + (lane & 15);
+        v4i v = (v4i){0, 0, 0, 0};
+        if (row < (size_t)rows) v = *(const v4i *)(W + row * ld + 64 * s + 16 * (lane >> 4));
+        *(v4i *)(tiles + o * 16) = v;
+    }
+}
+
 struct OutArgs {
     const int8_t *W;
+    const int8_t *tiles;    // matrix-core streaming order, or NULL
     const float *T, *bias;
     float *logits;          // [n x ldl], always written
     float *part_max;        // [n x tiles]
@@ -29,7 +47,7 @@ struct OutArgs {
 // round-robin to blocks and, within a block, to waves, so every CU streams the same
 // number of bytes.  Work is cut into items of 16 rows x 512 k; two items are in flight
 // per wave.  Each tile's (max, sum of exp) per hypothesis is reduced in registers.
-template <int CH>
+template <int CH, bool PACKED>
 __global__ __launch_bounds__(256) void out_logits_kernel(OutArgs a)
 {
     extern __shared__ __align__(16) int8_t smem[];
@@ -48,22 +66,39 @@ __global__ __launch_bounds__(256) void out_logits_kernel(OutArgs a)
     Q8_STAMP(0);
     XRegs<8, CH> xr;
     x_load<8, CH>(xr, a.T, n, a.K, a.ldt);
+    Q8_STAMP(4);
 
     auto load_item = [&](int it, v4i (&av)[8]) {
         const int q = it / kchunks, kc = it - q * kchunks;
-        const int row = (tile0 + q * tstride) * OUT_TILE + i;
-        const int8_t *wp = a.W + (size_t)row * ld + kc * 512 + 16 * g;
+        const int tile = tile0 + q * tstride;
+        if (PACKED) {
+            // one contiguous KiB per wave-wide load
+            const int8_t *wp = a.tiles + ((size_t)tile * (ld >> 6) + kc * 8) * 1024 + lane * 16;
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            av[s] = (v4i){0, 0, 0, 0};
-            if (it < items && row < a.V && kc * 512 + 64 * s + 16 * g < ld) av[s] = *(const v4i *)(wp + 64 * s);
+            for (int s = 0; s < 8; ++s) {
+                av[s] = (v4i){0, 0, 0, 0};
+                if (it < items && kc * 512 + 64 * s < ld) av[s] = *(const v4i *)(wp + 1024 * s);
+            }
+        } else {
+            const int row = tile * OUT_TILE + i;
+            const int8_t *wp = a.W + (size_t)row * ld + kc * 512 + 16 * g;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                av[s] = (v4i){0, 0, 0, 0};
+                if (it < items && row < a.V && kc * 512 + 64 * s + 16 * g < ld) av[s] = *(const v4i *)(wp + 64 * s);
+            }
         }
     };
     v4i bufA[8], bufB[8];
+#ifndef Q8_EXPERIMENT_X_FIRST
     load_item(0, bufA);
     load_item(1, bufB);
-
+#endif
     x_finish<8, CH>(xr, n, ld, smem, s_scale, s_red);
+#ifdef Q8_EXPERIMENT_X_FIRST
+    load_item(0, bufA);
+    load_item(1, bufB);
+#endif
     Q8_STAMP(1);
     if (blockIdx.x == 0) {
         if (a.taps.xq)
@@ -288,17 +323,35 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
 int q8i_out_tiles(int V) { return (V + OUT_TILE - 1) / OUT_TILE; }
 int q8i_out_max_rows(void) { return OUT_MAX_TILES * OUT_TILE; }
 
-template <int CH>
-static void launch_out(q8_ctx *ctx, const OutArgs &a, int nblk, size_t smem)
+template <int CH, bool PACKED>
+static void launch_out2(q8_ctx *ctx, const OutArgs &a, int nblk, size_t smem)
 {
     if (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) {
         // timed dispatch: the two events take the kernel's own begin and end timestamps
         hipEvent_t e0 = ctx->prof_ev[2 * ctx->prof_n], e1 = ctx->prof_ev[2 * ctx->prof_n + 1];
         ++ctx->prof_n;
-        hipExtLaunchKernelGGL(out_logits_kernel<CH>, dim3(nblk), dim3(256), smem, ctx->stream, e0, e1, 0, a);
+        hipExtLaunchKernelGGL((out_logits_kernel<CH, PACKED>), dim3(nblk), dim3(256), smem, ctx->stream, e0, e1, 0, a);
     } else {
-        hipLaunchKernelGGL(out_logits_kernel<CH>, dim3(nblk), dim3(256), smem, ctx->stream, a);
+        hipLaunchKernelGGL((out_logits_kernel<CH, PACKED>), dim3(nblk), dim3(256), smem, ctx->stream, a);
     }
+}
+
+template <int CH>
+static void launch_out(q8_ctx *ctx, const OutArgs &a, int nblk, size_t smem)
+{
+    if (a.tiles) launch_out2<CH, true>(ctx, a, nblk, smem);
+    else launch_out2<CH, false>(ctx, a, nblk, smem);
+}
+
+size_t q8i_tiles_bytes(int rows, int ld) { return (size_t)q8i_out_tiles(rows) * OUT_TILE * (size_t)ld; }
+
+q8_status q8i_pack_tiles(q8_ctx *ctx, const q8_mat *W, int8_t *tiles)
+{
+    const size_t chunks = q8i_tiles_bytes(W->rows, W->ld) / 16;
+    int blocks = (int)((chunks + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(pack_tiles_kernel, dim3(blocks), dim3(256), 0, ctx->stream, W->data, W->rows, W->ld, tiles, chunks);
+    return q8i_launch_check(ctx, "pack_tiles");
 }
 
 q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const float *T, int ldt, int n, int k,
@@ -306,7 +359,7 @@ q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const floa
                      float *part_max, double *part_sum)
 {
     OutArgs a;
-    a.W = W->data; a.T = T; a.bias = bias; a.logits = logits;
+    a.W = W->data; a.tiles = (W->ld % 64 == 0) ? W->tiles : nullptr; a.T = T; a.bias = bias; a.logits = logits;
     a.part_max = part_max; a.part_sum = part_sum;
     q8_taps none = {nullptr, nullptr, nullptr};
     a.taps = taps ? *taps : none;

@@ -115,12 +115,19 @@ def test_cgru_uniform_attention_special_case(q, ctx, oracle):
 
 # ---------------------------------------------------------------- output layer ----
 
+@pytest.mark.parametrize("packed", [False, True])
 @pytest.mark.parametrize("V,R,n,k", [(50000, 512, 5, 12), (50000, 512, 1, 12), (300, 64, 3, 12), (129, 48, 8, 16),
-                                     (1000, 512, 2, 1), (12, 16, 2, 12)])
-def test_output_layer_given_t(q, ctx, oracle, V, R, n, k):
+                                     (1000, 512, 2, 1), (12, 16, 2, 12), (777, 1024, 4, 12), (33658, 640, 6, 12)])
+def test_output_layer_given_t(q, ctx, oracle, V, R, n, k, packed):
     p = synth.output_layer(seed=2, V=V, R=R, n_beam=n)
     L = oracle.QLinear(p["out.W"], p["out.b"])
     W = gpu_mat(q, ctx, p["out.W"])
+    if packed:
+        if W.ld % 64:
+            with pytest.raises(q.Q8Error):
+                q.q8_pack_tiles(ctx, W)
+            return
+        W = q.q8_pack_tiles(ctx, W)
     r = q.output_logits_q8(ctx, None, W, ctx.f32(p["out.b"]), t_in=ctx.f32(p["t"]), k=k, taps=True)
     tap = r["taps"][3]
     for j in range(n):
@@ -159,7 +166,7 @@ def test_output_layer_with_readout(q, ctx, oracle, n):
     s, y, c = (rng.standard_normal((n, d)).astype(np.float32) for d in (1024, 512, 2048))
     ro = q.ReadoutWeights(gpu_mat(q, ctx, p["ro.Ws"]), gpu_mat(q, ctx, p["ro.Wy"]), gpu_mat(q, ctx, p["ro.Wc"]),
                           ctx.f32(p["ro.b"]))
-    W = gpu_mat(q, ctx, p["out.W"])
+    W = q.q8_pack_tiles(ctx, gpu_mat(q, ctx, p["out.W"]))
     r = q.output_logits_q8(ctx, ro, W, ctx.f32(p["out.b"]), s=ctx.f32(s), y_emb=ctx.f32(y), ctx_vec=ctx.f32(c),
                            k=12, taps=True)
     T = r["taps"]
