@@ -388,6 +388,8 @@ q8_status q8_beam_update(q8_ctx *ctx, void *state, const float *topk_logp, const
     if (n_beam <= 0 || n_beam > Q8_MAX_BEAM || k < n_beam || k > kMaxK || E <= 0 || H <= 0)
         return q8_fail(ctx, Q8_ERR_SHAPE, "q8_beam_update: need 1 <= n_beam <= %d and n_beam <= k <= %d", Q8_MAX_BEAM, kMaxK);
     if (s_next == s_step) return q8_fail(ctx, Q8_ERR_SHAPE, "s_next must not alias s_step");
+    if (!aligned16(s_step) || !aligned16(s_next) || !aligned16(E_tgt) || !aligned16(y_emb))
+        return q8_fail(ctx, Q8_ERR_ALIGN, "q8_beam_update: fp32 buffers need 16-byte alignment");
     return q8i_beam_update(ctx, state, topk_logp, topk_idx, n_beam, k, s_step, H, E_tgt, E, y_emb, s_next);
 }
 

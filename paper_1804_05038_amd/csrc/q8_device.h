@@ -17,9 +17,14 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 static __device__ long long q8_trace_buf[64];
 #define Q8_STAMP(slot) do { if (threadIdx.x == 0 && blockIdx.x == (gridDim.x >> 1) && blockIdx.y == 0) q8_trace_buf[slot] = clock64(); } while (0)
 __device__ __forceinline__ void q8_trace_stamp(int slot) { q8_trace_buf[slot] = clock64(); }
-#define Q8_TRACE_READER(name) extern "C" void name(long long *host) { (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(q8_trace_buf), sizeof(long long) * 64); }
+#define Q8_TRACE_READER(name) extern "C" void name(long long *host) { (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(q8_trace_buf), sizeof(long long) * 64); } \
+    extern "C" void name##_set(const long long *host) { (void)hipMemcpyToSymbol(HIP_SYMBOL(q8_trace_buf), host, sizeof(long long) * 64); }
+#define Q8_SPAN_BEGIN() do { if (threadIdx.x == 0 && (blockIdx.x % 64 == 0 || blockIdx.x == gridDim.x - 1)) q8_trace_buf[40 + (blockIdx.x + 63) / 64] = wall_clock64(); } while (0)
+#define Q8_SPAN_END() do { if (threadIdx.x == 0 && (blockIdx.x % 64 == 0 || blockIdx.x == gridDim.x - 1)) q8_trace_buf[50 + (blockIdx.x + 63) / 64] = wall_clock64(); } while (0)
 #else
 #define Q8_STAMP(slot) do {} while (0)
+#define Q8_SPAN_BEGIN() do {} while (0)
+#define Q8_SPAN_END() do {} while (0)
 #define Q8_TRACE_READER(name)
 __device__ __forceinline__ void q8_trace_stamp(int) {}
 #endif
@@ -327,11 +332,12 @@ __device__ __forceinline__ void wave_max_multi(float (&m)[N])
 // Turns the staged vectors into int8 codes in LDS (xq[j * ld + k], bytes [K, ld) zero) and
 // scales in s_scale[j].  s_red: N * 4 floats.  Ends with a block barrier.  The two
 // divisions per vector are done once per wave, by lane j for vector j, and broadcast.
+// Thread-local max |x| of every staged vector: the first use of the loaded values.  Calling
+// this before the weight loads are issued makes the block wait for the (short) activation
+// loads alone; the rest of the quantization then overlaps the weight stream.
 template <int N, int CH>
-__device__ __forceinline__ void x_finish(const XRegs<N, CH> &R, int n, int ld, int8_t *xq, float *s_scale, float *s_red)
+__device__ __forceinline__ void x_absmax(const XRegs<N, CH> &R, float (&m)[N])
 {
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    float m[N];
 #pragma unroll
     for (int j = 0; j < N; ++j) {
         m[j] = 0.0f;
@@ -341,6 +347,26 @@ __device__ __forceinline__ void x_finish(const XRegs<N, CH> &R, int n, int ld, i
             m[j] = fmaxf(m[j], fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
         }
     }
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int N, int CH>
+__device__ __forceinline__ void x_finish_m(const XRegs<N, CH> &R, float (&m)[N], int n, int ld, int8_t *xq, float *s_scale,
+                                           float *s_red);
+
+template <int N, int CH>
+__device__ __forceinline__ void x_finish(const XRegs<N, CH> &R, int n, int ld, int8_t *xq, float *s_scale, float *s_red)
+{
+    float m[N];
+    x_absmax<N, CH>(R, m);
+    x_finish_m<N, CH>(R, m, n, ld, xq, s_scale, s_red);
+}
+
+template <int N, int CH>
+__device__ __forceinline__ void x_finish_m(const XRegs<N, CH> &R, float (&m)[N], int n, int ld, int8_t *xq, float *s_scale,
+                                           float *s_red)
+{
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     Q8_STAMP(20);
     wave_max_multi<N>(m);
     Q8_STAMP(21);

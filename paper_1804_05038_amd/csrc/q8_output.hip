@@ -8,7 +8,9 @@
 
 #define OUT_TILE 16                  // vocabulary rows per matrix-core tile = one selection group
 #define OUT_SB 16                    // tiles per super-block of the threshold search
+#ifndef OUT_BLOCKS
 #define OUT_BLOCKS 512               // blocks of 4 waves; tile t belongs to block t % OUT_BLOCKS
+#endif
 #define OUT_MAX_TILES 4096           // 65536 vocabulary rows
 
 // tiles[((t * ksteps + s) * 64 + lane) * 16 ..] = W[(16 t + lane % 16) * ld + 64 s + 16 * (lane / 16) ..], 16 bytes
@@ -47,9 +49,59 @@ struct OutArgs {
 // round-robin to blocks and, within a block, to waves, so every CU streams the same
 // number of bytes.  Work is cut into items of 16 rows x 512 k; two items are in flight
 // per wave.  Each tile's (max, sum of exp) per hypothesis is reduced in registers.
-template <int CH, bool PACKED>
-__global__ __launch_bounds__(256) void out_logits_kernel(OutArgs a)
+// The hidden vectors of all hypotheses, quantized by ONE wave (rows of at most 1024
+// columns): the wave loads every vector (KPL float4 per lane and vector), reduces max|x|
+// without leaving the wave, and writes the codes and scales to LDS.  The streaming waves
+// of the block meanwhile have their weight loads in flight and meet this wave at a barrier.
+template <int KPL>
+__device__ __forceinline__ void wave_quantize(const float *__restrict__ X, int n, int K, int ldx, int ld, int8_t *xq,
+                                              float *s_scale, int lane)
 {
+    float4 v[8][KPL];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int t = 0; t < KPL; ++t) {
+            const int k = (t * 64 + lane) * 4;
+            v[j][t] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (j < n && k < K) v[j][t] = *(const float4 *)(X + (size_t)j * ldx + k);
+        }
+    float m[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        m[j] = 0.0f;
+#pragma unroll
+        for (int t = 0; t < KPL; ++t)
+            m[j] = fmaxf(m[j], fmaxf(fmaxf(fabsf(v[j][t].x), fabsf(v[j][t].y)), fmaxf(fabsf(v[j][t].z), fabsf(v[j][t].w))));
+    }
+    wave_max_multi<8>(m);
+    float mine = 0.0f;                       // lane j owns vector j's two divisions
+#pragma unroll
+    for (int j = 0; j < 8; ++j) mine = (lane == j) ? m[j] : mine;
+    float scale, inv;
+    q8_scale_of(mine, scale, inv);
+    if (lane < 8) s_scale[lane] = scale;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        if (j < n) {
+            const float invj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(inv), j));
+#pragma unroll
+            for (int t = 0; t < KPL; ++t) {
+                const int k = (t * 64 + lane) * 4;
+                if (k < ld) *(int *)(xq + (size_t)j * ld + k) = q8_pack4(v[j][t].x, v[j][t].y, v[j][t].z, v[j][t].w, invj);
+            }
+        }
+    }
+}
+
+#define OUT_STREAM_WAVES 4
+
+// QKPL = 0: four waves, all of them quantize and stream.  QKPL = 1, 2, 4: blocks of five waves,
+// the fifth only quantizes (QKPL float4 per lane and vector; rows of at most 256 * QKPL columns).
+template <int CH, bool PACKED, int QKPL>
+__device__ __forceinline__ void out_logits_body(const OutArgs &a)
+{
+    constexpr bool QW = QKPL != 0;
     extern __shared__ __align__(16) int8_t smem[];
     __shared__ float s_scale[8];
     __shared__ float s_red[8 * 4];
@@ -57,15 +109,27 @@ __global__ __launch_bounds__(256) void out_logits_kernel(OutArgs a)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 15, g = lane >> 4;
     const int kchunks = (ld + 511) / 512;
+    Q8_SPAN_BEGIN();
+    if (QW && wave == OUT_STREAM_WAVES) {
+        wave_quantize<QW ? QKPL : 1>(a.T, n, a.K, a.ldt, ld, smem, s_scale, lane);
+        __syncthreads();
+        if (blockIdx.x == 0) {
+            if (a.taps.xq)
+                for (int e = lane; e < n * a.K; e += 64) a.taps.xq[e] = smem[(e / a.K) * ld + e % a.K];
+            if (a.taps.xscale && lane < n) a.taps.xscale[lane] = s_scale[lane];
+        }
+        return;
+    }
     // tiles of this wave: blockIdx + (wave + 4 q) * gridDim, q = 0, 1, ...
     const int tstride = 4 * gridDim.x;
     const int tile0 = blockIdx.x + wave * gridDim.x;
     const int ntw = tile0 < a.ntiles ? (a.ntiles - tile0 + tstride - 1) / tstride : 0;
     const int items = ntw * kchunks;
+    const bool bias_vec = (((uintptr_t)a.bias) & 15) == 0;
 
     Q8_STAMP(0);
-    XRegs<8, CH> xr;
-    x_load<8, CH>(xr, a.T, n, a.K, a.ldt);
+    XRegs<8, QW ? 1 : CH> xr;
+    if (!QW) x_load<8, CH>(xr, a.T, n, a.K, a.ldt);
     Q8_STAMP(4);
 
     auto load_item = [&](int it, v4i (&av)[8]) {
@@ -89,18 +153,37 @@ __global__ __launch_bounds__(256) void out_logits_kernel(OutArgs a)
             }
         }
     };
+    // wait for the hidden vectors alone, then put the whole weight stream (and the biases of
+    // the wave's first two tiles) in flight; the reduction and packing below overlap it
+    float xm[8];
+    if (!QW) x_absmax<8, QW ? 1 : CH>(xr, xm);
+    // bias of the four rows this lane finishes in the tile of item `it` (needed when the
+    // tile's last k chunk is multiplied); rows past V read as zero
+    auto load_bias = [&](int it) {
+        float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
+        const int q = it / kchunks;
+        const int row0 = (tile0 + q * tstride) * OUT_TILE + 4 * g;
+        if (a.bias && it < items && i < n) {
+            if (bias_vec && row0 + 3 < a.V) {
+                b = *(const float4 *)(a.bias + row0);
+            } else {
+                if (row0 < a.V) b.x = a.bias[row0];
+                if (row0 + 1 < a.V) b.y = a.bias[row0 + 1];
+                if (row0 + 2 < a.V) b.z = a.bias[row0 + 2];
+                if (row0 + 3 < a.V) b.w = a.bias[row0 + 3];
+            }
+        }
+        return b;
+    };
     v4i bufA[8], bufB[8];
-#ifndef Q8_EXPERIMENT_X_FIRST
     load_item(0, bufA);
     load_item(1, bufB);
-#endif
-    x_finish<8, CH>(xr, n, ld, smem, s_scale, s_red);
-#ifdef Q8_EXPERIMENT_X_FIRST
-    load_item(0, bufA);
-    load_item(1, bufB);
-#endif
+    float4 bias_cur = load_bias(0), bias_nxt = load_bias(kchunks);   // this wave's first and second tile
+    __builtin_amdgcn_sched_barrier(0);
+    if (QW) __syncthreads();                 // the quantizing wave has filled smem and s_scale
+    else x_finish_m<8, QW ? 1 : CH>(xr, xm, n, ld, smem, s_scale, s_red);
     Q8_STAMP(1);
-    if (blockIdx.x == 0) {
+    if (!QW && blockIdx.x == 0) {
         if (a.taps.xq)
             for (int e = threadIdx.x; e < n * a.K; e += blockDim.x) a.taps.xq[e] = smem[(e / a.K) * ld + e % a.K];
         if (a.taps.xscale && threadIdx.x < n) a.taps.xscale[threadIdx.x] = s_scale[threadIdx.x];
@@ -128,12 +211,16 @@ __global__ __launch_bounds__(256) void out_logits_kernel(OutArgs a)
             y[r] = -INFINITY;
             if (i < n && row0 + r < a.V) {
                 y[r] = (float)acc[r] * cj;
-                if (a.bias) y[r] = y[r] + a.bias[row0 + r];
+                if (a.bias) y[r] = y[r] + (r == 0 ? bias_cur.x : r == 1 ? bias_cur.y : r == 2 ? bias_cur.z : bias_cur.w);
                 if (a.taps.acc) a.taps.acc[(size_t)i * a.V + row0 + r] = acc[r];
             }
             m = fmaxf(m, y[r]);
         }
+#ifdef Q8_EXP_NOSTORE
+        if (i < n && y[0] == 123.456f) {
+#else
         if (i < n) {
+#endif
             if (vec_ok && row0 + 3 < a.V) {
                 *(float4 *)(a.logits + (size_t)i * a.ldl + row0) = make_float4(y[0], y[1], y[2], y[3]);
             } else {
@@ -146,16 +233,20 @@ __global__ __launch_bounds__(256) void out_logits_kernel(OutArgs a)
         m = fmaxf(m, __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(m), SWZ_XOR16)));
         m = fmaxf(m, __shfl_xor(m, 32, 64));
         double sd = 0.0;
+#ifndef Q8_EXP_NOEXP
 #pragma unroll
         for (int r = 0; r < 4; ++r)
             if (y[r] > -INFINITY) sd += (double)__expf(y[r] - m);
         sd += __shfl_xor(sd, 16, 64);
         sd += __shfl_xor(sd, 32, 64);
+#endif
         if (i < n && g == 0) {
             a.part_max[(size_t)i * a.ntiles + tile] = m;
             a.part_sum[(size_t)i * a.ntiles + tile] = sd;
         }
         acc = (v4i){0, 0, 0, 0};
+        bias_cur = bias_nxt;                       // tiles finish in order: q, q + 1, ...
+        bias_nxt = load_bias((q + 2) * kchunks);
     };
     for (int it = 0; it < items; it += 2) {
         compute_item(it, bufA);
@@ -166,6 +257,22 @@ __global__ __launch_bounds__(256) void out_logits_kernel(OutArgs a)
         }
     }
     Q8_STAMP(3);
+    Q8_SPAN_END();
+}
+
+template <int CH, bool PACKED>
+__global__ __launch_bounds__(256) void out_logits_kernel(OutArgs a)
+{
+    out_logits_body<CH, PACKED, 0>(a);
+}
+
+// Five-wave blocks.  At most 128 registers per lane (four waves per SIMD): the fifth waves of
+// two blocks land on the same SIMD, and with fewer waves per SIMD the second block of a CU
+// could not start before the first block's fifth wave has left.
+template <bool PACKED, int QKPL>
+__global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(4, 8))) void out_logits5_kernel(OutArgs a)
+{
+    out_logits_body<1, PACKED, QKPL>(a);
 }
 Q8_TRACE_READER(q8_trace_output)
 
@@ -189,9 +296,9 @@ struct SelectArgs {
 // whole row run instead.
 __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
 {
-    __shared__ unsigned long long s_sbkey[256];
+    __shared__ __align__(16) unsigned long long s_sbkey[256];
     __shared__ unsigned short s_q[OUT_MAX_TILES];
-    __shared__ unsigned long long s_key[SEL_CAP];
+    __shared__ __align__(16) unsigned long long s_key[SEL_CAP + 4];
     __shared__ float s_f[4];
     __shared__ double s_d[4];
     __shared__ unsigned long long s_u[4];
@@ -232,7 +339,11 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     if (tid < nsb) {
         const unsigned long long key = s_sbkey[tid];
         int rank = 0;
-        for (int u = 0; u < nsb; ++u) rank += (s_sbkey[u] > key);
+#pragma unroll 4
+        for (int u = 0; u < 256; u += 4) {       // entries past nsb are zero keys: never greater
+            const ulonglong2 p0 = *(const ulonglong2 *)&s_sbkey[u], p1 = *(const ulonglong2 *)&s_sbkey[u + 2];
+            rank += (p0.x > key) + (p0.y > key) + (p1.x > key) + (p1.y > key);
+        }
         if (rank == k - 1) s_T = bm;
     }
     __syncthreads();
@@ -282,10 +393,16 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     if (!overflow) {
         // rank every survivor among the survivors; ranks below k are the answer
         const int ns = s_ns;
+        if (tid < 4) s_key[ns + tid] = 0ull;     // pad to a multiple of four with keys that are never greater
+        __syncthreads();
         for (int t = tid; t < ns; t += 256) {
             const unsigned long long key = s_key[t];
             int rank = 0;
-            for (int u = 0; u < ns; ++u) rank += (s_key[u] > key);
+#pragma unroll 2
+            for (int u = 0; u < ns; u += 4) {
+                const ulonglong2 p0 = *(const ulonglong2 *)&s_key[u], p1 = *(const ulonglong2 *)&s_key[u + 2];
+                rank += (p0.x > key) + (p0.y > key) + (p1.x > key) + (p1.y > key);
+            }
             if (rank < k) {
                 a.topk_idx[(size_t)j * k + rank] = topk_key_idx(key);
                 a.topk_logp[(size_t)j * k + rank] = topk_key_val(key) - lse;
@@ -323,24 +440,26 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
 int q8i_out_tiles(int V) { return (V + OUT_TILE - 1) / OUT_TILE; }
 int q8i_out_max_rows(void) { return OUT_MAX_TILES * OUT_TILE; }
 
-template <int CH, bool PACKED>
-static void launch_out2(q8_ctx *ctx, const OutArgs &a, int nblk, size_t smem)
-{
-    if (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) {
-        // timed dispatch: the two events take the kernel's own begin and end timestamps
-        hipEvent_t e0 = ctx->prof_ev[2 * ctx->prof_n], e1 = ctx->prof_ev[2 * ctx->prof_n + 1];
-        ++ctx->prof_n;
-        hipExtLaunchKernelGGL((out_logits_kernel<CH, PACKED>), dim3(nblk), dim3(256), smem, ctx->stream, e0, e1, 0, a);
-    } else {
-        hipLaunchKernelGGL((out_logits_kernel<CH, PACKED>), dim3(nblk), dim3(256), smem, ctx->stream, a);
-    }
-}
+#define Q8_LAUNCH_TIMED(kernel, nblk, block, smem, a)                                                     \
+    do {                                                                                                   \
+        if (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) {                                                 \
+            /* timed dispatch: the two events take the kernel's own begin and end timestamps */            \
+            hipEvent_t e0 = ctx->prof_ev[2 * ctx->prof_n], e1 = ctx->prof_ev[2 * ctx->prof_n + 1];         \
+            ++ctx->prof_n;                                                                                 \
+            hipExtLaunchKernelGGL(kernel, dim3(nblk), dim3(block), smem, ctx->stream, e0, e1, 0, a);       \
+        } else {                                                                                           \
+            hipLaunchKernelGGL(kernel, dim3(nblk), dim3(block), smem, ctx->stream, a);                     \
+        }                                                                                                  \
+    } while (0)
 
-template <int CH>
-static void launch_out(q8_ctx *ctx, const OutArgs &a, int nblk, size_t smem)
+template <bool PACKED>
+static void launch_out_packed(q8_ctx *ctx, const OutArgs &a, int nblk, size_t smem, int ch)
 {
-    if (a.tiles) launch_out2<CH, true>(ctx, a, nblk, smem);
-    else launch_out2<CH, false>(ctx, a, nblk, smem);
+    if (ch == 1 && a.ld <= 256) Q8_LAUNCH_TIMED((out_logits5_kernel<PACKED, 1>), nblk, 320, smem, a);
+    else if (ch == 1 && a.ld <= 512) Q8_LAUNCH_TIMED((out_logits5_kernel<PACKED, 2>), nblk, 320, smem, a);
+    else if (ch == 1) Q8_LAUNCH_TIMED((out_logits_kernel<1, PACKED>), nblk, 256, smem, a);
+    else if (ch == 2) Q8_LAUNCH_TIMED((out_logits_kernel<2, PACKED>), nblk, 256, smem, a);
+    else Q8_LAUNCH_TIMED((out_logits_kernel<4, PACKED>), nblk, 256, smem, a);
 }
 
 size_t q8i_tiles_bytes(int rows, int ld) { return (size_t)q8i_out_tiles(rows) * OUT_TILE * (size_t)ld; }
@@ -369,9 +488,8 @@ q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const floa
     const int nblk = a.ntiles < 4 * OUT_BLOCKS ? (a.ntiles + 3) / 4 : OUT_BLOCKS;
     const size_t smem = (size_t)n * a.ld;
     const int ch = q8_fast_ch(a.ld);
-    if (ch == 1) launch_out<1>(ctx, a, nblk, smem);
-    else if (ch == 2) launch_out<2>(ctx, a, nblk, smem);
-    else launch_out<4>(ctx, a, nblk, smem);
+    if (a.tiles) launch_out_packed<true>(ctx, a, nblk, smem, ch);
+    else launch_out_packed<false>(ctx, a, nblk, smem, ch);
     SelectArgs s;
     s.part_max = part_max; s.part_sum = part_sum; s.logits = logits;
     s.lse = lse; s.topk_logp = topk_logp; s.topk_idx = topk_idx;

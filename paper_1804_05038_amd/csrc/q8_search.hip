@@ -14,20 +14,22 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const float *__restric
     for (int c = threadIdx.x; c < dim; c += blockDim.x) out[(size_t)i * dim + c] = src[c];
 }
 
-// Device-resident search state.  hist holds two [Q8_MAX_BEAM x max_steps] token tables used
-// alternately; fin holds the best finished hypothesis.
+// Device-resident search state.  Hypotheses are kept as back-pointers: link[t][q] =
+// (parent slot << 24) | token of live slot q after step t, so a step costs O(beam) and the
+// token sequences are rebuilt on the host when the result is read.
 struct BeamState {
     int n_live, b_live, step, done;
-    int have_fin, fin_len, max_steps, beam;
+    int have_fin, fin_len, fin_parent, max_steps;
     float fin_score;
+    int beam;
     float score[Q8_MAX_BEAM];
     int last[Q8_MAX_BEAM];
-    int tokens[1];          // hist[2][Q8_MAX_BEAM][max_steps], then fin[max_steps]
+    int link[1];            // [max_steps][Q8_MAX_BEAM]
 };
 
 size_t q8i_beam_state_bytes(int max_steps)
 {
-    return sizeof(BeamState) + sizeof(int) * ((size_t)2 * Q8_MAX_BEAM * max_steps + max_steps);
+    return sizeof(BeamState) + sizeof(int) * (size_t)Q8_MAX_BEAM * max_steps;
 }
 
 struct BeamInitArgs {
@@ -42,7 +44,7 @@ __global__ __launch_bounds__(256) void beam_init_kernel(BeamInitArgs a)
     BeamState *st = a.st;
     if (threadIdx.x == 0) {
         st->n_live = 1; st->b_live = a.beam; st->step = 0; st->done = 0;
-        st->have_fin = 0; st->fin_len = 0; st->max_steps = a.max_steps; st->beam = a.beam;
+        st->have_fin = 0; st->fin_len = 0; st->fin_parent = 0; st->max_steps = a.max_steps; st->beam = a.beam;
         st->fin_score = -INFINITY;
         for (int b = 0; b < Q8_MAX_BEAM; ++b) { st->score[b] = b == 0 ? 0.0f : -INFINITY; st->last[b] = 0; }
     }
@@ -83,9 +85,7 @@ __global__ __launch_bounds__(256) void beam_update_kernel(BeamUpdateArgs a)
         const int n_live = st->n_live, b_live = st->b_live, step = st->step;
         const bool skip = st->done != 0;
         if (!skip) {
-            int *hist_old = st->tokens + (size_t)(step & 1) * Q8_MAX_BEAM * max_steps;
-            int *hist_new = st->tokens + (size_t)((step + 1) & 1) * Q8_MAX_BEAM * max_steps;
-            int *fin = st->tokens + (size_t)2 * Q8_MAX_BEAM * max_steps;
+            int *link = st->link + (size_t)step * Q8_MAX_BEAM;
             // two candidates per lane: c = lane, lane + 64 over [n_live x k]
             unsigned long long key[2];
             float csc[2];
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void beam_update_kernel(BeamUpdateArgs a)
             }
             const int take = min(b_live, n_live * a.k);
             int n_new = 0, b_left = b_live;
-            int have_fin = st->have_fin, fin_len = st->fin_len;
+            int have_fin = st->have_fin, fin_len = st->fin_len, fin_parent = st->fin_parent;
             float fin_score = st->fin_score;
             for (int r = 0; r < take; ++r) {
                 const unsigned long long best = wave_max_u64(key[0] > key[1] ? key[0] : key[1]);
@@ -116,8 +116,7 @@ __global__ __launch_bounds__(256) void beam_update_kernel(BeamUpdateArgs a)
                 sc = wave_max_f(sc);
                 if (token == 0) {                      // end of sentence: the hypothesis is finished
                     if (!have_fin || sc > fin_score) {
-                        have_fin = 1; fin_score = sc; fin_len = step;
-                        for (int e = lane; e < step; e += 64) fin[e] = hist_old[(size_t)parent * max_steps + e];
+                        have_fin = 1; fin_score = sc; fin_len = step; fin_parent = parent;
                     }
                     --b_left;
                 } else {
@@ -125,23 +124,17 @@ __global__ __launch_bounds__(256) void beam_update_kernel(BeamUpdateArgs a)
                     ++n_new;
                 }
             }
-            // histories of the survivors (LDS writes of lane 0 above are visible to the wave: same wave, in order)
-            for (int q = 0; q < n_new; ++q) {
-                const int parent = s_parent[q];
-                for (int e = lane; e < step; e += 64)
-                    hist_new[(size_t)q * max_steps + e] = hist_old[(size_t)parent * max_steps + e];
-                if (lane == 0) hist_new[(size_t)q * max_steps + step] = s_token[q];
-            }
             if (lane == 0) {
                 for (int q = 0; q < Q8_MAX_BEAM; ++q) {
                     st->score[q] = q < n_new ? s_score[q] : -INFINITY;
                     st->last[q] = q < n_new ? s_token[q] : 0;
+                    if (q < n_new) link[q] = (s_parent[q] << 24) | s_token[q];
                     if (q >= n_new) {               // dead slots repeat survivor 0: finite data for the next step
                         s_parent[q] = n_new ? s_parent[0] : 0;
                         s_token[q] = n_new ? s_token[0] : 0;
                     }
                 }
-                st->have_fin = have_fin; st->fin_score = fin_score; st->fin_len = fin_len;
+                st->have_fin = have_fin; st->fin_score = fin_score; st->fin_len = fin_len; st->fin_parent = fin_parent;
                 st->n_live = n_new; st->b_live = b_left; st->step = step + 1;
                 if (b_left == 0 || n_new == 0 || step + 1 >= max_steps) st->done = 1;
             }
@@ -150,14 +143,40 @@ __global__ __launch_bounds__(256) void beam_update_kernel(BeamUpdateArgs a)
     }
     __syncthreads();
     if (s_skip) return;
-    // slots beyond the survivors repeat survivor 0 so that the next step works on finite data
-    for (int e = tid; e < a.n * a.H; e += blockDim.x) {
-        const int q = e / a.H, c = e - q * a.H;
-        a.s_next[e] = a.s_step[(size_t)s_parent[q] * a.H + c];
-    }
-    for (int e = tid; e < a.n * a.E; e += blockDim.x) {
-        const int q = e / a.E, c = e - q * a.E;
-        a.y_emb[e] = a.E_tgt[(size_t)s_token[q] * a.E + c];
+    // Gather the surviving decoder states and the embeddings of the new tokens (slots beyond
+    // the survivors repeat survivor 0).  All loads of a thread are issued before its stores.
+    if (((a.H | a.E) & 3) == 0) {
+        const int H4 = a.H >> 2, E4 = a.E >> 2, nH4 = a.n * H4, total4 = nH4 + a.n * E4;
+        for (int base = tid; base < total4; base += 256 * 8) {
+            float4 v[8];
+            float4 *dst[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + 256 * u;
+                dst[u] = nullptr;
+                if (idx < nH4) {
+                    const int q = idx / H4, c = idx - q * H4;
+                    v[u] = ((const float4 *)(a.s_step + (size_t)s_parent[q] * a.H))[c];
+                    dst[u] = (float4 *)a.s_next + idx;
+                } else if (idx < total4) {
+                    const int r = idx - nH4, q = r / E4, c = r - q * E4;
+                    v[u] = ((const float4 *)(a.E_tgt + (size_t)s_token[q] * a.E))[c];
+                    dst[u] = (float4 *)a.y_emb + r;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (dst[u]) *dst[u] = v[u];
+        }
+    } else {
+        for (int e = tid; e < a.n * a.H; e += blockDim.x) {
+            const int q = e / a.H, c = e - q * a.H;
+            a.s_next[e] = a.s_step[(size_t)s_parent[q] * a.H + c];
+        }
+        for (int e = tid; e < a.n * a.E; e += blockDim.x) {
+            const int q = e / a.E, c = e - q * a.E;
+            a.y_emb[e] = a.E_tgt[(size_t)s_token[q] * a.E + c];
+        }
     }
 }
 
@@ -194,16 +213,20 @@ q8_status q8i_beam_read(q8_ctx *ctx, const void *state, int max_steps, int32_t *
     hipError_t e = hipMemcpyAsync(h, state, bytes, hipMemcpyDeviceToHost, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) { free(h); return q8_fail(ctx, Q8_ERR_DEVICE, "beam read: %s", hipGetErrorString(e)); }
-    const int ms = h->max_steps;
-    int len;
+    int len, slot;
     if (h->have_fin) {
         len = h->fin_len;
-        if (tokens_host) memcpy(tokens_host, h->tokens + (size_t)2 * Q8_MAX_BEAM * ms, sizeof(int) * (size_t)len);
+        slot = h->fin_parent;
         if (score_host) *score_host = h->fin_score;
     } else {
         len = h->step;
-        if (tokens_host) memcpy(tokens_host, h->tokens + (size_t)(h->step & 1) * Q8_MAX_BEAM * ms, sizeof(int) * (size_t)len);
+        slot = 0;
         if (score_host) *score_host = h->n_live > 0 ? h->score[0] : 0.0f;
+    }
+    for (int t = len - 1; t >= 0; --t) {          // follow the back-pointers from the last token
+        const int e = h->link[(size_t)t * Q8_MAX_BEAM + slot];
+        if (tokens_host) tokens_host[t] = e & 0xFFFFFF;
+        slot = (e >> 24) & 0xF;
     }
     if (len_host) *len_host = len;
     if (steps_host) *steps_host = h->step;
