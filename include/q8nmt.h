@@ -204,6 +204,15 @@ q8_status q8_beam_init(q8_ctx *ctx, void *state, int beam, int max_steps, const 
 q8_status q8_beam_update(q8_ctx *ctx, void *state, const float *topk_logp, const int32_t *topk_idx, int n_beam,
                          int k, const float *s_step, int H, const float *E_tgt, int E, float *y_emb, float *s_next);
 
+/* output_logits_q8 followed by q8_beam_update in the same launches (the update runs in the
+ * block of the selection kernel that finishes last): logits of the decoder states s
+ * [n_beam x H] of this step, their k best entries, then the search step, which writes
+ * s_next [n_beam x H] (must not alias s) and overwrites y_emb [n_beam x E] with the
+ * embeddings of the new tokens.  topk_logp / topk_idx [n_beam x k] may be NULL (workspace). */
+q8_status output_logits_beam_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                                const float *s, float *y_emb, const float *ctx_vec, int n_beam, int k, void *state,
+                                const float *E_tgt, int E, float *s_next, float *topk_logp, int32_t *topk_idx);
+
 /* Waits for the stream and copies the result to the host: tokens (without the final
  * token 0), their number, the cumulative log-probability, the steps made, and whether
  * the search is over.  Host pointers; any may be NULL. */

@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 
 __all__ = ["Q8Error", "Context", "Mat", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
            "q8_quantize_matrix", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "gru_step_q8", "cgru_decoder_step_q8",
-           "output_logits_q8", "q8_encode", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
+           "output_logits_q8", "output_logits_beam_q8", "q8_encode", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
            "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "LIB_PATH"]
 LIB_PATH = _LIB_PATH
 
@@ -89,6 +89,8 @@ def load_library():
         lib.q8_beam_update.argtypes = [vp, vp, vp, vp, ci, ci, vp, ci, vp, ci, vp, vp]
         ip = C.POINTER(C.c_int)
         lib.q8_beam_result.argtypes = [vp, vp, ci, vp, ip, C.POINTER(C.c_float), ip, ip]
+        lib.output_logits_beam_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, ci, ci, vp,
+                                              vp, ci, vp, vp, vp]
         lib.q8_translate_bytes.restype = C.c_size_t
         lib.q8_translate_bytes.argtypes = [C.POINTER(_Model), ci, ci, ci, ci]
         lib.q8_translate.argtypes = [vp, C.POINTER(_Model), vp, ci, ci, ci, ci, vp, ip, C.POINTER(C.c_float), ip]
@@ -392,3 +394,18 @@ def q8_beam_result(ctx, state, max_steps):
     ctx.check(ctx.lib.q8_beam_result(ctx.handle, _ptr(state), max_steps, out, C.byref(n), C.byref(score), C.byref(steps),
                                      C.byref(done)))
     return np.array(out[:n.value], dtype=np.int32), np.float32(score.value), steps.value, bool(done.value)
+
+
+def output_logits_beam_q8(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, state, E_tgt, s_next, k=12, bind=False):
+    """Output layer + top-k + beam update; returns dict(topk_logp, topk_idx)."""
+    n = s.shape[0]
+    lp = ctx.empty(n, k)
+    idx = ctx.empty(n, k, dtype=torch.int32)
+    args = (ctx.handle, C.byref(ro.c), C.byref(W_out.c), _ptr(b_out), _ptr(s), _ptr(y_emb), _ptr(ctx_vec), n, k,
+            _ptr(state), _ptr(E_tgt), E_tgt.shape[1], _ptr(s_next), _ptr(lp), _ptr(idx))
+    r = {"topk_logp": lp, "topk_idx": idx}
+    if bind:
+        r["keep"] = (ro, W_out, b_out, s, y_emb, ctx_vec, state, E_tgt, s_next)
+        return _Bound(ctx, ctx.lib.output_logits_beam_q8, args, r)
+    ctx.check(ctx.lib.output_logits_beam_q8(*args))
+    return r

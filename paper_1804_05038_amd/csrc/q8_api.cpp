@@ -278,10 +278,10 @@ q8_status cgru_decoder_step_q8(q8_ctx *ctx, const q8_cgru_weights *w, const floa
     return q8i_gru(ctx, &dq, 1, n, Q8I_GRU_GH_PRE);
 }
 
-q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
-                           const float *s, const float *y_emb, const float *ctx_vec, const float *t_in, int n_beam,
-                           int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx, float *t_out,
-                           const q8_taps *taps4)
+static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                             const float *s, const float *y_emb, const float *ctx_vec, const float *t_in, int n_beam,
+                             int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx, float *t_out,
+                             const q8_taps *taps4, const q8i_beam_desc *beam)
 {
     if (!ctx) return Q8_ERR_NULL;
     TRY(check_mat(ctx, W_out, "W_out"));
@@ -292,8 +292,10 @@ q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_m
     if (W_out->ld > 4096) return q8_fail(ctx, Q8_ERR_SHAPE, "W_out: ld above 4096");
     if (R % 4) return q8_fail(ctx, Q8_ERR_ALIGN, "R must be a multiple of 4");
     if (W_out->tiles && !aligned16(W_out->tiles)) return q8_fail(ctx, Q8_ERR_ALIGN, "W_out.tiles needs 16-byte alignment");
-    if (!topk_logp || !topk_idx) return q8_fail(ctx, Q8_ERR_NULL, "top-k outputs: NULL");
+    if (!beam && (!topk_logp || !topk_idx)) return q8_fail(ctx, Q8_ERR_NULL, "top-k outputs: NULL");
     Carver cv(ctx);
+    if (!topk_logp) topk_logp = cv.take<float>((size_t)n * k);
+    if (!topk_idx) topk_idx = cv.take<int32_t>((size_t)n * k);
     const float *T = t_in;
     if (ro) {
         TRY(check_mat(ctx, &ro->W_s, "W_s"));
@@ -320,7 +322,33 @@ q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_m
     double *ps = cv.take<double>(ngrp * n);
     float *lg = logits ? logits : cv.take<float>((size_t)n * V);    // the selection reads the logits back
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
-    return q8i_output(ctx, W_out, b_out, T, R, n, k, lg, lse, topk_logp, topk_idx, taps4 ? taps4 + 3 : nullptr, pm, ps);
+    return q8i_output(ctx, W_out, b_out, T, R, n, k, lg, lse, topk_logp, topk_idx, taps4 ? taps4 + 3 : nullptr, pm, ps,
+                      beam);
+}
+
+q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                           const float *s, const float *y_emb, const float *ctx_vec, const float *t_in, int n_beam,
+                           int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx, float *t_out,
+                           const q8_taps *taps4)
+{
+    return output_impl(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, t_in, n_beam, k, logits, lse, topk_logp, topk_idx,
+                       t_out, taps4, nullptr);
+}
+
+q8_status output_logits_beam_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                                const float *s, float *y_emb, const float *ctx_vec, int n_beam, int k, void *state,
+                                const float *E_tgt, int E, float *s_next, float *topk_logp, int32_t *topk_idx)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!ro || !state || !E_tgt || !s_next || !s || !y_emb)
+        return q8_fail(ctx, Q8_ERR_NULL, "output_logits_beam_q8: NULL argument");
+    if (k < n_beam) return q8_fail(ctx, Q8_ERR_SHAPE, "output_logits_beam_q8: need k >= n_beam");
+    if (s_next == s) return q8_fail(ctx, Q8_ERR_SHAPE, "s_next must not alias s");
+    if (!aligned16(E_tgt) || !aligned16(s_next)) return q8_fail(ctx, Q8_ERR_ALIGN, "fp32 buffers need 16-byte alignment");
+    if (E != ro->W_y.cols) return q8_fail(ctx, Q8_ERR_SHAPE, "E does not match the readout's embedding width");
+    q8i_beam_desc bd = {state, s, E_tgt, y_emb, s_next, E, ro->W_s.cols};
+    return output_impl(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, nullptr, n_beam, k, nullptr, nullptr, topk_logp,
+                       topk_idx, nullptr, nullptr, &bd);
 }
 
 q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights *bwd, const float *X, int l,
@@ -464,10 +492,10 @@ q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens
     int cur = 0, done = 0;
     for (int t = 0; t < max_steps && !st && !done; ++t) {
         st = cgru_decoder_step_q8(ctx, &m->dec, P, enc_h, l, y, s[cur], beam, s[cur ^ 1], cv, nullptr, nullptr, nullptr);
-        if (!st) st = output_logits_q8(ctx, &m->ro, &m->W_out, m->b_out, s[cur ^ 1], y, cv, nullptr, beam, k,
-                                       nullptr, nullptr, lp, idx, nullptr, nullptr);
-        // the update gathers the surviving states from s[cur ^ 1] into s[cur]
-        if (!st) st = q8i_beam_update(ctx, state, lp, idx, beam, k, s[cur ^ 1], H, m->E_tgt, E, y, s[cur]);
+        // output layer, top-k and (in the selection kernel's last block) the beam update, which
+        // gathers the surviving states from s[cur ^ 1] into s[cur] and the new embeddings into y
+        if (!st) st = output_logits_beam_q8(ctx, &m->ro, &m->W_out, m->b_out, s[cur ^ 1], y, cv, beam, k, state,
+                                            m->E_tgt, E, s[cur], lp, idx);
         if (!st && (t % 8 == 7))
             st = q8i_beam_read(ctx, state, max_steps, nullptr, nullptr, nullptr, nullptr, &done);
     }

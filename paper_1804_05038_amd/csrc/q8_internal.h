@@ -17,6 +17,7 @@
 #define Q8_MAX_BEAM 8
 #define Q8_WS_HEADER 4096
 #define Q8_WS_SCRATCH_SLOT 2048
+#define Q8_WS_SELECT_COUNTER 1024   // arrival counter of the fused selection + beam update
 
 struct q8_ctx {
     hipStream_t stream;
@@ -61,6 +62,14 @@ struct q8i_gru_desc {
     const q8_taps *taps; // NULL or [2]
 };
 
+// beam update run by the last block of the selection kernel (NULL = none)
+struct q8i_beam_desc {
+    void *state;
+    const float *s_step, *E_tgt;
+    float *y_emb, *s_next;
+    int E, H;
+};
+
 enum { Q8I_GRU_FULL = 0, Q8I_GRU_GX_PRE = 1, Q8I_GRU_GH_PRE = 2 };
 
 q8_status q8i_fill_u32(q8_ctx *ctx, void *p, int n, unsigned v);   // fill kernel (safe under graph capture)
@@ -81,7 +90,7 @@ int q8i_out_max_rows(void);
 q8_status q8i_launch_check(q8_ctx *ctx, const char *what);
 q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const float *T, int ldt, int n, int k,
                      float *logits, float *lse, float *topk_logp, int32_t *topk_idx, const q8_taps *taps,
-                     float *part_max, double *part_sum);
+                     float *part_max, double *part_sum, const struct q8i_beam_desc *beam);
 
 size_t q8i_beam_state_bytes(int max_steps);
 q8_status q8i_gather_rows(q8_ctx *ctx, const float *table, const int *idx, int n, int dim, float *out);

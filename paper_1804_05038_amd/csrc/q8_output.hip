@@ -2,7 +2,7 @@
 // Neural Machine Translation"): the vocabulary projection as Section 3's narrow product
 // on the int8 matrix cores, fused with bias and log-sum-exp partials; a second kernel
 // finishes the log-sum-exp and selects the k best entries of every hypothesis.
-#include "q8_internal.h"
+#include "q8_beam.h"
 
 #include <hip/hip_ext.h>
 
@@ -108,7 +108,8 @@ __device__ __forceinline__ void out_logits_body(const OutArgs &a)
     const int ld = a.ld, n = a.n;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int i = lane & 15, g = lane >> 4;
-    const int kchunks = (ld + 511) / 512;
+    // five-wave blocks only run rows of at most 512 bytes: one k chunk, no index divisions
+    const int kchunks = QW ? 1 : (ld + 511) / 512;
     Q8_SPAN_BEGIN();
     if (QW && wave == OUT_STREAM_WAVES) {
         wave_quantize<QW ? QKPL : 1>(a.T, n, a.K, a.ldt, ld, smem, s_scale, lane);
@@ -283,9 +284,24 @@ struct SelectArgs {
     float *lse, *topk_logp;
     int *topk_idx;
     int ntiles, n, k, V, ldl;
+    int fuse_update;        // 1: the last block to finish also runs the beam update
+    unsigned *counter;      // arrival counter for that, zero on entry and on exit
+    BeamUpdateArgs bu;
 };
 
 #define SEL_CAP 2048          // survivors held in LDS
+
+// Top-k entry `o` of the output tables; device-coherent when another block will read it.
+__device__ __forceinline__ void put_topk(const SelectArgs &a, size_t o, int idx, float logp)
+{
+    if (a.fuse_update) {
+        __hip_atomic_store(a.topk_idx + o, idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(a.topk_logp + o, logp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        a.topk_idx[o] = idx;
+        a.topk_logp[o] = logp;
+    }
+}
 
 // One block of 256 threads per hypothesis; thread t owns super-block t (16 tiles, 256 rows).
 // (1) log-sum-exp from the tile partials.  (2) T = the k-th largest super-block maximum
@@ -403,15 +419,10 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
                 const ulonglong2 p0 = *(const ulonglong2 *)&s_key[u], p1 = *(const ulonglong2 *)&s_key[u + 2];
                 rank += (p0.x > key) + (p0.y > key) + (p1.x > key) + (p1.y > key);
             }
-            if (rank < k) {
-                a.topk_idx[(size_t)j * k + rank] = topk_key_idx(key);
-                a.topk_logp[(size_t)j * k + rank] = topk_key_val(key) - lse;
-            }
+            if (rank < k) put_topk(a, (size_t)j * k + rank, topk_key_idx(key), topk_key_val(key) - lse);
         }
         Q8_STAMP(13);
-        return;
-    }
-
+    } else {
     // ---- heavily tied logits: k exact rounds of arg-max over the whole row
     unsigned long long prev = ~0ull;
     for (int r = 0; r < k; ++r) {
@@ -427,12 +438,26 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
         best = s_u[0];
 #pragma unroll
         for (int w = 1; w < 4; ++w) best = s_u[w] > best ? s_u[w] : best;
-        if (tid == 0) {
-            a.topk_idx[(size_t)j * k + r] = topk_key_idx(best);
-            a.topk_logp[(size_t)j * k + r] = topk_key_val(best) - lse;
-        }
+        if (tid == 0) put_topk(a, (size_t)j * k + r, topk_key_idx(best), topk_key_val(best) - lse);
         prev = best;
     }
+    }
+
+    if (!a.fuse_update) return;
+    // ---- the block that finishes last continues with the beam update.  Every thread waits
+    // until its own (device-coherent) top-k stores have been performed, then one thread
+    // counts the block's arrival with a device-coherent atomic.
+    __shared__ int s_is_last;
+    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned prev_cnt = __hip_atomic_fetch_add(a.counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_is_last = (prev_cnt == (unsigned)n - 1u);
+        if (s_is_last) __hip_atomic_store(a.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!s_is_last) return;
+    beam_update_body<true>(a.bu);
 }
 
 // =================================================================== host launcher ==
@@ -475,7 +500,7 @@ q8_status q8i_pack_tiles(q8_ctx *ctx, const q8_mat *W, int8_t *tiles)
 
 q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const float *T, int ldt, int n, int k,
                      float *logits, float *lse, float *topk_logp, int32_t *topk_idx, const q8_taps *taps,
-                     float *part_max, double *part_sum)
+                     float *part_max, double *part_sum, const q8i_beam_desc *beam)
 {
     OutArgs a;
     a.W = W->data; a.tiles = (W->ld % 64 == 0) ? W->tiles : nullptr; a.T = T; a.bias = bias; a.logits = logits;
@@ -494,6 +519,15 @@ q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const floa
     s.part_max = part_max; s.part_sum = part_sum; s.logits = logits;
     s.lse = lse; s.topk_logp = topk_logp; s.topk_idx = topk_idx;
     s.ntiles = a.ntiles; s.n = n; s.k = k; s.V = a.V; s.ldl = a.ldl;
+    s.fuse_update = beam ? 1 : 0;
+    s.counter = (unsigned *)(ctx->ws + Q8_WS_SELECT_COUNTER);
+    if (beam) {
+        BeamUpdateArgs bu = {(BeamState *)beam->state, topk_logp, topk_idx, beam->s_step, beam->E_tgt, beam->y_emb,
+                             beam->s_next, n, k, beam->E, beam->H};
+        s.bu = bu;
+    } else {
+        memset(&s.bu, 0, sizeof(s.bu));
+    }
     hipLaunchKernelGGL(out_select_kernel, dim3(n), dim3(256), 0, ctx->stream, s);
     return q8i_launch_check(ctx, "output");
 }
