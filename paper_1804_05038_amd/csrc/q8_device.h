@@ -123,6 +123,23 @@ __device__ __forceinline__ unsigned long long wave_max_u64(unsigned long long v)
     return a > b ? a : b;
 }
 
+// Bitonic sort of one float per lane across the wave, descending: lane r ends up holding
+// the (r+1)-th largest value (with multiplicity).
+__device__ __forceinline__ float wave_sort_desc_f(float v, int lane)
+{
+#pragma unroll
+    for (int k2 = 2; k2 <= 64; k2 <<= 1) {
+#pragma unroll
+        for (int j = k2 >> 1; j > 0; j >>= 1) {
+            const float o = __shfl_xor(v, j, 64);
+            const bool up = (lane & k2) == 0;          // this block of k2 lanes is sorted descending
+            const bool low = (lane & j) == 0;          // lower lane of the pair
+            v = (up == low) ? fmaxf(v, o) : fminf(v, o);
+        }
+    }
+    return v;
+}
+
 // Order-preserving key: larger value first, then lower index.  -0.0 is folded into +0.0
 // so that equal floats compare equal.
 __device__ __forceinline__ unsigned long long topk_key(float val, int idx)

@@ -7,7 +7,7 @@
 #include <hip/hip_ext.h>
 
 #define OUT_TILE 16                  // vocabulary rows per matrix-core tile = one selection group
-#define OUT_SB 16                    // tiles per super-block of the threshold search
+#define OUT_SB 16                    // tiles per thread of the selection kernel (256 threads)
 #ifndef OUT_BLOCKS
 #define OUT_BLOCKS 512               // blocks of 4 waves; tile t belongs to block t % OUT_BLOCKS
 #endif
@@ -303,33 +303,33 @@ __device__ __forceinline__ void put_topk(const SelectArgs &a, size_t o, int idx,
     }
 }
 
-// One block of 256 threads per hypothesis; thread t owns super-block t (16 tiles, 256 rows).
-// (1) log-sum-exp from the tile partials.  (2) T = the k-th largest super-block maximum
-// (by rank counting): at least k logits are >= T, so each of the k best logits is >= T and
-// lies in a tile whose maximum is >= T.  (3) Those tiles are read back, logits >= T
+// One block of 256 threads per hypothesis; thread t owns tiles t, t + 256, ... (up to 16).
+// (1) log-sum-exp from the tile partials.  (2) Each wave sorts its 64 threads' maxima; the
+// wave's k-th largest has at least k logits at or above it, and T is the largest of the four
+// such values: at least k logits are >= T, so each of the k best logits is >= T and lies in
+// a tile whose maximum is >= T.  (3) Those tiles are read back, logits >= T
 // collected (a few dozen unless many logits tie) and ranked by (value descending, index
 // ascending).  If ties overflow the survivor list, k exact rounds of arg-max over the
 // whole row run instead.
 __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
 {
-    __shared__ __align__(16) unsigned long long s_sbkey[256];
     __shared__ unsigned short s_q[OUT_MAX_TILES];
     __shared__ __align__(16) unsigned long long s_key[SEL_CAP + 4];
     __shared__ float s_f[4];
     __shared__ double s_d[4];
     __shared__ unsigned long long s_u[4];
-    __shared__ float s_T;
+    __shared__ float s_t4[4];
     __shared__ int s_nq, s_ns;
     const int j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = a.n, k = a.k;
-    const int ntiles = a.ntiles, nsb = (ntiles + OUT_SB - 1) / OUT_SB;
-    if (tid == 0) { s_nq = 0; s_ns = 0; s_T = -INFINITY; }
+    const int ntiles = a.ntiles;
+    if (tid == 0) { s_nq = 0; s_ns = 0; }
     Q8_STAMP(8);
 
     float pm[OUT_SB];
     double ps[OUT_SB];
 #pragma unroll
     for (int t = 0; t < OUT_SB; ++t) {
-        const int tile = tid * OUT_SB + t;
+        const int tile = tid + 256 * t;            // consecutive threads, consecutive tiles
         pm[t] = -INFINITY;
         ps[t] = 0.0;
         if (tile < ntiles) {
@@ -340,39 +340,32 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     float bm = -INFINITY;
 #pragma unroll
     for (int t = 0; t < OUT_SB; ++t) bm = fmaxf(bm, pm[t]);
-    s_sbkey[tid] = tid < nsb ? topk_key(bm, tid) : 0ull;
-    float m = wave_max_f(bm);
-    if (lane == 0) s_f[wave] = m;
+    Q8_STAMP(14);
+    // the wave's maxima in descending order: lane 0 holds the largest, lane k - 1 the k-th
+    const float sorted = wave_sort_desc_f(bm, lane);
+    if (lane == 0) s_f[wave] = sorted;
+    if (lane == k - 1) s_t4[wave] = sorted;       // -inf if the wave has fewer than k non-empty threads
     __syncthreads();
-    m = fmaxf(fmaxf(s_f[0], s_f[1]), fmaxf(s_f[2], s_f[3]));
+    float m = fmaxf(fmaxf(s_f[0], s_f[1]), fmaxf(s_f[2], s_f[3]));
     double S = 0.0;
 #pragma unroll
     for (int t = 0; t < OUT_SB; ++t)
         if (pm[t] > -INFINITY) S += ps[t] * (double)__expf(pm[t] - m);
     S = wave_sum_d(S);
     if (lane == 0) s_d[wave] = S;
-    // rank of this super-block's maximum among all of them
-    if (tid < nsb) {
-        const unsigned long long key = s_sbkey[tid];
-        int rank = 0;
-#pragma unroll 4
-        for (int u = 0; u < 256; u += 4) {       // entries past nsb are zero keys: never greater
-            const ulonglong2 p0 = *(const ulonglong2 *)&s_sbkey[u], p1 = *(const ulonglong2 *)&s_sbkey[u + 2];
-            rank += (p0.x > key) + (p0.y > key) + (p1.x > key) + (p1.y > key);
-        }
-        if (rank == k - 1) s_T = bm;
-    }
+    Q8_STAMP(15);
+    Q8_STAMP(16);
     __syncthreads();
     S = (s_d[0] + s_d[1]) + (s_d[2] + s_d[3]);
     const float lse = (float)((double)m + log(S));
     if (tid == 0 && a.lse) a.lse[j] = lse;
-    const float T = s_T;                        // -inf when there are fewer than k super-blocks
+    const float T = fmaxf(fmaxf(s_t4[0], s_t4[1]), fmaxf(s_t4[2], s_t4[3]));   // -inf: everything qualifies
     Q8_STAMP(10);
 
     // ---- tiles that can hold a logit >= T
 #pragma unroll
     for (int t = 0; t < OUT_SB; ++t)
-        if (tid * OUT_SB + t < ntiles && pm[t] >= T) s_q[atomicAdd(&s_nq, 1)] = (unsigned short)(tid * OUT_SB + t);
+        if (tid + 256 * t < ntiles && pm[t] >= T) s_q[atomicAdd(&s_nq, 1)] = (unsigned short)(tid + 256 * t);
     __syncthreads();
     Q8_STAMP(11);
     const int total = s_nq * OUT_TILE;
