@@ -87,3 +87,85 @@ def test_beam_update_rules(q, ctx):
     assert steps == 2 and not done and toks.tolist() == [] and score == np.float32(-2.0)
     assert np_(y)[:2].tolist() == np_(E_tgt)[[4, 4]].tolist()
     assert (np_(s)[0] == np_(s_step)[0]).all() and (np_(s)[1] == np_(s_step)[1]).all()
+
+
+def _decode_loop(q, c, m, P, enc_h, n, s0, T):
+    """Bound calls of a search: init, decoder step, fused output layer + beam update."""
+    E, H = m.E_tgt.shape[1], m.dec.r.H
+    state = torch.zeros(q.q8_beam_state_bytes(T), dtype=torch.uint8, device=c.device)
+    y, s = c.empty(n, E), c.empty(n, H)
+    c0 = q.q8_beam_init(c, state, n, T, s0, m.E_tgt, y, s, bind=True)
+    c1 = q.cgru_decoder_step_q8(c, m.dec, P, enc_h, y, s, bind=True)
+    c2 = q.output_logits_beam_q8(c, m.ro, m.W_out, m.b_out, c1.out["s"], y, c1.out["ctx"], state, m.E_tgt, s, k=6, bind=True)
+    return state, c0, c1, c2
+
+
+def test_fused_tail_equals_separate_calls_and_graph_replays(q, ctx, oracle):
+    """output_logits_beam_q8 against output_logits_q8 + q8_beam_update, eagerly and from a HIP
+    graph replayed several times with eager work between the replays."""
+    V, E, H, A, R, n, T = 500, 64, 128, 64, 64, 4, 12
+    p = synth.full_model(seed=21, V=V, E=E, H=H, A=A, R=R, w_std=0.2, b_std=0.1)
+    m = q.Model.from_params(ctx, p)
+    rng = np.random.default_rng(3)
+    enc_h = ctx.f32(rng.standard_normal((9, 2 * H)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    s0 = ctx.f32(rng.standard_normal(H).astype(np.float32))
+
+    # reference: separate calls
+    state = torch.zeros(q.q8_beam_state_bytes(T), dtype=torch.uint8, device=ctx.device)
+    y, s = ctx.empty(n, E), ctx.empty(n, H)
+    q.q8_beam_init(ctx, state, n, T, s0, m.E_tgt, y, s)
+    for _ in range(T):
+        r = q.cgru_decoder_step_q8(ctx, m.dec, P, enc_h, y, s)
+        o = q.output_logits_q8(ctx, m.ro, m.W_out, m.b_out, s=r["s"], y_emb=y, ctx_vec=r["ctx"], k=6, want_logits=False)
+        q.q8_beam_update(ctx, state, o["topk_logp"], o["topk_idx"], r["s"], m.E_tgt, y, s)
+    ref = q.q8_beam_result(ctx, state, T)
+
+    # fused, eager
+    st2, c0, c1, c2 = _decode_loop(q, ctx, m, P, enc_h, n, s0, T)
+    c0.launch()
+    for _ in range(T):
+        c1.launch(); c2.launch()
+    got = q.q8_beam_result(ctx, st2, T)
+    assert got[0].tolist() == ref[0].tolist() and got[1] == ref[1] and got[2:] == ref[2:]
+
+    # fused, captured: one graph holds the whole search; replay it three times
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        gctx = q.Context("cuda:0", stream=side)
+        st3, g0, g1, g2 = _decode_loop(q, gctx, m, P, enc_h, n, s0, T)
+        g0.launch(); g1.launch(); g2.launch()
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            g0.launch()
+            for _ in range(T):
+                g1.launch(); g2.launch()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        g.replay()
+        torch.cuda.synchronize()
+        got = q.q8_beam_result(gctx, st3, T)
+        assert got[0].tolist() == ref[0].tolist() and got[1] == ref[1] and got[2:] == ref[2:], rep
+        q.q8_gemv(ctx, m.att_W, enc_h[0])          # unrelated eager work between replays
+        torch.cuda.synchronize()
+
+
+def test_two_contexts_on_two_streams(q, ctx, oracle):
+    """Independent contexts (own stream, own workspace) translate concurrently and agree with the oracle."""
+    p = synth.full_model(seed=33, V=60, E=32, H=48, A=40, R=24, w_std=0.3, b_std=0.1)
+    p["out.b"][0] += 1.0
+    m_ref = oracle.OracleModel(p)
+    m = q.Model.from_params(ctx, p)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ctxs = [q.Context("cuda:0", stream=st) for st in streams]
+    rng = np.random.default_rng(5)
+    for i in range(4):
+        srcs = [rng.integers(1, 60, size=int(rng.integers(2, 10))).astype(np.int32) for _ in ctxs]
+        outs = []
+        for c, st, src in zip(ctxs, streams, srcs):
+            with torch.cuda.stream(st):
+                outs.append(q.q8_translate(c, m, src, beam=4, k=6, max_steps=10))
+        for (toks, score, steps), src in zip(outs, srcs):
+            r_toks, r_score, r_steps = m_ref.translate(src, beam=4, topk=6, max_steps=10)
+            assert toks.tolist() == r_toks.tolist() and steps == r_steps
