@@ -179,16 +179,16 @@ __global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
 {
     extern __shared__ __align__(16) int8_t smem[];
     __shared__ float s_scale[24];
-    __shared__ float s_red[8 * 4];
+    __shared__ float s_red[3 * 8 * 4];
     int8_t *sq = smem, *yq = sq + N * a.lds, *cq = yq + N * a.ldy;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int unit = blockIdx.x * 4 + wave;
     const bool ok = unit < a.R;
 
-    XRegs<N, CH> rs, ry, rc;
-    x_load<N, CH>(rs, a.s, N, a.H, a.H);
-    x_load<N, CH>(ry, a.y, N, a.E, a.E);
-    x_load<N, CH>(rc, a.c, N, a.C, a.C);
+    XRegs<N, CH> rin[3];                     // s, y, ctx
+    x_load<N, CH>(rin[0], a.s, N, a.H, a.H);
+    x_load<N, CH>(rin[1], a.y, N, a.E, a.E);
+    x_load<N, CH>(rin[2], a.c, N, a.C, a.C);
     v4i ws[1][CH], wy[1][CH], wc[1][CH];
     {
         const int8_t *w1[1];
@@ -201,9 +201,11 @@ __global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
     }
     float bt = 0.f;
     if (ok && a.b_t) bt = a.b_t[unit];
-    x_finish<N, CH>(rs, N, a.lds, sq, s_scale, s_red);
-    x_finish<N, CH>(ry, N, a.ldy, yq, s_scale + 8, s_red);
-    x_finish<N, CH>(rc, N, a.ldc, cq, s_scale + 16, s_red);
+    {
+        const int lds3[3] = {a.lds, a.ldy, a.ldc};
+        int8_t *const dst[3] = {sq, yq, cq};
+        x_finish_multi<N, CH, 3>(rin, lds3, dst, s_scale, s_red);
+    }
     if (blockIdx.x == 0) readout_x_taps<N>(a, sq, yq, cq, s_scale);
 
     int as[1][N], ay[1][N], ac[1][N];

@@ -415,6 +415,55 @@ __device__ __forceinline__ void x_finish_m(const XRegs<N, CH> &R, float (&m)[N],
     __syncthreads();
 }
 
+// The same for NIN staged inputs at once (different widths allowed): one pair of barriers
+// for all of them, their reductions interleaved.  Input i uses s_scale[8 * i + j];
+// s_red needs NIN * N * 4 floats.
+template <int N, int CH, int NIN>
+__device__ __forceinline__ void x_finish_multi(const XRegs<N, CH> (&R)[NIN], const int (&ld)[NIN], int8_t *const (&xq)[NIN],
+                                               float *s_scale, float *s_red)
+{
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    float m[NIN * N];
+#pragma unroll
+    for (int i = 0; i < NIN; ++i)
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            float mm = 0.0f;
+#pragma unroll
+            for (int t = 0; t < CH; ++t) {
+                const float4 v = R[i].v[j][t];
+                mm = fmaxf(mm, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+            }
+            m[i * N + j] = mm;
+        }
+    wave_max_multi<NIN * N>(m);
+    if (lane == 0) {
+#pragma unroll
+        for (int e = 0; e < NIN * N; ++e) s_red[e * 4 + wave] = m[e];
+    }
+    __syncthreads();
+    float scale = 1.0f, inv = 0.0f;          // lane 8 i + j owns vector j of input i
+    if (lane < 8 * NIN && (lane & 7) < N) {
+        const int e = (lane >> 3) * N + (lane & 7);
+        const float mm = fmaxf(fmaxf(s_red[e * 4], s_red[e * 4 + 1]), fmaxf(s_red[e * 4 + 2], s_red[e * 4 + 3]));
+        q8_scale_of(mm, scale, inv);
+        if (wave == 0) s_scale[lane] = scale;
+    }
+#pragma unroll
+    for (int i = 0; i < NIN; ++i)
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const float invj = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(inv), 8 * i + j));
+#pragma unroll
+            for (int t = 0; t < CH; ++t) {
+                const int k = (t * 256 + tid) * 4;
+                const float4 v = R[i].v[j][t];
+                if (k < ld[i]) *(int *)(xq[i] + (size_t)j * ld[i] + k) = q8_pack4(v.x, v.y, v.z, v.w, invj);
+            }
+        }
+    __syncthreads();
+}
+
 // Requests U weight rows for this wave: lane covers bytes [(c * 64 + lane) * 16, +16) of a row.
 template <int U, int CH>
 __device__ __forceinline__ void rows_load(v4i (&w)[U][CH], const int8_t *const (&wrow)[U], int ld, int lane)
@@ -466,10 +515,5 @@ static inline int q8_lanes_per_row(int ld)
 }
 
 // fp32 nonlinearities of the gates, evaluated in double and rounded once.
-#ifdef Q8_EXPERIMENT_F32MATH   // timing experiment only: never defined in the product build
-__device__ __forceinline__ float sigmoid_rn(float a) { return 1.0f / (1.0f + __expf(-a)); }
-__device__ __forceinline__ float tanh_rn(float a) { return 1.0f - 2.0f / (1.0f + __expf(2.0f * a)); }
-#else
 __device__ __forceinline__ float sigmoid_rn(float a) { return (float)(1.0 / (1.0 + exp(-(double)a))); }
 __device__ __forceinline__ float tanh_rn(float a) { return (float)tanh((double)a); }
-#endif

@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
 {
     extern __shared__ __align__(16) int8_t smem[];
     __shared__ float s_scale[16];
-    __shared__ float s_red[8 * 4];
+    __shared__ float s_red[2 * 8 * 4];
     const GruJob &J = jobs.j[blockIdx.y];
     const int H = J.H;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -144,7 +144,8 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
     int8_t *hq = smem + (MODE == GRU_GX_PRE ? 0 : N * J.ldwx);
 
     Q8_STAMP(0);
-    XRegs<N, CH> xr, hr;
+    XRegs<N, CH> xh[2];                      // [0]: x, [1]: h_prev
+    XRegs<N, CH> &xr = xh[0], &hr = xh[1];
     if (MODE != GRU_GX_PRE) x_load<N, CH>(xr, J.x, N, J.I, J.ldx);
     if (MODE != GRU_GH_PRE) x_load<N, CH>(hr, J.h_prev, N, H, J.ldh);
     v4i wx[3][CH], wh[3][CH];
@@ -174,8 +175,15 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
     }
 
     Q8_STAMP(1);
-    if (MODE != GRU_GX_PRE) x_finish<N, CH>(xr, N, J.ldwx, xq, s_scale, s_red);
-    if (MODE != GRU_GH_PRE) x_finish<N, CH>(hr, N, J.ldwh, hq, s_scale + 8, s_red);
+    if (MODE == GRU_FULL) {
+        const int lds[2] = {J.ldwx, J.ldwh};
+        int8_t *const dst[2] = {xq, hq};
+        x_finish_multi<N, CH, 2>(xh, lds, dst, s_scale, s_red);
+    } else if (MODE == GRU_GH_PRE) {
+        x_finish<N, CH>(xr, N, J.ldwx, xq, s_scale, s_red);
+    } else {
+        x_finish<N, CH>(hr, N, J.ldwh, hq, s_scale + 8, s_red);
+    }
     Q8_STAMP(2);
     if (blockIdx.x == 0) gru_x_taps<N, MODE>(J, xq, hq, s_scale);
 

@@ -217,11 +217,7 @@ __device__ __forceinline__ void out_logits_body(const OutArgs &a)
             }
             m = fmaxf(m, y[r]);
         }
-#ifdef Q8_EXP_NOSTORE
-        if (i < n && y[0] == 123.456f) {
-#else
         if (i < n) {
-#endif
             if (vec_ok && row0 + 3 < a.V) {
                 *(float4 *)(a.logits + (size_t)i * a.ldl + row0) = make_float4(y[0], y[1], y[2], y[3]);
             } else {
@@ -234,13 +230,11 @@ __device__ __forceinline__ void out_logits_body(const OutArgs &a)
         m = fmaxf(m, __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(m), SWZ_XOR16)));
         m = fmaxf(m, __shfl_xor(m, 32, 64));
         double sd = 0.0;
-#ifndef Q8_EXP_NOEXP
 #pragma unroll
         for (int r = 0; r < 4; ++r)
             if (y[r] > -INFINITY) sd += (double)__expf(y[r] - m);
         sd += __shfl_xor(sd, 16, 64);
         sd += __shfl_xor(sd, 32, 64);
-#endif
         if (i < n && g == 0) {
             a.part_max[(size_t)i * a.ntiles + tile] = m;
             a.part_sum[(size_t)i * a.ntiles + tile] = sd;
