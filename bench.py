@@ -95,6 +95,21 @@ def cpu_baseline(p, seconds=12.0):
     P = m.attention_precompute(enc_h)
     y = rng.standard_normal((BEAM, 512)).astype(np.float32)
     s = rng.standard_normal((BEAM, 1024)).astype(np.float32)
+    # the units of work on one core (the per-core figure the paper reports its speeds in)
+    def one_core(fn, budget=0.6):
+        fn()
+        t0, k = time.perf_counter(), 0
+        while time.perf_counter() - t0 < budget:
+            fn()
+            k += 1
+        return (time.perf_counter() - t0) / k * 1e6
+
+    Wq = o.QLinear((rng.standard_normal((3072, 1024)) * 0.05).astype(np.float32))
+    xv = rng.standard_normal(1024).astype(np.float32)
+    gv = one_core(lambda: Wq.gemv(xv))
+    units = {"gemv_3072x1024_us": gv, "gemv_3072x1024_GBps": 3072 * 1024 / gv / 1e3,
+             "cgru_step_one_hypothesis_us": one_core(lambda: m.cgru_step(P, enc_h, y[0], s[0])),
+             "output_layer_one_hypothesis_us": one_core(lambda: m.output(rng.standard_normal(512).astype(np.float32), TOPK), 1.5)}
     threads = min(16, os.cpu_count() or 1)
     counts = [0] * threads
     stop = time.perf_counter() + seconds
@@ -113,7 +128,7 @@ def cpu_baseline(p, seconds=12.0):
     [t.join() for t in th]
     dt = time.perf_counter() - t0
     total = sum(counts)
-    return {"value": total / dt, "unit": "steps/s", "cores": threads, "kind": "oracle",
+    return {"value": total / dt, "unit": "steps/s", "cores": threads, "kind": "oracle", "units_on_one_core": units,
             "sample": "%d beam-5 decoder steps (cGRU step + output layer, source length %d) in %.1f s, one "
                       "independent stream of steps per thread" % (total, L, dt)}
 
@@ -143,6 +158,55 @@ def gemv_bandwidth(torch, q, ctx, rng):
                      "cold_us": cold[0], "cold_GBps": nbytes / cold[0] / 1e3, "cold_copies": copies,
                      "note": "wall time of back-to-back calls, launch included"}
         del mats
+    return out
+
+
+def kernel_times(torch, q, ctx, step, steps):
+    """Average duration of every kernel class inside the running decoder loop, from event
+    pairs attached to the dispatches (one class per pass over `steps` steps)."""
+    out = {}
+    for kind in ("gru", "gemv", "attention", "readout", "vocab", "select"):
+        q.q8_profile_begin(ctx, kind, 4 * steps)
+        for _ in range(steps):
+            step()
+        ms, n = q.q8_profile_end(ctx)
+        out[kind] = {"avg_us": ms * 1e3, "launches_per_step": n / steps}
+    return out
+
+
+def read_ceiling(torch, q, ctx, nbytes, cold):
+    """Duration of a plain read stream (q8_probe_read) over a buffer of nbytes: warm = the same
+    buffer every launch, cold = rotating over copies that together exceed twice the Infinity Cache."""
+    copies = max(2, int(2.2 * 256e6 / nbytes) + 1) if cold else 1
+    bufs = [torch.ones(nbytes, dtype=torch.uint8, device=ctx.device) for _ in range(copies)]
+    reps = max(200, 2 * copies)
+    for i in range(copies):
+        q.q8_probe_read(ctx, bufs[i])
+    q.q8_profile_begin(ctx, "probe", reps)
+    for i in range(reps):
+        q.q8_probe_read(ctx, bufs[i % copies])
+    ms, n = q.q8_profile_end(ctx)
+    return {"bytes": nbytes, "kernel_us": ms * 1e3, "GBps": nbytes / (ms * 1e-3) / 1e9, "copies": copies}
+
+
+def mfma_products(torch, q, ctx, m, rng):
+    """The two products with more than 8 columns (matrix-core kernel): encoder input
+    projections for 50 positions and attention pre-computation for 30 positions."""
+    out = {}
+    for name, M, n in (("enc_Wx_3072x512_n50", m.enc_fwd.Wx, 50), ("att_W_1024x2048_n30", m.att_W, 30)):
+        X = ctx.f32(rng.standard_normal((n, M.cols)).astype(np.float32))
+        Y = ctx.empty(n, M.rows)
+        for _ in range(10):
+            q.q8_gemm_narrow(ctx, M, X, None, Y)
+        q.q8_profile_begin(ctx, "mfma", 200)
+        for _ in range(200):
+            q.q8_gemm_narrow(ctx, M, X, None, Y)
+        ms, k = q.q8_profile_end(ctx)
+        ops = 2.0 * M.rows * M.cols * n
+        out[name] = {"kernel_us": ms * 1e3, "int8_TOPs": ops / (ms * 1e-3) / 1e12,
+                     "frac_of_int8_mfma_peak": ops / (ms * 1e-3) / 5.0e15,
+                     "weights_GBps": M.rows * M.cols / (ms * 1e-3) / 1e9,
+                     "note": "bytes-bound, not matrix-core-bound: 2n ops per weight byte is far under the ridge"}
     return out
 
 
@@ -258,10 +322,9 @@ def main():
             concurrent = "unavailable: %s" % (str(e).splitlines()[0][:120])
 
     # ---- dominant kernel: the vocabulary projection, timed by events attached to its dispatch ----
-    q.q8_profile_begin(ctx, args.steps)
-    for _ in range(args.steps):
-        loop5.step()
-    k_ms, k_n = q.q8_profile_end(ctx)
+    ktimes = kernel_times(torch, q, ctx, loop5.step, args.steps)
+    k_ms, k_n = ktimes["vocab"]["avg_us"] * 1e-3, int(ktimes["vocab"]["launches_per_step"] * args.steps)
+    ceil_warm = read_ceiling(torch, q, ctx, 25600000, cold=False)
     V, R = 50000, 512
     out_bytes = V * R + 4 * V + BEAM * R * 4 + BEAM * V * 4   # int8 weights, bias, hidden vectors, logits written
     achieved = out_bytes / (k_ms * 1e-3) / 1e9
@@ -294,6 +357,11 @@ def main():
         X4, eo = ctx.f32(p4["X"]), ctx.empty(50, 2048)
         extra["calls_us_median_min"]["encoder_l50"] = median_of(torch, lambda: q.q8_encode(ctx, fwd, bwd, X4, eo), inner=10, warmup=3)
         extra["gemv"] = gemv_bandwidth(torch, q, ctx, rng)
+        extra["read_stream_ceiling"] = {"25.6MB_warm": ceil_warm,
+                                        "25.6MB_cold": read_ceiling(torch, q, ctx, 25600000, cold=True),
+                                        "3.1MB_warm": read_ceiling(torch, q, ctx, 3145728, cold=False),
+                                        "3.1MB_cold": read_ceiling(torch, q, ctx, 3145728, cold=True)}
+        extra["mfma_products"] = mfma_products(torch, q, ctx, m, rng)
         extra["translate"] = translate_run(q, ctx, m, args.sentences)
         extra["steps_per_s_beam1"] = 1.0 / eager1
     cpu = None if (args.no_cpu_baseline or args.quick) else cpu_baseline(p)
@@ -313,7 +381,10 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "out_logits_kernel (50000x512 int8 weights, 5 hypotheses)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": None, "bytes_per_launch": out_bytes, "kernel_us": k_ms * 1e3, "samples": k_n,
-                     "regime": "warm: the same weights every step, served from the 256 MB Infinity Cache"},
+                     "regime": "warm: the same weights every step, served from the 256 MB Infinity Cache",
+                     "read_stream_ceiling_GBps": ceil_warm["GBps"], "read_stream_ceiling_us": ceil_warm["kernel_us"],
+                     "frac_of_read_stream_ceiling": ceil_warm["kernel_us"] / (k_ms * 1e3)},
+        "kernels_in_loop_us": ktimes,
         "cpu_baseline": cpu,
     }
     line.update(extra)

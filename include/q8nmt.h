@@ -243,14 +243,32 @@ size_t q8_translate_bytes(const q8_model *m, int max_l, int beam, int k, int max
 q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens, int l, int beam, int k,
                        int max_steps, int32_t *tokens_host, int *len_host, float *score_host, int *steps_host);
 
-/* Measurement helper (not an operation of the paper): between q8_profile_begin and
- * q8_profile_end, up to max_samples launches of the vocabulary-layer kernel of
- * output_logits_q8 carry a pair of HIP events that take the kernel's own begin and
- * end timestamps.  q8_profile_end waits for the stream and returns the average
+/* Measurement helpers (not operations of the paper).
+ *
+ * Between q8_profile_begin and q8_profile_end, up to max_samples launches of the
+ * kernels of one class carry a pair of HIP events that take the kernel's own begin
+ * and end timestamps.  q8_profile_end waits for the stream and returns the average
  * kernel duration in milliseconds and the number of samples (host pointers, may be
  * NULL).  Not for use under stream capture. */
-q8_status q8_profile_begin(q8_ctx *ctx, int max_samples);
+enum {
+    Q8_KERNEL_VOCAB = 0,     /* vocabulary projection of output_logits_q8 (Eq. 2) */
+    Q8_KERNEL_SELECT = 1,    /* log-softmax + top-k (+ fused beam update) */
+    Q8_KERNEL_GEMV = 2,      /* streaming product of q8_gemv / q8_gemm_narrow, n <= 8 */
+    Q8_KERNEL_GRU = 3,       /* GRU transition (encoder cell, decoder r and q) */
+    Q8_KERNEL_ATTENTION = 4, /* energies, softmax, context (Eqs. 5-6) */
+    Q8_KERNEL_READOUT = 5,   /* hidden layer g of Eq. 2 */
+    Q8_KERNEL_MFMA = 6,      /* matrix-core product of q8_gemm_narrow, n > 8 */
+    Q8_KERNEL_PROBE = 7,     /* q8_probe_read */
+    Q8_KERNEL_CLASSES = 8
+};
+q8_status q8_profile_begin(q8_ctx *ctx, int kernel_class, int max_samples);
 q8_status q8_profile_end(q8_ctx *ctx, float *avg_ms_host, int *samples_host);
+
+/* Enqueues a plain read stream over buf (device pointer, 16-byte aligned, bytes a
+ * positive multiple of 16): nothing is computed or written.  Timed with the profile
+ * calls above it gives the read bandwidth of whichever memory level holds buf, the
+ * ceiling the streaming kernels are compared with.  Uses 8 KiB of the workspace. */
+q8_status q8_probe_read(q8_ctx *ctx, const void *buf, size_t bytes);
 
 #ifdef __cplusplus
 }

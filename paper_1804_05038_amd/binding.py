@@ -15,7 +15,8 @@ _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 __all__ = ["Q8Error", "Context", "Mat", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
            "q8_quantize_matrix", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "gru_step_q8", "cgru_decoder_step_q8",
            "output_logits_q8", "output_logits_beam_q8", "q8_encode", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
-           "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "LIB_PATH"]
+           "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read",
+           "KERNEL_CLASSES", "LIB_PATH"]
 LIB_PATH = _LIB_PATH
 
 STATUS = {0: "Q8_OK", 1: "Q8_ERR_NULL", 2: "Q8_ERR_SHAPE", 3: "Q8_ERR_ALIGN", 4: "Q8_ERR_WORKSPACE", 5: "Q8_ERR_DEVICE"}
@@ -94,7 +95,8 @@ def load_library():
         lib.q8_translate_bytes.restype = C.c_size_t
         lib.q8_translate_bytes.argtypes = [C.POINTER(_Model), ci, ci, ci, ci]
         lib.q8_translate.argtypes = [vp, C.POINTER(_Model), vp, ci, ci, ci, ci, vp, ip, C.POINTER(C.c_float), ip]
-        lib.q8_profile_begin.argtypes = [vp, ci]
+        lib.q8_profile_begin.argtypes = [vp, ci, ci]
+        lib.q8_probe_read.argtypes = [vp, vp, C.c_size_t]
         lib.q8_profile_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int)]
         _lib = lib
     return _lib
@@ -316,8 +318,15 @@ def q8_encode(ctx, fwd, bwd, X, enc_h=None):
     return enc_h
 
 
-def q8_profile_begin(ctx, max_samples):
-    ctx.check(ctx.lib.q8_profile_begin(ctx.handle, max_samples))
+KERNEL_CLASSES = {"vocab": 0, "select": 1, "gemv": 2, "gru": 3, "attention": 4, "readout": 5, "mfma": 6, "probe": 7}
+
+
+def q8_profile_begin(ctx, kernel_class, max_samples):
+    ctx.check(ctx.lib.q8_profile_begin(ctx.handle, KERNEL_CLASSES[kernel_class], max_samples))
+
+
+def q8_probe_read(ctx, buf):
+    ctx.check(ctx.lib.q8_probe_read(ctx.handle, _ptr(buf), buf.numel() * buf.element_size()))
 
 
 def q8_profile_end(ctx):

@@ -99,6 +99,7 @@ q8_status q8_create(q8_ctx **out, void *hip_stream, void *workspace, size_t work
     c->err[0] = 0;
     c->prof_ev = nullptr;
     c->prof_cap = c->prof_n = 0;
+    c->prof_kind = Q8_KERNEL_VOCAB;
     c->ws_reserved_top = 0;
     q8_status st = q8i_fill_u32(c, c->ws, Q8_WS_HEADER / 4, 0u);
     if (st) { delete c; return st; }
@@ -114,9 +115,10 @@ q8_status q8_destroy(q8_ctx *ctx)
     return Q8_OK;
 }
 
-q8_status q8_profile_begin(q8_ctx *ctx, int max_samples)
+q8_status q8_profile_begin(q8_ctx *ctx, int kernel_class, int max_samples)
 {
     if (!ctx) return Q8_ERR_NULL;
+    if (kernel_class < 0 || kernel_class >= Q8_KERNEL_CLASSES) return q8_fail(ctx, Q8_ERR_SHAPE, "unknown kernel class %d", kernel_class);
     if (max_samples <= 0 || max_samples > 65536) return q8_fail(ctx, Q8_ERR_SHAPE, "max_samples outside [1, 65536]");
     if (ctx->prof_ev) q8_profile_end(ctx, nullptr, nullptr);
     ctx->prof_ev = (hipEvent_t *)calloc(2 * (size_t)max_samples, sizeof(hipEvent_t));
@@ -130,6 +132,7 @@ q8_status q8_profile_begin(q8_ctx *ctx, int max_samples)
         }
     ctx->prof_cap = max_samples;
     ctx->prof_n = 0;
+    ctx->prof_kind = kernel_class;
     return Q8_OK;
 }
 
@@ -169,6 +172,16 @@ q8_status q8_quantize_matrix(q8_ctx *ctx, const float *W, int rows, int cols, in
     if (!aligned16(Wq_out) || ld_out % 16 != 0)
         return q8_fail(ctx, Q8_ERR_ALIGN, "q8_quantize_matrix: output needs a 16-byte aligned base and ld_out %% 16 == 0");
     return q8i_quantize_matrix(ctx, W, rows, cols, ld_in, Wq_out, ld_out, scale_out_host);
+}
+
+q8_status q8_probe_read(q8_ctx *ctx, const void *buf, size_t bytes)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!buf) return q8_fail(ctx, Q8_ERR_NULL, "q8_probe_read: NULL buffer");
+    if (!aligned16(buf) || bytes % 16 != 0 || bytes == 0)
+        return q8_fail(ctx, Q8_ERR_ALIGN, "q8_probe_read needs a 16-byte aligned buffer and a positive multiple of 16 bytes");
+    if (ctx->ws_bytes < Q8_WS_HEADER + 2048 * 4) return q8_fail(ctx, Q8_ERR_WORKSPACE, "q8_probe_read: workspace too small");
+    return q8i_probe_read(ctx, buf, bytes);
 }
 
 size_t q8_tiles_bytes(int rows, int ld)

@@ -241,16 +241,16 @@ q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, 
     t.P = P; t.enc_h = enc_h; t.a = a; t.v = v; t.e = e; t.alpha = alpha; t.ctx = cvec;
     t.counters = (unsigned *)ctx->ws;
     t.l = l; t.A = A; t.C = C;
-    hipLaunchKernelGGL(attention_kernel, dim3(l, n), dim3(ATT_THREADS), 0, ctx->stream, t);
+    Q8_LAUNCH(ctx, Q8_KERNEL_ATTENTION, attention_kernel, dim3(l, n), dim3(ATT_THREADS), 0, t);
     return q8i_launch_check(ctx, "attention");
 }
 
 template <int N>
 static void launch_readout_n(q8_ctx *ctx, const ReadoutArgs &a, int blocks, size_t smem, int ch)
 {
-    if (ch == 1) hipLaunchKernelGGL((readout_fast_kernel<N, 1>), dim3(blocks), dim3(256), smem, ctx->stream, a);
-    else if (ch == 2) hipLaunchKernelGGL((readout_fast_kernel<N, 2>), dim3(blocks), dim3(256), smem, ctx->stream, a);
-    else hipLaunchKernelGGL(readout_kernel<N>, dim3(blocks), dim3(256), smem, ctx->stream, a);
+    if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_fast_kernel<N, 1>), dim3(blocks), dim3(256), smem, a);
+    else if (ch == 2) Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_fast_kernel<N, 2>), dim3(blocks), dim3(256), smem, a);
+    else Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, readout_kernel<N>, dim3(blocks), dim3(256), smem, a);
 }
 
 q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,

@@ -235,9 +235,9 @@ template <int N, int MODE>
 static void launch_gru_nm(q8_ctx *ctx, const GruJobs &jobs, int njobs, int blocks, size_t smem, int ch)
 {
     dim3 grid(blocks, njobs);
-    if (ch == 1) hipLaunchKernelGGL((gru_fast_kernel<N, MODE, 1>), grid, dim3(256), smem, ctx->stream, jobs);
-    else if (ch == 2) hipLaunchKernelGGL((gru_fast_kernel<N, MODE, 2>), grid, dim3(256), smem, ctx->stream, jobs);
-    else hipLaunchKernelGGL((gru_kernel<N, MODE>), grid, dim3(256), smem, ctx->stream, jobs);
+    if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_GRU, (gru_fast_kernel<N, MODE, 1>), grid, dim3(256), smem, jobs);
+    else if (ch == 2) Q8_LAUNCH(ctx, Q8_KERNEL_GRU, (gru_fast_kernel<N, MODE, 2>), grid, dim3(256), smem, jobs);
+    else Q8_LAUNCH(ctx, Q8_KERNEL_GRU, (gru_kernel<N, MODE>), grid, dim3(256), smem, jobs);
 }
 
 template <int N>

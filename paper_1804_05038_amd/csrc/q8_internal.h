@@ -3,6 +3,9 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#ifdef __HIPCC__
+#include <hip/hip_ext.h>
+#endif
 #include <stdarg.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -26,11 +29,26 @@ struct q8_ctx {
     char err[256];
     // kernel timing (q8_profile_begin / q8_profile_end): event pairs attached to dispatches
     hipEvent_t *prof_ev;
-    int prof_cap, prof_n;
+    int prof_cap, prof_n, prof_kind;
     // bytes at the top of the workspace held by a composite call (q8_translate) while it
     // issues other calls, which carve from the bottom
     size_t ws_reserved_top;
 };
+
+// Launch of a kernel of class `kind` (a Q8_KERNEL_* value).  While a profile of that class
+// is open the dispatch carries an event pair that takes the kernel's own begin and end
+// timestamps; otherwise it is an ordinary launch.
+#define Q8_LAUNCH(ctx, kind, kernel, grid, block, smem, ...)                                                   \
+    do {                                                                                                       \
+        q8_ctx *c_ = (ctx);                                                                                    \
+        if (c_->prof_ev && c_->prof_kind == (kind) && c_->prof_n < c_->prof_cap) {                             \
+            hipEvent_t e0_ = c_->prof_ev[2 * c_->prof_n], e1_ = c_->prof_ev[2 * c_->prof_n + 1];               \
+            ++c_->prof_n;                                                                                      \
+            hipExtLaunchKernelGGL(kernel, grid, block, smem, c_->stream, e0_, e1_, 0, __VA_ARGS__);            \
+        } else {                                                                                               \
+            hipLaunchKernelGGL(kernel, grid, block, smem, c_->stream, __VA_ARGS__);                            \
+        }                                                                                                      \
+    } while (0)
 
 static inline q8_status q8_fail(q8_ctx *ctx, q8_status code, const char *fmt, ...)
 {
@@ -83,6 +101,7 @@ q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, 
                         const float *v, int n, float *e, float *alpha, float *cvec);
 q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,
                       float *t_out, const q8_taps *taps3);
+q8_status q8i_probe_read(q8_ctx *ctx, const void *buf, size_t bytes);
 int q8i_out_tiles(int V);
 size_t q8i_tiles_bytes(int rows, int ld);
 q8_status q8i_pack_tiles(q8_ctx *ctx, const q8_mat *W, int8_t *tiles);

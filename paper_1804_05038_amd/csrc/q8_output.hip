@@ -6,6 +6,11 @@
 
 #include <hip/hip_ext.h>
 
+// The vocabulary matrix (25.6 MB at V = 50000) is read with the non-temporal hint: it is
+// used once per step and would otherwise push the decoder's other 17 MB of weights out of
+// the 32 MB of L2, which keeps them from one step to the next.
+#define Q8_WLOAD(p) __builtin_nontemporal_load(p)
+
 #define OUT_TILE 16                  // vocabulary rows per matrix-core tile = one selection group
 #define OUT_SB 16                    // tiles per thread of the selection kernel (256 threads)
 #ifndef OUT_BLOCKS
@@ -142,7 +147,7 @@ __device__ __forceinline__ void out_logits_body(const OutArgs &a)
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
                 av[s] = (v4i){0, 0, 0, 0};
-                if (it < items && kc * 512 + 64 * s < ld) av[s] = *(const v4i *)(wp + 1024 * s);
+                if (it < items && kc * 512 + 64 * s < ld) av[s] = Q8_WLOAD((const v4i *)(wp + 1024 * s));
             }
         } else {
             const int row = tile * OUT_TILE + i;
@@ -150,7 +155,7 @@ __device__ __forceinline__ void out_logits_body(const OutArgs &a)
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
                 av[s] = (v4i){0, 0, 0, 0};
-                if (it < items && row < a.V && kc * 512 + 64 * s + 16 * g < ld) av[s] = *(const v4i *)(wp + 64 * s);
+                if (it < items && row < a.V && kc * 512 + 64 * s + 16 * g < ld) av[s] = Q8_WLOAD((const v4i *)(wp + 64 * s));
             }
         }
     };
@@ -452,26 +457,14 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
 int q8i_out_tiles(int V) { return (V + OUT_TILE - 1) / OUT_TILE; }
 int q8i_out_max_rows(void) { return OUT_MAX_TILES * OUT_TILE; }
 
-#define Q8_LAUNCH_TIMED(kernel, nblk, block, smem, a)                                                     \
-    do {                                                                                                   \
-        if (ctx->prof_ev && ctx->prof_n < ctx->prof_cap) {                                                 \
-            /* timed dispatch: the two events take the kernel's own begin and end timestamps */            \
-            hipEvent_t e0 = ctx->prof_ev[2 * ctx->prof_n], e1 = ctx->prof_ev[2 * ctx->prof_n + 1];         \
-            ++ctx->prof_n;                                                                                 \
-            hipExtLaunchKernelGGL(kernel, dim3(nblk), dim3(block), smem, ctx->stream, e0, e1, 0, a);       \
-        } else {                                                                                           \
-            hipLaunchKernelGGL(kernel, dim3(nblk), dim3(block), smem, ctx->stream, a);                     \
-        }                                                                                                  \
-    } while (0)
-
 template <bool PACKED>
 static void launch_out_packed(q8_ctx *ctx, const OutArgs &a, int nblk, size_t smem, int ch)
 {
-    if (ch == 1 && a.ld <= 256) Q8_LAUNCH_TIMED((out_logits5_kernel<PACKED, 1>), nblk, 320, smem, a);
-    else if (ch == 1 && a.ld <= 512) Q8_LAUNCH_TIMED((out_logits5_kernel<PACKED, 2>), nblk, 320, smem, a);
-    else if (ch == 1) Q8_LAUNCH_TIMED((out_logits_kernel<1, PACKED>), nblk, 256, smem, a);
-    else if (ch == 2) Q8_LAUNCH_TIMED((out_logits_kernel<2, PACKED>), nblk, 256, smem, a);
-    else Q8_LAUNCH_TIMED((out_logits_kernel<4, PACKED>), nblk, 256, smem, a);
+    if (ch == 1 && a.ld <= 256) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits5_kernel<PACKED, 1>), dim3(nblk), dim3(320), smem, a);
+    else if (ch == 1 && a.ld <= 512) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits5_kernel<PACKED, 2>), dim3(nblk), dim3(320), smem, a);
+    else if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits_kernel<1, PACKED>), dim3(nblk), dim3(256), smem, a);
+    else if (ch == 2) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits_kernel<2, PACKED>), dim3(nblk), dim3(256), smem, a);
+    else Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits_kernel<4, PACKED>), dim3(nblk), dim3(256), smem, a);
 }
 
 size_t q8i_tiles_bytes(int rows, int ld) { return (size_t)q8i_out_tiles(rows) * OUT_TILE * (size_t)ld; }
@@ -515,6 +508,6 @@ q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const floa
     } else {
         memset(&s.bu, 0, sizeof(s.bu));
     }
-    hipLaunchKernelGGL(out_select_kernel, dim3(n), dim3(256), 0, ctx->stream, s);
+    Q8_LAUNCH(ctx, Q8_KERNEL_SELECT, out_select_kernel, dim3(n), dim3(256), 0, s);
     return q8i_launch_check(ctx, "output");
 }
