@@ -30,8 +30,10 @@
  *    anything is launched; nothing aborts or throws.  q8_last_error gives text.
  *  - Limits: 1 <= cols <= ld <= 16384 for products (the int32 sum cannot overflow
  *    below 133143 columns); narrow products take n <= 8 vectors in one pass over the
- *    weights and 8 < n <= 1024 on the MFMA path; GRU / decoder / output calls take
- *    1 <= n <= 8 hypotheses; source length l <= 1024; top-k <= 16.
+ *    weights and 8 < n <= 1024 on the matrix cores (blocked int8 GEMM); the same two
+ *    regimes hold for gru_step_q8 and output_logits_q8; cgru_decoder_step_q8 takes
+ *    n <= 8 hypotheses of one sentence, cgru_decoder_step_batch_q8 up to 1024 slots of
+ *    several sentences; source length l <= 1024; top-k <= 16.
  *  - Non-finite inputs give unspecified results (no fault).
  *  - A context is tied to one stream and one workspace and is not thread-safe.  Calls
  *    that use the workspace (everything but q8_gemv and n <= 8 q8_gemm_narrow) must
@@ -143,7 +145,8 @@ q8_status q8_gemm_narrow(q8_ctx *ctx, const q8_mat *W, const float *X, int n, in
  * r = sigmoid(gx_r + gh_r), z = sigmoid(gx_z + gh_z), n = tanh(gx_n + r * gh_n),
  * h' = (1 - z) * n + z * h (h in fp32).  x [n x I], h_prev [n x H], h_out [n x H]
  * (must not alias h_prev).  taps: NULL or two entries, [0] for the Wx product and
- * [1] for the Wh product. */
+ * [1] for the Wh product.  n <= 8: one fused streaming kernel; 8 < n <= 1024: both
+ * products on the matrix cores, then the gates; the values are the same. */
 q8_status gru_step_q8(q8_ctx *ctx, const q8_gru_weights *g, const float *x, const float *h_prev,
                       int n, float *h_out, const q8_taps *taps2);
 
@@ -165,11 +168,27 @@ q8_status cgru_decoder_step_q8(q8_ctx *ctx, const q8_cgru_weights *w, const floa
  * hypothesis, ordered by (logit descending, index ascending), are returned as
  * topk_idx [n x k] and topk_logp [n x k] = logit - lse.  logits [n x rows(W_out)],
  * lse [n] and t_out [n x R] may be NULL.  taps4: NULL or four entries for the products
- * W_s(s), W_y(y), W_c(ctx), W_out(t) (the first three unused when ro == NULL). */
+ * W_s(s), W_y(y), W_c(ctx), W_out(t) (the first three unused when ro == NULL).
+ * n_beam <= 8: streaming kernels.  8 < n_beam <= 1024 (hypotheses of many sentences): every
+ * product on the matrix cores; the [n x rows] logits are then always materialized (in
+ * the workspace when logits == NULL, which must have room for them). */
 q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
                            const float *s, const float *y_emb, const float *ctx_vec, const float *t_in,
                            int n_beam, int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx,
                            float *t_out, const q8_taps *taps4);
+
+/* The decoder step of Eq. 3-6 for several sentences side by side (batching is the extension
+ * Section 6 names).  Sentence s owns hypothesis slots [s beam, (s + 1) beam) of y_emb,
+ * s_prev, s_out [n x H], ctx_out [n x C] (n = n_sent * beam <= 1024) and rows
+ * [sent_off[s], sent_off[s + 1]) of P [L x A] and enc_h [L x C]; sent_off is a device
+ * array of n_sent + 1 int32, max_l the longest sentence (<= 1024).  alpha_out
+ * [n x max_l] (row pitch max_l, entries past the sentence's length untouched) and
+ * s_mid_out [n x H] may be NULL.  Per-vector quantization makes every slot's result
+ * the one cgru_decoder_step_q8 gives for that slot alone. */
+q8_status cgru_decoder_step_batch_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h,
+                                     const int32_t *sent_off, int n_sent, int beam, int max_l, const float *y_emb,
+                                     const float *s_prev, float *s_out, float *ctx_out, float *alpha_out,
+                                     float *s_mid_out);
 
 /* Bidirectional GRU encoder of Eq. 1 over l embedding vectors X [l x E]:
  * enc_h [l x 2H], backward state in columns [0,H), forward state in [H,2H); both
@@ -242,6 +261,35 @@ size_t q8_translate_bytes(const q8_model *m, int max_l, int beam, int k, int max
  * steps.  src_tokens: l device int32 ids in [0, V_src).  Results as q8_beam_result. */
 q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens, int l, int beam, int k,
                        int max_steps, int32_t *tokens_host, int *len_host, float *score_host, int *steps_host);
+
+/* Beam search for n_sent sentences side by side: states = n_sent consecutive search states
+ * of q8_beam_state_bytes(max_steps) bytes each; per-hypothesis tables hold sentence s in
+ * slots [s beam, (s + 1) beam).  The rules per sentence are those of q8_beam_update.
+ * done [n_sent] (device int32) is set to 1 for a sentence once its search is over; such a
+ * sentence's slots keep finite contents and are ignored.
+ * q8_beam_init_batch: sentence s starts from the backward encoder state at its first
+ * position, enc_h[sent_off[s], 0 .. H) (row pitch C), and token 0. */
+q8_status q8_beam_init_batch(q8_ctx *ctx, void *states, int n_sent, int beam, int max_steps, const float *enc_h,
+                             const int32_t *sent_off, int C, const float *E_tgt, int E, int H, float *y_emb, float *s,
+                             int32_t *done);
+q8_status q8_beam_update_batch(q8_ctx *ctx, void *states, int n_sent, int beam, int k, int max_steps,
+                               const float *topk_logp, const int32_t *topk_idx, const float *s_step, int H,
+                               const float *E_tgt, int E, float *y_emb, float *s_next, int32_t *done);
+/* Waits for the stream; sentence s's tokens go to tokens_host + s * max_steps; len_host,
+ * score_host, steps_host [n_sent] (host pointers, each may be NULL). */
+q8_status q8_beam_result_batch(q8_ctx *ctx, const void *states, int n_sent, int max_steps, int32_t *tokens_host,
+                               int *len_host, float *score_host, int *steps_host);
+
+/* Translates n_sent sentences together: src_tokens = their ids back to back (device),
+ * sent_off_host [n_sent + 1] their offsets (host, sent_off_host[0] = 0).  Encoders run
+ * sentence by sentence, the decoder steps for all sentences at once (n_sent * beam <= 1024
+ * slots) until every search is over or max_steps is reached.  Results as
+ * q8_beam_result_batch; each sentence's translation is the one q8_translate gives for it.
+ * Needs q8_translate_batch_bytes more workspace than q8_workspace_bytes(n_sent * beam, ...). */
+size_t q8_translate_batch_bytes(const q8_model *m, int total_l, int n_sent, int beam, int k, int max_steps);
+q8_status q8_translate_batch(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens, const int32_t *sent_off_host,
+                             int n_sent, int beam, int k, int max_steps, int32_t *tokens_host, int *len_host,
+                             float *score_host, int *steps_host);
 
 /* Measurement helpers (not operations of the paper).
  *

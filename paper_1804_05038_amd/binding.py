@@ -15,7 +15,8 @@ _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 __all__ = ["Q8Error", "Context", "Mat", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
            "q8_quantize_matrix", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "gru_step_q8", "cgru_decoder_step_q8",
            "output_logits_q8", "output_logits_beam_q8", "q8_encode", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
-           "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read",
+           "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "cgru_decoder_step_batch_q8", "q8_beam_init_batch",
+           "q8_beam_update_batch", "q8_beam_result_batch", "q8_translate_batch", "q8_translate_batch_bytes",
            "KERNEL_CLASSES", "LIB_PATH"]
 LIB_PATH = _LIB_PATH
 
@@ -97,6 +98,13 @@ def load_library():
         lib.q8_translate.argtypes = [vp, C.POINTER(_Model), vp, ci, ci, ci, ci, vp, ip, C.POINTER(C.c_float), ip]
         lib.q8_profile_begin.argtypes = [vp, ci, ci]
         lib.q8_probe_read.argtypes = [vp, vp, C.c_size_t]
+        lib.cgru_decoder_step_batch_q8.argtypes = [vp, C.POINTER(_Cgru), vp, vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+        lib.q8_beam_init_batch.argtypes = [vp, vp, ci, ci, ci, vp, vp, ci, vp, ci, ci, vp, vp, vp]
+        lib.q8_beam_update_batch.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, ci, vp, ci, vp, vp, vp]
+        lib.q8_beam_result_batch.argtypes = [vp, vp, ci, ci, vp, ip, C.POINTER(C.c_float), ip]
+        lib.q8_translate_batch_bytes.restype = C.c_size_t
+        lib.q8_translate_batch_bytes.argtypes = [C.POINTER(_Model), ci, ci, ci, ci, ci]
+        lib.q8_translate_batch.argtypes = [vp, C.POINTER(_Model), vp, ip, ci, ci, ci, ci, vp, ip, C.POINTER(C.c_float), ip]
         lib.q8_profile_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int)]
         _lib = lib
     return _lib
@@ -281,6 +289,28 @@ def cgru_decoder_step_q8(ctx, w, P, enc_h, y_emb, s_prev, out=None, taps=False, 
     return r
 
 
+def cgru_decoder_step_batch_q8(ctx, w, P, enc_h, sent_off, beam, max_l, y_emb, s_prev, out=None, bind=False):
+    """Decoder step for len(sent_off) - 1 sentences side by side; sent_off: device int32 offsets
+    into P / enc_h.  Returns dict(s, ctx, alpha [n x max_l], s_mid)."""
+    n = y_emb.shape[0]
+    S = sent_off.shape[0] - 1
+    assert n == S * beam
+    H, Cd = w.r.H, w.q.Wx.cols
+    o = out or {}
+    s_out = o["s"] if "s" in o else ctx.empty(n, H)
+    c_out = o["ctx"] if "ctx" in o else ctx.empty(n, Cd)
+    alpha = o["alpha"] if "alpha" in o else torch.zeros(n, max_l, dtype=torch.float32, device=ctx.device)
+    s_mid = o["s_mid"] if "s_mid" in o else ctx.empty(n, H)
+    args = (ctx.handle, C.byref(w.c), _ptr(P), _ptr(enc_h), _ptr(sent_off), S, beam, max_l, _ptr(y_emb), _ptr(s_prev),
+            _ptr(s_out), _ptr(c_out), _ptr(alpha), _ptr(s_mid))
+    r = {"s": s_out, "ctx": c_out, "alpha": alpha, "s_mid": s_mid}
+    if bind:
+        r["keep"] = (w, P, enc_h, sent_off, y_emb, s_prev)
+        return _Bound(ctx, ctx.lib.cgru_decoder_step_batch_q8, args, r)
+    ctx.check(ctx.lib.cgru_decoder_step_batch_q8(*args))
+    return r
+
+
 def output_logits_q8(ctx, ro, W_out, b_out, s=None, y_emb=None, ctx_vec=None, t_in=None, k=12,
                      want_logits=True, taps=False, bind=False):
     """Returns dict(logits?, lse, topk_logp, topk_idx, t?) (+ 'taps': four entries)."""
@@ -373,6 +403,53 @@ def q8_translate(ctx, model, src_tokens, beam=5, k=12, max_steps=100):
     ctx.check(ctx.lib.q8_translate(ctx.handle, C.byref(model.c), _ptr(src), src.shape[0], beam, k, max_steps,
                                    out, C.byref(n), C.byref(score), C.byref(steps)))
     return np.array(out[:n.value], dtype=np.int32), np.float32(score.value), steps.value
+
+
+def q8_translate_batch_bytes(model, total_l, n_sent, beam=5, k=12, max_steps=100):
+    return load_library().q8_translate_batch_bytes(C.byref(model.c), total_l, n_sent, beam, k, max_steps)
+
+
+def q8_translate_batch(ctx, model, sentences, beam=5, k=12, max_steps=100):
+    """Translates the sentences together; returns a list of (tokens ndarray, score, steps)."""
+    import numpy as np
+    S = len(sentences)
+    off = np.zeros(S + 1, dtype=np.int32)
+    off[1:] = np.cumsum([len(x) for x in sentences])
+    src = torch.as_tensor(np.concatenate([np.asarray(x, dtype=np.int32) for x in sentences])).to(ctx.device)
+    out = (C.c_int32 * (max_steps * S))()
+    n, steps, score = (C.c_int * S)(), (C.c_int * S)(), (C.c_float * S)()
+    ctx.check(ctx.lib.q8_translate_batch(ctx.handle, C.byref(model.c), _ptr(src), off.ctypes.data_as(C.POINTER(C.c_int)), S,
+                                         beam, k, max_steps, out, n, score, steps))
+    return [(np.array(out[i * max_steps:i * max_steps + n[i]], dtype=np.int32), np.float32(score[i]), steps[i])
+            for i in range(S)]
+
+
+def q8_beam_init_batch(ctx, states, n_sent, beam, max_steps, enc_h, sent_off, E_tgt, y_emb, s, done, bind=False):
+    args = (ctx.handle, _ptr(states), n_sent, beam, max_steps, _ptr(enc_h), _ptr(sent_off), enc_h.shape[1], _ptr(E_tgt),
+            E_tgt.shape[1], s.shape[1], _ptr(y_emb), _ptr(s), _ptr(done))
+    if bind:
+        return _Bound(ctx, ctx.lib.q8_beam_init_batch, args, {"keep": (states, enc_h, sent_off, E_tgt, y_emb, s, done)})
+    ctx.check(ctx.lib.q8_beam_init_batch(*args))
+
+
+def q8_beam_update_batch(ctx, states, n_sent, beam, max_steps, topk_logp, topk_idx, s_step, E_tgt, y_emb, s_next, done,
+                         bind=False):
+    k = topk_logp.shape[1]
+    args = (ctx.handle, _ptr(states), n_sent, beam, k, max_steps, _ptr(topk_logp), _ptr(topk_idx), _ptr(s_step),
+            s_step.shape[1], _ptr(E_tgt), E_tgt.shape[1], _ptr(y_emb), _ptr(s_next), _ptr(done))
+    if bind:
+        return _Bound(ctx, ctx.lib.q8_beam_update_batch, args,
+                      {"keep": (states, topk_logp, topk_idx, s_step, E_tgt, y_emb, s_next, done)})
+    ctx.check(ctx.lib.q8_beam_update_batch(*args))
+
+
+def q8_beam_result_batch(ctx, states, n_sent, max_steps):
+    import numpy as np
+    out = (C.c_int32 * (max_steps * n_sent))()
+    n, steps, score = (C.c_int * n_sent)(), (C.c_int * n_sent)(), (C.c_float * n_sent)()
+    ctx.check(ctx.lib.q8_beam_result_batch(ctx.handle, _ptr(states), n_sent, max_steps, out, n, score, steps))
+    return [(np.array(out[i * max_steps:i * max_steps + n[i]], dtype=np.int32), np.float32(score[i]), steps[i])
+            for i in range(n_sent)]
 
 
 def q8_beam_state_bytes(max_steps):

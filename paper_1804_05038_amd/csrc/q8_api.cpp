@@ -63,6 +63,26 @@ q8_status check_gru(q8_ctx *ctx, const q8_gru_weights *g, const char *name)
 
 #define TRY(expr) do { q8_status st_ = (expr); if (st_) return st_; } while (0)
 
+// ---- panels of more than 8 vectors: quantize, matrix-core products, element-wise tail ----
+
+// One GRU transition for n vectors (Eq. 1, 3, 4): h_out = GRU(x, h_prev).  gh_pre non-NULL:
+// the recurrent product (bias included) is already there and x alone is multiplied.
+q8_status gru_panel(q8_ctx *ctx, Carver &cv, const q8_gru_weights *g, const float *x, const float *h_prev, int n,
+                    const float *gh_pre, float *h_out, const q8_taps *taps2)
+{
+    const int I = g->Wx.cols, H = g->Wh.cols;
+    int8_t *xq = cv.take<int8_t>((size_t)n * g->Wx.ld), *hq = gh_pre ? nullptr : cv.take<int8_t>((size_t)n * g->Wh.ld);
+    float *xs = cv.take<float>(n), *hs = cv.take<float>(n);
+    float *gx = cv.take<float>((size_t)n * 3 * H), *gh = gh_pre ? nullptr : cv.take<float>((size_t)n * 3 * H);
+    if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "GRU panel: workspace too small");
+    const q8i_quant_job qj[2] = {{x, I, I, g->Wx.ld, xq, xs, taps2}, {h_prev, H, H, g->Wh.ld, hq, hs, taps2 ? taps2 + 1 : nullptr}};
+    TRY(q8i_quantize_jobs(ctx, qj, gh_pre ? 1 : 2, n));
+    const q8i_gemm_job gj[2] = {{&g->Wx, xq, xs, g->bx, gx, 3 * H, taps2 ? taps2[0].acc : nullptr, nullptr, nullptr},
+                                {&g->Wh, hq, hs, g->bh, gh, 3 * H, taps2 ? taps2[1].acc : nullptr, nullptr, nullptr}};
+    TRY(q8i_gemm_jobs(ctx, gj, gh_pre ? 1 : 2, n));
+    return q8i_gru_gates(ctx, gx, gh_pre ? gh_pre : gh, h_prev, H, h_out, H, H, n);
+}
+
 }  // namespace
 
 extern "C" {
@@ -233,13 +253,17 @@ q8_status gru_step_q8(q8_ctx *ctx, const q8_gru_weights *g, const float *x, cons
 {
     if (!ctx) return Q8_ERR_NULL;
     TRY(check_gru(ctx, g, "gru"));
-    if (n <= 0 || n > kMaxNarrow) return q8_fail(ctx, Q8_ERR_SHAPE, "n = %d outside [1, %d]", n, kMaxNarrow);
+    if (n <= 0 || n > kMaxMfmaN) return q8_fail(ctx, Q8_ERR_SHAPE, "n = %d outside [1, %d]", n, kMaxMfmaN);
     const int I = g->Wx.cols, H = g->Wh.cols;
     if (n > 1 && (I % 4 || H % 4)) return q8_fail(ctx, Q8_ERR_ALIGN, "batched vectors need dims %% 4 == 0");
     TRY(check_vecs(ctx, x, (I + 3) & ~3, I, "x"));
     TRY(check_vecs(ctx, h_prev, (H + 3) & ~3, H, "h_prev"));
     if (!h_out) return q8_fail(ctx, Q8_ERR_NULL, "h_out: NULL");
     if (h_out == h_prev) return q8_fail(ctx, Q8_ERR_SHAPE, "h_out must not alias h_prev");
+    if (n > kMaxNarrow) {
+        Carver cv(ctx);
+        return gru_panel(ctx, cv, g, x, h_prev, n, nullptr, h_out, taps2);
+    }
     if ((size_t)n * (g->Wx.ld + g->Wh.ld) > 65536) return q8_fail(ctx, Q8_ERR_SHAPE, "n * (ld_x + ld_h) exceeds 65536");
     q8i_gru_desc d = {g, x, I, h_prev, H, nullptr, 0, h_out, H, taps2};
     return q8i_gru(ctx, &d, 1, n, Q8I_GRU_FULL);
@@ -283,12 +307,60 @@ q8_status cgru_decoder_step_q8(q8_ctx *ctx, const q8_cgru_weights *w, const floa
                            {&qWh, s_mid, H, w->q.bh, ghq, 3 * H, taps5 ? taps5 + 4 : nullptr}};
     TRY(q8i_gemv_jobs(ctx, dj, 2, n));
     // Eq. 5-6: energies, weights, context
-    TRY(q8i_attention(ctx, P, enc_h, l, A, C, a, w->att_v, n, e, alpha_out, ctx_out));
+    TRY(q8i_attention(ctx, P, enc_h, l, A, C, a, w->att_v, n, e, alpha_out, ctx_out, nullptr, 0));
     // Eq. 4: s = q(H_t, s')
     q8_taps tq[2];
     if (taps5) { tq[0] = taps5[3]; tq[1].xq = nullptr; tq[1].xscale = nullptr; tq[1].acc = nullptr; }
     q8i_gru_desc dq = {&w->q, ctx_out, C, s_mid, H, ghq, 3 * H, s_out, H, taps5 ? tq : nullptr};
     return q8i_gru(ctx, &dq, 1, n, Q8I_GRU_GH_PRE);
+}
+
+q8_status cgru_decoder_step_batch_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h,
+                                     const int32_t *sent_off, int n_sent, int beam, int max_l, const float *y_emb,
+                                     const float *s_prev, float *s_out, float *ctx_out, float *alpha_out, float *s_mid_out)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!w) return q8_fail(ctx, Q8_ERR_NULL, "weights: NULL");
+    TRY(check_gru(ctx, &w->r, "r"));
+    TRY(check_gru(ctx, &w->q, "q"));
+    TRY(check_mat(ctx, &w->att_U, "att_U"));
+    const int H = w->r.Wh.cols, E = w->r.Wx.cols, C = w->q.Wx.cols, A = w->att_U.rows;
+    if (n_sent <= 0 || beam <= 0 || beam > Q8_MAX_BEAM || (long long)n_sent * beam > kMaxMfmaN)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "need n_sent > 0, 1 <= beam <= %d, n_sent * beam <= %d", Q8_MAX_BEAM, kMaxMfmaN);
+    const int n = n_sent * beam;
+    if (max_l <= 0 || max_l > kMaxL) return q8_fail(ctx, Q8_ERR_SHAPE, "max_l = %d outside [1, %d]", max_l, kMaxL);
+    if (w->q.Wh.cols != H || w->att_U.cols != H) return q8_fail(ctx, Q8_ERR_SHAPE, "hidden sizes of r, q and att_U differ");
+    if (E % 4 || H % 4 || C % 4 || A % 4) return q8_fail(ctx, Q8_ERR_ALIGN, "E, H, C, A must be multiples of 4");
+    if (!w->att_v || !P || !enc_h || !sent_off || !y_emb || !s_prev || !s_out || !ctx_out)
+        return q8_fail(ctx, Q8_ERR_NULL, "cgru_decoder_step_batch_q8: NULL argument");
+    if (!aligned16(w->att_v) || !aligned16(P) || !aligned16(enc_h) || !aligned16(y_emb) || !aligned16(s_prev) || !aligned16(s_out) || !aligned16(ctx_out))
+        return q8_fail(ctx, Q8_ERR_ALIGN, "cgru_decoder_step_batch_q8: fp32 buffers need 16-byte alignment");
+    if (s_out == s_prev) return q8_fail(ctx, Q8_ERR_SHAPE, "s_out must not alias s_prev");
+
+    Carver cv(ctx);
+    float *s_mid = s_mid_out ? s_mid_out : cv.take<float>((size_t)n * H);
+    float *a = cv.take<float>((size_t)n * A);
+    float *ghq = cv.take<float>((size_t)n * 3 * H);
+    float *e = cv.take<float>((size_t)n * max_l);
+    int8_t *mq_u = cv.take<int8_t>((size_t)n * w->att_U.ld), *mq_h = cv.take<int8_t>((size_t)n * w->q.Wh.ld);
+    float *ms_u = cv.take<float>(n), *ms_h = cv.take<float>(n);
+    if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "cgru_decoder_step_batch_q8: workspace too small");
+    // Eq. 3: s' = r(y, s_prev)
+    {
+        Carver sub = cv;
+        TRY(gru_panel(ctx, sub, &w->r, y_emb, s_prev, n, nullptr, s_mid, nullptr));
+    }
+    // everything that depends on s' alone: u(s') of Eq. 6 and the recurrent half of GRU q
+    const q8i_quant_job qj[2] = {{s_mid, H, H, w->att_U.ld, mq_u, ms_u, nullptr}, {s_mid, H, H, w->q.Wh.ld, mq_h, ms_h, nullptr}};
+    TRY(q8i_quantize_jobs(ctx, qj, 2, n));
+    const q8i_gemm_job gj[2] = {{&w->att_U, mq_u, ms_u, nullptr, a, A, nullptr, nullptr, nullptr},
+                                {&w->q.Wh, mq_h, ms_h, w->q.bh, ghq, 3 * H, nullptr, nullptr, nullptr}};
+    TRY(q8i_gemm_jobs(ctx, gj, 2, n));
+    // Eq. 5-6 per hypothesis, against the positions of its own sentence
+    TRY(q8i_attention(ctx, P, enc_h, max_l, A, C, a, w->att_v, n, e, alpha_out, ctx_out, sent_off, beam));
+    // Eq. 4: s = q(H_t, s')
+    Carver sub = cv;
+    return gru_panel(ctx, sub, &w->q, ctx_out, s_mid, n, ghq, s_out, nullptr);
 }
 
 static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
@@ -299,7 +371,8 @@ static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8
     if (!ctx) return Q8_ERR_NULL;
     TRY(check_mat(ctx, W_out, "W_out"));
     const int n = n_beam, R = W_out->cols, V = W_out->rows;
-    if (n <= 0 || n > kMaxNarrow) return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam = %d outside [1, %d]", n, kMaxNarrow);
+    if (n <= 0 || n > kMaxMfmaN) return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam = %d outside [1, %d]", n, kMaxMfmaN);
+    if (n > kMaxNarrow && beam) return q8_fail(ctx, Q8_ERR_SHAPE, "the fused beam update takes at most %d hypotheses", kMaxNarrow);
     if (k <= 0 || k > kMaxK || k > V) return q8_fail(ctx, Q8_ERR_SHAPE, "k = %d outside [1, min(%d, rows)]", k, kMaxK);
     if (V > q8i_out_max_rows()) return q8_fail(ctx, Q8_ERR_SHAPE, "W_out: more than %d rows", q8i_out_max_rows());
     if (W_out->ld > 4096) return q8_fail(ctx, Q8_ERR_SHAPE, "W_out: ld above 4096");
@@ -321,12 +394,8 @@ static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8
         if (!s || !y_emb || !ctx_vec) return q8_fail(ctx, Q8_ERR_NULL, "s, y_emb, ctx: NULL");
         if (!aligned16(s) || !aligned16(y_emb) || !aligned16(ctx_vec))
             return q8_fail(ctx, Q8_ERR_ALIGN, "s, y_emb, ctx need 16-byte alignment");
-        if ((size_t)n * (ro->W_s.ld + ro->W_y.ld + ro->W_c.ld) > 65536)
+        if (n <= kMaxNarrow && (size_t)n * (ro->W_s.ld + ro->W_y.ld + ro->W_c.ld) > 65536)
             return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam * (H + E + C) exceeds 65536");
-        float *t = t_out ? t_out : cv.take<float>((size_t)n * R);
-        if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
-        TRY(q8i_readout(ctx, ro, s, y_emb, ctx_vec, n, t, taps4));
-        T = t;
     } else {
         TRY(check_vecs(ctx, t_in, R, R, "t_in"));
     }
@@ -334,6 +403,39 @@ static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8
     float *pm = cv.take<float>(ngrp * n);
     double *ps = cv.take<double>(ngrp * n);
     float *lg = logits ? logits : cv.take<float>((size_t)n * V);    // the selection reads the logits back
+    if (n > kMaxNarrow) {
+        // panel path: codes of t from the combine kernel (or from t_in), then the blocked product
+        int8_t *tq = cv.take<int8_t>((size_t)n * W_out->ld);
+        float *tsc = cv.take<float>(n);
+        if (ro) {
+            const q8_mat *M[3] = {&ro->W_s, &ro->W_y, &ro->W_c};
+            const float *X[3] = {s, y_emb, ctx_vec};
+            float *t = t_out ? t_out : cv.take<float>((size_t)n * R);
+            q8i_quant_job qj[3];
+            q8i_gemm_job gj[3];
+            for (int u = 0; u < 3; ++u) {
+                int8_t *xq = cv.take<int8_t>((size_t)n * M[u]->ld);
+                float *xs = cv.take<float>(n), *part = cv.take<float>((size_t)n * R);
+                qj[u] = {X[u], M[u]->cols, M[u]->cols, M[u]->ld, xq, xs, taps4 ? taps4 + u : nullptr};
+                gj[u] = {M[u], xq, xs, nullptr, part, R, taps4 ? taps4[u].acc : nullptr, nullptr, nullptr};
+            }
+            if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
+            TRY(q8i_quantize_jobs(ctx, qj, 3, n));
+            TRY(q8i_gemm_jobs(ctx, gj, 3, n));
+            TRY(q8i_readout_combine(ctx, gj[0].Y, gj[1].Y, gj[2].Y, ro->b_t, R, n, t, W_out->ld, tq, tsc, taps4 ? taps4 + 3 : nullptr));
+        } else {
+            if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
+            const q8i_quant_job qj = {t_in, R, R, W_out->ld, tq, tsc, taps4 ? taps4 + 3 : nullptr};
+            TRY(q8i_quantize_jobs(ctx, &qj, 1, n));
+        }
+        return q8i_output_codes(ctx, W_out, b_out, tq, tsc, n, k, lg, lse, topk_logp, topk_idx, taps4 ? taps4[3].acc : nullptr, pm, ps);
+    }
+    if (ro) {
+        float *t = t_out ? t_out : cv.take<float>((size_t)n * R);
+        if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
+        TRY(q8i_readout(ctx, ro, s, y_emb, ctx_vec, n, t, taps4));
+        T = t;
+    }
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
     return q8i_output(ctx, W_out, b_out, T, R, n, k, lg, lse, topk_logp, topk_idx, taps4 ? taps4 + 3 : nullptr, pm, ps,
                       beam);
@@ -392,8 +494,12 @@ q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights
         q8i_gemv_desc d[2] = {{&fwd->Wx, X, E, fwd->bx, gxf, 3 * H, nullptr}, {&bwd->Wx, X, E, bwd->bx, gxb, 3 * H, nullptr}};
         TRY(q8i_gemv_jobs(ctx, d, 2, l));
     } else {
-        TRY(q8i_gemm_mfma(ctx, &fwd->Wx, X, l, E, fwd->bx, gxf, 3 * H, nullptr, xq, xs));
-        TRY(q8i_gemm_mfma(ctx, &bwd->Wx, X, l, E, bwd->bx, gxb, 3 * H, nullptr, xq, xs));
+        if (fwd->Wx.ld != bwd->Wx.ld) return q8_fail(ctx, Q8_ERR_SHAPE, "q8_encode: the two Wx need the same ld");
+        const q8i_quant_job qj = {X, E, E, fwd->Wx.ld, xq, xs, nullptr};            // one quantization serves both
+        TRY(q8i_quantize_jobs(ctx, &qj, 1, l));
+        const q8i_gemm_job gj[2] = {{&fwd->Wx, xq, xs, fwd->bx, gxf, 3 * H, nullptr, nullptr, nullptr},
+                                    {&bwd->Wx, xq, xs, bwd->bx, gxb, 3 * H, nullptr, nullptr, nullptr}};
+        TRY(q8i_gemm_jobs(ctx, gj, 2, l));
     }
     // l sequential recurrent steps, both directions in each launch
     for (int t = 0; t < l; ++t) {
@@ -513,6 +619,158 @@ q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens
             st = q8i_beam_read(ctx, state, max_steps, nullptr, nullptr, nullptr, nullptr, &done);
     }
     if (!st) st = q8i_beam_read(ctx, state, max_steps, tokens_host, len_host, score_host, steps_host, nullptr);
+    ctx->ws_reserved_top = 0;
+    return st;
+}
+
+// ---------------------------------------------------------------- sentences side by side ----
+
+q8_status q8_beam_init_batch(q8_ctx *ctx, void *states, int n_sent, int beam, int max_steps, const float *enc_h,
+                             const int32_t *sent_off, int C, const float *E_tgt, int E, int H, float *y_emb, float *s,
+                             int32_t *done)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!states || !enc_h || !sent_off || !E_tgt || !y_emb || !s || !done)
+        return q8_fail(ctx, Q8_ERR_NULL, "q8_beam_init_batch: NULL argument");
+    if (n_sent <= 0 || beam <= 0 || beam > Q8_MAX_BEAM || (long long)n_sent * beam > kMaxMfmaN || max_steps <= 0 || E <= 0 ||
+        H <= 0 || C < H)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "q8_beam_init_batch: bad sizes");
+    return q8i_beam_batch(ctx, 1, states, q8i_beam_state_bytes(max_steps), n_sent, beam, 0, max_steps, nullptr, nullptr,
+                          nullptr, E_tgt, E, H, y_emb, s, done, enc_h, sent_off, C);
+}
+
+q8_status q8_beam_update_batch(q8_ctx *ctx, void *states, int n_sent, int beam, int k, int max_steps,
+                               const float *topk_logp, const int32_t *topk_idx, const float *s_step, int H,
+                               const float *E_tgt, int E, float *y_emb, float *s_next, int32_t *done)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!states || !topk_logp || !topk_idx || !s_step || !E_tgt || !y_emb || !s_next || !done)
+        return q8_fail(ctx, Q8_ERR_NULL, "q8_beam_update_batch: NULL argument");
+    if (n_sent <= 0 || beam <= 0 || beam > Q8_MAX_BEAM || (long long)n_sent * beam > kMaxMfmaN || k < beam || k > kMaxK ||
+        max_steps <= 0 || E <= 0 || H <= 0)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "q8_beam_update_batch: bad sizes");
+    if (s_next == s_step) return q8_fail(ctx, Q8_ERR_SHAPE, "s_next must not alias s_step");
+    return q8i_beam_batch(ctx, 0, states, q8i_beam_state_bytes(max_steps), n_sent, beam, k, max_steps, topk_logp, topk_idx,
+                          s_step, E_tgt, E, H, y_emb, s_next, done, nullptr, nullptr, 0);
+}
+
+q8_status q8_beam_result_batch(q8_ctx *ctx, const void *states, int n_sent, int max_steps, int32_t *tokens_host,
+                               int *len_host, float *score_host, int *steps_host)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!states || n_sent <= 0 || max_steps <= 0) return q8_fail(ctx, Q8_ERR_NULL, "q8_beam_result_batch: bad argument");
+    return q8i_beam_read_batch(ctx, states, q8i_beam_state_bytes(max_steps), n_sent, max_steps, tokens_host, len_host,
+                               score_host, steps_host);
+}
+
+namespace {
+struct BatchBufs {
+    size_t X, enc_h, P, off, y, s0, s1, cv, lp, idx, done, states, total;
+};
+BatchBufs batch_layout(const q8_model *m, int total_l, int n_sent, int beam, int k, int max_steps)
+{
+    const size_t E = m->E, H = m->dec.r.Wh.cols, C = m->dec.q.Wx.cols, A = m->dec.att_U.rows, n = (size_t)n_sent * beam;
+    BatchBufs b;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += up256(bytes); return at; };
+    b.X = take((size_t)total_l * E * 4); b.enc_h = take((size_t)total_l * C * 4); b.P = take((size_t)total_l * A * 4);
+    b.off = take((size_t)(n_sent + 1) * 4);
+    b.y = take(n * E * 4); b.s0 = take(n * H * 4); b.s1 = take(n * H * 4);
+    b.cv = take(n * C * 4); b.lp = take(n * k * 4); b.idx = take(n * k * 4);
+    b.done = take((size_t)n_sent * 4);
+    b.states = take(q8i_beam_state_bytes(max_steps) * n_sent);
+    b.total = o;
+    return b;
+}
+}  // namespace
+
+size_t q8_translate_batch_bytes(const q8_model *m, int total_l, int n_sent, int beam, int k, int max_steps)
+{
+    if (!m || total_l < 1 || n_sent < 1 || beam < 1 || k < 1 || max_steps < 1) return 0;
+    return batch_layout(m, total_l, n_sent, beam, k, max_steps).total;
+}
+
+q8_status q8_translate_batch(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens, const int32_t *sent_off_host,
+                             int n_sent, int beam, int k, int max_steps, int32_t *tokens_host, int *len_host,
+                             float *score_host, int *steps_host)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!m || !src_tokens || !sent_off_host || !m->E_src || !m->E_tgt)
+        return q8_fail(ctx, Q8_ERR_NULL, "q8_translate_batch: NULL argument");
+    TRY(check_gru(ctx, &m->enc_fwd, "enc_fwd"));
+    TRY(check_gru(ctx, &m->dec.r, "dec.r"));
+    TRY(check_gru(ctx, &m->dec.q, "dec.q"));
+    TRY(check_mat(ctx, &m->att_W, "att_W"));
+    TRY(check_mat(ctx, &m->dec.att_U, "att_U"));
+    const int E = m->E, H = m->dec.r.Wh.cols, C = m->dec.q.Wx.cols, A = m->dec.att_U.rows;
+    if (beam <= 0 || beam > Q8_MAX_BEAM || k < beam || k > kMaxK || max_steps <= 0)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "need 1 <= beam <= %d, beam <= k <= %d, max_steps > 0", Q8_MAX_BEAM, kMaxK);
+    if (n_sent <= 0 || (long long)n_sent * beam > kMaxMfmaN)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "need 1 <= n_sent and n_sent * beam <= %d", kMaxMfmaN);
+    if (m->enc_fwd.Wx.cols != E || m->dec.r.Wx.cols != E || 2 * m->enc_fwd.Wh.cols != C || m->att_W.cols != C ||
+        m->att_W.rows != A || m->enc_fwd.Wh.cols != H)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "q8_translate_batch: model dimensions are inconsistent");
+    int max_l = 0;
+    if (sent_off_host[0] != 0) return q8_fail(ctx, Q8_ERR_SHAPE, "sent_off[0] must be 0");
+    for (int s = 0; s < n_sent; ++s) {
+        const int l = sent_off_host[s + 1] - sent_off_host[s];
+        if (l <= 0 || l > kMaxL) return q8_fail(ctx, Q8_ERR_SHAPE, "sentence %d: length %d outside [1, %d]", s, l, kMaxL);
+        if (l > max_l) max_l = l;
+    }
+    const int total_l = sent_off_host[n_sent];
+    if (ctx->ws_reserved_top) return q8_fail(ctx, Q8_ERR_WORKSPACE, "q8_translate_batch is not re-entrant");
+    const BatchBufs b = batch_layout(m, total_l, n_sent, beam, k, max_steps);
+    if (b.total + Q8_WS_HEADER > ctx->ws_bytes) return q8_fail(ctx, Q8_ERR_WORKSPACE, "q8_translate_batch: workspace too small");
+    char *top = ctx->ws + ((ctx->ws_bytes - b.total) & ~(size_t)255);
+    float *X = (float *)(top + b.X), *enc_h = (float *)(top + b.enc_h), *P = (float *)(top + b.P);
+    int32_t *off = (int32_t *)(top + b.off), *done = (int32_t *)(top + b.done);
+    float *y = (float *)(top + b.y), *sv[2] = {(float *)(top + b.s0), (float *)(top + b.s1)};
+    float *cvec = (float *)(top + b.cv), *lp = (float *)(top + b.lp);
+    int32_t *idx = (int32_t *)(top + b.idx);
+    void *states = top + b.states;
+    const int n = n_sent * beam;
+    ctx->ws_reserved_top = ctx->ws_bytes - (size_t)(top - ctx->ws);
+
+    q8_status st = Q8_OK;
+    if (hipMemcpyAsync(off, sent_off_host, sizeof(int32_t) * (n_sent + 1), hipMemcpyHostToDevice, ctx->stream) != hipSuccess)
+        st = q8_fail(ctx, Q8_ERR_DEVICE, "q8_translate_batch: offsets copy failed");
+    if (!st) st = q8i_gather_rows(ctx, m->E_src, src_tokens, total_l, E, X);                   // x_i of Eq. 1
+    for (int s = 0; s < n_sent && !st; ++s) {                                                  // Eq. 1, sentence by sentence
+        const int o = sent_off_host[s], l = sent_off_host[s + 1] - o;
+        st = q8_encode(ctx, &m->enc_fwd, &m->enc_bwd, X + (size_t)o * E, l, enc_h + (size_t)o * C);
+    }
+    // w(h_i) of Eq. 6 for every position of every sentence (per-vector quantization: the
+    // same values as sentence by sentence), in panels of at most 1024 positions
+    for (int o = 0; o < total_l && !st; o += kMaxMfmaN) {
+        const int cnt = total_l - o < kMaxMfmaN ? total_l - o : kMaxMfmaN;
+        st = q8_gemm_narrow(ctx, &m->att_W, enc_h + (size_t)o * C, cnt, C, m->att_b, P + (size_t)o * A, A, nullptr);
+    }
+    if (!st) st = q8_beam_init_batch(ctx, states, n_sent, beam, max_steps, enc_h, off, C, m->E_tgt, E, H, y, sv[0], done);
+    int cur = 0;
+    bool all_done = false;
+    int32_t *done_host = (int32_t *)malloc(sizeof(int32_t) * n_sent);
+    if (!done_host && !st) st = q8_fail(ctx, Q8_ERR_DEVICE, "out of host memory");
+    for (int t = 0; t < max_steps && !st && !all_done; ++t) {
+        if (n <= kMaxNarrow && n_sent == 1) {
+            st = cgru_decoder_step_q8(ctx, &m->dec, P, enc_h, total_l, y, sv[cur], n, sv[cur ^ 1], cvec, nullptr, nullptr, nullptr);
+        } else {
+            st = cgru_decoder_step_batch_q8(ctx, &m->dec, P, enc_h, off, n_sent, beam, max_l, y, sv[cur], sv[cur ^ 1], cvec,
+                                            nullptr, nullptr);
+        }
+        if (!st) st = output_impl(ctx, &m->ro, &m->W_out, m->b_out, sv[cur ^ 1], y, cvec, nullptr, n, k, nullptr, nullptr, lp,
+                                  idx, nullptr, nullptr, nullptr);
+        if (!st) st = q8_beam_update_batch(ctx, states, n_sent, beam, k, max_steps, lp, idx, sv[cur ^ 1], H, m->E_tgt, E, y,
+                                           sv[cur], done);
+        if (!st && (t % 8 == 7)) {
+            hipError_t e = hipMemcpyAsync(done_host, done, sizeof(int32_t) * n_sent, hipMemcpyDeviceToHost, ctx->stream);
+            if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+            if (e != hipSuccess) st = q8_fail(ctx, Q8_ERR_DEVICE, "q8_translate_batch: %s", hipGetErrorString(e));
+            all_done = true;
+            for (int s = 0; s < n_sent && !st; ++s) all_done = all_done && done_host[s] != 0;
+        }
+    }
+    free(done_host);
+    if (!st) st = q8_beam_result_batch(ctx, states, n_sent, max_steps, tokens_host, len_host, score_host, steps_host);
     ctx->ws_reserved_top = 0;
     return st;
 }

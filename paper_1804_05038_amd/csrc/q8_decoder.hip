@@ -9,6 +9,10 @@ struct AttArgs {
     float *e, *alpha, *ctx;
     unsigned *counters;     // one arrival counter per hypothesis, zero on entry and on exit
     int l, A, C;
+    // several sentences side by side: hypothesis b belongs to sentence b / beam, whose rows of
+    // P and enc_h are [sent_off[s], sent_off[s + 1]); NULL = one sentence of l positions
+    const int *sent_off;
+    int beam, lde;          // lde: row pitch of e and alpha
 };
 
 // Block (i, b), 1024 threads: energy e[b, i] = sum_j v_j tanh(P[i, j] + a[b, j]) (Eq. 6).
@@ -22,7 +26,16 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
     __shared__ int s_last;
     const int i = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     Q8_STAMP(0);
-    const float *Pi = a.P + (size_t)i * a.A;
+    int l = a.l;
+    const float *P = a.P, *enc_h = a.enc_h;
+    if (a.sent_off) {
+        const int s = b / a.beam, o = a.sent_off[s];
+        l = a.sent_off[s + 1] - o;
+        if (i >= l) return;                  // the grid spans the longest sentence
+        P += (size_t)o * a.A;
+        enc_h += (size_t)o * a.C;
+    }
+    const float *Pi = P + (size_t)i * a.A;
     const float *ab = a.a + (size_t)b * a.A;
     double acc = 0.0;
     for (int j = tid; j < a.A; j += ATT_THREADS) acc += (double)a.v[j] * (double)tanh_rn(Pi[j] + ab[j]);
@@ -37,10 +50,10 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
         // Publish the energy with a device-coherent store, wait until it has been performed,
         // then count the arrival with a device-coherent atomic: the block that sees the last
         // count can read every energy with device-coherent loads, no cache flush needed.
-        __hip_atomic_store(&a.e[(size_t)b * a.l + i], (float)tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&a.e[(size_t)b * a.lde + i], (float)tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): the store above has been performed
         const unsigned prev = __hip_atomic_fetch_add(&a.counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = (prev == (unsigned)a.l - 1u);
+        s_last = (prev == (unsigned)l - 1u);
     }
     __syncthreads();
     Q8_STAMP(2);
@@ -48,9 +61,8 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
     if (tid == 0 && b == 0) q8_trace_stamp(16);
 
     // softmax over the l energies of hypothesis b: one wave, lane t holds e[t], e[t+64], ...
-    const int l = a.l;
     if (wave == 0) {
-        const float *e = a.e + (size_t)b * l;
+        const float *e = a.e + (size_t)b * a.lde;
         float mx = -INFINITY;
         for (int t = lane; t < l; t += 64) {
             const float ev = __hip_atomic_load(e + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -64,7 +76,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
         for (int t = lane; t < l; t += 64) {
             const float al = (float)(exp((double)s_alpha[t] - (double)mx) / Z);
             s_alpha[t] = al;
-            if (a.alpha) a.alpha[(size_t)b * l + t] = al;
+            if (a.alpha) a.alpha[(size_t)b * a.lde + t] = al;
         }
         if (lane == 0) __hip_atomic_store(&a.counters[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -74,7 +86,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
     if ((a.C & 1) == 0) {
         for (int c = tid * 2; c < a.C; c += 2 * ATT_THREADS) {
             double s0 = 0.0, s1 = 0.0;
-            const float *h = a.enc_h + c;
+            const float *h = enc_h + c;
 #pragma unroll 10
             for (int t = 0; t < l; ++t) {
                 const float2 hv = *(const float2 *)(h + (size_t)t * a.C);
@@ -87,7 +99,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
     } else {
         for (int c = tid; c < a.C; c += ATT_THREADS) {
             double s = 0.0;
-            for (int t = 0; t < l; ++t) s += (double)s_alpha[t] * (double)a.enc_h[(size_t)t * a.C + c];
+            for (int t = 0; t < l; ++t) s += (double)s_alpha[t] * (double)enc_h[(size_t)t * a.C + c];
             a.ctx[(size_t)b * a.C + c] = (float)s;
         }
     }
@@ -232,15 +244,55 @@ __global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
     }
 }
 
+// Panels of more than 8 hypotheses: the three products of g's first layer came from the
+// matrix cores (no bias); block j adds them in the order of the fused kernels, applies tanh,
+// and quantizes t_j for the vocabulary product.
+__global__ __launch_bounds__(256) void readout_combine_kernel(const float *__restrict__ ts, const float *__restrict__ ty,
+                                                              const float *__restrict__ tc, const float *__restrict__ b_t,
+                                                              int R, float *t_out, int ld, int8_t *tq, float *tscale,
+                                                              int8_t *tap_xq, float *tap_scale)
+{
+    __shared__ float s_scale[1];
+    __shared__ float s_red[4];
+    const int j = blockIdx.x;
+    for (int u = threadIdx.x; u < R; u += 256) {
+        const size_t o = (size_t)j * R + u;
+        float p = ts[o] + ty[o];
+        p = p + tc[o];
+        if (b_t) p = p + b_t[u];
+        t_out[o] = tanh_rn(p);
+    }
+    __syncthreads();                          // this block's t_j is read back below
+    block_quantize<1>(t_out + (size_t)j * R, 1, R, R, ld, tq + (size_t)j * ld, s_scale, s_red);
+    if (threadIdx.x == 0) {
+        tscale[j] = s_scale[0];
+        if (tap_scale) tap_scale[j] = s_scale[0];
+    }
+    if (tap_xq) {
+        __syncthreads();
+        for (int k = threadIdx.x; k < R; k += 256) tap_xq[(size_t)j * R + k] = tq[(size_t)j * ld + k];
+    }
+}
+
 // =================================================================== host launchers ==
 
+q8_status q8i_readout_combine(q8_ctx *ctx, const float *ts, const float *ty, const float *tc, const float *b_t, int R,
+                              int n, float *t_out, int ld, int8_t *tq, float *tscale, const q8_taps *tap)
+{
+    Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, readout_combine_kernel, dim3(n), dim3(256), 0, ts, ty, tc, b_t, R, t_out, ld, tq,
+              tscale, tap ? tap->xq : nullptr, tap ? tap->xscale : nullptr);
+    return q8i_launch_check(ctx, "readout combine");
+}
+
+
 q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, int A, int C, const float *a,
-                        const float *v, int n, float *e, float *alpha, float *cvec)
+                        const float *v, int n, float *e, float *alpha, float *cvec, const int *sent_off, int beam)
 {
     AttArgs t;
     t.P = P; t.enc_h = enc_h; t.a = a; t.v = v; t.e = e; t.alpha = alpha; t.ctx = cvec;
     t.counters = (unsigned *)ctx->ws;
     t.l = l; t.A = A; t.C = C;
+    t.sent_off = sent_off; t.beam = beam; t.lde = l;
     Q8_LAUNCH(ctx, Q8_KERNEL_ATTENTION, attention_kernel, dim3(l, n), dim3(ATT_THREADS), 0, t);
     return q8i_launch_check(ctx, "attention");
 }

@@ -229,7 +229,31 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
 }
 Q8_TRACE_READER(q8_trace_gru)
 
-// =================================================================== host launcher ==
+// Gates alone, for panels of more than 8 vectors whose two products came from the matrix
+// cores: gx, gh [n x 3H] (biases included), one thread per (vector, hidden unit).
+__global__ __launch_bounds__(256) void gru_gates_kernel(const float *__restrict__ gx, const float *__restrict__ gh,
+                                                        const float *__restrict__ h_prev, int ldh, float *h_out, int ldo,
+                                                        int H, int n)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)n * H) return;
+    const int j = (int)(idx / H), u = (int)(idx - (size_t)j * H);
+    const float *x = gx + (size_t)j * 3 * H + u, *h = gh + (size_t)j * 3 * H + u;
+    const float xv[3] = {x[0], x[H], x[2 * H]}, hv[3] = {h[0], h[H], h[2 * H]};
+    h_out[(size_t)j * ldo + u] = gru_gates(xv, hv, h_prev[(size_t)j * ldh + u]);
+}
+
+// =================================================================== host launchers ==
+
+q8_status q8i_gru_gates(q8_ctx *ctx, const float *gx, const float *gh, const float *h_prev, int ldh, float *h_out,
+                        int ldo, int H, int n)
+{
+    const size_t total = (size_t)n * H;
+    Q8_LAUNCH(ctx, Q8_KERNEL_GRU, gru_gates_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, gx, gh, h_prev, ldh,
+              h_out, ldo, H, n);
+    return q8i_launch_check(ctx, "gru gates");
+}
+
 
 template <int N, int MODE>
 static void launch_gru_nm(q8_ctx *ctx, const GruJobs &jobs, int njobs, int blocks, size_t smem, int ch)

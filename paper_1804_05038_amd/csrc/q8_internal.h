@@ -16,11 +16,13 @@
 #include "q8_device.h"
 #endif
 
-// Workspace header: arrival counters [0, 2048), scratch slots (max bits, scale) at 2048.
+// Workspace header: one attention arrival counter per hypothesis [0, 4096), the counter of
+// the fused selection + beam update at 4096, scratch slots (max bits, scale) at 6144.
 #define Q8_MAX_BEAM 8
-#define Q8_WS_HEADER 4096
-#define Q8_WS_SCRATCH_SLOT 2048
-#define Q8_WS_SELECT_COUNTER 1024   // arrival counter of the fused selection + beam update
+#define Q8_MAX_COLS 1024            // vectors of one batched call
+#define Q8_WS_HEADER 8192
+#define Q8_WS_SELECT_COUNTER 4096
+#define Q8_WS_SCRATCH_SLOT 6144
 
 struct q8_ctx {
     hipStream_t stream;
@@ -96,9 +98,41 @@ q8_status q8i_quantize_matrix(q8_ctx *ctx, const float *W, int rows, int cols, i
 q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n);
 q8_status q8i_gemm_mfma(q8_ctx *ctx, const q8_mat *W, const float *X, int n, int ldx, const float *bias, float *Y,
                         int ldy, const q8_taps *taps, int8_t *xq, float *xscale);
+struct q8i_quant_job {          // quantization of n vectors X [n x ldx] (K floats each) into xq [n x ld], xscale [n]
+    const float *X;
+    int K, ldx, ld;
+    int8_t *xq;
+    float *xscale;
+    const q8_taps *taps;
+};
+struct q8i_gemm_job {           // Y [n x ldy] = dequantize(W . xq) + bias on the matrix cores
+    const q8_mat *W;
+    const int8_t *xq;
+    const float *xscale;
+    const float *bias;
+    float *Y;
+    int ldy;
+    int32_t *tap_acc;
+    float *part_max;            // vocabulary layer: per-tile softmax statistics [n x ceil(rows / 16)]
+    double *part_sum;
+};
+q8_status q8i_quantize_jobs(q8_ctx *ctx, const q8i_quant_job *d, int njobs, int n);   // njobs <= 3
+q8_status q8i_gemm_jobs(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n);        // njobs <= 3
 q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode);
 q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, int A, int C, const float *a,
-                        const float *v, int n, float *e, float *alpha, float *cvec);
+                        const float *v, int n, float *e, float *alpha, float *cvec, const int *sent_off, int beam);
+q8_status q8i_gru_gates(q8_ctx *ctx, const float *gx, const float *gh, const float *h_prev, int ldh, float *h_out,
+                        int ldo, int H, int n);
+q8_status q8i_readout_combine(q8_ctx *ctx, const float *ts, const float *ty, const float *tc, const float *b_t, int R,
+                              int n, float *t_out, int ld, int8_t *tq, float *tscale, const q8_taps *tap);
+q8_status q8i_output_codes(q8_ctx *ctx, const q8_mat *W, const float *bias, const int8_t *tq, const float *tscale, int n,
+                           int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx, int32_t *tap_acc,
+                           float *part_max, double *part_sum);
+q8_status q8i_beam_batch(q8_ctx *ctx, int init, void *states, size_t stride, int S, int beam, int k, int max_steps,
+                         const float *topk_logp, const int *topk_idx, const float *s_step, const float *E_tgt, int E,
+                         int H, float *y_emb, float *s_next, int *done, const float *enc_h, const int *sent_off, int C);
+q8_status q8i_beam_read_batch(q8_ctx *ctx, const void *states, size_t stride, int S, int max_steps, int32_t *tokens_host,
+                              int *len_host, float *score_host, int *steps_host);
 q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,
                       float *t_out, const q8_taps *taps3);
 q8_status q8i_probe_read(q8_ctx *ctx, const void *buf, size_t bytes);

@@ -478,6 +478,26 @@ q8_status q8i_pack_tiles(q8_ctx *ctx, const q8_mat *W, int8_t *tiles)
     return q8i_launch_check(ctx, "pack_tiles");
 }
 
+static q8_status launch_select(q8_ctx *ctx, const float *part_max, const double *part_sum, const float *logits, int V,
+                               int n, int k, float *lse, float *topk_logp, int32_t *topk_idx, const q8i_beam_desc *beam)
+{
+    SelectArgs s;
+    s.part_max = part_max; s.part_sum = part_sum; s.logits = logits;
+    s.lse = lse; s.topk_logp = topk_logp; s.topk_idx = topk_idx;
+    s.ntiles = q8i_out_tiles(V); s.n = n; s.k = k; s.V = V; s.ldl = V;
+    s.fuse_update = beam ? 1 : 0;
+    s.counter = (unsigned *)(ctx->ws + Q8_WS_SELECT_COUNTER);
+    if (beam) {
+        BeamUpdateArgs bu = {(BeamState *)beam->state, topk_logp, topk_idx, beam->s_step, beam->E_tgt, beam->y_emb,
+                             beam->s_next, n, k, beam->E, beam->H};
+        s.bu = bu;
+    } else {
+        memset(&s.bu, 0, sizeof(s.bu));
+    }
+    Q8_LAUNCH(ctx, Q8_KERNEL_SELECT, out_select_kernel, dim3(n), dim3(256), 0, s);
+    return q8i_launch_check(ctx, "output");
+}
+
 q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const float *T, int ldt, int n, int k,
                      float *logits, float *lse, float *topk_logp, int32_t *topk_idx, const q8_taps *taps,
                      float *part_max, double *part_sum, const q8i_beam_desc *beam)
@@ -495,19 +515,18 @@ q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const floa
     const int ch = q8_fast_ch(a.ld);
     if (a.tiles) launch_out_packed<true>(ctx, a, nblk, smem, ch);
     else launch_out_packed<false>(ctx, a, nblk, smem, ch);
-    SelectArgs s;
-    s.part_max = part_max; s.part_sum = part_sum; s.logits = logits;
-    s.lse = lse; s.topk_logp = topk_logp; s.topk_idx = topk_idx;
-    s.ntiles = a.ntiles; s.n = n; s.k = k; s.V = a.V; s.ldl = a.ldl;
-    s.fuse_update = beam ? 1 : 0;
-    s.counter = (unsigned *)(ctx->ws + Q8_WS_SELECT_COUNTER);
-    if (beam) {
-        BeamUpdateArgs bu = {(BeamState *)beam->state, topk_logp, topk_idx, beam->s_step, beam->E_tgt, beam->y_emb,
-                             beam->s_next, n, k, beam->E, beam->H};
-        s.bu = bu;
-    } else {
-        memset(&s.bu, 0, sizeof(s.bu));
-    }
-    Q8_LAUNCH(ctx, Q8_KERNEL_SELECT, out_select_kernel, dim3(n), dim3(256), 0, s);
-    return q8i_launch_check(ctx, "output");
+    return launch_select(ctx, part_max, part_sum, logits, a.V, n, k, lse, topk_logp, topk_idx, beam);
 }
+
+// Vocabulary layer for more than 8 hypotheses, from the codes of t: the blocked matrix-core
+// product (which also leaves the per-tile softmax statistics), then the same selection.
+q8_status q8i_output_codes(q8_ctx *ctx, const q8_mat *W, const float *bias, const int8_t *tq, const float *tscale, int n,
+                           int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx, int32_t *tap_acc,
+                           float *part_max, double *part_sum)
+{
+    const q8i_gemm_job gj = {W, tq, tscale, bias, logits, W->rows, tap_acc, part_max, part_sum};
+    q8_status st = q8i_gemm_jobs(ctx, &gj, 1, n);
+    if (st) return st;
+    return launch_select(ctx, part_max, part_sum, logits, W->rows, n, k, lse, topk_logp, topk_idx, nullptr);
+}
+

@@ -209,81 +209,6 @@ Q8_TRACE_READER(q8_trace_products)
 
 // ================================================ narrow product on the matrix cores ==
 
-// One block per vector: quantize X[j] into global xq[j * ld ..] (pad zeroed), scale[j].
-__global__ __launch_bounds__(256) void quantize_rows_kernel(const float *__restrict__ X, int K, int ldx, int ld,
-                                                            int8_t *xq, float *xscale, int8_t *tap_xq)
-{
-    __shared__ float s_scale[1];
-    __shared__ float s_red[4];
-    const int j = blockIdx.x;
-    block_quantize<1>(X + (size_t)j * ldx, 1, K, ldx, ld, xq + (size_t)j * ld, s_scale, s_red);
-    if (threadIdx.x == 0) xscale[j] = s_scale[0];
-    if (tap_xq) {
-        __threadfence_block();
-        for (int k = threadIdx.x; k < K; k += blockDim.x) tap_xq[(size_t)j * K + k] = xq[(size_t)j * ld + k];
-    }
-}
-
-struct MfmaArgs {
-    const int8_t *W;
-    const int8_t *xq;      // [n x ld] int8, global
-    const float *xscale;   // [n]
-    const float *bias;
-    float *Y;
-    int32_t *tap_acc;
-    int rows, ld, n, ldy;
-    float w_scale;
-};
-
-// Y[j, row] for 16-row x 16-vector tiles on v_mfma_i32_16x16x64_i8.  Operand A = 16
-// weight rows x 64 k (lane: row lane%16, 16 consecutive k at 16*(lane/16)); operand B =
-// 64 k x 16 vectors with the same k split, so any internal k order cancels.  Result:
-// lane holds rows 4*(lane/16)+r, r = 0..3, of vector lane%16.
-template <int NT>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(MfmaArgs a)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int i = lane & 15, g = lane >> 4;
-    const int r0 = (blockIdx.x * 4 + wave) * 16;
-    if (r0 >= a.rows) return;
-    const int ld = a.ld;
-    const bool row_ok = r0 + i < a.rows;
-    const int8_t *wp = a.W + (size_t)(r0 + i) * ld + 16 * g;
-    for (int ct = 0; ct * 16 < a.n; ct += NT) {
-        v4i acc[NT];
-#pragma unroll
-        for (int t = 0; t < NT; ++t) acc[t] = (v4i){0, 0, 0, 0};
-        for (int k0 = 0; k0 < ld; k0 += 64) {
-            const bool k_ok = k0 + 16 * g < ld;
-            v4i av = (v4i){0, 0, 0, 0};
-            if (row_ok && k_ok) av = *(const v4i *)(wp + k0);
-#pragma unroll
-            for (int t = 0; t < NT; ++t) {
-                const int col = (ct + t) * 16 + i;
-                v4i bv = (v4i){0, 0, 0, 0};
-                if (col < a.n && k_ok) bv = *(const v4i *)(a.xq + (size_t)col * ld + k0 + 16 * g);
-                acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bv, acc[t], 0, 0, 0);
-            }
-        }
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const int col = (ct + t) * 16 + i;
-            if (col >= a.n) continue;
-            const float c = a.w_scale * a.xscale[col];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int row = r0 + 4 * g + r;
-                if (row < a.rows) {
-                    float y = (float)acc[t][r] * c;
-                    if (a.bias) y = y + a.bias[row];
-                    a.Y[(size_t)col * a.ldy + row] = y;
-                    if (a.tap_acc) a.tap_acc[(size_t)col * a.rows + row] = acc[t][r];
-                }
-            }
-        }
-    }
-}
-
 // ==================================================================== read probe ==
 // Measurement aid: a plain read stream over `chunks` 16-byte pieces, every wave-wide
 // load one contiguous KiB, eight loads in flight per lane, nothing computed but an xor.
@@ -409,25 +334,4 @@ q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
     default: launch_gemv_n<8>(ctx, jobs, blocks, smem, ch); break;
     }
     return q8i_launch_check(ctx, "gemv");
-}
-
-q8_status q8i_gemm_mfma(q8_ctx *ctx, const q8_mat *W, const float *X, int n, int ldx, const float *bias, float *Y,
-                        int ldy, const q8_taps *taps, int8_t *xq, float *xscale)
-{
-    hipLaunchKernelGGL(quantize_rows_kernel, dim3(n), dim3(256), 0, ctx->stream, X, W->cols, ldx, W->ld, xq, xscale,
-                       taps ? taps->xq : nullptr);
-    if (taps && taps->xscale) {
-        hipError_t e = hipMemcpyAsync(taps->xscale, xscale, sizeof(float) * n, hipMemcpyDeviceToDevice, ctx->stream);
-        if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "tap copy: %s", hipGetErrorString(e));
-    }
-    MfmaArgs a;
-    a.W = W->data; a.xq = xq; a.xscale = xscale; a.bias = bias; a.Y = Y;
-    a.tap_acc = taps ? taps->acc : nullptr;
-    a.rows = W->rows; a.ld = W->ld; a.n = n; a.ldy = ldy; a.w_scale = W->scale;
-    const int blocks = (W->rows + 63) / 64;
-    const int tiles = (n + 15) / 16;
-    if (tiles == 1) Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, gemm_mfma_kernel<1>, dim3(blocks), dim3(256), 0, a);
-    else if (tiles == 2) Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, gemm_mfma_kernel<2>, dim3(blocks), dim3(256), 0, a);
-    else Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, gemm_mfma_kernel<4>, dim3(blocks), dim3(256), 0, a);
-    return q8i_launch_check(ctx, "gemm_mfma");
 }

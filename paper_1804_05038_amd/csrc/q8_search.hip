@@ -32,7 +32,7 @@ struct BeamInitArgs {
     int beam, max_steps, E, H;
 };
 
-__global__ __launch_bounds__(256) void beam_init_kernel(BeamInitArgs a)
+__device__ __forceinline__ void beam_init_body(const BeamInitArgs &a)
 {
     BeamState *st = a.st;
     if (threadIdx.x == 0) {
@@ -45,6 +45,48 @@ __global__ __launch_bounds__(256) void beam_init_kernel(BeamInitArgs a)
     // the first are not live; they only need finite contents)
     for (int e = threadIdx.x; e < a.beam * a.E; e += blockDim.x) a.y_emb[e] = a.E_tgt[e % a.E];
     for (int e = threadIdx.x; e < a.beam * a.H; e += blockDim.x) a.s[e] = a.s0[e % a.H];
+}
+
+__global__ __launch_bounds__(256) void beam_init_kernel(BeamInitArgs a)
+{
+    beam_init_body(a);
+}
+
+// Several sentences side by side: block s runs sentence s, whose beam occupies slots
+// [s beam, (s + 1) beam) of every per-hypothesis table.
+struct BeamBatchArgs {
+    char *states;
+    size_t stride;               // bytes between the states of consecutive sentences
+    const float *topk_logp;
+    const int *topk_idx;
+    const float *s_step, *E_tgt;
+    float *y_emb, *s_next;
+    int *done;                   // [S]: 1 once the sentence's search is over
+    const float *enc_h;          // initialization: encoder states, sentence s starts at row sent_off[s]
+    const int *sent_off;
+    int beam, k, E, H, C, max_steps;
+};
+
+__global__ __launch_bounds__(256) void beam_update_batch_kernel(BeamBatchArgs b)
+{
+    const int s = blockIdx.x;
+    const size_t slot = (size_t)s * b.beam;
+    BeamUpdateArgs a = {(BeamState *)(b.states + (size_t)s * b.stride), b.topk_logp + slot * b.k, b.topk_idx + slot * b.k,
+                        b.s_step + slot * b.H, b.E_tgt, b.y_emb + slot * b.E, b.s_next + slot * b.H, b.beam, b.k, b.E, b.H};
+    beam_update_body<false>(a);
+    __syncthreads();
+    if (threadIdx.x == 0) b.done[s] = a.st->done;
+}
+
+__global__ __launch_bounds__(256) void beam_init_batch_kernel(BeamBatchArgs b)
+{
+    const int s = blockIdx.x;
+    const size_t slot = (size_t)s * b.beam;
+    // initial decoder state: the backward encoder state at the sentence's first position
+    BeamInitArgs a = {(BeamState *)(b.states + (size_t)s * b.stride), b.enc_h + (size_t)b.sent_off[s] * b.C, b.E_tgt,
+                      b.y_emb + slot * b.E, b.s_next + slot * b.H, b.beam, b.max_steps, b.E, b.H};
+    beam_init_body(a);
+    if (threadIdx.x == 0) b.done[s] = 0;
 }
 
 // =================================================================== host launchers ==
@@ -71,15 +113,22 @@ q8_status q8i_beam_update(q8_ctx *ctx, void *state, const float *topk_logp, cons
     return q8i_launch_check(ctx, "beam_update");
 }
 
-q8_status q8i_beam_read(q8_ctx *ctx, const void *state, int max_steps, int32_t *tokens_host, int *len_host,
-                        float *score_host, int *steps_host, int *done_host)
+q8_status q8i_beam_batch(q8_ctx *ctx, int init, void *states, size_t stride, int S, int beam, int k, int max_steps,
+                         const float *topk_logp, const int *topk_idx, const float *s_step, const float *E_tgt, int E,
+                         int H, float *y_emb, float *s_next, int *done, const float *enc_h, const int *sent_off, int C)
 {
-    const size_t bytes = q8i_beam_state_bytes(max_steps);
-    BeamState *h = (BeamState *)malloc(bytes);
-    if (!h) return q8_fail(ctx, Q8_ERR_DEVICE, "out of host memory");
-    hipError_t e = hipMemcpyAsync(h, state, bytes, hipMemcpyDeviceToHost, ctx->stream);
-    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
-    if (e != hipSuccess) { free(h); return q8_fail(ctx, Q8_ERR_DEVICE, "beam read: %s", hipGetErrorString(e)); }
+    BeamBatchArgs b = {(char *)states, stride, topk_logp, topk_idx, s_step, E_tgt, y_emb, s_next, done, enc_h, sent_off,
+                       beam, k, E, H, C, max_steps};
+    if (init) hipLaunchKernelGGL(beam_init_batch_kernel, dim3(S), dim3(256), 0, ctx->stream, b);
+    else hipLaunchKernelGGL(beam_update_batch_kernel, dim3(S), dim3(256), 0, ctx->stream, b);
+    return q8i_launch_check(ctx, init ? "beam init (batch)" : "beam update (batch)");
+}
+
+// Rebuilds a finished search from a host copy of its state: the best finished hypothesis,
+// else the best live one, by following the back-pointers from its last token.
+static void parse_state(const BeamState *h, int32_t *tokens_host, int *len_host, float *score_host, int *steps_host,
+                        int *done_host)
+{
     int len, slot;
     if (h->have_fin) {
         len = h->fin_len;
@@ -90,7 +139,7 @@ q8_status q8i_beam_read(q8_ctx *ctx, const void *state, int max_steps, int32_t *
         slot = 0;
         if (score_host) *score_host = h->n_live > 0 ? h->score[0] : 0.0f;
     }
-    for (int t = len - 1; t >= 0; --t) {          // follow the back-pointers from the last token
+    for (int t = len - 1; t >= 0; --t) {
         const int e = h->link[(size_t)t * Q8_MAX_BEAM + slot];
         if (tokens_host) tokens_host[t] = e & 0xFFFFFF;
         slot = (e >> 24) & 0xF;
@@ -98,6 +147,35 @@ q8_status q8i_beam_read(q8_ctx *ctx, const void *state, int max_steps, int32_t *
     if (len_host) *len_host = len;
     if (steps_host) *steps_host = h->step;
     if (done_host) *done_host = h->done;
+}
+
+// All S states in one copy; sentence s's tokens go to tokens_host + s * max_steps.
+q8_status q8i_beam_read_batch(q8_ctx *ctx, const void *states, size_t stride, int S, int max_steps, int32_t *tokens_host,
+                              int *len_host, float *score_host, int *steps_host)
+{
+    char *h = (char *)malloc(stride * S);
+    if (!h) return q8_fail(ctx, Q8_ERR_DEVICE, "out of host memory");
+    hipError_t e = hipMemcpyAsync(h, states, stride * S, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) { free(h); return q8_fail(ctx, Q8_ERR_DEVICE, "beam read: %s", hipGetErrorString(e)); }
+    for (int s = 0; s < S; ++s)
+        parse_state((const BeamState *)(h + (size_t)s * stride), tokens_host ? tokens_host + (size_t)s * max_steps : nullptr,
+                    len_host ? len_host + s : nullptr, score_host ? score_host + s : nullptr,
+                    steps_host ? steps_host + s : nullptr, nullptr);
+    free(h);
+    return Q8_OK;
+}
+
+q8_status q8i_beam_read(q8_ctx *ctx, const void *state, int max_steps, int32_t *tokens_host, int *len_host,
+                        float *score_host, int *steps_host, int *done_host)
+{
+    const size_t bytes = q8i_beam_state_bytes(max_steps);
+    BeamState *h = (BeamState *)malloc(bytes);
+    if (!h) return q8_fail(ctx, Q8_ERR_DEVICE, "out of host memory");
+    hipError_t e = hipMemcpyAsync(h, state, bytes, hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) { free(h); return q8_fail(ctx, Q8_ERR_DEVICE, "beam read: %s", hipGetErrorString(e)); }
+    parse_state(h, tokens_host, len_host, score_host, steps_host, done_host);
     free(h);
     return Q8_OK;
 }

@@ -1,0 +1,173 @@
+"""GPU parity of the panel / batched paths (more than 8 vectors, hypotheses of several sentences
+side by side; Section 6's "batching"): every product on the int8 matrix cores.
+
+Per-vector quantization makes a panel's result for vector j the result of the single-vector
+call, so each case is checked twice: against the oracle (codes and sums bit-exact through the
+taps, floats to 1e-5) and against this library's own streaming kernels (bit for bit).
+"""
+import numpy as np
+import pytest
+import torch
+
+from parity import assert_close, assert_same, np_, gpu_gru, gpu_mat
+from workloads import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def q():
+    import paper_1804_05038_amd as q
+    return q
+
+
+@pytest.fixture(scope="module")
+def ctx(q):
+    return q.Context(workspace_bytes=q.q8_workspace_bytes(max_n=160, max_l=256, max_rows=50000, max_ld=2048) + (64 << 20))
+
+
+def _check_product(oracle, L, x_gpu, tap, j, what):
+    xq, xs = oracle.quantize(x_gpu)
+    assert_same(tap["xq"][j], xq, what + " xq")
+    assert float(tap["xscale"][j]) == float(xs), what + " xscale"
+    acc = oracle.accumulate(L.Wq, L.cols, xq)
+    assert_same(tap["acc"][j], acc, what + " acc")
+    return oracle.dequantize(acc, L.scale, xs, L.bias)
+
+
+@pytest.mark.parametrize("I,H,n", [(512, 1024, 9), (512, 1024, 70), (2048, 1024, 33), (36, 20, 12), (620, 1000, 17),
+                                   (256, 256, 130)])
+def test_gru_step_panel(q, ctx, oracle, I, H, n):
+    p = synth.gru_cell(seed=0, I=I, H=H, n_batch=n)
+    p["x"] = p["x"] * np.random.default_rng(n).uniform(0.1, 10, (n, 1)).astype(np.float32)
+    g = oracle.QGru(p["Wx"], p["Wh"], p["bx"], p["bh"])
+    G = q.GruWeights(gpu_mat(q, ctx, p["Wx"]), gpu_mat(q, ctx, p["Wh"]), ctx.f32(p["bx"]), ctx.f32(p["bh"]))
+    x, h0 = ctx.f32(p["x"]), ctx.f32(p["h_prev"])
+    h, taps = q.gru_step_q8(ctx, G, x, h0, taps=True)
+    for j in range(0, n, max(1, n // 7)):
+        gx = _check_product(oracle, g.Wx, p["x"][j], taps[0], j, "Wx")
+        gh = _check_product(oracle, g.Wh, p["h_prev"][j], taps[1], j, "Wh")
+        assert_close(h[j], oracle.gru_gates(gx, gh, p["h_prev"][j]), "h' (teacher-forced)")
+        assert_close(h[j], g.step(p["x"][j], p["h_prev"][j]), "h' (free-running)")
+    assert_same(q.gru_step_q8(ctx, G, x, h0), np_(h), "no taps")
+    # the streaming kernel on groups of at most 8 vectors gives the same bits
+    for j0 in (0, n - 5):
+        assert_same(q.gru_step_q8(ctx, G, x[j0:j0 + 5].contiguous(), h0[j0:j0 + 5].contiguous()), np_(h)[j0:j0 + 5],
+                    "panel vs streaming kernel")
+
+
+@pytest.mark.parametrize("V,R,n,k", [(50000, 512, 20, 12), (300, 64, 9, 12), (1000, 512, 130, 5), (33658, 640, 11, 12),
+                                     (129, 48, 40, 16)])
+def test_output_layer_panel_given_t(q, ctx, oracle, V, R, n, k):
+    p = synth.output_layer(seed=2, V=V, R=R, n_beam=n)
+    L = oracle.QLinear(p["out.W"], p["out.b"])
+    W = gpu_mat(q, ctx, p["out.W"])
+    t = ctx.f32(p["t"])
+    r = q.output_logits_q8(ctx, None, W, ctx.f32(p["out.b"]), t_in=t, k=k, taps=True)
+    tap = r["taps"][3]
+    for j in range(0, n, max(1, n // 6)):
+        logits_ref = _check_product(oracle, L, p["t"][j], tap, j, "W_out")
+        assert_same(r["logits"][j], logits_ref, "logits")
+        lse, lp, idx = oracle.logsoftmax_topk(logits_ref, k)
+        assert_close(r["lse"][j:j + 1], np.array([lse]), "lse")
+        assert_same(r["topk_idx"][j], idx, "top-k indices")
+        assert_close(r["topk_logp"][j], lp, "top-k logp")
+    r2 = q.output_logits_q8(ctx, None, W, ctx.f32(p["out.b"]), t_in=t, k=k, want_logits=False)
+    assert_same(r2["topk_idx"], np_(r["topk_idx"]), "logits in the workspace: same top-k")
+    r8 = q.output_logits_q8(ctx, None, W, ctx.f32(p["out.b"]), t_in=t[:8].contiguous(), k=k)
+    assert_same(r8["logits"], np_(r["logits"])[:8], "panel vs streaming kernel: logits")
+    assert_same(r8["topk_idx"], np_(r["topk_idx"])[:8], "panel vs streaming kernel: top-k")
+    assert_same(r8["topk_logp"], np_(r["topk_logp"])[:8])
+
+
+def test_output_layer_panel_with_readout(q, ctx, oracle):
+    n = 23
+    p = synth.full_model(seed=4, V=3000, E=512, H=1024, A=64, R=512)
+    m = oracle.OracleModel(p)
+    rng = np.random.default_rng(n)
+    s, y, c = (rng.standard_normal((n, d)).astype(np.float32) for d in (1024, 512, 2048))
+    ro = q.ReadoutWeights(gpu_mat(q, ctx, p["ro.Ws"]), gpu_mat(q, ctx, p["ro.Wy"]), gpu_mat(q, ctx, p["ro.Wc"]),
+                          ctx.f32(p["ro.b"]))
+    W = gpu_mat(q, ctx, p["out.W"])
+    r = q.output_logits_q8(ctx, ro, W, ctx.f32(p["out.b"]), s=ctx.f32(s), y_emb=ctx.f32(y), ctx_vec=ctx.f32(c),
+                           k=12, taps=True)
+    T = r["taps"]
+    Ls = oracle.QLinear(p["ro.Ws"])
+    for j in range(0, n, 4):
+        u1 = _check_product(oracle, Ls, s[j], T[0], j, "W_s")
+        u2 = _check_product(oracle, m.ro_y, y[j], T[1], j, "W_y")
+        u3 = _check_product(oracle, m.ro_c, c[j], T[2], j, "W_c")
+        pre = ((u1 + u2) + u3) + p["ro.b"]
+        t_gpu = np_(r["t"])[j]
+        assert_close(t_gpu, np.tanh(pre.astype(np.float64)).astype(np.float32), "t (teacher-forced)")
+        assert_close(t_gpu, m.readout(s[j], y[j], c[j]), "t (free-running)")
+        logits = _check_product(oracle, m.out, t_gpu, T[3], j, "W_out")
+        lse, lp, idx = oracle.logsoftmax_topk(logits, 12)
+        assert_same(r["topk_idx"][j], idx); assert_close(r["topk_logp"][j], lp)
+    r5 = q.output_logits_q8(ctx, ro, W, ctx.f32(p["out.b"]), s=ctx.f32(s[:5]), y_emb=ctx.f32(y[:5]), ctx_vec=ctx.f32(c[:5]), k=12)
+    assert_same(r5["t"], np_(r["t"])[:5], "panel vs streaming kernels: t")
+    assert_same(r5["topk_idx"], np_(r["topk_idx"])[:5]); assert_same(r5["topk_logp"], np_(r["topk_logp"])[:5])
+
+
+@pytest.mark.parametrize("E,H,A,lens,beam", [(512, 1024, 1024, (30, 11, 50), 5), (36, 40, 28, (7, 1, 3, 12), 3),
+                                             (64, 64, 64, (5, 300), 2), (512, 1024, 1024, (9,) * 26, 5)])
+def test_cgru_decoder_step_batch(q, ctx, oracle, E, H, A, lens, beam):
+    S, L, n = len(lens), sum(lens), len(lens) * beam
+    p = synth.cgru_step(seed=1, E=E, H=H, A=A, l=L, n_beam=n)
+    m = oracle.OracleModel(p)
+    w = q.CgruWeights(gpu_gru(q, ctx, p, "dec_r"), gpu_mat(q, ctx, p["att.U"]), ctx.f32(p["att.v"]), gpu_gru(q, ctx, p, "dec_q"))
+    enc_h = ctx.f32(p["enc_h"])
+    P = q.q8_gemm_narrow(ctx, gpu_mat(q, ctx, p["att.W"]), enc_h, ctx.f32(p["att.b"]))
+    P_ref = m.attention_precompute(p["enc_h"])
+    assert_same(P, P_ref, "P")
+    off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    y, s0 = ctx.f32(p["y_emb"]), ctx.f32(p["s_prev"])
+    r = q.cgru_decoder_step_batch_q8(ctx, w, P, enc_h, torch.tensor(off, device=ctx.device), beam, max(lens), y, s0)
+    for si in range(S):
+        lo, hi, sl = off[si], off[si + 1], slice(si * beam, (si + 1) * beam)
+        # the single-sentence entry point on this sentence's slots: the same bits
+        r1 = q.cgru_decoder_step_q8(ctx, w, P[lo:hi].contiguous(), enc_h[lo:hi].contiguous(), y[sl].contiguous(), s0[sl].contiguous())
+        for key in ("s_mid", "ctx", "s"):
+            assert_same(r[key][sl], np_(r1[key]), "sentence %d %s vs single-sentence call" % (si, key))
+        assert_same(r["alpha"][sl, :hi - lo], np_(r1["alpha"]), "alpha")
+        # and the oracle, free-running, on the sentence's first and last slot
+        for j in (si * beam, (si + 1) * beam - 1):
+            sm_o, al_o, cx_o, s_o = m.cgru_step(P_ref[lo:hi], p["enc_h"][lo:hi], p["y_emb"][j], p["s_prev"][j])
+            assert_close(r["s_mid"][j], sm_o, "s'"); assert_close(r["alpha"][j, :hi - lo], al_o, "alpha")
+            assert_close(r["ctx"][j], cx_o, "H_t"); assert_close(r["s"][j], s_o, "s")
+    r2 = q.cgru_decoder_step_batch_q8(ctx, w, P, enc_h, torch.tensor(off, device=ctx.device), beam, max(lens), y, s0)
+    assert_same(r2["s"], np_(r["s"]), "second call: arrival counters back at zero")
+
+
+def _translate_all(q, ctx, m_gpu, m_ref, sents, beam, k, max_steps):
+    got = q.q8_translate_batch(ctx, m_gpu, sents, beam=beam, k=k, max_steps=max_steps)
+    finished = 0
+    for src, (toks, score, steps) in zip(sents, got):
+        r_toks, r_score, r_steps = m_ref.translate(src, beam=beam, topk=k, max_steps=max_steps)
+        assert toks.tolist() == r_toks.tolist(), (src.tolist(), toks.tolist(), r_toks.tolist())
+        assert abs(float(score) - float(r_score)) <= 1e-5 * max(1.0, abs(float(r_score)))
+        assert steps == r_steps               # a finished sentence stops counting while the batch runs on
+        t1, s1, st1 = q.q8_translate(ctx, m_gpu, src, beam=beam, k=k, max_steps=max_steps)
+        assert t1.tolist() == toks.tolist() and np.float32(s1) == np.float32(score)
+        finished += len(toks) < max_steps
+    return finished
+
+
+@pytest.mark.parametrize("V,E,H,A,R,beam,k,S", [(13, 16, 24, 20, 12, 5, 6, 4), (50, 32, 48, 40, 24, 3, 5, 7),
+                                                (200, 64, 64, 32, 48, 5, 12, 3), (40, 36, 40, 28, 20, 8, 12, 2),
+                                                (13, 16, 24, 20, 12, 1, 4, 11)])
+def test_translate_batch_small_models(q, ctx, oracle, V, E, H, A, R, beam, k, S):
+    p = synth.full_model(seed=V + beam, V=V, E=E, H=H, A=A, R=R, w_std=0.3, b_std=0.1)
+    p["out.b"][0] += 1.5                 # make the end token frequent enough to finish hypotheses
+    m_ref, m_gpu = oracle.OracleModel(p), q.Model.from_params(ctx, p)
+    rng = np.random.default_rng(V + S)
+    sents = [rng.integers(1, V, size=int(rng.integers(1, 12))).astype(np.int32) for _ in range(S)]
+    finished = _translate_all(q, ctx, m_gpu, m_ref, sents, beam, k, max_steps=15)
+    assert finished > 0 or V > 100       # some searches ended early while others went on
+
+
+def test_translate_batch_full_size_model(q, ctx, oracle):
+    p = synth.full_model(seed=4)
+    m_ref, m_gpu = oracle.OracleModel(p), q.Model.from_params(ctx, p)
+    sents = synth.sentences(seed=4, n=4, V=50000, min_len=5, max_len=14)
+    _translate_all(q, ctx, m_gpu, m_ref, sents, beam=5, k=12, max_steps=4)

@@ -102,7 +102,8 @@ def test_gemm_narrow_streaming(q, ctx, oracle, rows, cols, n):
 
 
 @pytest.mark.parametrize("rows,cols,n", [(3072, 512, 50), (1024, 2048, 30), (1000, 620, 13), (100, 48, 9),
-                                         (3072, 512, 60), (77, 1000, 70)])
+                                         (3072, 512, 60), (77, 1000, 70), (3072, 1024, 320), (130, 272, 129),
+                                         (9000, 512, 130), (50000, 512, 40), (8200, 144, 257)])
 def test_gemm_narrow_matrix_cores(q, ctx, oracle, rows, cols, n):
     rng = np.random.default_rng(rows + cols + n)
     W = _w(rng, rows, cols)
