@@ -15,9 +15,70 @@ struct AttArgs {
     int beam, lde;          // lde: row pitch of e and alpha
 };
 
-// Block (i, b), 1024 threads: energy e[b, i] = sum_j v_j tanh(P[i, j] + a[b, j]) (Eq. 6).
-// The last block to arrive for hypothesis b turns the energies into weights and the
-// context vector H_t (Eq. 5).  Sums run in double; every stored value is rounded once.
+// Rows of P and enc_h that hypothesis b attends over, and how many.
+__device__ __forceinline__ int att_sentence(const AttArgs &a, int b, const float *&P, const float *&enc_h)
+{
+    P = a.P;
+    enc_h = a.enc_h;
+    if (!a.sent_off) return a.l;
+    const int s = b / a.beam, o = a.sent_off[s];
+    P += (size_t)o * a.A;
+    enc_h += (size_t)o * a.C;
+    return a.sent_off[s + 1] - o;
+}
+
+// Run by the last block to arrive for hypothesis b (all its l energies are in a.e, written
+// with device-coherent stores): softmax over the energies in one wave, then the context
+// vector H_t (Eq. 5), a thread owning two adjacent columns and walking the source positions
+// in order.  Sums run in double; every stored value is rounded once.
+__device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const float *enc_h, float *s_alpha)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nt = blockDim.x;
+    if (wave == 0) {
+        const float *e = a.e + (size_t)b * a.lde;
+        float mx = -INFINITY;
+        for (int t = lane; t < l; t += 64) {
+            const float ev = __hip_atomic_load(e + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s_alpha[t] = ev;
+            mx = fmaxf(mx, ev);
+        }
+        mx = wave_max_f(mx);
+        double Z = 0.0;
+        for (int t = lane; t < l; t += 64) Z += q8_exp_d(fmax((double)s_alpha[t] - (double)mx, -700.0));
+        Z = wave_sum_d(Z);
+        for (int t = lane; t < l; t += 64) {
+            const float al = (float)(q8_exp_d(fmax((double)s_alpha[t] - (double)mx, -700.0)) / Z);
+            s_alpha[t] = al;
+            if (a.alpha) a.alpha[(size_t)b * a.lde + t] = al;
+        }
+        if (lane == 0) __hip_atomic_store(&a.counters[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if ((a.C & 1) == 0) {
+        for (int c = tid * 2; c < a.C; c += 2 * nt) {
+            double s0 = 0.0, s1 = 0.0;
+            const float *h = enc_h + c;
+#pragma unroll 10
+            for (int t = 0; t < l; ++t) {
+                const float2 hv = *(const float2 *)(h + (size_t)t * a.C);
+                const double al = (double)s_alpha[t];
+                s0 += al * (double)hv.x;
+                s1 += al * (double)hv.y;
+            }
+            *(float2 *)(a.ctx + (size_t)b * a.C + c) = make_float2((float)s0, (float)s1);
+        }
+    } else {
+        for (int c = tid; c < a.C; c += nt) {
+            double s = 0.0;
+            for (int t = 0; t < l; ++t) s += (double)s_alpha[t] * (double)enc_h[(size_t)t * a.C + c];
+            a.ctx[(size_t)b * a.C + c] = (float)s;
+        }
+    }
+}
+
+// One sentence, a handful of hypotheses: block (i, b) of 1024 threads computes one energy
+// e[b, i] = sum_j v_j tanh(P[i, j] + a[b, j]) (Eq. 6), so that the l n blocks run side by side;
+// the last block to arrive for hypothesis b finishes (att_finish).
 #define ATT_THREADS 1024
 __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
 {
@@ -25,23 +86,15 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
     __shared__ float s_alpha[1024];
     __shared__ int s_last;
     const int i = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    Q8_STAMP(0);
-    int l = a.l;
-    const float *P = a.P, *enc_h = a.enc_h;
-    if (a.sent_off) {
-        const int s = b / a.beam, o = a.sent_off[s];
-        l = a.sent_off[s + 1] - o;
-        if (i >= l) return;                  // the grid spans the longest sentence
-        P += (size_t)o * a.A;
-        enc_h += (size_t)o * a.C;
-    }
+    const float *P, *enc_h;
+    const int l = att_sentence(a, b, P, enc_h);
+    if (i >= l) return;                      // the grid spans the longest sentence
     const float *Pi = P + (size_t)i * a.A;
     const float *ab = a.a + (size_t)b * a.A;
     double acc = 0.0;
     for (int j = tid; j < a.A; j += ATT_THREADS) acc += (double)a.v[j] * (double)tanh_rn(Pi[j] + ab[j]);
     acc = wave_sum_d(acc);
     if (lane == 0) s_red[wave] = acc;
-    Q8_STAMP(1);
     __syncthreads();
     if (tid == 0) {
         double tot = 0.0;
@@ -56,56 +109,56 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
         s_last = (prev == (unsigned)l - 1u);
     }
     __syncthreads();
-    Q8_STAMP(2);
     if (!s_last) return;
-    if (tid == 0 && b == 0) q8_trace_stamp(16);
+    att_finish(a, b, l, enc_h, s_alpha);
+}
 
-    // softmax over the l energies of hypothesis b: one wave, lane t holds e[t], e[t+64], ...
-    if (wave == 0) {
-        const float *e = a.e + (size_t)b * a.lde;
-        float mx = -INFINITY;
-        for (int t = lane; t < l; t += 64) {
-            const float ev = __hip_atomic_load(e + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_alpha[t] = ev;
-            mx = fmaxf(mx, ev);
+// Many hypotheses (sentences side by side): throughput matters, not the latency of one
+// energy.  Block (g, b) of 256 threads takes source positions 8 g .. 8 g + 7 of hypothesis
+// b; thread (p, c) = (tid / 32, tid % 32) sums columns 4 c + 128 u, u = 0, 1, ..., of
+// position 8 g + p, and the 32 partial sums of a position are added across lanes.
+#define ATTP_POS 8
+__global__ __launch_bounds__(256) void attention_panel_kernel(AttArgs a)
+{
+    __shared__ float s_alpha[1024];
+    __shared__ int s_last;
+    const int b = blockIdx.y, tid = threadIdx.x;
+    const float *P, *enc_h;
+    const int l = att_sentence(a, b, P, enc_h);
+    const int i0 = blockIdx.x * ATTP_POS;
+    if (i0 >= l) return;
+    const int p = tid >> 5, c = tid & 31, i = i0 + p;
+    double acc = 0.0;
+    if (i < l) {
+        const float *Pi = P + (size_t)i * a.A;
+        const float *ab = a.a + (size_t)b * a.A;
+        if ((a.A & 3) == 0) {
+            for (int j = 4 * c; j < a.A; j += 128) {
+                const float4 pv = *(const float4 *)(Pi + j), av = *(const float4 *)(ab + j), vv = *(const float4 *)(a.v + j);
+                acc += (double)vv.x * (double)tanh_rn(pv.x + av.x);
+                acc += (double)vv.y * (double)tanh_rn(pv.y + av.y);
+                acc += (double)vv.z * (double)tanh_rn(pv.z + av.z);
+                acc += (double)vv.w * (double)tanh_rn(pv.w + av.w);
+            }
+        } else {
+            for (int j = c; j < a.A; j += 32) acc += (double)a.v[j] * (double)tanh_rn(Pi[j] + ab[j]);
         }
-        mx = wave_max_f(mx);
-        double Z = 0.0;
-        for (int t = lane; t < l; t += 64) Z += exp((double)s_alpha[t] - (double)mx);
-        Z = wave_sum_d(Z);
-        for (int t = lane; t < l; t += 64) {
-            const float al = (float)(exp((double)s_alpha[t] - (double)mx) / Z);
-            s_alpha[t] = al;
-            if (a.alpha) a.alpha[(size_t)b * a.lde + t] = al;
-        }
-        if (lane == 0) __hip_atomic_store(&a.counters[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+#pragma unroll
+    for (int m = 16; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);     // within the position's 32 lanes
+    if (c == 0 && i < l)
+        __hip_atomic_store(&a.e[(size_t)b * a.lde + i], (float)acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): this wave's energies have been performed
+    __syncthreads();                             // ... and so have those of the other waves
+    if (tid == 0) {
+        const unsigned nblk = (unsigned)((l + ATTP_POS - 1) / ATTP_POS);
+        const unsigned prev = __hip_atomic_fetch_add(&a.counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = (prev == nblk - 1u);
     }
     __syncthreads();
-    if (tid == 0 && b == 0) q8_trace_stamp(17);
-    // context: a thread owns two adjacent columns and walks the source positions in order
-    if ((a.C & 1) == 0) {
-        for (int c = tid * 2; c < a.C; c += 2 * ATT_THREADS) {
-            double s0 = 0.0, s1 = 0.0;
-            const float *h = enc_h + c;
-#pragma unroll 10
-            for (int t = 0; t < l; ++t) {
-                const float2 hv = *(const float2 *)(h + (size_t)t * a.C);
-                const double al = (double)s_alpha[t];
-                s0 += al * (double)hv.x;
-                s1 += al * (double)hv.y;
-            }
-            *(float2 *)(a.ctx + (size_t)b * a.C + c) = make_float2((float)s0, (float)s1);
-        }
-    } else {
-        for (int c = tid; c < a.C; c += ATT_THREADS) {
-            double s = 0.0;
-            for (int t = 0; t < l; ++t) s += (double)s_alpha[t] * (double)enc_h[(size_t)t * a.C + c];
-            a.ctx[(size_t)b * a.C + c] = (float)s;
-        }
-    }
-    if (tid == 0 && b == 0) q8_trace_stamp(18);
+    if (!s_last) return;
+    att_finish(a, b, l, enc_h, s_alpha);
 }
-Q8_TRACE_READER(q8_trace_decoder)
 
 // ========================================================================== readout ==
 
@@ -293,7 +346,10 @@ q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, 
     t.counters = (unsigned *)ctx->ws;
     t.l = l; t.A = A; t.C = C;
     t.sent_off = sent_off; t.beam = beam; t.lde = l;
-    Q8_LAUNCH(ctx, Q8_KERNEL_ATTENTION, attention_kernel, dim3(l, n), dim3(ATT_THREADS), 0, t);
+    if (n > Q8_MAX_BEAM)
+        Q8_LAUNCH(ctx, Q8_KERNEL_ATTENTION, attention_panel_kernel, dim3((l + ATTP_POS - 1) / ATTP_POS, n), dim3(256), 0, t);
+    else
+        Q8_LAUNCH(ctx, Q8_KERNEL_ATTENTION, attention_kernel, dim3(l, n), dim3(ATT_THREADS), 0, t);
     return q8i_launch_check(ctx, "attention");
 }
 

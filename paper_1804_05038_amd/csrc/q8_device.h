@@ -7,6 +7,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include "q8_math.h"
 #include <stdint.h>
 
 typedef int v4i __attribute__((ext_vector_type(4)));
@@ -514,6 +515,6 @@ static inline int q8_lanes_per_row(int ld)
     return ld <= 256 ? 16 : (ld <= 512 ? 32 : 64);
 }
 
-// fp32 nonlinearities of the gates, evaluated in double and rounded once.
-__device__ __forceinline__ float sigmoid_rn(float a) { return (float)(1.0 / (1.0 + exp(-(double)a))); }
-__device__ __forceinline__ float tanh_rn(float a) { return (float)tanh((double)a); }
+// fp32 nonlinearities of the gates, evaluated in double and rounded once (q8_math.h).
+__device__ __forceinline__ float sigmoid_rn(float a) { return q8_sigmoid_rn(a); }
+__device__ __forceinline__ float tanh_rn(float a) { return q8_tanh_rn(a); }

@@ -1,0 +1,76 @@
+// q8_math.h -- sigmoid, tanh and exp of the float parts of the model (Section 3 keeps them in
+// floating point): each is evaluated in double to about 1e-15 relative accuracy and rounded
+// once to float, so the float result is the correctly rounded one except for arguments
+// whose exact value lies within ~1e-15 (relative) of a rounding boundary.  Plain fma / add /
+// divide only, the same on the host and on the device; no library calls on the device.
+#pragma once
+
+#include <math.h>
+
+#if defined(__HIPCC__)
+#define Q8_MATH_FN __host__ __device__ __forceinline__
+#else
+#define Q8_MATH_FN static inline
+#endif
+
+// exp(r) - 1 for |r| <= 0.35: Taylor polynomial of degree 14 (next term below 1e-19 relative).
+Q8_MATH_FN double q8_expm1_small(double r)
+{
+    double p = 1.0 / 87178291200.0;             // 1/14!
+    p = fma(p, r, 1.0 / 6227020800.0);
+    p = fma(p, r, 1.0 / 479001600.0);
+    p = fma(p, r, 1.0 / 39916800.0);
+    p = fma(p, r, 1.0 / 3628800.0);
+    p = fma(p, r, 1.0 / 362880.0);
+    p = fma(p, r, 1.0 / 40320.0);
+    p = fma(p, r, 1.0 / 5040.0);
+    p = fma(p, r, 1.0 / 720.0);
+    p = fma(p, r, 1.0 / 120.0);
+    p = fma(p, r, 1.0 / 24.0);
+    p = fma(p, r, 1.0 / 6.0);
+    p = fma(p, r, 0.5);
+    p = fma(p, r, 1.0);
+    return p * r;
+}
+
+// Splits y (|y| <= 700) as y = k ln 2 + r with k integral and |r| <= 0.347; returns r.
+Q8_MATH_FN double q8_reduce_ln2(double y, int *k_out)
+{
+    const double k = rint(y * 1.44269504088896338700e+00);
+    double r = fma(k, -6.93147180369123816490e-01, y);       // high part of ln 2: 32 significant bits, k times it is exact
+    r = fma(k, -1.90821492927058770002e-10, r);
+    *k_out = (int)k;
+    return r;
+}
+
+// exp(y) in double for |y| <= 700 (callers clamp).
+Q8_MATH_FN double q8_exp_d(double y)
+{
+    int k;
+    const double r = q8_reduce_ln2(y, &k);
+    return ldexp(1.0 + q8_expm1_small(r), k);
+}
+
+// tanh(a) = (e^{2|a|} - 1) / (e^{2|a|} + 1) with the sign of a.  With e^{y} = 2^k (1 + m),
+// m = expm1(r), the numerator is 2^k m + (2^k - 1), which keeps full accuracy for small |a|.
+Q8_MATH_FN float q8_tanh_rn(float a)
+{
+    const double x = (double)a;
+    const double y = fmin(2.0 * fabs(x), 80.0);               // tanh is 1 to double precision long before
+    int k;
+    const double r = q8_reduce_ln2(y, &k);
+    const double m = q8_expm1_small(r);
+    const double s = ldexp(1.0, k);
+    const double num = fma(s, m, s - 1.0);
+    const double t = num / (num + 2.0);
+    return (float)copysign(t, x);
+}
+
+// sigmoid(a) = 1 / (1 + e^{-a}); with E = e^{-|a|} in (0, 1]: 1 / (1 + E) for a >= 0, E / (1 + E) below.
+Q8_MATH_FN float q8_sigmoid_rn(float a)
+{
+    const double x = (double)a;
+    const double E = q8_exp_d(-fmin(fabs(x), 700.0));
+    const double num = x >= 0.0 ? 1.0 : E;
+    return (float)(num / (1.0 + E));
+}
