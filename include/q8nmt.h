@@ -177,6 +177,17 @@ q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_m
                            int n_beam, int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx,
                            float *t_out, const q8_taps *taps4);
 
+/* The encoder of Eq. 1 for n_sent sentences side by side: X [L x E] holds their embedding
+ * vectors back to back, sentence s in rows [sent_off[s], sent_off[s + 1]) (sent_off: device
+ * int32 [n_sent + 1]; sent_off_host: the same values on the host, sent_off_host[0] = 0);
+ * enc_h [L x 2H] as q8_encode.  All input products run as matrix-core panels; time step t
+ * of every sentence that has one, in both directions, runs in one quantize / product /
+ * gates launch triple.  Values are those of q8_encode sentence by sentence.  Needs
+ * q8_encode_batch_bytes(fwd, L, n_sent) bytes of workspace. */
+size_t q8_encode_batch_bytes(const q8_gru_weights *fwd, int total_l, int n_sent);
+q8_status q8_encode_batch(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights *bwd, const float *X,
+                          const int32_t *sent_off, const int32_t *sent_off_host, int n_sent, float *enc_h);
+
 /* The decoder step of Eq. 3-6 for several sentences side by side (batching is the extension
  * Section 6 names).  Sentence s owns hypothesis slots [s beam, (s + 1) beam) of y_emb,
  * s_prev, s_out [n x H], ctx_out [n x C] (n = n_sent * beam <= 1024) and rows
@@ -281,11 +292,12 @@ q8_status q8_beam_result_batch(q8_ctx *ctx, const void *states, int n_sent, int 
                                int *len_host, float *score_host, int *steps_host);
 
 /* Translates n_sent sentences together: src_tokens = their ids back to back (device),
- * sent_off_host [n_sent + 1] their offsets (host, sent_off_host[0] = 0).  Encoders run
- * sentence by sentence, the decoder steps for all sentences at once (n_sent * beam <= 1024
+ * sent_off_host [n_sent + 1] their offsets (host, sent_off_host[0] = 0).  Encoder
+ * (q8_encode_batch) and decoder steps run for all sentences at once (n_sent * beam <= 1024
  * slots) until every search is over or max_steps is reached.  Results as
  * q8_beam_result_batch; each sentence's translation is the one q8_translate gives for it.
- * Needs q8_translate_batch_bytes more workspace than q8_workspace_bytes(n_sent * beam, ...). */
+ * Needs q8_translate_batch_bytes + q8_encode_batch_bytes more workspace than
+ * q8_workspace_bytes(n_sent * beam, ...). */
 size_t q8_translate_batch_bytes(const q8_model *m, int total_l, int n_sent, int beam, int k, int max_steps);
 q8_status q8_translate_batch(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens, const int32_t *sent_off_host,
                              int n_sent, int beam, int k, int max_steps, int32_t *tokens_host, int *len_host,

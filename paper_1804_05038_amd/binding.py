@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 __all__ = ["Q8Error", "Context", "Mat", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
            "q8_quantize_matrix", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "gru_step_q8", "cgru_decoder_step_q8",
            "output_logits_q8", "output_logits_beam_q8", "q8_encode", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
-           "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "cgru_decoder_step_batch_q8", "q8_beam_init_batch",
+           "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "cgru_decoder_step_batch_q8", "q8_encode_batch", "q8_encode_batch_bytes", "q8_beam_init_batch",
            "q8_beam_update_batch", "q8_beam_result_batch", "q8_translate_batch", "q8_translate_batch_bytes",
            "KERNEL_CLASSES", "LIB_PATH"]
 LIB_PATH = _LIB_PATH
@@ -99,6 +99,9 @@ def load_library():
         lib.q8_profile_begin.argtypes = [vp, ci, ci]
         lib.q8_probe_read.argtypes = [vp, vp, C.c_size_t]
         lib.cgru_decoder_step_batch_q8.argtypes = [vp, C.POINTER(_Cgru), vp, vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+        lib.q8_encode_batch_bytes.restype = C.c_size_t
+        lib.q8_encode_batch_bytes.argtypes = [C.POINTER(_Gru), ci, ci]
+        lib.q8_encode_batch.argtypes = [vp, C.POINTER(_Gru), C.POINTER(_Gru), vp, vp, ip, ci, vp]
         lib.q8_beam_init_batch.argtypes = [vp, vp, ci, ci, ci, vp, vp, ci, vp, ci, ci, vp, vp, vp]
         lib.q8_beam_update_batch.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, ci, vp, ci, vp, vp, vp]
         lib.q8_beam_result_batch.argtypes = [vp, vp, ci, ci, vp, ip, C.POINTER(C.c_float), ip]
@@ -349,6 +352,23 @@ def q8_encode(ctx, fwd, bwd, X, enc_h=None):
 
 
 KERNEL_CLASSES = {"vocab": 0, "select": 1, "gemv": 2, "gru": 3, "attention": 4, "readout": 5, "mfma": 6, "probe": 7}
+
+
+def q8_encode_batch_bytes(fwd, total_l, n_sent):
+    return load_library().q8_encode_batch_bytes(C.byref(fwd.c), total_l, n_sent)
+
+
+def q8_encode_batch(ctx, fwd, bwd, X, lengths, enc_h=None):
+    """Encoder for sentences of the given lengths, whose embeddings are the rows of X back to back."""
+    import numpy as np
+    off = np.zeros(len(lengths) + 1, dtype=np.int32)
+    off[1:] = np.cumsum(lengths)
+    assert off[-1] == X.shape[0]
+    off_dev = torch.as_tensor(off).to(ctx.device)
+    enc_h = ctx.empty(X.shape[0], 2 * fwd.H) if enc_h is None else enc_h
+    ctx.check(ctx.lib.q8_encode_batch(ctx.handle, C.byref(fwd.c), C.byref(bwd.c), _ptr(X), _ptr(off_dev),
+                                      off.ctypes.data_as(C.POINTER(C.c_int)), len(lengths), _ptr(enc_h)))
+    return enc_h
 
 
 def q8_profile_begin(ctx, kernel_class, max_samples):

@@ -514,6 +514,66 @@ q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights
     return Q8_OK;
 }
 
+size_t q8_encode_batch_bytes(const q8_gru_weights *fwd, int total_l, int n_sent)
+{
+    if (!fwd || total_l < 1 || n_sent < 1) return 0;
+    const size_t H = fwd->Wh.cols, panel = total_l < kMaxMfmaN ? total_l : kMaxMfmaN;
+    return 2 * up256((size_t)total_l * 3 * H * 4) + up256(panel * fwd->Wx.ld) + up256(panel * 4) +
+           2 * (up256((size_t)n_sent * fwd->Wh.ld) + up256((size_t)n_sent * 4) + up256((size_t)n_sent * 3 * H * 4)) + 4096;
+}
+
+q8_status q8_encode_batch(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights *bwd, const float *X,
+                          const int32_t *sent_off, const int32_t *sent_off_host, int n_sent, float *enc_h)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    TRY(check_gru(ctx, fwd, "fwd"));
+    TRY(check_gru(ctx, bwd, "bwd"));
+    const int E = fwd->Wx.cols, H = fwd->Wh.cols;
+    if (bwd->Wx.cols != E || bwd->Wh.cols != H || fwd->Wx.ld != bwd->Wx.ld || fwd->Wh.ld != bwd->Wh.ld)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "directions differ in shape");
+    if (E % 4 || H % 4) return q8_fail(ctx, Q8_ERR_ALIGN, "E and H must be multiples of 4");
+    if (!sent_off || !sent_off_host || !enc_h) return q8_fail(ctx, Q8_ERR_NULL, "q8_encode_batch: NULL argument");
+    if (n_sent <= 0 || n_sent > kMaxMfmaN) return q8_fail(ctx, Q8_ERR_SHAPE, "n_sent = %d outside [1, %d]", n_sent, kMaxMfmaN);
+    if (sent_off_host[0] != 0) return q8_fail(ctx, Q8_ERR_SHAPE, "sent_off[0] must be 0");
+    int max_l = 0;
+    for (int s = 0; s < n_sent; ++s) {
+        const int l = sent_off_host[s + 1] - sent_off_host[s];
+        if (l <= 0 || l > kMaxL) return q8_fail(ctx, Q8_ERR_SHAPE, "sentence %d: length %d outside [1, %d]", s, l, kMaxL);
+        if (l > max_l) max_l = l;
+    }
+    const int total_l = sent_off_host[n_sent];
+    TRY(check_vecs(ctx, X, E, E, "X"));
+    if (!aligned16(enc_h)) return q8_fail(ctx, Q8_ERR_ALIGN, "enc_h needs 16-byte alignment");
+
+    Carver cv(ctx);
+    const int panel = total_l < kMaxMfmaN ? total_l : kMaxMfmaN;
+    float *gxf = cv.take<float>((size_t)total_l * 3 * H), *gxb = cv.take<float>((size_t)total_l * 3 * H);
+    int8_t *xq = cv.take<int8_t>((size_t)panel * fwd->Wx.ld);
+    float *xs = cv.take<float>(panel);
+    int8_t *hqf = cv.take<int8_t>((size_t)n_sent * fwd->Wh.ld), *hqb = cv.take<int8_t>((size_t)n_sent * fwd->Wh.ld);
+    float *hsf = cv.take<float>(n_sent), *hsb = cv.take<float>(n_sent);
+    float *ghf = cv.take<float>((size_t)n_sent * 3 * H), *ghb = cv.take<float>((size_t)n_sent * 3 * H);
+    if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "q8_encode_batch: workspace too small");
+    // input products of every position of every sentence, both directions per launch
+    for (int o = 0; o < total_l; o += kMaxMfmaN) {
+        const int cnt = total_l - o < kMaxMfmaN ? total_l - o : kMaxMfmaN;
+        const q8i_quant_job qj = {X + (size_t)o * E, E, E, fwd->Wx.ld, xq, xs, nullptr};
+        TRY(q8i_quantize_jobs(ctx, &qj, 1, cnt));
+        const q8i_gemm_job gj[2] = {{&fwd->Wx, xq, xs, fwd->bx, gxf + (size_t)o * 3 * H, 3 * H, nullptr, nullptr, nullptr},
+                                    {&bwd->Wx, xq, xs, bwd->bx, gxb + (size_t)o * 3 * H, 3 * H, nullptr, nullptr, nullptr}};
+        TRY(q8i_gemm_jobs(ctx, gj, 2, cnt));
+    }
+    // the recurrences, all sentences and both directions per time step
+    for (int t = 0; t < max_l; ++t) {
+        TRY(q8i_enc_step(ctx, 0, sent_off, n_sent, t, H, fwd->Wh.ld, enc_h, gxf, gxb, ghf, ghb, hqf, hqb, hsf, hsb));
+        const q8i_gemm_job gj[2] = {{&fwd->Wh, hqf, hsf, fwd->bh, ghf, 3 * H, nullptr, nullptr, nullptr},
+                                    {&bwd->Wh, hqb, hsb, bwd->bh, ghb, 3 * H, nullptr, nullptr, nullptr}};
+        TRY(q8i_gemm_jobs(ctx, gj, 2, n_sent));
+        TRY(q8i_enc_step(ctx, 1, sent_off, n_sent, t, H, fwd->Wh.ld, enc_h, gxf, gxb, ghf, ghb, hqf, hqb, hsf, hsb));
+    }
+    return Q8_OK;
+}
+
 size_t q8_beam_state_bytes(int max_steps) { return q8i_beam_state_bytes(max_steps < 1 ? 1 : max_steps); }
 
 q8_status q8_beam_init(q8_ctx *ctx, void *state, int beam, int max_steps, const float *s0, const float *E_tgt, int E,
@@ -735,10 +795,7 @@ q8_status q8_translate_batch(q8_ctx *ctx, const q8_model *m, const int32_t *src_
     if (hipMemcpyAsync(off, sent_off_host, sizeof(int32_t) * (n_sent + 1), hipMemcpyHostToDevice, ctx->stream) != hipSuccess)
         st = q8_fail(ctx, Q8_ERR_DEVICE, "q8_translate_batch: offsets copy failed");
     if (!st) st = q8i_gather_rows(ctx, m->E_src, src_tokens, total_l, E, X);                   // x_i of Eq. 1
-    for (int s = 0; s < n_sent && !st; ++s) {                                                  // Eq. 1, sentence by sentence
-        const int o = sent_off_host[s], l = sent_off_host[s + 1] - o;
-        st = q8_encode(ctx, &m->enc_fwd, &m->enc_bwd, X + (size_t)o * E, l, enc_h + (size_t)o * C);
-    }
+    if (!st) st = q8_encode_batch(ctx, &m->enc_fwd, &m->enc_bwd, X, off, sent_off_host, n_sent, enc_h);    // Eq. 1
     // w(h_i) of Eq. 6 for every position of every sentence (per-vector quantization: the
     // same values as sentence by sentence), in panels of at most 1024 positions
     for (int o = 0; o < total_l && !st; o += kMaxMfmaN) {

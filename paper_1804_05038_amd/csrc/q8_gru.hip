@@ -243,7 +243,83 @@ __global__ __launch_bounds__(256) void gru_gates_kernel(const float *__restrict_
     h_out[(size_t)j * ldo + u] = gru_gates(xv, hv, h_prev[(size_t)j * ldh + u]);
 }
 
+// Encoder recurrences of many sentences side by side (Eq. 1), one launch pair per time
+// step.  Direction d = 0: forward state, columns [H, 2H) of enc_h, step t works on position
+// t; d = 1: backward state, columns [0, H), position l - 1 - t.  Sentence s occupies rows
+// [sent_off[s], sent_off[s + 1]) of enc_h [L x 2H] and of the input pre-activations
+// gx[d] [L x 3H]; sentences shorter than t + 1 positions are skipped.
+struct EncStepArgs {
+    const int *sent_off;
+    float *enc_h;
+    const float *gx[2];          // Wx q(x_i) + bx for every position
+    const float *gh[2];          // [S x 3H] recurrent products of this step
+    int8_t *hq[2];               // [S x ld] codes of the previous states
+    float *hs[2];                // [S] their scales
+    int t, H, ld;
+};
+
+__device__ __forceinline__ bool enc_rows(const EncStepArgs &a, int s, int d, int &pos, int &prev)
+{
+    const int o = a.sent_off[s], l = a.sent_off[s + 1] - o;
+    if (a.t >= l) return false;
+    pos = d == 0 ? o + a.t : o + l - 1 - a.t;
+    prev = d == 0 ? pos - 1 : pos + 1;
+    return true;
+}
+
+// Block (s, d): quantizes the previous state of sentence s, direction d (zero at t = 0).
+__global__ __launch_bounds__(256) void enc_quantize_kernel(EncStepArgs a)
+{
+    __shared__ float s_scale[1];
+    __shared__ float s_red[4];
+    const int s = blockIdx.x, d = blockIdx.y;
+    int pos, prev;
+    if (!enc_rows(a, s, d, pos, prev)) return;
+    int8_t *xq = a.hq[d] + (size_t)s * a.ld;
+    if (a.t == 0) {
+        for (int k = threadIdx.x * 4; k < a.ld; k += 1024) *(int *)(xq + k) = 0;
+        if (threadIdx.x == 0) a.hs[d][s] = 1.0f;
+        return;
+    }
+    const float *h = a.enc_h + (size_t)prev * 2 * a.H + (d == 0 ? a.H : 0);
+    block_quantize<1>(h, 1, a.H, a.H, a.ld, xq, s_scale, s_red);
+    if (threadIdx.x == 0) a.hs[d][s] = s_scale[0];
+}
+
+// One thread per (direction, sentence, hidden unit): gates and the new state.
+__global__ __launch_bounds__(256) void enc_gates_kernel(EncStepArgs a, int S)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int H = a.H;
+    if (idx >= (size_t)2 * S * H) return;
+    const int d = (int)(idx / ((size_t)S * H));
+    const size_t rest = idx - (size_t)d * S * H;
+    const int s = (int)(rest / H), u = (int)(rest - (size_t)s * H);
+    int pos, prev;
+    if (!enc_rows(a, s, d, pos, prev)) return;
+    const float *x = a.gx[d] + (size_t)pos * 3 * H + u, *h = a.gh[d] + (size_t)s * 3 * H + u;
+    const float xv[3] = {x[0], x[H], x[2 * H]}, hv[3] = {h[0], h[H], h[2 * H]};
+    const int col = (d == 0 ? H : 0) + u;
+    const float hp = a.t == 0 ? 0.0f : a.enc_h[(size_t)prev * 2 * H + col];
+    a.enc_h[(size_t)pos * 2 * H + col] = gru_gates(xv, hv, hp);
+}
+
 // =================================================================== host launchers ==
+
+q8_status q8i_enc_step(q8_ctx *ctx, int phase, const int *sent_off, int S, int t, int H, int ld, float *enc_h,
+                       const float *gxf, const float *gxb, float *ghf, float *ghb, int8_t *hqf, int8_t *hqb, float *hsf,
+                       float *hsb)
+{
+    EncStepArgs a = {sent_off, enc_h, {gxf, gxb}, {ghf, ghb}, {hqf, hqb}, {hsf, hsb}, t, H, ld};
+    if (phase == 0) {
+        hipLaunchKernelGGL(enc_quantize_kernel, dim3(S, 2), dim3(256), 0, ctx->stream, a);
+    } else {
+        const size_t total = (size_t)2 * S * H;
+        Q8_LAUNCH(ctx, Q8_KERNEL_GRU, enc_gates_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, a, S);
+    }
+    return q8i_launch_check(ctx, "encoder step");
+}
+
 
 q8_status q8i_gru_gates(q8_ctx *ctx, const float *gx, const float *gh, const float *h_prev, int ldh, float *h_out,
                         int ldo, int H, int n)

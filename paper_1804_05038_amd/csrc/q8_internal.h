@@ -123,6 +123,10 @@ q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, 
                         const float *v, int n, float *e, float *alpha, float *cvec, const int *sent_off, int beam);
 q8_status q8i_gru_gates(q8_ctx *ctx, const float *gx, const float *gh, const float *h_prev, int ldh, float *h_out,
                         int ldo, int H, int n);
+// one time step of the batched encoder: phase 0 quantizes the previous states, phase 1 applies the gates
+q8_status q8i_enc_step(q8_ctx *ctx, int phase, const int *sent_off, int S, int t, int H, int ld, float *enc_h,
+                       const float *gxf, const float *gxb, float *ghf, float *ghb, int8_t *hqf, int8_t *hqb, float *hsf,
+                       float *hsb);
 q8_status q8i_readout_combine(q8_ctx *ctx, const float *ts, const float *ty, const float *tc, const float *b_t, int R,
                               int n, float *t_out, int ld, int8_t *tq, float *tscale, const q8_taps *tap);
 q8_status q8i_output_codes(q8_ctx *ctx, const q8_mat *W, const float *bias, const int8_t *tq, const float *tscale, int n,

@@ -171,3 +171,28 @@ def test_translate_batch_full_size_model(q, ctx, oracle):
     m_ref, m_gpu = oracle.OracleModel(p), q.Model.from_params(ctx, p)
     sents = synth.sentences(seed=4, n=4, V=50000, min_len=5, max_len=14)
     _translate_all(q, ctx, m_gpu, m_ref, sents, beam=5, k=12, max_steps=4)
+
+
+@pytest.mark.parametrize("E,H,lens", [(512, 1024, (12, 1, 30, 7)), (36, 40, (5, 5, 9, 2, 1, 17)), (100, 60, (3,) * 12 + (40,)),
+                                      (512, 1024, (20,))])
+def test_encoder_batch(q, ctx, oracle, E, H, lens):
+    L = sum(lens)
+    p = synth.encoder(seed=3, l=L, E=E, H=H)
+    fwd, bwd = gpu_gru(q, ctx, p, "enc_fwd"), gpu_gru(q, ctx, p, "enc_bwd")
+    X = ctx.f32(p["X"])
+    enc = q.q8_encode_batch(ctx, fwd, bwd, X, list(lens))
+    gf = oracle.QGru(p["enc_fwd.Wx"], p["enc_fwd.Wh"], p["enc_fwd.bx"], p["enc_fwd.bh"])
+    gb = oracle.QGru(p["enc_bwd.Wx"], p["enc_bwd.Wh"], p["enc_bwd.bx"], p["enc_bwd.bh"])
+    o = 0
+    for l in lens:
+        one = q.q8_encode(ctx, fwd, bwd, X[o:o + l].contiguous())
+        assert_same(enc[o:o + l], np_(one), "sentence at row %d vs q8_encode" % o)
+        # the oracle's recurrences, free-running, on this sentence
+        hf, hb = np.zeros(H, np.float32), np.zeros(H, np.float32)
+        ref = np.zeros((l, 2 * H), np.float32)
+        for i in range(l):
+            hf = gf.step(p["X"][o + i], hf); ref[i, H:] = hf
+        for i in range(l - 1, -1, -1):
+            hb = gb.step(p["X"][o + i], hb); ref[i, :H] = hb
+        assert_close(enc[o:o + l], ref, "sentence at row %d vs oracle" % o)
+        o += l
