@@ -77,8 +77,8 @@ q8_status gru_panel(q8_ctx *ctx, Carver &cv, const q8_gru_weights *g, const floa
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "GRU panel: workspace too small");
     const q8i_quant_job qj[2] = {{x, I, I, g->Wx.ld, xq, xs, taps2}, {h_prev, H, H, g->Wh.ld, hq, hs, taps2 ? taps2 + 1 : nullptr}};
     TRY(q8i_quantize_jobs(ctx, qj, gh_pre ? 1 : 2, n));
-    const q8i_gemm_job gj[2] = {{&g->Wx, xq, xs, g->bx, gx, 3 * H, taps2 ? taps2[0].acc : nullptr, nullptr, nullptr},
-                                {&g->Wh, hq, hs, g->bh, gh, 3 * H, taps2 ? taps2[1].acc : nullptr, nullptr, nullptr}};
+    const q8i_gemm_job gj[2] = {{&g->Wx, xq, xs, g->bx, gx, 3 * H, taps2 ? taps2[0].acc : nullptr, nullptr, nullptr, 0},
+                                {&g->Wh, hq, hs, g->bh, gh, 3 * H, taps2 ? taps2[1].acc : nullptr, nullptr, nullptr, 0}};
     TRY(q8i_gemm_jobs(ctx, gj, gh_pre ? 1 : 2, n));
     return q8i_gru_gates(ctx, gx, gh_pre ? gh_pre : gh, h_prev, H, h_out, H, H, n);
 }
@@ -353,8 +353,8 @@ q8_status cgru_decoder_step_batch_q8(q8_ctx *ctx, const q8_cgru_weights *w, cons
     // everything that depends on s' alone: u(s') of Eq. 6 and the recurrent half of GRU q
     const q8i_quant_job qj[2] = {{s_mid, H, H, w->att_U.ld, mq_u, ms_u, nullptr}, {s_mid, H, H, w->q.Wh.ld, mq_h, ms_h, nullptr}};
     TRY(q8i_quantize_jobs(ctx, qj, 2, n));
-    const q8i_gemm_job gj[2] = {{&w->att_U, mq_u, ms_u, nullptr, a, A, nullptr, nullptr, nullptr},
-                                {&w->q.Wh, mq_h, ms_h, w->q.bh, ghq, 3 * H, nullptr, nullptr, nullptr}};
+    const q8i_gemm_job gj[2] = {{&w->att_U, mq_u, ms_u, nullptr, a, A, nullptr, nullptr, nullptr, 0},
+                                {&w->q.Wh, mq_h, ms_h, w->q.bh, ghq, 3 * H, nullptr, nullptr, nullptr, 0}};
     TRY(q8i_gemm_jobs(ctx, gj, 2, n));
     // Eq. 5-6 per hypothesis, against the positions of its own sentence
     TRY(q8i_attention(ctx, P, enc_h, max_l, A, C, a, w->att_v, n, e, alpha_out, ctx_out, sent_off, beam));
@@ -402,7 +402,10 @@ static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8
     const size_t ngrp = (size_t)q8i_out_tiles(V);
     float *pm = cv.take<float>(ngrp * n);
     double *ps = cv.take<double>(ngrp * n);
-    float *lg = logits ? logits : cv.take<float>((size_t)n * V);    // the selection reads the logits back
+    // the selection reads the logits back; a panel's logits that stay in the workspace are kept
+    // tile by tile (contiguous stores from the matrix cores' result layout)
+    const int tiled = (n > kMaxNarrow && !logits) ? 1 : 0;
+    float *lg = logits ? logits : cv.take<float>(tiled ? ngrp * 16 * n : (size_t)n * V);
     if (n > kMaxNarrow) {
         // panel path: codes of t from the combine kernel (or from t_in), then the blocked product
         int8_t *tq = cv.take<int8_t>((size_t)n * W_out->ld);
@@ -417,7 +420,7 @@ static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8
                 int8_t *xq = cv.take<int8_t>((size_t)n * M[u]->ld);
                 float *xs = cv.take<float>(n), *part = cv.take<float>((size_t)n * R);
                 qj[u] = {X[u], M[u]->cols, M[u]->cols, M[u]->ld, xq, xs, taps4 ? taps4 + u : nullptr};
-                gj[u] = {M[u], xq, xs, nullptr, part, R, taps4 ? taps4[u].acc : nullptr, nullptr, nullptr};
+                gj[u] = {M[u], xq, xs, nullptr, part, R, taps4 ? taps4[u].acc : nullptr, nullptr, nullptr, 0};
             }
             if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
             TRY(q8i_quantize_jobs(ctx, qj, 3, n));
@@ -428,7 +431,8 @@ static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8
             const q8i_quant_job qj = {t_in, R, R, W_out->ld, tq, tsc, taps4 ? taps4 + 3 : nullptr};
             TRY(q8i_quantize_jobs(ctx, &qj, 1, n));
         }
-        return q8i_output_codes(ctx, W_out, b_out, tq, tsc, n, k, lg, lse, topk_logp, topk_idx, taps4 ? taps4[3].acc : nullptr, pm, ps);
+        return q8i_output_codes(ctx, W_out, b_out, tq, tsc, n, k, lg, tiled, lse, topk_logp, topk_idx,
+                                taps4 ? taps4[3].acc : nullptr, pm, ps);
     }
     if (ro) {
         float *t = t_out ? t_out : cv.take<float>((size_t)n * R);
@@ -497,8 +501,8 @@ q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights
         if (fwd->Wx.ld != bwd->Wx.ld) return q8_fail(ctx, Q8_ERR_SHAPE, "q8_encode: the two Wx need the same ld");
         const q8i_quant_job qj = {X, E, E, fwd->Wx.ld, xq, xs, nullptr};            // one quantization serves both
         TRY(q8i_quantize_jobs(ctx, &qj, 1, l));
-        const q8i_gemm_job gj[2] = {{&fwd->Wx, xq, xs, fwd->bx, gxf, 3 * H, nullptr, nullptr, nullptr},
-                                    {&bwd->Wx, xq, xs, bwd->bx, gxb, 3 * H, nullptr, nullptr, nullptr}};
+        const q8i_gemm_job gj[2] = {{&fwd->Wx, xq, xs, fwd->bx, gxf, 3 * H, nullptr, nullptr, nullptr, 0},
+                                    {&bwd->Wx, xq, xs, bwd->bx, gxb, 3 * H, nullptr, nullptr, nullptr, 0}};
         TRY(q8i_gemm_jobs(ctx, gj, 2, l));
     }
     // l sequential recurrent steps, both directions in each launch
@@ -559,15 +563,15 @@ q8_status q8_encode_batch(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_w
         const int cnt = total_l - o < kMaxMfmaN ? total_l - o : kMaxMfmaN;
         const q8i_quant_job qj = {X + (size_t)o * E, E, E, fwd->Wx.ld, xq, xs, nullptr};
         TRY(q8i_quantize_jobs(ctx, &qj, 1, cnt));
-        const q8i_gemm_job gj[2] = {{&fwd->Wx, xq, xs, fwd->bx, gxf + (size_t)o * 3 * H, 3 * H, nullptr, nullptr, nullptr},
-                                    {&bwd->Wx, xq, xs, bwd->bx, gxb + (size_t)o * 3 * H, 3 * H, nullptr, nullptr, nullptr}};
+        const q8i_gemm_job gj[2] = {{&fwd->Wx, xq, xs, fwd->bx, gxf + (size_t)o * 3 * H, 3 * H, nullptr, nullptr, nullptr, 0},
+                                    {&bwd->Wx, xq, xs, bwd->bx, gxb + (size_t)o * 3 * H, 3 * H, nullptr, nullptr, nullptr, 0}};
         TRY(q8i_gemm_jobs(ctx, gj, 2, cnt));
     }
     // the recurrences, all sentences and both directions per time step
     for (int t = 0; t < max_l; ++t) {
         TRY(q8i_enc_step(ctx, 0, sent_off, n_sent, t, H, fwd->Wh.ld, enc_h, gxf, gxb, ghf, ghb, hqf, hqb, hsf, hsb));
-        const q8i_gemm_job gj[2] = {{&fwd->Wh, hqf, hsf, fwd->bh, ghf, 3 * H, nullptr, nullptr, nullptr},
-                                    {&bwd->Wh, hqb, hsb, bwd->bh, ghb, 3 * H, nullptr, nullptr, nullptr}};
+        const q8i_gemm_job gj[2] = {{&fwd->Wh, hqf, hsf, fwd->bh, ghf, 3 * H, nullptr, nullptr, nullptr, 0},
+                                    {&bwd->Wh, hqb, hsb, bwd->bh, ghb, 3 * H, nullptr, nullptr, nullptr, 0}};
         TRY(q8i_gemm_jobs(ctx, gj, 2, n_sent));
         TRY(q8i_enc_step(ctx, 1, sent_off, n_sent, t, H, fwd->Wh.ld, enc_h, gxf, gxb, ghf, ghb, hqf, hqb, hsf, hsb));
     }

@@ -15,6 +15,7 @@ struct GemmArgs {
     float *part_max;       // STATS: [n x ntiles] maximum of each 16-row tile
     double *part_sum;      // STATS: [n x ntiles] sum of exp(y - maximum)
     int rows, ld, n, ldy, ntiles;
+    int tiled;             // Y as [ntiles][n][16]: every 16 x 16 result tile is one contiguous KiB
     float w_scale;
 };
 #define GEMM_MAX_JOBS 3
@@ -22,6 +23,16 @@ struct GemmJobs {          // products of one launch (blockIdx.z), all over the 
     GemmArgs j[GEMM_MAX_JOBS];
 };
 
+// Block tiles (row tiles per wave, vector tiles): matrices of more than 8192 rows (the
+// vocabulary) and the rest.
+#ifndef GB_BIG_RT
+#define GB_BIG_RT 2
+#define GB_BIG_NT 8
+#endif
+#ifndef GB_SMALL_RT
+#define GB_SMALL_RT 1
+#define GB_SMALL_NT 4
+#endif
 #define GB_K 128           // k bytes per stage
 #define GB_PITCH 144       // LDS bytes per staged vector: 16 lanes x 16 bytes fall on 64 distinct banks
 
@@ -34,84 +45,127 @@ struct GemmJobs {          // products of one launch (blockIdx.z), all over the 
 template <int RT, int NT, bool STATS>
 __global__ __launch_bounds__(256) void gemm_block_kernel(GemmJobs jobs)
 {
-    const GemmArgs &a = jobs.j[blockIdx.z];
+    const int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    const GemmArgs &a = jobs.j[bz];
     constexpr int BN = 16 * NT;
-    if ((int)blockIdx.x * 64 * RT >= a.rows) return;     // the grid is sized for the largest job
+    if (bx * 64 * RT >= a.rows) return;                  // the grid is sized for the largest job
     constexpr int PIECES = BN * (GB_K / 16) / 256;      // 16-byte pieces of a stage per thread
     __shared__ __align__(16) int8_t s_b[2][BN * GB_PITCH];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int i = lane & 15, g = lane >> 4;
-    const int r0 = (blockIdx.x * 4 + wave) * 16 * RT;
-    const int c0 = blockIdx.y * BN;
+    const int r0 = (bx * 4 + wave) * 16 * RT;
+    const int c0 = by * BN;
     const int ld = a.ld, n = a.n, rows = a.rows;
 
+    // Every load below is unconditional and in bounds (rows, vectors and k offsets are clamped);
+    // what lies outside the matrix is replaced by zeros when a stage is consumed.  That keeps the
+    // number of loads per step fixed, so that waiting for one stage leaves the later ones in flight.
     const int8_t *wp[RT];
     bool row_ok[RT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         const int row = r0 + 16 * rt + i;
         row_ok[rt] = row < rows;
-        wp[rt] = a.W + (size_t)(row_ok[rt] ? row : 0) * ld + 16 * g;
+        wp[rt] = a.W + (size_t)(row_ok[rt] ? row : rows - 1) * ld;
     }
-    v4i breg[PIECES], anext[RT][2], acur[RT][2];
-    auto load_stage = [&](int k0) {
+    const int8_t *bp_g[PIECES];
+    bool col_ok[PIECES];
 #pragma unroll
-        for (int u = 0; u < PIECES; ++u) {
-            const int p = u * 256 + tid;
-            const int col = c0 + (p >> 3), k = k0 + (p & 7) * 16;
-            breg[u] = (v4i){0, 0, 0, 0};
-            if (col < n && k < ld) breg[u] = *(const v4i *)(a.xq + (size_t)col * ld + k);
-        }
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
-#pragma unroll
-            for (int kc = 0; kc < 2; ++kc) {
-                anext[rt][kc] = (v4i){0, 0, 0, 0};
-                if (row_ok[rt] && k0 + 64 * kc + 16 * g < ld) anext[rt][kc] = *(const v4i *)(wp[rt] + k0 + 64 * kc);
-            }
+    for (int u = 0; u < PIECES; ++u) {
+        const int col = c0 + ((u * 256 + tid) >> 3);
+        col_ok[u] = col < n;
+        bp_g[u] = a.xq + (size_t)(col_ok[u] ? col : n - 1) * ld;
+    }
+    const int kb = (tid & 7) * 16;            // k offset of this thread's pieces within a stage
+    const int klast = ld - 16;
+
+    // Software pipeline over stages of GB_K k bytes, loads two stages ahead: while stage s is
+    // multiplied out of LDS, stage s + 1 sits in one register set (or is still arriving) and
+    // stage s + 2 is in flight into the other.
+    struct Stage {
+        v4i b[PIECES];       // this thread's pieces of the vectors' codes
+        v4i a[RT][2];        // this lane's weight operands
     };
-    auto store_stage = [&](int buf) {
+    Stage R0, R1;
+    v4i acur[RT][2];
+    const v4i zero4 = (v4i){0, 0, 0, 0};
+    auto load_stage = [&](Stage &R, int k0) {
+        const int kB = min(k0 + kb, klast);
+#pragma unroll
+        for (int u = 0; u < PIECES; ++u) R.b[u] = *(const v4i *)(bp_g[u] + kB);
+#pragma unroll
+        for (int kc = 0; kc < 2; ++kc) {
+            const int kA = min(k0 + 64 * kc + 16 * g, klast);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) R.a[rt][kc] = *(const v4i *)(wp[rt] + kA);
+        }
+    };
+    auto store_stage = [&](const Stage &R, int buf, int k0) {
+        const bool kB_ok = k0 + kb < ld;
 #pragma unroll
         for (int u = 0; u < PIECES; ++u) {
             const int p = u * 256 + tid;
-            *(v4i *)(s_b[buf] + (p >> 3) * GB_PITCH + (p & 7) * 16) = breg[u];
+            *(v4i *)(s_b[buf] + (p >> 3) * GB_PITCH + (p & 7) * 16) = (col_ok[u] && kB_ok) ? R.b[u] : zero4;
         }
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt)
+        for (int kc = 0; kc < 2; ++kc) {
+            const bool kA_ok = k0 + 64 * kc + 16 * g < ld;
 #pragma unroll
-            for (int kc = 0; kc < 2; ++kc) acur[rt][kc] = anext[rt][kc];
+            for (int rt = 0; rt < RT; ++rt) acur[rt][kc] = (row_ok[rt] && kA_ok) ? R.a[rt][kc] : zero4;
+        }
     };
 
     v4i acc[RT][NT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-        for (int t = 0; t < NT; ++t) acc[rt][t] = (v4i){0, 0, 0, 0};
+        for (int t = 0; t < NT; ++t) acc[rt][t] = zero4;
 
-    load_stage(0);
-    store_stage(0);
+    const int nst = (ld + GB_K - 1) / GB_K;
+    load_stage(R0, 0);
+    load_stage(R1, GB_K);                      // past the last stage: a clamped, unused reload
+    store_stage(R0, 0, 0);
+    load_stage(R0, 2 * GB_K);
     __syncthreads();
-    int buf = 0;
-    for (int k0 = 0; k0 < ld; k0 += GB_K, buf ^= 1) {
-        const bool more = k0 + GB_K < ld;
-        if (more) load_stage(k0 + GB_K);
-        const int8_t *bp = s_b[buf] + i * GB_PITCH + 16 * g;
+    // step s: multiply stage s (LDS buffer s & 1), move stage s + 1 from Rn to the other buffer,
+    // which was last read before the previous barrier, and reuse Rn for stage s + 3
+    auto step = [&](Stage &Rn, int s) {
+        const int8_t *bp = s_b[s & 1] + i * GB_PITCH + 16 * g;
+        v4i av[RT][2];
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+            for (int kc = 0; kc < 2; ++kc) av[rt][kc] = acur[rt][kc];
+        store_stage(Rn, (s + 1) & 1, (s + 1) * GB_K);
+        load_stage(Rn, (s + 3) * GB_K);
 #pragma unroll
         for (int kc = 0; kc < 2; ++kc)
 #pragma unroll
             for (int t = 0; t < NT; ++t) {
-                if (c0 + 16 * t >= n) continue;          // block-uniform: vectors past n
                 const v4i bv = *(const v4i *)(bp + t * 16 * GB_PITCH + 64 * kc);
 #pragma unroll
                 for (int rt = 0; rt < RT; ++rt)
-                    acc[rt][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(acur[rt][kc], bv, acc[rt][t], 0, 0, 0);
+                    acc[rt][t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[rt][kc], bv, acc[rt][t], 0, 0, 0);
             }
-        if (more) store_stage(buf ^ 1);   // the other buffer was last read before the previous barrier
         __syncthreads();
+    };
+    int s = 0;
+    for (; s + 1 < nst; s += 2) {                // always both halves: the load counts per path stay fixed
+        step(R1, s);
+        step(R0, s + 1);
     }
+    if (s < nst) step(R1, s);
 
+    // Epilogue, written so that the loads and the cross-lane steps of all NT tiles of a row tile
+    // are issued together instead of one tile after the other.
     const bool vec_ok = ((a.ldy & 3) == 0) && (((uintptr_t)a.Y & 15) == 0);
     const bool bias_vec = (((uintptr_t)a.bias) & 15) == 0;
+    float cs[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int col = c0 + 16 * t + i;
+        cs[t] = col < n ? a.w_scale * a.xscale[col] : 0.0f;
+    }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         const int row0 = r0 + 16 * rt + 4 * g;
@@ -127,47 +181,63 @@ __global__ __launch_bounds__(256) void gemm_block_kernel(GemmJobs jobs)
                 if (row0 + 3 < rows) b.w = a.bias[row0 + 3];
             }
         }
+        float y[NT][4], m[NT];
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            if (c0 + 16 * t >= n) continue;
             const int col = c0 + 16 * t + i;
             const bool col_ok = col < n;
-            const float c = col_ok ? a.w_scale * a.xscale[col] : 0.0f;
-            float y[4];
-            float m = -INFINITY;
+            m[t] = -INFINITY;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                y[r] = -INFINITY;
+                y[t][r] = -INFINITY;
                 if (col_ok && row0 + r < rows) {
-                    y[r] = (float)acc[rt][t][r] * c;
-                    if (a.bias) y[r] = y[r] + (r == 0 ? b.x : r == 1 ? b.y : r == 2 ? b.z : b.w);
+                    y[t][r] = (float)acc[rt][t][r] * cs[t];
+                    if (a.bias) y[t][r] = y[t][r] + (r == 0 ? b.x : r == 1 ? b.y : r == 2 ? b.z : b.w);
                     if (a.tap_acc) a.tap_acc[(size_t)col * rows + row0 + r] = acc[rt][t][r];
                 }
-                m = fmaxf(m, y[r]);
+                m[t] = fmaxf(m[t], y[t][r]);
             }
-            if (col_ok) {
+            if (a.tiled) {
+                // rows past the matrix carry -inf; whoever reads the tile skips them
+                if (col_ok)
+                    *(float4 *)(a.Y + ((size_t)((r0 + 16 * rt) >> 4) * n + col) * 16 + 4 * g) =
+                        make_float4(y[t][0], y[t][1], y[t][2], y[t][3]);
+            } else if (col_ok) {
                 if (vec_ok && row0 + 3 < rows) {
-                    *(float4 *)(a.Y + (size_t)col * a.ldy + row0) = make_float4(y[0], y[1], y[2], y[3]);
+                    *(float4 *)(a.Y + (size_t)col * a.ldy + row0) = make_float4(y[t][0], y[t][1], y[t][2], y[t][3]);
                 } else {
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        if (row0 + r < rows) a.Y[(size_t)col * a.ldy + row0 + r] = y[r];
+                        if (row0 + r < rows) a.Y[(size_t)col * a.ldy + row0 + r] = y[t][r];
                 }
             }
-            if (STATS) {
-                // (max, sum of exp) of the tile's 16 rows per vector: lanes i, i+16, i+32, i+48
-                m = fmaxf(m, __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(m), SWZ_XOR16)));
-                m = fmaxf(m, __shfl_xor(m, 32, 64));
-                double sd = 0.0;
+        }
+        if (STATS) {
+            // (max, sum of exp) of the tile's 16 rows per vector: lanes i, i+16, i+32, i+48
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                m[t] = fmaxf(m[t], __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(m[t]), SWZ_XOR16)));
+#pragma unroll
+            for (int t = 0; t < NT; ++t) m[t] = fmaxf(m[t], __shfl_xor(m[t], 32, 64));
+            double sd[NT];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                sd[t] = 0.0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    if (y[r] > -INFINITY) sd += (double)__expf(y[r] - m);
-                sd += __shfl_xor(sd, 16, 64);
-                sd += __shfl_xor(sd, 32, 64);
-                if (col_ok && g == 0) {
-                    const int tile = (r0 + 16 * rt) >> 4;
-                    a.part_max[(size_t)col * a.ntiles + tile] = m;
-                    a.part_sum[(size_t)col * a.ntiles + tile] = sd;
+                    if (y[t][r] > -INFINITY) sd[t] += (double)__expf(y[t][r] - m[t]);
+            }
+#pragma unroll
+            for (int t = 0; t < NT; ++t) sd[t] += __shfl_xor(sd[t], 16, 64);
+#pragma unroll
+            for (int t = 0; t < NT; ++t) sd[t] += __shfl_xor(sd[t], 32, 64);
+            const int tile = (r0 + 16 * rt) >> 4;
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int col = c0 + 16 * t + i;
+                if (col < n && g == 0) {
+                    a.part_max[(size_t)col * a.ntiles + tile] = m[t];
+                    a.part_sum[(size_t)col * a.ntiles + tile] = sd[t];
                 }
             }
         }
@@ -229,18 +299,19 @@ q8_status q8i_gemm_jobs(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n)
         a.W = q.W->data; a.xq = q.xq; a.xscale = q.xscale; a.bias = q.bias; a.Y = q.Y; a.tap_acc = q.tap_acc;
         a.part_max = q.part_max; a.part_sum = q.part_sum;
         a.rows = q.W->rows; a.ld = q.W->ld; a.n = n; a.ldy = q.ldy; a.ntiles = (q.W->rows + 15) / 16;
+        a.tiled = q.tiled;
         a.w_scale = q.W->scale;
         if (a.rows > max_rows) max_rows = a.rows;
     }
     const bool stats = d[0].part_max != nullptr;
     if (max_rows > 8192) {
-        const dim3 grid((max_rows + 127) / 128, (n + 127) / 128, njobs);
-        if (stats) Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, (gemm_block_kernel<2, 8, true>), grid, dim3(256), 0, jobs);
-        else Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, (gemm_block_kernel<2, 8, false>), grid, dim3(256), 0, jobs);
+        const dim3 grid((max_rows + 64 * GB_BIG_RT - 1) / (64 * GB_BIG_RT), (n + 16 * GB_BIG_NT - 1) / (16 * GB_BIG_NT), njobs);
+        if (stats) Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, (gemm_block_kernel<GB_BIG_RT, GB_BIG_NT, true>), grid, dim3(256), 0, jobs);
+        else Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, (gemm_block_kernel<GB_BIG_RT, GB_BIG_NT, false>), grid, dim3(256), 0, jobs);
     } else {
-        const dim3 grid((max_rows + 63) / 64, (n + 63) / 64, njobs);
-        if (stats) Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, (gemm_block_kernel<1, 4, true>), grid, dim3(256), 0, jobs);
-        else Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, (gemm_block_kernel<1, 4, false>), grid, dim3(256), 0, jobs);
+        const dim3 grid((max_rows + 64 * GB_SMALL_RT - 1) / (64 * GB_SMALL_RT), (n + 16 * GB_SMALL_NT - 1) / (16 * GB_SMALL_NT), njobs);
+        if (stats) Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, (gemm_block_kernel<GB_SMALL_RT, GB_SMALL_NT, true>), grid, dim3(256), 0, jobs);
+        else Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, (gemm_block_kernel<GB_SMALL_RT, GB_SMALL_NT, false>), grid, dim3(256), 0, jobs);
     }
     return q8i_launch_check(ctx, "gemm");
 }
@@ -251,6 +322,6 @@ q8_status q8i_gemm_mfma(q8_ctx *ctx, const q8_mat *W, const float *X, int n, int
     q8i_quant_job qj = {X, W->cols, ldx, W->ld, xq, xscale, taps};
     q8_status st = q8i_quantize_jobs(ctx, &qj, 1, n);
     if (st) return st;
-    q8i_gemm_job gj = {W, xq, xscale, bias, Y, ldy, taps ? taps->acc : nullptr, nullptr, nullptr};
+    q8i_gemm_job gj = {W, xq, xscale, bias, Y, ldy, taps ? taps->acc : nullptr, nullptr, nullptr, 0};
     return q8i_gemm_jobs(ctx, &gj, 1, n);
 }

@@ -115,6 +115,7 @@ struct q8i_gemm_job {           // Y [n x ldy] = dequantize(W . xq) + bias on th
     int32_t *tap_acc;
     float *part_max;            // vocabulary layer: per-tile softmax statistics [n x ceil(rows / 16)]
     double *part_sum;
+    int tiled;                  // 1: Y is written as [ceil(rows / 16)][n][16] (needs that many floats)
 };
 q8_status q8i_quantize_jobs(q8_ctx *ctx, const q8i_quant_job *d, int njobs, int n);   // njobs <= 3
 q8_status q8i_gemm_jobs(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n);        // njobs <= 3
@@ -130,8 +131,8 @@ q8_status q8i_enc_step(q8_ctx *ctx, int phase, const int *sent_off, int S, int t
 q8_status q8i_readout_combine(q8_ctx *ctx, const float *ts, const float *ty, const float *tc, const float *b_t, int R,
                               int n, float *t_out, int ld, int8_t *tq, float *tscale, const q8_taps *tap);
 q8_status q8i_output_codes(q8_ctx *ctx, const q8_mat *W, const float *bias, const int8_t *tq, const float *tscale, int n,
-                           int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx, int32_t *tap_acc,
-                           float *part_max, double *part_sum);
+                           int k, float *logits, int tiled, float *lse, float *topk_logp, int32_t *topk_idx,
+                           int32_t *tap_acc, float *part_max, double *part_sum);
 q8_status q8i_beam_batch(q8_ctx *ctx, int init, void *states, size_t stride, int S, int beam, int k, int max_steps,
                          const float *topk_logp, const int *topk_idx, const float *s_step, const float *E_tgt, int E,
                          int H, float *y_emb, float *s_next, int *done, const float *enc_h, const int *sent_off, int C);

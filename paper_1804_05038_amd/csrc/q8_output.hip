@@ -283,6 +283,7 @@ struct SelectArgs {
     float *lse, *topk_logp;
     int *topk_idx;
     int ntiles, n, k, V, ldl;
+    int tiled;              // logits kept as [ntiles][n][16] instead of [n][ldl]
     int fuse_update;        // 1: the last block to finish also runs the beam update
     unsigned *counter;      // arrival counter for that, zero on entry and on exit
     BeamUpdateArgs bu;
@@ -368,7 +369,10 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     __syncthreads();
     Q8_STAMP(11);
     const int total = s_nq * OUT_TILE;
-    const float *lg = a.logits + (size_t)j * a.ldl;
+    // logit of vocabulary row r of this hypothesis, in either layout
+    const float *lg = a.tiled ? a.logits + (size_t)j * OUT_TILE : a.logits + (size_t)j * a.ldl;
+    const size_t tile_pitch = a.tiled ? (size_t)a.n * OUT_TILE - OUT_TILE : 0;     // extra floats per tile boundary
+    auto logit = [&](int r) { return lg[(size_t)r + (size_t)(r / OUT_TILE) * tile_pitch]; };
     bool overflow = false;
     if (total <= 16 * SEL_CAP) {
         for (int c0 = tid; c0 < total; c0 += 1024) {
@@ -381,7 +385,7 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
                 v[t] = -INFINITY;
                 if (c < total) {
                     const int r = (int)s_q[c / OUT_TILE] * OUT_TILE + c % OUT_TILE;
-                    if (r < a.V) { row[t] = r; v[t] = lg[r]; }
+                    if (r < a.V) { row[t] = r; v[t] = logit(r); }
                 }
             }
 #pragma unroll
@@ -420,7 +424,7 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     for (int r = 0; r < k; ++r) {
         unsigned long long best = 0ull;
         for (int row = tid; row < a.V; row += 256) {
-            const unsigned long long key = topk_key(lg[row], row);
+            const unsigned long long key = topk_key(logit(row), row);
             if (key < prev && key > best) best = key;
         }
         best = wave_max_u64(best);
@@ -478,13 +482,14 @@ q8_status q8i_pack_tiles(q8_ctx *ctx, const q8_mat *W, int8_t *tiles)
     return q8i_launch_check(ctx, "pack_tiles");
 }
 
-static q8_status launch_select(q8_ctx *ctx, const float *part_max, const double *part_sum, const float *logits, int V,
-                               int n, int k, float *lse, float *topk_logp, int32_t *topk_idx, const q8i_beam_desc *beam)
+static q8_status launch_select(q8_ctx *ctx, const float *part_max, const double *part_sum, const float *logits, int tiled,
+                               int V, int n, int k, float *lse, float *topk_logp, int32_t *topk_idx,
+                               const q8i_beam_desc *beam)
 {
     SelectArgs s;
     s.part_max = part_max; s.part_sum = part_sum; s.logits = logits;
     s.lse = lse; s.topk_logp = topk_logp; s.topk_idx = topk_idx;
-    s.ntiles = q8i_out_tiles(V); s.n = n; s.k = k; s.V = V; s.ldl = V;
+    s.ntiles = q8i_out_tiles(V); s.n = n; s.k = k; s.V = V; s.ldl = V; s.tiled = tiled;
     s.fuse_update = beam ? 1 : 0;
     s.counter = (unsigned *)(ctx->ws + Q8_WS_SELECT_COUNTER);
     if (beam) {
@@ -515,18 +520,19 @@ q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const floa
     const int ch = q8_fast_ch(a.ld);
     if (a.tiles) launch_out_packed<true>(ctx, a, nblk, smem, ch);
     else launch_out_packed<false>(ctx, a, nblk, smem, ch);
-    return launch_select(ctx, part_max, part_sum, logits, a.V, n, k, lse, topk_logp, topk_idx, beam);
+    return launch_select(ctx, part_max, part_sum, logits, 0, a.V, n, k, lse, topk_logp, topk_idx, beam);
 }
 
 // Vocabulary layer for more than 8 hypotheses, from the codes of t: the blocked matrix-core
 // product (which also leaves the per-tile softmax statistics), then the same selection.
+// tiled: the logits go to the workspace tile by tile (see GemmArgs) instead of row-major.
 q8_status q8i_output_codes(q8_ctx *ctx, const q8_mat *W, const float *bias, const int8_t *tq, const float *tscale, int n,
-                           int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx, int32_t *tap_acc,
-                           float *part_max, double *part_sum)
+                           int k, float *logits, int tiled, float *lse, float *topk_logp, int32_t *topk_idx,
+                           int32_t *tap_acc, float *part_max, double *part_sum)
 {
-    const q8i_gemm_job gj = {W, tq, tscale, bias, logits, W->rows, tap_acc, part_max, part_sum};
+    const q8i_gemm_job gj = {W, tq, tscale, bias, logits, W->rows, tap_acc, part_max, part_sum, tiled};
     q8_status st = q8i_gemm_jobs(ctx, &gj, 1, n);
     if (st) return st;
-    return launch_select(ctx, part_max, part_sum, logits, W->rows, n, k, lse, topk_logp, topk_idx, nullptr);
+    return launch_select(ctx, part_max, part_sum, logits, tiled, W->rows, n, k, lse, topk_logp, topk_idx, nullptr);
 }
 

@@ -196,3 +196,21 @@ def test_encoder_batch(q, ctx, oracle, E, H, lens):
             hb = gb.step(p["X"][o + i], hb); ref[i, :H] = hb
         assert_close(enc[o:o + l], ref, "sentence at row %d vs oracle" % o)
         o += l
+
+
+def test_output_layer_panel_ties(q, ctx, oracle):
+    """Heavily tied logits overflow the survivor list and take the exact fallback, with the logits
+    in the caller's row-major buffer or tile by tile in the workspace.  Equals: lowest index first."""
+    V, R, n = 2500, 32, 9
+    W = np.zeros((V, R), np.float32); W[:, 0] = 1.0
+    b = np.zeros(V, np.float32)
+    b[[5, 130, 131, 400, 2499]] = 2.0
+    t = np.zeros((n, R), np.float32); t[:, 0] = 0.5
+    Wm = gpu_mat(q, ctx, W)
+    L = oracle.QLinear(W, b)
+    for want in (False, True):
+        r = q.output_logits_q8(ctx, None, Wm, ctx.f32(b), t_in=ctx.f32(t), k=12, want_logits=want)
+        for j in range(n):
+            lse, lp, idx = oracle.logsoftmax_topk(L.gemv(t[j]), 12)
+            assert idx[:5].tolist() == [5, 130, 131, 400, 2499] and idx[5:].tolist() == list(range(0, 5)) + [6, 7]
+            assert_same(r["topk_idx"][j], idx); assert_close(r["topk_logp"][j], lp)
