@@ -210,6 +210,64 @@ def mfma_products(torch, q, ctx, m, rng):
     return out
 
 
+def batched_decoding(torch, q, m, rng, steps):
+    from workloads import synth
+    """Section 6's batching: S sentences decoded side by side (S x beam hypothesis slots per
+    step), every product on the int8 matrix cores.  A step is cgru_decoder_step_batch_q8 +
+    output_logits_q8 (panel path) + q8_beam_update_batch; the rate is in sentence-steps."""
+    wsb = q.q8_workspace_bytes(max_n=1024, max_l=64, max_rows=50000, max_ld=2048) + (1024 << 20)
+    ctx = q.Context("cuda:0", workspace_bytes=wsb)
+    out = {}
+    for S in (16, 64, 200):
+        n = S * BEAM
+        enc_h = ctx.f32(rng.standard_normal((S * L, 2048)).astype(np.float32))
+        P = torch.cat([q.q8_gemm_narrow(ctx, m.att_W, enc_h[o:o + 1000].contiguous(), m.att_b) for o in range(0, S * L, 1000)])
+        off = torch.arange(0, (S + 1) * L, L, dtype=torch.int32, device=ctx.device)
+        states = torch.zeros(q.q8_beam_state_bytes(MAX_STEPS) * S, dtype=torch.uint8, device=ctx.device)
+        y, s = ctx.empty(n, 512), ctx.empty(n, 1024)
+        done = torch.zeros(S, dtype=torch.int32, device=ctx.device)
+        c0 = q.q8_beam_init_batch(ctx, states, S, BEAM, MAX_STEPS, enc_h, off, m.E_tgt, y, s, done, bind=True)
+        c1 = q.cgru_decoder_step_batch_q8(ctx, m.dec, P, enc_h, off, BEAM, L, y, s, bind=True)
+        c2 = q.output_logits_q8(ctx, m.ro, m.W_out, m.b_out, s=c1.out["s"], y_emb=y, ctx_vec=c1.out["ctx"], k=TOPK,
+                                want_logits=False, bind=True)
+        c3 = q.q8_beam_update_batch(ctx, states, S, BEAM, MAX_STEPS, c2.out["topk_logp"], c2.out["topk_idx"],
+                                    c1.out["s"], m.E_tgt, y, s, done, bind=True)
+        t = [0]
+
+        def step():
+            if t[0] % MAX_STEPS == 0:
+                c0.launch()
+            t[0] += 1
+            c1.launch(); c2.launch(); c3.launch()
+        per = time_loop(torch, step, steps, max(steps // 10, 10))
+        r = {"us_per_step": per * 1e6, "sentence_steps_per_s": S / per, "hypothesis_slots": n}
+        if S == 64:
+            # the vocabulary product (50000 x 512 x 320) alone: its share of the int8 matrix-core peak
+            q.q8_profile_begin(ctx, "mfma", 8 * 50)
+            for _ in range(50):
+                c2.launch()
+            ms, cnt = q.q8_profile_end(ctx)          # two launches per call: readout products, vocabulary
+            r["output_layer_matrix_core_kernels_avg_us"] = ms * 1e3
+            q.q8_profile_begin(ctx, "attention", 50)
+            for _ in range(50):
+                c1.launch()
+            ms, cnt = q.q8_profile_end(ctx)
+            r["attention_us"] = ms * 1e3
+        out["%d_sentences" % S] = r
+    sents = synth.sentences(seed=4, n=200)
+    q.q8_translate_batch(ctx, m, sents[:4], beam=BEAM, k=TOPK, max_steps=MAX_STEPS)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    res = q.q8_translate_batch(ctx, m, sents, beam=BEAM, k=TOPK, max_steps=MAX_STEPS)
+    dt = time.perf_counter() - t0
+    out["translate_200_sentences"] = {"seconds": dt, "sentences_per_s": 200 / dt,
+                                      "target_tokens_per_s": sum(len(r[0]) for r in res) / dt,
+                                      "source_tokens_per_s": sum(len(x) for x in sents) / dt,
+                                      "note": "the 200 synthetic sentences (lengths 10-60, Zipf ids) in one q8_translate_batch "
+                                              "call: batched encoder, 1000 hypothesis slots per decoder step, beam 5"}
+    return out
+
+
 def translate_run(q, ctx, m, n_sent):
     from workloads import synth
     sents = synth.sentences(seed=4, n=200)[:n_sent]
@@ -362,6 +420,7 @@ def main():
                                         "3.1MB_warm": read_ceiling(torch, q, ctx, 3145728, cold=False),
                                         "3.1MB_cold": read_ceiling(torch, q, ctx, 3145728, cold=True)}
         extra["mfma_products"] = mfma_products(torch, q, ctx, m, rng)
+        extra["batched_decoding"] = batched_decoding(torch, q, m, rng, max(args.steps // 10, 50))
         extra["translate"] = translate_run(q, ctx, m, args.sentences)
         extra["steps_per_s_beam1"] = 1.0 / eager1
     cpu = None if (args.no_cpu_baseline or args.quick) else cpu_baseline(p)

@@ -48,7 +48,6 @@ __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
     __shared__ int s_skip;
     BeamState *st = a.st;
     const int tid = threadIdx.x, lane = tid & 63;
-    Q8_STAMP(30);
     if (tid < 64) {
         // Everything the selection needs is requested at once, before any of it is looked at:
         // the state words, and this lane's two candidates of the [n x k] tables (whether their
@@ -87,7 +86,6 @@ __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
                     key[t] = cand_key(sc, c / a.k, tk[t]);
                 }
             }
-            Q8_STAMP(31);
             const int take = min(b_live, n_live * a.k);
             int n_new = 0, b_left = b_live;
             for (int r = 0; r < take; ++r) {
@@ -109,7 +107,6 @@ __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
                     ++n_new;
                 }
             }
-            Q8_STAMP(32);
             if (lane == 0) {
                 for (int q = 0; q < Q8_MAX_BEAM; ++q) {
                     st->score[q] = q < n_new ? s_score[q] : -INFINITY;
@@ -127,9 +124,7 @@ __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
         }
         if (lane == 0) s_skip = skip;
     }
-    Q8_STAMP(33);
     __syncthreads();
-    Q8_STAMP(34);
     if (s_skip) return;
     // Gather the surviving decoder states and the embeddings of the new tokens (slots beyond
     // the survivors repeat survivor 0).  All loads of a thread are issued before its stores.
@@ -166,5 +161,4 @@ __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
             a.y_emb[e] = a.E_tgt[(size_t)s_token[q] * a.E + c];
         }
     }
-    Q8_STAMP(36);
 }

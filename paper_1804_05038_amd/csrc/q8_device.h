@@ -14,22 +14,6 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 
 #define Q8_WAVE 64
 
-#ifdef Q8_TRACE   // phase timing experiment only: never defined in the product build
-static __device__ long long q8_trace_buf[64];
-#define Q8_STAMP(slot) do { if (threadIdx.x == 0 && blockIdx.x == (gridDim.x >> 1) && blockIdx.y == 0) q8_trace_buf[slot] = clock64(); } while (0)
-__device__ __forceinline__ void q8_trace_stamp(int slot) { q8_trace_buf[slot] = clock64(); }
-#define Q8_TRACE_READER(name) extern "C" void name(long long *host) { (void)hipMemcpyFromSymbol(host, HIP_SYMBOL(q8_trace_buf), sizeof(long long) * 64); } \
-    extern "C" void name##_set(const long long *host) { (void)hipMemcpyToSymbol(HIP_SYMBOL(q8_trace_buf), host, sizeof(long long) * 64); }
-#define Q8_SPAN_BEGIN() do { if (threadIdx.x == 0 && (blockIdx.x % 64 == 0 || blockIdx.x == gridDim.x - 1)) q8_trace_buf[40 + (blockIdx.x + 63) / 64] = wall_clock64(); } while (0)
-#define Q8_SPAN_END() do { if (threadIdx.x == 0 && (blockIdx.x % 64 == 0 || blockIdx.x == gridDim.x - 1)) q8_trace_buf[50 + (blockIdx.x + 63) / 64] = wall_clock64(); } while (0)
-#else
-#define Q8_STAMP(slot) do {} while (0)
-#define Q8_SPAN_BEGIN() do {} while (0)
-#define Q8_SPAN_END() do {} while (0)
-#define Q8_TRACE_READER(name)
-__device__ __forceinline__ void q8_trace_stamp(int) {}
-#endif
-
 // ---------------------------------------------------------------- cross-lane ----
 
 template <int CTRL>
@@ -385,15 +369,12 @@ __device__ __forceinline__ void x_finish_m(const XRegs<N, CH> &R, float (&m)[N],
                                            float *s_red)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    Q8_STAMP(20);
     wave_max_multi<N>(m);
-    Q8_STAMP(21);
     if (lane == 0) {
 #pragma unroll
         for (int j = 0; j < N; ++j) s_red[j * 4 + wave] = m[j];
     }
     __syncthreads();
-    Q8_STAMP(22);
     float scale = 1.0f, inv = 0.0f;
     if (lane < N) {
         const float mm = fmaxf(fmaxf(s_red[lane * 4], s_red[lane * 4 + 1]), fmaxf(s_red[lane * 4 + 2], s_red[lane * 4 + 3]));
@@ -412,7 +393,6 @@ __device__ __forceinline__ void x_finish_m(const XRegs<N, CH> &R, float (&m)[N],
             }
         }
     }
-    Q8_STAMP(23);
     __syncthreads();
 }
 

@@ -143,7 +143,6 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
     int8_t *xq = smem;
     int8_t *hq = smem + (MODE == GRU_GX_PRE ? 0 : N * J.ldwx);
 
-    Q8_STAMP(0);
     XRegs<N, CH> xh[2];                      // [0]: x, [1]: h_prev
     XRegs<N, CH> &xr = xh[0], &hr = xh[1];
     if (MODE != GRU_GX_PRE) x_load<N, CH>(xr, J.x, N, J.I, J.ldx);
@@ -174,7 +173,6 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
         hp = J.h_prev[(size_t)lane * J.ldh + unit];
     }
 
-    Q8_STAMP(1);
     if (MODE == GRU_FULL) {
         const int lds[2] = {J.ldwx, J.ldwh};
         int8_t *const dst[2] = {xq, hq};
@@ -184,13 +182,11 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
     } else {
         x_finish<N, CH>(hr, N, J.ldwh, hq, s_scale + 8, s_red);
     }
-    Q8_STAMP(2);
     if (blockIdx.x == 0) gru_x_taps<N, MODE>(J, xq, hq, s_scale);
 
     int ax[3][N], ah[3][N];
     if (MODE != GRU_GX_PRE) rows_dot<N, 3, CH>(wx, J.ldwx, lane, xq, ax);
     if (MODE != GRU_GH_PRE) rows_dot<N, 3, CH>(wh, J.ldwh, lane, hq, ah);
-    Q8_STAMP(3);
     if (ok && lane < N) {
         const int j = lane;
         float cx = 0.f, ch = 0.f;
@@ -225,9 +221,7 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
         }
         J.h_out[(size_t)j * J.ldo + unit] = gru_gates(gx, gh, hp);
     }
-    Q8_STAMP(4);
 }
-Q8_TRACE_READER(q8_trace_gru)
 
 // Gates alone, for panels of more than 8 vectors whose two products came from the matrix
 // cores: gx, gh [n x 3H] (biases included), one thread per (vector, hidden unit).

@@ -115,7 +115,6 @@ __device__ __forceinline__ void out_logits_body(const OutArgs &a)
     const int i = lane & 15, g = lane >> 4;
     // five-wave blocks only run rows of at most 512 bytes: one k chunk, no index divisions
     const int kchunks = QW ? 1 : (ld + 511) / 512;
-    Q8_SPAN_BEGIN();
     if (QW && wave == OUT_STREAM_WAVES) {
         wave_quantize<QW ? QKPL : 1>(a.T, n, a.K, a.ldt, ld, smem, s_scale, lane);
         __syncthreads();
@@ -133,10 +132,8 @@ __device__ __forceinline__ void out_logits_body(const OutArgs &a)
     const int items = ntw * kchunks;
     const bool bias_vec = (((uintptr_t)a.bias) & 15) == 0;
 
-    Q8_STAMP(0);
     XRegs<8, QW ? 1 : CH> xr;
     if (!QW) x_load<8, CH>(xr, a.T, n, a.K, a.ldt);
-    Q8_STAMP(4);
 
     auto load_item = [&](int it, v4i (&av)[8]) {
         const int q = it / kchunks, kc = it - q * kchunks;
@@ -188,7 +185,6 @@ __device__ __forceinline__ void out_logits_body(const OutArgs &a)
     __builtin_amdgcn_sched_barrier(0);
     if (QW) __syncthreads();                 // the quantizing wave has filled smem and s_scale
     else x_finish_m<8, QW ? 1 : CH>(xr, xm, n, ld, smem, s_scale, s_red);
-    Q8_STAMP(1);
     if (!QW && blockIdx.x == 0) {
         if (a.taps.xq)
             for (int e = threadIdx.x; e < n * a.K; e += blockDim.x) a.taps.xq[e] = smem[(e / a.K) * ld + e % a.K];
@@ -256,8 +252,6 @@ __device__ __forceinline__ void out_logits_body(const OutArgs &a)
             load_item(it + 3, bufB);
         }
     }
-    Q8_STAMP(3);
-    Q8_SPAN_END();
 }
 
 template <int CH, bool PACKED>
@@ -274,7 +268,6 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
 {
     out_logits_body<1, PACKED, QKPL>(a);
 }
-Q8_TRACE_READER(q8_trace_output)
 
 struct SelectArgs {
     const float *part_max;
@@ -323,7 +316,6 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     const int j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = a.n, k = a.k;
     const int ntiles = a.ntiles;
     if (tid == 0) { s_nq = 0; s_ns = 0; }
-    Q8_STAMP(8);
 
     float pm[OUT_SB];
     double ps[OUT_SB];
@@ -340,7 +332,6 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     float bm = -INFINITY;
 #pragma unroll
     for (int t = 0; t < OUT_SB; ++t) bm = fmaxf(bm, pm[t]);
-    Q8_STAMP(14);
     // the wave's maxima in descending order: lane 0 holds the largest, lane k - 1 the k-th
     const float sorted = wave_sort_desc_f(bm, lane);
     if (lane == 0) s_f[wave] = sorted;
@@ -353,21 +344,17 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
         if (pm[t] > -INFINITY) S += ps[t] * (double)__expf(pm[t] - m);
     S = wave_sum_d(S);
     if (lane == 0) s_d[wave] = S;
-    Q8_STAMP(15);
-    Q8_STAMP(16);
     __syncthreads();
     S = (s_d[0] + s_d[1]) + (s_d[2] + s_d[3]);
     const float lse = (float)((double)m + log(S));
     if (tid == 0 && a.lse) a.lse[j] = lse;
     const float T = fmaxf(fmaxf(s_t4[0], s_t4[1]), fmaxf(s_t4[2], s_t4[3]));   // -inf: everything qualifies
-    Q8_STAMP(10);
 
     // ---- tiles that can hold a logit >= T
 #pragma unroll
     for (int t = 0; t < OUT_SB; ++t)
         if (tid + 256 * t < ntiles && pm[t] >= T) s_q[atomicAdd(&s_nq, 1)] = (unsigned short)(tid + 256 * t);
     __syncthreads();
-    Q8_STAMP(11);
     const int total = s_nq * OUT_TILE;
     // logit of vocabulary row r of this hypothesis, in either layout
     const float *lg = a.tiled ? a.logits + (size_t)j * OUT_TILE : a.logits + (size_t)j * a.ldl;
@@ -396,7 +383,6 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
                 }
         }
         __syncthreads();
-        Q8_STAMP(12);
         overflow = s_ns > SEL_CAP;
     } else {
         overflow = true;
@@ -417,7 +403,6 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
             }
             if (rank < k) put_topk(a, (size_t)j * k + rank, topk_key_idx(key), topk_key_val(key) - lse);
         }
-        Q8_STAMP(13);
     } else {
     // ---- heavily tied logits: k exact rounds of arg-max over the whole row
     unsigned long long prev = ~0ull;

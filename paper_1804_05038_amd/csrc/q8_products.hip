@@ -155,7 +155,6 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
     const int r_begin = blk * J.rpb;
     const int r_end = min(J.rows, r_begin + J.rpb);
 
-    Q8_STAMP(0);
     XRegs<N, CH> xr;
     x_load<N, CH>(xr, J.X, N, J.cols, J.ldx);
     int r = r_begin + wave * U;
@@ -166,9 +165,7 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
         for (int u = 0; u < U; ++u) wrow[u] = r + u < r_end ? J.W + (size_t)(r + u) * ld : nullptr;
         rows_load<U, CH>(w, wrow, ld, lane);
     }
-    Q8_STAMP(1);
     x_finish<N, CH>(xr, N, ld, smem, s_scale, s_red);
-    Q8_STAMP(2);
     if (blk == 0) write_x_taps<N>(J, smem, s_scale);
     float cj = 0.0f;
     if (lane < N) cj = J.w_scale * s_scale[lane];
@@ -184,7 +181,6 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
         }
         int acc[U][N];
         rows_dot<N, U, CH>(w, ld, lane, smem, acc);
-        Q8_STAMP(3);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int a = 0;
@@ -203,9 +199,7 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
             for (int c = 0; c < CH; ++c) w[u][c] = wn[u][c];
         r = rn;
     }
-    Q8_STAMP(4);
 }
-Q8_TRACE_READER(q8_trace_products)
 
 // ================================================ narrow product on the matrix cores ==
 

@@ -18,7 +18,6 @@ __global__ __launch_bounds__(256) void beam_update_kernel(BeamUpdateArgs a)
 {
     beam_update_body<false>(a);
 }
-Q8_TRACE_READER(q8_trace_search)
 
 size_t q8i_beam_state_bytes(int max_steps)
 {
