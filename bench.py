@@ -268,6 +268,23 @@ def batched_decoding(torch, q, m, rng, steps):
     return out
 
 
+def paper_shapes(torch, q, ctx, rng, steps):
+    """The dimensions of the paper's own systems (Section 4: embedding 620, hidden 1000; the largest
+    vocabulary of its Table 4, 63644), none a multiple of 64: rows are padded to 16-byte multiples."""
+    from workloads import synth
+    p = synth.full_model(seed=5, V=63644, E=620, H=1000, A=1000, R=620)
+    m = q.Model.from_params(ctx, p)
+    enc_h = ctx.f32(rng.standard_normal((L, 2000)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    out = {}
+    for n in (1, BEAM):
+        loop = DecodeLoop(q, ctx, m, P, enc_h, n, rng)
+        out["steps_per_s_beam%d" % n] = 1.0 / time_loop(torch, loop.step, steps, max(steps // 10, 10))
+    out["int8_weight_bytes_per_step"] = int(sum(M.rows * M.ld for M in (m.dec.r.Wx, m.dec.r.Wh, m.dec.att_U, m.dec.q.Wx, m.dec.q.Wh,
+                                                                         m.ro.W_s, m.ro.W_y, m.ro.W_c, m.W_out)))
+    return out
+
+
 def translate_run(q, ctx, m, n_sent):
     from workloads import synth
     sents = synth.sentences(seed=4, n=200)[:n_sent]
@@ -420,6 +437,7 @@ def main():
                                         "3.1MB_warm": read_ceiling(torch, q, ctx, 3145728, cold=False),
                                         "3.1MB_cold": read_ceiling(torch, q, ctx, 3145728, cold=True)}
         extra["mfma_products"] = mfma_products(torch, q, ctx, m, rng)
+        extra["paper_shapes_620_1000_63644"] = paper_shapes(torch, q, ctx, rng, max(args.steps // 4, 100))
         extra["batched_decoding"] = batched_decoding(torch, q, m, rng, max(args.steps // 10, 50))
         extra["translate"] = translate_run(q, ctx, m, args.sentences)
         extra["steps_per_s_beam1"] = 1.0 / eager1

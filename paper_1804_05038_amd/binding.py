@@ -403,8 +403,11 @@ class Model:
         gru = lambda pre: GruWeights(mat(pre + ".Wx"), mat(pre + ".Wh"), ctx.f32(p[pre + ".bx"]), ctx.f32(p[pre + ".bh"]))
         dec = CgruWeights(gru("dec_r"), mat("att.U"), ctx.f32(p["att.v"]), gru("dec_q"))
         ro = ReadoutWeights(mat("ro.Ws"), mat("ro.Wy"), mat("ro.Wc"), ctx.f32(p["ro.b"]))
-        out_W = mat("out.W")
-        if out_W.ld % 64 == 0:          # the streaming order of the vocabulary layer needs whole 64-byte k steps
+        # the streaming order of the vocabulary layer needs whole 64-byte k steps: wide rows are
+        # padded (with zero codes) to the next multiple of 64, narrow test models stay unpacked
+        R = p["out.W"].shape[1]
+        out_W = q8_quantize_matrix(ctx, p["out.W"], ld_out=(R + 63) // 64 * 64 if R >= 256 else None)
+        if out_W.ld % 64 == 0:
             out_W = q8_pack_tiles(ctx, out_W)
         return cls(ctx.f32(p["E_src"]), ctx.f32(p["E_tgt"]), gru("enc_fwd"), gru("enc_bwd"), mat("att.W"),
                    ctx.f32(p["att.b"]), dec, ro, out_W, ctx.f32(p["out.b"]))

@@ -58,6 +58,23 @@ def test_translate_full_size_model(q, ctx, oracle):
     _check_sentence(q, ctx, m_gpu, m_ref, src[:3], beam=1, k=12, max_steps=4)
 
 
+def test_translate_paper_dimensions(q, ctx, oracle):
+    """Embedding 620, hidden 1000 (Section 4) and the smallest vocabulary of Table 4: no dimension is a
+    multiple of 64, so every row is padded; single-sentence and batched drivers against the oracle."""
+    p = synth.full_model(seed=6, V=33658, E=620, H=1000, A=1000, R=620)
+    m_ref = oracle.OracleModel(p)
+    m_gpu = q.Model.from_params(ctx, p)
+    sents = synth.sentences(seed=6, n=3, V=33658, min_len=4, max_len=9)
+    for src in sents[:2]:
+        _check_sentence(q, ctx, m_gpu, m_ref, src, beam=5, k=12, max_steps=3)
+    bctx = q.Context(workspace_bytes=q.q8_workspace_bytes(max_n=16, max_l=64, max_rows=33658, max_ld=2048) + (64 << 20))
+    got = q.q8_translate_batch(bctx, m_gpu, sents, beam=5, k=12, max_steps=3)
+    for src, (toks, score, steps) in zip(sents, got):
+        r_toks, r_score, r_steps = m_ref.translate(src, beam=5, topk=12, max_steps=3)
+        assert toks.tolist() == r_toks.tolist() and steps == r_steps
+        assert abs(float(score) - float(r_score)) <= 1e-5 * max(1.0, abs(float(r_score)))
+
+
 def test_beam_update_rules(q, ctx):
     """Hand-made top-k tables: ordering by (score, parent, token), finishing on token 0, dead slots."""
     n, k, E, H, T = 4, 4, 8, 8, 6
