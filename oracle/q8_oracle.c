@@ -331,34 +331,77 @@ static int cand_before(const cand_t *a, const cand_t *b)
     return a->token < b->token;
 }
 
-int q8o_translate(const q8o_model *m, const int32_t *src_tokens, int l, int beam, int topk,
-                  int max_steps, int use_q8, int32_t *out_tokens, float *out_score, int *out_steps)
+/* Ensemble decoding (Section 4: the English-German systems decode with two models): the
+ * models' probabilities of the next word are averaged before the k best are taken,
+ *   c[v] = log((1/M) sum_m exp(logp_m[v])),  logp_m[v] = logits_m[v] - lse_m,
+ * evaluated in double and rounded once. */
+void q8o_ensemble_logp(const float *const *logp, int M, int V, float *c)
 {
-    int H = m->H, E = m->E, C = m->C, A = m->A, R = m->R;
-    float *X = (float *)malloc(sizeof(float) * (size_t)l * E);
-    float *enc_h = (float *)malloc(sizeof(float) * (size_t)l * C);
-    float *P = (float *)malloc(sizeof(float) * (size_t)l * A);
-    for (int i = 0; i < l; ++i)
-        memcpy(X + (size_t)i * E, m->E_src + (size_t)src_tokens[i] * E, sizeof(float) * (size_t)E);
-    q8o_encode(m, X, l, use_q8, enc_h);
-    q8o_attention_precompute(m, enc_h, l, use_q8, P);
+    for (int v = 0; v < V; ++v) {
+        double p = 0.0;
+        for (int m = 0; m < M; ++m) p += exp((double)logp[m][v]);
+        c[v] = (float)log(p / (double)M);
+    }
+}
 
-    /* live hypotheses: state, last token, score, token history */
-    float *s = (float *)calloc((size_t)beam * H, sizeof(float));
-    float *s_new = (float *)calloc((size_t)beam * H, sizeof(float));
+/* The k largest entries of v by (value descending, index ascending). */
+static void select_topk(const float *v, int V, int k, float *val, int32_t *idx)
+{
+    for (int r = 0; r < k; ++r) {
+        int best = -1;
+        for (int i = 0; i < V; ++i) {
+            int taken = 0;
+            for (int p = 0; p < r; ++p)
+                if (idx[p] == i) { taken = 1; break; }
+            if (taken) continue;
+            if (best < 0 || v[i] > v[best]) best = i;
+        }
+        idx[r] = best;
+        val[r] = v[best];
+    }
+}
+
+/* Beam search over M models that share the target vocabulary (M = 1: one model, its own
+ * top-k of log-probabilities).  Every model keeps its own encoder states, attention
+ * pre-computation and decoder state per hypothesis; the search itself is common. */
+int q8o_translate_ensemble(const q8o_model *const *ms, int M, const int32_t *src_tokens, int l, int beam, int topk,
+                           int max_steps, int use_q8, int32_t *out_tokens, float *out_score, int *out_steps)
+{
+    const int V = ms[0]->out.rows;
+    float **enc_h = (float **)malloc(sizeof(float *) * (size_t)M);
+    float **P = (float **)malloc(sizeof(float *) * (size_t)M);
+    float **s = (float **)malloc(sizeof(float *) * (size_t)M);
+    float **s_new = (float **)malloc(sizeof(float *) * (size_t)M);
+    float **s_step = (float **)malloc(sizeof(float *) * (size_t)M);
+    float **logp = (float **)malloc(sizeof(float *) * (size_t)M);
+    for (int m = 0; m < M; ++m) {
+        const q8o_model *mo = ms[m];
+        const int H = mo->H, E = mo->E, C = mo->C, A = mo->A;
+        float *X = (float *)malloc(sizeof(float) * (size_t)l * E);
+        enc_h[m] = (float *)malloc(sizeof(float) * (size_t)l * C);
+        P[m] = (float *)malloc(sizeof(float) * (size_t)l * A);
+        for (int i = 0; i < l; ++i)
+            memcpy(X + (size_t)i * E, mo->E_src + (size_t)src_tokens[i] * E, sizeof(float) * (size_t)E);
+        q8o_encode(mo, X, l, use_q8, enc_h[m]);
+        q8o_attention_precompute(mo, enc_h[m], l, use_q8, P[m]);
+        free(X);
+        s[m] = (float *)calloc((size_t)beam * H, sizeof(float));
+        s_new[m] = (float *)calloc((size_t)beam * H, sizeof(float));
+        s_step[m] = (float *)malloc(sizeof(float) * (size_t)beam * H);
+        logp[m] = (float *)malloc(sizeof(float) * (size_t)V);
+        /* initial decoder state: the backward encoder state at the first source position */
+        memcpy(s[m], enc_h[m], sizeof(float) * (size_t)H);
+    }
+    /* live hypotheses: last token, score, token history */
     int32_t *hist = (int32_t *)calloc((size_t)beam * max_steps, sizeof(int32_t));
     int32_t *hist_new = (int32_t *)calloc((size_t)beam * max_steps, sizeof(int32_t));
     int32_t *last = (int32_t *)calloc((size_t)beam, sizeof(int32_t));
     float *score = (float *)calloc((size_t)beam, sizeof(float));
-    float *ctx = (float *)malloc(sizeof(float) * (size_t)C);
-    float *t = (float *)malloc(sizeof(float) * (size_t)R);
     float *tk_logp = (float *)malloc(sizeof(float) * (size_t)beam * topk);
     int32_t *tk_idx = (int32_t *)malloc(sizeof(int32_t) * (size_t)beam * topk);
     cand_t *cand = (cand_t *)malloc(sizeof(cand_t) * (size_t)beam * topk);
-    float *s_step = (float *)malloc(sizeof(float) * (size_t)beam * H);
+    float *comb = (float *)malloc(sizeof(float) * (size_t)V);
 
-    /* initial decoder state: the backward encoder state at the first source position */
-    memcpy(s, enc_h, sizeof(float) * (size_t)H);
     int n_live = 1, b_live = beam;
     last[0] = 0;
     score[0] = 0.0f;
@@ -371,10 +414,28 @@ int q8o_translate(const q8o_model *m, const int32_t *src_tokens, int l, int beam
     for (int step = 0; step < max_steps && b_live > 0 && n_live > 0; ++step) {
         ++steps;
         for (int b = 0; b < n_live; ++b) {
-            const float *y = m->E_tgt + (size_t)last[b] * E;
-            q8o_cgru_step(m, P, enc_h, l, y, s + (size_t)b * H, use_q8, NULL, NULL, ctx, s_step + (size_t)b * H);
-            q8o_readout(m, s_step + (size_t)b * H, y, ctx, use_q8, t);
-            q8o_output(m, t, use_q8, topk, NULL, NULL, tk_logp + (size_t)b * topk, tk_idx + (size_t)b * topk);
+            for (int m = 0; m < M; ++m) {
+                const q8o_model *mo = ms[m];
+                const int H = mo->H;
+                float *ctx = (float *)malloc(sizeof(float) * (size_t)mo->C);
+                float *t = (float *)malloc(sizeof(float) * (size_t)mo->R);
+                const float *y = mo->E_tgt + (size_t)last[b] * mo->E;
+                q8o_cgru_step(mo, P[m], enc_h[m], l, y, s[m] + (size_t)b * H, use_q8, NULL, NULL, ctx,
+                              s_step[m] + (size_t)b * H);
+                q8o_readout(mo, s_step[m] + (size_t)b * H, y, ctx, use_q8, t);
+                if (M == 1) {
+                    q8o_output(mo, t, use_q8, topk, NULL, NULL, tk_logp + (size_t)b * topk, tk_idx + (size_t)b * topk);
+                } else {
+                    float lse;
+                    q8o_output(mo, t, use_q8, 0, logp[m], &lse, NULL, NULL);
+                    for (int v = 0; v < V; ++v) logp[m][v] = logp[m][v] - lse;
+                }
+                free(ctx); free(t);
+            }
+            if (M > 1) {
+                q8o_ensemble_logp((const float *const *)logp, M, V, comb);
+                select_topk(comb, V, topk, tk_logp + (size_t)b * topk, tk_idx + (size_t)b * topk);
+            }
         }
         int nc = n_live * topk;
         for (int b = 0; b < n_live; ++b)
@@ -409,7 +470,10 @@ int q8o_translate(const q8o_model *m, const int32_t *src_tokens, int l, int beam
                 memcpy(hist_new + (size_t)n_new * max_steps, hist + (size_t)c->parent * max_steps,
                        sizeof(int32_t) * (size_t)step);
                 hist_new[(size_t)n_new * max_steps + step] = c->token;
-                memcpy(s_new + (size_t)n_new * H, s_step + (size_t)c->parent * H, sizeof(float) * (size_t)H);
+                for (int m = 0; m < M; ++m) {
+                    const int H = ms[m]->H;
+                    memcpy(s_new[m] + (size_t)n_new * H, s_step[m] + (size_t)c->parent * H, sizeof(float) * (size_t)H);
+                }
                 last[n_new] = c->token;
                 score[n_new] = c->score;
                 ++n_new;
@@ -417,7 +481,7 @@ int q8o_translate(const q8o_model *m, const int32_t *src_tokens, int l, int beam
         }
         /* `last` and `score` were overwritten in place: entries [0,n_new) only depend
          * on cand[], which was copied before, so this is safe. */
-        float *tmpf = s; s = s_new; s_new = tmpf;
+        for (int m = 0; m < M; ++m) { float *tmpf = s[m]; s[m] = s_new[m]; s_new[m] = tmpf; }
         int32_t *tmpi = hist; hist = hist_new; hist_new = tmpi;
         n_live = n_new;
     }
@@ -434,7 +498,15 @@ int q8o_translate(const q8o_model *m, const int32_t *src_tokens, int l, int beam
     }
     if (out_steps) *out_steps = steps;
 
-    free(X); free(enc_h); free(P); free(s); free(s_new); free(hist); free(hist_new); free(last);
-    free(score); free(ctx); free(t); free(tk_logp); free(tk_idx); free(cand); free(s_step); free(fin_tokens);
+    for (int m = 0; m < M; ++m) { free(enc_h[m]); free(P[m]); free(s[m]); free(s_new[m]); free(s_step[m]); free(logp[m]); }
+    free(enc_h); free(P); free(s); free(s_new); free(s_step); free(logp);
+    free(hist); free(hist_new); free(last); free(score); free(tk_logp); free(tk_idx); free(cand); free(comb);
+    free(fin_tokens);
     return n_out;
+}
+
+int q8o_translate(const q8o_model *m, const int32_t *src_tokens, int l, int beam, int topk,
+                  int max_steps, int use_q8, int32_t *out_tokens, float *out_score, int *out_steps)
+{
+    return q8o_translate_ensemble(&m, 1, src_tokens, l, beam, topk, max_steps, use_q8, out_tokens, out_score, out_steps);
 }

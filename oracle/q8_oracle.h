@@ -155,6 +155,17 @@ void q8o_output(const q8o_model *m, const float *t, int use_q8, int k,
 int q8o_translate(const q8o_model *m, const int32_t *src_tokens, int l, int beam, int topk,
                   int max_steps, int use_q8, int32_t *out_tokens, float *out_score, int *out_steps);
 
+/* Ensemble of M models that share the target vocabulary (Section 4: the English-German
+ * systems decode with two models).  The models' next-word probabilities are averaged
+ * before the k best are taken: c[v] = log((1/M) sum_m exp(logp_m[v])) with
+ * logp_m[v] = logits_m[v] - lse_m (fp32), the average evaluated in double and rounded
+ * once; candidates are ordered by (c descending, index ascending).  Every model has its
+ * own encoder states, attention pre-computation and decoder state per hypothesis; the
+ * search is O9's.  M = 1 is q8o_translate. */
+void q8o_ensemble_logp(const float *const *logp, int M, int V, float *c);
+int q8o_translate_ensemble(const q8o_model *const *ms, int M, const int32_t *src_tokens, int l, int beam, int topk,
+                           int max_steps, int use_q8, int32_t *out_tokens, float *out_score, int *out_steps);
+
 #ifdef __cplusplus
 }
 #endif

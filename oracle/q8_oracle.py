@@ -55,6 +55,7 @@ def lib():
     if _lib is None:
         _lib = C.CDLL(build())
         _lib.q8o_translate.restype = C.c_int
+        _lib.q8o_translate_ensemble.restype = C.c_int
     return _lib
 
 
@@ -312,3 +313,26 @@ class OracleModel:
         n = lib().q8o_translate(C.byref(self.c), _p(src), C.c_int(src.shape[0]), C.c_int(beam), C.c_int(topk),
                                 C.c_int(max_steps), C.c_int(int(use_q8)), _p(out), C.byref(score), C.byref(steps))
         return out[:n].copy(), np.float32(score.value), steps.value
+
+
+def ensemble_logp(logps):
+    """c[v] = log(mean_m exp(logp_m[v])) for a list of log-probability vectors (Section 4's ensemble)."""
+    arrs = [_f32(a) for a in logps]
+    V = arrs[0].shape[0]
+    ptrs = (C.c_void_p * len(arrs))(*[a.ctypes.data for a in arrs])
+    out = np.empty(V, np.float32)
+    lib().q8o_ensemble_logp(ptrs, C.c_int(len(arrs)), C.c_int(V), _p(out))
+    return out
+
+
+def translate_ensemble(models, src_tokens, beam=5, topk=12, max_steps=100, use_q8=True):
+    """Beam search over several OracleModel objects with averaged next-word probabilities."""
+    src = np.ascontiguousarray(src_tokens, np.int32)
+    out = np.zeros(max_steps, np.int32)
+    score = C.c_float()
+    steps = C.c_int()
+    ptrs = (C.c_void_p * len(models))(*[C.addressof(m.c) for m in models])
+    n = lib().q8o_translate_ensemble(ptrs, C.c_int(len(models)), _p(src), C.c_int(src.shape[0]), C.c_int(beam),
+                                     C.c_int(topk), C.c_int(max_steps), C.c_int(int(use_q8)), _p(out), C.byref(score),
+                                     C.byref(steps))
+    return out[:n].copy(), np.float32(score.value), steps.value

@@ -273,3 +273,71 @@ def test_int8_step_close_to_fp32_step(oracle):
         out.append(full)
     d = np.abs(out[0] - out[1]).max()
     assert 0 < d < 0.05
+
+
+# ------------------------------------------------------------------ ensemble ----
+
+def test_ensemble_logp_is_log_of_mean_probability(oracle):
+    """Section 4's ensemble averages probabilities: checked against the library's logaddexp and
+    against plain probabilities; the result is again a distribution."""
+    rng = np.random.default_rng(20)
+    V = 500
+    lps = []
+    for scale in (1.0, 3.0, 0.2):
+        z = (rng.standard_normal(V) * scale).astype(np.float64)
+        lps.append((z - np.log(np.exp(z).sum())).astype(np.float32))
+    c2 = oracle.ensemble_logp(lps[:2])
+    ref2 = np.logaddexp(lps[0].astype(np.float64), lps[1].astype(np.float64)) - np.log(2.0)
+    np.testing.assert_allclose(c2, ref2, rtol=1e-6, atol=1e-7)
+    c3 = oracle.ensemble_logp(lps)
+    p3 = sum(np.exp(l.astype(np.float64)) for l in lps) / 3.0
+    np.testing.assert_allclose(np.exp(c3.astype(np.float64)), p3, rtol=1e-6)
+    assert abs(np.exp(c3.astype(np.float64)).sum() - 1.0) < 1e-6
+    # not the average of log-probabilities (a plausible mistake): Jensen's inequality is strict here
+    assert (c2 > (lps[0] + lps[1]) / 2 + 1e-4).any()
+    # one model: the identity, up to one rounding of log(exp(x))
+    np.testing.assert_allclose(oracle.ensemble_logp(lps[:1]), lps[0], rtol=1e-6)
+
+
+def test_ensemble_of_a_model_with_itself_is_the_model(oracle):
+    p, _ = _small_model(oracle, seed=21, V=30, std=0.3)
+    p["out.b"][0] += 1.0                 # make some hypotheses finish
+    m = oracle.OracleModel(p)
+    rng = np.random.default_rng(21)
+    for _ in range(4):
+        src = rng.integers(1, 30, size=int(rng.integers(1, 8))).astype(np.int32)
+        one = m.translate(src, beam=3, topk=5, max_steps=8)
+        two = oracle.translate_ensemble([m, m], src, beam=3, topk=5, max_steps=8)
+        assert one[0].tolist() == two[0].tolist() and one[2] == two[2]
+        assert abs(float(one[1]) - float(two[1])) < 1e-5
+
+
+def test_ensemble_beam_one_follows_the_mean_distribution(oracle):
+    """Greedy decoding with two different models, replayed step by step from the models' own
+    distributions: the token taken is the arg-max of the mean probability, and each model's
+    decoder state advances with its own weights."""
+    pa, ma = _small_model(oracle, seed=22, V=17, std=0.4)
+    pb, mb = _small_model(oracle, seed=23, V=17, std=0.4)
+    src = np.array([4, 9, 2, 16], np.int32)
+    toks, score, steps = oracle.translate_ensemble([ma, mb], src, beam=1, topk=3, max_steps=5)
+    st = []
+    for p, m in ((pa, ma), (pb, mb)):
+        enc = m.encode(p["E_src"][src])
+        st.append([p, m, enc, m.attention_precompute(enc), enc[0, :m.H].copy()])
+    last, total, exp = 0, np.float32(0), []
+    differs = False
+    for _ in range(5):
+        lps = []
+        for e in st:
+            lp, e[4] = _step_logp(e[1], e[0], e[3], e[2], e[4], last)
+            lps.append(lp)
+        mean = (np.exp(lps[0].astype(np.float64)) + np.exp(lps[1].astype(np.float64))) / 2
+        differs |= int(np.argmax(lps[0])) != int(np.argmax(lps[1]))
+        last = int(np.argmax(mean))
+        total = np.float32(total + np.float32(np.log(mean[last])))
+        if last == 0:
+            break
+        exp.append(last)
+    assert toks.tolist() == exp
+    assert abs(float(score) - float(total)) < 1e-5
+    assert differs          # the two models disagree somewhere, so averaging mattered
