@@ -285,6 +285,25 @@ def paper_shapes(torch, q, ctx, rng, steps):
     return out
 
 
+def ensemble_run(torch, q, p, m, n_sent):
+    """Section 4's ensemble of two models (the second one an independent random model of the
+    same shape): each step runs both decoders and output layers and averages the distributions."""
+    from workloads import synth
+    m2 = q.Model.from_params(m.ctx_for_bench, synth.full_model(seed=14))
+    models = [m, m2]
+    ctx = q.Context("cuda:0", workspace_bytes=q.q8_workspace_bytes() + q.q8_translate_ensemble_bytes(models, 64) + (1 << 20))
+    sents = synth.sentences(seed=4, n=200)[:n_sent]
+    q.q8_translate_ensemble(ctx, models, sents[0], beam=BEAM, k=TOPK, max_steps=MAX_STEPS)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    steps = 0
+    for sent in sents:
+        steps += q.q8_translate_ensemble(ctx, models, sent, beam=BEAM, k=TOPK, max_steps=MAX_STEPS)[2]
+    dt = time.perf_counter() - t0
+    return {"sentences": n_sent, "sentences_per_s": n_sent / dt, "decoder_steps_per_s": steps / dt,
+            "note": "two full-size models, beam 5, encoders and host round trips included"}
+
+
 def translate_run(q, ctx, m, n_sent):
     from workloads import synth
     sents = synth.sentences(seed=4, n=200)[:n_sent]
@@ -440,6 +459,8 @@ def main():
         extra["paper_shapes_620_1000_63644"] = paper_shapes(torch, q, ctx, rng, max(args.steps // 4, 100))
         extra["batched_decoding"] = batched_decoding(torch, q, m, rng, max(args.steps // 10, 50))
         extra["translate"] = translate_run(q, ctx, m, args.sentences)
+        m.ctx_for_bench = ctx
+        extra["ensemble_of_2"] = ensemble_run(torch, q, p, m, 5)
         extra["steps_per_s_beam1"] = 1.0 / eager1
     cpu = None if (args.no_cpu_baseline or args.quick) else cpu_baseline(p)
 

@@ -303,6 +303,19 @@ q8_status q8_translate_batch(q8_ctx *ctx, const q8_model *m, const int32_t *src_
                              int n_sent, int beam, int k, int max_steps, int32_t *tokens_host, int *len_host,
                              float *score_host, int *steps_host);
 
+/* Ensemble decoding (Section 4: the English-German systems use two models): n_models <= 4
+ * models that share the target vocabulary.  Each step runs every model's decoder step and
+ * output layer, averages the models' next-word probabilities,
+ * c[v] = log((1 / n_models) sum_m exp(logits_m[v] - lse_m)) (double, rounded once), takes the
+ * k best entries of c and makes one search step; every model keeps its own encoder states
+ * and decoder state per hypothesis.  Arguments and results as q8_translate.  Needs
+ * q8_translate_ensemble_bytes more workspace than q8_workspace_bytes(beam, ...). */
+size_t q8_translate_ensemble_bytes(const q8_model *const *models, int n_models, int max_l, int beam, int k,
+                                   int max_steps);
+q8_status q8_translate_ensemble(q8_ctx *ctx, const q8_model *const *models, int n_models, const int32_t *src_tokens,
+                                int l, int beam, int k, int max_steps, int32_t *tokens_host, int *len_host,
+                                float *score_host, int *steps_host);
+
 /* Measurement helpers (not operations of the paper).
  *
  * Between q8_profile_begin and q8_profile_end, up to max_samples launches of the

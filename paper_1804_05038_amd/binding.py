@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 __all__ = ["Q8Error", "Context", "Mat", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
            "q8_quantize_matrix", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "gru_step_q8", "cgru_decoder_step_q8",
            "output_logits_q8", "output_logits_beam_q8", "q8_encode", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
-           "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "cgru_decoder_step_batch_q8", "q8_encode_batch", "q8_encode_batch_bytes", "q8_beam_init_batch",
+           "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "q8_translate_ensemble", "q8_translate_ensemble_bytes", "cgru_decoder_step_batch_q8", "q8_encode_batch", "q8_encode_batch_bytes", "q8_beam_init_batch",
            "q8_beam_update_batch", "q8_beam_result_batch", "q8_translate_batch", "q8_translate_batch_bytes",
            "KERNEL_CLASSES", "LIB_PATH"]
 LIB_PATH = _LIB_PATH
@@ -99,6 +99,9 @@ def load_library():
         lib.q8_profile_begin.argtypes = [vp, ci, ci]
         lib.q8_probe_read.argtypes = [vp, vp, C.c_size_t]
         lib.cgru_decoder_step_batch_q8.argtypes = [vp, C.POINTER(_Cgru), vp, vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+        lib.q8_translate_ensemble_bytes.restype = C.c_size_t
+        lib.q8_translate_ensemble_bytes.argtypes = [vp, ci, ci, ci, ci, ci]
+        lib.q8_translate_ensemble.argtypes = [vp, vp, ci, vp, ci, ci, ci, ci, vp, ip, C.POINTER(C.c_float), ip]
         lib.q8_encode_batch_bytes.restype = C.c_size_t
         lib.q8_encode_batch_bytes.argtypes = [C.POINTER(_Gru), ci, ci]
         lib.q8_encode_batch.argtypes = [vp, C.POINTER(_Gru), C.POINTER(_Gru), vp, vp, ip, ci, vp]
@@ -425,6 +428,25 @@ def q8_translate(ctx, model, src_tokens, beam=5, k=12, max_steps=100):
     n, steps, score = C.c_int(), C.c_int(), C.c_float()
     ctx.check(ctx.lib.q8_translate(ctx.handle, C.byref(model.c), _ptr(src), src.shape[0], beam, k, max_steps,
                                    out, C.byref(n), C.byref(score), C.byref(steps)))
+    return np.array(out[:n.value], dtype=np.int32), np.float32(score.value), steps.value
+
+
+def _model_ptrs(models):
+    return (C.c_void_p * len(models))(*[C.addressof(m.c) for m in models])
+
+
+def q8_translate_ensemble_bytes(models, max_l, beam=5, k=12, max_steps=100):
+    return load_library().q8_translate_ensemble_bytes(_model_ptrs(models), len(models), max_l, beam, k, max_steps)
+
+
+def q8_translate_ensemble(ctx, models, src_tokens, beam=5, k=12, max_steps=100):
+    """Ensemble decoding over a list of Model objects; returns (tokens ndarray, score, steps)."""
+    import numpy as np
+    src = torch.as_tensor(np.asarray(src_tokens, dtype=np.int32)).to(ctx.device)
+    out = (C.c_int32 * max_steps)()
+    n, steps, score = C.c_int(), C.c_int(), C.c_float()
+    ctx.check(ctx.lib.q8_translate_ensemble(ctx.handle, _model_ptrs(models), len(models), _ptr(src), src.shape[0], beam, k,
+                                            max_steps, out, C.byref(n), C.byref(score), C.byref(steps)))
     return np.array(out[:n.value], dtype=np.int32), np.float32(score.value), steps.value
 
 

@@ -687,6 +687,142 @@ q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens
     return st;
 }
 
+// ------------------------------------------------------------------------------ ensembles ----
+
+namespace {
+const int kMaxModels = 4;
+struct EnsModelBufs {
+    size_t X, enc_h, P, y, s0, s1, cv, logits, lse;
+};
+struct EnsBufs {
+    EnsModelBufs m[kMaxModels];
+    size_t comb, lp, idx, state, total;
+};
+EnsBufs ensemble_layout(const q8_model *const *ms, int M, int l, int beam, int k, int max_steps)
+{
+    EnsBufs b;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o += up256(bytes); return at; };
+    const size_t V = ms[0]->W_out.rows;
+    for (int i = 0; i < M; ++i) {
+        const q8_model *m = ms[i];
+        const size_t E = m->E, H = m->dec.r.Wh.cols, C = m->dec.q.Wx.cols, A = m->dec.att_U.rows;
+        EnsModelBufs &e = b.m[i];
+        e.X = take((size_t)l * E * 4); e.enc_h = take((size_t)l * C * 4); e.P = take((size_t)l * A * 4);
+        e.y = take((size_t)beam * E * 4); e.s0 = take((size_t)beam * H * 4); e.s1 = take((size_t)beam * H * 4);
+        e.cv = take((size_t)beam * C * 4); e.logits = take((size_t)beam * V * 4); e.lse = take((size_t)beam * 4);
+    }
+    b.comb = take((size_t)beam * V * 4);
+    b.lp = take((size_t)beam * k * 4); b.idx = take((size_t)beam * k * 4);
+    b.state = take(q8i_beam_state_bytes(max_steps));
+    b.total = o;
+    return b;
+}
+}  // namespace
+
+size_t q8_translate_ensemble_bytes(const q8_model *const *models, int n_models, int max_l, int beam, int k, int max_steps)
+{
+    if (!models || n_models < 1 || n_models > kMaxModels || max_l < 1 || beam < 1 || k < 1 || max_steps < 1) return 0;
+    for (int i = 0; i < n_models; ++i)
+        if (!models[i]) return 0;
+    return ensemble_layout(models, n_models, max_l, beam, k, max_steps).total;
+}
+
+q8_status q8_translate_ensemble(q8_ctx *ctx, const q8_model *const *models, int n_models, const int32_t *src_tokens, int l,
+                                int beam, int k, int max_steps, int32_t *tokens_host, int *len_host, float *score_host,
+                                int *steps_host)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!models || !src_tokens) return q8_fail(ctx, Q8_ERR_NULL, "q8_translate_ensemble: NULL argument");
+    if (n_models < 1 || n_models > kMaxModels) return q8_fail(ctx, Q8_ERR_SHAPE, "n_models = %d outside [1, %d]", n_models, kMaxModels);
+    for (int i = 0; i < n_models; ++i)
+        if (!models[i]) return q8_fail(ctx, Q8_ERR_NULL, "model %d: NULL", i);
+    if (n_models == 1)
+        return q8_translate(ctx, models[0], src_tokens, l, beam, k, max_steps, tokens_host, len_host, score_host, steps_host);
+    const int V = models[0]->W_out.rows;
+    for (int i = 0; i < n_models; ++i) {
+        const q8_model *m = models[i];
+        if (!m->E_src || !m->E_tgt) return q8_fail(ctx, Q8_ERR_NULL, "model %d: NULL embedding table", i);
+        TRY(check_gru(ctx, &m->enc_fwd, "enc_fwd"));
+        TRY(check_gru(ctx, &m->dec.r, "dec.r"));
+        TRY(check_gru(ctx, &m->dec.q, "dec.q"));
+        TRY(check_mat(ctx, &m->att_W, "att_W"));
+        TRY(check_mat(ctx, &m->dec.att_U, "att_U"));
+        TRY(check_mat(ctx, &m->W_out, "W_out"));
+        const int E = m->E, H = m->dec.r.Wh.cols, C = m->dec.q.Wx.cols, A = m->dec.att_U.rows;
+        if (m->enc_fwd.Wx.cols != E || m->dec.r.Wx.cols != E || 2 * m->enc_fwd.Wh.cols != C || m->att_W.cols != C ||
+            m->att_W.rows != A || m->enc_fwd.Wh.cols != H)
+            return q8_fail(ctx, Q8_ERR_SHAPE, "model %d: dimensions are inconsistent", i);
+        if (m->W_out.rows != V) return q8_fail(ctx, Q8_ERR_SHAPE, "the models must share the target vocabulary");
+    }
+    if (l <= 0 || l > kMaxL) return q8_fail(ctx, Q8_ERR_SHAPE, "l = %d outside [1, %d]", l, kMaxL);
+    if (beam <= 0 || beam > Q8_MAX_BEAM || k < beam || k > kMaxK || k > V || max_steps <= 0)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "need 1 <= beam <= %d, beam <= k <= %d, max_steps > 0", Q8_MAX_BEAM, kMaxK);
+    if (ctx->ws_reserved_top) return q8_fail(ctx, Q8_ERR_WORKSPACE, "q8_translate_ensemble is not re-entrant");
+    const EnsBufs b = ensemble_layout(models, n_models, l, beam, k, max_steps);
+    const size_t ngrp = (size_t)q8i_out_tiles(V);
+    const size_t stats = up256(ngrp * beam * 4) + up256(ngrp * beam * 8);
+    if (b.total + stats + Q8_WS_HEADER > ctx->ws_bytes)
+        return q8_fail(ctx, Q8_ERR_WORKSPACE, "q8_translate_ensemble: workspace too small");
+    char *top = ctx->ws + ((ctx->ws_bytes - b.total) & ~(size_t)255);
+    ctx->ws_reserved_top = ctx->ws_bytes - (size_t)(top - ctx->ws);
+    float *lp = (float *)(top + b.lp), *comb = (float *)(top + b.comb);
+    int32_t *idx = (int32_t *)(top + b.idx);
+    void *state = top + b.state;
+    auto F = [&](size_t off) { return (float *)(top + off); };
+
+    q8_status st = Q8_OK;
+    for (int i = 0; i < n_models && !st; ++i) {
+        const q8_model *m = models[i];
+        const EnsModelBufs &e = b.m[i];
+        const int E = m->E, H = m->dec.r.Wh.cols, C = m->dec.q.Wx.cols, A = m->dec.att_U.rows;
+        st = q8i_gather_rows(ctx, m->E_src, src_tokens, l, E, F(e.X));
+        if (!st) st = q8_encode(ctx, &m->enc_fwd, &m->enc_bwd, F(e.X), l, F(e.enc_h));
+        if (!st) st = q8_gemm_narrow(ctx, &m->att_W, F(e.enc_h), l, C, m->att_b, F(e.P), A, nullptr);
+        // the same initial search state from every model; each call also fills that model's first inputs
+        if (!st) st = q8i_beam_init(ctx, state, beam, max_steps, F(e.enc_h), m->E_tgt, E, H, F(e.y), F(e.s0));
+    }
+    int cur = 0, done = 0;
+    for (int t = 0; t < max_steps && !st && !done; ++t) {
+        const float *lg[kMaxModels], *ls[kMaxModels];
+        for (int i = 0; i < n_models && !st; ++i) {
+            const q8_model *m = models[i];
+            const EnsModelBufs &e = b.m[i];
+            float *s_in = F(cur ? e.s1 : e.s0), *s_out = F(cur ? e.s0 : e.s1);
+            st = cgru_decoder_step_q8(ctx, &m->dec, F(e.P), F(e.enc_h), l, F(e.y), s_in, beam, s_out, F(e.cv), nullptr,
+                                      nullptr, nullptr);
+            // this model's logits and log-sum-exp (its own top-k is not used)
+            if (!st) st = output_impl(ctx, &m->ro, &m->W_out, m->b_out, s_out, F(e.y), F(e.cv), nullptr, beam, k, F(e.logits),
+                                      F(e.lse), lp, idx, nullptr, nullptr, nullptr);
+            lg[i] = F(e.logits);
+            ls[i] = F(e.lse);
+        }
+        if (st) break;
+        // averaged distribution, its k best entries, and the search step (first model's buffers)
+        Carver cv(ctx);
+        float *pm = cv.take<float>(ngrp * beam);
+        double *ps = cv.take<double>(ngrp * beam);
+        if (!cv.ok) { st = q8_fail(ctx, Q8_ERR_WORKSPACE, "q8_translate_ensemble: workspace too small"); break; }
+        st = q8i_ensemble_combine(ctx, lg, ls, n_models, beam, V, comb, pm, ps);
+        const q8_model *m0 = models[0];
+        const EnsModelBufs &e0 = b.m[0];
+        q8i_beam_desc bd = {state, F(cur ? e0.s0 : e0.s1), m0->E_tgt, F(e0.y), F(cur ? e0.s1 : e0.s0), m0->E,
+                            m0->dec.r.Wh.cols};
+        if (!st) st = q8i_select_normalized(ctx, pm, ps, comb, V, beam, k, lp, idx, &bd);
+        for (int i = 1; i < n_models && !st; ++i) {
+            const q8_model *m = models[i];
+            const EnsModelBufs &e = b.m[i];
+            st = q8i_beam_regather(ctx, state, beam, F(cur ? e.s0 : e.s1), m->dec.r.Wh.cols, m->E_tgt, m->E, F(e.y),
+                                   F(cur ? e.s1 : e.s0));
+        }
+        if (!st && (t % 8 == 7))
+            st = q8i_beam_read(ctx, state, max_steps, nullptr, nullptr, nullptr, nullptr, &done);
+    }
+    if (!st) st = q8i_beam_read(ctx, state, max_steps, tokens_host, len_host, score_host, steps_host, nullptr);
+    ctx->ws_reserved_top = 0;
+    return st;
+}
+
 // ---------------------------------------------------------------- sentences side by side ----
 
 q8_status q8_beam_init_batch(q8_ctx *ctx, void *states, int n_sent, int beam, int max_steps, const float *enc_h,

@@ -14,6 +14,7 @@ struct BeamState {
     int have_fin, fin_len, fin_parent, max_steps;
     float fin_score;
     int beam;
+    int gathered;           // 1 if the last update ran (and gathered the next step's inputs), 0 if the search was over
     float score[Q8_MAX_BEAM];
     int last[Q8_MAX_BEAM];
     int link[1];            // [max_steps][Q8_MAX_BEAM]
@@ -35,6 +36,8 @@ __device__ __forceinline__ unsigned long long cand_key(float score, int parent, 
     u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
     return ((unsigned long long)u << 32) | ((unsigned)(15 - parent) << 20) | (unsigned)(0xFFFFF - token);
 }
+
+__device__ __forceinline__ void beam_gather(const BeamUpdateArgs &a, const int *s_parent, const int *s_token);
 
 // One block of 256 threads.  Wave 0 selects the b_live best continuations and rewrites the
 // state; all threads then gather the surviving decoder states and the embeddings of the new
@@ -122,12 +125,19 @@ __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
                 if (b_left == 0 || n_new == 0 || step + 1 >= max_steps) st->done = 1;
             }
         }
-        if (lane == 0) s_skip = skip;
+        if (lane == 0) { s_skip = skip; st->gathered = skip ? 0 : 1; }
     }
     __syncthreads();
     if (s_skip) return;
-    // Gather the surviving decoder states and the embeddings of the new tokens (slots beyond
-    // the survivors repeat survivor 0).  All loads of a thread are issued before its stores.
+    beam_gather(a, s_parent, s_token);
+}
+
+// Gathers the surviving decoder states and the embeddings of the new tokens: slot q of the
+// next step continues slot s_parent[q] with token s_token[q] (slots beyond the survivors
+// repeat survivor 0).  All loads of a thread are issued before its stores.
+__device__ __forceinline__ void beam_gather(const BeamUpdateArgs &a, const int *s_parent, const int *s_token)
+{
+    const int tid = threadIdx.x;
     if (((a.H | a.E) & 3) == 0) {
         const int H4 = a.H >> 2, E4 = a.E >> 2, nH4 = a.n * H4, total4 = nH4 + a.n * E4;
         for (int base = tid; base < total4; base += 256 * 8) {

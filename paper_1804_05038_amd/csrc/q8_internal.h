@@ -150,6 +150,12 @@ q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const floa
                      float *logits, float *lse, float *topk_logp, int32_t *topk_idx, const q8_taps *taps,
                      float *part_max, double *part_sum, const struct q8i_beam_desc *beam);
 
+q8_status q8i_ensemble_combine(q8_ctx *ctx, const float *const *logits, const float *const *lse, int M, int n, int V,
+                               float *c, float *part_max, double *part_sum);
+q8_status q8i_select_normalized(q8_ctx *ctx, const float *part_max, const double *part_sum, const float *c, int V, int n,
+                                int k, float *topk_logp, int32_t *topk_idx, const struct q8i_beam_desc *beam);
+q8_status q8i_beam_regather(q8_ctx *ctx, void *state, int n, const float *s_step, int H, const float *E_tgt, int E,
+                            float *y_emb, float *s_next);
 size_t q8i_beam_state_bytes(int max_steps);
 q8_status q8i_gather_rows(q8_ctx *ctx, const float *table, const int *idx, int n, int dim, float *out);
 q8_status q8i_beam_init(q8_ctx *ctx, void *state, int beam, int max_steps, const float *s0, const float *E_tgt, int E,

@@ -277,6 +277,7 @@ struct SelectArgs {
     int *topk_idx;
     int ntiles, n, k, V, ldl;
     int tiled;              // logits kept as [ntiles][n][16] instead of [n][ldl]
+    int normalized;         // the "logits" are log-probabilities already: nothing is subtracted
     int fuse_update;        // 1: the last block to finish also runs the beam update
     unsigned *counter;      // arrival counter for that, zero on entry and on exit
     BeamUpdateArgs bu;
@@ -346,7 +347,7 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     if (lane == 0) s_d[wave] = S;
     __syncthreads();
     S = (s_d[0] + s_d[1]) + (s_d[2] + s_d[3]);
-    const float lse = (float)((double)m + log(S));
+    const float lse = a.normalized ? 0.0f : (float)((double)m + log(S));
     if (tid == 0 && a.lse) a.lse[j] = lse;
     const float T = fmaxf(fmaxf(s_t4[0], s_t4[1]), fmaxf(s_t4[2], s_t4[3]));   // -inf: everything qualifies
 
@@ -467,14 +468,76 @@ q8_status q8i_pack_tiles(q8_ctx *ctx, const q8_mat *W, int8_t *tiles)
     return q8i_launch_check(ctx, "pack_tiles");
 }
 
+// Ensemble (Section 4): c[j, v] = log(mean over the models of exp(logits_m[j, v] - lse_m[j])), in
+// double, rounded once; one thread per (hypothesis, 16-row tile) also leaves the tile's maximum
+// and sum of exponentials for the selection kernel.
+#define ENS_MAX_MODELS 4
+struct CombineArgs {
+    const float *logits[ENS_MAX_MODELS];
+    const float *lse[ENS_MAX_MODELS];
+    float *c, *part_max;
+    double *part_sum;
+    int M, n, V, ntiles;
+};
+
+__global__ __launch_bounds__(256) void ensemble_combine_kernel(CombineArgs a)
+{
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= a.n * a.ntiles) return;
+    const int j = idx / a.ntiles, tile = idx - j * a.ntiles;
+    const int r0 = tile * OUT_TILE, rows = min(OUT_TILE, a.V - r0);
+    float ls[ENS_MAX_MODELS];
+#pragma unroll
+    for (int m = 0; m < ENS_MAX_MODELS; ++m) ls[m] = m < a.M ? a.lse[m][j] : 0.0f;
+    const double inv_m = 1.0 / (double)a.M;
+    float c[OUT_TILE], mx = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < OUT_TILE; ++r) {
+        c[r] = -INFINITY;
+        if (r < rows) {
+            double p = 0.0;
+#pragma unroll
+            for (int m = 0; m < ENS_MAX_MODELS; ++m)
+                if (m < a.M) {
+                    const float lp = a.logits[m][(size_t)j * a.V + r0 + r] - ls[m];
+                    p += q8_exp_d(fmax((double)lp, -700.0));
+                }
+            c[r] = (float)log(p * inv_m);
+            a.c[(size_t)j * a.V + r0 + r] = c[r];
+        }
+        mx = fmaxf(mx, c[r]);
+    }
+    double sd = 0.0;
+#pragma unroll
+    for (int r = 0; r < OUT_TILE; ++r)
+        if (r < rows) sd += (double)__expf(c[r] - mx);
+    a.part_max[(size_t)j * a.ntiles + tile] = mx;
+    a.part_sum[(size_t)j * a.ntiles + tile] = sd;
+}
+
+q8_status q8i_ensemble_combine(q8_ctx *ctx, const float *const *logits, const float *const *lse, int M, int n, int V,
+                               float *c, float *part_max, double *part_sum)
+{
+    CombineArgs a;
+    for (int m = 0; m < ENS_MAX_MODELS; ++m) {
+        a.logits[m] = logits[m < M ? m : 0];
+        a.lse[m] = lse[m < M ? m : 0];
+    }
+    a.c = c; a.part_max = part_max; a.part_sum = part_sum;
+    a.M = M; a.n = n; a.V = V; a.ntiles = q8i_out_tiles(V);
+    const int total = n * a.ntiles;
+    hipLaunchKernelGGL(ensemble_combine_kernel, dim3((total + 255) / 256), dim3(256), 0, ctx->stream, a);
+    return q8i_launch_check(ctx, "ensemble combine");
+}
+
 static q8_status launch_select(q8_ctx *ctx, const float *part_max, const double *part_sum, const float *logits, int tiled,
                                int V, int n, int k, float *lse, float *topk_logp, int32_t *topk_idx,
-                               const q8i_beam_desc *beam)
+                               const q8i_beam_desc *beam, int normalized = 0)
 {
     SelectArgs s;
     s.part_max = part_max; s.part_sum = part_sum; s.logits = logits;
     s.lse = lse; s.topk_logp = topk_logp; s.topk_idx = topk_idx;
-    s.ntiles = q8i_out_tiles(V); s.n = n; s.k = k; s.V = V; s.ldl = V; s.tiled = tiled;
+    s.ntiles = q8i_out_tiles(V); s.n = n; s.k = k; s.V = V; s.ldl = V; s.tiled = tiled; s.normalized = normalized;
     s.fuse_update = beam ? 1 : 0;
     s.counter = (unsigned *)(ctx->ws + Q8_WS_SELECT_COUNTER);
     if (beam) {
@@ -486,6 +549,14 @@ static q8_status launch_select(q8_ctx *ctx, const float *part_max, const double 
     }
     Q8_LAUNCH(ctx, Q8_KERNEL_SELECT, out_select_kernel, dim3(n), dim3(256), 0, s);
     return q8i_launch_check(ctx, "output");
+}
+
+// Selection alone over values that are log-probabilities already (the ensemble's averaged
+// distribution), row-major [n x V], with their tile statistics; optional fused beam update.
+q8_status q8i_select_normalized(q8_ctx *ctx, const float *part_max, const double *part_sum, const float *c, int V, int n,
+                                int k, float *topk_logp, int32_t *topk_idx, const q8i_beam_desc *beam)
+{
+    return launch_select(ctx, part_max, part_sum, c, 0, V, n, k, nullptr, topk_logp, topk_idx, beam, 1);
 }
 
 q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const float *T, int ldt, int n, int k,

@@ -37,6 +37,7 @@ __device__ __forceinline__ void beam_init_body(const BeamInitArgs &a)
     if (threadIdx.x == 0) {
         st->n_live = 1; st->b_live = a.beam; st->step = 0; st->done = 0;
         st->have_fin = 0; st->fin_len = 0; st->fin_parent = 0; st->max_steps = a.max_steps; st->beam = a.beam;
+        st->gathered = 0;
         st->fin_score = -INFINITY;
         for (int b = 0; b < Q8_MAX_BEAM; ++b) { st->score[b] = b == 0 ? 0.0f : -INFINITY; st->last[b] = 0; }
     }
@@ -49,6 +50,24 @@ __device__ __forceinline__ void beam_init_body(const BeamInitArgs &a)
 __global__ __launch_bounds__(256) void beam_init_kernel(BeamInitArgs a)
 {
     beam_init_body(a);
+}
+
+// Ensembles: the search state was updated from the first model's call; every further model
+// gathers its own decoder states and embeddings along the same back-pointers.
+__global__ __launch_bounds__(256) void beam_regather_kernel(BeamUpdateArgs a)
+{
+    __shared__ int s_parent[Q8_MAX_BEAM], s_token[Q8_MAX_BEAM];
+    const BeamState *st = a.st;
+    if (!st->gathered) return;
+    if (threadIdx.x < Q8_MAX_BEAM) {
+        const int *link = st->link + (size_t)(st->step - 1) * Q8_MAX_BEAM;
+        const int n_live = st->n_live, q = threadIdx.x < n_live ? threadIdx.x : 0;
+        const int e = n_live > 0 ? link[q] : 0;
+        s_parent[threadIdx.x] = (e >> 24) & 0xF;
+        s_token[threadIdx.x] = e & 0xFFFFFF;
+    }
+    __syncthreads();
+    beam_gather(a, s_parent, s_token);
 }
 
 // Several sentences side by side: block s runs sentence s, whose beam occupies slots
@@ -121,6 +140,14 @@ q8_status q8i_beam_batch(q8_ctx *ctx, int init, void *states, size_t stride, int
     if (init) hipLaunchKernelGGL(beam_init_batch_kernel, dim3(S), dim3(256), 0, ctx->stream, b);
     else hipLaunchKernelGGL(beam_update_batch_kernel, dim3(S), dim3(256), 0, ctx->stream, b);
     return q8i_launch_check(ctx, init ? "beam init (batch)" : "beam update (batch)");
+}
+
+q8_status q8i_beam_regather(q8_ctx *ctx, void *state, int n, const float *s_step, int H, const float *E_tgt, int E,
+                            float *y_emb, float *s_next)
+{
+    BeamUpdateArgs a = {(BeamState *)state, nullptr, nullptr, s_step, E_tgt, y_emb, s_next, n, 0, E, H};
+    hipLaunchKernelGGL(beam_regather_kernel, dim3(1), dim3(256), 0, ctx->stream, a);
+    return q8i_launch_check(ctx, "beam regather");
 }
 
 // Rebuilds a finished search from a host copy of its state: the best finished hypothesis,

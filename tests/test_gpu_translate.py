@@ -186,3 +186,45 @@ def test_two_contexts_on_two_streams(q, ctx, oracle):
         for (toks, score, steps), src in zip(outs, srcs):
             r_toks, r_score, r_steps = m_ref.translate(src, beam=4, topk=6, max_steps=10)
             assert toks.tolist() == r_toks.tolist() and steps == r_steps
+
+
+@pytest.mark.parametrize("V,dims_a,dims_b,beam,k", [(13, (16, 24, 20, 12), (16, 24, 20, 12), 3, 5),
+                                                    (50, (32, 48, 40, 24), (16, 24, 20, 12), 5, 6),
+                                                    (200, (64, 64, 32, 48), (36, 40, 28, 20), 5, 12)])
+def test_translate_ensemble_of_two_models(q, ctx, oracle, V, dims_a, dims_b, beam, k):
+    """Section 4's ensemble: two models (of different sizes) sharing the vocabulary, probabilities
+    averaged before the top-k; the whole search against the oracle's."""
+    ps = []
+    for seed, (E, H, A, R) in ((V + 1, dims_a), (V + 2, dims_b)):
+        p = synth.full_model(seed=seed, V=V, E=E, H=H, A=A, R=R, w_std=0.3, b_std=0.1)
+        p["out.b"][0] += 1.2
+        ps.append(p)
+    refs = [oracle.OracleModel(p) for p in ps]
+    gpus = [q.Model.from_params(ctx, p) for p in ps]
+    rng = np.random.default_rng(V)
+    finished = differs = 0
+    for i in range(5):
+        src = rng.integers(1, V, size=int(rng.integers(1, 10))).astype(np.int32)
+        toks, score, steps = q.q8_translate_ensemble(ctx, gpus, src, beam=beam, k=k, max_steps=12)
+        r_toks, r_score, r_steps = oracle.translate_ensemble(refs, src, beam=beam, topk=k, max_steps=12)
+        assert toks.tolist() == r_toks.tolist(), (src.tolist(), toks.tolist(), r_toks.tolist())
+        assert steps == r_steps
+        assert abs(float(score) - float(r_score)) <= 1e-5 * max(1.0, abs(float(r_score)))
+        finished += len(toks) < steps
+        differs += toks.tolist() != q.q8_translate(ctx, gpus[0], src, beam=beam, k=k, max_steps=12)[0].tolist()
+    assert finished > 0 and differs > 0       # searches ended early, and the second model changed results
+    # one model through the ensemble entry point is the single-model search
+    one = q.q8_translate_ensemble(ctx, gpus[:1], src, beam=beam, k=k, max_steps=12)
+    assert one[0].tolist() == q.q8_translate(ctx, gpus[0], src, beam=beam, k=k, max_steps=12)[0].tolist()
+
+
+def test_translate_ensemble_full_size(q, ctx, oracle):
+    pa, pb = synth.full_model(seed=4), synth.full_model(seed=14)
+    refs = [oracle.OracleModel(pa), oracle.OracleModel(pb)]
+    gpus = [q.Model.from_params(ctx, pa), q.Model.from_params(ctx, pb)]
+    src = synth.sentences(seed=4, n=1, V=50000, min_len=6, max_len=8)[0]
+    ectx = q.Context(workspace_bytes=q.q8_workspace_bytes() + q.q8_translate_ensemble_bytes(gpus, 16) + (1 << 20))
+    toks, score, steps = q.q8_translate_ensemble(ectx, gpus, src, beam=5, k=12, max_steps=3)
+    r_toks, r_score, r_steps = oracle.translate_ensemble(refs, src, beam=5, topk=12, max_steps=3)
+    assert toks.tolist() == r_toks.tolist() and steps == r_steps
+    assert abs(float(score) - float(r_score)) <= 1e-5 * max(1.0, abs(float(r_score)))
