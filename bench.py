@@ -285,6 +285,41 @@ def paper_shapes(torch, q, ctx, rng, steps):
     return out
 
 
+def fp32_engine(torch, q, ctx, p, m, rng, steps, int8_steps_per_s):
+    """The paper's comparison (Tables 3 and 6: 8-bit against 32-bit decoding speed) on this GPU: the same
+    decoder step with fp32 weights and no quantization (171 MB of weights per step instead of 43 MB)."""
+    mf = lambda k: q.MatF(ctx, p[k])
+    gru = lambda pre: q.GruWeightsF32(mf(pre + ".Wx"), mf(pre + ".Wh"), ctx.f32(p[pre + ".bx"]), ctx.f32(p[pre + ".bh"]))
+    w = q.CgruWeightsF32(gru("dec_r"), mf("att.U"), ctx.f32(p["att.v"]), gru("dec_q"))
+    ro = q.ReadoutWeightsF32(mf("ro.Ws"), mf("ro.Wy"), mf("ro.Wc"), ctx.f32(p["ro.b"]))
+    W_out, b_out = mf("out.W"), ctx.f32(p["out.b"])
+    enc_h = ctx.f32(rng.standard_normal((L, 2048)).astype(np.float32))
+    attW = mf("att.W")
+    P = torch.cat([q.q8_gemv_f32(ctx, attW, enc_h[o:o + 8].contiguous(), m.att_b) for o in range(0, L, 8)])
+    out = {}
+    for n in (1, BEAM):
+        state = torch.zeros(q.q8_beam_state_bytes(MAX_STEPS), dtype=torch.uint8, device=ctx.device)
+        y, s = ctx.empty(n, 512), ctx.empty(n, 1024)
+        s0 = ctx.f32(rng.standard_normal(1024).astype(np.float32))
+        c0 = q.q8_beam_init(ctx, state, n, MAX_STEPS, s0, m.E_tgt, y, s, bind=True)
+        c1 = q.cgru_decoder_step_f32(ctx, w, P, enc_h, y, s, bind=True)
+        c2 = q.output_logits_f32(ctx, ro, W_out, b_out, c1.out["s"], y, c1.out["ctx"], k=TOPK, want_logits=False, bind=True)
+        c3 = q.q8_beam_update(ctx, state, c2.out["topk_logp"], c2.out["topk_idx"], c1.out["s"], m.E_tgt, y, s, bind=True)
+        t = [0]
+
+        def step():
+            if t[0] % MAX_STEPS == 0:
+                c0.launch()
+            t[0] += 1
+            c1.launch(); c2.launch(); c3.launch()
+        out["steps_per_s_beam%d" % n] = 1.0 / time_loop(torch, step, steps, max(steps // 10, 10))
+    out["fp32_weight_bytes_per_step"] = 4 * (15204352 + 1835008 + 25600000)
+    out["int8_over_fp32_beam5"] = int8_steps_per_s / out["steps_per_s_beam5"]
+    out["note"] = ("the paper reports 4-6x for 8-bit over 32-bit on a Xeon core, where the step is bound by arithmetic and "
+                   "memory bandwidth; here both engines are bound by launch and dependency latency at one sentence")
+    return out
+
+
 def ensemble_run(torch, q, p, m, n_sent):
     """Section 4's ensemble of two models (the second one an independent random model of the
     same shape): each step runs both decoders and output layers and averages the distributions."""
@@ -459,6 +494,7 @@ def main():
         extra["paper_shapes_620_1000_63644"] = paper_shapes(torch, q, ctx, rng, max(args.steps // 4, 100))
         extra["batched_decoding"] = batched_decoding(torch, q, m, rng, max(args.steps // 10, 50))
         extra["translate"] = translate_run(q, ctx, m, args.sentences)
+        extra["fp32_engine"] = fp32_engine(torch, q, ctx, p, m, rng, max(args.steps // 4, 100), 1.0 / eager5)
         m.ctx_for_bench = ctx
         extra["ensemble_of_2"] = ensemble_run(torch, q, p, m, 5)
         extra["steps_per_s_beam1"] = 1.0 / eager1

@@ -316,6 +316,26 @@ q8_status q8_translate_ensemble(q8_ctx *ctx, const q8_model *const *models, int 
                                 int l, int beam, int k, int max_steps, int32_t *tokens_host, int *len_host,
                                 float *score_host, int *steps_host);
 
+/* ---- The 32-bit engine (Section 4 compares the 8-bit engine with it, Tables 3 and 6) ----
+ * The same model with fp32 weights and no quantization: a product is
+ * y = (float)(sum_k W[i,k] x[k], accumulated in double) + bias.  Everything else (gates,
+ * attention, softmax, top-k, search) is shared with the 8-bit path.  fp32 matrices are
+ * row-major [rows x ld] with ld % 4 == 0 and a 16-byte aligned base; n <= 8 vectors. */
+typedef struct { const float *data; int rows, cols, ld; } q8_matf;
+typedef struct { q8_matf Wx, Wh; const float *bx, *bh; } q8_gru_weights_f32;
+typedef struct { q8_gru_weights_f32 r; q8_matf att_U; const float *att_v; q8_gru_weights_f32 q; } q8_cgru_weights_f32;
+typedef struct { q8_matf W_s, W_y, W_c; const float *b_t; } q8_readout_weights_f32;
+
+q8_status q8_gemv_f32(q8_ctx *ctx, const q8_matf *W, const float *X, int n, int ldx, const float *bias, float *Y,
+                      int ldy);
+/* As cgru_decoder_step_q8 / output_logits_q8 (ro must not be NULL), without taps. */
+q8_status cgru_decoder_step_f32(q8_ctx *ctx, const q8_cgru_weights_f32 *w, const float *P, const float *enc_h, int l,
+                                const float *y_emb, const float *s_prev, int n_beam, float *s_out, float *ctx_out,
+                                float *alpha_out, float *s_mid_out);
+q8_status output_logits_f32(q8_ctx *ctx, const q8_readout_weights_f32 *ro, const q8_matf *W_out, const float *b_out,
+                            const float *s, const float *y_emb, const float *ctx_vec, int n_beam, int k, float *logits,
+                            float *lse, float *topk_logp, int32_t *topk_idx, float *t_out);
+
 /* Measurement helpers (not operations of the paper).
  *
  * Between q8_profile_begin and q8_profile_end, up to max_samples launches of the

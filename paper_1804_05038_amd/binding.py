@@ -15,7 +15,8 @@ _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 __all__ = ["Q8Error", "Context", "Mat", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
            "q8_quantize_matrix", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "gru_step_q8", "cgru_decoder_step_q8",
            "output_logits_q8", "output_logits_beam_q8", "q8_encode", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
-           "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "q8_translate_ensemble", "q8_translate_ensemble_bytes", "cgru_decoder_step_batch_q8", "q8_encode_batch", "q8_encode_batch_bytes", "q8_beam_init_batch",
+           "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "MatF", "GruWeightsF32", "CgruWeightsF32", "ReadoutWeightsF32", "q8_gemv_f32",
+           "cgru_decoder_step_f32", "output_logits_f32", "q8_translate_ensemble", "q8_translate_ensemble_bytes", "cgru_decoder_step_batch_q8", "q8_encode_batch", "q8_encode_batch_bytes", "q8_beam_init_batch",
            "q8_beam_update_batch", "q8_beam_result_batch", "q8_translate_batch", "q8_translate_batch_bytes",
            "KERNEL_CLASSES", "LIB_PATH"]
 LIB_PATH = _LIB_PATH
@@ -99,6 +100,9 @@ def load_library():
         lib.q8_profile_begin.argtypes = [vp, ci, ci]
         lib.q8_probe_read.argtypes = [vp, vp, C.c_size_t]
         lib.cgru_decoder_step_batch_q8.argtypes = [vp, C.POINTER(_Cgru), vp, vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+        lib.q8_gemv_f32.argtypes = [vp, C.POINTER(_MatF), vp, ci, ci, vp, vp, ci]
+        lib.cgru_decoder_step_f32.argtypes = [vp, C.POINTER(_CgruF), vp, vp, ci, vp, vp, ci, vp, vp, vp, vp]
+        lib.output_logits_f32.argtypes = [vp, C.POINTER(_ReadoutF), C.POINTER(_MatF), vp, vp, vp, vp, ci, ci, vp, vp, vp, vp, vp]
         lib.q8_translate_ensemble_bytes.restype = C.c_size_t
         lib.q8_translate_ensemble_bytes.argtypes = [vp, ci, ci, ci, ci, ci]
         lib.q8_translate_ensemble.argtypes = [vp, vp, ci, vp, ci, ci, ci, ci, vp, ip, C.POINTER(C.c_float), ip]
@@ -179,6 +183,56 @@ class Mat:
         self.scale = float(scale)
         self.tiles = tiles
         self.c = _Mat(data.data_ptr(), self.rows, cols, self.ld, self.scale, tiles.data_ptr() if tiles is not None else None)
+
+
+class _MatF(C.Structure):
+    _fields_ = [("data", C.c_void_p), ("rows", C.c_int), ("cols", C.c_int), ("ld", C.c_int)]
+
+
+class _GruF(C.Structure):
+    _fields_ = [("Wx", _MatF), ("Wh", _MatF), ("bx", C.c_void_p), ("bh", C.c_void_p)]
+
+
+class _CgruF(C.Structure):
+    _fields_ = [("r", _GruF), ("att_U", _MatF), ("att_v", C.c_void_p), ("q", _GruF)]
+
+
+class _ReadoutF(C.Structure):
+    _fields_ = [("W_s", _MatF), ("W_y", _MatF), ("W_c", _MatF), ("b_t", C.c_void_p)]
+
+
+class MatF:
+    """q8_matf: fp32 device matrix [rows x ld] of the 32-bit engine (ld padded to a multiple of 4)."""
+
+    def __init__(self, ctx, W):
+        import numpy as np
+        W = np.asarray(W, dtype=np.float32)
+        rows, cols = W.shape
+        ld = (cols + 3) // 4 * 4
+        buf = np.zeros((rows, ld), np.float32)
+        buf[:, :cols] = W
+        self.data = ctx.f32(buf)
+        self.rows, self.cols, self.ld = rows, cols, ld
+        self.c = _MatF(self.data.data_ptr(), rows, cols, ld)
+
+
+class GruWeightsF32:
+    def __init__(self, Wx, Wh, bx, bh):
+        self.Wx, self.Wh, self.bx, self.bh = Wx, Wh, bx, bh
+        self.H = Wh.cols
+        self.c = _GruF(Wx.c, Wh.c, bx.data_ptr(), bh.data_ptr())
+
+
+class CgruWeightsF32:
+    def __init__(self, r, att_U, att_v, q):
+        self.r, self.att_U, self.att_v, self.q = r, att_U, att_v, q
+        self.c = _CgruF(r.c, att_U.c, att_v.data_ptr(), q.c)
+
+
+class ReadoutWeightsF32:
+    def __init__(self, W_s, W_y, W_c, b_t):
+        self.W_s, self.W_y, self.W_c, self.b_t = W_s, W_y, W_c, b_t
+        self.c = _ReadoutF(W_s.c, W_y.c, W_c.c, b_t.data_ptr())
 
 
 class _Bound:
@@ -429,6 +483,43 @@ def q8_translate(ctx, model, src_tokens, beam=5, k=12, max_steps=100):
     ctx.check(ctx.lib.q8_translate(ctx.handle, C.byref(model.c), _ptr(src), src.shape[0], beam, k, max_steps,
                                    out, C.byref(n), C.byref(score), C.byref(steps)))
     return np.array(out[:n.value], dtype=np.int32), np.float32(score.value), steps.value
+
+
+def q8_gemv_f32(ctx, W, X, bias=None, Y=None):
+    """fp32 product of the 32-bit engine for n <= 8 vectors X [n x cols] (or one vector [cols])."""
+    one = X.dim() == 1
+    n = 1 if one else X.shape[0]
+    ldx = W.cols if one else X.stride(0)
+    Y = ctx.empty(n, W.rows) if Y is None else Y
+    ctx.check(ctx.lib.q8_gemv_f32(ctx.handle, C.byref(W.c), _ptr(X), n, ldx, _ptr(bias), _ptr(Y), W.rows))
+    return Y[0] if one else Y
+
+
+def cgru_decoder_step_f32(ctx, w, P, enc_h, y_emb, s_prev, bind=False):
+    n, l = y_emb.shape[0], P.shape[0]
+    H, Cd = w.r.H, w.q.Wx.cols
+    r = {"s": ctx.empty(n, H), "ctx": ctx.empty(n, Cd), "alpha": ctx.empty(n, l), "s_mid": ctx.empty(n, H)}
+    args = (ctx.handle, C.byref(w.c), _ptr(P), _ptr(enc_h), l, _ptr(y_emb), _ptr(s_prev), n, _ptr(r["s"]), _ptr(r["ctx"]),
+            _ptr(r["alpha"]), _ptr(r["s_mid"]))
+    if bind:
+        r["keep"] = (w, P, enc_h, y_emb, s_prev)
+        return _Bound(ctx, ctx.lib.cgru_decoder_step_f32, args, r)
+    ctx.check(ctx.lib.cgru_decoder_step_f32(*args))
+    return r
+
+
+def output_logits_f32(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, k=12, want_logits=True, bind=False):
+    n, V, R = s.shape[0], W_out.rows, W_out.cols
+    r = {"lse": ctx.empty(n), "topk_logp": ctx.empty(n, k), "topk_idx": ctx.empty(n, k, dtype=torch.int32), "t": ctx.empty(n, R)}
+    if want_logits:
+        r["logits"] = ctx.empty(n, V)
+    args = (ctx.handle, C.byref(ro.c), C.byref(W_out.c), _ptr(b_out), _ptr(s), _ptr(y_emb), _ptr(ctx_vec), n, k,
+            _ptr(r.get("logits")), _ptr(r["lse"]), _ptr(r["topk_logp"]), _ptr(r["topk_idx"]), _ptr(r["t"]))
+    if bind:
+        r["keep"] = (ro, W_out, b_out, s, y_emb, ctx_vec)
+        return _Bound(ctx, ctx.lib.output_logits_f32, args, r)
+    ctx.check(ctx.lib.output_logits_f32(*args))
+    return r
 
 
 def _model_ptrs(models):

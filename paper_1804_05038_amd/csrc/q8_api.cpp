@@ -687,6 +687,123 @@ q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens
     return st;
 }
 
+// -------------------------------------------------------------------- the 32-bit engine ----
+
+namespace {
+q8_status check_matf(q8_ctx *ctx, const q8_matf *W, const char *name)
+{
+    if (!W || !W->data) return q8_fail(ctx, Q8_ERR_NULL, "%s: NULL matrix", name);
+    if (W->rows <= 0 || W->cols <= 0 || W->ld < W->cols || W->cols > kMaxLd)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "%s: bad shape %d x %d (ld %d)", name, W->rows, W->cols, W->ld);
+    if (!aligned16(W->data) || W->ld % 4 != 0)
+        return q8_fail(ctx, Q8_ERR_ALIGN, "%s: needs a 16-byte aligned base and ld %% 4 == 0", name);
+    return Q8_OK;
+}
+q8_status check_gruf(q8_ctx *ctx, const q8_gru_weights_f32 *g, const char *name)
+{
+    TRY(check_matf(ctx, &g->Wx, name));
+    TRY(check_matf(ctx, &g->Wh, name));
+    if (g->Wx.rows != g->Wh.rows || g->Wh.rows != 3 * g->Wh.cols)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "%s: expected Wx [3H x I], Wh [3H x H]", name);
+    return Q8_OK;
+}
+// the vectors of one launch sit in LDS as floats
+bool f32_fits(int n, int cols) { return (size_t)n * ((cols + 3) & ~3) * 4 <= 65536; }
+}  // namespace
+
+q8_status q8_gemv_f32(q8_ctx *ctx, const q8_matf *W, const float *X, int n, int ldx, const float *bias, float *Y, int ldy)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    TRY(check_matf(ctx, W, "W"));
+    if (n <= 0 || n > kMaxNarrow) return q8_fail(ctx, Q8_ERR_SHAPE, "n = %d outside [1, %d]", n, kMaxNarrow);
+    if (!X || !Y) return q8_fail(ctx, Q8_ERR_NULL, "q8_gemv_f32: NULL argument");
+    if (n > 1 && (ldx < W->cols || ldy < W->rows)) return q8_fail(ctx, Q8_ERR_SHAPE, "q8_gemv_f32: leading dimensions too small");
+    if (!f32_fits(n, W->cols)) return q8_fail(ctx, Q8_ERR_SHAPE, "n * cols exceeds 16384");
+    const q8i_f32_job j = {W, X, ldx, bias, Y, ldy};
+    return q8i_gemv_f32(ctx, &j, 1, n);
+}
+
+q8_status cgru_decoder_step_f32(q8_ctx *ctx, const q8_cgru_weights_f32 *w, const float *P, const float *enc_h, int l,
+                                const float *y_emb, const float *s_prev, int n_beam, float *s_out, float *ctx_out,
+                                float *alpha_out, float *s_mid_out)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!w) return q8_fail(ctx, Q8_ERR_NULL, "weights: NULL");
+    TRY(check_gruf(ctx, &w->r, "r"));
+    TRY(check_gruf(ctx, &w->q, "q"));
+    TRY(check_matf(ctx, &w->att_U, "att_U"));
+    const int n = n_beam, H = w->r.Wh.cols, E = w->r.Wx.cols, C = w->q.Wx.cols, A = w->att_U.rows;
+    if (n <= 0 || n > kMaxNarrow) return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam = %d outside [1, %d]", n, kMaxNarrow);
+    if (l <= 0 || l > kMaxL) return q8_fail(ctx, Q8_ERR_SHAPE, "l = %d outside [1, %d]", l, kMaxL);
+    if (w->q.Wh.cols != H || w->att_U.cols != H) return q8_fail(ctx, Q8_ERR_SHAPE, "hidden sizes of r, q and att_U differ");
+    if (E % 4 || H % 4 || C % 4 || A % 4) return q8_fail(ctx, Q8_ERR_ALIGN, "E, H, C, A must be multiples of 4");
+    if (!w->att_v || !P || !enc_h || !y_emb || !s_prev || !s_out || !ctx_out)
+        return q8_fail(ctx, Q8_ERR_NULL, "cgru_decoder_step_f32: NULL argument");
+    if (!aligned16(w->att_v) || !aligned16(P) || !aligned16(enc_h) || !aligned16(ctx_out))
+        return q8_fail(ctx, Q8_ERR_ALIGN, "cgru_decoder_step_f32: fp32 buffers need 16-byte alignment");
+    if (s_out == s_prev) return q8_fail(ctx, Q8_ERR_SHAPE, "s_out must not alias s_prev");
+    if (!f32_fits(n, C) || !f32_fits(n, H) || !f32_fits(n, E)) return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam * dimension exceeds 16384");
+
+    Carver cv(ctx);
+    float *s_mid = s_mid_out ? s_mid_out : cv.take<float>((size_t)n * H);
+    float *a = cv.take<float>((size_t)n * A);
+    float *gx = cv.take<float>((size_t)n * 3 * H), *gh = cv.take<float>((size_t)n * 3 * H);
+    float *e = cv.take<float>((size_t)n * l);
+    if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "cgru_decoder_step_f32: workspace too small");
+    // Eq. 3: s' = r(y, s_prev)
+    const q8i_f32_job j1[2] = {{&w->r.Wx, y_emb, E, w->r.bx, gx, 3 * H}, {&w->r.Wh, s_prev, H, w->r.bh, gh, 3 * H}};
+    TRY(q8i_gemv_f32(ctx, j1, 2, n));
+    TRY(q8i_gru_gates(ctx, gx, gh, s_prev, H, s_mid, H, H, n));
+    // u(s') of Eq. 6 and the recurrent half of GRU q
+    const q8i_f32_job j2[2] = {{&w->att_U, s_mid, H, nullptr, a, A}, {&w->q.Wh, s_mid, H, w->q.bh, gh, 3 * H}};
+    TRY(q8i_gemv_f32(ctx, j2, 2, n));
+    // Eq. 5-6
+    TRY(q8i_attention(ctx, P, enc_h, l, A, C, a, w->att_v, n, e, alpha_out, ctx_out, nullptr, 0));
+    // Eq. 4: s = q(H_t, s')
+    const q8i_f32_job j3 = {&w->q.Wx, ctx_out, C, w->q.bx, gx, 3 * H};
+    TRY(q8i_gemv_f32(ctx, &j3, 1, n));
+    return q8i_gru_gates(ctx, gx, gh, s_mid, H, s_out, H, H, n);
+}
+
+q8_status output_logits_f32(q8_ctx *ctx, const q8_readout_weights_f32 *ro, const q8_matf *W_out, const float *b_out,
+                            const float *s, const float *y_emb, const float *ctx_vec, int n_beam, int k, float *logits,
+                            float *lse, float *topk_logp, int32_t *topk_idx, float *t_out)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!ro) return q8_fail(ctx, Q8_ERR_NULL, "readout weights: NULL");
+    TRY(check_matf(ctx, W_out, "W_out"));
+    TRY(check_matf(ctx, &ro->W_s, "W_s"));
+    TRY(check_matf(ctx, &ro->W_y, "W_y"));
+    TRY(check_matf(ctx, &ro->W_c, "W_c"));
+    const int n = n_beam, R = W_out->cols, V = W_out->rows;
+    if (n <= 0 || n > kMaxNarrow) return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam = %d outside [1, %d]", n, kMaxNarrow);
+    if (k <= 0 || k > kMaxK || k > V) return q8_fail(ctx, Q8_ERR_SHAPE, "k = %d outside [1, min(%d, rows)]", k, kMaxK);
+    if (V > q8i_out_max_rows()) return q8_fail(ctx, Q8_ERR_SHAPE, "W_out: more than %d rows", q8i_out_max_rows());
+    if (ro->W_s.rows != R || ro->W_y.rows != R || ro->W_c.rows != R)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "readout matrices must have %d rows", R);
+    if (R % 4) return q8_fail(ctx, Q8_ERR_ALIGN, "R must be a multiple of 4");
+    if (!s || !y_emb || !ctx_vec || !topk_logp || !topk_idx) return q8_fail(ctx, Q8_ERR_NULL, "output_logits_f32: NULL argument");
+    if (!f32_fits(n, ro->W_c.cols) || !f32_fits(n, ro->W_s.cols) || !f32_fits(n, ro->W_y.cols) || !f32_fits(n, R))
+        return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam * dimension exceeds 16384");
+    Carver cv(ctx);
+    float *part[3];
+    for (int u = 0; u < 3; ++u) part[u] = cv.take<float>((size_t)n * R);
+    float *t = t_out ? t_out : cv.take<float>((size_t)n * R);
+    const size_t ngrp = (size_t)q8i_out_tiles(V);
+    float *pm = cv.take<float>(ngrp * n);
+    double *ps = cv.take<double>(ngrp * n);
+    float *lg = logits ? logits : cv.take<float>((size_t)n * V);
+    if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_f32: workspace too small");
+    const q8i_f32_job j[3] = {{&ro->W_s, s, ro->W_s.cols, nullptr, part[0], R}, {&ro->W_y, y_emb, ro->W_y.cols, nullptr, part[1], R},
+                              {&ro->W_c, ctx_vec, ro->W_c.cols, nullptr, part[2], R}};
+    TRY(q8i_gemv_f32(ctx, j, 3, n));
+    TRY(q8i_readout_combine(ctx, part[0], part[1], part[2], ro->b_t, R, n, t, 0, nullptr, nullptr, nullptr));
+    const q8i_f32_job jo = {W_out, t, R, b_out, lg, V};
+    TRY(q8i_gemv_f32(ctx, &jo, 1, n));
+    TRY(q8i_logit_stats(ctx, lg, n, V, pm, ps));
+    return q8i_select_logits(ctx, pm, ps, lg, V, n, k, lse, topk_logp, topk_idx);
+}
+
 // ------------------------------------------------------------------------------ ensembles ----
 
 namespace {

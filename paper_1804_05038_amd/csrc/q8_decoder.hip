@@ -315,6 +315,7 @@ __global__ __launch_bounds__(256) void readout_combine_kernel(const float *__res
         if (b_t) p = p + b_t[u];
         t_out[o] = tanh_rn(p);
     }
+    if (!tq) return;                          // the 32-bit engine stops at t
     __syncthreads();                          // this block's t_j is read back below
     block_quantize<1>(t_out + (size_t)j * R, 1, R, R, ld, tq + (size_t)j * ld, s_scale, s_red);
     if (threadIdx.x == 0) {

@@ -156,6 +156,18 @@ q8_status q8i_select_normalized(q8_ctx *ctx, const float *part_max, const double
                                 int k, float *topk_logp, int32_t *topk_idx, const struct q8i_beam_desc *beam);
 q8_status q8i_beam_regather(q8_ctx *ctx, void *state, int n, const float *s_step, int H, const float *E_tgt, int E,
                             float *y_emb, float *s_next);
+struct q8i_f32_job {            // Y [n x ldy] = W . X + bias in fp32 (the 32-bit engine)
+    const q8_matf *W;
+    const float *X;
+    int ldx;
+    const float *bias;
+    float *Y;
+    int ldy;
+};
+q8_status q8i_gemv_f32(q8_ctx *ctx, const q8i_f32_job *d, int njobs, int n);          // njobs <= 3, n <= 8
+q8_status q8i_logit_stats(q8_ctx *ctx, const float *logits, int n, int V, float *part_max, double *part_sum);
+q8_status q8i_select_logits(q8_ctx *ctx, const float *part_max, const double *part_sum, const float *logits, int V, int n,
+                            int k, float *lse, float *topk_logp, int32_t *topk_idx);
 size_t q8i_beam_state_bytes(int max_steps);
 q8_status q8i_gather_rows(q8_ctx *ctx, const float *table, const int *idx, int n, int dim, float *out);
 q8_status q8i_beam_init(q8_ctx *ctx, void *state, int beam, int max_steps, const float *s0, const float *E_tgt, int E,

@@ -559,6 +559,13 @@ q8_status q8i_select_normalized(q8_ctx *ctx, const float *part_max, const double
     return launch_select(ctx, part_max, part_sum, c, 0, V, n, k, nullptr, topk_logp, topk_idx, beam, 1);
 }
 
+// Selection alone over stored row-major logits [n x V] and their tile statistics.
+q8_status q8i_select_logits(q8_ctx *ctx, const float *part_max, const double *part_sum, const float *logits, int V, int n,
+                            int k, float *lse, float *topk_logp, int32_t *topk_idx)
+{
+    return launch_select(ctx, part_max, part_sum, logits, 0, V, n, k, lse, topk_logp, topk_idx, nullptr, 0);
+}
+
 q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const float *T, int ldt, int n, int k,
                      float *logits, float *lse, float *topk_logp, int32_t *topk_idx, const q8_taps *taps,
                      float *part_max, double *part_sum, const q8i_beam_desc *beam)
