@@ -24,6 +24,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM-side bytes of one launch of the vocabulary kernel, from the two counter runs recorded in
+# profiles/decode_step_beam5_kernels.txt: 26.28 MB fetched + 2.00 MB written
+VOCAB_KERNEL_TRAFFIC_BYTES = 28.28e6
 L, BEAM, TOPK, MAX_STEPS = 30, 5, 12, 100
 
 
@@ -210,7 +213,7 @@ def mfma_products(torch, q, ctx, m, rng):
     return out
 
 
-def batched_decoding(torch, q, m, rng, steps):
+def batched_decoding(torch, q, m, rng, steps, sizes=(16, 64, 200), translate=True):
     from workloads import synth
     """Section 6's batching: S sentences decoded side by side (S x beam hypothesis slots per
     step), every product on the int8 matrix cores.  A step is cgru_decoder_step_batch_q8 +
@@ -218,7 +221,7 @@ def batched_decoding(torch, q, m, rng, steps):
     wsb = q.q8_workspace_bytes(max_n=1024, max_l=64, max_rows=50000, max_ld=2048) + (1024 << 20)
     ctx = q.Context("cuda:0", workspace_bytes=wsb)
     out = {}
-    for S in (16, 64, 200):
+    for S in sizes:
         n = S * BEAM
         enc_h = ctx.f32(rng.standard_normal((S * L, 2048)).astype(np.float32))
         P = torch.cat([q.q8_gemm_narrow(ctx, m.att_W, enc_h[o:o + 1000].contiguous(), m.att_b) for o in range(0, S * L, 1000)])
@@ -254,6 +257,8 @@ def batched_decoding(torch, q, m, rng, steps):
             ms, cnt = q.q8_profile_end(ctx)
             r["attention_us"] = ms * 1e3
         out["%d_sentences" % S] = r
+    if not translate:
+        return out
     sents = synth.sentences(seed=4, n=200)
     q.q8_translate_batch(ctx, m, sents[:4], beam=BEAM, k=TOPK, max_steps=MAX_STEPS)
     torch.cuda.synchronize()
@@ -368,6 +373,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--quick", action="store_true", help="beam-5 timed region and kernel timing only (profiling runs)")
     ap.add_argument("--sentences", type=int, default=20)
+    ap.add_argument("--batched", action="store_true", help="only the batched decoder step at 64 sentences (profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (translation shards by sentence, one sentence per GPU, "
@@ -386,6 +392,9 @@ def main():
     enc_h = ctx.f32(rng.standard_normal((L, 2048)).astype(np.float32))
     P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
 
+    if args.batched:
+        print(json.dumps({"batched_decoding": batched_decoding(torch, q, m, rng, args.steps // 10, sizes=(64,), translate=False)}))
+        return
     loop5 = DecodeLoop(q, ctx, m, P, enc_h, BEAM, rng)
     loop1 = DecodeLoop(q, ctx, m, P, enc_h, 1, rng)
 
@@ -514,7 +523,9 @@ def main():
         "weights_GBps_whole_step": weights_per_step / best5 / 1e9,
         "roofline": {"bound": "hbm", "kernel": "out_logits_kernel (50000x512 int8 weights, 5 hypotheses)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None, "bytes_per_launch": out_bytes, "kernel_us": k_ms * 1e3, "samples": k_n,
+                     "traffic": VOCAB_KERNEL_TRAFFIC_BYTES, "traffic_unit": "bytes per launch",
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE (x2.00) + WRITE_SIZE (x1.00) of bench.py --quick, "
+                                       "profiles/decode_step_beam5_kernels.txt", "bytes_per_launch": out_bytes, "kernel_us": k_ms * 1e3, "samples": k_n,
                      "regime": "warm: the same weights every step, served from the 256 MB Infinity Cache",
                      "read_stream_ceiling_GBps": ceil_warm["GBps"], "read_stream_ceiling_us": ceil_warm["kernel_us"],
                      "frac_of_read_stream_ceiling": ceil_warm["kernel_us"] / (k_ms * 1e3)},
