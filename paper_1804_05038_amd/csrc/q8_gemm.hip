@@ -244,6 +244,196 @@ __global__ __launch_bounds__(256) void gemm_block_kernel(GemmJobs jobs)
     }
 }
 
+// ================================================================ vocabulary panel ==
+// The vocabulary product for a panel of hypothesis slots (many sentences side by side).  Unlike
+// the block kernel above, a block keeps its share of the vectors' codes in LDS for its whole
+// life (up to 160 KB per workgroup on gfx950) and streams tile-packed 16-row weight tiles past
+// them, one tile ahead in registers: no barrier after the prologue, every weight byte read once
+// per column group.  Per (row tile, column tile): KC matrix-core steps, then dequantize, bias,
+// logits (tile by tile: one contiguous KiB per wave), and the tile's (max, sum of exp) per slot
+// with the cross-lane steps on v_permlane16/32_swap.
+struct PanelArgs {
+    const int8_t *tiles;   // tile-packed weights (q8_pack_tiles)
+    const int8_t *xq;      // [n x ld] codes
+    const float *xscale, *bias;
+    float *Y;              // [ntiles][n][16]
+    float *part_max;       // [n x ntiles]
+    double *part_sum;
+    int rows, ld, n, ntiles, cols_per_group;
+    float w_scale;
+};
+
+#define VP_WAVES 8
+#define VP_MAX_NT 16
+
+// combine lanes i, i + 16, i + 32, i + 48 (the four row groups of a result tile), all lanes get the result
+__device__ __forceinline__ float quad_rows_max(float v)
+{
+    auto q = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(q[0]), __uint_as_float(q[1]));
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ double quad_rows_sum(double v)
+{
+    unsigned lo = (unsigned)__double2loint(v), hi = (unsigned)__double2hiint(v);
+    auto ql = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+    auto qh = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+    v = __hiloint2double((int)qh[0], (int)ql[0]) + __hiloint2double((int)qh[1], (int)ql[1]);
+    lo = (unsigned)__double2loint(v); hi = (unsigned)__double2hiint(v);
+    auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    return __hiloint2double((int)rh[0], (int)rl[0]) + __hiloint2double((int)rh[1], (int)rl[1]);
+}
+
+template <int KC>      // 64-byte k steps per row: ld = 64 KC
+__global__ __launch_bounds__(64 * VP_WAVES) void vocab_panel_kernel(PanelArgs a)
+{
+    extern __shared__ __align__(16) int8_t s_x[];        // [cols x pitch]
+    constexpr int ld = 64 * KC, pitch = ld + 16;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int n = a.n, c_base = blockIdx.y * a.cols_per_group;
+    const int cols = min(a.cols_per_group, n - c_base);       // > 0 by construction of the grid
+    const int nt = (cols + 15) >> 4;
+    // this wave's row tiles: gw, gw + stride, ...
+    const int gw = blockIdx.x * VP_WAVES + wave, stride = gridDim.x * VP_WAVES;
+
+    v4i A0[KC], A1[KC];
+    auto load_tile = [&](v4i (&A)[KC], int tile) {
+        const int8_t *p = a.tiles + ((size_t)(tile < a.ntiles ? tile : a.ntiles - 1) * KC) * 1024 + lane * 16;
+#pragma unroll
+        for (int s = 0; s < KC; ++s) A[s] = __builtin_nontemporal_load((const v4i *)(p + 1024 * s));
+    };
+    load_tile(A0, gw);
+    // the codes of this block's slots into LDS (rows past the panel are zero)
+    for (int p = tid; p < nt * 16 * (ld / 16); p += 64 * VP_WAVES) {
+        const int col = p / (ld / 16), ch = p - col * (ld / 16);
+        v4i v = (v4i){0, 0, 0, 0};
+        if (col < cols) v = *(const v4i *)(a.xq + (size_t)(c_base + col) * ld + ch * 16);
+        *(v4i *)(s_x + col * pitch + ch * 16) = v;
+    }
+    float *s_c = (float *)(s_x + (size_t)a.cols_per_group * pitch);      // dequantization factor of every slot
+    for (int c = tid; c < nt * 16; c += 64 * VP_WAVES) s_c[c] = c < cols ? a.w_scale * a.xscale[c_base + c] : 0.0f;
+    __syncthreads();
+
+    const bool bias_vec = (((uintptr_t)a.bias) & 15) == 0;
+    const int8_t *bp = s_x + i * pitch + 16 * g;
+    auto do_tile = [&](const v4i (&A)[KC], int tile) {
+        const int row0 = tile * 16 + 4 * g;
+        float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (a.bias) {
+            if (bias_vec && row0 + 3 < a.rows) {
+                b = *(const float4 *)(a.bias + row0);
+            } else {
+                if (row0 < a.rows) b.x = a.bias[row0];
+                if (row0 + 1 < a.rows) b.y = a.bias[row0 + 1];
+                if (row0 + 2 < a.rows) b.z = a.bias[row0 + 2];
+                if (row0 + 3 < a.rows) b.w = a.bias[row0 + 3];
+            }
+        }
+        float *ytile = a.Y + (size_t)tile * n * 16;
+        // four column tiles at a time: four independent accumulation chains keep the matrix core
+        // busy (a single chain waits ~44 cycles per step), and their epilogues interleave
+        for (int t0 = 0; t0 < nt; t0 += 4) {
+            v4i acc[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[u] = (v4i){0, 0, 0, 0};
+            const int8_t *bt = bp + t0 * 16 * pitch;
+#pragma unroll
+            for (int s = 0; s < KC; ++s)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    // column tiles past the panel read the last tile again (in bounds); their results are dropped
+                    const v4i bv = *(const v4i *)(bt + (t0 + u < nt ? u : 0) * 16 * pitch + 64 * s);
+                    acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[s], bv, acc[u], 0, 0, 0);
+                }
+            float y[4][4], m[4];
+            double sd[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int colr = 16 * (t0 + u) + i;                  // column within the panel
+                const bool col_ok = t0 + u < nt && colr < cols;
+                const float c = col_ok ? s_c[colr] : 0.0f;
+                m[u] = -INFINITY;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    y[u][r] = -INFINITY;
+                    if (col_ok && row0 + r < a.rows) {
+                        y[u][r] = (float)acc[u][r] * c;
+                        if (a.bias) y[u][r] = y[u][r] + (r == 0 ? b.x : r == 1 ? b.y : r == 2 ? b.z : b.w);
+                    }
+                    m[u] = fmaxf(m[u], y[u][r]);
+                }
+                if (col_ok)
+                    *(float4 *)(ytile + (size_t)(c_base + colr) * 16 + 4 * g) = make_float4(y[u][0], y[u][1], y[u][2], y[u][3]);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) m[u] = quad_rows_max(m[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                sd[u] = 0.0;
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (y[u][r] > -INFINITY) sd[u] += (double)__expf(y[u][r] - m[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) sd[u] = quad_rows_sum(sd[u]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int colr = 16 * (t0 + u) + i;
+                if (t0 + u < nt && colr < cols && g == 0) {
+                    a.part_max[(size_t)(c_base + colr) * a.ntiles + tile] = m[u];
+                    a.part_sum[(size_t)(c_base + colr) * a.ntiles + tile] = sd[u];
+                }
+            }
+        }
+    };
+    for (int tile = gw; tile < a.ntiles; tile += 2 * stride) {
+        load_tile(A1, tile + stride);
+        do_tile(A0, tile);
+        if (tile + stride < a.ntiles) {
+            load_tile(A0, tile + 2 * stride);
+            do_tile(A1, tile + stride);
+        }
+    }
+}
+
+// Whether the panel kernel takes this product: tile-packed weights with rows of 512 or 640 bytes.
+bool q8i_vocab_panel_ok(const q8_mat *W) { return W->tiles != nullptr && (W->ld == 512 || W->ld == 640); }
+
+q8_status q8i_vocab_panel(q8_ctx *ctx, const q8_mat *W, const float *bias, const int8_t *xq, const float *xscale, int n,
+                          float *Y_tiled, float *part_max, double *part_sum)
+{
+    PanelArgs a;
+    a.tiles = W->tiles; a.xq = xq; a.xscale = xscale; a.bias = bias; a.Y = Y_tiled;
+    a.part_max = part_max; a.part_sum = part_sum;
+    a.rows = W->rows; a.ld = W->ld; a.n = n; a.ntiles = (W->rows + 15) / 16; a.w_scale = W->scale;
+    // column groups of equal size, as many slots as fit the LDS (codes at pitch ld + 16, one float
+    // per slot) and VP_MAX_NT column tiles; about one block per compute unit
+    int max_cols = (int)((160 * 1024) / (size_t)(W->ld + 16 + 4)) & ~15;
+    if (max_cols > 16 * VP_MAX_NT) max_cols = 16 * VP_MAX_NT;
+    const int ngroups = (n + max_cols - 1) / max_cols;
+    a.cols_per_group = ((n + ngroups - 1) / ngroups + 15) & ~15;
+    int gx = 256 / ngroups;
+    if (gx < 1) gx = 1;
+    if (gx * VP_WAVES > a.ntiles) gx = (a.ntiles + VP_WAVES - 1) / VP_WAVES;
+    const int gy = (n + a.cols_per_group - 1) / a.cols_per_group;
+    const size_t smem = (size_t)a.cols_per_group * (W->ld + 16 + 4);
+    static bool attr_set[2] = {false, false};
+    const int which = W->ld == 512 ? 0 : 1;
+    if (!attr_set[which]) {
+        const hipError_t e = which == 0
+            ? hipFuncSetAttribute((const void *)vocab_panel_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)
+            : hipFuncSetAttribute((const void *)vocab_panel_kernel<10>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "vocabulary panel kernel: %s", hipGetErrorString(e));
+        attr_set[which] = true;
+    }
+    if (which == 0) Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, vocab_panel_kernel<8>, dim3(gx, gy), dim3(64 * VP_WAVES), smem, a);
+    else Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, vocab_panel_kernel<10>, dim3(gx, gy), dim3(64 * VP_WAVES), smem, a);
+    return q8i_launch_check(ctx, "vocabulary panel");
+}
+
 // Block (j, job): max-abs quantization of vector j's K floats into ld code bytes (pad bytes
 // zero), Section 3's "8-bit approximation" of an activation.
 struct QuantJob {

@@ -119,6 +119,9 @@ struct q8i_gemm_job {           // Y [n x ldy] = dequantize(W . xq) + bias on th
 };
 q8_status q8i_quantize_jobs(q8_ctx *ctx, const q8i_quant_job *d, int njobs, int n);   // njobs <= 3
 q8_status q8i_gemm_jobs(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n);        // njobs <= 3
+bool q8i_vocab_panel_ok(const q8_mat *W);
+q8_status q8i_vocab_panel(q8_ctx *ctx, const q8_mat *W, const float *bias, const int8_t *xq, const float *xscale, int n,
+                          float *Y_tiled, float *part_max, double *part_sum);
 q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode);
 q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, int A, int C, const float *a,
                         const float *v, int n, float *e, float *alpha, float *cvec, const int *sent_off, int beam);

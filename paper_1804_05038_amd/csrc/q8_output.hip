@@ -593,8 +593,13 @@ q8_status q8i_output_codes(q8_ctx *ctx, const q8_mat *W, const float *bias, cons
                            int k, float *logits, int tiled, float *lse, float *topk_logp, int32_t *topk_idx,
                            int32_t *tap_acc, float *part_max, double *part_sum)
 {
-    const q8i_gemm_job gj = {W, tq, tscale, bias, logits, W->rows, tap_acc, part_max, part_sum, tiled};
-    q8_status st = q8i_gemm_jobs(ctx, &gj, 1, n);
+    q8_status st;
+    if (tiled && !tap_acc && q8i_vocab_panel_ok(W)) {
+        st = q8i_vocab_panel(ctx, W, bias, tq, tscale, n, logits, part_max, part_sum);
+    } else {
+        const q8i_gemm_job gj = {W, tq, tscale, bias, logits, W->rows, tap_acc, part_max, part_sum, tiled};
+        st = q8i_gemm_jobs(ctx, &gj, 1, n);
+    }
     if (st) return st;
     return launch_select(ctx, part_max, part_sum, logits, tiled, W->rows, n, k, lse, topk_logp, topk_idx, nullptr);
 }

@@ -214,3 +214,22 @@ def test_output_layer_panel_ties(q, ctx, oracle):
             lse, lp, idx = oracle.logsoftmax_topk(L.gemv(t[j]), 12)
             assert idx[:5].tolist() == [5, 130, 131, 400, 2499] and idx[5:].tolist() == list(range(0, 5)) + [6, 7]
             assert_same(r["topk_idx"][j], idx); assert_close(r["topk_logp"][j], lp)
+
+
+@pytest.mark.parametrize("V,R,n,k", [(50000, 512, 20, 12), (3001, 512, 300, 12), (2000, 620, 250, 5), (777, 512, 9, 16),
+                                     (5000, 640, 1000, 12)])
+def test_output_layer_panel_persistent_kernel(q, ctx, oracle, V, R, n, k):
+    """Tile-packed vocabulary matrix and no logits requested: the panel kernel that keeps the slots'
+    codes in LDS and streams weight tiles (rows of 512 or 640 bytes)."""
+    p = synth.output_layer(seed=2, V=V, R=R, n_beam=n)
+    L = oracle.QLinear(p["out.W"], p["out.b"])
+    W = q.q8_pack_tiles(ctx, q.q8_quantize_matrix(ctx, p["out.W"], ld_out=(R + 63) // 64 * 64))
+    t = ctx.f32(p["t"])
+    r = q.output_logits_q8(ctx, None, W, ctx.f32(p["out.b"]), t_in=t, k=k, want_logits=False)
+    full = q.output_logits_q8(ctx, None, W, ctx.f32(p["out.b"]), t_in=t, k=k)          # stored logits: block kernel
+    assert_same(r["topk_idx"], np_(full["topk_idx"]), "panel kernel vs block kernel: top-k")
+    assert_same(r["topk_logp"], np_(full["topk_logp"])); assert_same(r["lse"], np_(full["lse"]))
+    for j in sorted(set([0, n // 3, n - 1])):
+        lse, lp, idx = oracle.logsoftmax_topk(L.gemv(p["t"][j]), k)
+        assert_same(r["topk_idx"][j], idx, "top-k indices"); assert_close(r["topk_logp"][j], lp, "top-k logp")
+        assert_close(r["lse"][j:j + 1], np.array([lse]), "lse")
