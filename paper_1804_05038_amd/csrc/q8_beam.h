@@ -39,93 +39,105 @@ __device__ __forceinline__ unsigned long long cand_key(float score, int parent, 
 
 __device__ __forceinline__ void beam_gather(const BeamUpdateArgs &a, const int *s_parent, const int *s_token);
 
-// One block of 256 threads.  Wave 0 selects the b_live best continuations and rewrites the
-// state; all threads then gather the surviving decoder states and the embeddings of the new
-// tokens.  COHERENT: the top-k tables were written by other blocks of the same kernel with
-// device-coherent stores and are read with device-coherent loads.
+// One block of 256 threads.  The (at most 128) candidates are ranked by counting: thread
+// (c, half) counts how many of one half of the keys beat candidate c, so a candidate's rank is
+// known after two barriers; thread 0 then walks the best b_live in order (finished hypotheses
+// leave the beam, the others become the next step's slots) and rewrites the state; all threads
+// gather the surviving decoder states and the embeddings of the new tokens.  COHERENT: the top-k
+// tables were written by other blocks of the same kernel with device-coherent stores and are
+// read with device-coherent loads.
 template <bool COHERENT>
 __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
 {
     __shared__ int s_parent[Q8_MAX_BEAM], s_token[Q8_MAX_BEAM];
-    __shared__ float s_score[Q8_MAX_BEAM];
+    __shared__ __align__(16) unsigned long long s_key[128];
+    __shared__ int s_rank[128];
+    __shared__ float s_rscore[Q8_MAX_BEAM];
+    __shared__ int s_rtoken[Q8_MAX_BEAM], s_rparent[Q8_MAX_BEAM];
     __shared__ int s_skip;
     BeamState *st = a.st;
-    const int tid = threadIdx.x, lane = tid & 63;
-    if (tid < 64) {
-        // Everything the selection needs is requested at once, before any of it is looked at:
-        // the state words, and this lane's two candidates of the [n x k] tables (whether their
-        // hypothesis is live is decided afterwards).
-        float lp[2], sc0[2];
-        int tk[2];
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int c = lane + 64 * t;
-            lp[t] = 0.0f; tk[t] = 0; sc0[t] = 0.0f;
-            if (c < a.n * a.k) {
-                lp[t] = COHERENT ? __hip_atomic_load(a.topk_logp + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                 : a.topk_logp[c];
-                tk[t] = COHERENT ? __hip_atomic_load(a.topk_idx + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                 : a.topk_idx[c];
-                sc0[t] = st->score[c / a.k];
-            }
+    const int tid = threadIdx.x;
+    // everything the selection needs is requested at once, before any of it is looked at
+    const int c = tid & 127, half = tid >> 7;
+    float lp = 0.0f, sc0 = 0.0f;
+    int tk = 0;
+    if (c < a.n * a.k) {
+        lp = COHERENT ? __hip_atomic_load(a.topk_logp + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.topk_logp[c];
+        tk = COHERENT ? __hip_atomic_load(a.topk_idx + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.topk_idx[c];
+        sc0 = st->score[c / a.k];
+    }
+    const int n_live = st->n_live, b_live = st->b_live, step = st->step, max_steps = st->max_steps;
+    const bool skip = st->done != 0;
+    const int have_fin0 = st->have_fin, fin_len0 = st->fin_len, fin_parent0 = st->fin_parent;
+    const float fin_score0 = st->fin_score;
+    const int ncand = skip ? 0 : n_live * a.k;
+    const int take = min(b_live, ncand);
+    unsigned long long key = 0ull;
+    float csc = -INFINITY;
+    if (c < ncand) {
+        csc = sc0 + lp;
+        key = cand_key(csc, c / a.k, tk);
+    }
+    if (half == 0) { s_key[c] = key; s_rank[c] = 0; }
+    __syncthreads();
+    if (c < ncand) {
+        // keys are distinct (they contain parent and token), so the counts are a permutation
+        const int lo = half * 64;
+        int cnt = 0;
+#pragma unroll 4
+        for (int u = lo; u < lo + 64 && u < ncand; u += 2) {
+            const ulonglong2 p2 = *(const ulonglong2 *)&s_key[u];
+            cnt += (p2.x > key) + (p2.y > key);
         }
-        const int n_live = st->n_live, b_live = st->b_live, step = st->step, max_steps = st->max_steps;
-        const bool skip = st->done != 0;
-        int have_fin = st->have_fin, fin_len = st->fin_len, fin_parent = st->fin_parent;
-        float fin_score = st->fin_score;
+        if (cnt) atomicAdd(&s_rank[c], cnt);
+    }
+    __syncthreads();
+    if (half == 0 && c < ncand) {
+        const int r = s_rank[c];
+        if (r < take) { s_rscore[r] = csc; s_rtoken[r] = tk; s_rparent[r] = c / a.k; }
+    }
+    __syncthreads();
+    __shared__ float s_nscore[Q8_MAX_BEAM];
+    __shared__ int s_nnew;
+    if (tid == 0) {
+        int n_new = 0;
         if (!skip) {
-            int *link = st->link + (size_t)step * Q8_MAX_BEAM;
-            // two candidates per lane: c = lane, lane + 64 over [n_live x k]
-            unsigned long long key[2];
-            float csc[2];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const int c = lane + 64 * t;
-                key[t] = 0ull;
-                csc[t] = -INFINITY;
-                if (c < n_live * a.k) {
-                    const float sc = sc0[t] + lp[t];
-                    csc[t] = sc;
-                    key[t] = cand_key(sc, c / a.k, tk[t]);
-                }
-            }
-            const int take = min(b_live, n_live * a.k);
-            int n_new = 0, b_left = b_live;
+            int have_fin = have_fin0, fin_len = fin_len0, fin_parent = fin_parent0;
+            float fin_score = fin_score0;
+            int b_left = b_live;
             for (int r = 0; r < take; ++r) {
-                const unsigned long long best = wave_max_u64(key[0] > key[1] ? key[0] : key[1]);
-                const int parent = 15 - (int)((best >> 20) & 0xF);
-                const int token = 0xFFFFF - (int)(best & 0xFFFFF);
-                // the owner lane supplies the exact score
-                float sc = -INFINITY;
-                if (key[0] == best) { sc = csc[0]; key[0] = 0ull; }
-                if (key[1] == best) { sc = csc[1]; key[1] = 0ull; }
-                sc = wave_max_f(sc);
+                const float sc = s_rscore[r];
+                const int token = s_rtoken[r], parent = s_rparent[r];
                 if (token == 0) {                      // end of sentence: the hypothesis is finished
                     if (!have_fin || sc > fin_score) {
                         have_fin = 1; fin_score = sc; fin_len = step; fin_parent = parent;
                     }
                     --b_left;
                 } else {
-                    if (lane == 0) { s_score[n_new] = sc; s_token[n_new] = token; s_parent[n_new] = parent; }
+                    s_nscore[n_new] = sc; s_token[n_new] = token; s_parent[n_new] = parent;
                     ++n_new;
                 }
             }
-            if (lane == 0) {
-                for (int q = 0; q < Q8_MAX_BEAM; ++q) {
-                    st->score[q] = q < n_new ? s_score[q] : -INFINITY;
-                    st->last[q] = q < n_new ? s_token[q] : 0;
-                    if (q < n_new) link[q] = (s_parent[q] << 24) | s_token[q];
-                    if (q >= n_new) {               // dead slots repeat survivor 0: finite data for the next step
-                        s_parent[q] = n_new ? s_parent[0] : 0;
-                        s_token[q] = n_new ? s_token[0] : 0;
-                    }
-                }
-                st->have_fin = have_fin; st->fin_score = fin_score; st->fin_len = fin_len; st->fin_parent = fin_parent;
-                st->n_live = n_new; st->b_live = b_left; st->step = step + 1;
-                if (b_left == 0 || n_new == 0 || step + 1 >= max_steps) st->done = 1;
-            }
+            st->have_fin = have_fin; st->fin_score = fin_score; st->fin_len = fin_len; st->fin_parent = fin_parent;
+            st->n_live = n_new; st->b_live = b_left; st->step = step + 1;
+            if (b_left == 0 || n_new == 0 || step + 1 >= max_steps) st->done = 1;
         }
-        if (lane == 0) { s_skip = skip; st->gathered = skip ? 0 : 1; }
+        s_nnew = n_new;
+        s_skip = skip;
+        st->gathered = skip ? 0 : 1;
+    }
+    __syncthreads();
+    if (!skip && tid < Q8_MAX_BEAM) {                   // slot tid of the state, one thread each
+        const int n_new = s_nnew, q = tid;
+        st->score[q] = q < n_new ? s_nscore[q] : -INFINITY;
+        st->last[q] = q < n_new ? s_token[q] : 0;
+        if (q < n_new) st->link[(size_t)step * Q8_MAX_BEAM + q] = (s_parent[q] << 24) | s_token[q];
+    }
+    __syncthreads();
+    if (!skip && tid < Q8_MAX_BEAM && tid >= s_nnew) {  // dead slots repeat survivor 0: finite data for the next step
+        const int p0 = s_nnew ? s_parent[0] : 0, t0 = s_nnew ? s_token[0] : 0;
+        s_parent[tid] = p0;
+        s_token[tid] = t0;
     }
     __syncthreads();
     if (s_skip) return;
