@@ -495,6 +495,26 @@ static inline int q8_lanes_per_row(int ld)
     return ld <= 256 ? 16 : (ld <= 512 ? 32 : 64);
 }
 
+// combine lanes i, i + 16, i + 32, i + 48 (the four row groups of a result tile), all lanes get the result
+__device__ __forceinline__ float quad_rows_max(float v)
+{
+    auto q = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(q[0]), __uint_as_float(q[1]));
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ double quad_rows_sum(double v)
+{
+    unsigned lo = (unsigned)__double2loint(v), hi = (unsigned)__double2hiint(v);
+    auto ql = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+    auto qh = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+    v = __hiloint2double((int)qh[0], (int)ql[0]) + __hiloint2double((int)qh[1], (int)ql[1]);
+    lo = (unsigned)__double2loint(v); hi = (unsigned)__double2hiint(v);
+    auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    return __hiloint2double((int)rh[0], (int)rl[0]) + __hiloint2double((int)rh[1], (int)rl[1]);
+}
+
 // fp32 nonlinearities of the gates, evaluated in double and rounded once (q8_math.h).
 __device__ __forceinline__ float sigmoid_rn(float a) { return q8_sigmoid_rn(a); }
 __device__ __forceinline__ float tanh_rn(float a) { return q8_tanh_rn(a); }

@@ -269,6 +269,135 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     out_logits_body<1, PACKED, QKPL>(a);
 }
 
+// Buffer descriptor over [base, base + bytes): a load through it at an offset at or past
+// `bytes` returns zero without touching memory.  A load that has nothing to fetch is then
+// still an unconditional instruction, and the counts the compiler waits on stay exact
+// (a load inside a branch makes it wait for everything in flight).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t q8_rsrc(const void *base, size_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)bytes, 0x00020000);
+}
+#define Q8_OOB 0x80000000u           // past the end of every descriptor used here (sizes stay below 2^31)
+
+// The kernel for tile-packed matrices with rows of at most 512 bytes: one tile per wave, eight
+// waves per block, two blocks per compute unit, so that all of the matrix is requested within
+// the first microsecond and nothing loops.  Wave j < n requests hidden vector j first (its
+// data comes back ahead of the weights, which every wave requests next), quantizes it alone
+// (no exchange between waves) and leaves the codes in LDS; after the one barrier every wave
+// holds the codes of all vectors as operand B in registers.  KPL float4 per lane and vector.
+template <int KPL>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))) void out_logits8_kernel(OutArgs a)
+{
+    extern __shared__ __align__(16) int8_t smem[];     // [n x pitch] codes of the hidden vectors
+    __shared__ float s_scale[8];
+    const int ld = a.ld, n = a.n, pitch = ld + 16, ksteps = ld >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int i = lane & 15, g = lane >> 4;
+    const int tile = blockIdx.x + wave * gridDim.x;
+    const bool have = tile < a.ntiles;
+
+    const __amdgpu_buffer_rsrc_t rT = q8_rsrc(a.T, ((size_t)(n - 1) * a.ldt + a.K) * sizeof(float));
+    float4 tv[KPL];
+#pragma unroll
+    for (int t = 0; t < KPL; ++t) {
+        const int k = (t * 64 + lane) * 4;
+        const unsigned off = (wave < n && k < a.K) ? (unsigned)(wave * a.ldt + k) * 4u : Q8_OOB;
+        tv[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rT, (int)off, 0, 0));
+    }
+    // the tile: eight wave-wide loads of one contiguous KiB each, non-temporal like Q8_WLOAD
+    const __amdgpu_buffer_rsrc_t rW = q8_rsrc(a.tiles, (size_t)a.ntiles * ld * OUT_TILE);
+    const unsigned woff = have ? (unsigned)tile * (unsigned)(ld * OUT_TILE) + lane * 16u : Q8_OOB;
+    v4i av[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        const unsigned off = s < ksteps ? woff + 1024u * s : Q8_OOB;
+        av[s] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rW, (int)off, 0, 2));
+    }
+    // bias of the four rows this lane finishes
+    const int row0 = tile * OUT_TILE + 4 * g;
+    const __amdgpu_buffer_rsrc_t rB = q8_rsrc(a.bias, a.bias ? (size_t)a.V * sizeof(float) : 0);
+    float bias[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const unsigned off = (have && i < n) ? (unsigned)(row0 + r) * 4u : Q8_OOB;
+        bias[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rB, (int)off, 0, 0));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    if (wave < n) {
+        float m = 0.0f;
+#pragma unroll
+        for (int t = 0; t < KPL; ++t)
+            m = fmaxf(m, fmaxf(fmaxf(fabsf(tv[t].x), fabsf(tv[t].y)), fmaxf(fabsf(tv[t].z), fabsf(tv[t].w))));
+        m = wave_max_f(m);
+        float scale, inv;
+        q8_scale_of(m, scale, inv);
+#pragma unroll
+        for (int t = 0; t < KPL; ++t) {
+            const int k = (t * 64 + lane) * 4;         // values beyond K are zero, so the pad bytes come out zero
+            if (k < ld) *(int *)(smem + (size_t)wave * pitch + k) = q8_pack4(tv[t].x, tv[t].y, tv[t].z, tv[t].w, inv);
+        }
+        if (lane == 0) s_scale[wave] = scale;
+    }
+    __syncthreads();
+    if (blockIdx.x == 0) {
+        if (a.taps.xq)
+            for (int e = threadIdx.x; e < n * a.K; e += blockDim.x) a.taps.xq[e] = smem[(e / a.K) * pitch + e % a.K];
+        if (a.taps.xscale && threadIdx.x < n) a.taps.xscale[threadIdx.x] = s_scale[threadIdx.x];
+    }
+    if (!have) return;
+
+    // operand B: hypothesis i's codes, k = 64 s + 16 g ..
+    v4i bv[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        bv[s] = (v4i){0, 0, 0, 0};
+        if (i < n && s < ksteps) bv[s] = *(const v4i *)(smem + (size_t)i * pitch + 64 * s + 16 * g);
+    }
+    const float cj = i < n ? a.w_scale * s_scale[i] : 0.0f;
+    v4i acc0 = (v4i){0, 0, 0, 0}, acc1 = (v4i){0, 0, 0, 0};     // two chains: a dependent matrix-core op waits twice as long
+#pragma unroll
+    for (int s = 0; s < 8; s += 2) {
+        acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[s], bv[s], acc0, 0, 0, 0);
+        acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[s + 1], bv[s + 1], acc1, 0, 0, 0);
+    }
+    const v4i acc = acc0 + acc1;
+
+    float y[4];
+    float m = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        y[r] = -INFINITY;
+        if (i < n && row0 + r < a.V) {
+            y[r] = (float)acc[r] * cj;
+            if (a.bias) y[r] = y[r] + bias[r];
+            if (a.taps.acc) a.taps.acc[(size_t)i * a.V + row0 + r] = acc[r];
+        }
+        m = fmaxf(m, y[r]);
+    }
+    if (i < n) {
+        const bool vec_ok = ((a.ldl & 3) == 0) && (((uintptr_t)a.logits & 15) == 0);
+        if (vec_ok && row0 + 3 < a.V) {
+            *(float4 *)(a.logits + (size_t)i * a.ldl + row0) = make_float4(y[0], y[1], y[2], y[3]);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (row0 + r < a.V) a.logits[(size_t)i * a.ldl + row0 + r] = y[r];
+        }
+    }
+    // (max, sum of exp) of the tile's 16 rows per hypothesis: lanes i, i + 16, i + 32, i + 48
+    m = quad_rows_max(m);
+    double sd = 0.0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        if (y[r] > -INFINITY) sd += (double)__expf(y[r] - m);
+    sd = quad_rows_sum(sd);
+    if (i < n && g == 0) {
+        a.part_max[(size_t)i * a.ntiles + tile] = m;
+        a.part_sum[(size_t)i * a.ntiles + tile] = sd;
+    }
+}
+
 struct SelectArgs {
     const float *part_max;
     const double *part_sum;
@@ -581,8 +710,18 @@ q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const floa
     const int nblk = a.ntiles < 4 * OUT_BLOCKS ? (a.ntiles + 3) / 4 : OUT_BLOCKS;
     const size_t smem = (size_t)n * a.ld;
     const int ch = q8_fast_ch(a.ld);
-    if (a.tiles) launch_out_packed<true>(ctx, a, nblk, smem, ch);
-    else launch_out_packed<false>(ctx, a, nblk, smem, ch);
+    if (a.tiles && a.ld <= 512) {
+        // one tile per wave: a.ntiles <= OUT_MAX_TILES = 8 * OUT_BLOCKS
+        // (at most 256 blocks' worth of tiles: one block per compute unit; more: two each, evenly filled)
+        const int nblk8 = a.ntiles <= 8 * (OUT_BLOCKS / 2) ? (a.ntiles + 7) / 8 : OUT_BLOCKS;
+        const size_t smem8 = (size_t)n * (a.ld + 16);
+        if (a.K <= 256) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, out_logits8_kernel<1>, dim3(nblk8), dim3(512), smem8, a);
+        else Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, out_logits8_kernel<2>, dim3(nblk8), dim3(512), smem8, a);
+    } else if (a.tiles) {
+        launch_out_packed<true>(ctx, a, nblk, smem, ch);
+    } else {
+        launch_out_packed<false>(ctx, a, nblk, smem, ch);
+    }
     return launch_select(ctx, part_max, part_sum, logits, 0, a.V, n, k, lse, topk_logp, topk_idx, beam);
 }
 
