@@ -230,7 +230,8 @@ q8_status q8_beam_init(q8_ctx *ctx, void *state, int beam, int max_steps, const 
 /* One search step from the top-k of output_logits_q8 (topk_logp, topk_idx [n_beam x k]) and
  * the decoder states s_step [n_beam x H] of this step: updates the state and writes the
  * inputs of the next step, s_next [n_beam x H] (must not alias s_step) and y_emb
- * [n_beam x E] = E_tgt[new tokens].  Does nothing once the search is over. */
+ * [n_beam x E] = E_tgt[new tokens].  Does nothing once the search is over.  Every topk_idx must
+ * be a row of E_tgt: the table's height is not known here and the ids are not checked. */
 q8_status q8_beam_update(q8_ctx *ctx, void *state, const float *topk_logp, const int32_t *topk_idx, int n_beam,
                          int k, const float *s_step, int H, const float *E_tgt, int E, float *y_emb, float *s_next);
 
@@ -238,7 +239,9 @@ q8_status q8_beam_update(q8_ctx *ctx, void *state, const float *topk_logp, const
  * block of the selection kernel that finishes last): logits of the decoder states s
  * [n_beam x H] of this step, their k best entries, then the search step, which writes
  * s_next [n_beam x H] (must not alias s) and overwrites y_emb [n_beam x E] with the
- * embeddings of the new tokens.  topk_logp / topk_idx [n_beam x k] may be NULL (workspace). */
+ * embeddings of the new tokens.  topk_logp / topk_idx [n_beam x k] may be NULL (workspace).
+ * E_tgt must have W_out->rows rows.  Non-finite inputs give an unspecified search step, with
+ * every token id inside the table. */
 q8_status output_logits_beam_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
                                 const float *s, float *y_emb, const float *ctx_vec, int n_beam, int k, void *state,
                                 const float *E_tgt, int E, float *s_next, float *topk_logp, int32_t *topk_idx);

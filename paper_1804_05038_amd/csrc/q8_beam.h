@@ -27,6 +27,7 @@ struct BeamUpdateArgs {
     const float *s_step, *E_tgt;
     float *y_emb, *s_next;
     int n, k, E, H;
+    int V;                  // rows of E_tgt when known (token ids are then kept inside the table), else 0
 };
 
 // key: larger score first, then lower parent, then lower token id
@@ -107,7 +108,11 @@ __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
             int b_left = b_live;
             for (int r = 0; r < take; ++r) {
                 const float sc = s_rscore[r];
-                const int token = s_rtoken[r], parent = s_rparent[r];
+                int token = s_rtoken[r], parent = s_rparent[r];
+                // non-finite scores can leave fewer than k valid candidates per hypothesis: whatever
+                // the tables then hold, the gather below stays inside s_step and E_tgt
+                if (a.V > 0 && (unsigned)token >= (unsigned)a.V) token = 0;
+                if ((unsigned)parent >= (unsigned)a.n) parent = 0;
                 if (token == 0) {                      // end of sentence: the hypothesis is finished
                     if (!have_fin || sc > fin_score) {
                         have_fin = 1; fin_score = sc; fin_len = step; fin_parent = parent;

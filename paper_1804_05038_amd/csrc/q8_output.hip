@@ -671,7 +671,7 @@ static q8_status launch_select(q8_ctx *ctx, const float *part_max, const double 
     s.counter = (unsigned *)(ctx->ws + Q8_WS_SELECT_COUNTER);
     if (beam) {
         BeamUpdateArgs bu = {(BeamState *)beam->state, topk_logp, topk_idx, beam->s_step, beam->E_tgt, beam->y_emb,
-                             beam->s_next, n, k, beam->E, beam->H};
+                             beam->s_next, n, k, beam->E, beam->H, V};
         s.bu = bu;
     } else {
         memset(&s.bu, 0, sizeof(s.bu));

@@ -117,6 +117,31 @@ def _decode_loop(q, c, m, P, enc_h, n, s0, T):
     return state, c0, c1, c2
 
 
+def test_non_finite_logits_keep_the_search_inside_its_tables(q, ctx):
+    """A NaN bias makes every logit NaN: none qualifies for the top-k tables, which keep what
+    they held before (here: ids far outside the vocabulary).  The fused search step must still
+    gather only rows of E_tgt and of the decoder states."""
+    V, E, H, A, R, n, T = 500, 64, 128, 64, 64, 4, 6
+    p = synth.full_model(seed=22, V=V, E=E, H=H, A=A, R=R, w_std=0.2, b_std=0.1)
+    m = q.Model.from_params(ctx, p)
+    rng = np.random.default_rng(4)
+    enc_h = ctx.f32(rng.standard_normal((7, 2 * H)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    s0 = ctx.f32(rng.standard_normal(H).astype(np.float32))
+    m.b_out = torch.full_like(m.b_out, float("nan"))
+    state, c0, c1, c2 = _decode_loop(q, ctx, m, P, enc_h, n, s0, T)
+    c2.out["topk_idx"].fill_(2 ** 31 - 1)
+    c2.out["topk_logp"].fill_(float("nan"))
+    c0.launch()
+    E_rows = np_(m.E_tgt)
+    for _ in range(3):
+        c1.launch(); c2.launch()
+    toks, score, steps, done = q.q8_beam_result(ctx, state, T)
+    assert all(0 <= int(t) < V for t in toks)
+    y = np_(c2.out["keep"][4])
+    assert ((y[:, None, :] == E_rows[None, :, :]).all(-1)).any(-1).all()     # every row of y is a row of E_tgt
+
+
 def test_fused_tail_equals_separate_calls_and_graph_replays(q, ctx, oracle):
     """output_logits_beam_q8 against output_logits_q8 + q8_beam_update, eagerly and from a HIP
     graph replayed several times with eager work between the replays."""
