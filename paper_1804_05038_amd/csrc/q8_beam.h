@@ -156,27 +156,29 @@ __device__ __forceinline__ void beam_gather(const BeamUpdateArgs &a, const int *
 {
     const int tid = threadIdx.x;
     if (((a.H | a.E) & 3) == 0) {
+        // piece idx < nH4: float4 (idx % H4) of state row (idx / H4); the rest: embedding rows.  Loads and
+        // stores are all unconditional (a piece past the end repeats the last one, same value to the same
+        // place): inside a branch the compiler waits for each of them on the spot, and a thread's eight
+        // loads and eight stores become sixteen memory round trips in a row.
         const int H4 = a.H >> 2, E4 = a.E >> 2, nH4 = a.n * H4, total4 = nH4 + a.n * E4;
+        const float4 *s4 = (const float4 *)a.s_step, *e4 = (const float4 *)a.E_tgt;
         for (int base = tid; base < total4; base += 256 * 8) {
             float4 v[8];
-            float4 *dst[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int idx = base + 256 * u;
-                dst[u] = nullptr;
-                if (idx < nH4) {
-                    const int q = idx / H4, c = idx - q * H4;
-                    v[u] = ((const float4 *)(a.s_step + (size_t)s_parent[q] * a.H))[c];
-                    dst[u] = (float4 *)a.s_next + idx;
-                } else if (idx < total4) {
-                    const int r = idx - nH4, q = r / E4, c = r - q * E4;
-                    v[u] = ((const float4 *)(a.E_tgt + (size_t)s_token[q] * a.E))[c];
-                    dst[u] = (float4 *)a.y_emb + r;
-                }
+                const int idx = min(base + 256 * u, total4 - 1);
+                const bool state = idx < nH4;
+                const int r = state ? idx : idx - nH4, D4 = state ? H4 : E4;
+                const int q = r / D4, c = r - q * D4;
+                const float4 *src = state ? s4 + (size_t)s_parent[q] * H4 + c : e4 + (size_t)s_token[q] * E4 + c;
+                v[u] = *src;
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (dst[u]) *dst[u] = v[u];
+            for (int u = 0; u < 8; ++u) {
+                const int idx = min(base + 256 * u, total4 - 1);
+                float4 *dst = idx < nH4 ? (float4 *)a.s_next + idx : (float4 *)a.y_emb + (idx - nH4);
+                *dst = v[u];
+            }
         }
     } else {
         for (int e = tid; e < a.n * a.H; e += blockDim.x) {
