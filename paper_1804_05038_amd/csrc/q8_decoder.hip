@@ -43,11 +43,15 @@ __device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const
             mx = fmaxf(mx, ev);
         }
         mx = wave_max_f(mx);
-        double Z = 0.0;
-        for (int t = lane; t < l; t += 64) Z += q8_exp_d(fmax((double)s_alpha[t] - (double)mx, -700.0));
+        double Z = 0.0, ex0 = 0.0;               // ex0: the lane's first term, kept for the division below
+        for (int t = lane; t < l; t += 64) {
+            const double ex = q8_exp_d(fmax((double)s_alpha[t] - (double)mx, -700.0));
+            if (t == lane) ex0 = ex;
+            Z += ex;
+        }
         Z = wave_sum_d(Z);
         for (int t = lane; t < l; t += 64) {
-            const float al = (float)(q8_exp_d(fmax((double)s_alpha[t] - (double)mx, -700.0)) / Z);
+            const float al = (float)((t == lane ? ex0 : q8_exp_d(fmax((double)s_alpha[t] - (double)mx, -700.0))) / Z);
             s_alpha[t] = al;
             if (a.alpha) a.alpha[(size_t)b * a.lde + t] = al;
         }
