@@ -249,6 +249,7 @@ __global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
     extern __shared__ __align__(16) int8_t smem[];
     __shared__ float s_scale[24];
     __shared__ float s_red[3 * 8 * 4];
+    __shared__ int s_t[4][3 * N];
     int8_t *sq = smem, *yq = sq + N * a.lds, *cq = yq + N * a.ldy;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int unit = blockIdx.x * 4 + wave;
@@ -277,18 +278,24 @@ __global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
     }
     if (blockIdx.x == 0) readout_x_taps<N>(a, sq, yq, cq, s_scale);
 
-    int as[1][N], ay[1][N], ac[1][N];
-    rows_dot<N, 1, CH>(ws, a.lds, lane, sq, as);
-    rows_dot<N, 1, CH>(wy, a.ldy, lane, yq, ay);
-    rows_dot<N, 1, CH>(wc, a.ldc, lane, cq, ac);
-    if (ok && lane < N) {
-        int vs = 0, vy = 0, vc = 0;
+    // the three rows' partial sums against their vectors, totalled over the wave in one pass;
+    // lane j < N receives the totals of hypothesis j
+    int part[3][N], mine[3];
+    {
+        int p1[1][N];
+        rows_dot_part<N, 1, CH>(ws, a.lds, lane, sq, p1);
 #pragma unroll
-        for (int jj = 0; jj < N; ++jj) {
-            vs = (lane == jj) ? as[0][jj] : vs;
-            vy = (lane == jj) ? ay[0][jj] : vy;
-            vc = (lane == jj) ? ac[0][jj] : vc;
-        }
+        for (int jj = 0; jj < N; ++jj) part[0][jj] = p1[0][jj];
+        rows_dot_part<N, 1, CH>(wy, a.ldy, lane, yq, p1);
+#pragma unroll
+        for (int jj = 0; jj < N; ++jj) part[1][jj] = p1[0][jj];
+        rows_dot_part<N, 1, CH>(wc, a.ldc, lane, cq, p1);
+#pragma unroll
+        for (int jj = 0; jj < N; ++jj) part[2][jj] = p1[0][jj];
+    }
+    sums_to_lanes<N, 3>(part, lane, s_t[wave], mine);
+    if (ok && lane < N) {
+        const int vs = mine[0], vy = mine[1], vc = mine[2];
         const float cs = a.ss_w * s_scale[lane], cy = a.sy_w * s_scale[8 + lane], cc = a.sc_w * s_scale[16 + lane];
         const float u1 = (float)vs * cs, u2 = (float)vy * cy, u3 = (float)vc * cc;
         float p = u1 + u2;

@@ -310,6 +310,108 @@ __device__ __forceinline__ void x_load(XRegs<N, CH> &R, const float *__restrict_
     __builtin_amdgcn_sched_barrier(0);
 }
 
+// ---------------------------------------------------------- transposed wave reductions ----
+// M values per lane (M a power of two, at most 64) reduced over the wave's 64 lanes.  In the first
+// log2(M) exchange stages the two partners split the values between them: each keeps one half,
+// hands the other half over and combines what it receives, so the work halves from stage to
+// stage; the stages that are left run on the single remaining value.  About 4 M instructions
+// instead of the 12 M of M separate reductions.  Stage s pairs lane L with L ^ 7, ^ 1, ^ 2, ^ 8,
+// ^ 16, ^ 32 and lets lane bit 2, 0, 1, 3, 4, 5 choose the half that is kept (the first stage
+// flips bits 0 and 1 as well, which is harmless while every lane still holds every value).
+// Afterwards lane L holds the total of value t_index<M>(L).
+__host__ __device__ constexpr int t_bit(int s) { return s == 0 ? 2 : s == 1 ? 0 : s == 2 ? 1 : s; }
+__host__ __device__ constexpr int t_log2(int m) { return m <= 1 ? 0 : 1 + t_log2(m >> 1); }
+__host__ __device__ constexpr int t_pow2(int n) { return n <= 1 ? 1 : 2 * t_pow2((n + 1) >> 1); }
+
+template <int S>
+__device__ __forceinline__ int t_xchg(int v, int lane)
+{
+    if constexpr (S == 0) return dpp_mov_i<DPP_HALF_MIRROR>(v);
+    else if constexpr (S == 1) return dpp_mov_i<DPP_XOR1>(v);
+    else if constexpr (S == 2) return dpp_mov_i<DPP_XOR2>(v);
+    else if constexpr (S == 3) return dpp_mov_i<0x128>(v);                        // row_ror:8 = lane ^ 8 within 16
+    else if constexpr (S == 4) {
+        // (x, x) -> {rows 0 0 2 2, rows 1 1 3 3} of x
+        auto q = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
+        return (int)((lane & 16) ? q[0] : q[1]);
+    } else {
+        auto q = __builtin_amdgcn_permlane32_swap((unsigned)v, (unsigned)v, false, false);   // {low half twice, high half twice}
+        return (int)((lane & 32) ? q[0] : q[1]);
+    }
+}
+
+struct TSumI { static __device__ __forceinline__ int op(int a, int b) { return a + b; } };
+struct TMaxF {
+    static __device__ __forceinline__ int op(int a, int b) { return __float_as_int(fmaxf(__int_as_float(a), __int_as_float(b))); }
+};
+
+template <int S, int M, class Op>
+__device__ __forceinline__ void t_stage(int (&v)[M], int lane)
+{
+    if constexpr (S < t_log2(M)) {
+        constexpr int half = M >> (S + 1);
+        const bool up = (lane >> t_bit(S)) & 1;
+#pragma unroll
+        for (int i = 0; i < half; ++i) {
+            const int give = up ? v[i] : v[i + half];
+            const int keep = up ? v[i + half] : v[i];
+            v[i] = Op::op(keep, t_xchg<S>(give, lane));
+        }
+    } else {
+        v[0] = Op::op(v[0], t_xchg<S>(v[0], lane));
+    }
+}
+
+template <int M, class Op>
+__device__ __forceinline__ int wave_reduce_t(int (&v)[M], int lane)
+{
+    static_assert(M >= 1 && M <= 64 && (M & (M - 1)) == 0, "power of two up to 64");
+    t_stage<0, M, Op>(v, lane);
+    t_stage<1, M, Op>(v, lane);
+    t_stage<2, M, Op>(v, lane);
+    t_stage<3, M, Op>(v, lane);
+    t_stage<4, M, Op>(v, lane);
+    t_stage<5, M, Op>(v, lane);
+    return v[0];
+}
+
+// Index of the value whose total lane `lane` holds after wave_reduce_t<M>, and whether the lane
+// is the first of the 64 / M lanes that hold that same total.
+template <int M>
+__device__ __forceinline__ int t_index(int lane)
+{
+    int idx = 0;
+#pragma unroll
+    for (int s = 0; s < t_log2(M); ++s) idx |= ((lane >> t_bit(s)) & 1) * (M >> (s + 1));
+    return idx;
+}
+template <int M>
+__device__ __forceinline__ bool t_first(int lane)
+{
+    int used = 0;
+#pragma unroll
+    for (int s = 0; s < t_log2(M); ++s) used |= 1 << t_bit(s);
+    return (lane & (63 & ~used)) == 0;
+}
+
+// Totals of CNT = UT * N partial sums per lane, handed to the lanes that finish them: lane j < N
+// receives the UT totals of vector j (part[u][j] summed over the wave) in mine[u].  s_t: CNT
+// ints of LDS owned by this wave.
+template <int N, int UT>
+__device__ __forceinline__ void sums_to_lanes(const int (&part)[UT][N], int lane, int *s_t, int (&mine)[UT])
+{
+    constexpr int CNT = UT * N, M = t_pow2(CNT);
+    int v[M];
+#pragma unroll
+    for (int e = 0; e < M; ++e) v[e] = e < CNT ? part[e / N][e % N] : 0;
+    const int tot = wave_reduce_t<M, TSumI>(v, lane);
+    const int idx = t_index<M>(lane);
+    if (idx < CNT && t_first<M>(lane)) s_t[idx] = tot;
+    __builtin_amdgcn_wave_barrier();             // same wave: the reads below are issued after the writes
+#pragma unroll
+    for (int u = 0; u < UT; ++u) mine[u] = lane < N ? s_t[u * N + lane] : 0;
+}
+
 // Wave maxima of N independent values, the cross-lane steps of all N interleaved so that
 // their latencies overlap.
 template <int N>
@@ -369,10 +471,14 @@ __device__ __forceinline__ void x_finish_m(const XRegs<N, CH> &R, float (&m)[N],
                                            float *s_red)
 {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    wave_max_multi<N>(m);
-    if (lane == 0) {
+    {
+        constexpr int M = t_pow2(N);
+        int mv[M];
 #pragma unroll
-        for (int j = 0; j < N; ++j) s_red[j * 4 + wave] = m[j];
+        for (int e = 0; e < M; ++e) mv[e] = e < N ? __float_as_int(m[e]) : 0;
+        const int tot = wave_reduce_t<M, TMaxF>(mv, lane);
+        const int idx = t_index<M>(lane);
+        if (idx < N && t_first<M>(lane)) s_red[idx * 4 + wave] = __int_as_float(tot);
     }
     __syncthreads();
     float scale = 1.0f, inv = 0.0f;
@@ -417,10 +523,14 @@ __device__ __forceinline__ void x_finish_multi(const XRegs<N, CH> (&R)[NIN], con
             }
             m[i * N + j] = mm;
         }
-    wave_max_multi<NIN * N>(m);
-    if (lane == 0) {
+    {
+        constexpr int M = t_pow2(NIN * N);
+        int mv[M];
 #pragma unroll
-        for (int e = 0; e < NIN * N; ++e) s_red[e * 4 + wave] = m[e];
+        for (int e = 0; e < M; ++e) mv[e] = e < NIN * N ? __float_as_int(m[e]) : 0;
+        const int tot = wave_reduce_t<M, TMaxF>(mv, lane);
+        const int idx = t_index<M>(lane);
+        if (idx < NIN * N && t_first<M>(lane)) s_red[idx * 4 + wave] = __int_as_float(tot);
     }
     __syncthreads();
     float scale = 1.0f, inv = 0.0f;          // lane 8 i + j owns vector j of input i
@@ -457,6 +567,29 @@ __device__ __forceinline__ void rows_load(v4i (&w)[U][CH], const int8_t *const (
             w[u][c] = (v4i){0, 0, 0, 0};
             if (wrow[u] != nullptr && off < ld) w[u][c] = *(const v4i *)(wrow[u] + off);
         }
+}
+
+// Dots the staged rows with the N quantized vectors in LDS: the lane's partial sums (its 16 bytes
+// of every chunk), to be totalled over the wave by sums_to_lanes.
+template <int N, int U, int CH>
+__device__ __forceinline__ void rows_dot_part(const v4i (&w)[U][CH], int ld, int lane, const int8_t *xq, int (&acc)[U][N])
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int j = 0; j < N; ++j) acc[u][j] = 0;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int off = (c * 64 + lane) * 16;
+        if (off < ld) {
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+                const v4i x = *(const v4i *)(xq + (size_t)j * ld + off);
+#pragma unroll
+                for (int u = 0; u < U; ++u) acc[u][j] = dot16(w[u][c], x, acc[u][j]);
+            }
+        }
+    }
 }
 
 // Dots the staged rows with the N quantized vectors in LDS; every lane gets every sum.

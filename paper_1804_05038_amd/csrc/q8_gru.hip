@@ -135,6 +135,7 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
     extern __shared__ __align__(16) int8_t smem[];
     __shared__ float s_scale[16];
     __shared__ float s_red[2 * 8 * 4];
+    __shared__ int s_t[4][6 * N];
     const GruJob &J = jobs.j[blockIdx.y];
     const int H = J.H;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -184,9 +185,23 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
     }
     if (blockIdx.x == 0) gru_x_taps<N, MODE>(J, xq, hq, s_scale);
 
-    int ax[3][N], ah[3][N];
-    if (MODE != GRU_GX_PRE) rows_dot<N, 3, CH>(wx, J.ldwx, lane, xq, ax);
-    if (MODE != GRU_GH_PRE) rows_dot<N, 3, CH>(wh, J.ldwh, lane, hq, ah);
+    // partial sums of the unit's rows against every vector, totalled over the wave in one pass;
+    // lane j < N receives the totals of vector j: [0, 3) input product, [3, 6) recurrent product
+    constexpr int UT = MODE == GRU_FULL ? 6 : 3;
+    int part[UT][N], mine[UT];
+    {
+        int px[3][N], ph[3][N];
+        if (MODE != GRU_GX_PRE) rows_dot_part<N, 3, CH>(wx, J.ldwx, lane, xq, px);
+        if (MODE != GRU_GH_PRE) rows_dot_part<N, 3, CH>(wh, J.ldwh, lane, hq, ph);
+#pragma unroll
+        for (int gt = 0; gt < 3; ++gt)
+#pragma unroll
+            for (int jj = 0; jj < N; ++jj) {
+                if (MODE == GRU_FULL) { part[gt][jj] = px[gt][jj]; part[3 + gt][jj] = ph[gt][jj]; }
+                else part[gt][jj] = MODE == GRU_GH_PRE ? px[gt][jj] : ph[gt][jj];
+            }
+    }
+    sums_to_lanes<N, UT>(part, lane, s_t[wave], mine);
     if (ok && lane < N) {
         const int j = lane;
         float cx = 0.f, ch = 0.f;
@@ -199,9 +214,7 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
             if (MODE == GRU_GX_PRE) {
                 gx[gt] = pre[gt];
             } else {
-                int a = 0;
-#pragma unroll
-                for (int jj = 0; jj < N; ++jj) a = (j == jj) ? ax[gt][jj] : a;
+                const int a = mine[gt];
                 float y = (float)a * cx;
                 if (J.bx) y = y + bxv[gt];
                 gx[gt] = y;
@@ -210,9 +223,7 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
             if (MODE == GRU_GH_PRE) {
                 gh[gt] = pre[gt];
             } else {
-                int a = 0;
-#pragma unroll
-                for (int jj = 0; jj < N; ++jj) a = (j == jj) ? ah[gt][jj] : a;
+                const int a = mine[MODE == GRU_FULL ? 3 + gt : gt];
                 float y = (float)a * ch;
                 if (J.bh) y = y + bhv[gt];
                 gh[gt] = y;

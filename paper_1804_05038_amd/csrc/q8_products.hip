@@ -147,11 +147,12 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
     extern __shared__ __align__(16) int8_t smem[];
     __shared__ float s_scale[8];
     __shared__ float s_red[8 * 4];
+    constexpr int U = 2;
+    __shared__ int s_t[4][U * N];
     const GemvJob &J = jobs.j[pick_job(jobs)];
     const int blk = blockIdx.x - J.block0;
     const int ld = J.ld;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    constexpr int U = 2;
     const int r_begin = blk * J.rpb;
     const int r_end = min(J.rows, r_begin + J.rpb);
 
@@ -179,13 +180,12 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
             for (int u = 0; u < U; ++u) wrow[u] = rn + u < r_end ? J.W + (size_t)(rn + u) * ld : nullptr;
             rows_load<U, CH>(wn, wrow, ld, lane);
         }
-        int acc[U][N];
-        rows_dot<N, U, CH>(w, ld, lane, smem, acc);
+        int part[U][N], mine[U];
+        rows_dot_part<N, U, CH>(w, ld, lane, smem, part);
+        sums_to_lanes<N, U>(part, lane, s_t[wave], mine);      // lane j < N: the totals of vector j
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            int a = 0;
-#pragma unroll
-            for (int j = 0; j < N; ++j) a = (lane == j) ? acc[u][j] : a;
+            const int a = mine[u];
             if (lane < N && r + u < r_end) {
                 float y = (float)a * cj;
                 if (J.bias) y = y + J.bias[r + u];
