@@ -296,6 +296,8 @@ q8_status cgru_decoder_step_q8(q8_ctx *ctx, const q8_cgru_weights *w, const floa
     float *a = cv.take<float>((size_t)n * A);
     float *ghq = cv.take<float>((size_t)n * 3 * H);
     float *e = cv.take<float>((size_t)n * l);
+    int8_t *cq = cv.take<int8_t>((size_t)n * w->q.Wx.ld);      // codes and scales of the context vectors,
+    float *cqs = cv.take<float>(n);                             // from the attention kernel to GRU q
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "cgru_decoder_step_q8: workspace too small");
 
     // Eq. 3: s' = r(y, s_prev)
@@ -307,11 +309,13 @@ q8_status cgru_decoder_step_q8(q8_ctx *ctx, const q8_cgru_weights *w, const floa
                            {&qWh, s_mid, H, w->q.bh, ghq, 3 * H, taps5 ? taps5 + 4 : nullptr}};
     TRY(q8i_gemv_jobs(ctx, dj, 2, n));
     // Eq. 5-6: energies, weights, context
-    TRY(q8i_attention(ctx, P, enc_h, l, A, C, a, w->att_v, n, e, alpha_out, ctx_out, nullptr, 0));
+    int have_codes = 0;
+    TRY(q8i_attention(ctx, P, enc_h, l, A, C, a, w->att_v, n, e, alpha_out, ctx_out, nullptr, 0, cq, cqs, w->q.Wx.ld, &have_codes));
     // Eq. 4: s = q(H_t, s')
     q8_taps tq[2];
     if (taps5) { tq[0] = taps5[3]; tq[1].xq = nullptr; tq[1].xscale = nullptr; tq[1].acc = nullptr; }
-    q8i_gru_desc dq = {&w->q, ctx_out, C, s_mid, H, ghq, 3 * H, s_out, H, taps5 ? tq : nullptr};
+    q8i_gru_desc dq = {&w->q, ctx_out, C, s_mid, H, ghq, 3 * H, s_out, H, taps5 ? tq : nullptr,
+                       have_codes ? cq : nullptr, have_codes ? cqs : nullptr};
     return q8i_gru(ctx, &dq, 1, n, Q8I_GRU_GH_PRE);
 }
 
@@ -357,7 +361,7 @@ q8_status cgru_decoder_step_batch_q8(q8_ctx *ctx, const q8_cgru_weights *w, cons
                                 {&w->q.Wh, mq_h, ms_h, w->q.bh, ghq, 3 * H, nullptr, nullptr, nullptr, 0}};
     TRY(q8i_gemm_jobs(ctx, gj, 2, n));
     // Eq. 5-6 per hypothesis, against the positions of its own sentence
-    TRY(q8i_attention(ctx, P, enc_h, max_l, A, C, a, w->att_v, n, e, alpha_out, ctx_out, sent_off, beam));
+    TRY(q8i_attention(ctx, P, enc_h, max_l, A, C, a, w->att_v, n, e, alpha_out, ctx_out, sent_off, beam, nullptr, nullptr, 0, nullptr));
     // Eq. 4: s = q(H_t, s')
     Carver sub = cv;
     return gru_panel(ctx, sub, &w->q, ctx_out, s_mid, n, ghq, s_out, nullptr);
@@ -758,7 +762,7 @@ q8_status cgru_decoder_step_f32(q8_ctx *ctx, const q8_cgru_weights_f32 *w, const
     const q8i_f32_job j2[2] = {{&w->att_U, s_mid, H, nullptr, a, A}, {&w->q.Wh, s_mid, H, w->q.bh, gh, 3 * H}};
     TRY(q8i_gemv_f32(ctx, j2, 2, n));
     // Eq. 5-6
-    TRY(q8i_attention(ctx, P, enc_h, l, A, C, a, w->att_v, n, e, alpha_out, ctx_out, nullptr, 0));
+    TRY(q8i_attention(ctx, P, enc_h, l, A, C, a, w->att_v, n, e, alpha_out, ctx_out, nullptr, 0, nullptr, nullptr, 0, nullptr));
     // Eq. 4: s = q(H_t, s')
     const q8i_f32_job j3 = {&w->q.Wx, ctx_out, C, w->q.bx, gx, 3 * H};
     TRY(q8i_gemv_f32(ctx, &j3, 1, n));

@@ -13,6 +13,11 @@ struct AttArgs {
     // P and enc_h are [sent_off[s], sent_off[s + 1]); NULL = one sentence of l positions
     const int *sent_off;
     int beam, lde;          // lde: row pitch of e and alpha
+    // optional: codes [n x ldq] (bytes [C, ldq) zero) and scales [n] of the context vectors, so that
+    // the consumer (GRU q) does not quantize them again in every block; needs C even, ldq <= 2 blockDim
+    int8_t *ctx_q;
+    float *ctx_qscale;
+    int ldq;
 };
 
 // Rows of P and enc_h that hypothesis b attends over, and how many.
@@ -27,6 +32,7 @@ __device__ __forceinline__ int att_sentence(const AttArgs &a, int b, const float
     return a.sent_off[s + 1] - o;
 }
 
+#define ATT_MAX_THREADS 1024
 // Run by the last block to arrive for hypothesis b (all its l energies are in a.e, written
 // with device-coherent stores): softmax over the energies in one wave, then the context
 // vector H_t (Eq. 5), a thread owning two adjacent columns and walking the source positions
@@ -58,7 +64,35 @@ __device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const
         if (lane == 0) __hip_atomic_store(&a.counters[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
-    if ((a.C & 1) == 0) {
+    if (a.ctx_q) {
+        // one pair of columns per thread; the vector's codes come from the rounded values in registers
+        __shared__ float s_m[ATT_MAX_THREADS / 64];
+        const int c = tid * 2;
+        float f0 = 0.0f, f1 = 0.0f;
+        if (c < a.C) {
+            double s0 = 0.0, s1 = 0.0;
+            const float *h = enc_h + c;
+#pragma unroll 10
+            for (int t = 0; t < l; ++t) {
+                const float2 hv = *(const float2 *)(h + (size_t)t * a.C);
+                const double al = (double)s_alpha[t];
+                s0 += al * (double)hv.x;
+                s1 += al * (double)hv.y;
+            }
+            f0 = (float)s0;
+            f1 = (float)s1;
+            *(float2 *)(a.ctx + (size_t)b * a.C + c) = make_float2(f0, f1);
+        }
+        float m = wave_max_f(fmaxf(fabsf(f0), fabsf(f1)));
+        if (lane == 0) s_m[wave] = m;
+        __syncthreads();
+        m = 0.0f;
+        for (int w = 0; w < nt / 64; ++w) m = fmaxf(m, s_m[w]);
+        float scale, inv;
+        q8_scale_of(m, scale, inv);
+        if (c < a.ldq) *(short *)(a.ctx_q + (size_t)b * a.ldq + c) = (short)q8_pack2(f0, f1, inv);   // zeros past C
+        if (tid == 0) a.ctx_qscale[b] = scale;
+    } else if ((a.C & 1) == 0) {
         for (int c = tid * 2; c < a.C; c += 2 * nt) {
             double s0 = 0.0, s1 = 0.0;
             const float *h = enc_h + c;
@@ -351,13 +385,17 @@ q8_status q8i_readout_combine(q8_ctx *ctx, const float *ts, const float *ty, con
 
 
 q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, int A, int C, const float *a,
-                        const float *v, int n, float *e, float *alpha, float *cvec, const int *sent_off, int beam)
+                        const float *v, int n, float *e, float *alpha, float *cvec, const int *sent_off, int beam,
+                        int8_t *ctx_q, float *ctx_qscale, int ldq, int *codes_written)
 {
     AttArgs t;
     t.P = P; t.enc_h = enc_h; t.a = a; t.v = v; t.e = e; t.alpha = alpha; t.ctx = cvec;
     t.counters = (unsigned *)ctx->ws;
     t.l = l; t.A = A; t.C = C;
     t.sent_off = sent_off; t.beam = beam; t.lde = l;
+    const bool codes = ctx_q && ctx_qscale && n <= Q8_MAX_BEAM && C % 2 == 0 && ldq >= C && ldq % 2 == 0 && ldq <= 2 * ATT_THREADS;
+    t.ctx_q = codes ? ctx_q : nullptr; t.ctx_qscale = ctx_qscale; t.ldq = ldq;
+    if (codes_written) *codes_written = codes ? 1 : 0;
     if (n > Q8_MAX_BEAM)
         Q8_LAUNCH(ctx, Q8_KERNEL_ATTENTION, attention_panel_kernel, dim3((l + ATTP_POS - 1) / ATTP_POS, n), dim3(256), 0, t);
     else

@@ -181,6 +181,25 @@ __device__ __forceinline__ int q8_pack4(float a, float b, float c, float d, floa
     return (int)(lo | hi);
 }
 
+// Two codes in the low half of a dword (same rounding as q8_pack4).
+__device__ __forceinline__ int q8_pack2(float a, float b, float inv)
+{
+    const float magic = 12582912.0f;
+    const unsigned ua = __float_as_uint(__fadd_rn(__fmul_rn(a, inv), magic));
+    const unsigned ub = __float_as_uint(__fadd_rn(__fmul_rn(b, inv), magic));
+    return (int)__builtin_amdgcn_perm(ub, ua, 0x0c0c0400u);
+}
+
+// Buffer descriptor over [base, base + bytes): a load through it at an offset at or past
+// `bytes` returns zero without touching memory.  A load that has nothing to fetch is then
+// still an unconditional instruction, and the counts the compiler waits on stay exact
+// (a load inside a branch makes it wait for everything in flight).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t q8_rsrc(const void *base, size_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)bytes, 0x00020000);
+}
+#define Q8_OOB 0x80000000u           // past the end of every descriptor used here (sizes stay below 2^31)
+
 // Quantizes n (<= NMAX) fp32 vectors X[j * ldx + k], k < K, into LDS bytes
 // xq[j * ld + k] (ld % 16 == 0, bytes [K, ld) zeroed) and their scales into s_scale[j].
 // s_red needs NMAX * (blockDim.x / 64) floats.  Ends with a block barrier.

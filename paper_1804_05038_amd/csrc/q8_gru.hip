@@ -12,6 +12,8 @@ struct GruJob {
     const int8_t *Wx, *Wh;
     const float *bx, *bh;
     const float *x, *h_prev, *g_pre;
+    const int8_t *xq_pre;      // GH_PRE, kernels with XPRE: codes [N x ldwx] and scales [N] of x from its producer
+    const float *xs_pre;
     float *h_out;
     q8_taps tx, th;
     int I, ldwx, H, ldwh, ldx, ldh, ldo, ldg, lpr;
@@ -128,10 +130,12 @@ __global__ __launch_bounds__(256) void gru_kernel(GruJobs jobs)
 
 // Rows of at most 1024 * CH bytes, I % 4 == 0, H % 4 == 0, one hidden unit per wave
 // (grid.x * 4 >= H).  Activations, the unit's six (or three) weight rows and the
-// epilogue's operands are all requested before the block first waits.
-template <int N, int MODE, int CH>
+// epilogue's operands are all requested before the block first waits.  XPRE (with
+// GRU_GH_PRE): x arrives as codes and scales, which are copied to LDS instead of quantized.
+template <int N, int MODE, int CH, bool XPRE = false>
 __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
 {
+    static_assert(!XPRE || MODE == GRU_GH_PRE, "codes are taken for the input of GRU_GH_PRE only");
     extern __shared__ __align__(16) int8_t smem[];
     __shared__ float s_scale[16];
     __shared__ float s_red[2 * 8 * 4];
@@ -146,7 +150,18 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
 
     XRegs<N, CH> xh[2];                      // [0]: x, [1]: h_prev
     XRegs<N, CH> &xr = xh[0], &hr = xh[1];
-    if (MODE != GRU_GX_PRE) x_load<N, CH>(xr, J.x, N, J.I, J.ldx);
+    // XPRE: N * ldwx code bytes in 16-byte pieces, thread tid takes pieces tid, tid + 256, ...; a piece
+    // past the end is read through the descriptor as zero, so the loads need no branch
+    constexpr int NPRE = XPRE ? (N * CH * 64 + 255) / 256 : 1;
+    v4i pre_q[NPRE];
+    if (XPRE) {
+        const __amdgpu_buffer_rsrc_t rq = q8_rsrc(J.xq_pre, (size_t)N * J.ldwx);
+#pragma unroll
+        for (int t = 0; t < NPRE; ++t)
+            pre_q[t] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rq, (t * 256 + (int)threadIdx.x) * 16, 0, 0));
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (MODE != GRU_GX_PRE && !XPRE) x_load<N, CH>(xr, J.x, N, J.I, J.ldx);
     if (MODE != GRU_GH_PRE) x_load<N, CH>(hr, J.h_prev, N, H, J.ldh);
     v4i wx[3][CH], wh[3][CH];
     if (MODE != GRU_GX_PRE) {
@@ -178,6 +193,14 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
         const int lds[2] = {J.ldwx, J.ldwh};
         int8_t *const dst[2] = {xq, hq};
         x_finish_multi<N, CH, 2>(xh, lds, dst, s_scale, s_red);
+    } else if (XPRE) {
+#pragma unroll
+        for (int t = 0; t < NPRE; ++t) {
+            const int o = (t * 256 + (int)threadIdx.x) * 16;
+            if (o < N * J.ldwx) *(v4i *)(xq + o) = pre_q[t];
+        }
+        if (threadIdx.x < N) s_scale[threadIdx.x] = J.xs_pre[threadIdx.x];
+        __syncthreads();
     } else if (MODE == GRU_GH_PRE) {
         x_finish<N, CH>(xr, N, J.ldwx, xq, s_scale, s_red);
     } else {
@@ -337,20 +360,27 @@ q8_status q8i_gru_gates(q8_ctx *ctx, const float *gx, const float *gh, const flo
 
 
 template <int N, int MODE>
-static void launch_gru_nm(q8_ctx *ctx, const GruJobs &jobs, int njobs, int blocks, size_t smem, int ch)
+static void launch_gru_nm(q8_ctx *ctx, const GruJobs &jobs, int njobs, int blocks, size_t smem, int ch, bool xpre)
 {
     dim3 grid(blocks, njobs);
+    if constexpr (MODE == GRU_GH_PRE) {
+        if (xpre && (ch == 1 || ch == 2)) {
+            if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_GRU, (gru_fast_kernel<N, GRU_GH_PRE, 1, true>), grid, dim3(256), smem, jobs);
+            else Q8_LAUNCH(ctx, Q8_KERNEL_GRU, (gru_fast_kernel<N, GRU_GH_PRE, 2, true>), grid, dim3(256), smem, jobs);
+            return;
+        }
+    }
     if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_GRU, (gru_fast_kernel<N, MODE, 1>), grid, dim3(256), smem, jobs);
     else if (ch == 2) Q8_LAUNCH(ctx, Q8_KERNEL_GRU, (gru_fast_kernel<N, MODE, 2>), grid, dim3(256), smem, jobs);
     else Q8_LAUNCH(ctx, Q8_KERNEL_GRU, (gru_kernel<N, MODE>), grid, dim3(256), smem, jobs);
 }
 
 template <int N>
-static void launch_gru_n(q8_ctx *ctx, const GruJobs &jobs, int njobs, int mode, int blocks, size_t smem, int ch)
+static void launch_gru_n(q8_ctx *ctx, const GruJobs &jobs, int njobs, int mode, int blocks, size_t smem, int ch, bool xpre)
 {
-    if (mode == GRU_FULL) launch_gru_nm<N, GRU_FULL>(ctx, jobs, njobs, blocks, smem, ch);
-    else if (mode == GRU_GX_PRE) launch_gru_nm<N, GRU_GX_PRE>(ctx, jobs, njobs, blocks, smem, ch);
-    else launch_gru_nm<N, GRU_GH_PRE>(ctx, jobs, njobs, blocks, smem, ch);
+    if (mode == GRU_FULL) launch_gru_nm<N, GRU_FULL>(ctx, jobs, njobs, blocks, smem, ch, false);
+    else if (mode == GRU_GX_PRE) launch_gru_nm<N, GRU_GX_PRE>(ctx, jobs, njobs, blocks, smem, ch, false);
+    else launch_gru_nm<N, GRU_GH_PRE>(ctx, jobs, njobs, blocks, smem, ch, xpre);
 }
 
 q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode)
@@ -358,12 +388,14 @@ q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode
     GruJobs jobs;
     size_t smem = 0;
     int max_ld = 0, maxH = 0;
-    bool fast = true;
+    bool fast = true, xpre = mode == GRU_GH_PRE;      // codes of x: only if every job brings them
     for (int t = 0; t < njobs; ++t) {
         GruJob &J = jobs.j[t];
         const q8_gru_weights *g = d[t].g;
         J.Wx = g->Wx.data; J.Wh = g->Wh.data; J.bx = g->bx; J.bh = g->bh;
         J.x = d[t].x; J.h_prev = d[t].h_prev; J.g_pre = d[t].g_pre; J.h_out = d[t].h_out;
+        J.xq_pre = d[t].xq_pre; J.xs_pre = d[t].xs_pre;
+        if (!J.xq_pre || !J.xs_pre) xpre = false;
         q8_taps none = {nullptr, nullptr, nullptr};
         J.tx = d[t].taps ? d[t].taps[0] : none;
         J.th = d[t].taps ? d[t].taps[1] : none;
@@ -390,14 +422,14 @@ q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode
         if (b > blocks) blocks = b;
     }
     switch (n) {
-    case 1: launch_gru_n<1>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
-    case 2: launch_gru_n<2>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
-    case 3: launch_gru_n<3>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
-    case 4: launch_gru_n<4>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
-    case 5: launch_gru_n<5>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
-    case 6: launch_gru_n<6>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
-    case 7: launch_gru_n<7>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
-    default: launch_gru_n<8>(ctx, jobs, njobs, mode, blocks, smem, ch); break;
+    case 1: launch_gru_n<1>(ctx, jobs, njobs, mode, blocks, smem, ch, xpre); break;
+    case 2: launch_gru_n<2>(ctx, jobs, njobs, mode, blocks, smem, ch, xpre); break;
+    case 3: launch_gru_n<3>(ctx, jobs, njobs, mode, blocks, smem, ch, xpre); break;
+    case 4: launch_gru_n<4>(ctx, jobs, njobs, mode, blocks, smem, ch, xpre); break;
+    case 5: launch_gru_n<5>(ctx, jobs, njobs, mode, blocks, smem, ch, xpre); break;
+    case 6: launch_gru_n<6>(ctx, jobs, njobs, mode, blocks, smem, ch, xpre); break;
+    case 7: launch_gru_n<7>(ctx, jobs, njobs, mode, blocks, smem, ch, xpre); break;
+    default: launch_gru_n<8>(ctx, jobs, njobs, mode, blocks, smem, ch, xpre); break;
     }
     return q8i_launch_check(ctx, "gru");
 }

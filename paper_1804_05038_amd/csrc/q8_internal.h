@@ -80,6 +80,9 @@ struct q8i_gru_desc {
     const float *g_pre;  int ldg;
     float *h_out;        int ldo;
     const q8_taps *taps; // NULL or [2]
+    // GH_PRE only, may be NULL: codes [n x Wx.ld] (pad bytes zero) and scales [n] of x, left by its producer
+    const int8_t *xq_pre;
+    const float *xs_pre;
 };
 
 // beam update run by the last block of the selection kernel (NULL = none)
@@ -123,8 +126,11 @@ bool q8i_vocab_panel_ok(const q8_mat *W);
 q8_status q8i_vocab_panel(q8_ctx *ctx, const q8_mat *W, const float *bias, const int8_t *xq, const float *xscale, int n,
                           float *Y_tiled, float *part_max, double *part_sum);
 q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode);
+// ctx_q / ctx_qscale (may be NULL): where the finishing blocks leave the codes [n x ldq] and scales [n] of the
+// context vectors; *codes_written says whether this launch does (single sentence, C even, ldq <= 2048)
 q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, int A, int C, const float *a,
-                        const float *v, int n, float *e, float *alpha, float *cvec, const int *sent_off, int beam);
+                        const float *v, int n, float *e, float *alpha, float *cvec, const int *sent_off, int beam,
+                        int8_t *ctx_q, float *ctx_qscale, int ldq, int *codes_written);
 q8_status q8i_gru_gates(q8_ctx *ctx, const float *gx, const float *gh, const float *h_prev, int ldh, float *h_out,
                         int ldo, int H, int n);
 // one time step of the batched encoder: phase 0 quantizes the previous states, phase 1 applies the gates

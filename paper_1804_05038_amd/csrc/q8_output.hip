@@ -272,16 +272,6 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     out_logits_body<1, PACKED, QKPL>(a);
 }
 
-// Buffer descriptor over [base, base + bytes): a load through it at an offset at or past
-// `bytes` returns zero without touching memory.  A load that has nothing to fetch is then
-// still an unconditional instruction, and the counts the compiler waits on stay exact
-// (a load inside a branch makes it wait for everything in flight).
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t q8_rsrc(const void *base, size_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)bytes, 0x00020000);
-}
-#define Q8_OOB 0x80000000u           // past the end of every descriptor used here (sizes stay below 2^31)
-
 // The kernel for tile-packed matrices with rows of at most 512 bytes: one tile per wave, eight
 // waves per block, two blocks per compute unit, so that all of the matrix is requested within
 // the first microsecond and nothing loops.  Wave j < n requests hidden vector j first (its
