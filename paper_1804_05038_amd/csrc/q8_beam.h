@@ -79,7 +79,10 @@ __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
         csc = sc0 + lp;
         key = cand_key(csc, c / a.k, tk);
     }
-    if (half == 0) { s_key[c] = key; s_rank[c] = 0; }
+    if (half == 0) {
+        s_key[c] = key;
+        s_rank[c] = 0;
+    }
     __syncthreads();
     if (c < ncand) {
         // keys are distinct (they contain parent and token), so the counts are a permutation
@@ -156,28 +159,29 @@ __device__ __forceinline__ void beam_gather(const BeamUpdateArgs &a, const int *
 {
     const int tid = threadIdx.x;
     if (((a.H | a.E) & 3) == 0) {
-        // piece idx < nH4: float4 (idx % H4) of state row (idx / H4); the rest: embedding rows.  Loads and
-        // stores are all unconditional (a piece past the end repeats the last one, same value to the same
-        // place): inside a branch the compiler waits for each of them on the spot, and a thread's eight
-        // loads and eight stores become sixteen memory round trips in a row.
-        const int H4 = a.H >> 2, E4 = a.E >> 2, nH4 = a.n * H4, total4 = nH4 + a.n * E4;
-        const float4 *s4 = (const float4 *)a.s_step, *e4 = (const float4 *)a.E_tgt;
-        for (int base = tid; base < total4; base += 256 * 8) {
-            float4 v[8];
+        // Thread tid moves 16-byte piece tid (+ 256 per pass) of every row: eight state rows and eight
+        // embedding rows per pass, rows past n repeating row n - 1 and pieces past a row's end repeating
+        // its last piece (same value to the same place).  So there is no division in the addressing and no
+        // branch around a load or a store: inside a branch the compiler waits for each of them on the
+        // spot, and a thread's loads and stores become as many memory round trips in a row.
+        // (Moved as plain 16-byte vectors: nothing here looks inside the values.)
+        const int H4 = a.H >> 2, E4 = a.E >> 2;
+        const v4i *s4 = (const v4i *)a.s_step, *e4 = (const v4i *)a.E_tgt;
+        v4i *sn4 = (v4i *)a.s_next, *y4 = (v4i *)a.y_emb;
+        for (int c0 = 0; c0 < max(H4, E4); c0 += 256) {
+            const int ch = min(c0 + tid, H4 - 1), ce = min(c0 + tid, E4 - 1);
+            v4i vs[Q8_MAX_BEAM], ve[Q8_MAX_BEAM];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int idx = min(base + 256 * u, total4 - 1);
-                const bool state = idx < nH4;
-                const int r = state ? idx : idx - nH4, D4 = state ? H4 : E4;
-                const int q = r / D4, c = r - q * D4;
-                const float4 *src = state ? s4 + (size_t)s_parent[q] * H4 + c : e4 + (size_t)s_token[q] * E4 + c;
-                v[u] = *src;
+            for (int q = 0; q < Q8_MAX_BEAM; ++q) {
+                const int qq = min(q, a.n - 1);
+                vs[q] = s4[(size_t)s_parent[qq] * H4 + ch];
+                ve[q] = e4[(size_t)s_token[qq] * E4 + ce];
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int idx = min(base + 256 * u, total4 - 1);
-                float4 *dst = idx < nH4 ? (float4 *)a.s_next + idx : (float4 *)a.y_emb + (idx - nH4);
-                *dst = v[u];
+            for (int q = 0; q < Q8_MAX_BEAM; ++q) {
+                const int qq = min(q, a.n - 1);
+                sn4[(size_t)qq * H4 + ch] = vs[q];
+                y4[(size_t)qq * E4 + ce] = ve[q];
             }
         }
     } else {
