@@ -26,7 +26,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM-side bytes of one launch of the vocabulary kernel, from the two counter runs recorded in
 # profiles/decode_step_beam5_kernels.txt: 26.28 MB fetched + 2.00 MB written
-VOCAB_KERNEL_TRAFFIC_BYTES = 28.14e6
+VOCAB_KERNEL_TRAFFIC_BYTES = 28.15e6
 L, BEAM, TOPK, MAX_STEPS = 30, 5, 12, 100
 
 
