@@ -295,13 +295,10 @@ __global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
     x_load<N, CH>(rin[2], a.c, N, a.C, a.C);
     v4i ws[1][CH], wy[1][CH], wc[1][CH];
     {
-        const int8_t *w1[1];
-        w1[0] = ok ? a.Ws + (size_t)unit * a.lds : nullptr;
-        rows_load<1, CH>(ws, w1, a.lds, lane);
-        w1[0] = ok ? a.Wy + (size_t)unit * a.ldy : nullptr;
-        rows_load<1, CH>(wy, w1, a.ldy, lane);
-        w1[0] = ok ? a.Wc + (size_t)unit * a.ldc : nullptr;
-        rows_load<1, CH>(wc, w1, a.ldc, lane);
+        const int row[1] = {ok ? unit : -1};
+        rows_load<1, CH>(ws, q8_rsrc(a.Ws, (size_t)a.R * a.lds), row, a.lds, lane);
+        rows_load<1, CH>(wy, q8_rsrc(a.Wy, (size_t)a.R * a.ldy), row, a.ldy, lane);
+        rows_load<1, CH>(wc, q8_rsrc(a.Wc, (size_t)a.R * a.ldc), row, a.ldc, lane);
     }
     float bt = 0.f;
     if (ok && a.b_t) bt = a.b_t[unit];
@@ -428,6 +425,7 @@ q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s,
     a.ss_w = ro->W_s.scale; a.sy_w = ro->W_y.scale; a.sc_w = ro->W_c.scale;
     int ch = q8_fast_ch(ldmax);                 // dims % 4 == 0 is checked by the caller
     if (ch == 4) ch = 0;
+    if ((size_t)a.R * ldmax >= (1u << 31)) ch = 0;      // the fast kernel addresses the matrices with 32-bit offsets
     const int upb = ch ? 4 : 4 * (64 / a.lpr);
     const int blocks = (a.R + upb - 1) / upb;
     const size_t smem = (size_t)n * (a.lds + a.ldy + a.ldc);

@@ -326,16 +326,20 @@ struct XRegs {
     float4 v[N][CH];
 };
 
+// (Unconditional loads through a bounds-checked descriptor: a slice with nothing to fetch reads as
+// zero.  A load inside a branch costs a dozen instructions of mask handling and makes the compiler
+// wait for it before anything else.)
 template <int N, int CH>
 __device__ __forceinline__ void x_load(XRegs<N, CH> &R, const float *__restrict__ X, int n, int K, int ldx)
 {
+    const __amdgpu_buffer_rsrc_t rx = q8_rsrc(X, ((size_t)(n - 1) * ldx + K) * sizeof(float));
 #pragma unroll
     for (int j = 0; j < N; ++j)
 #pragma unroll
         for (int t = 0; t < CH; ++t) {
             const int k = (t * 256 + (int)threadIdx.x) * 4;
-            R.v[j][t] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (j < n && k < K) R.v[j][t] = *(const float4 *)(X + (size_t)j * ldx + k);
+            const unsigned off = (j < n && k < K) ? (unsigned)(j * ldx + k) * 4u : Q8_OOB;
+            R.v[j][t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0));
         }
     // loads return in issue order: nothing issued later may be moved ahead of these
     __builtin_amdgcn_sched_barrier(0);
@@ -587,16 +591,17 @@ __device__ __forceinline__ void x_finish_multi(const XRegs<N, CH> (&R)[NIN], con
 }
 
 // Requests U weight rows for this wave: lane covers bytes [(c * 64 + lane) * 16, +16) of a row.
+// rw: descriptor over the whole matrix (below 2 GiB); row[u] < 0: no such row, reads as zero.
 template <int U, int CH>
-__device__ __forceinline__ void rows_load(v4i (&w)[U][CH], const int8_t *const (&wrow)[U], int ld, int lane)
+__device__ __forceinline__ void rows_load(v4i (&w)[U][CH], __amdgpu_buffer_rsrc_t rw, const int (&row)[U], int ld, int lane)
 {
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
             const int off = (c * 64 + lane) * 16;
-            w[u][c] = (v4i){0, 0, 0, 0};
-            if (wrow[u] != nullptr && off < ld) w[u][c] = *(const v4i *)(wrow[u] + off);
+            const unsigned o = (row[u] >= 0 && off < ld) ? (unsigned)row[u] * (unsigned)ld + (unsigned)off : Q8_OOB;
+            w[u][c] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rw, (int)o, 0, 0));
         }
 }
 

@@ -164,29 +164,33 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
     if (MODE != GRU_GX_PRE && !XPRE) x_load<N, CH>(xr, J.x, N, J.I, J.ldx);
     if (MODE != GRU_GH_PRE) x_load<N, CH>(hr, J.h_prev, N, H, J.ldh);
     v4i wx[3][CH], wh[3][CH];
-    if (MODE != GRU_GX_PRE) {
-        const int8_t *wrow[3];
+    {
+        int row[3];
 #pragma unroll
-        for (int gt = 0; gt < 3; ++gt) wrow[gt] = ok ? J.Wx + (size_t)(gt * H + unit) * J.ldwx : nullptr;
-        rows_load<3, CH>(wx, wrow, J.ldwx, lane);
-    }
-    if (MODE != GRU_GH_PRE) {
-        const int8_t *wrow[3];
-#pragma unroll
-        for (int gt = 0; gt < 3; ++gt) wrow[gt] = ok ? J.Wh + (size_t)(gt * H + unit) * J.ldwh : nullptr;
-        rows_load<3, CH>(wh, wrow, J.ldwh, lane);
+        for (int gt = 0; gt < 3; ++gt) row[gt] = ok ? gt * H + unit : -1;
+        if (MODE != GRU_GX_PRE) rows_load<3, CH>(wx, q8_rsrc(J.Wx, (size_t)3 * H * J.ldwx), row, J.ldwx, lane);
+        if (MODE != GRU_GH_PRE) rows_load<3, CH>(wh, q8_rsrc(J.Wh, (size_t)3 * H * J.ldwh), row, J.ldwh, lane);
     }
     // epilogue operands of lane j < N: biases, supplied pre-activations, previous state
+    // (unconditional, through descriptors: the other lanes and absent arrays read as zero)
     float pre[3] = {0.f, 0.f, 0.f}, bxv[3] = {0.f, 0.f, 0.f}, bhv[3] = {0.f, 0.f, 0.f}, hp = 0.f;
-    if (ok && lane < N) {
+    {
+        const bool mine = ok && lane < N;
+        const __amdgpu_buffer_rsrc_t rp = q8_rsrc(J.g_pre, MODE != GRU_FULL ? ((size_t)(N - 1) * J.ldg + 3 * H) * sizeof(float) : 0);
+        const __amdgpu_buffer_rsrc_t rbx = q8_rsrc(J.bx, J.bx ? (size_t)3 * H * sizeof(float) : 0);
+        const __amdgpu_buffer_rsrc_t rbh = q8_rsrc(J.bh, J.bh ? (size_t)3 * H * sizeof(float) : 0);
+        const __amdgpu_buffer_rsrc_t rh = q8_rsrc(J.h_prev, ((size_t)(N - 1) * J.ldh + H) * sizeof(float));
 #pragma unroll
         for (int gt = 0; gt < 3; ++gt) {
             const int row = gt * H + unit;
-            if (MODE != GRU_FULL) pre[gt] = J.g_pre[(size_t)lane * J.ldg + row];
-            if (MODE != GRU_GX_PRE && J.bx) bxv[gt] = J.bx[row];
-            if (MODE != GRU_GH_PRE && J.bh) bhv[gt] = J.bh[row];
+            if (MODE != GRU_FULL)
+                pre[gt] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rp, (int)(mine ? (unsigned)(lane * J.ldg + row) * 4u : Q8_OOB), 0, 0));
+            if (MODE != GRU_GX_PRE)
+                bxv[gt] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rbx, (int)(mine ? (unsigned)row * 4u : Q8_OOB), 0, 0));
+            if (MODE != GRU_GH_PRE)
+                bhv[gt] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rbh, (int)(mine ? (unsigned)row * 4u : Q8_OOB), 0, 0));
         }
-        hp = J.h_prev[(size_t)lane * J.ldh + unit];
+        hp = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rh, (int)(mine ? (unsigned)(lane * J.ldh + unit) * 4u : Q8_OOB), 0, 0));
     }
 
     if (MODE == GRU_FULL) {
@@ -407,6 +411,7 @@ q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode
         if (lh > max_ld) max_ld = lh;
         if (J.H > maxH) maxH = J.H;
         if ((mode != GRU_GX_PRE && J.I % 4) || J.H % 4) fast = false;
+        if ((size_t)3 * J.H * J.ldwx >= (1u << 31) || (size_t)3 * J.H * J.ldwh >= (1u << 31)) fast = false;   // 32-bit offsets
         int ldmin = mode == GRU_GX_PRE ? J.ldwh : (mode == GRU_GH_PRE ? J.ldwx : (J.ldwx < J.ldwh ? J.ldwx : J.ldwh));
         J.lpr = q8_lanes_per_row(ldmin);
         const size_t s = (size_t)n * (lx + lh);

@@ -160,11 +160,12 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
     x_load<N, CH>(xr, J.X, N, J.cols, J.ldx);
     int r = r_begin + wave * U;
     v4i w[U][CH];
+    const __amdgpu_buffer_rsrc_t rw = q8_rsrc(J.W, (size_t)J.rows * ld);
     {
-        const int8_t *wrow[U];
+        int row[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) wrow[u] = r + u < r_end ? J.W + (size_t)(r + u) * ld : nullptr;
-        rows_load<U, CH>(w, wrow, ld, lane);
+        for (int u = 0; u < U; ++u) row[u] = r + u < r_end ? r + u : -1;
+        rows_load<U, CH>(w, rw, row, ld, lane);
     }
     x_finish<N, CH>(xr, N, ld, smem, s_scale, s_red);
     if (blk == 0) write_x_taps<N>(J, smem, s_scale);
@@ -175,10 +176,10 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
         const int rn = r + 4 * U;
         v4i wn[U][CH];
         {
-            const int8_t *wrow[U];
+            int row[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) wrow[u] = rn + u < r_end ? J.W + (size_t)(rn + u) * ld : nullptr;
-            rows_load<U, CH>(wn, wrow, ld, lane);
+            for (int u = 0; u < U; ++u) row[u] = rn + u < r_end ? rn + u : -1;
+            rows_load<U, CH>(wn, rw, row, ld, lane);
         }
         int part[U][N], mine[U];
         rows_dot_part<N, U, CH>(w, ld, lane, smem, part);
@@ -302,6 +303,7 @@ q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
         J.ldx = d[t].ldx; J.ldy = d[t].ldy; J.w_scale = d[t].W->scale;
         if (J.ld > max_ld) max_ld = J.ld;
         if (J.cols % 4 != 0) fast = false;
+        if ((size_t)J.rows * J.ld >= (1u << 31)) fast = false;       // the fast kernel addresses the matrix with 32-bit offsets
     }
     const int ch = fast ? q8_fast_ch(max_ld) : 0;
     int blocks = 0;
