@@ -300,8 +300,8 @@ __global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
         rows_load<1, CH>(wy, q8_rsrc(a.Wy, (size_t)a.R * a.ldy), row, a.ldy, lane);
         rows_load<1, CH>(wc, q8_rsrc(a.Wc, (size_t)a.R * a.ldc), row, a.ldc, lane);
     }
-    float bt = 0.f;
-    if (ok && a.b_t) bt = a.b_t[unit];
+    const float bt = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+        q8_rsrc(a.b_t, a.b_t ? (size_t)a.R * sizeof(float) : 0), (int)(ok ? (unsigned)unit * 4u : Q8_OOB), 0, 0));
     {
         const int lds3[3] = {a.lds, a.ldy, a.ldc};
         int8_t *const dst[3] = {sq, yq, cq};

@@ -161,11 +161,20 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
     int r = r_begin + wave * U;
     v4i w[U][CH];
     const __amdgpu_buffer_rsrc_t rw = q8_rsrc(J.W, (size_t)J.rows * ld);
+    const __amdgpu_buffer_rsrc_t rb = q8_rsrc(J.bias, J.bias ? (size_t)J.rows * sizeof(float) : 0);
+    // biases of the rows in flight, requested with them (lane j < N finishes vector j; absent: zero)
+    auto bias_load = [&](float (&b)[U], int r0) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            b[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, (int)((lane < N && r0 + u < r_end) ? (unsigned)(r0 + u) * 4u : Q8_OOB), 0, 0));
+    };
+    float bw[U];
     {
         int row[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) row[u] = r + u < r_end ? r + u : -1;
         rows_load<U, CH>(w, rw, row, ld, lane);
+        bias_load(bw, r);
     }
     x_finish<N, CH>(xr, N, ld, smem, s_scale, s_red);
     if (blk == 0) write_x_taps<N>(J, smem, s_scale);
@@ -181,6 +190,8 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
             for (int u = 0; u < U; ++u) row[u] = rn + u < r_end ? rn + u : -1;
             rows_load<U, CH>(wn, rw, row, ld, lane);
         }
+        float bn[U];
+        bias_load(bn, rn);
         int part[U][N], mine[U];
         rows_dot_part<N, U, CH>(w, ld, lane, smem, part);
         sums_to_lanes<N, U>(part, lane, s_t[wave], mine);      // lane j < N: the totals of vector j
@@ -189,7 +200,7 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
             const int a = mine[u];
             if (lane < N && r + u < r_end) {
                 float y = (float)a * cj;
-                if (J.bias) y = y + J.bias[r + u];
+                if (J.bias) y = y + bw[u];
                 J.Y[(size_t)lane * J.ldy + r + u] = y;
                 if (J.tap_acc) J.tap_acc[(size_t)lane * J.rows + r + u] = a;
             }
@@ -198,6 +209,8 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
         for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int c = 0; c < CH; ++c) w[u][c] = wn[u][c];
+#pragma unroll
+        for (int u = 0; u < U; ++u) bw[u] = bn[u];
         r = rn;
     }
 }
