@@ -67,19 +67,33 @@ q8_status check_gru(q8_ctx *ctx, const q8_gru_weights *g, const char *name)
 
 // One GRU transition for n vectors (Eq. 1, 3, 4): h_out = GRU(x, h_prev).  gh_pre non-NULL:
 // the recurrent product (bias included) is already there and x alone is multiplied.
+// codes of the new states for whoever consumes them next (see q8i_gru_gates_q)
+struct PanelCodesOut {
+    int8_t *q1; int ld1; float *s1;
+    int8_t *q2; int ld2; float *s2;
+};
+
+// xq_pre / xs_pre (with gh_pre only): x arrives quantized.  out: the gates kernel also quantizes h_out.
 q8_status gru_panel(q8_ctx *ctx, Carver &cv, const q8_gru_weights *g, const float *x, const float *h_prev, int n,
-                    const float *gh_pre, float *h_out, const q8_taps *taps2)
+                    const float *gh_pre, float *h_out, const q8_taps *taps2, const int8_t *xq_pre = nullptr,
+                    const float *xs_pre = nullptr, const PanelCodesOut *out = nullptr)
 {
     const int I = g->Wx.cols, H = g->Wh.cols;
-    int8_t *xq = cv.take<int8_t>((size_t)n * g->Wx.ld), *hq = gh_pre ? nullptr : cv.take<int8_t>((size_t)n * g->Wh.ld);
-    float *xs = cv.take<float>(n), *hs = cv.take<float>(n);
+    const bool have_x = gh_pre && xq_pre && xs_pre && !taps2;
+    int8_t *xq = have_x ? nullptr : cv.take<int8_t>((size_t)n * g->Wx.ld), *hq = gh_pre ? nullptr : cv.take<int8_t>((size_t)n * g->Wh.ld);
+    float *xs = have_x ? nullptr : cv.take<float>(n), *hs = cv.take<float>(n);
     float *gx = cv.take<float>((size_t)n * 3 * H), *gh = gh_pre ? nullptr : cv.take<float>((size_t)n * 3 * H);
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "GRU panel: workspace too small");
-    const q8i_quant_job qj[2] = {{x, I, I, g->Wx.ld, xq, xs, taps2}, {h_prev, H, H, g->Wh.ld, hq, hs, taps2 ? taps2 + 1 : nullptr}};
-    TRY(q8i_quantize_jobs(ctx, qj, gh_pre ? 1 : 2, n));
-    const q8i_gemm_job gj[2] = {{&g->Wx, xq, xs, g->bx, gx, 3 * H, taps2 ? taps2[0].acc : nullptr, nullptr, nullptr, 0},
+    if (!have_x) {
+        const q8i_quant_job qj[2] = {{x, I, I, g->Wx.ld, xq, xs, taps2}, {h_prev, H, H, g->Wh.ld, hq, hs, taps2 ? taps2 + 1 : nullptr}};
+        TRY(q8i_quantize_jobs(ctx, qj, gh_pre ? 1 : 2, n));
+    }
+    const q8i_gemm_job gj[2] = {{&g->Wx, have_x ? xq_pre : xq, have_x ? xs_pre : xs, g->bx, gx, 3 * H, taps2 ? taps2[0].acc : nullptr, nullptr, nullptr, 0},
                                 {&g->Wh, hq, hs, g->bh, gh, 3 * H, taps2 ? taps2[1].acc : nullptr, nullptr, nullptr, 0}};
     TRY(q8i_gemm_jobs(ctx, gj, gh_pre ? 1 : 2, n));
+    if (out)
+        return q8i_gru_gates_q(ctx, gx, gh_pre ? gh_pre : gh, h_prev, H, h_out, H, H, n, out->q1, out->ld1, out->s1, out->q2,
+                               out->ld2, out->s2);
     return q8i_gru_gates(ctx, gx, gh_pre ? gh_pre : gh, h_prev, H, h_out, H, H, n);
 }
 
@@ -349,22 +363,30 @@ q8_status cgru_decoder_step_batch_q8(q8_ctx *ctx, const q8_cgru_weights *w, cons
     int8_t *mq_u = cv.take<int8_t>((size_t)n * w->att_U.ld), *mq_h = cv.take<int8_t>((size_t)n * w->q.Wh.ld);
     float *ms_u = cv.take<float>(n), *ms_h = cv.take<float>(n);
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "cgru_decoder_step_batch_q8: workspace too small");
-    // Eq. 3: s' = r(y, s_prev)
+    int8_t *cq = cv.take<int8_t>((size_t)n * w->q.Wx.ld);      // codes and scales of the context vectors,
+    float *cqs = cv.take<float>(n);                             // from the attention kernel to GRU q
+    if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "cgru_decoder_step_batch_q8: workspace too small");
+    // Eq. 3: s' = r(y, s_prev); the gates kernel leaves s' quantized for the two products below
+    const bool fused_codes = q8i_gru_gates_q_ok(H, H, H, w->att_U.ld, w->q.Wh.ld);
     {
         Carver sub = cv;
-        TRY(gru_panel(ctx, sub, &w->r, y_emb, s_prev, n, nullptr, s_mid, nullptr));
+        const PanelCodesOut out = {mq_u, w->att_U.ld, ms_u, mq_h, w->q.Wh.ld, ms_h};
+        TRY(gru_panel(ctx, sub, &w->r, y_emb, s_prev, n, nullptr, s_mid, nullptr, nullptr, nullptr, fused_codes ? &out : nullptr));
     }
     // everything that depends on s' alone: u(s') of Eq. 6 and the recurrent half of GRU q
-    const q8i_quant_job qj[2] = {{s_mid, H, H, w->att_U.ld, mq_u, ms_u, nullptr}, {s_mid, H, H, w->q.Wh.ld, mq_h, ms_h, nullptr}};
-    TRY(q8i_quantize_jobs(ctx, qj, 2, n));
+    if (!fused_codes) {
+        const q8i_quant_job qj[2] = {{s_mid, H, H, w->att_U.ld, mq_u, ms_u, nullptr}, {s_mid, H, H, w->q.Wh.ld, mq_h, ms_h, nullptr}};
+        TRY(q8i_quantize_jobs(ctx, qj, 2, n));
+    }
     const q8i_gemm_job gj[2] = {{&w->att_U, mq_u, ms_u, nullptr, a, A, nullptr, nullptr, nullptr, 0},
                                 {&w->q.Wh, mq_h, ms_h, w->q.bh, ghq, 3 * H, nullptr, nullptr, nullptr, 0}};
     TRY(q8i_gemm_jobs(ctx, gj, 2, n));
     // Eq. 5-6 per hypothesis, against the positions of its own sentence
-    TRY(q8i_attention(ctx, P, enc_h, max_l, A, C, a, w->att_v, n, e, alpha_out, ctx_out, sent_off, beam, nullptr, nullptr, 0, nullptr));
+    int have_codes = 0;
+    TRY(q8i_attention(ctx, P, enc_h, max_l, A, C, a, w->att_v, n, e, alpha_out, ctx_out, sent_off, beam, cq, cqs, w->q.Wx.ld, &have_codes));
     // Eq. 4: s = q(H_t, s')
     Carver sub = cv;
-    return gru_panel(ctx, sub, &w->q, ctx_out, s_mid, n, ghq, s_out, nullptr);
+    return gru_panel(ctx, sub, &w->q, ctx_out, s_mid, n, ghq, s_out, nullptr, have_codes ? cq : nullptr, have_codes ? cqs : nullptr);
 }
 
 static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,

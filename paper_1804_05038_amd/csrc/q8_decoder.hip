@@ -14,7 +14,7 @@ struct AttArgs {
     const int *sent_off;
     int beam, lde;          // lde: row pitch of e and alpha
     // optional: codes [n x ldq] (bytes [C, ldq) zero) and scales [n] of the context vectors, so that
-    // the consumer (GRU q) does not quantize them again in every block; needs C even, ldq <= 2 blockDim
+    // the consumer (GRU q) does not quantize them again; needs C even, ldq <= 2 ATT_PAIRS blockDim
     int8_t *ctx_q;
     float *ctx_qscale;
     int ldq;
@@ -33,6 +33,7 @@ __device__ __forceinline__ int att_sentence(const AttArgs &a, int b, const float
 }
 
 #define ATT_MAX_THREADS 1024
+#define ATT_PAIRS 4
 // Run by the last block to arrive for hypothesis b (all its l energies are in a.e, written
 // with device-coherent stores): softmax over the energies in one wave, then the context
 // vector H_t (Eq. 5), a thread owning two adjacent columns and walking the source positions
@@ -65,32 +66,43 @@ __device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const
     }
     __syncthreads();
     if (a.ctx_q) {
-        // one pair of columns per thread; the vector's codes come from the rounded values in registers
+        // up to ATT_PAIRS pairs of columns per thread, kept in registers: the vector's codes come from
+        // the rounded values (C <= 2 ATT_PAIRS blockDim)
         __shared__ float s_m[ATT_MAX_THREADS / 64];
-        const int c = tid * 2;
-        float f0 = 0.0f, f1 = 0.0f;
-        if (c < a.C) {
-            double s0 = 0.0, s1 = 0.0;
-            const float *h = enc_h + c;
+        float f[ATT_PAIRS][2];
+        float m = 0.0f;
+#pragma unroll
+        for (int it = 0; it < ATT_PAIRS; ++it) {
+            const int c = (it * nt + tid) * 2;
+            f[it][0] = f[it][1] = 0.0f;
+            if (c < a.C) {
+                double s0 = 0.0, s1 = 0.0;
+                const float *h = enc_h + c;
 #pragma unroll 10
-            for (int t = 0; t < l; ++t) {
-                const float2 hv = *(const float2 *)(h + (size_t)t * a.C);
-                const double al = (double)s_alpha[t];
-                s0 += al * (double)hv.x;
-                s1 += al * (double)hv.y;
+                for (int t = 0; t < l; ++t) {
+                    const float2 hv = *(const float2 *)(h + (size_t)t * a.C);
+                    const double al = (double)s_alpha[t];
+                    s0 += al * (double)hv.x;
+                    s1 += al * (double)hv.y;
+                }
+                f[it][0] = (float)s0;
+                f[it][1] = (float)s1;
+                *(float2 *)(a.ctx + (size_t)b * a.C + c) = make_float2(f[it][0], f[it][1]);
             }
-            f0 = (float)s0;
-            f1 = (float)s1;
-            *(float2 *)(a.ctx + (size_t)b * a.C + c) = make_float2(f0, f1);
+            m = fmaxf(m, fmaxf(fabsf(f[it][0]), fabsf(f[it][1])));
         }
-        float m = wave_max_f(fmaxf(fabsf(f0), fabsf(f1)));
+        m = wave_max_f(m);
         if (lane == 0) s_m[wave] = m;
         __syncthreads();
         m = 0.0f;
         for (int w = 0; w < nt / 64; ++w) m = fmaxf(m, s_m[w]);
         float scale, inv;
         q8_scale_of(m, scale, inv);
-        if (c < a.ldq) *(short *)(a.ctx_q + (size_t)b * a.ldq + c) = (short)q8_pack2(f0, f1, inv);   // zeros past C
+#pragma unroll
+        for (int it = 0; it < ATT_PAIRS; ++it) {
+            const int c = (it * nt + tid) * 2;
+            if (c < a.ldq) *(short *)(a.ctx_q + (size_t)b * a.ldq + c) = (short)q8_pack2(f[it][0], f[it][1], inv);   // zeros past C
+        }
         if (tid == 0) a.ctx_qscale[b] = scale;
     } else if ((a.C & 1) == 0) {
         for (int c = tid * 2; c < a.C; c += 2 * nt) {
@@ -390,7 +402,8 @@ q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, 
     t.counters = (unsigned *)ctx->ws;
     t.l = l; t.A = A; t.C = C;
     t.sent_off = sent_off; t.beam = beam; t.lde = l;
-    const bool codes = ctx_q && ctx_qscale && n <= Q8_MAX_BEAM && C % 2 == 0 && ldq >= C && ldq % 2 == 0 && ldq <= 2 * ATT_THREADS;
+    const int threads = n > Q8_MAX_BEAM ? 256 : ATT_THREADS;
+    const bool codes = ctx_q && ctx_qscale && C % 2 == 0 && ldq >= C && ldq % 2 == 0 && ldq <= 2 * ATT_PAIRS * threads;
     t.ctx_q = codes ? ctx_q : nullptr; t.ctx_qscale = ctx_qscale; t.ldq = ldq;
     if (codes_written) *codes_written = codes ? 1 : 0;
     if (n > Q8_MAX_BEAM)

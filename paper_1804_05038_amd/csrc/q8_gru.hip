@@ -275,6 +275,61 @@ __global__ __launch_bounds__(256) void gru_gates_kernel(const float *__restrict_
     h_out[(size_t)j * ldo + u] = gru_gates(xv, hv, h_prev[(size_t)j * ldh + u]);
 }
 
+// The same gates, one block per vector, which also leaves the new state quantized for the products
+// that consume it next (up to two code buffers with their own row pitch, pad bytes zero): the block
+// holds the whole vector, so its max |h| costs one exchange.  Thread t owns units 4 t .. 4 t + 3 of
+// every 1024 (G groups: H <= 1024 G, H % 4 == 0).
+struct GatesQArgs {
+    const float *gx, *gh, *h_prev;
+    float *h_out;
+    int8_t *q1, *q2;            // q2 may be NULL
+    float *s1, *s2;
+    int ldh, ldo, H, ld1, ld2;
+};
+template <int G>
+__global__ __launch_bounds__(256) void gru_gates_q_kernel(GatesQArgs a)
+{
+    __shared__ float s_m[4];
+    const int j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, H = a.H;
+    const float *x = a.gx + (size_t)j * 3 * H, *h = a.gh + (size_t)j * 3 * H, *hp = a.h_prev + (size_t)j * a.ldh;
+    float4 hv[G];
+    float m = 0.0f;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const int u = (g * 256 + tid) * 4;
+        hv[g] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (u < H) {
+            const float4 x0 = *(const float4 *)(x + u), x1 = *(const float4 *)(x + H + u), x2 = *(const float4 *)(x + 2 * H + u);
+            const float4 h0 = *(const float4 *)(h + u), h1 = *(const float4 *)(h + H + u), h2 = *(const float4 *)(h + 2 * H + u);
+            const float4 p = *(const float4 *)(hp + u);
+            const float xa[3] = {x0.x, x1.x, x2.x}, ha[3] = {h0.x, h1.x, h2.x};
+            const float xb[3] = {x0.y, x1.y, x2.y}, hb[3] = {h0.y, h1.y, h2.y};
+            const float xc[3] = {x0.z, x1.z, x2.z}, hc[3] = {h0.z, h1.z, h2.z};
+            const float xd[3] = {x0.w, x1.w, x2.w}, hd[3] = {h0.w, h1.w, h2.w};
+            hv[g] = make_float4(gru_gates(xa, ha, p.x), gru_gates(xb, hb, p.y), gru_gates(xc, hc, p.z), gru_gates(xd, hd, p.w));
+            *(float4 *)(a.h_out + (size_t)j * a.ldo + u) = hv[g];
+        }
+        m = fmaxf(m, fmaxf(fmaxf(fabsf(hv[g].x), fabsf(hv[g].y)), fmaxf(fabsf(hv[g].z), fabsf(hv[g].w))));
+    }
+    m = wave_max_f(m);
+    if (lane == 0) s_m[wave] = m;
+    __syncthreads();
+    m = fmaxf(fmaxf(s_m[0], s_m[1]), fmaxf(s_m[2], s_m[3]));
+    float scale, inv;
+    q8_scale_of(m, scale, inv);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const int u = (g * 256 + tid) * 4;
+        const int code = q8_pack4(hv[g].x, hv[g].y, hv[g].z, hv[g].w, inv);       // zero past H
+        if (u < a.ld1) *(int *)(a.q1 + (size_t)j * a.ld1 + u) = code;
+        if (a.q2 && u < a.ld2) *(int *)(a.q2 + (size_t)j * a.ld2 + u) = code;
+    }
+    if (tid == 0) {
+        a.s1[j] = scale;
+        if (a.q2) a.s2[j] = scale;
+    }
+}
+
 // Encoder recurrences of many sentences side by side (Eq. 1), one launch pair per time
 // step.  Direction d = 0: forward state, columns [H, 2H) of enc_h, step t works on position
 // t; d = 1: backward state, columns [0, H), position l - 1 - t.  Sentence s occupies rows
@@ -362,6 +417,25 @@ q8_status q8i_gru_gates(q8_ctx *ctx, const float *gx, const float *gh, const flo
     return q8i_launch_check(ctx, "gru gates");
 }
 
+
+// gates + codes of the new states; false if the shape is not covered (the caller then runs the
+// gates and the quantization as two launches)
+bool q8i_gru_gates_q_ok(int H, int ldh, int ldo, int ld1, int ld2)
+{
+    const int G = (H + 1023) / 1024;
+    return H % 4 == 0 && ldh % 4 == 0 && ldo % 4 == 0 && G <= 4 && ld1 <= 1024 * G && ld2 <= 1024 * G && ld1 % 4 == 0 && ld2 % 4 == 0;
+}
+
+q8_status q8i_gru_gates_q(q8_ctx *ctx, const float *gx, const float *gh, const float *h_prev, int ldh, float *h_out,
+                          int ldo, int H, int n, int8_t *q1, int ld1, float *s1, int8_t *q2, int ld2, float *s2)
+{
+    GatesQArgs a = {gx, gh, h_prev, h_out, q1, q2, s1, s2, ldh, ldo, H, ld1, q2 ? ld2 : 0};
+    const int G = (H + 1023) / 1024;
+    if (G == 1) Q8_LAUNCH(ctx, Q8_KERNEL_GRU, gru_gates_q_kernel<1>, dim3(n), dim3(256), 0, a);
+    else if (G == 2) Q8_LAUNCH(ctx, Q8_KERNEL_GRU, gru_gates_q_kernel<2>, dim3(n), dim3(256), 0, a);
+    else Q8_LAUNCH(ctx, Q8_KERNEL_GRU, gru_gates_q_kernel<4>, dim3(n), dim3(256), 0, a);
+    return q8i_launch_check(ctx, "gru gates + codes");
+}
 
 template <int N, int MODE>
 static void launch_gru_nm(q8_ctx *ctx, const GruJobs &jobs, int njobs, int blocks, size_t smem, int ch, bool xpre)

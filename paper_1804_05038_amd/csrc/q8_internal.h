@@ -127,12 +127,16 @@ q8_status q8i_vocab_panel(q8_ctx *ctx, const q8_mat *W, const float *bias, const
                           float *Y_tiled, float *part_max, double *part_sum);
 q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode);
 // ctx_q / ctx_qscale (may be NULL): where the finishing blocks leave the codes [n x ldq] and scales [n] of the
-// context vectors; *codes_written says whether this launch does (single sentence, C even, ldq <= 2048)
+// context vectors; *codes_written says whether this launch does (C even, ldq <= 8192, panels: ldq <= 2048)
 q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, int A, int C, const float *a,
                         const float *v, int n, float *e, float *alpha, float *cvec, const int *sent_off, int beam,
                         int8_t *ctx_q, float *ctx_qscale, int ldq, int *codes_written);
 q8_status q8i_gru_gates(q8_ctx *ctx, const float *gx, const float *gh, const float *h_prev, int ldh, float *h_out,
                         int ldo, int H, int n);
+// the same, also leaving the new states quantized in q1 [n x ld1] / s1 [n] (and q2 / s2 unless q2 is NULL)
+bool q8i_gru_gates_q_ok(int H, int ldh, int ldo, int ld1, int ld2);
+q8_status q8i_gru_gates_q(q8_ctx *ctx, const float *gx, const float *gh, const float *h_prev, int ldh, float *h_out,
+                          int ldo, int H, int n, int8_t *q1, int ld1, float *s1, int8_t *q2, int ld2, float *s2);
 // one time step of the batched encoder: phase 0 quantizes the previous states, phase 1 applies the gates
 q8_status q8i_enc_step(q8_ctx *ctx, int phase, const int *sent_off, int S, int t, int H, int ld, float *enc_h,
                        const float *gxf, const float *gxb, float *ghf, float *ghb, int8_t *hqf, int8_t *hqb, float *hsf,
