@@ -38,7 +38,7 @@ __device__ __forceinline__ int att_sentence(const AttArgs &a, int b, const float
 // with device-coherent stores): softmax over the energies in one wave, then the context
 // vector H_t (Eq. 5), a thread owning two adjacent columns and walking the source positions
 // in order.  Sums run in double; every stored value is rounded once.
-__device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const float *enc_h, float *s_alpha)
+__device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const float *enc_h, double *s_alpha)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nt = blockDim.x;
     if (wave == 0) {
@@ -46,20 +46,20 @@ __device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const
         float mx = -INFINITY;
         for (int t = lane; t < l; t += 64) {
             const float ev = __hip_atomic_load(e + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s_alpha[t] = ev;
+            s_alpha[t] = (double)ev;
             mx = fmaxf(mx, ev);
         }
         mx = wave_max_f(mx);
         double Z = 0.0, ex0 = 0.0;               // ex0: the lane's first term, kept for the division below
         for (int t = lane; t < l; t += 64) {
-            const double ex = q8_exp_d(fmax((double)s_alpha[t] - (double)mx, -700.0));
+            const double ex = q8_exp_d(fmax(s_alpha[t] - (double)mx, -700.0));
             if (t == lane) ex0 = ex;
             Z += ex;
         }
         Z = wave_sum_d(Z);
         for (int t = lane; t < l; t += 64) {
-            const float al = (float)((t == lane ? ex0 : q8_exp_d(fmax((double)s_alpha[t] - (double)mx, -700.0))) / Z);
-            s_alpha[t] = al;
+            const float al = (float)((t == lane ? ex0 : q8_exp_d(fmax(s_alpha[t] - (double)mx, -700.0))) / Z);
+            s_alpha[t] = (double)al;          // the weight as the context sum uses it: converted once, not per column
             if (a.alpha) a.alpha[(size_t)b * a.lde + t] = al;
         }
         if (lane == 0) __hip_atomic_store(&a.counters[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -81,7 +81,7 @@ __device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const
 #pragma unroll 10
                 for (int t = 0; t < l; ++t) {
                     const float2 hv = *(const float2 *)(h + (size_t)t * a.C);
-                    const double al = (double)s_alpha[t];
+                    const double al = s_alpha[t];
                     s0 += al * (double)hv.x;
                     s1 += al * (double)hv.y;
                 }
@@ -111,7 +111,7 @@ __device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const
 #pragma unroll 10
             for (int t = 0; t < l; ++t) {
                 const float2 hv = *(const float2 *)(h + (size_t)t * a.C);
-                const double al = (double)s_alpha[t];
+                const double al = s_alpha[t];
                 s0 += al * (double)hv.x;
                 s1 += al * (double)hv.y;
             }
@@ -120,7 +120,7 @@ __device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const
     } else {
         for (int c = tid; c < a.C; c += nt) {
             double s = 0.0;
-            for (int t = 0; t < l; ++t) s += (double)s_alpha[t] * (double)enc_h[(size_t)t * a.C + c];
+            for (int t = 0; t < l; ++t) s += s_alpha[t] * (double)enc_h[(size_t)t * a.C + c];
             a.ctx[(size_t)b * a.C + c] = (float)s;
         }
     }
@@ -133,7 +133,7 @@ __device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const
 __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
 {
     __shared__ double s_red[ATT_THREADS / 64];
-    __shared__ float s_alpha[1024];
+    __shared__ double s_alpha[1024];
     __shared__ int s_last;
     const int i = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const float *P, *enc_h;
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
 #define ATTP_POS 8
 __global__ __launch_bounds__(256) void attention_panel_kernel(AttArgs a)
 {
-    __shared__ float s_alpha[1024];
+    __shared__ double s_alpha[1024];
     __shared__ int s_last;
     const int b = blockIdx.y, tid = threadIdx.x;
     const float *P, *enc_h;
