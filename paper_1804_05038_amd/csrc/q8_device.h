@@ -628,32 +628,6 @@ __device__ __forceinline__ void rows_dot_part(const v4i (&w)[U][CH], int ld, int
     }
 }
 
-// Dots the staged rows with the N quantized vectors in LDS; every lane gets every sum.
-template <int N, int U, int CH>
-__device__ __forceinline__ void rows_dot(const v4i (&w)[U][CH], int ld, int lane, const int8_t *xq, int (&acc)[U][N])
-{
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int j = 0; j < N; ++j) acc[u][j] = 0;
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-        const int off = (c * 64 + lane) * 16;
-        if (off < ld) {
-#pragma unroll
-            for (int j = 0; j < N; ++j) {
-                const v4i x = *(const v4i *)(xq + (size_t)j * ld + off);
-#pragma unroll
-                for (int u = 0; u < U; ++u) acc[u][j] = dot16(w[u][c], x, acc[u][j]);
-            }
-        }
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int j = 0; j < N; ++j) acc[u][j] = group_sum_i(acc[u][j], 64);
-}
-
 // Chunks per lane of the fast path for a row of ld bytes (0 = not covered).
 static inline int q8_fast_ch(int ld) { return ld <= 1024 ? 1 : (ld <= 2048 ? 2 : (ld <= 4096 ? 4 : 0)); }
 
