@@ -460,17 +460,7 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     if (lane == 0) s_f[wave] = sorted;
     if (lane == k - 1) s_t4[wave] = sorted;       // -inf if the wave has fewer than k non-empty threads
     __syncthreads();
-    float m = fmaxf(fmaxf(s_f[0], s_f[1]), fmaxf(s_f[2], s_f[3]));
-    double S = 0.0;
-#pragma unroll
-    for (int t = 0; t < OUT_SB; ++t)
-        if (pm[t] > -INFINITY) S += ps[t] * (double)__expf(pm[t] - m);
-    S = wave_sum_d(S);
-    if (lane == 0) s_d[wave] = S;
-    __syncthreads();
-    S = (s_d[0] + s_d[1]) + (s_d[2] + s_d[3]);
-    const float lse = a.normalized ? 0.0f : (float)((double)m + log(S));
-    if (tid == 0 && a.lse) a.lse[j] = lse;
+    const float m = fmaxf(fmaxf(s_f[0], s_f[1]), fmaxf(s_f[2], s_f[3]));
     const float T = fmaxf(fmaxf(s_t4[0], s_t4[1]), fmaxf(s_t4[2], s_t4[3]));   // -inf: everything qualifies
 
     // ---- tiles that can hold a logit >= T
@@ -483,9 +473,34 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     const float *lg = a.tiled ? a.logits + (size_t)j * OUT_TILE : a.logits + (size_t)j * a.ldl;
     const size_t tile_pitch = a.tiled ? (size_t)a.n * OUT_TILE - OUT_TILE : 0;     // extra floats per tile boundary
     auto logit = [&](int r) { return lg[(size_t)r + (size_t)(r / OUT_TILE) * tile_pitch]; };
-    bool overflow = false;
-    if (total <= 16 * SEL_CAP) {
-        for (int c0 = tid; c0 < total; c0 += 1024) {
+    // The first 1024 logits of those tiles are requested now, without branches (an entry past the end
+    // reads some valid row and is dropped), and the log-sum-exp is summed while they are on their way.
+    float v0[4];
+    int row0[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int c = tid + 256 * t, cc = min(c, max(total, 1) - 1);
+        const int r = (int)s_q[cc / OUT_TILE] * OUT_TILE + cc % OUT_TILE;
+        row0[t] = (c < total && r < a.V) ? r : -1;
+        v0[t] = logit(min(r, a.V - 1));
+    }
+    // ---- log-sum-exp (1): this wave's share of the sum
+    double S = 0.0;
+#pragma unroll
+    for (int t = 0; t < OUT_SB; ++t)
+        if (pm[t] > -INFINITY) S += ps[t] * (double)__expf(pm[t] - m);
+    S = wave_sum_d(S);
+    if (lane == 0) s_d[wave] = S;
+    // ---- logits >= T of the qualifying tiles
+    bool overflow = total > 16 * SEL_CAP;
+    if (!overflow) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            if (row0[t] >= 0 && v0[t] >= T) {
+                const int pos = atomicAdd(&s_ns, 1);
+                if (pos < SEL_CAP) s_key[pos] = topk_key(v0[t], row0[t]);
+            }
+        for (int c0 = tid + 1024; c0 < total; c0 += 1024) {
             float v[4];
             int row[4];
 #pragma unroll
@@ -505,11 +520,13 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
                     if (pos < SEL_CAP) s_key[pos] = topk_key(v[t], row[t]);
                 }
         }
-        __syncthreads();
-        overflow = s_ns > SEL_CAP;
-    } else {
-        overflow = true;
     }
+    __syncthreads();
+    overflow = overflow || s_ns > SEL_CAP;
+    // ---- log-sum-exp (2)
+    S = (s_d[0] + s_d[1]) + (s_d[2] + s_d[3]);
+    const float lse = a.normalized ? 0.0f : (float)((double)m + log(S));
+    if (tid == 0 && a.lse) a.lse[j] = lse;
 
     if (!overflow) {
         // rank every survivor among the survivors; ranks below k are the answer
