@@ -272,13 +272,13 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     out_logits_body<1, PACKED, QKPL>(a);
 }
 
-// The kernel for tile-packed matrices with rows of at most 512 bytes: one tile per wave, eight
+// The kernel for tile-packed matrices with rows of at most 64 KS bytes (KS = 8 or 10): one tile per wave, eight
 // waves per block, two blocks per compute unit, so that all of the matrix is requested within
 // the first microsecond and nothing loops.  Wave j < n requests hidden vector j first (its
 // data comes back ahead of the weights, which every wave requests next), quantizes it alone
 // (no exchange between waves) and leaves the codes in LDS; after the one barrier every wave
 // holds the codes of all vectors as operand B in registers.  KPL float4 per lane and vector.
-template <int KPL>
+template <int KPL, int KS>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))) void out_logits8_kernel(OutArgs a)
 {
     extern __shared__ __align__(16) int8_t smem[];     // [n x pitch] codes of the hidden vectors
@@ -297,12 +297,12 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
         const unsigned off = (wave < n && k < a.K) ? (unsigned)(wave * a.ldt + k) * 4u : Q8_OOB;
         tv[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rT, (int)off, 0, 0));
     }
-    // the tile: eight wave-wide loads of one contiguous KiB each, non-temporal like Q8_WLOAD
+    // the tile: up to KS wave-wide loads of one contiguous KiB each, non-temporal like Q8_WLOAD
     const __amdgpu_buffer_rsrc_t rW = q8_rsrc(a.tiles, (size_t)a.ntiles * ld * OUT_TILE);
     const unsigned woff = have ? (unsigned)tile * (unsigned)(ld * OUT_TILE) + lane * 16u : Q8_OOB;
-    v4i av[8];
+    v4i av[KS];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+    for (int s = 0; s < KS; ++s) {
         const unsigned off = s < ksteps ? woff + 1024u * s : Q8_OOB;
         av[s] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rW, (int)off, 0, 2));
     }
@@ -341,16 +341,16 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     if (!have) return;
 
     // operand B: hypothesis i's codes, k = 64 s + 16 g ..
-    v4i bv[8];
+    v4i bv[KS];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
+    for (int s = 0; s < KS; ++s) {
         bv[s] = (v4i){0, 0, 0, 0};
         if (i < n && s < ksteps) bv[s] = *(const v4i *)(smem + (size_t)i * pitch + 64 * s + 16 * g);
     }
     const float cj = i < n ? a.w_scale * s_scale[i] : 0.0f;
     v4i acc0 = (v4i){0, 0, 0, 0}, acc1 = (v4i){0, 0, 0, 0};     // two chains: a dependent matrix-core op waits twice as long
 #pragma unroll
-    for (int s = 0; s < 8; s += 2) {
+    for (int s = 0; s < KS; s += 2) {
         acc0 = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[s], bv[s], acc0, 0, 0, 0);
         acc1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[s + 1], bv[s + 1], acc1, 0, 0, 0);
     }
@@ -720,13 +720,14 @@ q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const floa
     const int nblk = a.ntiles < 4 * OUT_BLOCKS ? (a.ntiles + 3) / 4 : OUT_BLOCKS;
     const size_t smem = (size_t)n * a.ld;
     const int ch = q8_fast_ch(a.ld);
-    if (a.tiles && a.ld <= 512) {
+    if (a.tiles && a.ld <= 640) {
         // one tile per wave: a.ntiles <= OUT_MAX_TILES = 8 * OUT_BLOCKS
         // (at most 256 blocks' worth of tiles: one block per compute unit; more: two each, evenly filled)
         const int nblk8 = a.ntiles <= 8 * (OUT_BLOCKS / 2) ? (a.ntiles + 7) / 8 : OUT_BLOCKS;
         const size_t smem8 = (size_t)n * (a.ld + 16);
-        if (a.K <= 256) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, out_logits8_kernel<1>, dim3(nblk8), dim3(512), smem8, a);
-        else Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, out_logits8_kernel<2>, dim3(nblk8), dim3(512), smem8, a);
+        if (a.ld > 512) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits8_kernel<3, 10>), dim3(nblk8), dim3(512), smem8, a);
+        else if (a.K <= 256) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits8_kernel<1, 8>), dim3(nblk8), dim3(512), smem8, a);
+        else Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits8_kernel<2, 8>), dim3(nblk8), dim3(512), smem8, a);
     } else if (a.tiles) {
         launch_out_packed<true>(ctx, a, nblk, smem, ch);
     } else {
