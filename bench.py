@@ -521,7 +521,7 @@ def main():
         "steps_per_s_beam5_eager": 1.0 / eager5, "us_per_step_graph": graph_us,
         "concurrent_sentences": concurrent,
         "weights_GBps_whole_step": weights_per_step / best5 / 1e9,
-        "roofline": {"bound": "hbm", "kernel": "out_logits8_kernel<2> (50000x512 int8 vocabulary matrix, 5 hypotheses)",
+        "roofline": {"bound": "hbm", "kernel": "out_logits8_kernel<2, 8> (50000x512 int8 vocabulary matrix, 5 hypotheses)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": VOCAB_KERNEL_TRAFFIC_BYTES, "traffic_unit": "bytes per launch",
                      "traffic_source": "rocprofv3 --pmc FETCH_SIZE (x2.00) + WRITE_SIZE (x1.00) of bench.py --quick, "
