@@ -286,12 +286,26 @@ __global__ __launch_bounds__(64 * VP_WAVES) void vocab_panel_kernel(PanelArgs a)
         for (int s = 0; s < KC; ++s) A[s] = __builtin_nontemporal_load((const v4i *)(p + 1024 * s));
     };
     load_tile(A0, gw);
-    // the codes of this block's slots into LDS (rows past the panel are zero)
-    for (int p = tid; p < nt * 16 * (ld / 16); p += 64 * VP_WAVES) {
-        const int col = p / (ld / 16), ch = p - col * (ld / 16);
-        v4i v = (v4i){0, 0, 0, 0};
-        if (col < cols) v = *(const v4i *)(a.xq + (size_t)(c_base + col) * ld + ch * 16);
-        *(v4i *)(s_x + col * pitch + ch * 16) = v;
+    // the codes of this block's slots into LDS (slots past the panel are zero): eight 16-byte pieces per
+    // thread and round, requested together through a bounds-checked descriptor (no branch around a
+    // load: inside one, every piece would be a memory round trip of its own)
+    {
+        const __amdgpu_buffer_rsrc_t rx = q8_rsrc(a.xq + (size_t)c_base * ld, (size_t)cols * ld);
+        const int total = nt * 16 * (ld / 16);
+        for (int p0 = 0; p0 < total; p0 += 8 * 64 * VP_WAVES) {
+            v4i v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int p = p0 + u * 64 * VP_WAVES + tid;      // piece p: slot p / (ld / 16), bytes 16 (p % (ld / 16)) ..
+                v[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(p < total ? (unsigned)p * 16u : Q8_OOB), 0, 0));
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int p = p0 + u * 64 * VP_WAVES + tid;
+                const int col = p / (ld / 16), ch = p - col * (ld / 16);
+                if (p < total) *(v4i *)(s_x + col * pitch + ch * 16) = v[u];
+            }
+        }
     }
     float *s_c = (float *)(s_x + (size_t)a.cols_per_group * pitch);      // dequantization factor of every slot
     for (int c = tid; c < nt * 16; c += 64 * VP_WAVES) s_c[c] = c < cols ? a.w_scale * a.xscale[c_base + c] : 0.0f;

@@ -116,6 +116,7 @@ def test_gemm_narrow_matrix_cores(q, ctx, oracle, rows, cols, n):
     assert_same(taps["xq"], xq, "xq"); assert_same(taps["xscale"], xs, "xscale")
     assert_same(taps["acc"], acc, "acc"); assert_same(Y, Y_ref, "Y")
     assert_same(q.q8_gemm_narrow(ctx, M, ctx.f32(X), ctx.f32(b)), Y_ref, "Y, no taps")
+    assert_same(q.q8_gemm_narrow(ctx, M, ctx.f32(X)), oracle.QLinear(W, None).gemm_narrow(X), "Y, no taps, no bias")
 
 
 def test_argument_errors_are_reported_not_launched(q, ctx):
