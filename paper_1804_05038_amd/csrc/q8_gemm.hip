@@ -244,6 +244,99 @@ __global__ __launch_bounds__(256) void gemm_block_kernel(GemmJobs jobs)
     }
 }
 
+// ============================================================== K-resident blocks ==
+// Rows of at most 64 KS bytes (KS = 8 or 16): nothing is staged.  A block of four waves takes
+// 64 rows x 64 vectors; every wave requests its 16 rows whole (KS operands per lane), the block
+// requests the 64 vectors' codes whole (one vector row per wave-wide load) and parks them in LDS
+// at pitch 64 KS + 16 (16 lanes x 16 bytes then fall on distinct banks); one barrier; 4 KS
+// matrix-core instructions per wave in four independent chains.  All loads go through
+// bounds-checked descriptors without branches (what lies outside reads as zero), so they are all
+// in flight before the first wait.  Matrices and panels below 2 GiB, no taps, no statistics.
+template <int KS>
+__global__ __launch_bounds__(256) void gemm_resident_kernel(GemmJobs jobs)
+{
+    extern __shared__ __align__(16) int8_t s_v[];        // [64 x pitch]
+    const GemmArgs &a = jobs.j[blockIdx.z];
+    if ((int)blockIdx.x * 64 >= a.rows) return;          // the grid is sized for the largest job
+    constexpr int pitch = 64 * KS + 16, PCS = 4 * KS;    // 16-byte pieces per (padded) vector
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int i = lane & 15, g = lane >> 4;
+    const int r0 = ((int)blockIdx.x * 4 + wave) * 16, c0 = (int)blockIdx.y * 64;
+    const int ld = a.ld, n = a.n, rows = a.rows;
+
+    // the vectors' codes: thread (v, pc) = (tid / PCS, tid % PCS) takes piece pc of vectors v, v + 256 / PCS, ...
+    const __amdgpu_buffer_rsrc_t rx = q8_rsrc(a.xq, (size_t)n * ld);
+    const int pc = tid & (PCS - 1), v0 = tid / PCS;
+    v4i bq[KS];
+#pragma unroll
+    for (int u = 0; u < KS; ++u) {
+        const int col = c0 + v0 + u * (256 / PCS);
+        const unsigned off = (col < n && pc * 16 < ld) ? (unsigned)col * (unsigned)ld + pc * 16u : Q8_OOB;
+        bq[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0));
+    }
+    // this wave's 16 rows
+    const __amdgpu_buffer_rsrc_t rw = q8_rsrc(a.W, (size_t)rows * ld);
+    const int row = r0 + i;
+    v4i av[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        const int k = 64 * s + 16 * g;
+        const unsigned off = (row < rows && k < ld) ? (unsigned)row * (unsigned)ld + (unsigned)k : Q8_OOB;
+        av[s] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rw, (int)off, 0, 0));
+    }
+    // epilogue operands: dequantization factors and biases
+    float cs[4];
+    const __amdgpu_buffer_rsrc_t rs = q8_rsrc(a.xscale, (size_t)n * sizeof(float));
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+        cs[t] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(c0 + 16 * t + i < n ? (unsigned)(c0 + 16 * t + i) * 4u : Q8_OOB), 0, 0));
+    const int row0 = r0 + 4 * g;
+    const __amdgpu_buffer_rsrc_t rb = q8_rsrc(a.bias, a.bias ? (size_t)rows * sizeof(float) : 0);
+    float bias[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        bias[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, (int)(row0 + r < rows ? (unsigned)(row0 + r) * 4u : Q8_OOB), 0, 0));
+    __builtin_amdgcn_sched_barrier(0);
+
+#pragma unroll
+    for (int u = 0; u < KS; ++u) *(v4i *)(s_v + (v0 + u * (256 / PCS)) * pitch + pc * 16) = bq[u];
+    __syncthreads();
+    if (r0 >= rows) return;                              // wave-uniform, after the only barrier
+
+    v4i acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[t] = (v4i){0, 0, 0, 0};
+    const int8_t *bp = s_v + i * pitch + 16 * g;
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const v4i bv = *(const v4i *)(bp + t * 16 * pitch + 64 * s);
+            acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[s], bv, acc[t], 0, 0, 0);
+        }
+
+    const bool vec_ok = ((a.ldy & 3) == 0) && (((uintptr_t)a.Y & 15) == 0);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int col = c0 + 16 * t + i;
+        if (col >= n) continue;
+        const float c = a.w_scale * cs[t];
+        float y[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            y[r] = (float)acc[t][r] * c;
+            if (a.bias) y[r] = y[r] + bias[r];
+        }
+        if (vec_ok && row0 + 3 < rows) {
+            *(float4 *)(a.Y + (size_t)col * a.ldy + row0) = make_float4(y[0], y[1], y[2], y[3]);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (row0 + r < rows) a.Y[(size_t)col * a.ldy + row0 + r] = y[r];
+        }
+    }
+}
+
 // ================================================================ vocabulary panel ==
 // The vocabulary product for a panel of hypothesis slots (many sentences side by side).  Unlike
 // the block kernel above, a block keeps its share of the vectors' codes in LDS for its whole
@@ -488,6 +581,30 @@ q8_status q8i_gemm_jobs(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n)
         if (a.rows > max_rows) max_rows = a.rows;
     }
     const bool stats = d[0].part_max != nullptr;
+    // K-resident blocks: every product with rows of at most 1024 bytes, plain output, no taps
+    bool resident = !stats && n > 8;
+    int max_ld = 0;
+    for (int t = 0; t < njobs; ++t) {
+        const GemmArgs &a = jobs.j[t];
+        if (a.ld > 1024 || a.tap_acc || a.tiled || (size_t)a.rows * a.ld >= (1u << 31) || (size_t)n * a.ld >= (1u << 31)) resident = false;
+        if (a.ld > max_ld) max_ld = a.ld;
+    }
+    if (resident) {
+        const dim3 grid((max_rows + 63) / 64, (n + 63) / 64, njobs);
+        static bool attr_set[2] = {false, false};
+        const int which = max_ld <= 512 ? 0 : 1;
+        const size_t smem = (size_t)64 * (which == 0 ? 64 * 8 + 16 : 64 * 16 + 16);
+        if (!attr_set[which]) {
+            const hipError_t e = which == 0
+                ? hipFuncSetAttribute((const void *)gemm_resident_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem)
+                : hipFuncSetAttribute((const void *)gemm_resident_kernel<16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "resident product kernel: %s", hipGetErrorString(e));
+            attr_set[which] = true;
+        }
+        if (which == 0) Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, gemm_resident_kernel<8>, grid, dim3(256), smem, jobs);
+        else Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, gemm_resident_kernel<16>, grid, dim3(256), smem, jobs);
+        return q8i_launch_check(ctx, "gemm");
+    }
     if (max_rows > 8192) {
         const dim3 grid((max_rows + 64 * GB_BIG_RT - 1) / (64 * GB_BIG_RT), (n + 16 * GB_BIG_NT - 1) / (16 * GB_BIG_NT), njobs);
         if (stats) Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, (gemm_block_kernel<GB_BIG_RT, GB_BIG_NT, true>), grid, dim3(256), 0, jobs);
