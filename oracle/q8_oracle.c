@@ -113,6 +113,46 @@ void q8o_gemm_narrow(const q8o_linear *L, const float *X, int n, int ldx, float 
                  tap_acc ? tap_acc + (size_t)j * L->rows : NULL);
 }
 
+void q8o_quantize_matrix_rows(const float *W, int rows, int cols, int ld_in,
+                              int8_t *Wq, int ld_out, float *row_scale)
+{
+    for (int i = 0; i < rows; ++i) {
+        q8o_quantize(W + (size_t)i * ld_in, cols, Wq + (size_t)i * ld_out, row_scale + i);
+        for (int k = cols; k < ld_out; ++k) Wq[(size_t)i * ld_out + k] = 0;
+    }
+}
+
+void q8o_dequantize_rows(const int32_t *acc, int rows, const float *row_scale, float s_x,
+                         const float *bias, float *y)
+{
+    for (int i = 0; i < rows; ++i) {
+        float c = row_scale[i] * s_x;
+        float f = (float)acc[i];
+        float p = f * c;
+        if (bias) p = p + bias[i];
+        y[i] = p;
+    }
+}
+
+void q8o_gemm_narrow_rows(const int8_t *Wq, int rows, int cols, int ld, const float *row_scale,
+                          const float *bias, const float *X, int n, int ldx, float *Y, int ldy,
+                          int8_t *tap_xq, float *tap_xscale, int32_t *tap_acc)
+{
+    int8_t *xq = (int8_t *)malloc((size_t)cols);
+    int32_t *acc = (int32_t *)malloc(sizeof(int32_t) * (size_t)rows);
+    for (int j = 0; j < n; ++j) {
+        float sx;
+        q8o_quantize(X + (size_t)j * ldx, cols, xq, &sx);
+        q8o_accumulate(Wq, rows, cols, ld, xq, acc);
+        q8o_dequantize_rows(acc, rows, row_scale, sx, bias, Y + (size_t)j * ldy);
+        if (tap_xq) memcpy(tap_xq + (size_t)j * cols, xq, (size_t)cols);
+        if (tap_xscale) tap_xscale[j] = sx;
+        if (tap_acc) memcpy(tap_acc + (size_t)j * rows, acc, sizeof(int32_t) * (size_t)rows);
+    }
+    free(xq);
+    free(acc);
+}
+
 void q8o_gemv_fp32(const q8o_linear *L, const float *x, float *y)
 {
     for (int i = 0; i < L->rows; ++i) {

@@ -93,6 +93,24 @@ void q8o_gemv(const q8o_linear *L, const float *x, float *y,
 void q8o_gemm_narrow(const q8o_linear *L, const float *X, int n, int ldx, float *Y, int ldy,
                      int8_t *tap_xq, float *tap_xscale, int32_t *tap_acc);
 
+/* Variant of O1-O3 with one weight scale per ROW (Section 3 does not state the granularity
+ * of the scale; the per-matrix reading is the default everywhere else).  Row i of W is
+ * quantized as a vector of its own: m_i = max_k |W[i,k]|, the rules of O1 with m_i, codes
+ * into Wq row i (pad bytes zero), scale into row_scale[i]. */
+void q8o_quantize_matrix_rows(const float *W, int rows, int cols, int ld_in,
+                              int8_t *Wq, int ld_out, float *row_scale);
+
+/* O3 with per-row weight scales: c_i = row_scale[i] * s_x (one fp32 multiply per row),
+ * y_i = (float)acc_i * c_i, then + bias_i as a separate add if bias != NULL. */
+void q8o_dequantize_rows(const int32_t *acc, int rows, const float *row_scale, float s_x,
+                         const float *bias, float *y);
+
+/* The narrow product with per-row weight scales: per vector j, O1 on X[j], O2, then
+ * q8o_dequantize_rows.  Taps as in q8o_gemm_narrow (NULL to skip). */
+void q8o_gemm_narrow_rows(const int8_t *Wq, int rows, int cols, int ld, const float *row_scale,
+                          const float *bias, const float *X, int n, int ldx, float *Y, int ldy,
+                          int8_t *tap_xq, float *tap_xscale, int32_t *tap_acc);
+
 /* The 32-bit engine's product: y_i = (float)(sum_k (double)W[i,k]*(double)x[k]), then + bias. */
 void q8o_gemv_fp32(const q8o_linear *L, const float *x, float *y);
 

@@ -153,6 +153,44 @@ class QLinear:
         return y
 
 
+class QLinearRows:
+    """A weight matrix quantized with one scale per row (the variant of Section 3's scheme)."""
+
+    def __init__(self, W, bias=None):
+        self.Wf = _f32(W)
+        self.rows, self.cols = self.Wf.shape
+        self.Wq = np.full((self.rows, pad16(self.cols)), 99, np.int8)
+        self.row_scale = np.empty(self.rows, np.float32)
+        lib().q8o_quantize_matrix_rows(_p(self.Wf), C.c_int(self.rows), C.c_int(self.cols), C.c_int(self.cols),
+                                       _p(self.Wq), C.c_int(self.Wq.shape[1]), _p(self.row_scale))
+        self.bias = None if bias is None else _f32(bias)
+
+    def gemm_narrow(self, X, taps=False):
+        X = _f32(X)
+        n = X.shape[0]
+        Y = np.empty((n, self.rows), np.float32)
+        xq = np.empty((n, self.cols), np.int8)
+        xs = np.empty(n, np.float32)
+        acc = np.empty((n, self.rows), np.int32)
+        lib().q8o_gemm_narrow_rows(_p(self.Wq), C.c_int(self.rows), C.c_int(self.cols), C.c_int(self.Wq.shape[1]),
+                                   _p(self.row_scale), _p(self.bias), _p(X), C.c_int(n), C.c_int(X.shape[1]),
+                                   _p(Y), C.c_int(self.rows), _p(xq), _p(xs), _p(acc))
+        return (Y, xq, xs, acc) if taps else Y
+
+    def gemv(self, x, taps=False):
+        r = self.gemm_narrow(_f32(x)[None, :], taps)
+        return tuple(a[0] for a in r) if taps else r[0]
+
+
+def dequantize_rows(acc, row_scale, s_x, bias=None):
+    acc = np.ascontiguousarray(acc, np.int32)
+    row_scale = _f32(row_scale)
+    bias = None if bias is None else _f32(bias)
+    y = np.empty(acc.shape[0], np.float32)
+    lib().q8o_dequantize_rows(_p(acc), C.c_int(acc.shape[0]), _p(row_scale), C.c_float(s_x), _p(bias), _p(y))
+    return y
+
+
 class QGru:
     def __init__(self, Wx, Wh, bx=None, bh=None):
         self.Wx = QLinear(Wx, bx)

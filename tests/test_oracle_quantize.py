@@ -141,3 +141,74 @@ def test_narrow_matrix_equals_column_by_column(oracle):
         y, q, s, a = L.gemv(X[j], taps=True)
         assert (Y[j] == y).all() and (xq[j] == q).all() and xs[j] == s and (acc[j] == a).all()
     assert xs[3] == 1.0 and (Y[3] == b).all()                        # the zero column: scale 1, result = bias
+
+
+# ---- the variant with one weight scale per row -------------------------------------------
+
+def test_row_scales_hand_case(oracle):
+    """Worked by hand: rows (1, -0.5, 0.25) and (0, 0, 0) and (-254, 127, 2): row maxima 1, 0, 254."""
+    W = np.array([[1.0, -0.5, 0.25], [0, 0, 0], [-254.0, 127.0, 2.0]], np.float32)
+    L = oracle.QLinearRows(W)
+    assert L.row_scale.tolist() == [np.float32(1.0) / np.float32(127.0), 1.0, 2.0]
+    assert L.Wq[:, :3].tolist() == [[127, -64, 32], [0, 0, 0], [-127, 64, 1]]      # 63.5 -> 64 and 31.75 -> 32
+    assert (L.Wq[:, 3:] == 0).all()
+    # x = (127, 0, -127)/127 quantizes to codes (127, 0, -127) with scale 1/127
+    x = np.array([1.0, 0.0, -1.0], np.float32)
+    y, xq, sx, acc = L.gemv(x, taps=True)
+    assert xq.tolist() == [127, 0, -127] and sx == np.float32(1.0) / np.float32(127.0)
+    assert acc.tolist() == [127 * 127 - 32 * 127, 0, -127 * 127 - 127]
+    c0 = np.float32(L.row_scale[0]) * sx
+    assert y[0] == np.float32(acc[0]) * c0 and y[1] == 0.0 and y[2] == np.float32(acc[2]) * (np.float32(2.0) * sx)
+
+
+def test_row_scales_commute_with_row_scaling(oracle):
+    """Scaling row i of W by a power of two scales y_i by exactly that factor and nothing else:
+    true for per-row scales, false for one scale per matrix."""
+    rng = np.random.default_rng(11)
+    W = (rng.standard_normal((24, 80)) * 0.1).astype(np.float32)
+    d = np.float32(2.0) ** rng.integers(-6, 7, size=24).astype(np.float32)
+    X = rng.standard_normal((3, 80)).astype(np.float32)
+    A, B = oracle.QLinearRows(W), oracle.QLinearRows(W * d[:, None])
+    assert (A.Wq == B.Wq).all() and (B.row_scale == A.row_scale * d).all()
+    assert (B.gemm_narrow(X) == A.gemm_narrow(X) * d[None, :]).all()
+    assert not (oracle.QLinear(W * d[:, None]).gemm_narrow(X) == oracle.QLinear(W).gemm_narrow(X) * d[None, :]).all()
+
+
+def test_row_scales_equal_matrix_scale_when_row_maxima_agree(oracle):
+    rng = np.random.default_rng(12)
+    W = (rng.standard_normal((10, 64)) * 0.05).astype(np.float32)
+    W[:, 7] = np.float32(0.75) * np.where(rng.random(10) < 0.5, -1, 1)      # every row's largest entry is +-0.75
+    b = rng.standard_normal(10).astype(np.float32)
+    X = rng.standard_normal((4, 64)).astype(np.float32)
+    R, M = oracle.QLinearRows(W, b), oracle.QLinear(W, b)
+    assert (R.row_scale == M.scale).all() and (R.Wq == M.Wq).all()
+    assert (R.gemm_narrow(X) == M.gemm_narrow(X)).all()
+
+
+@pytest.mark.parametrize("M,K", [(50, 512), (9, 1000)])
+def test_row_scales_bound_and_gain(oracle, M, K):
+    """Same closed-form bound as the per-matrix product with s_w replaced by the row's own scale;
+    on rows of very different size the per-row variant is the more accurate one."""
+    rng = np.random.default_rng(K + 1)
+    W = (rng.standard_normal((M, K)) * 0.05).astype(np.float32) * np.logspace(-2, 0, M, dtype=np.float32)[:, None]
+    x = rng.standard_normal(K).astype(np.float32)
+    R = oracle.QLinearRows(W)
+    y, xq, sx, acc = R.gemv(x, taps=True)
+    exact = W.astype(np.float64) @ x.astype(np.float64)
+    sw = R.row_scale.astype(np.float64)
+    bound = sw / 2 * np.abs(x).sum() + float(sx) / 2 * np.abs(W).sum(axis=1) + K * sw * float(sx) / 4
+    err = np.abs(y - exact)
+    assert (err <= bound * (1 + 1e-3) + 1e-7).all()
+    err_m = np.abs(oracle.QLinear(W).gemv(x) - exact)
+    small = slice(0, M // 3)                                                 # the rows a matrix-wide scale crushes
+    assert np.sqrt((err[small] ** 2).mean()) < 0.2 * np.sqrt((err_m[small] ** 2).mean())
+    # accumulators against a brute-force integer product
+    assert (acc == R.Wq[:, :K].astype(np.int64) @ xq.astype(np.int64)).all()
+
+
+def test_dequantize_rows_exact_small_case(oracle):
+    y = oracle.dequantize_rows(np.array([3, -8, 5], np.int32), np.array([0.5, 2.0, 0.0], np.float32), 0.25, None)
+    assert y.tolist() == [0.375, -4.0, 0.0]
+    y = oracle.dequantize_rows(np.array([3, -8, 5], np.int32), np.array([0.5, 2.0, 0.0], np.float32), 0.25,
+                               np.array([1, 2, 3], np.float32))
+    assert y.tolist() == [1.375, -2.0, 3.0]
