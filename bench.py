@@ -164,6 +164,34 @@ def gemv_bandwidth(torch, q, ctx, rng):
     return out
 
 
+def row_scale_variant(torch, q, ctx, rng):
+    """The variant of Section 3's scheme with one weight scale per row beside the per-matrix one:
+    duration of the streaming product, and the error of both against the fp64 product of the fp32
+    weights, on Gaussian weights and on weights whose rows differ in size by up to 100x."""
+    out = {}
+    for name, rows, cols, spread in (("3072x1024_gaussian", 3072, 1024, 0.0), ("50000x512_gaussian", 50000, 512, 0.0),
+                                     ("50000x512_row_sizes_1_to_100", 50000, 512, 2.0)):
+        W = (rng.standard_normal((rows, cols)) * 0.05).astype(np.float32)
+        W *= np.float32(10.0) ** (-spread * rng.random((rows, 1)).astype(np.float32))
+        x = rng.standard_normal(cols).astype(np.float32)
+        M = q.q8_quantize_matrix(ctx, W)
+        R, rs = q.q8_quantize_matrix_rows(ctx, W)
+        xd, y = ctx.f32(x[None, :]), ctx.empty(1, rows)
+        t_m = median_of(torch, lambda: q.q8_gemm_narrow(ctx, M, xd, None, y), inner=100)
+        t_r = median_of(torch, lambda: q.q8_gemm_narrow_rows(ctx, R, rs, xd, None, y), inner=100)
+        exact = W.astype(np.float64) @ x.astype(np.float64)
+        norm = np.abs(W.astype(np.float64)).max(axis=1) * np.sqrt((x.astype(np.float64) ** 2).sum())
+
+        def rms(Y):      # error of every row relative to the size of that row's entries
+            return float(np.sqrt((((Y.cpu().numpy()[0] - exact) / norm) ** 2).mean()))
+
+        out[name] = {"per_matrix_us": t_m[0], "per_row_us": t_r[0],
+                     "rms_error_per_matrix": rms(q.q8_gemm_narrow(ctx, M, xd)),
+                     "rms_error_per_row": rms(q.q8_gemm_narrow_rows(ctx, R, rs, xd)),
+                     "error_unit": "row maximum x |x|_2"}
+    return out
+
+
 def kernel_times(torch, q, ctx, step, steps):
     """Average duration of every kernel class inside the running decoder loop, from event
     pairs attached to the dispatches (one class per pass over `steps` steps)."""
@@ -499,6 +527,7 @@ def main():
                                         "25.6MB_cold": read_ceiling(torch, q, ctx, 25600000, cold=True),
                                         "3.1MB_warm": read_ceiling(torch, q, ctx, 3145728, cold=False),
                                         "3.1MB_cold": read_ceiling(torch, q, ctx, 3145728, cold=True)}
+        extra["row_scale_variant"] = row_scale_variant(torch, q, ctx, rng)
         extra["mfma_products"] = mfma_products(torch, q, ctx, m, rng)
         extra["paper_shapes_620_1000_63644"] = paper_shapes(torch, q, ctx, rng, max(args.steps // 4, 100))
         extra["batched_decoding"] = batched_decoding(torch, q, m, rng, max(args.steps // 10, 50))

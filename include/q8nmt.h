@@ -141,6 +141,20 @@ q8_status q8_gemv(q8_ctx *ctx, const q8_mat *W, const float *x, const float *bia
 q8_status q8_gemm_narrow(q8_ctx *ctx, const q8_mat *W, const float *X, int n, int ldx,
                          const float *bias, float *Y, int ldy, const q8_taps *taps);
 
+/* Variant of Section 3's scheme with one weight scale per ROW (the section does not state the
+ * granularity of the scale; every other entry point takes one scale per matrix).
+ * q8_quantize_matrix_rows: row i of W [rows x cols] (ld_in floats per row) is quantized on its
+ * own maximum: codes into Wq_out row i (ld_out bytes per row, pad bytes zero), scale into
+ * row_scale_out[i] (DEVICE pointer, rows floats).  Enqueued on the stream, nothing returns to
+ * the host.  Same shape and alignment rules as q8_quantize_matrix.
+ * q8_gemm_narrow_rows: Y[j][i] = (float)(Wq_i . quantize(X_j)) * (row_scale[i] * s_xj) + bias[i];
+ * W->scale is ignored, row_scale is a device pointer to W->rows floats; everything else as
+ * q8_gemm_narrow (n = 1 is the matrix x vector product). */
+q8_status q8_quantize_matrix_rows(q8_ctx *ctx, const float *W, int rows, int cols, int ld_in,
+                                  int8_t *Wq_out, int ld_out, float *row_scale_out);
+q8_status q8_gemm_narrow_rows(q8_ctx *ctx, const q8_mat *W, const float *row_scale, const float *X, int n,
+                              int ldx, const float *bias, float *Y, int ldy, const q8_taps *taps);
+
 /* GRU cell of Eq. 1 / Eq. 3-4 for n vectors: gx = Wx q(x) + bx, gh = Wh q(h) + bh,
  * r = sigmoid(gx_r + gh_r), z = sigmoid(gx_z + gh_z), n = tanh(gx_n + r * gh_n),
  * h' = (1 - z) * n + z * h (h in fp32).  x [n x I], h_prev [n x H], h_out [n x H]

@@ -234,10 +234,40 @@ q8_status q8_pack_tiles(q8_ctx *ctx, const q8_mat *W, int8_t *tiles_out)
     return q8i_pack_tiles(ctx, W, tiles_out);
 }
 
+static q8_status gemm_narrow_any(q8_ctx *ctx, const q8_mat *W, const float *row_scale, const float *X, int n, int ldx,
+                                 const float *bias, float *Y, int ldy, const q8_taps *taps);
+
 q8_status q8_gemm_narrow(q8_ctx *ctx, const q8_mat *W, const float *X, int n, int ldx, const float *bias, float *Y,
                          int ldy, const q8_taps *taps)
 {
     if (!ctx) return Q8_ERR_NULL;
+    return gemm_narrow_any(ctx, W, nullptr, X, n, ldx, bias, Y, ldy, taps);
+}
+
+q8_status q8_gemm_narrow_rows(q8_ctx *ctx, const q8_mat *W, const float *row_scale, const float *X, int n, int ldx,
+                              const float *bias, float *Y, int ldy, const q8_taps *taps)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!row_scale) return q8_fail(ctx, Q8_ERR_NULL, "row_scale: NULL");
+    if ((uintptr_t)row_scale % 4 != 0) return q8_fail(ctx, Q8_ERR_ALIGN, "row_scale: not aligned to 4 bytes");
+    return gemm_narrow_any(ctx, W, row_scale, X, n, ldx, bias, Y, ldy, taps);
+}
+
+q8_status q8_quantize_matrix_rows(q8_ctx *ctx, const float *W, int rows, int cols, int ld_in, int8_t *Wq_out, int ld_out,
+                                  float *row_scale_out)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!W || !Wq_out || !row_scale_out) return q8_fail(ctx, Q8_ERR_NULL, "q8_quantize_matrix_rows: NULL argument");
+    if (rows <= 0 || cols <= 0 || ld_in < cols || ld_out < cols || ld_out > kMaxLd)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "q8_quantize_matrix_rows: bad shape %d x %d (ld_in %d, ld_out %d)", rows, cols, ld_in, ld_out);
+    if (!aligned16(Wq_out) || ld_out % 16 != 0)
+        return q8_fail(ctx, Q8_ERR_ALIGN, "q8_quantize_matrix_rows: output needs a 16-byte aligned base and ld_out %% 16 == 0");
+    return q8i_quantize_matrix_rows(ctx, W, rows, cols, ld_in, Wq_out, ld_out, row_scale_out);
+}
+
+static q8_status gemm_narrow_any(q8_ctx *ctx, const q8_mat *W, const float *row_scale, const float *X, int n, int ldx,
+                                 const float *bias, float *Y, int ldy, const q8_taps *taps)
+{
     TRY(check_mat(ctx, W, "W"));
     if (n <= 0 || n > kMaxMfmaN) return q8_fail(ctx, Q8_ERR_SHAPE, "n = %d outside [1, %d]", n, kMaxMfmaN);
     TRY(check_vecs(ctx, X, n == 1 ? W->cols + ((4 - W->cols % 4) % 4) : ldx, W->cols, "X"));
@@ -245,14 +275,14 @@ q8_status q8_gemm_narrow(q8_ctx *ctx, const q8_mat *W, const float *X, int n, in
     if (n > 1 && ldy < W->rows) return q8_fail(ctx, Q8_ERR_SHAPE, "ldy %d < rows %d", ldy, W->rows);
     if (n <= kMaxNarrow) {
         if ((size_t)n * W->ld > 65536) return q8_fail(ctx, Q8_ERR_SHAPE, "n * ld = %zu exceeds 65536", (size_t)n * W->ld);
-        q8i_gemv_desc d = {W, X, ldx, bias, Y, ldy, taps};
+        q8i_gemv_desc d = {W, X, ldx, bias, Y, ldy, taps, row_scale};
         return q8i_gemv_jobs(ctx, &d, 1, n);
     }
     Carver cv(ctx);
     int8_t *xq = cv.take<int8_t>((size_t)n * W->ld);
     float *xs = cv.take<float>(n);
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "q8_gemm_narrow: workspace too small");
-    return q8i_gemm_mfma(ctx, W, X, n, ldx, bias, Y, ldy, taps, xq, xs);
+    return q8i_gemm_mfma(ctx, W, X, n, ldx, bias, Y, ldy, taps, xq, xs, row_scale);
 }
 
 q8_status q8_gemv(q8_ctx *ctx, const q8_mat *W, const float *x, const float *bias, float *y, const q8_taps *taps)

@@ -17,6 +17,7 @@ struct GemmArgs {
     int rows, ld, n, ldy, ntiles;
     int tiled;             // Y as [ntiles][n][16]: every 16 x 16 result tile is one contiguous KiB
     float w_scale;
+    const float *row_scale; // NULL, or one weight scale per row in place of w_scale
 };
 #define GEMM_MAX_JOBS 3
 struct GemmJobs {          // products of one launch (blockIdx.z), all over the same number of vectors
@@ -160,11 +161,12 @@ __global__ __launch_bounds__(256) void gemm_block_kernel(GemmJobs jobs)
     // are issued together instead of one tile after the other.
     const bool vec_ok = ((a.ldy & 3) == 0) && (((uintptr_t)a.Y & 15) == 0);
     const bool bias_vec = (((uintptr_t)a.bias) & 15) == 0;
-    float cs[NT];
+    float cs[NT], xs[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
         const int col = c0 + 16 * t + i;
-        cs[t] = col < n ? a.w_scale * a.xscale[col] : 0.0f;
+        xs[t] = col < n ? a.xscale[col] : 0.0f;
+        cs[t] = a.w_scale * xs[t];
     }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
@@ -181,6 +183,11 @@ __global__ __launch_bounds__(256) void gemm_block_kernel(GemmJobs jobs)
                 if (row0 + 3 < rows) b.w = a.bias[row0 + 3];
             }
         }
+        float rsv[4] = {0.f, 0.f, 0.f, 0.f};
+        if (a.row_scale) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) rsv[r] = a.row_scale[min(row0 + r, rows - 1)];
+        }
         float y[NT][4], m[NT];
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
@@ -191,7 +198,7 @@ __global__ __launch_bounds__(256) void gemm_block_kernel(GemmJobs jobs)
             for (int r = 0; r < 4; ++r) {
                 y[t][r] = -INFINITY;
                 if (col_ok && row0 + r < rows) {
-                    y[t][r] = (float)acc[rt][t][r] * cs[t];
+                    y[t][r] = (float)acc[rt][t][r] * (a.row_scale ? rsv[r] * xs[t] : cs[t]);
                     if (a.bias) y[t][r] = y[t][r] + (r == 0 ? b.x : r == 1 ? b.y : r == 2 ? b.z : b.w);
                     if (a.tap_acc) a.tap_acc[(size_t)col * rows + row0 + r] = acc[rt][t][r];
                 }
@@ -292,10 +299,14 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(GemmJobs jobs)
         cs[t] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(c0 + 16 * t + i < n ? (unsigned)(c0 + 16 * t + i) * 4u : Q8_OOB), 0, 0));
     const int row0 = r0 + 4 * g;
     const __amdgpu_buffer_rsrc_t rb = q8_rsrc(a.bias, a.bias ? (size_t)rows * sizeof(float) : 0);
-    float bias[4];
+    const __amdgpu_buffer_rsrc_t rr = q8_rsrc(a.row_scale, a.row_scale ? (size_t)rows * sizeof(float) : 0);
+    float bias[4], rsv[4];
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-        bias[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, (int)(row0 + r < rows ? (unsigned)(row0 + r) * 4u : Q8_OOB), 0, 0));
+    for (int r = 0; r < 4; ++r) {
+        const int off = (int)(row0 + r < rows ? (unsigned)(row0 + r) * 4u : Q8_OOB);
+        bias[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, off, 0, 0));
+        rsv[r] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rr, off, 0, 0));
+    }
     __builtin_amdgcn_sched_barrier(0);
 
 #pragma unroll
@@ -324,7 +335,7 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(GemmJobs jobs)
         float y[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            y[r] = (float)acc[t][r] * c;
+            y[r] = (float)acc[t][r] * (a.row_scale ? rsv[r] * cs[t] : c);
             if (a.bias) y[r] = y[r] + bias[r];
         }
         if (vec_ok && row0 + 3 < rows) {
@@ -578,6 +589,7 @@ q8_status q8i_gemm_jobs(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n)
         a.rows = q.W->rows; a.ld = q.W->ld; a.n = n; a.ldy = q.ldy; a.ntiles = (q.W->rows + 15) / 16;
         a.tiled = q.tiled;
         a.w_scale = q.W->scale;
+        a.row_scale = q.row_scale;
         if (a.rows > max_rows) max_rows = a.rows;
     }
     const bool stats = d[0].part_max != nullptr;
@@ -618,11 +630,11 @@ q8_status q8i_gemm_jobs(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n)
 }
 
 q8_status q8i_gemm_mfma(q8_ctx *ctx, const q8_mat *W, const float *X, int n, int ldx, const float *bias, float *Y,
-                        int ldy, const q8_taps *taps, int8_t *xq, float *xscale)
+                        int ldy, const q8_taps *taps, int8_t *xq, float *xscale, const float *row_scale)
 {
     q8i_quant_job qj = {X, W->cols, ldx, W->ld, xq, xscale, taps};
     q8_status st = q8i_quantize_jobs(ctx, &qj, 1, n);
     if (st) return st;
-    q8i_gemm_job gj = {W, xq, xscale, bias, Y, ldy, taps ? taps->acc : nullptr, nullptr, nullptr, 0};
+    q8i_gemm_job gj = {W, xq, xscale, bias, Y, ldy, taps ? taps->acc : nullptr, nullptr, nullptr, 0, row_scale};
     return q8i_gemm_jobs(ctx, &gj, 1, n);
 }

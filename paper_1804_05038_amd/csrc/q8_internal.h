@@ -71,6 +71,7 @@ struct q8i_gemv_desc {
     float *Y;
     int ldy;
     const q8_taps *taps;
+    const float *row_scale;     // NULL: W->scale; else one weight scale per row (device)
 };
 
 struct q8i_gru_desc {
@@ -100,7 +101,9 @@ q8_status q8i_quantize_matrix(q8_ctx *ctx, const float *W, int rows, int cols, i
                               float *scale_host);
 q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n);
 q8_status q8i_gemm_mfma(q8_ctx *ctx, const q8_mat *W, const float *X, int n, int ldx, const float *bias, float *Y,
-                        int ldy, const q8_taps *taps, int8_t *xq, float *xscale);
+                        int ldy, const q8_taps *taps, int8_t *xq, float *xscale, const float *row_scale = nullptr);
+q8_status q8i_quantize_matrix_rows(q8_ctx *ctx, const float *W, int rows, int cols, int ld_in, int8_t *Wq, int ld_out,
+                                   float *row_scale);
 struct q8i_quant_job {          // quantization of n vectors X [n x ldx] (K floats each) into xq [n x ld], xscale [n]
     const float *X;
     int K, ldx, ld;
@@ -119,6 +122,7 @@ struct q8i_gemm_job {           // Y [n x ldy] = dequantize(W . xq) + bias on th
     float *part_max;            // vocabulary layer: per-tile softmax statistics [n x ceil(rows / 16)]
     double *part_sum;
     int tiled;                  // 1: Y is written as [ceil(rows / 16)][n][16] (needs that many floats)
+    const float *row_scale;     // NULL: W->scale; else one weight scale per row (plain output without statistics only)
 };
 q8_status q8i_quantize_jobs(q8_ctx *ctx, const q8i_quant_job *d, int njobs, int n);   // njobs <= 3
 q8_status q8i_gemm_jobs(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n);        // njobs <= 3

@@ -46,6 +46,27 @@ __global__ __launch_bounds__(256) void quantize_matrix_kernel(const float *__res
     }
 }
 
+// One scale per row: a wave per row finds the row's maximum and writes its codes.
+__global__ __launch_bounds__(256) void quantize_matrix_rows_kernel(const float *__restrict__ W, int rows, int cols, int ld_in,
+                                                                   int8_t *__restrict__ Wq, int ld_out, float *__restrict__ row_scale)
+{
+    const int lane = threadIdx.x & 63;
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (r >= rows) return;                               // wave-uniform
+    const float *w = W + (size_t)r * ld_in;
+    float m = 0.0f;
+    for (int k = lane; k < cols; k += 64) m = fmaxf(m, fabsf(w[k]));
+    m = wave_max_f(m);
+    float scale, inv;
+    q8_scale_of(m, scale, inv);
+    if (lane == 0) row_scale[r] = scale;
+    for (int k = 4 * lane; k < ld_out; k += 256) {
+        float a = k < cols ? w[k] : 0.0f, b = k + 1 < cols ? w[k + 1] : 0.0f;
+        float c = k + 2 < cols ? w[k + 2] : 0.0f, d = k + 3 < cols ? w[k + 3] : 0.0f;
+        *(int *)(Wq + (size_t)r * ld_out + k) = q8_pack4(a, b, c, d, inv);
+    }
+}
+
 __global__ void fill_u32_kernel(unsigned *p, int n, unsigned v)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -64,6 +85,7 @@ struct GemvJob {
     int32_t *tap_acc;
     int rows, cols, ld, ldx, ldy, lpr, block0, rpb;
     float w_scale;
+    const float *row_scale;     // NULL, or one weight scale per row in place of w_scale
 };
 #define Q8_MAX_JOBS 3
 struct GemvJobs {
@@ -111,8 +133,8 @@ __global__ __launch_bounds__(256) void gemv_jobs_kernel(GemvJobs jobs)
     constexpr int U = 4;
     const int r_begin = blk * J.rpb;
     const int r_end = min(J.rows, r_begin + J.rpb);
-    float cj = 0.0f;                          // lane lir < N owns vector lir in the epilogue
-    if (lir < N) cj = J.w_scale * s_scale[lir];
+    float cj = 0.0f, sxj = 0.0f;              // lane lir < N owns vector lir in the epilogue
+    if (lir < N) { sxj = s_scale[lir]; cj = J.w_scale * sxj; }
 
     for (int r = r_begin + wave * rpp * U; r < r_end; r += 4 * rpp * U) {
         const int8_t *wrow[U];
@@ -130,7 +152,7 @@ __global__ __launch_bounds__(256) void gemv_jobs_kernel(GemvJobs jobs)
 #pragma unroll
             for (int j = 0; j < N; ++j) a = (lir == j) ? acc[u][j] : a;
             if (lir < N && row[u] < r_end) {
-                float y = (float)a * cj;
+                float y = (float)a * (J.row_scale ? J.row_scale[row[u]] * sxj : cj);
                 if (J.bias) y = y + J.bias[row[u]];
                 J.Y[(size_t)lir * J.ldy + row[u]] = y;
                 if (J.tap_acc) J.tap_acc[(size_t)lir * J.rows + row[u]] = a;
@@ -141,7 +163,8 @@ __global__ __launch_bounds__(256) void gemv_jobs_kernel(GemvJobs jobs)
 
 // Rows of at most 1024 * CH bytes and cols % 4 == 0: activations and the first two rows of
 // every wave are requested before anything is waited for; the row loop is double-buffered.
-template <int N, int CH>
+// ROWS: every job has one weight scale per row (requested with the row's bias).
+template <int N, int CH, bool ROWS>
 __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
 {
     extern __shared__ __align__(16) int8_t smem[];
@@ -162,13 +185,18 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
     v4i w[U][CH];
     const __amdgpu_buffer_rsrc_t rw = q8_rsrc(J.W, (size_t)J.rows * ld);
     const __amdgpu_buffer_rsrc_t rb = q8_rsrc(J.bias, J.bias ? (size_t)J.rows * sizeof(float) : 0);
-    // biases of the rows in flight, requested with them (lane j < N finishes vector j; absent: zero)
-    auto bias_load = [&](float (&b)[U], int r0) {
+    const __amdgpu_buffer_rsrc_t rs = q8_rsrc(J.row_scale, ROWS ? (size_t)J.rows * sizeof(float) : 0);
+    // biases (and per-row weight scales) of the rows in flight, requested with them (lane j < N
+    // finishes vector j; absent: zero, read from nowhere); b[U + u] is the scale of row u
+    auto bias_load = [&](float (&b)[2 * U], int r0) {
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            b[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, (int)((lane < N && r0 + u < r_end) ? (unsigned)(r0 + u) * 4u : Q8_OOB), 0, 0));
+        for (int u = 0; u < U; ++u) {
+            const int off = (int)((lane < N && r0 + u < r_end) ? (unsigned)(r0 + u) * 4u : Q8_OOB);
+            b[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, off, 0, 0));
+            b[U + u] = ROWS ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0)) : 0.0f;
+        }
     };
-    float bw[U];
+    float bw[2 * U];
     {
         int row[U];
 #pragma unroll
@@ -178,8 +206,8 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
     }
     x_finish<N, CH>(xr, N, ld, smem, s_scale, s_red);
     if (blk == 0) write_x_taps<N>(J, smem, s_scale);
-    float cj = 0.0f;
-    if (lane < N) cj = J.w_scale * s_scale[lane];
+    float cj = 0.0f, sxj = 0.0f;
+    if (lane < N) { sxj = s_scale[lane]; cj = J.w_scale * sxj; }
 
     while (r < r_end) {
         const int rn = r + 4 * U;
@@ -190,7 +218,7 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
             for (int u = 0; u < U; ++u) row[u] = rn + u < r_end ? rn + u : -1;
             rows_load<U, CH>(wn, rw, row, ld, lane);
         }
-        float bn[U];
+        float bn[2 * U];
         bias_load(bn, rn);
         int part[U][N], mine[U];
         rows_dot_part<N, U, CH>(w, ld, lane, smem, part);
@@ -199,7 +227,7 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
         for (int u = 0; u < U; ++u) {
             const int a = mine[u];
             if (lane < N && r + u < r_end) {
-                float y = (float)a * cj;
+                float y = (float)a * (ROWS ? bw[U + u] * sxj : cj);
                 if (J.bias) y = y + bw[u];
                 J.Y[(size_t)lane * J.ldy + r + u] = y;
                 if (J.tap_acc) J.tap_acc[(size_t)lane * J.rows + r + u] = a;
@@ -210,7 +238,7 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
 #pragma unroll
             for (int c = 0; c < CH; ++c) w[u][c] = wn[u][c];
 #pragma unroll
-        for (int u = 0; u < U; ++u) bw[u] = bn[u];
+        for (int u = 0; u < 2 * U; ++u) bw[u] = bn[u];
         r = rn;
     }
 }
@@ -285,6 +313,14 @@ q8_status q8i_quantize_matrix(q8_ctx *ctx, const float *W, int rows, int cols, i
     return Q8_OK;
 }
 
+q8_status q8i_quantize_matrix_rows(q8_ctx *ctx, const float *W, int rows, int cols, int ld_in, int8_t *Wq, int ld_out,
+                                   float *row_scale)
+{
+    hipLaunchKernelGGL(quantize_matrix_rows_kernel, dim3((rows + 3) / 4), dim3(256), 0, ctx->stream, W, rows, cols, ld_in,
+                       Wq, ld_out, row_scale);
+    return q8i_launch_check(ctx, "q8_quantize_matrix_rows");
+}
+
 q8_status q8i_fill_u32(q8_ctx *ctx, void *p, int n, unsigned v)
 {
     hipLaunchKernelGGL(fill_u32_kernel, dim3((n + 255) / 256), dim3(256), 0, ctx->stream, (unsigned *)p, n, v);
@@ -292,11 +328,14 @@ q8_status q8i_fill_u32(q8_ctx *ctx, void *p, int n, unsigned v)
 }
 
 template <int N>
-static void launch_gemv_n(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t smem, int ch)
+static void launch_gemv_n(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t smem, int ch, bool rows)
 {
-    if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 1>), dim3(blocks), dim3(256), smem, jobs);
-    else if (ch == 2) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 2>), dim3(blocks), dim3(256), smem, jobs);
-    else if (ch == 4) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 4>), dim3(blocks), dim3(256), smem, jobs);
+    if (ch == 1 && !rows) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 1, false>), dim3(blocks), dim3(256), smem, jobs);
+    else if (ch == 2 && !rows) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 2, false>), dim3(blocks), dim3(256), smem, jobs);
+    else if (ch == 4 && !rows) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 4, false>), dim3(blocks), dim3(256), smem, jobs);
+    else if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 1, true>), dim3(blocks), dim3(256), smem, jobs);
+    else if (ch == 2) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 2, true>), dim3(blocks), dim3(256), smem, jobs);
+    else if (ch == 4) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 4, true>), dim3(blocks), dim3(256), smem, jobs);
     else Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, gemv_jobs_kernel<N>, dim3(blocks), dim3(256), smem, jobs);
 }
 
@@ -304,20 +343,23 @@ q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
 {
     GemvJobs jobs;
     jobs.njobs = njobs;
-    int max_ld = 0;
+    int max_ld = 0, with_rows = 0;
     bool fast = true;
     for (int t = 0; t < njobs; ++t) {
         GemvJob &J = jobs.j[t];
+        with_rows += d[t].row_scale != nullptr;
         J.W = d[t].W->data; J.X = d[t].X; J.bias = d[t].bias; J.Y = d[t].Y;
         J.tap_xq = d[t].taps ? d[t].taps->xq : nullptr;
         J.tap_xscale = d[t].taps ? d[t].taps->xscale : nullptr;
         J.tap_acc = d[t].taps ? d[t].taps->acc : nullptr;
         J.rows = d[t].W->rows; J.cols = d[t].W->cols; J.ld = d[t].W->ld;
-        J.ldx = d[t].ldx; J.ldy = d[t].ldy; J.w_scale = d[t].W->scale;
+        J.ldx = d[t].ldx; J.ldy = d[t].ldy; J.w_scale = d[t].W->scale; J.row_scale = d[t].row_scale;
         if (J.ld > max_ld) max_ld = J.ld;
         if (J.cols % 4 != 0) fast = false;
         if ((size_t)J.rows * J.ld >= (1u << 31)) fast = false;       // the fast kernel addresses the matrix with 32-bit offsets
     }
+    if (with_rows != 0 && with_rows != njobs) fast = false;         // mixed launches run on the general kernel
+    const bool rows = with_rows != 0;
     const int ch = fast ? q8_fast_ch(max_ld) : 0;
     int blocks = 0;
     for (int t = 0; t < njobs; ++t) {
@@ -333,14 +375,14 @@ q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
     }
     const size_t smem = (size_t)n * max_ld;
     switch (n) {
-    case 1: launch_gemv_n<1>(ctx, jobs, blocks, smem, ch); break;
-    case 2: launch_gemv_n<2>(ctx, jobs, blocks, smem, ch); break;
-    case 3: launch_gemv_n<3>(ctx, jobs, blocks, smem, ch); break;
-    case 4: launch_gemv_n<4>(ctx, jobs, blocks, smem, ch); break;
-    case 5: launch_gemv_n<5>(ctx, jobs, blocks, smem, ch); break;
-    case 6: launch_gemv_n<6>(ctx, jobs, blocks, smem, ch); break;
-    case 7: launch_gemv_n<7>(ctx, jobs, blocks, smem, ch); break;
-    default: launch_gemv_n<8>(ctx, jobs, blocks, smem, ch); break;
+    case 1: launch_gemv_n<1>(ctx, jobs, blocks, smem, ch, rows); break;
+    case 2: launch_gemv_n<2>(ctx, jobs, blocks, smem, ch, rows); break;
+    case 3: launch_gemv_n<3>(ctx, jobs, blocks, smem, ch, rows); break;
+    case 4: launch_gemv_n<4>(ctx, jobs, blocks, smem, ch, rows); break;
+    case 5: launch_gemv_n<5>(ctx, jobs, blocks, smem, ch, rows); break;
+    case 6: launch_gemv_n<6>(ctx, jobs, blocks, smem, ch, rows); break;
+    case 7: launch_gemv_n<7>(ctx, jobs, blocks, smem, ch, rows); break;
+    default: launch_gemv_n<8>(ctx, jobs, blocks, smem, ch, rows); break;
     }
     return q8i_launch_check(ctx, "gemv");
 }

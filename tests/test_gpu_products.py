@@ -132,3 +132,66 @@ def test_argument_errors_are_reported_not_launched(q, ctx):
     with pytest.raises(q.Q8Error) as e:
         q.q8_gemm_narrow(ctx, W, ctx.f32(np.ones((2000, 16), np.float32)))
     assert e.value.code == 2
+
+
+# ---- the variant with one weight scale per row -------------------------------------------
+
+def _rows_case(rng, rows, cols):
+    # rows of very different size, one zero row, one tiny row: per-row scales differ by orders of magnitude
+    W = _w(rng, rows, cols) * np.logspace(-3, 0, rows, dtype=np.float32)[:, None]
+    W[rows // 2] = 0.0
+    if rows > 4:
+        W[3] = 1e-36
+    return W
+
+
+@pytest.mark.parametrize("rows,cols", [(768, 256), (3072, 1024), (33, 620), (7, 5), (2500, 1000), (50000, 512)])
+def test_quantize_matrix_rows_bit_exact(q, ctx, oracle, rows, cols):
+    rng = np.random.default_rng(rows * 3 + cols)
+    W = _rows_case(rng, rows, cols)
+    M, rs = q.q8_quantize_matrix_rows(ctx, W)
+    R = oracle.QLinearRows(W)
+    assert_same(rs, R.row_scale, "row scales")
+    assert_same(M.data, R.Wq, "Wq")
+
+
+@pytest.mark.parametrize("rows,cols", [(3072, 512), (1024, 2048), (1000, 620), (50, 16), (37, 3001), (50000, 512)])
+@pytest.mark.parametrize("n", [1, 5, 8])
+def test_gemm_narrow_rows_streaming(q, ctx, oracle, rows, cols, n):
+    if cols % 4 and n > 1:
+        pytest.skip("several vectors need a leading dimension that is a multiple of 4")
+    rng = np.random.default_rng(rows + cols + n + 1)
+    W = _rows_case(rng, rows, cols)
+    b = (rng.standard_normal(rows) * 0.01).astype(np.float32)
+    X = rng.standard_normal((n, cols)).astype(np.float32) * rng.uniform(0.1, 10, (n, 1)).astype(np.float32)
+    R = oracle.QLinearRows(W, b)
+    M, rs = q.q8_quantize_matrix_rows(ctx, W)
+    Y, taps = q.q8_gemm_narrow_rows(ctx, M, rs, ctx.f32(X), ctx.f32(b), taps=True)
+    Y_ref, xq, xs, acc = R.gemm_narrow(X, taps=True)
+    assert_same(taps["xq"], xq, "xq"); assert_same(taps["xscale"], xs, "xscale")
+    assert_same(taps["acc"], acc, "acc"); assert_same(Y, Y_ref, "Y")
+    assert_same(q.q8_gemm_narrow_rows(ctx, M, rs, ctx.f32(X)), oracle.QLinearRows(W).gemm_narrow(X), "Y, no taps, no bias")
+
+
+@pytest.mark.parametrize("rows,cols,n", [(3072, 512, 50), (1024, 2048, 30), (1000, 620, 13), (3072, 1024, 320),
+                                         (130, 272, 129), (9000, 512, 130)])
+def test_gemm_narrow_rows_matrix_cores(q, ctx, oracle, rows, cols, n):
+    rng = np.random.default_rng(rows + cols + n + 2)
+    W = _rows_case(rng, rows, cols)
+    b = (rng.standard_normal(rows) * 0.01).astype(np.float32)
+    X = rng.standard_normal((n, cols)).astype(np.float32) * rng.uniform(0.1, 10, (n, 1)).astype(np.float32)
+    X[3] = 0
+    R = oracle.QLinearRows(W, b)
+    M, rs = q.q8_quantize_matrix_rows(ctx, W)
+    Y, taps = q.q8_gemm_narrow_rows(ctx, M, rs, ctx.f32(X), ctx.f32(b), taps=True)
+    Y_ref, xq, xs, acc = R.gemm_narrow(X, taps=True)
+    assert_same(taps["acc"], acc, "acc"); assert_same(Y, Y_ref, "Y")
+    assert_same(q.q8_gemm_narrow_rows(ctx, M, rs, ctx.f32(X), ctx.f32(b)), Y_ref, "Y, no taps")
+    assert_same(q.q8_gemm_narrow_rows(ctx, M, rs, ctx.f32(X)), oracle.QLinearRows(W).gemm_narrow(X), "Y, no taps, no bias")
+
+
+def test_rows_variant_argument_errors(q, ctx):
+    M, rs = q.q8_quantize_matrix_rows(ctx, np.ones((4, 16), np.float32))
+    with pytest.raises(q.Q8Error) as e:
+        q.q8_gemm_narrow_rows(ctx, M, None, ctx.f32(np.ones((1, 16), np.float32)))
+    assert e.value.code == 1
