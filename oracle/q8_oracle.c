@@ -273,6 +273,44 @@ void q8o_attention(const float *P, const float *enc_h, int l, int A, int C,
     free(w);
 }
 
+void q8o_attention_q8(const float *P, int l, int A, const float *a, const int8_t *vq, float s_v,
+                      const int8_t *hTq, int C, int ldq, float s_h,
+                      float *e_out, float *alpha, float *ctx)
+{
+    float *e = (float *)malloc(sizeof(float) * (size_t)l);
+    double *w = (double *)malloc(sizeof(double) * (size_t)l);
+    float *T = (float *)malloc(sizeof(float) * (size_t)A);
+    int8_t *Tq = (int8_t *)malloc((size_t)A);
+    int8_t *aq = (int8_t *)malloc((size_t)l);
+    int32_t *acc = (int32_t *)malloc(sizeof(int32_t) * (size_t)C);
+    for (int i = 0; i < l; ++i) {
+        for (int j = 0; j < A; ++j) {
+            float pre = P[(size_t)i * A + j] + a[j];
+            T[j] = tanh_f(pre);
+        }
+        float sT;
+        int32_t dot;
+        q8o_quantize(T, A, Tq, &sT);
+        q8o_accumulate(vq, 1, A, A, Tq, &dot);
+        q8o_dequantize(&dot, 1, s_v, sT, NULL, &e[i]);
+    }
+    float mx = e[0];
+    for (int i = 1; i < l; ++i)
+        if (e[i] > mx) mx = e[i];
+    double Z = 0.0;
+    for (int i = 0; i < l; ++i) {
+        w[i] = exp((double)e[i] - (double)mx);
+        Z += w[i];
+    }
+    for (int i = 0; i < l; ++i) alpha[i] = (float)(w[i] / Z);
+    float sa;
+    q8o_quantize(alpha, l, aq, &sa);
+    q8o_accumulate(hTq, C, l, ldq, aq, acc);
+    q8o_dequantize(acc, C, s_h, sa, NULL, ctx);
+    if (e_out) memcpy(e_out, e, sizeof(float) * (size_t)l);
+    free(e); free(w); free(T); free(Tq); free(aq); free(acc);
+}
+
 void q8o_cgru_step(const q8o_model *m, const float *P, const float *enc_h, int l,
                    const float *y_emb, const float *s_prev, int use_q8,
                    float *s_mid, float *alpha, float *ctx, float *s_out)

@@ -144,6 +144,21 @@ void q8o_attention_precompute(const q8o_model *m, const float *enc_h, int l, int
 void q8o_attention(const float *P, const float *enc_h, int l, int A, int C,
                    const float *a, const float *v, float *e_out, float *alpha, float *ctx);
 
+/* Variant of the attention core in which the two products of Eq. 5-6 that involve no trained
+ * matrix also go through O1-O3 (the other reading of "the matrix products are 8-bit"; the
+ * default keeps them in float).
+ *   energies: T_i = tanh(P_i + a) (each element rounded to float) is the activation vector of
+ *     position i, (Tq_i, s_Ti) = O1(T_i); v is a 1 x A weight matrix (vq, s_v), quantized once
+ *     by O1's matrix rule; e_i = (float)(vq . Tq_i) * (s_v * s_Ti)        [O2, O3, no bias]
+ *   alpha = softmax(e) exactly as in q8o_attention
+ *   context: the C x l matrix of encoder states transposed, hTq [C x ldq] with one scale s_h
+ *     (O1's matrix rule, once per sentence), times the vector alpha: (aq, s_a) = O1(alpha);
+ *     ctx_c = (float)(sum_i hTq[c,i] * aq_i) * (s_h * s_a)                 [O2, O3, no bias]
+ * e_out may be NULL. */
+void q8o_attention_q8(const float *P, int l, int A, const float *a, const int8_t *vq, float s_v,
+                      const int8_t *hTq, int C, int ldq, float s_h,
+                      float *e_out, float *alpha, float *ctx);
+
 /* O7 (Eq. 3-6).  One conditional-GRU step for one hypothesis:
  * s' = r(y, s_prev); a = u(q(s')); attention -> H_t; s = q(H_t, s').
  * Outputs: s_mid [H] (= s'), alpha [l], ctx [C] (= H_t), s_out [H]; any may be NULL except s_out. */

@@ -224,6 +224,23 @@ def attention(P, enc_h, a, v):
     return e, alpha, ctx
 
 
+def attention_q8(P, enc_h, a, v):
+    """The attention block with its two activation products in 8 bits (q8o_attention_q8); v and the
+    transposed encoder states are quantized here by the oracle's matrix rule.  Returns
+    (e, alpha, ctx, (vq, s_v), (hTq, s_h))."""
+    P, enc_h, a, v = _f32(P), _f32(enc_h), _f32(a), _f32(v)
+    l, A = P.shape
+    Cc = enc_h.shape[1]
+    vq, s_v = quantize_matrix(v[None, :], ld_out=A)
+    hTq, s_h = quantize_matrix(np.ascontiguousarray(enc_h.T))
+    e = np.empty(l, np.float32)
+    alpha = np.empty(l, np.float32)
+    ctx = np.empty(Cc, np.float32)
+    lib().q8o_attention_q8(_p(P), C.c_int(l), C.c_int(A), _p(a), _p(vq), C.c_float(s_v), _p(hTq), C.c_int(Cc),
+                           C.c_int(hTq.shape[1]), C.c_float(s_h), _p(e), _p(alpha), _p(ctx))
+    return e, alpha, ctx, (vq, s_v), (hTq, s_h)
+
+
 def logsoftmax_topk(logits, k):
     logits = _f32(logits)
     lse = C.c_float()

@@ -341,3 +341,66 @@ def test_ensemble_beam_one_follows_the_mean_distribution(oracle):
     assert toks.tolist() == exp
     assert abs(float(score) - float(total)) < 1e-5
     assert differs          # the two models disagree somewhere, so averaging mattered
+
+
+# ---- attention with its two activation products in 8 bits (variant) ------------------------
+
+def test_attention_q8_hand_case(oracle):
+    """P + a = 0 everywhere: T = 0 (scale 1, codes 0), e = 0, alpha = (1/2, 1/2) with codes (127, 127)
+    and scale 0.5/127; states [[1, -1], [0.5, 0.25]] transposed: maximum 1, codes [[127, 64], [-127, 32]]."""
+    P = np.array([[0.3, -0.2, 0.1], [1.0, 2.0, -3.0]], np.float32)
+    a = np.zeros(3, np.float32)
+    h = np.array([[1.0, -1.0], [0.5, 0.25]], np.float32)
+    e, alpha, ctx, (vq, s_v), (hTq, s_h) = oracle.attention_q8(P * 0, h, a, np.array([0.5, -1.0, 0.25], np.float32))
+    assert vq[0].tolist() == [64, -127, 32] and s_v == np.float32(1.0) / np.float32(127.0)
+    assert hTq[:, :2].tolist() == [[127, 64], [-127, 32]] and s_h == np.float32(1.0) / np.float32(127.0)
+    assert e.tolist() == [0.0, 0.0] and alpha.tolist() == [0.5, 0.5]
+    s_a = np.float32(0.5) / np.float32(127.0)
+    c = s_h * s_a
+    assert ctx.tolist() == [np.float32(127 * (127 + 64)) * c, np.float32(127 * (-127 + 32)) * c]
+    np.testing.assert_allclose(ctx, [0.75, -0.375], atol=0.005)
+
+
+def test_attention_q8_single_position_and_energy(oracle):
+    """One source position: alpha = 1 (code 127, scale 1/127), so the context is the state's int8 image;
+    the energy is the plain 8-bit product of v with tanh(P + a), recomputed here with integer numpy."""
+    rng = np.random.default_rng(21)
+    A, Cc = 64, 40
+    P = rng.standard_normal((1, A)).astype(np.float32)
+    a = rng.standard_normal(A).astype(np.float32)
+    v = (rng.standard_normal(A) * 0.05).astype(np.float32)
+    h = rng.standard_normal((1, Cc)).astype(np.float32)
+    e, alpha, ctx, (vq, s_v), (hTq, s_h) = oracle.attention_q8(P, h, a, v)
+    assert alpha.tolist() == [1.0]
+    assert (ctx == (hTq[:, 0].astype(np.float32) * np.float32(127.0)) * (s_h * (np.float32(1.0) / np.float32(127.0)))).all()
+    assert np.abs(ctx - h[0]).max() <= float(s_h) / 2 * (1 + 1e-3)
+    T = np.tanh((P[0] + a).astype(np.float64)).astype(np.float32)
+    Tq, s_T = oracle.quantize(T)
+    assert e[0] == np.float32(int(vq[0].astype(np.int64) @ Tq.astype(np.int64))) * (s_v * s_T)
+
+
+def test_attention_q8_within_bound_of_float_attention(oracle):
+    rng = np.random.default_rng(22)
+    l, A, Cc = 30, 1024, 256
+    P = rng.standard_normal((l, A)).astype(np.float32)
+    a = rng.standard_normal(A).astype(np.float32)
+    v = (rng.standard_normal(A) * 0.05).astype(np.float32)
+    h = rng.standard_normal((l, Cc)).astype(np.float32)
+    e, alpha, ctx, (vq, s_v), (hTq, s_h) = oracle.attention_q8(P, h, a, v)
+    e_f, alpha_f, ctx_f = oracle.attention(P, h, a, v)
+    T = np.tanh((P + a[None, :]).astype(np.float64))
+    s_T = np.abs(T).max(axis=1) / 127
+    bound = float(s_v) / 2 * np.abs(T).sum(axis=1) + s_T / 2 * np.abs(v).sum() + A * float(s_v) * s_T / 4
+    assert (np.abs(e - e_f) <= bound * (1 + 1e-3) + 1e-6).all() and np.abs(e - e_f).max() > 0
+    # softmax of the variant's own energies, by the library
+    w = np.exp(e.astype(np.float64) - e.max())
+    np.testing.assert_allclose(alpha, w / w.sum(), rtol=1e-6)
+    # the context against the exact weighted sum with the variant's own alpha
+    exact = alpha.astype(np.float64) @ h.astype(np.float64)
+    s_a = alpha.max() / 127
+    cb = float(s_h) / 2 * np.abs(alpha).sum() + s_a / 2 * np.abs(h).sum(axis=0) + l * float(s_h) * s_a / 4
+    assert (np.abs(ctx - exact) <= cb * (1 + 1e-3) + 1e-6).all()
+    assert np.abs(ctx - ctx_f).max() < 0.2 and np.abs(ctx - ctx_f).max() > 0
+    # scaling v by a power of two scales the energies by exactly that factor
+    e4 = oracle.attention_q8(P, h, a, v * 4)[0]
+    assert (e4 == 4 * e).all()
