@@ -192,6 +192,29 @@ def row_scale_variant(torch, q, ctx, rng):
     return out
 
 
+def attention_variant(torch, q, ctx, rng, n=BEAM, l=L):
+    """The attention block with 8-bit energy and context products (a composition of five launches on
+    the product kernels) beside the float definition evaluated in fp64: duration and deviation."""
+    A, Cc = 1024, 2048
+    P = rng.standard_normal((l, A)).astype(np.float32)
+    a = rng.standard_normal((n, A)).astype(np.float32)
+    v = (rng.standard_normal(A) * 0.05).astype(np.float32)
+    h = rng.standard_normal((l, Cc)).astype(np.float32)
+    vm, hT = q.q8_quantize_matrix(ctx, v[None, :]), q.q8_attention_states_q8(ctx, ctx.f32(h))
+    Pd, ad = ctx.f32(P), ctx.f32(a)
+    t = median_of(torch, lambda: q.q8_attention_q8(ctx, vm, hT, Pd, ad), inner=50)
+    e, alpha, cvec = (x.cpu().numpy().astype(np.float64) for x in q.q8_attention_q8(ctx, vm, hT, Pd, ad))
+    T = np.tanh(P.astype(np.float64)[None, :, :] + a.astype(np.float64)[:, None, :])
+    e64 = T @ v.astype(np.float64)
+    w = np.exp(e64 - e64.max(axis=1, keepdims=True))
+    al64 = w / w.sum(axis=1, keepdims=True)
+    c64 = al64 @ h.astype(np.float64)
+    return {"us_median_min": t, "hypotheses": n, "source_length": l,
+            "energy_rms_dev": float(np.sqrt(((e - e64) ** 2).mean())), "energy_rms": float(np.sqrt((e64 ** 2).mean())),
+            "alpha_max_dev": float(np.abs(alpha - al64).max()),
+            "context_rms_dev": float(np.sqrt(((cvec - c64) ** 2).mean())), "context_rms": float(np.sqrt((c64 ** 2).mean()))}
+
+
 def kernel_times(torch, q, ctx, step, steps):
     """Average duration of every kernel class inside the running decoder loop, from event
     pairs attached to the dispatches (one class per pass over `steps` steps)."""
@@ -528,6 +551,7 @@ def main():
                                         "3.1MB_warm": read_ceiling(torch, q, ctx, 3145728, cold=False),
                                         "3.1MB_cold": read_ceiling(torch, q, ctx, 3145728, cold=True)}
         extra["row_scale_variant"] = row_scale_variant(torch, q, ctx, rng)
+        extra["attention_8bit_variant"] = attention_variant(torch, q, ctx, rng)
         extra["mfma_products"] = mfma_products(torch, q, ctx, m, rng)
         extra["paper_shapes_620_1000_63644"] = paper_shapes(torch, q, ctx, rng, max(args.steps // 4, 100))
         extra["batched_decoding"] = batched_decoding(torch, q, m, rng, max(args.steps // 10, 50))

@@ -176,6 +176,23 @@ q8_status cgru_decoder_step_q8(q8_ctx *ctx, const q8_cgru_weights *w, const floa
                                float *s_out, float *ctx_out, float *alpha_out, float *s_mid_out,
                                const q8_taps *taps5);
 
+/* Variant of the attention block of Eq. 5-6 in which the two products without a trained matrix
+ * are 8-bit as well (the other reading of Section 3; cgru_decoder_step_q8 keeps them in float).
+ * q8_attention_states_q8 (once per sentence, synchronous like q8_quantize_matrix): the encoder
+ *   states enc_h [l x C] are transposed and quantized with one scale into hT_out, int8
+ *   [C x ld_out] (ld_out >= l, ld_out % 16 == 0, pad bytes zero); the scale returns to the host.
+ *   Workspace: 4 C l bytes.
+ * q8_attention_q8: v is the energy vector as a 1 x A int8 matrix (q8_quantize_matrix of v),
+ *   hT the matrix made above (C x l).  For each of the n <= 8 hypotheses, with a [n x A] = u(s'):
+ *   T_i = tanh(P_i + a) is quantized per source position, e_i = (float)(vq . Tq_i) * (s_v * s_Ti);
+ *   alpha = softmax(e); alpha is quantized per hypothesis,
+ *   ctx_c = (float)(hTq_c . alphaq) * (s_h * s_alpha).  P [l x A]; ctx_out [n x C]; e_out and
+ *   alpha_out [n x l] may be NULL.  A % 4 == 0, l <= 1024.  Workspace: about n l (4 A + ld(v) + 12) bytes. */
+q8_status q8_attention_states_q8(q8_ctx *ctx, const float *enc_h, int l, int C, int8_t *hT_out, int ld_out,
+                                 float *scale_out_host);
+q8_status q8_attention_q8(q8_ctx *ctx, const q8_mat *v, const q8_mat *hT, const float *P, const float *a, int n,
+                          int l, float *e_out, float *alpha_out, float *ctx_out);
+
 /* Output network g of Eq. 2 for n_beam hypotheses.  If ro != NULL:
  * t = tanh(((W_s q(s) + W_y q(y_emb)) + W_c q(ctx)) + b_t), else t = t_in [n x R].
  * logits = W_out q(t) + b_out; lse = log sum exp(logits); the k best entries per

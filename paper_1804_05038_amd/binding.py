@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 
 __all__ = ["Q8Error", "Context", "Mat", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
-           "q8_quantize_matrix", "q8_quantize_matrix_rows", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "q8_gemm_narrow_rows", "gru_step_q8", "cgru_decoder_step_q8",
+           "q8_quantize_matrix", "q8_quantize_matrix_rows", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "q8_gemm_narrow_rows", "q8_attention_states_q8", "q8_attention_q8", "gru_step_q8", "cgru_decoder_step_q8",
            "output_logits_q8", "output_logits_beam_q8", "q8_encode", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
            "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "MatF", "GruWeightsF32", "CgruWeightsF32", "ReadoutWeightsF32", "q8_gemv_f32",
            "cgru_decoder_step_f32", "output_logits_f32", "q8_translate_ensemble", "q8_translate_ensemble_bytes", "cgru_decoder_step_batch_q8", "q8_encode_batch", "q8_encode_batch_bytes", "q8_beam_init_batch",
@@ -83,6 +83,8 @@ def load_library():
         lib.q8_gemm_narrow.argtypes = [vp, C.POINTER(_Mat), vp, ci, ci, vp, vp, ci, C.POINTER(_Taps)]
         lib.q8_quantize_matrix_rows.argtypes = [vp, vp, ci, ci, ci, vp, ci, vp]
         lib.q8_gemm_narrow_rows.argtypes = [vp, C.POINTER(_Mat), vp, vp, ci, ci, vp, vp, ci, C.POINTER(_Taps)]
+        lib.q8_attention_states_q8.argtypes = [vp, vp, ci, ci, vp, ci, C.POINTER(C.c_float)]
+        lib.q8_attention_q8.argtypes = [vp, C.POINTER(_Mat), C.POINTER(_Mat), vp, vp, ci, ci, vp, vp, vp]
         lib.gru_step_q8.argtypes = [vp, C.POINTER(_Gru), vp, vp, ci, vp, C.POINTER(_Taps)]
         lib.cgru_decoder_step_q8.argtypes = [vp, C.POINTER(_Cgru), vp, vp, ci, vp, vp, ci, vp, vp, vp, vp, C.POINTER(_Taps)]
         lib.output_logits_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, vp, ci, ci,
@@ -269,7 +271,8 @@ def q8_quantize_matrix(ctx, W, ld_out=None):
     ld_out = (cols + 15) // 16 * 16 if ld_out is None else ld_out
     Wq = ctx.empty(rows, ld_out, dtype=torch.int8)
     scale = C.c_float()
-    ctx.check(ctx.lib.q8_quantize_matrix(ctx.handle, _ptr(W), rows, cols, W.stride(0), _ptr(Wq), ld_out, C.byref(scale)))
+    ctx.check(ctx.lib.q8_quantize_matrix(ctx.handle, _ptr(W), rows, cols, W.stride(0) if rows > 1 else cols, _ptr(Wq), ld_out,
+                                         C.byref(scale)))
     return Mat(Wq, cols, scale.value)
 
 
@@ -304,7 +307,8 @@ def q8_quantize_matrix_rows(ctx, W, ld_out=None):
     ld_out = (cols + 15) // 16 * 16 if ld_out is None else ld_out
     Wq = ctx.empty(rows, ld_out, dtype=torch.int8)
     row_scale = ctx.empty(rows)
-    ctx.check(ctx.lib.q8_quantize_matrix_rows(ctx.handle, _ptr(W), rows, cols, W.stride(0), _ptr(Wq), ld_out, _ptr(row_scale)))
+    ctx.check(ctx.lib.q8_quantize_matrix_rows(ctx.handle, _ptr(W), rows, cols, W.stride(0) if rows > 1 else cols, _ptr(Wq),
+                                              ld_out, _ptr(row_scale)))
     return Mat(Wq, cols, 0.0), row_scale
 
 
@@ -315,6 +319,25 @@ def q8_gemm_narrow_rows(ctx, W, row_scale, X, bias=None, Y=None, taps=False):
     ctx.check(ctx.lib.q8_gemm_narrow_rows(ctx.handle, C.byref(W.c), _ptr(row_scale), _ptr(X), n, X.stride(0), _ptr(bias),
                                           _ptr(Y), Y.stride(0), ts.arr if ts else None))
     return (Y, ts.t[0]) if taps else Y
+
+
+def q8_attention_states_q8(ctx, enc_h):
+    """The transposed encoder states [C x l] as an int8 matrix with one scale."""
+    l, Cc = enc_h.shape
+    ld = (l + 15) // 16 * 16
+    hT = ctx.empty(Cc, ld, dtype=torch.int8)
+    scale = C.c_float()
+    ctx.check(ctx.lib.q8_attention_states_q8(ctx.handle, _ptr(enc_h), l, Cc, _ptr(hT), ld, C.byref(scale)))
+    return Mat(hT, l, scale.value)
+
+
+def q8_attention_q8(ctx, v, hT, P, a):
+    """Returns (e [n x l], alpha [n x l], ctx [n x C])."""
+    n, l = a.shape[0], P.shape[0]
+    e, alpha, cvec = ctx.empty(n, l), ctx.empty(n, l), ctx.empty(n, hT.rows)
+    ctx.check(ctx.lib.q8_attention_q8(ctx.handle, C.byref(v.c), C.byref(hT.c), _ptr(P), _ptr(a), n, l, _ptr(e),
+                                      _ptr(alpha), _ptr(cvec)))
+    return e, alpha, cvec
 
 
 class GruWeights:

@@ -285,6 +285,61 @@ static q8_status gemm_narrow_any(q8_ctx *ctx, const q8_mat *W, const float *row_
     return q8i_gemm_mfma(ctx, W, X, n, ldx, bias, Y, ldy, taps, xq, xs, row_scale);
 }
 
+q8_status q8_attention_states_q8(q8_ctx *ctx, const float *enc_h, int l, int C, int8_t *hT_out, int ld_out,
+                                 float *scale_out_host)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!enc_h || !hT_out || !scale_out_host) return q8_fail(ctx, Q8_ERR_NULL, "q8_attention_states_q8: NULL argument");
+    if (l <= 0 || l > kMaxL || C <= 0 || ld_out < l || ld_out > kMaxLd)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "q8_attention_states_q8: bad shape l %d, C %d, ld_out %d", l, C, ld_out);
+    if (!aligned16(hT_out) || ld_out % 16 != 0)
+        return q8_fail(ctx, Q8_ERR_ALIGN, "q8_attention_states_q8: output needs a 16-byte aligned base and ld_out %% 16 == 0");
+    Carver cv(ctx);
+    float *t = cv.take<float>((size_t)C * l);
+    if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "q8_attention_states_q8: workspace too small");
+    TRY(q8i_transpose(ctx, enc_h, l, C, t));
+    return q8i_quantize_matrix(ctx, t, C, l, l, hT_out, ld_out, scale_out_host);
+}
+
+q8_status q8_attention_q8(q8_ctx *ctx, const q8_mat *v, const q8_mat *hT, const float *P, const float *a, int n, int l,
+                          float *e_out, float *alpha_out, float *ctx_out)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    TRY(check_mat(ctx, v, "v"));
+    TRY(check_mat(ctx, hT, "hT"));
+    const int A = v->cols, C = hT->rows;
+    if (v->rows != 1) return q8_fail(ctx, Q8_ERR_SHAPE, "v: expected a 1 x A matrix, got %d rows", v->rows);
+    if (n <= 0 || n > kMaxNarrow) return q8_fail(ctx, Q8_ERR_SHAPE, "n = %d outside [1, %d]", n, kMaxNarrow);
+    if (l <= 0 || l > kMaxL || hT->cols != l) return q8_fail(ctx, Q8_ERR_SHAPE, "l = %d outside [1, %d] or hT has %d columns", l, kMaxL, hT->cols);
+    if (A % 4) return q8_fail(ctx, Q8_ERR_ALIGN, "A must be a multiple of 4");
+    if (!P || !a || !ctx_out) return q8_fail(ctx, Q8_ERR_NULL, "q8_attention_q8: NULL argument");
+    if (!aligned16(P) || !aligned16(a) || !aligned16(ctx_out))
+        return q8_fail(ctx, Q8_ERR_ALIGN, "q8_attention_q8: fp32 buffers need 16-byte alignment");
+    if ((size_t)n * hT->ld > 65536 || (size_t)kMaxNarrow * v->ld > 65536)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "q8_attention_q8: rows too long for the streaming kernel");
+    const int nl = n * l, lda = (l + 3) & ~3, chunk = nl < kMaxMfmaN ? nl : kMaxMfmaN;
+    Carver cv(ctx);
+    float *T = cv.take<float>((size_t)nl * A);
+    float *e = cv.take<float>((size_t)nl);
+    float *alpha = cv.take<float>((size_t)n * lda);
+    int8_t *xq = cv.take<int8_t>((size_t)chunk * v->ld);
+    float *xs = cv.take<float>((size_t)chunk);
+    if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "q8_attention_q8: workspace too small");
+    TRY(q8i_att_tanh(ctx, P, a, T, l, A, n));
+    for (int v0 = 0; v0 < nl; v0 += kMaxMfmaN) {                     // the energies: one product per <= 1024 positions
+        const int cnt = nl - v0 < kMaxMfmaN ? nl - v0 : kMaxMfmaN;
+        if (cnt <= kMaxNarrow) {
+            q8i_gemv_desc d = {v, T + (size_t)v0 * A, A, nullptr, e + v0, 1, nullptr};
+            TRY(q8i_gemv_jobs(ctx, &d, 1, cnt));
+        } else {
+            TRY(q8i_gemm_mfma(ctx, v, T + (size_t)v0 * A, cnt, A, nullptr, e + v0, 1, nullptr, xq, xs));
+        }
+    }
+    TRY(q8i_att_softmax(ctx, e, n, l, lda, alpha, alpha_out, e_out));
+    q8i_gemv_desc d = {hT, alpha, lda, nullptr, ctx_out, C, nullptr};
+    return q8i_gemv_jobs(ctx, &d, 1, n);
+}
+
 q8_status q8_gemv(q8_ctx *ctx, const q8_mat *W, const float *x, const float *bias, float *y, const q8_taps *taps)
 {
     if (!ctx) return Q8_ERR_NULL;

@@ -454,3 +454,82 @@ q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s,
     }
     return q8i_launch_check(ctx, "readout");
 }
+
+// ============================ attention with 8-bit activation products (a variant) ==
+// Under the other reading of Section 3 for Eq. 5-6 the products with v and with the encoder
+// states are 8-bit too.  Both are then ordinary narrow products and run on the product kernels
+// (v as a 1 x A matrix against the tanh vectors of all positions, the transposed states as a
+// C x l matrix against the attention weights); what is left are three element-wise kernels.
+
+// T[(b l + i) A + j] = tanh(P[i A + j] + a[b A + j])
+__global__ __launch_bounds__(256) void att_tanh_kernel(const float *__restrict__ P, const float *__restrict__ a,
+                                                       float *__restrict__ T, int l, int A, int n)
+{
+    const size_t total = (size_t)n * l * A;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
+        const size_t bi = e / A;
+        const int j = (int)(e - bi * A), b = (int)(bi / l), i = (int)(bi - (size_t)b * l);
+        const float pre = P[(size_t)i * A + j] + a[(size_t)b * A + j];
+        T[e] = q8_tanh_rn(pre);
+    }
+}
+
+// alpha = softmax(e) per hypothesis (one wave each), written with leading dimension ld_alpha
+// (pad zero) for the product that follows and, if asked for, densely to alpha_out / e_out.
+__global__ __launch_bounds__(64) void att_softmax_kernel(const float *__restrict__ e, int l, int ld_alpha,
+                                                         float *__restrict__ alpha_ws, float *__restrict__ alpha_out,
+                                                         float *__restrict__ e_out)
+{
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const float *eb = e + (size_t)b * l;
+    float mx = -INFINITY;
+    for (int i = lane; i < l; i += 64) mx = fmaxf(mx, eb[i]);
+    mx = wave_max_f(mx);
+    double z = 0.0;
+    for (int i = lane; i < l; i += 64) z += q8_exp_d(fmax((double)eb[i] - (double)mx, -700.0));
+    z = wave_sum_d(z);
+    for (int i = lane; i < ld_alpha; i += 64) {
+        float al = 0.0f;
+        if (i < l) {
+            al = (float)(q8_exp_d(fmax((double)eb[i] - (double)mx, -700.0)) / z);
+            if (alpha_out) alpha_out[(size_t)b * l + i] = al;
+            if (e_out) e_out[(size_t)b * l + i] = eb[i];
+        }
+        alpha_ws[(size_t)b * ld_alpha + i] = al;
+    }
+}
+
+// Xt[c rows + r] = X[r cols + c]
+__global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict__ X, int rows, int cols, float *__restrict__ Xt)
+{
+    const size_t total = (size_t)rows * cols;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (size_t)gridDim.x * 256) {
+        const size_t c = e / rows, r = e - c * rows;
+        Xt[e] = X[r * cols + c];
+    }
+}
+
+static int blocks_for(size_t total)
+{
+    const size_t b = (total + 255) / 256;
+    return (int)(b < 4096 ? b : 4096);
+}
+
+q8_status q8i_att_tanh(q8_ctx *ctx, const float *P, const float *a, float *T, int l, int A, int n)
+{
+    hipLaunchKernelGGL(att_tanh_kernel, dim3(blocks_for((size_t)n * l * A)), dim3(256), 0, ctx->stream, P, a, T, l, A, n);
+    return q8i_launch_check(ctx, "attention tanh");
+}
+
+q8_status q8i_att_softmax(q8_ctx *ctx, const float *e, int n, int l, int ld_alpha, float *alpha_ws, float *alpha_out,
+                          float *e_out)
+{
+    hipLaunchKernelGGL(att_softmax_kernel, dim3(n), dim3(64), 0, ctx->stream, e, l, ld_alpha, alpha_ws, alpha_out, e_out);
+    return q8i_launch_check(ctx, "attention softmax");
+}
+
+q8_status q8i_transpose(q8_ctx *ctx, const float *X, int rows, int cols, float *Xt)
+{
+    hipLaunchKernelGGL(transpose_kernel, dim3(blocks_for((size_t)rows * cols)), dim3(256), 0, ctx->stream, X, rows, cols, Xt);
+    return q8i_launch_check(ctx, "transpose");
+}

@@ -135,6 +135,11 @@ q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode
 q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, int A, int C, const float *a,
                         const float *v, int n, float *e, float *alpha, float *cvec, const int *sent_off, int beam,
                         int8_t *ctx_q, float *ctx_qscale, int ldq, int *codes_written);
+// element-wise parts of the attention variant with 8-bit activation products
+q8_status q8i_att_tanh(q8_ctx *ctx, const float *P, const float *a, float *T, int l, int A, int n);
+q8_status q8i_att_softmax(q8_ctx *ctx, const float *e, int n, int l, int ld_alpha, float *alpha_ws, float *alpha_out,
+                          float *e_out);
+q8_status q8i_transpose(q8_ctx *ctx, const float *X, int rows, int cols, float *Xt);
 q8_status q8i_gru_gates(q8_ctx *ctx, const float *gx, const float *gh, const float *h_prev, int ldh, float *h_out,
                         int ldo, int H, int n);
 // the same, also leaving the new states quantized in q1 [n x ld1] / s1 [n] (and q2 / s2 unless q2 is NULL)
