@@ -161,16 +161,38 @@ __global__ __launch_bounds__(256) void gemv_jobs_kernel(GemvJobs jobs)
     }
 }
 
-// Rows of at most 1024 * CH bytes and cols % 4 == 0: activations and the first two rows of
-// every wave are requested before anything is waited for; the row loop is double-buffered.
+// The lane's partial sums of U staged rows against the N quantized vectors in LDS, without a
+// branch: a lane whose 16 bytes lie past the row holds zeros (the loader read them from nowhere)
+// and multiplies them with the row's last 16 codes.
+template <int N, int U, int CH>
+__device__ __forceinline__ void rows_dot_part_nb(const v4i (&w)[U][CH], int ld, int lane, const int8_t *xq, int (&acc)[U][N])
+{
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int j = 0; j < N; ++j) acc[u][j] = 0;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int off = min((c * 64 + lane) * 16, ld - 16);
+#pragma unroll
+        for (int j = 0; j < N; ++j) {
+            const v4i x = *(const v4i *)(xq + (size_t)j * ld + off);
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc[u][j] = dot16(w[u][c], x, acc[u][j]);
+        }
+    }
+}
+
+// Rows of at most 1024 * CH bytes and cols % 4 == 0: activations and the first U rows of every
+// wave are requested before anything is waited for; after that two register sets take turns, one
+// pass's rows being multiplied while the next pass's are in flight (U rows per wave and pass).
 // ROWS: every job has one weight scale per row (requested with the row's bias).
-template <int N, int CH, bool ROWS>
+template <int N, int CH, bool ROWS, int U>
 __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
 {
     extern __shared__ __align__(16) int8_t smem[];
     __shared__ float s_scale[8];
     __shared__ float s_red[8 * 4];
-    constexpr int U = 2;
     __shared__ int s_t[4][U * N];
     const GemvJob &J = jobs.j[pick_job(jobs)];
     const int blk = blockIdx.x - J.block0;
@@ -182,64 +204,58 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
     XRegs<N, CH> xr;
     x_load<N, CH>(xr, J.X, N, J.cols, J.ldx);
     int r = r_begin + wave * U;
-    v4i w[U][CH];
     const __amdgpu_buffer_rsrc_t rw = q8_rsrc(J.W, (size_t)J.rows * ld);
     const __amdgpu_buffer_rsrc_t rb = q8_rsrc(J.bias, J.bias ? (size_t)J.rows * sizeof(float) : 0);
     const __amdgpu_buffer_rsrc_t rs = q8_rsrc(J.row_scale, ROWS ? (size_t)J.rows * sizeof(float) : 0);
-    // biases (and per-row weight scales) of the rows in flight, requested with them (lane j < N
-    // finishes vector j; absent: zero, read from nowhere); b[U + u] is the scale of row u
-    auto bias_load = [&](float (&b)[2 * U], int r0) {
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int off = (int)((lane < N && r0 + u < r_end) ? (unsigned)(r0 + u) * 4u : Q8_OOB);
-            b[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, off, 0, 0));
-            b[U + u] = ROWS ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0)) : 0.0f;
-        }
-    };
-    float bw[2 * U];
-    {
+    const int last_row = J.rows - 1;
+    // A pass's rows, their biases and (ROWS) their scales, all requested without a branch: rows past
+    // the block's end read from nowhere (zeros); the per-row floats take one load instruction per
+    // pass, lane u reading row u's (from a clamped row; absent arrays read as zero): a load
+    // instruction per row would double the kernel's count of them.
+    auto request = [&](v4i (&wr)[U][CH], float (&b)[2], int r0) {
         int row[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) row[u] = r + u < r_end ? r + u : -1;
-        rows_load<U, CH>(w, rw, row, ld, lane);
-        bias_load(bw, r);
-    }
+        for (int u = 0; u < U; ++u) row[u] = r0 + u < r_end ? r0 + u : -1;
+        rows_load<U, CH>(wr, rw, row, ld, lane);
+        const int off = min(r0 + (lane & (U - 1)), last_row) * 4;
+        b[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, off, 0, 0));
+        b[1] = ROWS ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0)) : 0.0f;
+    };
+    v4i w[U][CH], w2[U][CH];
+    float bw[2], bw2[2];
+    request(w, bw, r);
     x_finish<N, CH>(xr, N, ld, smem, s_scale, s_red);
     if (blk == 0) write_x_taps<N>(J, smem, s_scale);
     float cj = 0.0f, sxj = 0.0f;
     if (lane < N) { sxj = s_scale[lane]; cj = J.w_scale * sxj; }
+    const bool has_bias = J.bias != nullptr;
 
-    while (r < r_end) {
-        const int rn = r + 4 * U;
-        v4i wn[U][CH];
-        {
-            int row[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) row[u] = rn + u < r_end ? rn + u : -1;
-            rows_load<U, CH>(wn, rw, row, ld, lane);
-        }
-        float bn[2 * U];
-        bias_load(bn, rn);
+    auto finish = [&](const v4i (&wr)[U][CH], const float (&b)[2], int r0) {
         int part[U][N], mine[U];
-        rows_dot_part<N, U, CH>(w, ld, lane, smem, part);
+        rows_dot_part_nb<N, U, CH>(wr, ld, lane, smem, part);
         sums_to_lanes<N, U>(part, lane, s_t[wave], mine);      // lane j < N: the totals of vector j
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int a = mine[u];
-            if (lane < N && r + u < r_end) {
-                float y = (float)a * (ROWS ? bw[U + u] * sxj : cj);
-                if (J.bias) y = y + bw[u];
-                J.Y[(size_t)lane * J.ldy + r + u] = y;
-                if (J.tap_acc) J.tap_acc[(size_t)lane * J.rows + r + u] = a;
+            const float bu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(b[0]), u));
+            const float su = ROWS ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(b[1]), u)) : 0.0f;
+            float y = (float)a * (ROWS ? su * sxj : cj);
+            const float yb = y + bu;
+            y = has_bias ? yb : y;
+            if (lane < N && r0 + u < r_end) {
+                J.Y[(size_t)lane * J.ldy + r0 + u] = y;
+                if (J.tap_acc) J.tap_acc[(size_t)lane * J.rows + r0 + u] = a;
             }
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int c = 0; c < CH; ++c) w[u][c] = wn[u][c];
-#pragma unroll
-        for (int u = 0; u < 2 * U; ++u) bw[u] = bn[u];
-        r = rn;
+    };
+    while (r < r_end) {
+        request(w2, bw2, r + 4 * U);
+        finish(w, bw, r);
+        r += 4 * U;
+        if (r >= r_end) break;
+        request(w, bw, r + 4 * U);
+        finish(w2, bw2, r);
+        r += 4 * U;
     }
 }
 
@@ -327,16 +343,21 @@ q8_status q8i_fill_u32(q8_ctx *ctx, void *p, int n, unsigned v)
     return q8i_launch_check(ctx, "fill");
 }
 
-template <int N>
-static void launch_gemv_n(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t smem, int ch, bool rows)
+template <int N, bool ROWS, int U>
+static void launch_gemv_nu(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t smem, int ch)
 {
-    if (ch == 1 && !rows) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 1, false>), dim3(blocks), dim3(256), smem, jobs);
-    else if (ch == 2 && !rows) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 2, false>), dim3(blocks), dim3(256), smem, jobs);
-    else if (ch == 4 && !rows) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 4, false>), dim3(blocks), dim3(256), smem, jobs);
-    else if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 1, true>), dim3(blocks), dim3(256), smem, jobs);
-    else if (ch == 2) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 2, true>), dim3(blocks), dim3(256), smem, jobs);
-    else if (ch == 4) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 4, true>), dim3(blocks), dim3(256), smem, jobs);
-    else Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, gemv_jobs_kernel<N>, dim3(blocks), dim3(256), smem, jobs);
+    if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 1, ROWS, U>), dim3(blocks), dim3(256), smem, jobs);
+    else if (ch == 2) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 2, ROWS, U>), dim3(blocks), dim3(256), smem, jobs);
+    else Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 4, ROWS, U>), dim3(blocks), dim3(256), smem, jobs);
+}
+
+template <int N>
+static void launch_gemv_n(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t smem, int ch, bool rows, int u)
+{
+    (void)u;
+    if (ch == 0) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, gemv_jobs_kernel<N>, dim3(blocks), dim3(256), smem, jobs);
+    else if (rows) launch_gemv_nu<N, true, 2>(ctx, jobs, blocks, smem, ch);
+    else launch_gemv_nu<N, false, 2>(ctx, jobs, blocks, smem, ch);
 }
 
 q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
@@ -361,12 +382,13 @@ q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
     if (with_rows != 0 && with_rows != njobs) fast = false;         // mixed launches run on the general kernel
     const bool rows = with_rows != 0;
     const int ch = fast ? q8_fast_ch(max_ld) : 0;
+    const int u = 2;
     int blocks = 0;
     for (int t = 0; t < njobs; ++t) {
         GemvJob &J = jobs.j[t];
         J.lpr = q8_lanes_per_row(J.ld);
         // rows covered by one block iteration; large matrices spread over at most ~2048 blocks
-        const int pass = ch ? 4 * 2 : 4 * (64 / J.lpr) * 4;
+        const int pass = ch ? 4 * u : 4 * (64 / J.lpr) * 4;
         int rpb = (J.rows + 2047) / 2048;
         rpb = (rpb + pass - 1) / pass * pass;
         J.rpb = rpb;
@@ -375,14 +397,14 @@ q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
     }
     const size_t smem = (size_t)n * max_ld;
     switch (n) {
-    case 1: launch_gemv_n<1>(ctx, jobs, blocks, smem, ch, rows); break;
-    case 2: launch_gemv_n<2>(ctx, jobs, blocks, smem, ch, rows); break;
-    case 3: launch_gemv_n<3>(ctx, jobs, blocks, smem, ch, rows); break;
-    case 4: launch_gemv_n<4>(ctx, jobs, blocks, smem, ch, rows); break;
-    case 5: launch_gemv_n<5>(ctx, jobs, blocks, smem, ch, rows); break;
-    case 6: launch_gemv_n<6>(ctx, jobs, blocks, smem, ch, rows); break;
-    case 7: launch_gemv_n<7>(ctx, jobs, blocks, smem, ch, rows); break;
-    default: launch_gemv_n<8>(ctx, jobs, blocks, smem, ch, rows); break;
+    case 1: launch_gemv_n<1>(ctx, jobs, blocks, smem, ch, rows, u); break;
+    case 2: launch_gemv_n<2>(ctx, jobs, blocks, smem, ch, rows, u); break;
+    case 3: launch_gemv_n<3>(ctx, jobs, blocks, smem, ch, rows, u); break;
+    case 4: launch_gemv_n<4>(ctx, jobs, blocks, smem, ch, rows, u); break;
+    case 5: launch_gemv_n<5>(ctx, jobs, blocks, smem, ch, rows, u); break;
+    case 6: launch_gemv_n<6>(ctx, jobs, blocks, smem, ch, rows, u); break;
+    case 7: launch_gemv_n<7>(ctx, jobs, blocks, smem, ch, rows, u); break;
+    default: launch_gemv_n<8>(ctx, jobs, blocks, smem, ch, rows, u); break;
     }
     return q8i_launch_check(ctx, "gemv");
 }
