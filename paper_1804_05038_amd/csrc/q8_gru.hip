@@ -154,7 +154,10 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
     // past the end is read through the descriptor as zero, so the loads need no branch
     constexpr int NPRE = XPRE ? (N * CH * 64 + 255) / 256 : 1;
     v4i pre_q[NPRE];
+    float pre_s = 0.0f;                      // XPRE: scale of vector tid, requested first so that it is not waited for behind the weights
     if (XPRE) {
+        pre_s = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+            q8_rsrc(J.xs_pre, (size_t)N * sizeof(float)), (int)(threadIdx.x < N ? threadIdx.x * 4u : Q8_OOB), 0, 0));
         const __amdgpu_buffer_rsrc_t rq = q8_rsrc(J.xq_pre, (size_t)N * J.ldwx);
 #pragma unroll
         for (int t = 0; t < NPRE; ++t)
@@ -171,26 +174,39 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
         if (MODE != GRU_GX_PRE) rows_load<3, CH>(wx, q8_rsrc(J.Wx, (size_t)3 * H * J.ldwx), row, J.ldwx, lane);
         if (MODE != GRU_GH_PRE) rows_load<3, CH>(wh, q8_rsrc(J.Wh, (size_t)3 * H * J.ldwh), row, J.ldwh, lane);
     }
-    // epilogue operands of lane j < N: biases, supplied pre-activations, previous state
-    // (unconditional, through descriptors: the other lanes and absent arrays read as zero)
+    // Epilogue operands (biases, previous state, supplied pre-activations) in one load instruction, two
+    // with pre-activations: lane 8 k + j reads slot k for vector j (k = 0..2: bx of gate k, 3..5: bh of
+    // gate k - 3, 6: h_prev of vector j; second load, k = 0..2: pre-activation of gate k for vector j).
+    // Lanes with nothing to read (absent arrays, vectors past N, units past H) read the first float of
+    // h_prev and drop it.  Every further load instruction per wave costs more than moving the values
+    // between lanes afterwards.
     float pre[3] = {0.f, 0.f, 0.f}, bxv[3] = {0.f, 0.f, 0.f}, bhv[3] = {0.f, 0.f, 0.f}, hp = 0.f;
+    float ev, pv = 0.0f;
+    bool ev_used, pv_used = false;
+    typedef const __attribute__((address_space(1))) float *gfp;
     {
-        const bool mine = ok && lane < N;
-        const __amdgpu_buffer_rsrc_t rp = q8_rsrc(J.g_pre, MODE != GRU_FULL ? ((size_t)(N - 1) * J.ldg + 3 * H) * sizeof(float) : 0);
-        const __amdgpu_buffer_rsrc_t rbx = q8_rsrc(J.bx, J.bx ? (size_t)3 * H * sizeof(float) : 0);
-        const __amdgpu_buffer_rsrc_t rbh = q8_rsrc(J.bh, J.bh ? (size_t)3 * H * sizeof(float) : 0);
-        const __amdgpu_buffer_rsrc_t rh = q8_rsrc(J.h_prev, ((size_t)(N - 1) * J.ldh + H) * sizeof(float));
-#pragma unroll
-        for (int gt = 0; gt < 3; ++gt) {
-            const int row = gt * H + unit;
-            if (MODE != GRU_FULL)
-                pre[gt] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rp, (int)(mine ? (unsigned)(lane * J.ldg + row) * 4u : Q8_OOB), 0, 0));
-            if (MODE != GRU_GX_PRE)
-                bxv[gt] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rbx, (int)(mine ? (unsigned)row * 4u : Q8_OOB), 0, 0));
-            if (MODE != GRU_GH_PRE)
-                bhv[gt] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rbh, (int)(mine ? (unsigned)row * 4u : Q8_OOB), 0, 0));
+        const int k = lane >> 3, j = lane & 7;
+        const int gt = k < 3 ? k : (k < 6 ? k - 3 : 0);
+        const size_t row = (size_t)gt * H + (ok ? unit : 0);
+        const bool use_bx = ok && k < 3 && MODE != GRU_GX_PRE && J.bx != nullptr;
+        const bool use_bh = ok && k >= 3 && k < 6 && MODE != GRU_GH_PRE && J.bh != nullptr;
+        const bool use_h = ok && k == 6 && j < N;
+        const float *p = J.h_prev;
+        p = use_bx ? J.bx + row : p;
+        p = use_bh ? J.bh + row : p;
+        p = use_h ? J.h_prev + (size_t)j * J.ldh + unit : p;
+        uintptr_t addr = (uintptr_t)p;
+        asm volatile("" : "+v"(addr));                   // one load from the chosen address, not a load per choice
+        ev = *(gfp)addr;
+        ev_used = use_bx || use_bh || use_h;             // applied where the value is first needed: not here, where it would be waited for
+        if (MODE != GRU_FULL) {
+            const bool use_p = ok && k < 3 && j < N;
+            const float *pp = use_p ? J.g_pre + (size_t)j * J.ldg + row : J.h_prev;
+            uintptr_t addr2 = (uintptr_t)pp;
+            asm volatile("" : "+v"(addr2));
+            pv = *(gfp)addr2;
+            pv_used = use_p;
         }
-        hp = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rh, (int)(mine ? (unsigned)(lane * J.ldh + unit) * 4u : Q8_OOB), 0, 0));
     }
 
     if (MODE == GRU_FULL) {
@@ -203,7 +219,7 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
             const int o = (t * 256 + (int)threadIdx.x) * 16;
             if (o < N * J.ldwx) *(v4i *)(xq + o) = pre_q[t];
         }
-        if (threadIdx.x < N) s_scale[threadIdx.x] = J.xs_pre[threadIdx.x];
+        if (threadIdx.x < N) s_scale[threadIdx.x] = pre_s;
         __syncthreads();
     } else if (MODE == GRU_GH_PRE) {
         x_finish<N, CH>(xr, N, J.ldwx, xq, s_scale, s_red);
@@ -229,6 +245,17 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
             }
     }
     sums_to_lanes<N, UT>(part, lane, s_t[wave], mine);
+    // the epilogue operands to the lanes that use them: biases are the same for every vector (read from
+    // the slot's first lane), the rest comes from lane 8 k + j
+    ev = ev_used ? ev : 0.0f;
+    pv = pv_used ? pv : 0.0f;
+#pragma unroll
+    for (int gt = 0; gt < 3; ++gt) {
+        bxv[gt] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ev), 8 * gt));
+        bhv[gt] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ev), 24 + 8 * gt));
+        if (MODE != GRU_FULL) pre[gt] = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (8 * gt + (lane & 7)), __float_as_int(pv)));
+    }
+    hp = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (48 + (lane & 7)), __float_as_int(ev)));
     if (ok && lane < N) {
         const int j = lane;
         float cx = 0.f, ch = 0.f;
