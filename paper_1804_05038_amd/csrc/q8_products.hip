@@ -352,9 +352,8 @@ static void launch_gemv_nu(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t
 }
 
 template <int N>
-static void launch_gemv_n(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t smem, int ch, bool rows, int u)
+static void launch_gemv_n(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t smem, int ch, bool rows)
 {
-    (void)u;
     if (ch == 0) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, gemv_jobs_kernel<N>, dim3(blocks), dim3(256), smem, jobs);
     else if (rows) launch_gemv_nu<N, true, 2>(ctx, jobs, blocks, smem, ch);
     else launch_gemv_nu<N, false, 2>(ctx, jobs, blocks, smem, ch);
@@ -382,7 +381,7 @@ q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
     if (with_rows != 0 && with_rows != njobs) fast = false;         // mixed launches run on the general kernel
     const bool rows = with_rows != 0;
     const int ch = fast ? q8_fast_ch(max_ld) : 0;
-    const int u = 2;
+    const int u = 2;                              // rows per wave and pass of the fast kernel
     int blocks = 0;
     for (int t = 0; t < njobs; ++t) {
         GemvJob &J = jobs.j[t];
@@ -397,14 +396,14 @@ q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
     }
     const size_t smem = (size_t)n * max_ld;
     switch (n) {
-    case 1: launch_gemv_n<1>(ctx, jobs, blocks, smem, ch, rows, u); break;
-    case 2: launch_gemv_n<2>(ctx, jobs, blocks, smem, ch, rows, u); break;
-    case 3: launch_gemv_n<3>(ctx, jobs, blocks, smem, ch, rows, u); break;
-    case 4: launch_gemv_n<4>(ctx, jobs, blocks, smem, ch, rows, u); break;
-    case 5: launch_gemv_n<5>(ctx, jobs, blocks, smem, ch, rows, u); break;
-    case 6: launch_gemv_n<6>(ctx, jobs, blocks, smem, ch, rows, u); break;
-    case 7: launch_gemv_n<7>(ctx, jobs, blocks, smem, ch, rows, u); break;
-    default: launch_gemv_n<8>(ctx, jobs, blocks, smem, ch, rows, u); break;
+    case 1: launch_gemv_n<1>(ctx, jobs, blocks, smem, ch, rows); break;
+    case 2: launch_gemv_n<2>(ctx, jobs, blocks, smem, ch, rows); break;
+    case 3: launch_gemv_n<3>(ctx, jobs, blocks, smem, ch, rows); break;
+    case 4: launch_gemv_n<4>(ctx, jobs, blocks, smem, ch, rows); break;
+    case 5: launch_gemv_n<5>(ctx, jobs, blocks, smem, ch, rows); break;
+    case 6: launch_gemv_n<6>(ctx, jobs, blocks, smem, ch, rows); break;
+    case 7: launch_gemv_n<7>(ctx, jobs, blocks, smem, ch, rows); break;
+    default: launch_gemv_n<8>(ctx, jobs, blocks, smem, ch, rows); break;
     }
     return q8i_launch_check(ctx, "gemv");
 }
