@@ -80,6 +80,19 @@ typedef struct {
     int32_t *acc;
 } q8_taps;
 
+/* Codes that travel with n fp32 vectors from the entry point that quantized them (Section 3:
+ * one scale per vector) to the next one that multiplies the same vectors: int8 codes [n x ld]
+ * (bytes past the vector's length zero) and scales [n], device memory of the caller.  The
+ * producer sets `valid` (host side, before it returns) to say whether its launches write them;
+ * a consumer uses them only if valid and ld is the pitch of the matrix it multiplies, and then
+ * produces exactly what it would from the fp32 vectors, which it still needs. */
+typedef struct {
+    int8_t *q;
+    float *scale;
+    int ld;
+    int valid;
+} q8_codes;
+
 /* One GRU cell.  Gate row blocks in the order r, z, n; biases [3H] may be NULL. */
 typedef struct {
     q8_mat Wx;             /* [3H x I] */
@@ -276,6 +289,23 @@ q8_status q8_beam_update(q8_ctx *ctx, void *state, const float *topk_logp, const
 q8_status output_logits_beam_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
                                 const float *s, float *y_emb, const float *ctx_vec, int n_beam, int k, void *state,
                                 const float *E_tgt, int E, float *s_next, float *topk_logp, int32_t *topk_idx);
+
+/* The decoder step with the quantized vectors handed on instead of recomputed (for callers that
+ * cannot afford the second quantization: the readout of Eq. 2 multiplies the same y and H_t that
+ * GRU r and GRU q multiplied earlier in the step).  cgru_decoder_step_codes_q8 is
+ * cgru_decoder_step_q8 and also leaves the codes of y_emb (pitch r.Wx.ld) and of the context
+ * vectors (pitch q.Wx.ld) in y_codes / ctx_codes (either may be NULL; q, scale and ld are the
+ * caller's, valid is set here).  output_logits_beam_codes_q8 is output_logits_beam_q8 and takes
+ * them (either NULL: as output_logits_beam_q8).  Results are bit-identical to the plain calls. */
+q8_status cgru_decoder_step_codes_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h,
+                                     int l, const float *y_emb, const float *s_prev, int n_beam,
+                                     float *s_out, float *ctx_out, float *alpha_out, float *s_mid_out,
+                                     const q8_taps *taps5, q8_codes *y_codes, q8_codes *ctx_codes);
+q8_status output_logits_beam_codes_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out,
+                                      const float *b_out, const float *s, float *y_emb, const float *ctx_vec,
+                                      int n_beam, int k, void *state, const float *E_tgt, int E, float *s_next,
+                                      float *topk_logp, int32_t *topk_idx, const q8_codes *y_codes,
+                                      const q8_codes *ctx_codes);
 
 /* Waits for the stream and copies the result to the host: tokens (without the final
  * token 0), their number, the cumulative log-probability, the steps made, and whether

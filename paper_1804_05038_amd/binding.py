@@ -12,7 +12,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 
-__all__ = ["Q8Error", "Context", "Mat", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
+__all__ = ["Q8Error", "Context", "Mat", "Codes", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
            "q8_quantize_matrix", "q8_quantize_matrix_rows", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "q8_gemm_narrow_rows", "q8_attention_states_q8", "q8_attention_q8", "gru_step_q8", "cgru_decoder_step_q8",
            "output_logits_q8", "output_logits_beam_q8", "q8_encode", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
            "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "MatF", "GruWeightsF32", "CgruWeightsF32", "ReadoutWeightsF32", "q8_gemv_f32",
@@ -33,6 +33,10 @@ class Q8Error(RuntimeError):
 class _Mat(C.Structure):
     _fields_ = [("data", C.c_void_p), ("rows", C.c_int), ("cols", C.c_int), ("ld", C.c_int), ("scale", C.c_float),
                 ("tiles", C.c_void_p)]
+
+
+class _Codes(C.Structure):
+    _fields_ = [("q", C.c_void_p), ("scale", C.c_void_p), ("ld", C.c_int), ("valid", C.c_int)]
 
 
 class _Taps(C.Structure):
@@ -87,6 +91,7 @@ def load_library():
         lib.q8_attention_q8.argtypes = [vp, C.POINTER(_Mat), C.POINTER(_Mat), vp, vp, ci, ci, vp, vp, vp]
         lib.gru_step_q8.argtypes = [vp, C.POINTER(_Gru), vp, vp, ci, vp, C.POINTER(_Taps)]
         lib.cgru_decoder_step_q8.argtypes = [vp, C.POINTER(_Cgru), vp, vp, ci, vp, vp, ci, vp, vp, vp, vp, C.POINTER(_Taps)]
+        lib.cgru_decoder_step_codes_q8.argtypes = lib.cgru_decoder_step_q8.argtypes + [C.POINTER(_Codes), C.POINTER(_Codes)]
         lib.output_logits_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, vp, ci, ci,
                                          vp, vp, vp, vp, vp, C.POINTER(_Taps)]
         lib.q8_encode.argtypes = [vp, C.POINTER(_Gru), C.POINTER(_Gru), vp, ci, vp]
@@ -98,6 +103,7 @@ def load_library():
         lib.q8_beam_result.argtypes = [vp, vp, ci, vp, ip, C.POINTER(C.c_float), ip, ip]
         lib.output_logits_beam_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, ci, ci, vp,
                                               vp, ci, vp, vp, vp]
+        lib.output_logits_beam_codes_q8.argtypes = lib.output_logits_beam_q8.argtypes + [C.POINTER(_Codes), C.POINTER(_Codes)]
         lib.q8_translate_bytes.restype = C.c_size_t
         lib.q8_translate_bytes.argtypes = [C.POINTER(_Model), ci, ci, ci, ci]
         lib.q8_translate.argtypes = [vp, C.POINTER(_Model), vp, ci, ci, ci, ci, vp, ip, C.POINTER(C.c_float), ip]
@@ -239,6 +245,19 @@ class ReadoutWeightsF32:
         self.c = _ReadoutF(W_s.c, W_y.c, W_c.c, b_t.data_ptr())
 
 
+class Codes:
+    """q8_codes: buffers for the int8 codes [n x ld] and scales [n] that one entry point leaves for the next."""
+
+    def __init__(self, ctx, n, ld):
+        self.q = ctx.empty(n, ld, dtype=torch.int8)
+        self.scale = ctx.empty(n)
+        self.c = _Codes(self.q.data_ptr(), self.scale.data_ptr(), ld, 0)
+
+    @property
+    def valid(self):
+        return bool(self.c.valid)
+
+
 class _Bound:
     """A call with its arguments already marshalled: launch() re-issues it on the same
     buffers (what a decode loop or a captured graph needs); results live in .out."""
@@ -367,8 +386,9 @@ def gru_step_q8(ctx, g, x, h_prev, h_out=None, taps=False):
     return (h_out, ts.t) if taps else h_out
 
 
-def cgru_decoder_step_q8(ctx, w, P, enc_h, y_emb, s_prev, out=None, taps=False, bind=False):
-    """Returns dict(s, ctx, alpha, s_mid) (+ 'taps': five entries)."""
+def cgru_decoder_step_q8(ctx, w, P, enc_h, y_emb, s_prev, out=None, taps=False, bind=False, codes=None):
+    """Returns dict(s, ctx, alpha, s_mid) (+ 'taps': five entries).  codes = (y, ctx) Codes objects:
+    cgru_decoder_step_codes_q8, which also leaves the codes of y_emb and of the context vectors there."""
     n, l = y_emb.shape[0], P.shape[0]
     H, Cd = w.r.H, w.q.Wx.cols
     o = out or {}
@@ -387,10 +407,14 @@ def cgru_decoder_step_q8(ctx, w, P, enc_h, y_emb, s_prev, out=None, taps=False, 
     r = {"s": s_out, "ctx": c_out, "alpha": alpha, "s_mid": s_mid}
     if taps:
         r["taps"] = ts.t
+    fn = ctx.lib.cgru_decoder_step_q8
+    if codes is not None:
+        fn = ctx.lib.cgru_decoder_step_codes_q8
+        args = args + (C.byref(codes[0].c), C.byref(codes[1].c))
     if bind:
-        r["keep"] = (w, P, enc_h, y_emb, s_prev)
-        return _Bound(ctx, ctx.lib.cgru_decoder_step_q8, args, r)
-    ctx.check(ctx.lib.cgru_decoder_step_q8(*args))
+        r["keep"] = (w, P, enc_h, y_emb, s_prev, codes)
+        return _Bound(ctx, fn, args, r)
+    ctx.check(fn(*args))
     return r
 
 
@@ -663,16 +687,21 @@ def q8_beam_result(ctx, state, max_steps):
     return np.array(out[:n.value], dtype=np.int32), np.float32(score.value), steps.value, bool(done.value)
 
 
-def output_logits_beam_q8(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, state, E_tgt, s_next, k=12, bind=False):
-    """Output layer + top-k + beam update; returns dict(topk_logp, topk_idx)."""
+def output_logits_beam_q8(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, state, E_tgt, s_next, k=12, bind=False, codes=None):
+    """Output layer + top-k + beam update; returns dict(topk_logp, topk_idx).  codes = (y, ctx) Codes
+    objects filled by cgru_decoder_step_q8(codes=...): output_logits_beam_codes_q8."""
     n = s.shape[0]
     lp = ctx.empty(n, k)
     idx = ctx.empty(n, k, dtype=torch.int32)
     args = (ctx.handle, C.byref(ro.c), C.byref(W_out.c), _ptr(b_out), _ptr(s), _ptr(y_emb), _ptr(ctx_vec), n, k,
             _ptr(state), _ptr(E_tgt), E_tgt.shape[1], _ptr(s_next), _ptr(lp), _ptr(idx))
     r = {"topk_logp": lp, "topk_idx": idx}
+    fn = ctx.lib.output_logits_beam_q8
+    if codes is not None:
+        fn = ctx.lib.output_logits_beam_codes_q8
+        args = args + (C.byref(codes[0].c), C.byref(codes[1].c))
     if bind:
-        r["keep"] = (ro, W_out, b_out, s, y_emb, ctx_vec, state, E_tgt, s_next)
-        return _Bound(ctx, ctx.lib.output_logits_beam_q8, args, r)
-    ctx.check(ctx.lib.output_logits_beam_q8(*args))
+        r["keep"] = (ro, W_out, b_out, s, y_emb, ctx_vec, state, E_tgt, s_next, codes)
+        return _Bound(ctx, fn, args, r)
+    ctx.check(fn(*args))
     return r

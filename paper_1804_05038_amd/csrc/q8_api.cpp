@@ -372,6 +372,22 @@ q8_status cgru_decoder_step_q8(q8_ctx *ctx, const q8_cgru_weights *w, const floa
                                const float *y_emb, const float *s_prev, int n_beam, float *s_out, float *ctx_out,
                                float *alpha_out, float *s_mid_out, const q8_taps *taps5)
 {
+    return cgru_decoder_step_codes_q8(ctx, w, P, enc_h, l, y_emb, s_prev, n_beam, s_out, ctx_out, alpha_out, s_mid_out,
+                                      taps5, nullptr, nullptr);
+}
+
+static bool codes_usable(const q8_codes *c, int ld)
+{
+    return c && c->q && c->scale && c->ld == ld && aligned16(c->q);
+}
+
+q8_status cgru_decoder_step_codes_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h, int l,
+                                     const float *y_emb, const float *s_prev, int n_beam, float *s_out, float *ctx_out,
+                                     float *alpha_out, float *s_mid_out, const q8_taps *taps5, q8_codes *y_codes,
+                                     q8_codes *ctx_codes)
+{
+    if (y_codes) y_codes->valid = 0;
+    if (ctx_codes) ctx_codes->valid = 0;
     if (!ctx) return Q8_ERR_NULL;
     if (!w) return q8_fail(ctx, Q8_ERR_NULL, "weights: NULL");
     TRY(check_gru(ctx, &w->r, "r"));
@@ -398,10 +414,14 @@ q8_status cgru_decoder_step_q8(q8_ctx *ctx, const q8_cgru_weights *w, const floa
     int8_t *cq = cv.take<int8_t>((size_t)n * w->q.Wx.ld);      // codes and scales of the context vectors,
     float *cqs = cv.take<float>(n);                             // from the attention kernel to GRU q
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "cgru_decoder_step_q8: workspace too small");
+    if (codes_usable(ctx_codes, w->q.Wx.ld)) { cq = ctx_codes->q; cqs = ctx_codes->scale; }    // the caller keeps them
+    const bool y_out = codes_usable(y_codes, w->r.Wx.ld);
 
     // Eq. 3: s' = r(y, s_prev)
-    q8i_gru_desc dr = {&w->r, y_emb, E, s_prev, H, nullptr, 0, s_mid, H, taps5};
+    q8i_gru_desc dr = {&w->r, y_emb, E, s_prev, H, nullptr, 0, s_mid, H, taps5, nullptr, nullptr,
+                       y_out ? y_codes->q : nullptr, y_out ? y_codes->scale : nullptr};
     TRY(q8i_gru(ctx, &dr, 1, n, Q8I_GRU_FULL));
+    if (y_out) y_codes->valid = 1;
     // everything that depends on s' alone: u(s') of Eq. 6 and the recurrent half of GRU q
     q8_mat qWh = w->q.Wh;
     q8i_gemv_desc dj[2] = {{&w->att_U, s_mid, H, nullptr, a, A, taps5 ? taps5 + 2 : nullptr},
@@ -415,6 +435,7 @@ q8_status cgru_decoder_step_q8(q8_ctx *ctx, const q8_cgru_weights *w, const floa
     if (taps5) { tq[0] = taps5[3]; tq[1].xq = nullptr; tq[1].xscale = nullptr; tq[1].acc = nullptr; }
     q8i_gru_desc dq = {&w->q, ctx_out, C, s_mid, H, ghq, 3 * H, s_out, H, taps5 ? tq : nullptr,
                        have_codes ? cq : nullptr, have_codes ? cqs : nullptr};
+    if (have_codes && codes_usable(ctx_codes, w->q.Wx.ld)) ctx_codes->valid = 1;
     return q8i_gru(ctx, &dq, 1, n, Q8I_GRU_GH_PRE);
 }
 
@@ -477,7 +498,8 @@ q8_status cgru_decoder_step_batch_q8(q8_ctx *ctx, const q8_cgru_weights *w, cons
 static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
                              const float *s, const float *y_emb, const float *ctx_vec, const float *t_in, int n_beam,
                              int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx, float *t_out,
-                             const q8_taps *taps4, const q8i_beam_desc *beam)
+                             const q8_taps *taps4, const q8i_beam_desc *beam, const q8_codes *y_codes = nullptr,
+                             const q8_codes *ctx_codes = nullptr)
 {
     if (!ctx) return Q8_ERR_NULL;
     TRY(check_mat(ctx, W_out, "W_out"));
@@ -548,7 +570,7 @@ static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8
     if (ro) {
         float *t = t_out ? t_out : cv.take<float>((size_t)n * R);
         if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
-        TRY(q8i_readout(ctx, ro, s, y_emb, ctx_vec, n, t, taps4));
+        TRY(q8i_readout(ctx, ro, s, y_emb, ctx_vec, n, t, taps4, y_codes, ctx_codes));
         T = t;
     }
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
@@ -565,9 +587,10 @@ q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_m
                        t_out, taps4, nullptr);
 }
 
-q8_status output_logits_beam_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
-                                const float *s, float *y_emb, const float *ctx_vec, int n_beam, int k, void *state,
-                                const float *E_tgt, int E, float *s_next, float *topk_logp, int32_t *topk_idx)
+q8_status output_logits_beam_codes_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                                      const float *s, float *y_emb, const float *ctx_vec, int n_beam, int k, void *state,
+                                      const float *E_tgt, int E, float *s_next, float *topk_logp, int32_t *topk_idx,
+                                      const q8_codes *y_codes, const q8_codes *ctx_codes)
 {
     if (!ctx) return Q8_ERR_NULL;
     if (!ro || !state || !E_tgt || !s_next || !s || !y_emb)
@@ -578,7 +601,15 @@ q8_status output_logits_beam_q8(q8_ctx *ctx, const q8_readout_weights *ro, const
     if (E != ro->W_y.cols) return q8_fail(ctx, Q8_ERR_SHAPE, "E does not match the readout's embedding width");
     q8i_beam_desc bd = {state, s, E_tgt, y_emb, s_next, E, ro->W_s.cols};
     return output_impl(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, nullptr, n_beam, k, nullptr, nullptr, topk_logp,
-                       topk_idx, nullptr, nullptr, &bd);
+                       topk_idx, nullptr, nullptr, &bd, y_codes, ctx_codes);
+}
+
+q8_status output_logits_beam_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                                const float *s, float *y_emb, const float *ctx_vec, int n_beam, int k, void *state,
+                                const float *E_tgt, int E, float *s_next, float *topk_logp, int32_t *topk_idx)
+{
+    return output_logits_beam_codes_q8(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, n_beam, k, state, E_tgt, E, s_next,
+                                       topk_logp, topk_idx, nullptr, nullptr);
 }
 
 q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights *bwd, const float *X, int l,
@@ -726,7 +757,7 @@ q8_status q8_beam_result(q8_ctx *ctx, const void *state, int max_steps, int32_t 
 
 namespace {
 struct TranslateBufs {
-    size_t X, enc_h, P, y, s0, s1, cv, lp, idx, tok, state, total;
+    size_t X, enc_h, P, y, s0, s1, cv, lp, idx, tok, state, yq, ys, cq, cs, total;
 };
 TranslateBufs translate_layout(const q8_model *m, int l, int beam, int k, int max_steps)
 {
@@ -739,6 +770,9 @@ TranslateBufs translate_layout(const q8_model *m, int l, int beam, int k, int ma
     b.cv = take((size_t)beam * C * 4); b.lp = take((size_t)beam * k * 4); b.idx = take((size_t)beam * k * 4);
     b.tok = take((size_t)l * 4);
     b.state = take(q8i_beam_state_bytes(max_steps));
+    // codes of y and of the context vectors, handed from the decoder step to the output layer
+    b.yq = take((size_t)beam * m->dec.r.Wx.ld); b.ys = take((size_t)beam * 4);
+    b.cq = take((size_t)beam * m->dec.q.Wx.ld); b.cs = take((size_t)beam * 4);
     b.total = o;
     return b;
 }
@@ -776,6 +810,8 @@ q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens
     float *cv = (float *)(top + b.cv), *lp = (float *)(top + b.lp);
     int32_t *idx = (int32_t *)(top + b.idx);
     void *state = top + b.state;
+    q8_codes yc = {(int8_t *)(top + b.yq), (float *)(top + b.ys), m->dec.r.Wx.ld, 0};
+    q8_codes cc = {(int8_t *)(top + b.cq), (float *)(top + b.cs), m->dec.q.Wx.ld, 0};
     ctx->ws_reserved_top = ctx->ws_bytes - (size_t)(top - ctx->ws);
 
     q8_status st = q8i_gather_rows(ctx, m->E_src, src_tokens, l, E, X);                        // x_i of Eq. 1
@@ -785,11 +821,12 @@ q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens
     if (!st) st = q8i_beam_init(ctx, state, beam, max_steps, enc_h, m->E_tgt, E, H, y, s[0]);
     int cur = 0, done = 0;
     for (int t = 0; t < max_steps && !st && !done; ++t) {
-        st = cgru_decoder_step_q8(ctx, &m->dec, P, enc_h, l, y, s[cur], beam, s[cur ^ 1], cv, nullptr, nullptr, nullptr);
+        st = cgru_decoder_step_codes_q8(ctx, &m->dec, P, enc_h, l, y, s[cur], beam, s[cur ^ 1], cv, nullptr, nullptr, nullptr,
+                                        &yc, &cc);
         // output layer, top-k and (in the selection kernel's last block) the beam update, which
         // gathers the surviving states from s[cur ^ 1] into s[cur] and the new embeddings into y
-        if (!st) st = output_logits_beam_q8(ctx, &m->ro, &m->W_out, m->b_out, s[cur ^ 1], y, cv, beam, k, state,
-                                            m->E_tgt, E, s[cur], lp, idx);
+        if (!st) st = output_logits_beam_codes_q8(ctx, &m->ro, &m->W_out, m->b_out, s[cur ^ 1], y, cv, beam, k, state,
+                                                  m->E_tgt, E, s[cur], lp, idx, &yc, &cc);
         if (!st && (t % 8 == 7))
             st = q8i_beam_read(ctx, state, max_steps, nullptr, nullptr, nullptr, nullptr, &done);
     }

@@ -219,6 +219,9 @@ struct ReadoutArgs {
     q8_taps ts, ty, tc;
     int R, H, E, C, lds, ldy, ldc, lpr;
     float ss_w, sy_w, sc_w;
+    // fast kernel with PRE: codes [n x ldy], [n x ldc] (pad bytes zero) and scales [n] of y and c from their producers
+    const int8_t *yq_pre, *cq_pre;
+    const float *ys_pre, *cs_pre;
 };
 
 template <int N>
@@ -288,8 +291,10 @@ __global__ __launch_bounds__(256) void readout_kernel(ReadoutArgs a)
 }
 
 // Rows of at most 1024 * CH bytes, dims % 4 == 0, one output unit per wave: everything is
-// requested up front, then quantized and dotted.
-template <int N, int CH>
+// requested up front, then quantized and dotted.  PRE: y and c arrive as the codes and scales
+// their producers left (the GRU that multiplied y at the start of the step, the attention block
+// that finished c); they are copied into LDS and s alone is quantized here.
+template <int N, int CH, bool PRE>
 __global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
 {
     extern __shared__ __align__(16) int8_t smem[];
@@ -301,10 +306,30 @@ __global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
     const int unit = blockIdx.x * 4 + wave;
     const bool ok = unit < a.R;
 
+    // PRE: the codes as 16-byte pieces (thread tid takes pieces tid, tid + 256, ... of each input; a piece
+    // past the end reads as zero through the descriptor) and the scales, requested first
+    constexpr int NPRE = PRE ? (N * CH * 64 + 255) / 256 : 1;
+    v4i pre_y[NPRE], pre_c[NPRE];
+    float pre_sy = 0.0f, pre_sc = 0.0f;      // thread j < N: the scales of vector j
+    if (PRE) {
+        const int t = threadIdx.x;
+        const int so = (int)(t < N ? (unsigned)t * 4u : Q8_OOB);
+        pre_sy = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(q8_rsrc(a.ys_pre, (size_t)N * sizeof(float)), so, 0, 0));
+        pre_sc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(q8_rsrc(a.cs_pre, (size_t)N * sizeof(float)), so, 0, 0));
+        const __amdgpu_buffer_rsrc_t ry = q8_rsrc(a.yq_pre, (size_t)N * a.ldy), rc = q8_rsrc(a.cq_pre, (size_t)N * a.ldc);
+#pragma unroll
+        for (int u = 0; u < NPRE; ++u) {
+            pre_y[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(ry, (u * 256 + t) * 16, 0, 0));
+            pre_c[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rc, (u * 256 + t) * 16, 0, 0));
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
     XRegs<N, CH> rin[3];                     // s, y, ctx
     x_load<N, CH>(rin[0], a.s, N, a.H, a.H);
-    x_load<N, CH>(rin[1], a.y, N, a.E, a.E);
-    x_load<N, CH>(rin[2], a.c, N, a.C, a.C);
+    if (!PRE) {
+        x_load<N, CH>(rin[1], a.y, N, a.E, a.E);
+        x_load<N, CH>(rin[2], a.c, N, a.C, a.C);
+    }
     v4i ws[1][CH], wy[1][CH], wc[1][CH];
     {
         const int row[1] = {ok ? unit : -1};
@@ -314,7 +339,16 @@ __global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
     }
     const float bt = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
         q8_rsrc(a.b_t, a.b_t ? (size_t)a.R * sizeof(float) : 0), (int)(ok ? (unsigned)unit * 4u : Q8_OOB), 0, 0));
-    {
+    if (PRE) {
+#pragma unroll
+        for (int u = 0; u < NPRE; ++u) {
+            const int o = (u * 256 + (int)threadIdx.x) * 16;
+            if (o < N * a.ldy) *(v4i *)(yq + o) = pre_y[u];
+            if (o < N * a.ldc) *(v4i *)(cq + o) = pre_c[u];
+        }
+        if (threadIdx.x < N) { s_scale[8 + threadIdx.x] = pre_sy; s_scale[16 + threadIdx.x] = pre_sc; }
+        x_finish<N, CH>(rin[0], N, a.lds, sq, s_scale, s_red);       // scales of s in s_scale[0, N); ends with a barrier
+    } else {
         const int lds3[3] = {a.lds, a.ldy, a.ldc};
         int8_t *const dst[3] = {sq, yq, cq};
         x_finish_multi<N, CH, 3>(rin, lds3, dst, s_scale, s_red);
@@ -414,17 +448,24 @@ q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, 
 }
 
 template <int N>
-static void launch_readout_n(q8_ctx *ctx, const ReadoutArgs &a, int blocks, size_t smem, int ch)
+static void launch_readout_n(q8_ctx *ctx, const ReadoutArgs &a, int blocks, size_t smem, int ch, bool pre)
 {
-    if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_fast_kernel<N, 1>), dim3(blocks), dim3(256), smem, a);
-    else if (ch == 2) Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_fast_kernel<N, 2>), dim3(blocks), dim3(256), smem, a);
+    if (ch == 1 && pre) Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_fast_kernel<N, 1, true>), dim3(blocks), dim3(256), smem, a);
+    else if (ch == 2 && pre) Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_fast_kernel<N, 2, true>), dim3(blocks), dim3(256), smem, a);
+    else if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_fast_kernel<N, 1, false>), dim3(blocks), dim3(256), smem, a);
+    else if (ch == 2) Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_fast_kernel<N, 2, false>), dim3(blocks), dim3(256), smem, a);
     else Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, readout_kernel<N>, dim3(blocks), dim3(256), smem, a);
 }
 
 q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,
-                      float *t_out, const q8_taps *taps3)
+                      float *t_out, const q8_taps *taps3, const q8_codes *y_codes, const q8_codes *c_codes)
 {
     ReadoutArgs a;
+    // codes from the producers: both or neither, and only in the layout the kernel copies (the matrices' own pitches)
+    const bool pre = y_codes && c_codes && y_codes->valid && c_codes->valid && y_codes->q && c_codes->q && y_codes->scale &&
+                     c_codes->scale && y_codes->ld == ro->W_y.ld && c_codes->ld == ro->W_c.ld;
+    a.yq_pre = pre ? y_codes->q : nullptr; a.cq_pre = pre ? c_codes->q : nullptr;
+    a.ys_pre = pre ? y_codes->scale : nullptr; a.cs_pre = pre ? c_codes->scale : nullptr;
     a.Ws = ro->W_s.data; a.Wy = ro->W_y.data; a.Wc = ro->W_c.data; a.b_t = ro->b_t;
     a.s = s; a.y = y; a.c = c; a.t_out = t_out;
     q8_taps none = {nullptr, nullptr, nullptr};
@@ -443,14 +484,14 @@ q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s,
     const int blocks = (a.R + upb - 1) / upb;
     const size_t smem = (size_t)n * (a.lds + a.ldy + a.ldc);
     switch (n) {
-    case 1: launch_readout_n<1>(ctx, a, blocks, smem, ch); break;
-    case 2: launch_readout_n<2>(ctx, a, blocks, smem, ch); break;
-    case 3: launch_readout_n<3>(ctx, a, blocks, smem, ch); break;
-    case 4: launch_readout_n<4>(ctx, a, blocks, smem, ch); break;
-    case 5: launch_readout_n<5>(ctx, a, blocks, smem, ch); break;
-    case 6: launch_readout_n<6>(ctx, a, blocks, smem, ch); break;
-    case 7: launch_readout_n<7>(ctx, a, blocks, smem, ch); break;
-    default: launch_readout_n<8>(ctx, a, blocks, smem, ch); break;
+    case 1: launch_readout_n<1>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
+    case 2: launch_readout_n<2>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
+    case 3: launch_readout_n<3>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
+    case 4: launch_readout_n<4>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
+    case 5: launch_readout_n<5>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
+    case 6: launch_readout_n<6>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
+    case 7: launch_readout_n<7>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
+    default: launch_readout_n<8>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
     }
     return q8i_launch_check(ctx, "readout");
 }

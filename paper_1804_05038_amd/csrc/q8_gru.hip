@@ -14,6 +14,8 @@ struct GruJob {
     const float *x, *h_prev, *g_pre;
     const int8_t *xq_pre;      // GH_PRE, kernels with XPRE: codes [N x ldwx] and scales [N] of x from its producer
     const float *xs_pre;
+    int8_t *xq_out;            // may be NULL: where block 0 leaves the codes [N x ldwx] and scales [N] of x for a later consumer
+    float *xs_out;
     float *h_out;
     q8_taps tx, th;
     int I, ldwx, H, ldwh, ldx, ldh, ldo, ldg, lpr;
@@ -36,6 +38,15 @@ __device__ __forceinline__ void gru_x_taps(const GruJob &J, const int8_t *xq, co
             for (int e = threadIdx.x; e < N * J.H; e += blockDim.x) J.th.xq[e] = hq[(e / J.H) * J.ldwh + e % J.H];
         if (J.th.xscale && threadIdx.x < N) J.th.xscale[threadIdx.x] = s_scale[8 + threadIdx.x];
     }
+}
+
+// Block 0 hands the codes and scales of x on to whoever multiplies the same vectors next.
+template <int N>
+__device__ __forceinline__ void gru_x_export(const GruJob &J, const int8_t *xq, const float *s_scale)
+{
+    if (!J.xq_out) return;
+    for (int p = threadIdx.x; p < N * J.ldwx / 16; p += blockDim.x) *(v4i *)(J.xq_out + 16 * p) = *(const v4i *)(xq + 16 * p);
+    if (threadIdx.x < N) J.xs_out[threadIdx.x] = s_scale[threadIdx.x];
 }
 
 // Gates of one hidden unit from its six pre-activations (fp32, one operation per
@@ -69,6 +80,7 @@ __global__ __launch_bounds__(256) void gru_kernel(GruJobs jobs)
     if (MODE != GRU_GX_PRE) block_quantize<N>(J.x, N, J.I, J.ldx, J.ldwx, xq, s_scale, s_red);
     if (MODE != GRU_GH_PRE) block_quantize<N>(J.h_prev, N, H, J.ldh, J.ldwh, hq, s_scale + 8, s_red);
     if (blockIdx.x == 0) gru_x_taps<N, MODE>(J, xq, hq, s_scale);
+    if (blockIdx.x == 0 && MODE != GRU_GX_PRE) gru_x_export<N>(J, xq, s_scale);
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int lpr = J.lpr, lir = lane & (lpr - 1), sg = lane / lpr, upw = 64 / lpr;
@@ -227,6 +239,7 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
         x_finish<N, CH>(hr, N, J.ldwh, hq, s_scale + 8, s_red);
     }
     if (blockIdx.x == 0) gru_x_taps<N, MODE>(J, xq, hq, s_scale);
+    if (blockIdx.x == 0 && MODE != GRU_GX_PRE) gru_x_export<N>(J, xq, s_scale);
 
     // partial sums of the unit's rows against every vector, totalled over the wave in one pass;
     // lane j < N receives the totals of vector j: [0, 3) input product, [3, 6) recurrent product
@@ -500,6 +513,7 @@ q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode
         J.Wx = g->Wx.data; J.Wh = g->Wh.data; J.bx = g->bx; J.bh = g->bh;
         J.x = d[t].x; J.h_prev = d[t].h_prev; J.g_pre = d[t].g_pre; J.h_out = d[t].h_out;
         J.xq_pre = d[t].xq_pre; J.xs_pre = d[t].xs_pre;
+        J.xq_out = d[t].xs_out ? d[t].xq_out : nullptr; J.xs_out = d[t].xs_out;
         if (!J.xq_pre || !J.xs_pre) xpre = false;
         q8_taps none = {nullptr, nullptr, nullptr};
         J.tx = d[t].taps ? d[t].taps[0] : none;

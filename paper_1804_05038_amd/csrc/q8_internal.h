@@ -84,6 +84,9 @@ struct q8i_gru_desc {
     // GH_PRE only, may be NULL: codes [n x Wx.ld] (pad bytes zero) and scales [n] of x, left by its producer
     const int8_t *xq_pre;
     const float *xs_pre;
+    // not GX_PRE, may be NULL: where the codes [n x Wx.ld] and scales [n] of x are left for a later consumer
+    int8_t *xq_out;
+    float *xs_out;
 };
 
 // beam update run by the last block of the selection kernel (NULL = none)
@@ -160,8 +163,10 @@ q8_status q8i_beam_batch(q8_ctx *ctx, int init, void *states, size_t stride, int
                          int H, float *y_emb, float *s_next, int *done, const float *enc_h, const int *sent_off, int C);
 q8_status q8i_beam_read_batch(q8_ctx *ctx, const void *states, size_t stride, int S, int max_steps, int32_t *tokens_host,
                               int *len_host, float *score_host, int *steps_host);
+// y_codes / c_codes (may be NULL): codes of y and c left by their producers; used when both are valid and laid out
+// with the pitches of W_y and W_c
 q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,
-                      float *t_out, const q8_taps *taps3);
+                      float *t_out, const q8_taps *taps3, const q8_codes *y_codes = nullptr, const q8_codes *c_codes = nullptr);
 q8_status q8i_probe_read(q8_ctx *ctx, const void *buf, size_t bytes);
 int q8i_out_tiles(int V);
 size_t q8i_tiles_bytes(int rows, int ld);

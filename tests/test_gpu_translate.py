@@ -253,3 +253,45 @@ def test_translate_ensemble_full_size(q, ctx, oracle):
     r_toks, r_score, r_steps = oracle.translate_ensemble(refs, src, beam=5, topk=12, max_steps=3)
     assert toks.tolist() == r_toks.tolist() and steps == r_steps
     assert abs(float(score) - float(r_score)) <= 1e-5 * max(1.0, abs(float(r_score)))
+
+
+@pytest.mark.parametrize("dims,n,l", [(dict(), 5, 30), (dict(), 1, 7), (dict(), 8, 60),
+                                      (dict(V=33658, E=620, H=1000, A=1000, R=620), 5, 12),
+                                      (dict(V=50, E=32, H=48, A=40, R=24, w_std=0.3), 3, 5)])
+def test_codes_travel_from_the_decoder_step_to_the_output_layer(q, ctx, oracle, dims, n, l):
+    """cgru_decoder_step_codes_q8 + output_logits_beam_codes_q8 against the plain calls (identical bits)
+    and the codes they hand over against the oracle's quantization of the same fp32 vectors."""
+    p = synth.full_model(seed=11, **dims)
+    m = q.Model.from_params(ctx, p)
+    E, H = m.E_tgt.shape[1], m.dec.r.H
+    rng = np.random.default_rng(n + l)
+    enc_h = ctx.f32(rng.standard_normal((l, 2 * H)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    y = ctx.f32(rng.standard_normal((n, E)).astype(np.float32))
+    s = ctx.f32(rng.standard_normal((n, H)).astype(np.float32))
+    s0 = ctx.f32(rng.standard_normal(H).astype(np.float32))
+    res = []
+    for use in (False, True):
+        st = torch.zeros(q.q8_beam_state_bytes(20), dtype=torch.uint8, device=ctx.device)
+        yy, ss = y.clone(), s.clone()
+        q.q8_beam_init(ctx, st, n, 20, s0, m.E_tgt, yy, ss)
+        yy.copy_(y); ss.copy_(s)
+        codes = (q.Codes(ctx, n, m.dec.r.Wx.ld), q.Codes(ctx, n, m.dec.q.Wx.ld)) if use else None
+        r1 = q.cgru_decoder_step_q8(ctx, m.dec, P, enc_h, yy, ss, codes=codes)
+        if use:
+            assert codes[0].valid and codes[1].valid
+            for c, X in ((codes[0], y), (codes[1], r1["ctx"])):
+                for j in range(n):
+                    xq, xs = oracle.quantize(np_(X)[j])
+                    K = X.shape[1]
+                    assert_same(c.q[j, :K], xq, "codes of vector %d" % j)
+                    assert not np_(c.q[j, K:]).any() and float(c.scale[j]) == float(xs)
+        r2 = q.output_logits_beam_q8(ctx, m.ro, m.W_out, m.b_out, r1["s"], yy, r1["ctx"], st, m.E_tgt, ss, k=12, codes=codes)
+        res.append((r1["s"], r1["ctx"], r2["topk_logp"], r2["topk_idx"], yy, ss))
+    for a, b, what in zip(res[0], res[1], ("s", "ctx", "topk_logp", "topk_idx", "y_emb", "s_next")):
+        assert_same(b, np_(a), what + ": with codes against without")
+    # codes of another pitch are ignored, not misread
+    bad = (q.Codes(ctx, n, m.dec.r.Wx.ld + 16), q.Codes(ctx, n, m.dec.q.Wx.ld + 16))
+    r1 = q.cgru_decoder_step_q8(ctx, m.dec, P, enc_h, y.clone(), s.clone(), codes=bad)
+    assert not bad[0].valid and not bad[1].valid
+    assert_same(r1["s"], np_(res[0][0]), "s with unusable code buffers")
