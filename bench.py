@@ -283,9 +283,12 @@ def batched_decoding(torch, q, m, rng, steps, sizes=(16, 64, 200), translate=Tru
         y, s = ctx.empty(n, 512), ctx.empty(n, 1024)
         done = torch.zeros(S, dtype=torch.int32, device=ctx.device)
         c0 = q.q8_beam_init_batch(ctx, states, S, BEAM, MAX_STEPS, enc_h, off, m.E_tgt, y, s, done, bind=True)
-        c1 = q.cgru_decoder_step_batch_q8(ctx, m.dec, P, enc_h, off, BEAM, L, y, s, bind=True)
+        # codes of y, of the context vectors and of the new states travel from the step to the output layer
+        codes = None if os.environ.get("Q8_BENCH_NO_CODES") else (
+            q.Codes(ctx, n, m.dec.r.Wx.ld), q.Codes(ctx, n, m.dec.q.Wx.ld), q.Codes(ctx, n, m.ro.W_s.ld))
+        c1 = q.cgru_decoder_step_batch_q8(ctx, m.dec, P, enc_h, off, BEAM, L, y, s, bind=True, codes=codes)
         c2 = q.output_logits_q8(ctx, m.ro, m.W_out, m.b_out, s=c1.out["s"], y_emb=y, ctx_vec=c1.out["ctx"], k=TOPK,
-                                want_logits=False, bind=True)
+                                want_logits=False, bind=True, codes=codes)
         c3 = q.q8_beam_update_batch(ctx, states, S, BEAM, MAX_STEPS, c2.out["topk_logp"], c2.out["topk_idx"],
                                     c1.out["s"], m.E_tgt, y, s, done, bind=True)
         t = [0]

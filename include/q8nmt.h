@@ -307,6 +307,23 @@ q8_status output_logits_beam_codes_q8(q8_ctx *ctx, const q8_readout_weights *ro,
                                       float *topk_logp, int32_t *topk_idx, const q8_codes *y_codes,
                                       const q8_codes *ctx_codes);
 
+/* The same for panels of hypothesis slots: cgru_decoder_step_batch_codes_q8 is
+ * cgru_decoder_step_batch_q8 and also leaves the codes of y_emb (pitch r.Wx.ld), of the context
+ * vectors (pitch q.Wx.ld) and of the new states s_out (any pitch ld >= H that is a multiple of
+ * 16: the readout's W_s.ld) with the caller; output_logits_codes_q8 is output_logits_q8 with the
+ * readout (ro must not be NULL, no taps) and takes the three: when all are valid and have the
+ * pitches of W_s, W_y and W_c, a panel of more than 8 slots skips its quantization launch; up to
+ * 8 slots use y and the context as output_logits_beam_codes_q8 does.  Bit-identical results. */
+q8_status cgru_decoder_step_batch_codes_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h,
+                                           const int32_t *sent_off, int n_sent, int beam, int max_l,
+                                           const float *y_emb, const float *s_prev, float *s_out, float *ctx_out,
+                                           float *alpha_out, float *s_mid_out, q8_codes *y_codes,
+                                           q8_codes *ctx_codes, q8_codes *s_codes);
+q8_status output_logits_codes_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                                 const float *s, const float *y_emb, const float *ctx_vec, int n_beam, int k,
+                                 float *logits, float *lse, float *topk_logp, int32_t *topk_idx, float *t_out,
+                                 const q8_codes *s_codes, const q8_codes *y_codes, const q8_codes *ctx_codes);
+
 /* Waits for the stream and copies the result to the host: tokens (without the final
  * token 0), their number, the cumulative log-probability, the steps made, and whether
  * the search is over.  Host pointers; any may be NULL. */

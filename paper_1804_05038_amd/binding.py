@@ -110,6 +110,9 @@ def load_library():
         lib.q8_profile_begin.argtypes = [vp, ci, ci]
         lib.q8_probe_read.argtypes = [vp, vp, C.c_size_t]
         lib.cgru_decoder_step_batch_q8.argtypes = [vp, C.POINTER(_Cgru), vp, vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp]
+        lib.cgru_decoder_step_batch_codes_q8.argtypes = lib.cgru_decoder_step_batch_q8.argtypes + [C.POINTER(_Codes)] * 3
+        lib.output_logits_codes_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, ci, ci,
+                                               vp, vp, vp, vp, vp] + [C.POINTER(_Codes)] * 3
         lib.q8_gemv_f32.argtypes = [vp, C.POINTER(_MatF), vp, ci, ci, vp, vp, ci]
         lib.cgru_decoder_step_f32.argtypes = [vp, C.POINTER(_CgruF), vp, vp, ci, vp, vp, ci, vp, vp, vp, vp]
         lib.output_logits_f32.argtypes = [vp, C.POINTER(_ReadoutF), C.POINTER(_MatF), vp, vp, vp, vp, ci, ci, vp, vp, vp, vp, vp]
@@ -418,9 +421,10 @@ def cgru_decoder_step_q8(ctx, w, P, enc_h, y_emb, s_prev, out=None, taps=False, 
     return r
 
 
-def cgru_decoder_step_batch_q8(ctx, w, P, enc_h, sent_off, beam, max_l, y_emb, s_prev, out=None, bind=False):
+def cgru_decoder_step_batch_q8(ctx, w, P, enc_h, sent_off, beam, max_l, y_emb, s_prev, out=None, bind=False, codes=None):
     """Decoder step for len(sent_off) - 1 sentences side by side; sent_off: device int32 offsets
-    into P / enc_h.  Returns dict(s, ctx, alpha [n x max_l], s_mid)."""
+    into P / enc_h.  Returns dict(s, ctx, alpha [n x max_l], s_mid).  codes = (y, ctx, s) Codes objects:
+    cgru_decoder_step_batch_codes_q8, which leaves the three sets of codes there."""
     n = y_emb.shape[0]
     S = sent_off.shape[0] - 1
     assert n == S * beam
@@ -433,16 +437,21 @@ def cgru_decoder_step_batch_q8(ctx, w, P, enc_h, sent_off, beam, max_l, y_emb, s
     args = (ctx.handle, C.byref(w.c), _ptr(P), _ptr(enc_h), _ptr(sent_off), S, beam, max_l, _ptr(y_emb), _ptr(s_prev),
             _ptr(s_out), _ptr(c_out), _ptr(alpha), _ptr(s_mid))
     r = {"s": s_out, "ctx": c_out, "alpha": alpha, "s_mid": s_mid}
+    fn = ctx.lib.cgru_decoder_step_batch_q8
+    if codes is not None:
+        fn = ctx.lib.cgru_decoder_step_batch_codes_q8
+        args = args + tuple(C.byref(c.c) for c in codes)
     if bind:
-        r["keep"] = (w, P, enc_h, sent_off, y_emb, s_prev)
-        return _Bound(ctx, ctx.lib.cgru_decoder_step_batch_q8, args, r)
-    ctx.check(ctx.lib.cgru_decoder_step_batch_q8(*args))
+        r["keep"] = (w, P, enc_h, sent_off, y_emb, s_prev, codes)
+        return _Bound(ctx, fn, args, r)
+    ctx.check(fn(*args))
     return r
 
 
 def output_logits_q8(ctx, ro, W_out, b_out, s=None, y_emb=None, ctx_vec=None, t_in=None, k=12,
-                     want_logits=True, taps=False, bind=False):
-    """Returns dict(logits?, lse, topk_logp, topk_idx, t?) (+ 'taps': four entries)."""
+                     want_logits=True, taps=False, bind=False, codes=None):
+    """Returns dict(logits?, lse, topk_logp, topk_idx, t?) (+ 'taps': four entries).  codes = (y, ctx, s)
+    Codes objects from cgru_decoder_step_batch_q8(codes=...): output_logits_codes_q8 (needs ro, no taps)."""
     n = (t_in if ro is None else s).shape[0]
     V, R = W_out.rows, W_out.cols
     logits = ctx.empty(n, V) if want_logits else None
@@ -463,10 +472,17 @@ def output_logits_q8(ctx, ro, W_out, b_out, s=None, y_emb=None, ctx_vec=None, t_
     r = {"logits": logits, "lse": lse, "topk_logp": lp, "topk_idx": idx, "t": t_out}
     if taps:
         r["taps"] = ts.t
+    fn = ctx.lib.output_logits_q8
+    if codes is not None:
+        assert ro is not None and not taps
+        fn = ctx.lib.output_logits_codes_q8
+        args = (ctx.handle, C.byref(ro.c), C.byref(W_out.c), _ptr(b_out), _ptr(s), _ptr(y_emb), _ptr(ctx_vec), n, k,
+                _ptr(logits), _ptr(lse), _ptr(lp), _ptr(idx), _ptr(t_out),
+                C.byref(codes[2].c), C.byref(codes[0].c), C.byref(codes[1].c))
     if bind:
-        r["keep"] = (ro, W_out, b_out, s, y_emb, ctx_vec, t_in)
-        return _Bound(ctx, ctx.lib.output_logits_q8, args, r)
-    ctx.check(ctx.lib.output_logits_q8(*args))
+        r["keep"] = (ro, W_out, b_out, s, y_emb, ctx_vec, t_in, codes)
+        return _Bound(ctx, fn, args, r)
+    ctx.check(fn(*args))
     return r
 
 

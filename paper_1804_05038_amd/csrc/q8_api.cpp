@@ -73,15 +73,22 @@ struct PanelCodesOut {
     int8_t *q2; int ld2; float *s2;
 };
 
+// whether a caller's code buffers can hold the codes of vectors multiplied by a matrix of pitch ld
+bool codes_usable(const q8_codes *c, int ld)
+{
+    return c && c->q && c->scale && c->ld == ld && aligned16(c->q);
+}
+
 // xq_pre / xs_pre (with gh_pre only): x arrives quantized.  out: the gates kernel also quantizes h_out.
 q8_status gru_panel(q8_ctx *ctx, Carver &cv, const q8_gru_weights *g, const float *x, const float *h_prev, int n,
                     const float *gh_pre, float *h_out, const q8_taps *taps2, const int8_t *xq_pre = nullptr,
-                    const float *xs_pre = nullptr, const PanelCodesOut *out = nullptr)
+                    const float *xs_pre = nullptr, const PanelCodesOut *out = nullptr, const q8_codes *x_keep = nullptr)
 {
     const int I = g->Wx.cols, H = g->Wh.cols;
     const bool have_x = gh_pre && xq_pre && xs_pre && !taps2;
     int8_t *xq = have_x ? nullptr : cv.take<int8_t>((size_t)n * g->Wx.ld), *hq = gh_pre ? nullptr : cv.take<int8_t>((size_t)n * g->Wh.ld);
     float *xs = have_x ? nullptr : cv.take<float>(n), *hs = cv.take<float>(n);
+    if (!have_x && x_keep) { xq = x_keep->q; xs = x_keep->scale; }       // x's codes stay with the caller (pitch checked there)
     float *gx = cv.take<float>((size_t)n * 3 * H), *gh = gh_pre ? nullptr : cv.take<float>((size_t)n * 3 * H);
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "GRU panel: workspace too small");
     if (!have_x) {
@@ -376,11 +383,6 @@ q8_status cgru_decoder_step_q8(q8_ctx *ctx, const q8_cgru_weights *w, const floa
                                       taps5, nullptr, nullptr);
 }
 
-static bool codes_usable(const q8_codes *c, int ld)
-{
-    return c && c->q && c->scale && c->ld == ld && aligned16(c->q);
-}
-
 q8_status cgru_decoder_step_codes_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h, int l,
                                      const float *y_emb, const float *s_prev, int n_beam, float *s_out, float *ctx_out,
                                      float *alpha_out, float *s_mid_out, const q8_taps *taps5, q8_codes *y_codes,
@@ -443,6 +445,18 @@ q8_status cgru_decoder_step_batch_q8(q8_ctx *ctx, const q8_cgru_weights *w, cons
                                      const int32_t *sent_off, int n_sent, int beam, int max_l, const float *y_emb,
                                      const float *s_prev, float *s_out, float *ctx_out, float *alpha_out, float *s_mid_out)
 {
+    return cgru_decoder_step_batch_codes_q8(ctx, w, P, enc_h, sent_off, n_sent, beam, max_l, y_emb, s_prev, s_out, ctx_out,
+                                            alpha_out, s_mid_out, nullptr, nullptr, nullptr);
+}
+
+q8_status cgru_decoder_step_batch_codes_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h,
+                                           const int32_t *sent_off, int n_sent, int beam, int max_l, const float *y_emb,
+                                           const float *s_prev, float *s_out, float *ctx_out, float *alpha_out,
+                                           float *s_mid_out, q8_codes *y_codes, q8_codes *ctx_codes, q8_codes *s_codes)
+{
+    if (y_codes) y_codes->valid = 0;
+    if (ctx_codes) ctx_codes->valid = 0;
+    if (s_codes) s_codes->valid = 0;
     if (!ctx) return Q8_ERR_NULL;
     if (!w) return q8_fail(ctx, Q8_ERR_NULL, "weights: NULL");
     TRY(check_gru(ctx, &w->r, "r"));
@@ -472,12 +486,16 @@ q8_status cgru_decoder_step_batch_q8(q8_ctx *ctx, const q8_cgru_weights *w, cons
     int8_t *cq = cv.take<int8_t>((size_t)n * w->q.Wx.ld);      // codes and scales of the context vectors,
     float *cqs = cv.take<float>(n);                             // from the attention kernel to GRU q
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "cgru_decoder_step_batch_q8: workspace too small");
+    if (codes_usable(ctx_codes, w->q.Wx.ld)) { cq = ctx_codes->q; cqs = ctx_codes->scale; }    // the caller keeps them
+    const bool y_keep = codes_usable(y_codes, w->r.Wx.ld);
     // Eq. 3: s' = r(y, s_prev); the gates kernel leaves s' quantized for the two products below
     const bool fused_codes = q8i_gru_gates_q_ok(H, H, H, w->att_U.ld, w->q.Wh.ld);
     {
         Carver sub = cv;
         const PanelCodesOut out = {mq_u, w->att_U.ld, ms_u, mq_h, w->q.Wh.ld, ms_h};
-        TRY(gru_panel(ctx, sub, &w->r, y_emb, s_prev, n, nullptr, s_mid, nullptr, nullptr, nullptr, fused_codes ? &out : nullptr));
+        TRY(gru_panel(ctx, sub, &w->r, y_emb, s_prev, n, nullptr, s_mid, nullptr, nullptr, nullptr, fused_codes ? &out : nullptr,
+                      y_keep ? y_codes : nullptr));
+        if (y_keep) y_codes->valid = 1;
     }
     // everything that depends on s' alone: u(s') of Eq. 6 and the recurrent half of GRU q
     if (!fused_codes) {
@@ -490,16 +508,23 @@ q8_status cgru_decoder_step_batch_q8(q8_ctx *ctx, const q8_cgru_weights *w, cons
     // Eq. 5-6 per hypothesis, against the positions of its own sentence
     int have_codes = 0;
     TRY(q8i_attention(ctx, P, enc_h, max_l, A, C, a, w->att_v, n, e, alpha_out, ctx_out, sent_off, beam, cq, cqs, w->q.Wx.ld, &have_codes));
-    // Eq. 4: s = q(H_t, s')
+    if (have_codes && codes_usable(ctx_codes, w->q.Wx.ld)) ctx_codes->valid = 1;
+    // Eq. 4: s = q(H_t, s'); the gates kernel can leave s quantized for the caller's next product
     Carver sub = cv;
-    return gru_panel(ctx, sub, &w->q, ctx_out, s_mid, n, ghq, s_out, nullptr, have_codes ? cq : nullptr, have_codes ? cqs : nullptr);
+    const bool s_keep = s_codes && s_codes->q && s_codes->scale && aligned16(s_codes->q) && s_codes->ld >= H &&
+                        q8i_gru_gates_q_ok(H, H, H, s_codes->ld, s_codes->ld);
+    const PanelCodesOut s_out_codes = {s_keep ? s_codes->q : nullptr, s_keep ? s_codes->ld : 0, s_keep ? s_codes->scale : nullptr, nullptr, 0, nullptr};
+    q8_status st = gru_panel(ctx, sub, &w->q, ctx_out, s_mid, n, ghq, s_out, nullptr, have_codes ? cq : nullptr,
+                             have_codes ? cqs : nullptr, s_keep ? &s_out_codes : nullptr);
+    if (!st && s_keep) s_codes->valid = 1;
+    return st;
 }
 
 static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
                              const float *s, const float *y_emb, const float *ctx_vec, const float *t_in, int n_beam,
                              int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx, float *t_out,
                              const q8_taps *taps4, const q8i_beam_desc *beam, const q8_codes *y_codes = nullptr,
-                             const q8_codes *ctx_codes = nullptr)
+                             const q8_codes *ctx_codes = nullptr, const q8_codes *s_codes = nullptr)
 {
     if (!ctx) return Q8_ERR_NULL;
     TRY(check_mat(ctx, W_out, "W_out"));
@@ -549,14 +574,19 @@ static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8
             float *t = t_out ? t_out : cv.take<float>((size_t)n * R);
             q8i_quant_job qj[3];
             q8i_gemm_job gj[3];
+            // the three inputs' codes from their producers (all or none), else quantized here
+            const q8_codes *pre[3] = {s_codes, y_codes, ctx_codes};
+            bool have_pre = !taps4;
+            for (int u = 0; u < 3; ++u) have_pre = have_pre && pre[u] && pre[u]->valid && codes_usable(pre[u], M[u]->ld);
             for (int u = 0; u < 3; ++u) {
                 int8_t *xq = cv.take<int8_t>((size_t)n * M[u]->ld);
                 float *xs = cv.take<float>(n), *part = cv.take<float>((size_t)n * R);
+                if (have_pre) { xq = pre[u]->q; xs = pre[u]->scale; }
                 qj[u] = {X[u], M[u]->cols, M[u]->cols, M[u]->ld, xq, xs, taps4 ? taps4 + u : nullptr};
                 gj[u] = {M[u], xq, xs, nullptr, part, R, taps4 ? taps4[u].acc : nullptr, nullptr, nullptr, 0};
             }
             if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
-            TRY(q8i_quantize_jobs(ctx, qj, 3, n));
+            if (!have_pre) TRY(q8i_quantize_jobs(ctx, qj, 3, n));
             TRY(q8i_gemm_jobs(ctx, gj, 3, n));
             TRY(q8i_readout_combine(ctx, gj[0].Y, gj[1].Y, gj[2].Y, ro->b_t, R, n, t, W_out->ld, tq, tsc, taps4 ? taps4 + 3 : nullptr));
         } else {
@@ -585,6 +615,17 @@ q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_m
 {
     return output_impl(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, t_in, n_beam, k, logits, lse, topk_logp, topk_idx,
                        t_out, taps4, nullptr);
+}
+
+q8_status output_logits_codes_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                                 const float *s, const float *y_emb, const float *ctx_vec, int n_beam, int k, float *logits,
+                                 float *lse, float *topk_logp, int32_t *topk_idx, float *t_out, const q8_codes *s_codes,
+                                 const q8_codes *y_codes, const q8_codes *ctx_codes)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!ro) return q8_fail(ctx, Q8_ERR_NULL, "output_logits_codes_q8: the readout weights are required");
+    return output_impl(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, nullptr, n_beam, k, logits, lse, topk_logp, topk_idx, t_out,
+                       nullptr, nullptr, y_codes, ctx_codes, s_codes);
 }
 
 q8_status output_logits_beam_codes_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
@@ -1130,7 +1171,7 @@ q8_status q8_beam_result_batch(q8_ctx *ctx, const void *states, int n_sent, int 
 
 namespace {
 struct BatchBufs {
-    size_t X, enc_h, P, off, y, s0, s1, cv, lp, idx, done, states, total;
+    size_t X, enc_h, P, off, y, s0, s1, cv, lp, idx, done, states, yq, ys, cq, cs, sq, ss, total;
 };
 BatchBufs batch_layout(const q8_model *m, int total_l, int n_sent, int beam, int k, int max_steps)
 {
@@ -1144,6 +1185,10 @@ BatchBufs batch_layout(const q8_model *m, int total_l, int n_sent, int beam, int
     b.cv = take(n * C * 4); b.lp = take(n * k * 4); b.idx = take(n * k * 4);
     b.done = take((size_t)n_sent * 4);
     b.states = take(q8i_beam_state_bytes(max_steps) * n_sent);
+    // codes of y, of the context vectors and of the new states, handed from the decoder step to the output layer
+    b.yq = take(n * m->dec.r.Wx.ld); b.ys = take(n * 4);
+    b.cq = take(n * m->dec.q.Wx.ld); b.cs = take(n * 4);
+    b.sq = take(n * m->ro.W_s.ld); b.ss = take(n * 4);
     b.total = o;
     return b;
 }
@@ -1194,6 +1239,9 @@ q8_status q8_translate_batch(q8_ctx *ctx, const q8_model *m, const int32_t *src_
     int32_t *idx = (int32_t *)(top + b.idx);
     void *states = top + b.states;
     const int n = n_sent * beam;
+    q8_codes yc = {(int8_t *)(top + b.yq), (float *)(top + b.ys), m->dec.r.Wx.ld, 0};
+    q8_codes cc = {(int8_t *)(top + b.cq), (float *)(top + b.cs), m->dec.q.Wx.ld, 0};
+    q8_codes sc = {(int8_t *)(top + b.sq), (float *)(top + b.ss), m->ro.W_s.ld, 0};
     ctx->ws_reserved_top = ctx->ws_bytes - (size_t)(top - ctx->ws);
 
     q8_status st = Q8_OK;
@@ -1214,13 +1262,15 @@ q8_status q8_translate_batch(q8_ctx *ctx, const q8_model *m, const int32_t *src_
     if (!done_host && !st) st = q8_fail(ctx, Q8_ERR_DEVICE, "out of host memory");
     for (int t = 0; t < max_steps && !st && !all_done; ++t) {
         if (n <= kMaxNarrow && n_sent == 1) {
-            st = cgru_decoder_step_q8(ctx, &m->dec, P, enc_h, total_l, y, sv[cur], n, sv[cur ^ 1], cvec, nullptr, nullptr, nullptr);
+            st = cgru_decoder_step_codes_q8(ctx, &m->dec, P, enc_h, total_l, y, sv[cur], n, sv[cur ^ 1], cvec, nullptr, nullptr,
+                                            nullptr, &yc, &cc);
+            sc.valid = 0;
         } else {
-            st = cgru_decoder_step_batch_q8(ctx, &m->dec, P, enc_h, off, n_sent, beam, max_l, y, sv[cur], sv[cur ^ 1], cvec,
-                                            nullptr, nullptr);
+            st = cgru_decoder_step_batch_codes_q8(ctx, &m->dec, P, enc_h, off, n_sent, beam, max_l, y, sv[cur], sv[cur ^ 1],
+                                                  cvec, nullptr, nullptr, &yc, &cc, &sc);
         }
         if (!st) st = output_impl(ctx, &m->ro, &m->W_out, m->b_out, sv[cur ^ 1], y, cvec, nullptr, n, k, nullptr, nullptr, lp,
-                                  idx, nullptr, nullptr, nullptr);
+                                  idx, nullptr, nullptr, nullptr, &yc, &cc, &sc);
         if (!st) st = q8_beam_update_batch(ctx, states, n_sent, beam, k, max_steps, lp, idx, sv[cur ^ 1], H, m->E_tgt, E, y,
                                            sv[cur], done);
         if (!st && (t % 8 == 7)) {

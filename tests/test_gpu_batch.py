@@ -233,3 +233,37 @@ def test_output_layer_panel_persistent_kernel(q, ctx, oracle, V, R, n, k):
         lse, lp, idx = oracle.logsoftmax_topk(L.gemv(p["t"][j]), k)
         assert_same(r["topk_idx"][j], idx, "top-k indices"); assert_close(r["topk_logp"][j], lp, "top-k logp")
         assert_close(r["lse"][j:j + 1], np.array([lse]), "lse")
+
+
+@pytest.mark.parametrize("dims,S,beam,l", [(dict(), 4, 5, 7), (dict(), 30, 5, 30), (dict(), 3, 3, 5),
+                                           (dict(V=33658, E=620, H=1000, A=1000, R=620), 4, 5, 9),
+                                           (dict(V=50, E=32, H=48, A=40, R=24, w_std=0.3), 6, 2, 5)])
+def test_codes_travel_from_the_batched_step_to_the_output_layer(q, ctx, oracle, dims, S, beam, l):
+    """cgru_decoder_step_batch_codes_q8 + output_logits_codes_q8 against the plain calls (identical bits);
+    the three sets of codes against the oracle's quantization of the fp32 vectors they belong to."""
+    p = synth.full_model(seed=12, **dims)
+    m = q.Model.from_params(ctx, p)
+    E, H = m.E_tgt.shape[1], m.dec.r.H
+    n = S * beam
+    rng = np.random.default_rng(S + l)
+    enc_h = ctx.f32(rng.standard_normal((S * l, 2 * H)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    off = torch.arange(0, (S + 1) * l, l, dtype=torch.int32, device=ctx.device)
+    y = ctx.f32(rng.standard_normal((n, E)).astype(np.float32))
+    s = ctx.f32(rng.standard_normal((n, H)).astype(np.float32))
+    res = []
+    for use in (False, True):
+        codes = (q.Codes(ctx, n, m.dec.r.Wx.ld), q.Codes(ctx, n, m.dec.q.Wx.ld), q.Codes(ctx, n, m.ro.W_s.ld)) if use else None
+        r1 = q.cgru_decoder_step_batch_q8(ctx, m.dec, P, enc_h, off, beam, l, y, s, codes=codes)
+        if use:
+            assert all(c.valid for c in codes)
+            for c, X in ((codes[0], y), (codes[1], r1["ctx"]), (codes[2], r1["s"])):
+                for j in (0, n // 2, n - 1):
+                    xq, xs = oracle.quantize(np_(X)[j])
+                    K = X.shape[1]
+                    assert_same(c.q[j, :K], xq, "codes of slot %d" % j)
+                    assert not np_(c.q[j, K:]).any() and float(c.scale[j]) == float(xs)
+        r2 = q.output_logits_q8(ctx, m.ro, m.W_out, m.b_out, s=r1["s"], y_emb=y, ctx_vec=r1["ctx"], k=12, codes=codes)
+        res.append((r1["s"], r1["ctx"], r2["t"], r2["logits"], r2["lse"], r2["topk_logp"], r2["topk_idx"]))
+    for a, b, what in zip(res[0], res[1], ("s", "ctx", "t", "logits", "lse", "topk_logp", "topk_idx")):
+        assert_same(b, np_(a), what + ": with codes against without")
