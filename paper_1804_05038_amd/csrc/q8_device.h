@@ -594,7 +594,10 @@ __device__ __forceinline__ void x_finish_multi(const XRegs<N, CH> (&R)[NIN], con
 
 // Requests U weight rows for this wave: lane covers bytes [(c * 64 + lane) * 16, +16) of a row.
 // rw: descriptor over the whole matrix (below 2 GiB); row[u] < 0: no such row, reads as zero.
-template <int U, int CH>
+// STREAM: the loads carry the non-temporal hint.  The matrices of a decoder step other than the
+// vocabulary matrix are read once per step by kernels that are bound by latency wherever the
+// bytes come from; streaming them leaves the 32 MB of L2 to the vocabulary matrix.
+template <int U, int CH, bool STREAM = true>
 __device__ __forceinline__ void rows_load(v4i (&w)[U][CH], __amdgpu_buffer_rsrc_t rw, const int (&row)[U], int ld, int lane)
 {
 #pragma unroll
@@ -603,7 +606,8 @@ __device__ __forceinline__ void rows_load(v4i (&w)[U][CH], __amdgpu_buffer_rsrc_
         for (int c = 0; c < CH; ++c) {
             const int off = (c * 64 + lane) * 16;
             const unsigned o = (row[u] >= 0 && off < ld) ? (unsigned)row[u] * (unsigned)ld + (unsigned)off : Q8_OOB;
-            w[u][c] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rw, (int)o, 0, 0));
+            w[u][c] = STREAM ? __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rw, (int)o, 0, 2))
+                             : __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rw, (int)o, 0, 0));
         }
 }
 

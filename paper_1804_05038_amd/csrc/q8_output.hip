@@ -278,7 +278,10 @@ __global__ __launch_bounds__(320) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
 // data comes back ahead of the weights, which every wave requests next), quantizes it alone
 // (no exchange between waves) and leaves the codes in LDS; after the one barrier every wave
 // holds the codes of all vectors as operand B in registers.  KPL float4 per lane and vector.
-template <int KPL, int KS>
+// RESIDENT: the matrix fits the L2 (32 MB over the eight XCDs; a block reads the same tiles every
+// step and lands on the same XCD) and is read plainly, so that it stays there from one step to the
+// next; the other matrices of the step are streamed past it.  A larger matrix is streamed itself.
+template <int KPL, int KS, bool RESIDENT>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))) void out_logits8_kernel(OutArgs a)
 {
     extern __shared__ __align__(16) int8_t smem[];     // [n x pitch] codes of the hidden vectors
@@ -297,14 +300,15 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
         const unsigned off = (wave < n && k < a.K) ? (unsigned)(wave * a.ldt + k) * 4u : Q8_OOB;
         tv[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rT, (int)off, 0, 0));
     }
-    // the tile: up to KS wave-wide loads of one contiguous KiB each, non-temporal like Q8_WLOAD
+    // the tile: up to KS wave-wide loads of one contiguous KiB each
     const __amdgpu_buffer_rsrc_t rW = q8_rsrc(a.tiles, (size_t)a.ntiles * ld * OUT_TILE);
     const unsigned woff = have ? (unsigned)tile * (unsigned)(ld * OUT_TILE) + lane * 16u : Q8_OOB;
     v4i av[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
         const unsigned off = s < ksteps ? woff + 1024u * s : Q8_OOB;
-        av[s] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rW, (int)off, 0, 2));
+        av[s] = RESIDENT ? __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rW, (int)off, 0, 0))
+                         : __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rW, (int)off, 0, 2));
     }
     // bias of the four rows this lane finishes
     const int row0 = tile * OUT_TILE + 4 * g;
@@ -725,9 +729,13 @@ q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const floa
         // (at most 256 blocks' worth of tiles: one block per compute unit; more: two each, evenly filled)
         const int nblk8 = a.ntiles <= 8 * (OUT_BLOCKS / 2) ? (a.ntiles + 7) / 8 : OUT_BLOCKS;
         const size_t smem8 = (size_t)n * (a.ld + 16);
-        if (a.ld > 512) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits8_kernel<3, 10>), dim3(nblk8), dim3(512), smem8, a);
-        else if (a.K <= 256) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits8_kernel<1, 8>), dim3(nblk8), dim3(512), smem8, a);
-        else Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits8_kernel<2, 8>), dim3(nblk8), dim3(512), smem8, a);
+        const bool resident = (size_t)a.ntiles * OUT_TILE * a.ld <= ((size_t)27 << 20);
+        if (a.ld > 512 && resident) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits8_kernel<3, 10, true>), dim3(nblk8), dim3(512), smem8, a);
+        else if (a.ld > 512) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits8_kernel<3, 10, false>), dim3(nblk8), dim3(512), smem8, a);
+        else if (a.K <= 256 && resident) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits8_kernel<1, 8, true>), dim3(nblk8), dim3(512), smem8, a);
+        else if (a.K <= 256) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits8_kernel<1, 8, false>), dim3(nblk8), dim3(512), smem8, a);
+        else if (resident) Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits8_kernel<2, 8, true>), dim3(nblk8), dim3(512), smem8, a);
+        else Q8_LAUNCH(ctx, Q8_KERNEL_VOCAB, (out_logits8_kernel<2, 8, false>), dim3(nblk8), dim3(512), smem8, a);
     } else if (a.tiles) {
         launch_out_packed<true>(ctx, a, nblk, smem, ch);
     } else {

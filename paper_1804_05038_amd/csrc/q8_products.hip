@@ -187,7 +187,9 @@ __device__ __forceinline__ void rows_dot_part_nb(const v4i (&w)[U][CH], int ld, 
 // wave are requested before anything is waited for; after that two register sets take turns, one
 // pass's rows being multiplied while the next pass's are in flight (U rows per wave and pass).
 // ROWS: every job has one weight scale per row (requested with the row's bias).
-template <int N, int CH, bool ROWS, int U>
+// STREAM: small matrices (a decoder step's) are read with the non-temporal hint, large ones plainly,
+// so that a matrix of the size of the L2 that is multiplied again and again stays there.
+template <int N, int CH, bool ROWS, int U, bool STREAM>
 __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
 {
     extern __shared__ __align__(16) int8_t smem[];
@@ -216,7 +218,7 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
         int row[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) row[u] = r0 + u < r_end ? r0 + u : -1;
-        rows_load<U, CH>(wr, rw, row, ld, lane);
+        rows_load<U, CH, STREAM>(wr, rw, row, ld, lane);
         const int off = min(r0 + (lane & (U - 1)), last_row) * 4;
         b[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, off, 0, 0));
         b[1] = ROWS ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0)) : 0.0f;
@@ -343,20 +345,21 @@ q8_status q8i_fill_u32(q8_ctx *ctx, void *p, int n, unsigned v)
     return q8i_launch_check(ctx, "fill");
 }
 
-template <int N, bool ROWS, int U>
+template <int N, bool ROWS, int U, bool STREAM>
 static void launch_gemv_nu(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t smem, int ch)
 {
-    if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 1, ROWS, U>), dim3(blocks), dim3(256), smem, jobs);
-    else if (ch == 2) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 2, ROWS, U>), dim3(blocks), dim3(256), smem, jobs);
-    else Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 4, ROWS, U>), dim3(blocks), dim3(256), smem, jobs);
+    if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 1, ROWS, U, STREAM>), dim3(blocks), dim3(256), smem, jobs);
+    else if (ch == 2) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 2, ROWS, U, STREAM>), dim3(blocks), dim3(256), smem, jobs);
+    else Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_fast_kernel<N, 4, ROWS, U, STREAM>), dim3(blocks), dim3(256), smem, jobs);
 }
 
 template <int N>
-static void launch_gemv_n(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t smem, int ch, bool rows)
+static void launch_gemv_n(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t smem, int ch, bool rows, bool stream)
 {
     if (ch == 0) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, gemv_jobs_kernel<N>, dim3(blocks), dim3(256), smem, jobs);
-    else if (rows) launch_gemv_nu<N, true, 2>(ctx, jobs, blocks, smem, ch);
-    else launch_gemv_nu<N, false, 2>(ctx, jobs, blocks, smem, ch);
+    else if (rows) launch_gemv_nu<N, true, 2, false>(ctx, jobs, blocks, smem, ch);
+    else if (stream) launch_gemv_nu<N, false, 2, true>(ctx, jobs, blocks, smem, ch);
+    else launch_gemv_nu<N, false, 2, false>(ctx, jobs, blocks, smem, ch);
 }
 
 q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
@@ -395,15 +398,18 @@ q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
         blocks += (J.rows + rpb - 1) / rpb;
     }
     const size_t smem = (size_t)n * max_ld;
+    size_t bytes = 0;
+    for (int t = 0; t < njobs; ++t) bytes += (size_t)jobs.j[t].rows * jobs.j[t].ld;
+    const bool stream = bytes < ((size_t)8 << 20);          // the products inside a decoder step
     switch (n) {
-    case 1: launch_gemv_n<1>(ctx, jobs, blocks, smem, ch, rows); break;
-    case 2: launch_gemv_n<2>(ctx, jobs, blocks, smem, ch, rows); break;
-    case 3: launch_gemv_n<3>(ctx, jobs, blocks, smem, ch, rows); break;
-    case 4: launch_gemv_n<4>(ctx, jobs, blocks, smem, ch, rows); break;
-    case 5: launch_gemv_n<5>(ctx, jobs, blocks, smem, ch, rows); break;
-    case 6: launch_gemv_n<6>(ctx, jobs, blocks, smem, ch, rows); break;
-    case 7: launch_gemv_n<7>(ctx, jobs, blocks, smem, ch, rows); break;
-    default: launch_gemv_n<8>(ctx, jobs, blocks, smem, ch, rows); break;
+    case 1: launch_gemv_n<1>(ctx, jobs, blocks, smem, ch, rows, stream); break;
+    case 2: launch_gemv_n<2>(ctx, jobs, blocks, smem, ch, rows, stream); break;
+    case 3: launch_gemv_n<3>(ctx, jobs, blocks, smem, ch, rows, stream); break;
+    case 4: launch_gemv_n<4>(ctx, jobs, blocks, smem, ch, rows, stream); break;
+    case 5: launch_gemv_n<5>(ctx, jobs, blocks, smem, ch, rows, stream); break;
+    case 6: launch_gemv_n<6>(ctx, jobs, blocks, smem, ch, rows, stream); break;
+    case 7: launch_gemv_n<7>(ctx, jobs, blocks, smem, ch, rows, stream); break;
+    default: launch_gemv_n<8>(ctx, jobs, blocks, smem, ch, rows, stream); break;
     }
     return q8i_launch_check(ctx, "gemv");
 }
