@@ -387,7 +387,7 @@ __global__ __launch_bounds__(64 * VP_WAVES) void vocab_panel_kernel(PanelArgs a)
     auto load_tile = [&](v4i (&A)[KC], int tile) {
         const int8_t *p = a.tiles + ((size_t)(tile < a.ntiles ? tile : a.ntiles - 1) * KC) * 1024 + lane * 16;
 #pragma unroll
-        for (int s = 0; s < KC; ++s) A[s] = __builtin_nontemporal_load((const v4i *)(p + 1024 * s));
+        for (int s = 0; s < KC; ++s) A[s] = *(const v4i *)(p + 1024 * s);
     };
     load_tile(A0, gw);
     // the codes of this block's slots into LDS (slots past the panel are zero): eight 16-byte pieces per
