@@ -464,7 +464,9 @@ __global__ __launch_bounds__(64 * VP_WAVES) void vocab_panel_kernel(PanelArgs a)
                     m[u] = fmaxf(m[u], y[u][r]);
                 }
                 if (col_ok)
-                    *(float4 *)(ytile + (size_t)(c_base + colr) * 16 + 4 * g) = make_float4(y[u][0], y[u][1], y[u][2], y[u][3]);
+                    // (streamed: 64 MB of logits per step at 320 slots, of which the selection reads back a few tiles)
+                    __builtin_nontemporal_store((v4i){__float_as_int(y[u][0]), __float_as_int(y[u][1]), __float_as_int(y[u][2]), __float_as_int(y[u][3])},
+                                                (v4i *)(ytile + (size_t)(c_base + colr) * 16 + 4 * g));
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) m[u] = quad_rows_max(m[u]);
