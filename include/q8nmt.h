@@ -13,7 +13,9 @@
  * -127, 127) with round-half-to-even, all in IEEE fp32; if max|v| < 2^-100 the scale
  * is 1 and every code 0.  One scale per weight matrix, one per activation vector
  * (per column of a narrow matrix).  Accumulation is exact int32.  The float result is
- * y_i = (float)acc_i * (s_w * s_x), then + bias_i as a separate fp32 add.
+ * y_i = (float)acc_i * (s_w * s_x), then + bias_i as a separate fp32 add.  Two variants
+ * of the scheme exist beside it as entry points of their own: one weight scale per row
+ * (q8_gemm_narrow_rows) and 8-bit products inside the attention (q8_attention_q8).
  *
  * Conventions
  *  - Every pointer is a DEVICE pointer unless its name ends in _host.  All device
@@ -25,7 +27,8 @@
  *    fp32 vectors: 16-byte aligned base, leading dimensions % 4 == 0.  Batches are
  *    vector-major: [n x dim], each vector contiguous.
  *  - Calls enqueue work on the stream given to q8_create and return without waiting,
- *    except q8_quantize_matrix (load time; it returns the scale to the host).
+ *    except q8_quantize_matrix and q8_attention_states_q8 (they return a scale to the
+ *    host), the *_result calls and the q8_translate* drivers.
  *  - Every function returns a q8_status.  Argument errors are detected before
  *    anything is launched; nothing aborts or throws.  q8_last_error gives text.
  *  - Limits: 1 <= cols <= ld <= 16384 for products (the int32 sum cannot overflow
