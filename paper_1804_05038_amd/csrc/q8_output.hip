@@ -292,6 +292,10 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     const int tile = blockIdx.x + wave * gridDim.x;
     const bool have = tile < a.ntiles;
 
+    // The block's barrier waits for the waves that quantize; the compute unit's sixteen waves share one
+    // vector-memory queue, which takes about a microsecond to accept all their loads.  Raised priority
+    // puts the quantizing waves' requests in first (measured: barrier reached 0.25 us earlier).
+    if (wave < n) __builtin_amdgcn_s_setprio(3);
     const __amdgpu_buffer_rsrc_t rT = q8_rsrc(a.T, ((size_t)(n - 1) * a.ldt + a.K) * sizeof(float));
     float4 tv[KPL];
 #pragma unroll
@@ -335,6 +339,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
             if (k < ld) *(int *)(smem + (size_t)wave * pitch + k) = q8_pack4(tv[t].x, tv[t].y, tv[t].z, tv[t].w, inv);
         }
         if (lane == 0) s_scale[wave] = scale;
+        __builtin_amdgcn_s_setprio(0);
     }
     __syncthreads();
     if (blockIdx.x == 0) {
