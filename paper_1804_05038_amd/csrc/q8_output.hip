@@ -299,10 +299,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     const __amdgpu_buffer_rsrc_t rT = q8_rsrc(a.T, ((size_t)(n - 1) * a.ldt + a.K) * sizeof(float));
     float4 tv[KPL];
 #pragma unroll
-    for (int t = 0; t < KPL; ++t) {
-        const int k = (t * 64 + lane) * 4;
-        const unsigned off = (wave < n && k < a.K) ? (unsigned)(wave * a.ldt + k) * 4u : Q8_OOB;
-        tv[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rT, (int)off, 0, 0));
+    for (int t = 0; t < KPL; ++t) tv[t] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (wave < n) {                              // (the other waves would only add requests that fetch nothing to the queue)
+#pragma unroll
+        for (int t = 0; t < KPL; ++t) {
+            const int k = (t * 64 + lane) * 4;
+            const unsigned off = (k < a.K) ? (unsigned)(wave * a.ldt + k) * 4u : Q8_OOB;
+            tv[t] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(rT, (int)off, 0, 0));
+        }
     }
     // the tile: up to KS wave-wide loads of one contiguous KiB each
     const __amdgpu_buffer_rsrc_t rW = q8_rsrc(a.tiles, (size_t)a.ntiles * ld * OUT_TILE);
