@@ -119,7 +119,7 @@ def test_cgru_uniform_attention_special_case(q, ctx, oracle):
 @pytest.mark.parametrize("V,R,n,k", [(50000, 512, 5, 12), (50000, 512, 1, 12), (300, 64, 3, 12), (129, 48, 8, 16),
                                      (1000, 512, 2, 1), (12, 16, 2, 12), (777, 1024, 4, 12), (33658, 640, 6, 12),
                                      (5000, 320, 8, 16), (4097, 256, 7, 12), (17, 128, 4, 12), (2049, 448, 3, 5),
-                                     (40000, 384, 6, 12)])
+                                     (40000, 384, 6, 12), (45000, 640, 5, 12)])      # the last: 28.8 MB, streamed rather than kept in the L2
 def test_output_layer_given_t(q, ctx, oracle, V, R, n, k, packed):
     p = synth.output_layer(seed=2, V=V, R=R, n_beam=n)
     L = oracle.QLinear(p["out.W"], p["out.b"])
