@@ -12,10 +12,29 @@
 #include <stdlib.h>
 #include <string.h>
 
+/* Non-finite inputs: the method has no rule for them (a NaN has no 8-bit code), so the
+ * oracle defines no result; it counts them where data enters a product, and the callers
+ * turn a non-zero count into an error. */
+static long g_nonfinite = 0;
+
+static void note_nonfinite(const float *v, int n)
+{
+    for (int i = 0; i < n; ++i)
+        if (!isfinite(v[i])) ++g_nonfinite;
+}
+
+long q8o_nonfinite_count(int reset)
+{
+    long c = g_nonfinite;
+    if (reset) g_nonfinite = 0;
+    return c;
+}
+
 /* ------------------------------------------------------------------ Section 3 -- */
 
 void q8o_quantize(const float *v, int n, int8_t *q, float *scale)
 {
+    note_nonfinite(v, n);
     float m = 0.0f;
     for (int i = 0; i < n; ++i) {
         float a = fabsf(v[i]);
@@ -41,6 +60,7 @@ void q8o_quantize(const float *v, int n, int8_t *q, float *scale)
 void q8o_quantize_matrix(const float *W, int rows, int cols, int ld_in,
                          int8_t *Wq, int ld_out, float *scale)
 {
+    for (int i = 0; i < rows; ++i) note_nonfinite(W + (size_t)i * ld_in, cols);
     float m = 0.0f;
     for (int i = 0; i < rows; ++i)
         for (int k = 0; k < cols; ++k) {
@@ -155,6 +175,7 @@ void q8o_gemm_narrow_rows(const int8_t *Wq, int rows, int cols, int ld, const fl
 
 void q8o_gemv_fp32(const q8o_linear *L, const float *x, float *y)
 {
+    note_nonfinite(x, L->cols);
     for (int i = 0; i < L->rows; ++i) {
         double a = 0.0;
         for (int k = 0; k < L->cols; ++k)

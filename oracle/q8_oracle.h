@@ -63,6 +63,14 @@ typedef struct {
     q8o_linear out;                      /* second layer of g: [V_tgt x R], bias b_out */
 } q8o_model;
 
+/* Non-finite inputs (NaN, +-inf) have no 8-bit code and the method says nothing about
+ * them: the oracle defines no result for them.  Every vector or matrix that enters a
+ * product (q8o_quantize, q8o_quantize_matrix, q8o_gemv_fp32, and so everything built on
+ * them) is checked, and the number of non-finite elements seen since the last reset is
+ * returned here; the Python front-end raises FloatingPointError when it is not zero.
+ * Not thread-safe beyond a lost count. */
+long q8o_nonfinite_count(int reset);
+
 /* ---- Section 3: the 8-bit product, step by step -------------------------------- */
 
 /* O1. Symmetric max-abs quantization of one vector.  m = max|v_i|.  If m < 2^-100

@@ -25,6 +25,16 @@ def build(force=False):
     return _LIB
 
 
+def build_selftest(out=None, sanitize=False):
+    """Compile q8_oracle.c with its self-test driver into an executable; sanitize: under
+    AddressSanitizer and UndefinedBehaviorSanitizer (host code only), any finding is fatal."""
+    out = out or os.path.join(_HERE, "q8_oracle_selftest")
+    flags = ["-std=c11", "-Wall", "-Wextra", "-ffp-contract=off", "-fno-fast-math", "-g"]
+    flags += ["-O1", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan"] if sanitize else ["-O2"]
+    subprocess.check_call(["gcc", *flags, "-I" + _HERE, _SRC, os.path.join(_HERE, "q8_oracle_selftest.c"), "-o", out, "-lm"])
+    return out
+
+
 class Linear(C.Structure):
     _fields_ = [("rows", C.c_int), ("cols", C.c_int),
                 ("Wf", C.c_void_p), ("ldf", C.c_int),
@@ -50,12 +60,41 @@ class Model(C.Structure):
 _lib = None
 
 
+class _Checked:
+    """The C library with the oracle's finiteness rule applied to every call: a call that saw
+    a NaN or an infinity in a vector or matrix it was given raises FloatingPointError (the
+    method defines no result for such inputs)."""
+
+    def __init__(self, cdll):
+        self._c = cdll
+        cdll.q8o_translate.restype = C.c_int
+        cdll.q8o_translate_ensemble.restype = C.c_int
+        cdll.q8o_nonfinite_count.restype = C.c_long
+        cdll.q8o_nonfinite_count(C.c_int(1))
+
+    def __getattr__(self, name):
+        fn = getattr(self._c, name)
+
+        def call(*args):
+            r = fn(*args)
+            bad = self._c.q8o_nonfinite_count(C.c_int(1))
+            if bad:
+                raise FloatingPointError("%s: %d non-finite input values" % (name, bad))
+            return r
+
+        setattr(self, name, call)
+        return call
+
+
+def load(path):
+    """Front-end over a library built from q8_oracle.c at another path (a sanitizer or test build)."""
+    return _Checked(C.CDLL(path))
+
+
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
-        _lib.q8o_translate.restype = C.c_int
-        _lib.q8o_translate_ensemble.restype = C.c_int
+        _lib = load(build())
     return _lib
 
 
