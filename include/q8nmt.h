@@ -353,7 +353,9 @@ size_t q8_translate_bytes(const q8_model *m, int max_l, int beam, int k, int max
  * w(h_i), initial decoder state = backward encoder state at the first position, then up
  * to max_steps steps of cgru_decoder_step_q8 + output_logits_q8 + q8_beam_update, all
  * enqueued without reading anything back except a 4-byte "search over" flag every 8
- * steps.  src_tokens: l device int32 ids in [0, V_src).  Results as q8_beam_result. */
+ * steps.  src_tokens: l device int32 ids in [0, V_src); the library never reads them on the
+ * host, and an id outside that range is looked up as a zero embedding vector (no fault).
+ * m->V_src must be positive and m->V_tgt the number of rows of W_out.  Results as q8_beam_result. */
 q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens, int l, int beam, int k,
                        int max_steps, int32_t *tokens_host, int *len_host, float *score_host, int *steps_host);
 

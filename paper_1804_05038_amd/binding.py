@@ -18,7 +18,7 @@ __all__ = ["Q8Error", "Context", "Mat", "Codes", "GruWeights", "CgruWeights", "R
            "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "MatF", "GruWeightsF32", "CgruWeightsF32", "ReadoutWeightsF32", "q8_gemv_f32",
            "cgru_decoder_step_f32", "output_logits_f32", "q8_translate_ensemble", "q8_translate_ensemble_bytes", "cgru_decoder_step_batch_q8", "q8_encode_batch", "q8_encode_batch_bytes", "q8_beam_init_batch",
            "q8_beam_update_batch", "q8_beam_result_batch", "q8_translate_batch", "q8_translate_batch_bytes",
-           "KERNEL_CLASSES", "LIB_PATH"]
+           "KERNEL_CLASSES", "LIB_PATH", "source_ids"]
 LIB_PATH = _LIB_PATH
 
 STATUS = {0: "Q8_OK", 1: "Q8_ERR_NULL", 2: "Q8_ERR_SHAPE", 3: "Q8_ERR_ALIGN", 4: "Q8_ERR_WORKSPACE", 5: "Q8_ERR_DEVICE"}
@@ -555,6 +555,25 @@ class Model:
                    ctx.f32(p["att.b"]), dec, ro, out_W, ctx.f32(p["out.b"]))
 
 
+def source_ids(ids, V_src, device=None):
+    """Source token ids as a device int32 tensor.  Ids that arrive on the host (lists, arrays, CPU
+    tensors) are checked against [0, V_src) here and a violation raises ValueError; a tensor that
+    is already on the device is passed through unread (the kernels look up an id outside the
+    table as a zero vector)."""
+    import numpy as np
+    if isinstance(ids, torch.Tensor) and ids.is_cuda:
+        if ids.dtype != torch.int32:
+            raise ValueError("device token ids must be int32")
+        return ids
+    a = np.asarray(ids.numpy() if isinstance(ids, torch.Tensor) else ids)
+    if a.ndim != 1 or a.size == 0 or not np.issubdtype(a.dtype, np.integer):
+        raise ValueError("token ids: a non-empty one-dimensional integer sequence is required")
+    if int(a.min()) < 0 or int(a.max()) >= V_src:
+        raise ValueError("token id outside [0, %d)" % V_src)
+    t = torch.as_tensor(a.astype(np.int32))
+    return t if device is None else t.to(device)
+
+
 def q8_translate_bytes(model, max_l, beam, k, max_steps):
     return load_library().q8_translate_bytes(C.byref(model.c), max_l, beam, k, max_steps)
 
@@ -562,7 +581,7 @@ def q8_translate_bytes(model, max_l, beam, k, max_steps):
 def q8_translate(ctx, model, src_tokens, beam=5, k=12, max_steps=100):
     """Returns (tokens ndarray, score, steps)."""
     import numpy as np
-    src = torch.as_tensor(np.asarray(src_tokens, dtype=np.int32)).to(ctx.device) if not isinstance(src_tokens, torch.Tensor) else src_tokens
+    src = source_ids(src_tokens, model.E_src.shape[0], ctx.device)
     out = (C.c_int32 * max_steps)()
     n, steps, score = C.c_int(), C.c_int(), C.c_float()
     ctx.check(ctx.lib.q8_translate(ctx.handle, C.byref(model.c), _ptr(src), src.shape[0], beam, k, max_steps,
@@ -618,7 +637,7 @@ def q8_translate_ensemble_bytes(models, max_l, beam=5, k=12, max_steps=100):
 def q8_translate_ensemble(ctx, models, src_tokens, beam=5, k=12, max_steps=100):
     """Ensemble decoding over a list of Model objects; returns (tokens ndarray, score, steps)."""
     import numpy as np
-    src = torch.as_tensor(np.asarray(src_tokens, dtype=np.int32)).to(ctx.device)
+    src = source_ids(src_tokens, min(m.E_src.shape[0] for m in models), ctx.device)
     out = (C.c_int32 * max_steps)()
     n, steps, score = C.c_int(), C.c_int(), C.c_float()
     ctx.check(ctx.lib.q8_translate_ensemble(ctx.handle, _model_ptrs(models), len(models), _ptr(src), src.shape[0], beam, k,
@@ -636,7 +655,8 @@ def q8_translate_batch(ctx, model, sentences, beam=5, k=12, max_steps=100):
     S = len(sentences)
     off = np.zeros(S + 1, dtype=np.int32)
     off[1:] = np.cumsum([len(x) for x in sentences])
-    src = torch.as_tensor(np.concatenate([np.asarray(x, dtype=np.int32) for x in sentences])).to(ctx.device)
+    V_src = model.E_src.shape[0]
+    src = torch.cat([source_ids(x, V_src, ctx.device) for x in sentences])
     out = (C.c_int32 * (max_steps * S))()
     n, steps, score = (C.c_int * S)(), (C.c_int * S)(), (C.c_float * S)()
     ctx.check(ctx.lib.q8_translate_batch(ctx.handle, C.byref(model.c), _ptr(src), off.ctypes.data_as(C.POINTER(C.c_int)), S,

@@ -1,6 +1,6 @@
 // q8_api.cpp -- the C ABI declared in q8nmt.h: argument validation, workspace carving
 // and the sequence of launches that makes up each call.  All arithmetic is in the
-// kernels (q8_kernels.hip).
+// kernels (the .hip files beside this one).
 #include "q8_internal.h"
 
 #include <new>
@@ -839,6 +839,8 @@ q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens
     if (l <= 0 || l > kMaxL) return q8_fail(ctx, Q8_ERR_SHAPE, "l = %d outside [1, %d]", l, kMaxL);
     if (beam <= 0 || beam > Q8_MAX_BEAM || k < beam || k > kMaxK || max_steps <= 0)
         return q8_fail(ctx, Q8_ERR_SHAPE, "need 1 <= beam <= %d, beam <= k <= %d, max_steps > 0", Q8_MAX_BEAM, kMaxK);
+    if (m->V_src <= 0 || m->V_tgt != m->W_out.rows)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "q8_translate: need V_src > 0 and V_tgt = rows of W_out");
     if (m->enc_fwd.Wx.cols != E || m->dec.r.Wx.cols != E || 2 * m->enc_fwd.Wh.cols != C || m->att_W.cols != C ||
         m->att_W.rows != A || m->enc_fwd.Wh.cols != H)
         return q8_fail(ctx, Q8_ERR_SHAPE, "q8_translate: model dimensions are inconsistent");
@@ -855,7 +857,7 @@ q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens
     q8_codes cc = {(int8_t *)(top + b.cq), (float *)(top + b.cs), m->dec.q.Wx.ld, 0};
     ctx->ws_reserved_top = ctx->ws_bytes - (size_t)(top - ctx->ws);
 
-    q8_status st = q8i_gather_rows(ctx, m->E_src, src_tokens, l, E, X);                        // x_i of Eq. 1
+    q8_status st = q8i_gather_rows(ctx, m->E_src, src_tokens, l, E, m->V_src, X);                        // x_i of Eq. 1
     if (!st) st = q8_encode(ctx, &m->enc_fwd, &m->enc_bwd, X, l, enc_h);                       // Eq. 1
     if (!st) st = q8_gemm_narrow(ctx, &m->att_W, enc_h, l, C, m->att_b, P, A, nullptr);        // w(h_i) of Eq. 6
     // initial decoder state: the backward encoder state at the first source position
@@ -1060,6 +1062,7 @@ q8_status q8_translate_ensemble(q8_ctx *ctx, const q8_model *const *models, int 
             m->att_W.rows != A || m->enc_fwd.Wh.cols != H)
             return q8_fail(ctx, Q8_ERR_SHAPE, "model %d: dimensions are inconsistent", i);
         if (m->W_out.rows != V) return q8_fail(ctx, Q8_ERR_SHAPE, "the models must share the target vocabulary");
+        if (m->V_src <= 0 || m->V_tgt != V) return q8_fail(ctx, Q8_ERR_SHAPE, "model %d: need V_src > 0 and V_tgt = rows of W_out", i);
     }
     if (l <= 0 || l > kMaxL) return q8_fail(ctx, Q8_ERR_SHAPE, "l = %d outside [1, %d]", l, kMaxL);
     if (beam <= 0 || beam > Q8_MAX_BEAM || k < beam || k > kMaxK || k > V || max_steps <= 0)
@@ -1082,7 +1085,7 @@ q8_status q8_translate_ensemble(q8_ctx *ctx, const q8_model *const *models, int 
         const q8_model *m = models[i];
         const EnsModelBufs &e = b.m[i];
         const int E = m->E, H = m->dec.r.Wh.cols, C = m->dec.q.Wx.cols, A = m->dec.att_U.rows;
-        st = q8i_gather_rows(ctx, m->E_src, src_tokens, l, E, F(e.X));
+        st = q8i_gather_rows(ctx, m->E_src, src_tokens, l, E, m->V_src, F(e.X));
         if (!st) st = q8_encode(ctx, &m->enc_fwd, &m->enc_bwd, F(e.X), l, F(e.enc_h));
         if (!st) st = q8_gemm_narrow(ctx, &m->att_W, F(e.enc_h), l, C, m->att_b, F(e.P), A, nullptr);
         // the same initial search state from every model; each call also fills that model's first inputs
@@ -1217,6 +1220,8 @@ q8_status q8_translate_batch(q8_ctx *ctx, const q8_model *m, const int32_t *src_
         return q8_fail(ctx, Q8_ERR_SHAPE, "need 1 <= beam <= %d, beam <= k <= %d, max_steps > 0", Q8_MAX_BEAM, kMaxK);
     if (n_sent <= 0 || (long long)n_sent * beam > kMaxMfmaN)
         return q8_fail(ctx, Q8_ERR_SHAPE, "need 1 <= n_sent and n_sent * beam <= %d", kMaxMfmaN);
+    if (m->V_src <= 0 || m->V_tgt != m->W_out.rows)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "q8_translate_batch: need V_src > 0 and V_tgt = rows of W_out");
     if (m->enc_fwd.Wx.cols != E || m->dec.r.Wx.cols != E || 2 * m->enc_fwd.Wh.cols != C || m->att_W.cols != C ||
         m->att_W.rows != A || m->enc_fwd.Wh.cols != H)
         return q8_fail(ctx, Q8_ERR_SHAPE, "q8_translate_batch: model dimensions are inconsistent");
@@ -1247,7 +1252,7 @@ q8_status q8_translate_batch(q8_ctx *ctx, const q8_model *m, const int32_t *src_
     q8_status st = Q8_OK;
     if (hipMemcpyAsync(off, sent_off_host, sizeof(int32_t) * (n_sent + 1), hipMemcpyHostToDevice, ctx->stream) != hipSuccess)
         st = q8_fail(ctx, Q8_ERR_DEVICE, "q8_translate_batch: offsets copy failed");
-    if (!st) st = q8i_gather_rows(ctx, m->E_src, src_tokens, total_l, E, X);                   // x_i of Eq. 1
+    if (!st) st = q8i_gather_rows(ctx, m->E_src, src_tokens, total_l, E, m->V_src, X);                   // x_i of Eq. 1
     if (!st) st = q8_encode_batch(ctx, &m->enc_fwd, &m->enc_bwd, X, off, sent_off_host, n_sent, enc_h);    // Eq. 1
     // w(h_i) of Eq. 6 for every position of every sentence (per-vector quantization: the
     // same values as sentence by sentence), in panels of at most 1024 positions

@@ -1,5 +1,5 @@
 // q8_internal.h -- host-side context and the launcher interface between the C ABI
-// (q8_api.cpp) and the kernels (q8_kernels.hip).  Not part of the public interface.
+// (q8_api.cpp) and the kernels (the .hip files beside it).  Not part of the public interface.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -196,7 +196,7 @@ q8_status q8i_logit_stats(q8_ctx *ctx, const float *logits, int n, int V, float 
 q8_status q8i_select_logits(q8_ctx *ctx, const float *part_max, const double *part_sum, const float *logits, int V, int n,
                             int k, float *lse, float *topk_logp, int32_t *topk_idx);
 size_t q8i_beam_state_bytes(int max_steps);
-q8_status q8i_gather_rows(q8_ctx *ctx, const float *table, const int *idx, int n, int dim, float *out);
+q8_status q8i_gather_rows(q8_ctx *ctx, const float *table, const int *idx, int n, int dim, int V, float *out);
 q8_status q8i_beam_init(q8_ctx *ctx, void *state, int beam, int max_steps, const float *s0, const float *E_tgt, int E,
                         int H, float *y_emb, float *s);
 q8_status q8i_beam_update(q8_ctx *ctx, void *state, const float *topk_logp, const int *topk_idx, int n, int k,

@@ -4,14 +4,17 @@
 // host never reads a score or a token inside the step loop.
 #include "q8_beam.h"
 
-// Rows of a table: out[i, :] = table[idx[i], :] (embedding lookup, Eq. 1).
+// Rows of a table of V rows: out[i, :] = table[idx[i], :] (embedding lookup, Eq. 1).  The ids live on
+// the device and were never seen by the host: an id outside [0, V) reads nothing and gives a zero row.
 __global__ __launch_bounds__(256) void gather_rows_kernel(const float *__restrict__ table, const int *__restrict__ idx,
-                                                          int n, int dim, float *__restrict__ out)
+                                                          int n, int dim, int V, float *__restrict__ out)
 {
     const int i = blockIdx.x;
     if (i >= n) return;
-    const float *src = table + (size_t)idx[i] * dim;
-    for (int c = threadIdx.x; c < dim; c += blockDim.x) out[(size_t)i * dim + c] = src[c];
+    const int id = idx[i];
+    const bool ok = (unsigned)id < (unsigned)V;
+    const float *src = table + (size_t)(ok ? id : 0) * dim;
+    for (int c = threadIdx.x; c < dim; c += blockDim.x) out[(size_t)i * dim + c] = ok ? src[c] : 0.0f;
 }
 
 __global__ __launch_bounds__(256) void beam_update_kernel(BeamUpdateArgs a)
@@ -109,9 +112,9 @@ __global__ __launch_bounds__(256) void beam_init_batch_kernel(BeamBatchArgs b)
 
 // =================================================================== host launchers ==
 
-q8_status q8i_gather_rows(q8_ctx *ctx, const float *table, const int *idx, int n, int dim, float *out)
+q8_status q8i_gather_rows(q8_ctx *ctx, const float *table, const int *idx, int n, int dim, int V, float *out)
 {
-    hipLaunchKernelGGL(gather_rows_kernel, dim3(n), dim3(256), 0, ctx->stream, table, idx, n, dim, out);
+    hipLaunchKernelGGL(gather_rows_kernel, dim3(n), dim3(256), 0, ctx->stream, table, idx, n, dim, V, out);
     return q8i_launch_check(ctx, "gather");
 }
 

@@ -38,3 +38,26 @@ def gpu_mat(q, ctx, W):
 def gpu_gru(q, ctx, p, prefix):
     return q.GruWeights(gpu_mat(q, ctx, p[prefix + ".Wx"]), gpu_mat(q, ctx, p[prefix + ".Wh"]),
                         ctx.f32(p[prefix + ".bx"]), ctx.f32(p[prefix + ".bh"]))
+
+
+def first_divergence_gap(m_ref, p, src, toks_a, toks_b):
+    """Two translations of `src` that differ: the step where they part, and the oracle's gap in
+    log-probability between the two tokens chosen there, after the common prefix (a sequence that
+    has ended counts as token 0).  A search that followed the rules can only differ from the
+    oracle's where the oracle's candidates nearly tie."""
+    a, b = list(toks_a), list(toks_b)
+    t = 0
+    while t < len(a) and t < len(b) and a[t] == b[t]:
+        t += 1
+    enc = m_ref.encode(p["E_src"][src])
+    P = m_ref.attention_precompute(enc)
+    s, last = enc[0, :m_ref.H].copy(), 0
+    for i in range(t + 1):
+        y = p["E_tgt"][last]
+        _, _, ctx, s = m_ref.cgru_step(P, enc, y, s)
+        if i == t:
+            logits, lse, _, _ = m_ref.output(m_ref.readout(s, y, ctx), 1)
+            ta = a[t] if t < len(a) else 0
+            tb = b[t] if t < len(b) else 0
+            return t, abs(float(logits[ta]) - float(logits[tb]))
+        last = a[i]

@@ -51,3 +51,22 @@ def test_host_side_helpers(lib):
     assert lib.q8_destroy(None) == 1
     assert lib.q8_gemv(None, None, None, None, None, None) == 1
     assert lib.q8_last_error(None) == b"NULL context"
+
+
+def test_source_token_ids_are_range_checked_on_the_host():
+    """Ids that arrive on the host are rejected before anything reaches the GPU (the embedding
+    lookup indexes a device table with them)."""
+    import numpy as np
+    import torch
+    import paper_1804_05038_amd as q
+    ok = q.source_ids([0, 5, 9], 10)
+    assert ok.dtype == torch.int32 and ok.tolist() == [0, 5, 9]
+    assert q.source_ids(np.array([3], np.int64), 4).tolist() == [3]
+    for bad in ([10], [-1], [2, 11, 3], np.array([2 ** 31 + 5], np.int64)):
+        with pytest.raises(ValueError):
+            q.source_ids(bad, 10)
+    for bad in ([], [[1, 2]], [1.5]):
+        with pytest.raises(ValueError):
+            q.source_ids(bad, 10)
+    with pytest.raises(ValueError):
+        q.source_ids(torch.tensor([1, 20]), 10)

@@ -58,6 +58,60 @@ def test_translate_full_size_model(q, ctx, oracle):
     _check_sentence(q, ctx, m_gpu, m_ref, src[:3], beam=1, k=12, max_steps=4)
 
 
+def test_translate_config5_sentences_at_full_length(q, ctx, oracle):
+    """The end-to-end workload itself: the full-size model, sentences of the benchmark's set (one of
+    the shortest, one of the longest), beam 5, top-12, up to 100 steps, through q8_translate and
+    q8_translate_batch against the oracle's search.  With random weights the end token is
+    practically never chosen, so these are 100 steps of 5 hypotheses: long back-pointer walks, a
+    hundred re-quantizations of drifting states, every "search over" read-back.  The token
+    sequences are expected to be identical; should one differ, the oracle's own candidates must
+    nearly tie at the step where they part (both sides round differently only in the last bit of
+    a log-sum-exp)."""
+    from concurrent.futures import ThreadPoolExecutor
+    from parity import first_divergence_gap
+    p = synth.full_model(seed=4)
+    m_ref = oracle.OracleModel(p)
+    m_gpu = q.Model.from_params(ctx, p)
+    sents = synth.sentences(seed=4, n=200)
+    lens = [len(x) for x in sents]
+    pick = [sents[int(np.argmin(lens))], sents[int(np.argmax(lens))]]
+    assert len(pick[0]) <= 12 and len(pick[1]) >= 58
+    with ThreadPoolExecutor(2) as ex:        # the oracle's calls release the interpreter lock
+        refs = list(ex.map(lambda src: m_ref.translate(src, beam=5, topk=12, max_steps=100), pick))
+    single = [q.q8_translate(ctx, m_gpu, src, beam=5, k=12, max_steps=100) for src in pick]
+    bctx = q.Context(workspace_bytes=q.q8_workspace_bytes(max_n=16, max_l=64, max_rows=50000, max_ld=2048) + (64 << 20))
+    batch = q.q8_translate_batch(bctx, m_gpu, pick, beam=5, k=12, max_steps=100)
+    for src, ref, one, bat in zip(pick, refs, single, batch):
+        assert ref[2] >= 50                                  # a long search, as the workload has them
+        for got, what in ((one, "q8_translate"), (bat, "q8_translate_batch")):
+            if got[0].tolist() != ref[0].tolist():
+                t, gap = first_divergence_gap(m_ref, p, src, got[0], ref[0])
+                assert gap < 1e-4, "%s parts from the oracle at step %d where the oracle's gap is %.3g" % (what, t, gap)
+                continue
+            assert got[2] == ref[2], what
+            assert abs(float(got[1]) - float(ref[1])) <= 1e-5 * max(1.0, abs(float(ref[1]))), what
+
+
+def test_source_id_outside_the_table_is_a_zero_embedding(q, ctx):
+    """Ids that reach the library on the device are not seen by the host: one outside [0, V_src) must
+    read nothing and count as a zero vector, the same as an in-range id whose table row is zero."""
+    V = 40
+    p = synth.full_model(seed=9, V=V, E=32, H=48, A=40, R=24, w_std=0.3, b_std=0.1)
+    p["E_src"][7] = 0.0
+    m = q.Model.from_params(ctx, p)
+    inside = torch.tensor([3, 7, 11, 7], dtype=torch.int32, device=ctx.device)
+    res = [q.q8_translate(ctx, m, inside, beam=3, k=5, max_steps=8)]
+    for bad in (V, V + 1000, -1, 2 ** 31 - 1, -2 ** 31):
+        outside = torch.tensor([3, bad, 11, 7], dtype=torch.int32, device=ctx.device)
+        res.append(q.q8_translate(ctx, m, outside, beam=3, k=5, max_steps=8))
+    for r in res[1:]:
+        assert r[0].tolist() == res[0][0].tolist() and r[1] == res[0][1] and r[2] == res[0][2]
+    got = q.q8_translate_batch(ctx, m, [inside, torch.tensor([V + 5, 3], dtype=torch.int32, device=ctx.device)], beam=3, k=5, max_steps=4)
+    assert len(got) == 2
+    with pytest.raises(ValueError):
+        q.q8_translate(ctx, m, [3, V, 11], beam=3, k=5, max_steps=8)       # host ids are checked before any launch
+
+
 def test_translate_paper_dimensions(q, ctx, oracle):
     """Embedding 620, hidden 1000 (Section 4) and the smallest vocabulary of Table 4: no dimension is a
     multiple of 64, so every row is padded; single-sentence and batched drivers against the oracle."""
