@@ -192,6 +192,25 @@ q8_status cgru_decoder_step_q8(q8_ctx *ctx, const q8_cgru_weights *w, const floa
                                float *s_out, float *ctx_out, float *alpha_out, float *s_mid_out,
                                const q8_taps *taps5);
 
+/* cgru_decoder_step_q8 (without taps) for callers that cannot allocate device memory or hand over
+ * a workspace of their own: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Its kernels' scratch (s', u(s'), the recurrent half of GRU q, the attention energies,
+ * the context codes, the arrival counters) lives in a static device array of
+ * q8_noalloc_scratch_bytes() = 1 MiB that every GPU the library runs on holds until the process
+ * ends; the context's own workspace is not touched, and no device memory is allocated or freed.
+ * Sizes that need more scratch than the array holds are refused with Q8_ERR_WORKSPACE (with
+ * H = A = 1024 every n_beam <= 8 and l <= 1024 fits).  All calls on one GPU share that GPU's array:
+ * calls that overlap there (two streams, two contexts) race; calls on one stream do not.
+ * q8_noalloc_setup looks the array up on the current device and clears its counters (it waits for
+ * the stream); the first cgru_decoder_step_noalloc_q8 on a device does the same if it was not
+ * called, and therefore must not be made under stream capture.  Results are bit-identical to
+ * cgru_decoder_step_q8. */
+size_t q8_noalloc_scratch_bytes(void);
+q8_status q8_noalloc_setup(q8_ctx *ctx);
+q8_status cgru_decoder_step_noalloc_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h,
+                                       int l, const float *y_emb, const float *s_prev, int n_beam,
+                                       float *s_out, float *ctx_out, float *alpha_out, float *s_mid_out);
+
 /* Variant of the attention block of Eq. 5-6 in which the two products without a trained matrix
  * are 8-bit as well (the other reading of Section 3; cgru_decoder_step_q8 keeps them in float).
  * q8_attention_states_q8 (once per sentence, synchronous like q8_quantize_matrix): the encoder

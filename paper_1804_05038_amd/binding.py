@@ -18,7 +18,8 @@ __all__ = ["Q8Error", "Context", "Mat", "Codes", "GruWeights", "CgruWeights", "R
            "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "MatF", "GruWeightsF32", "CgruWeightsF32", "ReadoutWeightsF32", "q8_gemv_f32",
            "cgru_decoder_step_f32", "output_logits_f32", "q8_translate_ensemble", "q8_translate_ensemble_bytes", "cgru_decoder_step_batch_q8", "q8_encode_batch", "q8_encode_batch_bytes", "q8_beam_init_batch",
            "q8_beam_update_batch", "q8_beam_result_batch", "q8_translate_batch", "q8_translate_batch_bytes",
-           "KERNEL_CLASSES", "LIB_PATH", "source_ids"]
+           "KERNEL_CLASSES", "LIB_PATH", "source_ids",
+           "cgru_decoder_step_noalloc_q8", "q8_noalloc_setup", "q8_noalloc_scratch_bytes"]
 LIB_PATH = _LIB_PATH
 
 STATUS = {0: "Q8_OK", 1: "Q8_ERR_NULL", 2: "Q8_ERR_SHAPE", 3: "Q8_ERR_ALIGN", 4: "Q8_ERR_WORKSPACE", 5: "Q8_ERR_DEVICE"}
@@ -92,6 +93,10 @@ def load_library():
         lib.gru_step_q8.argtypes = [vp, C.POINTER(_Gru), vp, vp, ci, vp, C.POINTER(_Taps)]
         lib.cgru_decoder_step_q8.argtypes = [vp, C.POINTER(_Cgru), vp, vp, ci, vp, vp, ci, vp, vp, vp, vp, C.POINTER(_Taps)]
         lib.cgru_decoder_step_codes_q8.argtypes = lib.cgru_decoder_step_q8.argtypes + [C.POINTER(_Codes), C.POINTER(_Codes)]
+        lib.cgru_decoder_step_noalloc_q8.argtypes = lib.cgru_decoder_step_q8.argtypes[:-1]
+        lib.q8_noalloc_setup.argtypes = [vp]
+        lib.q8_noalloc_scratch_bytes.restype = C.c_size_t
+        lib.q8_noalloc_scratch_bytes.argtypes = []
         lib.output_logits_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, vp, ci, ci,
                                          vp, vp, vp, vp, vp, C.POINTER(_Taps)]
         lib.q8_encode.argtypes = [vp, C.POINTER(_Gru), C.POINTER(_Gru), vp, ci, vp]
@@ -419,6 +424,23 @@ def cgru_decoder_step_q8(ctx, w, P, enc_h, y_emb, s_prev, out=None, taps=False, 
         return _Bound(ctx, fn, args, r)
     ctx.check(fn(*args))
     return r
+
+
+def q8_noalloc_setup(ctx):
+    ctx.check(ctx.lib.q8_noalloc_setup(ctx.handle))
+
+
+def q8_noalloc_scratch_bytes():
+    return load_library().q8_noalloc_scratch_bytes()
+
+
+def cgru_decoder_step_noalloc_q8(ctx, w, P, enc_h, y_emb, s_prev, out):
+    """cgru_decoder_step_q8 with its scratch in the library's static device array; `out` holds the
+    caller's s, ctx, alpha and s_mid tensors (nothing is allocated, here or in the library)."""
+    n, l = y_emb.shape[0], P.shape[0]
+    ctx.check(ctx.lib.cgru_decoder_step_noalloc_q8(ctx.handle, C.byref(w.c), _ptr(P), _ptr(enc_h), l, _ptr(y_emb), _ptr(s_prev), n,
+                                                   _ptr(out["s"]), _ptr(out["ctx"]), _ptr(out.get("alpha")), _ptr(out.get("s_mid"))))
+    return out
 
 
 def cgru_decoder_step_batch_q8(ctx, w, P, enc_h, sent_off, beam, max_l, y_emb, s_prev, out=None, bind=False, codes=None):

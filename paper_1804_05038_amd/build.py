@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libq8nmt.so")
-SOURCES = ["q8_products.hip", "q8_gemm.hip", "q8_gru.hip", "q8_decoder.hip", "q8_output.hip", "q8_search.hip", "q8_fp32.hip", "q8_api.cpp"]
+SOURCES = ["q8_products.hip", "q8_gemm.hip", "q8_gru.hip", "q8_decoder.hip", "q8_output.hip", "q8_search.hip", "q8_fp32.hip", "q8_noalloc.hip", "q8_api.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-fPIC", "-shared", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
