@@ -7,7 +7,8 @@
 struct AttArgs {
     const float *P, *enc_h, *a, *v;
     float *e, *alpha, *ctx;
-    unsigned *counters;     // one arrival counter per hypothesis, zero on entry and on exit
+    unsigned *counters;     // one arrival counter per hypothesis (cstride words apart), zero on entry and on exit
+    int cstride;
     int l, A, C;
     // several sentences side by side: hypothesis b belongs to sentence b / beam, whose rows of
     // P and enc_h are [sent_off[s], sent_off[s + 1]); NULL = one sentence of l positions
@@ -62,7 +63,7 @@ __device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const
             s_alpha[t] = (double)al;          // the weight as the context sum uses it: converted once, not per column
             if (a.alpha) a.alpha[(size_t)b * a.lde + t] = al;
         }
-        if (lane == 0) __hip_atomic_store(&a.counters[b], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (lane == 0) __hip_atomic_store(&a.counters[b * a.cstride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (a.ctx_q) {
@@ -154,8 +155,8 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
         // then count the arrival with a device-coherent atomic: the block that sees the last
         // count can read every energy with device-coherent loads, no cache flush needed.
         __hip_atomic_store(&a.e[(size_t)b * a.lde + i], (float)tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): the store above has been performed
-        const unsigned prev = __hip_atomic_fetch_add(&a.counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        q8_stores_performed();
+        const unsigned prev = __hip_atomic_fetch_add(&a.counters[b * a.cstride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_last = (prev == (unsigned)l - 1u);
     }
     __syncthreads();
@@ -198,11 +199,11 @@ __global__ __launch_bounds__(256) void attention_panel_kernel(AttArgs a)
     for (int m = 16; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);     // within the position's 32 lanes
     if (c == 0 && i < l)
         __hip_atomic_store(&a.e[(size_t)b * a.lde + i], (float)acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0): this wave's energies have been performed
+    q8_stores_performed();                       // this wave's energies
     __syncthreads();                             // ... and so have those of the other waves
     if (tid == 0) {
         const unsigned nblk = (unsigned)((l + ATTP_POS - 1) / ATTP_POS);
-        const unsigned prev = __hip_atomic_fetch_add(&a.counters[b], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned prev = __hip_atomic_fetch_add(&a.counters[b * a.cstride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_last = (prev == nblk - 1u);
     }
     __syncthreads();
@@ -434,6 +435,7 @@ q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, 
     AttArgs t;
     t.P = P; t.enc_h = enc_h; t.a = a; t.v = v; t.e = e; t.alpha = alpha; t.ctx = cvec;
     t.counters = (unsigned *)ctx->ws;
+    t.cstride = n <= Q8_MAX_BEAM ? Q8_COUNTER_STRIDE : 1;        // header: 1024 words of counters
     t.l = l; t.A = A; t.C = C;
     t.sent_off = sent_off; t.beam = beam; t.lde = l;
     const int threads = n > Q8_MAX_BEAM ? 256 : ATT_THREADS;

@@ -16,6 +16,28 @@ typedef unsigned v2u __attribute__((ext_vector_type(2)));
 
 #define Q8_WAVE 64
 
+// ------------------------------------------------------ hand-off between blocks ----
+// "The last block to arrive finishes": blocks of one kernel leave results for the block that comes
+// last.  On gfx950 the L2 caches of the eight XCDs are not coherent with each other, so the ordering
+// is built from operations that act at agent scope by themselves, not from fences (a release fence
+// writes the whole L2 back and an acquire fence invalidates it: 1.5 us each, measured, and the
+// invalidation would also drop the vocabulary matrix that is kept resident there):
+//   writer: agent-scope relaxed atomic stores of the data (performed in memory, past the L2), then
+//           q8_stores_performed(), then one agent-scope relaxed atomic add on the arrival counter;
+//   reader: sees the last count (its own add returned it), then reads the data with agent-scope
+//           relaxed atomic loads, which are served from memory and cannot hit a stale line.
+// q8_stores_performed: the wave waits until every store it has issued has been acknowledged
+// (s_waitcnt vmcnt(0); gfx950 counts stores in vmcnt), and the compiler may not move memory
+// operations across it.  The counter's add is program-ordered after it, so it cannot be performed
+// before the data.  Block-wide: every wave calls it, then __syncthreads(), then one thread counts.
+__device__ __forceinline__ void q8_stores_performed()
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+// Arrival counters of concurrent hand-offs sit 256 bytes apart when there are few of them: atomics
+// on one address (and on neighbours in one line) are performed one after the other, about 10 ns each.
+#define Q8_COUNTER_STRIDE 64
+
 // ---------------------------------------------------------------- cross-lane ----
 
 template <int CTRL>

@@ -582,7 +582,7 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     // until its own (device-coherent) top-k stores have been performed, then one thread
     // counts the block's arrival with a device-coherent atomic.
     __shared__ int s_is_last;
-    __builtin_amdgcn_s_waitcnt(0x0F70);          // vmcnt(0)
+    q8_stores_performed();
     __syncthreads();
     if (tid == 0) {
         const unsigned prev_cnt = __hip_atomic_fetch_add(a.counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
