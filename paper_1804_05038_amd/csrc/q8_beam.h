@@ -40,112 +40,104 @@ __device__ __forceinline__ unsigned long long cand_key(float score, int parent, 
 
 __device__ __forceinline__ void beam_gather(const BeamUpdateArgs &a, const int *s_parent, const int *s_token);
 
-// One block of 256 threads.  The (at most 128) candidates are ranked by counting: thread
-// (c, half) counts how many of one half of the keys beat candidate c, so a candidate's rank is
-// known after two barriers; thread 0 then walks the best b_live in order (finished hypotheses
-// leave the beam, the others become the next step's slots) and rewrites the state; all threads
-// gather the surviving decoder states and the embeddings of the new tokens.  COHERENT: the top-k
-// tables were written by other blocks of the same kernel with device-coherent stores and are
-// read with device-coherent loads.
+// One block of at least 64 threads.  The decisions of a search step are taken by the block's first
+// wave alone, without barriers: lane L holds candidates L and L + 64 of the (at most 128) n_live x k
+// candidates as 64-bit keys (score, parent, token); b_live rounds of a wave-wide maximum hand the
+// best b_live of them, in order, to lanes 0, 1, ...; ballots over those lanes give every survivor its
+// slot, the number of hypotheses that ended and the best of them; lane q then writes slot q of the
+// state.  Only then does the block meet, and all threads gather the surviving decoder states and the
+// embeddings of the new tokens.  COHERENT: the top-k tables were written by other blocks of the same
+// kernel with device-coherent stores and are read with device-coherent loads.
 template <bool COHERENT>
 __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
 {
     __shared__ int s_parent[Q8_MAX_BEAM], s_token[Q8_MAX_BEAM];
-    __shared__ __align__(16) unsigned long long s_key[128];
-    __shared__ int s_rank[128];
-    __shared__ float s_rscore[Q8_MAX_BEAM];
-    __shared__ int s_rtoken[Q8_MAX_BEAM], s_rparent[Q8_MAX_BEAM];
     __shared__ int s_skip;
     BeamState *st = a.st;
     const int tid = threadIdx.x;
-    // everything the selection needs is requested at once, before any of it is looked at
-    const int c = tid & 127, half = tid >> 7;
-    float lp = 0.0f, sc0 = 0.0f;
-    int tk = 0;
-    if (c < a.n * a.k) {
-        lp = COHERENT ? __hip_atomic_load(a.topk_logp + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.topk_logp[c];
-        tk = COHERENT ? __hip_atomic_load(a.topk_idx + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.topk_idx[c];
-        sc0 = st->score[c / a.k];
-    }
-    const int n_live = st->n_live, b_live = st->b_live, step = st->step, max_steps = st->max_steps;
-    const bool skip = st->done != 0;
-    const int have_fin0 = st->have_fin, fin_len0 = st->fin_len, fin_parent0 = st->fin_parent;
-    const float fin_score0 = st->fin_score;
-    const int ncand = skip ? 0 : n_live * a.k;
-    const int take = min(b_live, ncand);
-    unsigned long long key = 0ull;
-    float csc = -INFINITY;
-    if (c < ncand) {
-        csc = sc0 + lp;
-        key = cand_key(csc, c / a.k, tk);
-    }
-    if (half == 0) {
-        s_key[c] = key;
-        s_rank[c] = 0;
-    }
-    __syncthreads();
-    if (c < ncand) {
-        // keys are distinct (they contain parent and token), so the counts are a permutation
-        const int lo = half * 64;
-        int cnt = 0;
-#pragma unroll 4
-        for (int u = lo; u < lo + 64 && u < ncand; u += 2) {
-            const ulonglong2 p2 = *(const ulonglong2 *)&s_key[u];
-            cnt += (p2.x > key) + (p2.y > key);
+    if (tid < 64) {
+        const int lane = tid;
+        // everything the decisions need is requested at once, before any of it is looked at
+        float lp[2];
+        int tk[2];
+        const int nk = a.n * a.k;
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int c = min(lane + 64 * u, nk - 1);      // (a lane past the tables reads their last entry and drops it)
+            lp[u] = COHERENT ? __hip_atomic_load(a.topk_logp + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.topk_logp[c];
+            tk[u] = COHERENT ? __hip_atomic_load(a.topk_idx + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.topk_idx[c];
         }
-        if (cnt) atomicAdd(&s_rank[c], cnt);
-    }
-    __syncthreads();
-    if (half == 0 && c < ncand) {
-        const int r = s_rank[c];
-        if (r < take) { s_rscore[r] = csc; s_rtoken[r] = tk; s_rparent[r] = c / a.k; }
-    }
-    __syncthreads();
-    __shared__ float s_nscore[Q8_MAX_BEAM];
-    __shared__ int s_nnew;
-    if (tid == 0) {
-        int n_new = 0;
+        const float sc_slot = st->score[lane & (Q8_MAX_BEAM - 1)];      // lane q < 8: score of slot q
+        const int n_live = st->n_live, b_live = st->b_live, step = st->step, max_steps = st->max_steps;
+        const bool skip = st->done != 0;
+        const int have_fin0 = st->have_fin;
+        const float fin_score0 = st->fin_score;
+        const int ncand = skip ? 0 : n_live * a.k;
+        const int take = min(b_live, ncand);
+        // candidate c = parent * k + rank in the parent's list; parent = floor((c + 0.5) / k) in float
+        // (the quotient is at least 1 / (2 k) away from an integer, far more than the reciprocal's error)
+        const float rk = __builtin_amdgcn_rcpf((float)a.k);
+        unsigned long long key[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int c = lane + 64 * u;
+            const int p = (int)(((float)c + 0.5f) * rk);
+            const float sp = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (p & (Q8_MAX_BEAM - 1)), __float_as_int(sc_slot)));
+            key[u] = c < ncand ? cand_key(sp + lp[u], p, tk[u]) : 0ull;
+        }
+        // the best `take` keys, in order, into lanes 0 .. take - 1 (keys are distinct: they contain parent and
+        // token).  Rounds of a wave-wide maximum: counting ranks through LDS was measured slower (1.3 against 1.0 us).
+        unsigned long long mine = 0ull;
+        for (int r = 0; r < take; ++r) {
+            const unsigned long long best = wave_max_u64(key[0] > key[1] ? key[0] : key[1]);
+            if (key[0] == best) key[0] = 0ull;
+            if (key[1] == best) key[1] = 0ull;
+            if (lane == r) mine = best;
+        }
+        const bool kept = lane < take;
+        unsigned ub = (unsigned)(mine >> 32);
+        ub = (ub & 0x80000000u) ? (ub & 0x7fffffffu) : ~ub;
+        const float sc = __uint_as_float(ub);
+        int parent = 15 - (int)((mine >> 20) & 0xFFFu), token = 0xFFFFF - (int)(mine & 0xFFFFFu);
+        // non-finite scores can leave fewer than k valid candidates per hypothesis: whatever the tables
+        // then hold, the gather below stays inside s_step and E_tgt
+        if (a.V > 0 && (unsigned)token >= (unsigned)a.V) token = 0;
+        if ((unsigned)parent >= (unsigned)a.n) parent = 0;
+        const unsigned long long ended = __ballot(kept && token == 0), alive = __ballot(kept && token != 0);
+        const int n_new = __popcll(alive), b_left = b_live - __popcll(ended);
+        const int slot = __popcll(alive & ((1ull << lane) - 1ull));
+        if (kept && token != 0) { s_parent[slot] = parent; s_token[slot] = token; }
+        // the hypotheses that ended: the first in order has the highest score; it replaces the remembered
+        // one only if it is better (ties to the earlier)
+        const int first_end = ended ? (int)__ffsll((long long)ended) - 1 : 0;
+        const float end_sc = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sc), first_end));
+        const int end_parent = __builtin_amdgcn_readlane(parent, first_end);
+        const int first_alive = alive ? (int)__ffsll((long long)alive) - 1 : 0;
+        const int parent0 = n_new ? __builtin_amdgcn_readlane(parent, first_alive) : 0;
+        const int token0 = n_new ? __builtin_amdgcn_readlane(token, first_alive) : 0;
+        __builtin_amdgcn_wave_barrier();
         if (!skip) {
-            int have_fin = have_fin0, fin_len = fin_len0, fin_parent = fin_parent0;
-            float fin_score = fin_score0;
-            int b_left = b_live;
-            for (int r = 0; r < take; ++r) {
-                const float sc = s_rscore[r];
-                int token = s_rtoken[r], parent = s_rparent[r];
-                // non-finite scores can leave fewer than k valid candidates per hypothesis: whatever
-                // the tables then hold, the gather below stays inside s_step and E_tgt
-                if (a.V > 0 && (unsigned)token >= (unsigned)a.V) token = 0;
-                if ((unsigned)parent >= (unsigned)a.n) parent = 0;
-                if (token == 0) {                      // end of sentence: the hypothesis is finished
-                    if (!have_fin || sc > fin_score) {
-                        have_fin = 1; fin_score = sc; fin_len = step; fin_parent = parent;
-                    }
-                    --b_left;
-                } else {
-                    s_nscore[n_new] = sc; s_token[n_new] = token; s_parent[n_new] = parent;
-                    ++n_new;
-                }
+            // slot q of the new state, lane q: its score and last token come from the survivor that took slot q
+            if (kept && token != 0) {
+                st->score[slot] = sc;
+                st->last[slot] = token;
+                st->link[(size_t)step * Q8_MAX_BEAM + slot] = (parent << 24) | token;
             }
-            st->have_fin = have_fin; st->fin_score = fin_score; st->fin_len = fin_len; st->fin_parent = fin_parent;
-            st->n_live = n_new; st->b_live = b_left; st->step = step + 1;
-            if (b_left == 0 || n_new == 0 || step + 1 >= max_steps) st->done = 1;
+            if (lane >= n_new && lane < Q8_MAX_BEAM) { st->score[lane] = -INFINITY; st->last[lane] = 0; }
+            if (lane == 0) {
+                if (ended && (!have_fin0 || end_sc > fin_score0)) {
+                    st->have_fin = 1; st->fin_score = end_sc; st->fin_len = step; st->fin_parent = end_parent;
+                }
+                st->n_live = n_new; st->b_live = b_left; st->step = step + 1;
+                if (b_left == 0 || n_new == 0 || step + 1 >= max_steps) st->done = 1;
+            }
         }
-        s_nnew = n_new;
-        s_skip = skip;
-        st->gathered = skip ? 0 : 1;
-    }
-    __syncthreads();
-    if (!skip && tid < Q8_MAX_BEAM) {                   // slot tid of the state, one thread each
-        const int n_new = s_nnew, q = tid;
-        st->score[q] = q < n_new ? s_nscore[q] : -INFINITY;
-        st->last[q] = q < n_new ? s_token[q] : 0;
-        if (q < n_new) st->link[(size_t)step * Q8_MAX_BEAM + q] = (s_parent[q] << 24) | s_token[q];
-    }
-    __syncthreads();
-    if (!skip && tid < Q8_MAX_BEAM && tid >= s_nnew) {  // dead slots repeat survivor 0: finite data for the next step
-        const int p0 = s_nnew ? s_parent[0] : 0, t0 = s_nnew ? s_token[0] : 0;
-        s_parent[tid] = p0;
-        s_token[tid] = t0;
+        if (lane == 0) { st->gathered = skip ? 0 : 1; s_skip = skip; }
+        // dead slots repeat survivor 0 (slot 0 of the tables if nothing survived): finite data for the next step
+        if (!skip && lane >= n_new && lane < Q8_MAX_BEAM) {
+            s_parent[lane] = parent0;
+            s_token[lane] = token0;
+        }
     }
     __syncthreads();
     if (s_skip) return;
