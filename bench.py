@@ -24,9 +24,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM-side bytes of one launch of the vocabulary kernel, from the two counter runs recorded in
-# profiles/decode_step_beam5_kernels.txt: 26.28 MB fetched + 2.00 MB written
+# From the committed profile profiles/decode_step_beam5_kernels.txt (rocprofv3 runs of this file with --quick):
+# HBM-side bytes of one launch of the vocabulary kernel (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00 with the L2 serialized away),
+# its average duration on the kernel trace's clock, and the 25.6 MB read probe's on the same clock
 VOCAB_KERNEL_TRAFFIC_BYTES = 28.15e6
+VOCAB_KERNEL_TRACE_US = 5.92
+READ_PROBE_TRACE_US = 2.68
 L, BEAM, TOPK, MAX_STEPS = 30, 5, 12, 100
 
 
@@ -136,6 +139,67 @@ def cpu_baseline(p, seconds=12.0):
     return {"value": total / dt, "unit": "steps/s", "cores": threads, "kind": "oracle", "units_on_one_core": units,
             "sample": "%d beam-5 decoder steps (cGRU step + output layer, source length %d) in %.1f s, one "
                       "independent stream of steps per thread" % (total, L, dt)}
+
+
+def parity_block(q, ctx, m, p, n_sent=3):
+    """Free-running agreement with the oracle on the end-to-end workload itself (part of the CPU leg): the
+    first sentences of the 200 are translated by both sides at full length (beam 5, up to 100 steps), and
+    the first decoder step of the first sentence is compared value by value, each side on its own
+    intermediates (encoder, attention pre-computation, conditional GRU)."""
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import q8_oracle as o
+    from workloads import synth
+    mo = o.OracleModel(p)
+    sents = synth.sentences(seed=4, n=200)[:n_sent]
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(n_sent) as ex:                     # the oracle's calls release the interpreter lock
+        refs = list(ex.map(lambda src: mo.translate(src, beam=BEAM, topk=TOPK, max_steps=MAX_STEPS), sents))
+    oracle_s = time.perf_counter() - t0
+    got = [q.q8_translate(ctx, m, src, beam=BEAM, k=TOPK, max_steps=MAX_STEPS) for src in sents]
+    same = sum(g[0].tolist() == r[0].tolist() for g, r in zip(got, refs))
+    score_dev = max(abs(float(g[1]) - float(r[1])) / max(1.0, abs(float(r[1]))) for g, r in zip(got, refs))
+    # first decoder step of the first sentence, free-running on both sides
+    src = sents[0]
+    enc_ref = mo.encode(p["E_src"][src])
+    P_ref = mo.attention_precompute(enc_ref)
+    y, s0 = p["E_tgt"][0], enc_ref[0, :mo.H].copy()
+    s_mid, alpha, cx, s_ref = mo.cgru_step(P_ref, enc_ref, y, s0)
+    enc = q.q8_encode(ctx, m.enc_fwd, m.enc_bwd, ctx.f32(p["E_src"][src]))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc, m.att_b)
+    r = q.cgru_decoder_step_q8(ctx, m.dec, P, enc, ctx.f32(y[None, :]), enc[0:1, :mo.H].contiguous(), taps=True)
+
+    def dev(a, b):
+        a, b = a.cpu().numpy().astype(np.float64).ravel(), np.asarray(b, np.float64).ravel()
+        return float((np.abs(a - b) / np.maximum(np.abs(b), np.sqrt((b ** 2).mean()))).max())
+
+    codes_ref = [o.quantize(v)[0] for v in (y, s0, s_mid, cx, s_mid)]      # inputs of the step's five products
+    differing = sum(int((r["taps"][i]["xq"][0].cpu().numpy() != c).sum()) for i, c in enumerate(codes_ref))
+    return {"sentences_checked": n_sent, "identical_token_sequences": same, "target_tokens": [int(len(x[0])) for x in refs],
+            "decoder_steps": [int(x[2]) for x in refs], "max_rel_deviation_of_scores": score_dev,
+            "first_step_max_rel_deviation": {"encoder_states": dev(enc, enc_ref), "P": dev(P, P_ref), "s_mid": dev(r["s_mid"], s_mid),
+                                             "context": dev(r["ctx"], cx), "s": dev(r["s"], s_ref)},
+            "first_step_int8_codes_differing": differing, "first_step_int8_codes_compared": int(sum(c.size for c in codes_ref)),
+            "oracle_seconds": oracle_s,
+            "note": "relative deviation = |gpu - oracle| / max(|oracle|, rms(oracle)), each side free-running on its own "
+                    "intermediates; sentences = the first of the 200 synthetic ones, beam 5, up to 100 steps"}
+
+
+def vocab_kernel_cold(torch, q, ctx, m, rng, reps=240):
+    """The vocabulary kernel with its matrix coming from HBM: 24 tile-packed copies of W_out (614 MB, more than
+    twice the Infinity Cache) taken in turn, timed by event pairs on the kernel's dispatches."""
+    copies = 24
+    W = m.W_out
+    mats = [q.Mat(W.data.clone(), W.cols, W.scale, W.tiles.clone()) for _ in range(copies)]
+    t = ctx.f32(rng.standard_normal((BEAM, W.cols)).astype(np.float32))
+    calls = [q.output_logits_q8(ctx, None, M, m.b_out, t_in=t, k=TOPK, want_logits=False, bind=True) for M in mats]
+    for c in calls:
+        c.launch()
+    q.q8_profile_begin(ctx, "vocab", reps)
+    for i in range(reps):
+        calls[i % copies].launch()
+    ms, n = q.q8_profile_end(ctx)
+    del calls, mats
+    return {"kernel_us": ms * 1e3, "samples": n, "copies": copies}
 
 
 def gemv_bandwidth(torch, q, ctx, rng):
@@ -454,9 +518,14 @@ def main():
     loop5 = DecodeLoop(q, ctx, m, P, enc_h, BEAM, rng)
     loop1 = DecodeLoop(q, ctx, m, P, enc_h, 1, rng)
 
-    # ---- timed region: K decoder steps at beam 5, launched eagerly on torch's current stream ----
+    # ---- timed region.  K decoder steps at beam 5 launched eagerly on torch's current stream (the
+    # contract's K and W), and the headline: the paper's own protocol (Section 4.1: median of 9 runs),
+    # 9 repetitions of a replayed HIP graph of one 100-step search, at least 1000 steps per repetition
+    # whatever K is, median and minimum reported.
     eager5 = time_loop(torch, loop5.step, args.steps, args.warmup)
-    best5, mode = eager5, "eager launches"
+    best5, mode = eager5, "eager launches, %d steps" % args.steps
+    timed = {"repetitions": 1, "steps_per_repetition": args.steps, "steps_timed": args.steps, "median_us_per_step": eager5 * 1e6,
+             "min_us_per_step": eager5 * 1e6}
     graph_us = None
     if not args.no_graph and not args.quick:
         try:
@@ -472,10 +541,23 @@ def main():
                     for _ in range(MAX_STEPS):
                         gloop.step()
             torch.cuda.synchronize()
-            graph_s = time_loop(torch, g.replay, max(args.steps // MAX_STEPS, 3), 2) / MAX_STEPS
+            replays = max(10, -(-args.steps // (9 * MAX_STEPS)))
+            for _ in range(3):
+                g.replay()
+            reps = []
+            for _ in range(9):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(replays):
+                    g.replay()
+                torch.cuda.synchronize()
+                reps.append((time.perf_counter() - t0) / (replays * MAX_STEPS))
+            graph_s = float(np.median(reps))
             graph_us = graph_s * 1e6
             if graph_s < best5:
-                best5, mode = graph_s, "HIP graph of one 100-step search, replayed"
+                best5, mode = graph_s, "HIP graph of one 100-step search, replayed: median of 9 repetitions of %d replays" % replays
+                timed = {"repetitions": 9, "steps_per_repetition": replays * MAX_STEPS, "steps_timed": 9 * replays * MAX_STEPS,
+                         "median_us_per_step": graph_us, "min_us_per_step": float(np.min(reps)) * 1e6}
         except Exception as e:  # graph capture only changes how the launches reach the GPU
             graph_us = "unavailable: %s" % (str(e).splitlines()[0][:120])
 
@@ -509,20 +591,27 @@ def main():
                     for st, c, lp, gr in lanes[:ns]:
                         with torch.cuda.stream(st):
                             gr.replay()
-                reps = max(args.steps // MAX_STEPS, 3)
+                reps = max(args.steps // MAX_STEPS, 10)
                 per = time_loop(torch, replay_all, reps, 2)
                 concurrent["%d_sentences_steps_per_s" % ns] = ns * MAX_STEPS / per
         except Exception as e:
             concurrent = "unavailable: %s" % (str(e).splitlines()[0][:120])
 
     # ---- dominant kernel: the vocabulary projection, timed by events attached to its dispatch ----
-    ktimes = kernel_times(torch, q, ctx, loop5.step, args.steps)
-    k_ms, k_n = ktimes["vocab"]["avg_us"] * 1e-3, int(ktimes["vocab"]["launches_per_step"] * args.steps)
+    ksteps = max(args.steps, 1000)
+    ktimes = kernel_times(torch, q, ctx, loop5.step, ksteps)
+    k_ms, k_n = ktimes["vocab"]["avg_us"] * 1e-3, int(ktimes["vocab"]["launches_per_step"] * ksteps)
     ceil_warm = read_ceiling(torch, q, ctx, 25600000, cold=False)
     V, R = 50000, 512
     out_bytes = V * R + 4 * V + BEAM * R * 4 + BEAM * V * 4   # int8 weights, bias, hidden vectors, logits written
     achieved = out_bytes / (k_ms * 1e-3) / 1e9
 
+    cold = None
+    if not args.quick:
+        c = vocab_kernel_cold(torch, q, ctx, m, rng)
+        cold = {"what": "the same kernel with the matrix coming from HBM: 24 tile-packed copies (614 MB) taken in turn, event pairs",
+                "kernel_us": c["kernel_us"], "samples": c["samples"], "achieved_GBps": out_bytes / c["kernel_us"] / 1e3,
+                "frac_of_peak": out_bytes / c["kernel_us"] / 1e3 / HBM_PEAK_GBS}
     extra = {}
     if args.quick:
         # reference for the HBM byte counters of a profiling run: a plain copy of known size
@@ -566,11 +655,13 @@ def main():
         extra["ensemble_of_2"] = ensemble_run(torch, q, p, m, 5)
         extra["steps_per_s_beam1"] = 1.0 / eager1
     cpu = None if (args.no_cpu_baseline or args.quick) else cpu_baseline(p)
+    if cpu is not None:
+        cpu["parity"] = parity_block(q, ctx, m, p)
 
     weights_per_step = 15204352 + 1835008 + 25600000
     line = {
         "metric": "decoder steps/sec at beam 5", "value": 1.0 / best5, "unit": "steps/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": best5 * 1e3,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": best5 * 1e3, "timed": timed,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
         "data": "synthetic",
         "config": {"workload": "full decoder step for one sentence: conditional-GRU step + output layer + beam update "
@@ -583,10 +674,20 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": VOCAB_KERNEL_TRAFFIC_BYTES, "traffic_unit": "bytes per launch",
                      "traffic_source": "rocprofv3 --pmc FETCH_SIZE (x2.00) + WRITE_SIZE (x1.00) of bench.py --quick (dispatches serialized by "
-                                       "the counter run: no reuse of the L2 between steps), profiles/decode_step_beam5_kernels.txt", "bytes_per_launch": out_bytes, "kernel_us": k_ms * 1e3, "samples": k_n,
-                     "regime": "warm: the same weights every step; the vocabulary matrix stays in the 32 MB of L2, the step's other matrices are streamed from the 256 MB Infinity Cache",
-                     "read_stream_ceiling_GBps": ceil_warm["GBps"], "read_stream_ceiling_us": ceil_warm["kernel_us"],
-                     "frac_of_read_stream_ceiling": ceil_warm["kernel_us"] / (k_ms * 1e3)},
+                                       "the counter run: no reuse of the L2 between steps), profiles/decode_step_beam5_kernels.txt",
+                     "bytes_per_launch": out_bytes, "kernel_us": k_ms * 1e3, "samples": k_n,
+                     "clock": "HIP event pair on the kernel's dispatch, measured live in the running decoder loop (includes the dispatch: "
+                              "about 0.5 us more than the kernel trace's duration)",
+                     "regime": "warm: the same weights every step; the vocabulary matrix stays in the 32 MB of L2, the step's other "
+                               "matrices are streamed from the 256 MB Infinity Cache",
+                     "cache_resident_bound": {"what": "a plain read stream over 25.6 MB in the same state (q8_probe_read on one buffer), same clock",
+                                              "kernel_us": ceil_warm["kernel_us"], "GBps": ceil_warm["GBps"],
+                                              "frac_of_bound": ceil_warm["kernel_us"] / (k_ms * 1e3)},
+                     "kernel_trace_clock": {"source": "profiles/decode_step_beam5_kernels.txt (rocprofv3 --kernel-trace --stats of bench.py --quick)",
+                                            "kernel_us": VOCAB_KERNEL_TRACE_US, "achieved_GBps": out_bytes / VOCAB_KERNEL_TRACE_US / 1e3,
+                                            "frac_of_peak": out_bytes / VOCAB_KERNEL_TRACE_US / 1e3 / HBM_PEAK_GBS,
+                                            "read_probe_us": READ_PROBE_TRACE_US, "frac_of_read_probe": READ_PROBE_TRACE_US / VOCAB_KERNEL_TRACE_US},
+                     "cold_hbm": cold},
         "kernels_in_loop_us": ktimes,
         "cpu_baseline": cpu,
     }
