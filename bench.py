@@ -205,15 +205,20 @@ def vocab_kernel_cold(torch, q, ctx, m, rng, reps=240):
 def gemv_bandwidth(torch, q, ctx, rng):
     """Metric M1: the streaming int8 matrix-vector product (one vector, dot4 path), warm (the
     same matrix every call: cache-resident) and cold (rotating over copies whose total size
-    exceeds twice the 256 MB Infinity Cache)."""
+    exceeds twice the 256 MB Infinity Cache).  The two sizes of the workload are followed by two
+    larger ones (the vocabulary matrix repeated 8 and 40 times: 205 MB and 1 GB) that show the
+    kernel's rate once the fixed cost of a launch no longer counts."""
     out = {}
-    for name, rows, cols in (("3072x1024", 3072, 1024), ("50000x512", 50000, 512)):
-        W = (rng.standard_normal((rows, cols)) * 0.05).astype(np.float32)
+    for name, rows, cols in (("3072x1024", 3072, 1024), ("50000x512", 50000, 512),
+                             ("400000x512", 400000, 512), ("2000000x512", 2000000, 512)):
+        W = (rng.standard_normal((min(rows, 50000), cols)) * 0.05).astype(np.float32)
         M = q.q8_quantize_matrix(ctx, W)
+        if rows > 50000:
+            M = q.Mat(M.data.repeat(rows // 50000, 1).contiguous(), cols, M.scale)
         x = ctx.f32(rng.standard_normal(cols).astype(np.float32))
         y = ctx.empty(rows)
         nbytes = rows * cols + 4 * cols + 4 * rows
-        warm = median_of(torch, lambda: q.q8_gemv(ctx, M, x, None, y), inner=100)
+        warm = median_of(torch, lambda: q.q8_gemv(ctx, M, x, None, y), inner=100 if rows <= 50000 else 20)
         copies = max(2, int(2.2 * 256e6 / (rows * cols)) + 1)
         mats = [q.Mat(M.data.clone(), cols, M.scale) for _ in range(copies)]
         it = [0]
@@ -494,6 +499,9 @@ def main():
     ap.add_argument("--quick", action="store_true", help="beam-5 timed region and kernel timing only (profiling runs)")
     ap.add_argument("--sentences", type=int, default=20)
     ap.add_argument("--batched", action="store_true", help="only the batched decoder step at 64 sentences (profiling runs)")
+    ap.add_argument("--counters", action="store_true",
+                    help="short workload for hardware-counter runs: 300 decoder steps at beam 5, the vocabulary kernel 200 times back "
+                         "to back on one matrix and on 24 copies in turn, the two matrix-core products of a sentence, 20 batched steps")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (translation shards by sentence, one sentence per GPU, "
@@ -512,6 +520,30 @@ def main():
     enc_h = ctx.f32(rng.standard_normal((L, 2048)).astype(np.float32))
     P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
 
+    if args.counters:
+        loop = DecodeLoop(q, ctx, m, P, enc_h, BEAM, rng)
+        for _ in range(300):
+            loop.step()
+        torch.cuda.synchronize()
+        t = ctx.f32(rng.standard_normal((BEAM, 512)).astype(np.float32))
+        one = q.output_logits_q8(ctx, None, m.W_out, m.b_out, t_in=t, k=TOPK, want_logits=False, bind=True)
+        for _ in range(200):                       # the same matrix every launch
+            one.launch()
+        torch.cuda.synchronize()
+        mats = [q.Mat(m.W_out.data.clone(), m.W_out.cols, m.W_out.scale, m.W_out.tiles.clone()) for _ in range(24)]
+        calls = [q.output_logits_q8(ctx, None, M, m.b_out, t_in=t, k=TOPK, want_logits=False, bind=True) for M in mats]
+        for i in range(240):                       # 24 copies in turn: every launch from HBM
+            calls[i % 24].launch()
+        torch.cuda.synchronize()
+        mfma_products(torch, q, ctx, m, rng)
+        batched_decoding(torch, q, m, rng, 20, sizes=(64,), translate=False)
+        src = torch.empty(64 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)      # the byte counters' reference
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"counters_workload": "done"}))
+        return
     if args.batched:
         print(json.dumps({"batched_decoding": batched_decoding(torch, q, m, rng, args.steps // 10, sizes=(64,), translate=False)}))
         return
