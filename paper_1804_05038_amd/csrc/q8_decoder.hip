@@ -165,14 +165,13 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
 }
 
 // Many hypotheses (sentences side by side): throughput matters, not the latency of one
-// energy.  Block (g, b) of 256 threads takes source positions 8 g .. 8 g + 7 of hypothesis
-// b; thread (p, c) = (tid / 32, tid % 32) sums columns 4 c + 128 u, u = 0, 1, ..., of
-// position 8 g + p, and the 32 partial sums of a position are added across lanes.
+// energy, and the work is split over two kernels.  First the energies: block (g, b) of 256
+// threads takes source positions 8 g .. 8 g + 7 of hypothesis b; thread (p, c) =
+// (tid / 32, tid % 32) sums columns 4 c + 128 u, u = 0, 1, ..., of position 8 g + p, and the
+// 32 partial sums of a position are added across lanes.
 #define ATTP_POS 8
 __global__ __launch_bounds__(256) void attention_panel_kernel(AttArgs a)
 {
-    __shared__ double s_alpha[1024];
-    __shared__ int s_last;
     const int b = blockIdx.y, tid = threadIdx.x;
     const float *P, *enc_h;
     const int l = att_sentence(a, b, P, enc_h);
@@ -197,17 +196,33 @@ __global__ __launch_bounds__(256) void attention_panel_kernel(AttArgs a)
     }
 #pragma unroll
     for (int m = 16; m >= 1; m >>= 1) acc += __shfl_xor(acc, m, 64);     // within the position's 32 lanes
-    if (c == 0 && i < l)
-        __hip_atomic_store(&a.e[(size_t)b * a.lde + i], (float)acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    q8_stores_performed();                       // this wave's energies
-    __syncthreads();                             // ... and so have those of the other waves
-    if (tid == 0) {
-        const unsigned nblk = (unsigned)((l + ATTP_POS - 1) / ATTP_POS);
-        const unsigned prev = __hip_atomic_fetch_add(&a.counters[b * a.cstride], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_last = (prev == nblk - 1u);
+    if (c == 0 && i < l) a.e[(size_t)b * a.lde + i] = (float)acc;
+}
+
+// Then softmax and context vector (Eq. 5) of every hypothesis: att_finish as a kernel of its own, one
+// block of 1024 threads per hypothesis (a thread owns one pair of columns at C = 2048 and has all
+// its loads in flight at once).  Measured at 320 hypotheses of 64 sentences: 256-thread blocks
+// finishing inside the energy kernel held that kernel at 34 us (each thread walked the positions
+// four times over); one block per sentence for all its hypotheses read every encoder state once
+// but kept a single compute unit busy for 17 us.
+//
+// Workgroups are handed to the eight XCDs in turn, each with an L2 of its own.  The hypotheses of a
+// sentence read the same encoder states, so they are given block numbers that fall on one XCD
+// (sentence s on XCD s % 8, its hypotheses in consecutive rounds): the first of them brings the
+// states into that L2 and the others find them there.  With consecutive block numbers per sentence
+// the same states were fetched once per hypothesis (78 MB at 320 hypotheses, 15.7 us).  Only the
+// speed depends on how the hardware deals the blocks out.
+__global__ __launch_bounds__(ATT_MAX_THREADS) void attention_finish_kernel(AttArgs a, int n)
+{
+    __shared__ double s_alpha[1024];
+    int b = blockIdx.x;
+    if (a.sent_off) {
+        const int xcd = b & 7, q = b >> 3;
+        b = ((q / a.beam) * 8 + xcd) * a.beam + q % a.beam;
     }
-    __syncthreads();
-    if (!s_last) return;
+    if (b >= n) return;
+    const float *P, *enc_h;
+    const int l = att_sentence(a, b, P, enc_h);
     att_finish(a, b, l, enc_h, s_alpha);
 }
 
@@ -438,14 +453,19 @@ q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, 
     t.cstride = n <= Q8_MAX_BEAM ? Q8_COUNTER_STRIDE : 1;        // header: 1024 words of counters
     t.l = l; t.A = A; t.C = C;
     t.sent_off = sent_off; t.beam = beam; t.lde = l;
-    const int threads = n > Q8_MAX_BEAM ? 256 : ATT_THREADS;
-    const bool codes = ctx_q && ctx_qscale && C % 2 == 0 && ldq >= C && ldq % 2 == 0 && ldq <= 2 * ATT_PAIRS * threads;
+    const bool panel = n > Q8_MAX_BEAM;
+    const bool codes = ctx_q && ctx_qscale && C % 2 == 0 && ldq >= C && ldq % 2 == 0 && ldq <= 2 * ATT_PAIRS * ATT_THREADS;
     t.ctx_q = codes ? ctx_q : nullptr; t.ctx_qscale = ctx_qscale; t.ldq = ldq;
     if (codes_written) *codes_written = codes ? 1 : 0;
-    if (n > Q8_MAX_BEAM)
+    if (panel) {
         Q8_LAUNCH(ctx, Q8_KERNEL_ATTENTION, attention_panel_kernel, dim3((l + ATTP_POS - 1) / ATTP_POS, n), dim3(256), 0, t);
-    else
+        // (block numbers are dealt to sentences in groups of eight, see the kernel: the grid covers whole groups)
+        const int nsent = sent_off ? (n + beam - 1) / beam : 0;
+        const int fin_blocks = sent_off ? (nsent + 7) / 8 * 8 * beam : n;
+        Q8_LAUNCH(ctx, Q8_KERNEL_ATTENTION, attention_finish_kernel, dim3(fin_blocks), dim3(ATT_MAX_THREADS), 0, t, n);
+    } else {
         Q8_LAUNCH(ctx, Q8_KERNEL_ATTENTION, attention_kernel, dim3(l, n), dim3(ATT_THREADS), 0, t);
+    }
     return q8i_launch_check(ctx, "attention");
 }
 

@@ -354,20 +354,20 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(GemmJobs jobs)
 // life (up to 160 KB per workgroup on gfx950) and streams tile-packed 16-row weight tiles past
 // them, one tile ahead in registers: no barrier after the prologue, every weight byte read once
 // per column group.  Per (row tile, column tile): KC matrix-core steps, then dequantize, bias,
-// logits (tile by tile: one contiguous KiB per wave), and the tile's (max, sum of exp) per slot
-// with the cross-lane steps on v_permlane16/32_swap.
+// and the tile's (max, sum of exp) per slot with the cross-lane steps on v_permlane16/32_swap.
+// The logits themselves are not kept (64 MB per step at 320 slots): the selection computes
+// those of the few tiles that can hold one of the k best again.
 struct PanelArgs {
     const int8_t *tiles;   // tile-packed weights (q8_pack_tiles)
     const int8_t *xq;      // [n x ld] codes
     const float *xscale, *bias;
-    float *Y;              // [ntiles][n][16]
     float *part_max;       // [n x ntiles]
     double *part_sum;
     int rows, ld, n, ntiles, cols_per_group;
     float w_scale;
 };
 
-#define VP_WAVES 8
+#define VP_WAVES 16
 #define VP_MAX_NT 16
 
 template <int KC>      // 64-byte k steps per row: ld = 64 KC
@@ -430,7 +430,6 @@ __global__ __launch_bounds__(64 * VP_WAVES) void vocab_panel_kernel(PanelArgs a)
                 if (row0 + 3 < a.rows) b.w = a.bias[row0 + 3];
             }
         }
-        float *ytile = a.Y + (size_t)tile * n * 16;
         // four column tiles at a time: four independent accumulation chains keep the matrix core
         // busy (a single chain waits ~44 cycles per step), and their epilogues interleave
         for (int t0 = 0; t0 < nt; t0 += 4) {
@@ -463,10 +462,6 @@ __global__ __launch_bounds__(64 * VP_WAVES) void vocab_panel_kernel(PanelArgs a)
                     }
                     m[u] = fmaxf(m[u], y[u][r]);
                 }
-                if (col_ok)
-                    // (streamed: 64 MB of logits per step at 320 slots, of which the selection reads back a few tiles)
-                    __builtin_nontemporal_store((v4i){__float_as_int(y[u][0]), __float_as_int(y[u][1]), __float_as_int(y[u][2]), __float_as_int(y[u][3])},
-                                                (v4i *)(ytile + (size_t)(c_base + colr) * 16 + 4 * g));
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) m[u] = quad_rows_max(m[u]);
@@ -503,10 +498,10 @@ __global__ __launch_bounds__(64 * VP_WAVES) void vocab_panel_kernel(PanelArgs a)
 bool q8i_vocab_panel_ok(const q8_mat *W) { return W->tiles != nullptr && (W->ld == 512 || W->ld == 640); }
 
 q8_status q8i_vocab_panel(q8_ctx *ctx, const q8_mat *W, const float *bias, const int8_t *xq, const float *xscale, int n,
-                          float *Y_tiled, float *part_max, double *part_sum)
+                          float *part_max, double *part_sum)
 {
     PanelArgs a;
-    a.tiles = W->tiles; a.xq = xq; a.xscale = xscale; a.bias = bias; a.Y = Y_tiled;
+    a.tiles = W->tiles; a.xq = xq; a.xscale = xscale; a.bias = bias;
     a.part_max = part_max; a.part_sum = part_sum;
     a.rows = W->rows; a.ld = W->ld; a.n = n; a.ntiles = (W->rows + 15) / 16; a.w_scale = W->scale;
     // column groups of equal size, as many slots as fit the LDS (codes at pitch ld + 16, one float

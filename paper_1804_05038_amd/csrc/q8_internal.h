@@ -131,7 +131,7 @@ q8_status q8i_quantize_jobs(q8_ctx *ctx, const q8i_quant_job *d, int njobs, int 
 q8_status q8i_gemm_jobs(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n);        // njobs <= 3
 bool q8i_vocab_panel_ok(const q8_mat *W);
 q8_status q8i_vocab_panel(q8_ctx *ctx, const q8_mat *W, const float *bias, const int8_t *xq, const float *xscale, int n,
-                          float *Y_tiled, float *part_max, double *part_sum);
+                          float *part_max, double *part_sum);
 q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode);
 // ctx_q / ctx_qscale (may be NULL): where the finishing blocks leave the codes [n x ldq] and scales [n] of the
 // context vectors; *codes_written says whether this launch does (C even, ldq <= 8192, panels: ldq <= 2048)

@@ -594,6 +594,223 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     beam_update_body<true>(a.bu);
 }
 
+// ========================================== selection for panels, logits recomputed ==
+// Many hypothesis slots (sentences side by side): the vocabulary panel kernel keeps no logits
+// (at 320 slots they would be 64 MB per step, written once and almost never read), only each
+// tile's (max, sum of exp).  This kernel, one block per slot, derives the log-sum-exp and the
+// threshold T from those, and computes the logits of the few tiles whose maximum reaches T a
+// second time: the same matrix-core instruction on the same tile-packed weights with the
+// slot's codes in column 0 of the second operand, so the int32 sums, and with the same
+// dequantization and bias steps the logits, are those the panel kernel saw.
+struct PanelSelectArgs {
+    const float *part_max;
+    const double *part_sum;
+    const int8_t *tiles;    // tile-packed weights (q8_pack_tiles)
+    const int8_t *xq;       // [n x 64 KC] codes of t
+    const float *xscale, *bias;
+    float *lse, *topk_logp;
+    int *topk_idx;
+    int ntiles, n, k, V;
+    float w_scale;
+};
+
+#define PSEL_BATCH 4          // tiles per wave whose weights are requested together
+
+template <int KC>
+__global__ __launch_bounds__(256) void panel_select_kernel(PanelSelectArgs a)
+{
+    __shared__ unsigned short s_q[OUT_MAX_TILES];
+    __shared__ __align__(16) unsigned long long s_key[SEL_CAP + 4];
+    __shared__ float s_f[4];
+    __shared__ double s_d[4];
+    __shared__ unsigned long long s_u[4];
+    __shared__ float s_top[64];
+    __shared__ float s_T;
+    __shared__ int s_nq, s_ns;
+    constexpr int ld = 64 * KC;
+    const int j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, k = a.k;
+    const int i = lane & 15, g = lane >> 4;
+    const int ntiles = a.ntiles;
+    if (tid == 0) { s_nq = 0; s_ns = 0; }
+    if (tid < 64) s_top[tid] = -INFINITY;
+
+    // the slot's codes as second operand: column 0 carries them, columns 1..15 are zero
+    v4i bv[KC];
+    {
+        const int8_t *xj = a.xq + (size_t)j * ld + 16 * g;
+#pragma unroll
+        for (int s = 0; s < KC; ++s) bv[s] = i == 0 ? *(const v4i *)(xj + 64 * s) : (v4i){0, 0, 0, 0};
+    }
+    const float c = a.w_scale * a.xscale[j];
+
+    float pm[OUT_SB];
+    double ps[OUT_SB];
+#pragma unroll
+    for (int t = 0; t < OUT_SB; ++t) {
+        const int tile = tid + 256 * t;
+        pm[t] = -INFINITY;
+        ps[t] = 0.0;
+        if (tile < ntiles) {
+            pm[t] = a.part_max[(size_t)j * ntiles + tile];
+            ps[t] = a.part_sum[(size_t)j * ntiles + tile];
+        }
+    }
+    float bm = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < OUT_SB; ++t) bm = fmaxf(bm, pm[t]);
+    // T = the k-th largest of the 256 threads' maxima (each the largest logit of up to 16 tiles of
+    // its own, so at least k logits are >= T): every wave sorts its 64, the k best of each wave are
+    // sorted once more.  k <= 16 (four waves' candidates fill one wave).
+    __syncthreads();
+    const float sorted = wave_sort_desc_f(bm, lane);
+    if (lane == 0) s_f[wave] = sorted;
+    if (lane < 16) s_top[16 * wave + lane] = lane < k ? sorted : -INFINITY;
+    __syncthreads();
+    const float m = fmaxf(fmaxf(s_f[0], s_f[1]), fmaxf(s_f[2], s_f[3]));
+    if (wave == 0) {
+        const float again = wave_sort_desc_f(s_top[lane], lane);
+        if (lane == k - 1) s_T = again;              // -inf if fewer than k threads own a tile: everything qualifies
+    }
+    __syncthreads();
+    const float T = s_T;
+
+#pragma unroll
+    for (int t = 0; t < OUT_SB; ++t)
+        if (tid + 256 * t < ntiles && pm[t] >= T) s_q[atomicAdd(&s_nq, 1)] = (unsigned short)(tid + 256 * t);
+    __syncthreads();
+    const int nq = s_nq;
+
+    // logits of tile `tile` for this slot: lanes 0, 16, 32, 48 (column 0) end up with rows 4 g .. 4 g + 3
+    auto tile_loads = [&](v4i (&A)[KC], int tile) {
+        const int8_t *p = a.tiles + (size_t)tile * KC * 1024 + lane * 16;
+#pragma unroll
+        for (int s = 0; s < KC; ++s) A[s] = *(const v4i *)(p + 1024 * s);
+    };
+    // (the biases of the lane's four rows are requested with the tile, not after the products)
+    // (unconditional loads: without biases the slot's scale is read instead and not used)
+    const float *bias_p = a.bias ? a.bias : a.xscale + j;
+    const int bias_last = a.bias ? a.V - 1 : 0;
+    auto tile_bias = [&](float (&bb)[4], int tile) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) bb[r] = bias_p[min(tile * OUT_TILE + 4 * g + r, bias_last)];
+    };
+    auto tile_logits = [&](const v4i (&A)[KC], const float (&bb)[4], int tile, float (&y)[4]) {
+        v4i acc = (v4i){0, 0, 0, 0};
+#pragma unroll
+        for (int s = 0; s < KC; ++s) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[s], bv[s], acc, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = tile * OUT_TILE + 4 * g + r;
+            y[r] = -INFINITY;
+            if (row < a.V) {
+                y[r] = (float)acc[r] * c;
+                if (a.bias) y[r] = y[r] + bb[r];
+            }
+        }
+    };
+
+    // this wave's share of the log-sum-exp from the tile partials
+    auto lse_share = [&]() {
+        double S = 0.0;
+#pragma unroll
+        for (int t = 0; t < OUT_SB; ++t)
+            if (pm[t] > -INFINITY) S += ps[t] * (double)__expf(pm[t] - m);
+        S = wave_sum_d(S);
+        if (lane == 0) s_d[wave] = S;
+    };
+    lse_share();
+    bool overflow = nq * OUT_TILE > 16 * SEL_CAP;
+    if (!overflow) {
+        for (int q0 = 0; q0 < nq; q0 += 4 * PSEL_BATCH) {
+            v4i A[PSEL_BATCH][KC];
+            float bb[PSEL_BATCH][4];
+            int tile[PSEL_BATCH];
+#pragma unroll
+            for (int u = 0; u < PSEL_BATCH; ++u) {
+                const int q = q0 + 4 * u + wave;
+                tile[u] = q < nq ? (int)s_q[q] : -1;
+                tile_loads(A[u], tile[u] < 0 ? 0 : tile[u]);         // a slot past the list reads tile 0 and drops it
+                tile_bias(bb[u], tile[u] < 0 ? 0 : tile[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < PSEL_BATCH; ++u) {
+                float y[4];
+                tile_logits(A[u], bb[u], tile[u] < 0 ? 0 : tile[u], y);
+                if (tile[u] >= 0 && i == 0) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (y[r] >= T) {                             // -inf (a row past the matrix) only if T is -inf too
+                            const int row = tile[u] * OUT_TILE + 4 * g + r;
+                            if (row < a.V) {
+                                const int pos = atomicAdd(&s_ns, 1);
+                                if (pos < SEL_CAP) s_key[pos] = topk_key(y[r], row);
+                            }
+                        }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    overflow = overflow || s_ns > SEL_CAP;
+    const double S = (s_d[0] + s_d[1]) + (s_d[2] + s_d[3]);
+    const float lse = (float)((double)m + log(S));
+    if (tid == 0 && a.lse) a.lse[j] = lse;
+
+    if (!overflow) {
+        const int ns = s_ns;
+        if (tid < 4) s_key[ns + tid] = 0ull;
+        __syncthreads();
+        for (int t = tid; t < ns; t += 256) {
+            const unsigned long long key = s_key[t];
+            int rank = 0;
+#pragma unroll 2
+            for (int u = 0; u < ns; u += 4) {
+                const ulonglong2 p0 = *(const ulonglong2 *)&s_key[u], p1 = *(const ulonglong2 *)&s_key[u + 2];
+                rank += (p0.x > key) + (p0.y > key) + (p1.x > key) + (p1.y > key);
+            }
+            if (rank < k) {
+                a.topk_idx[(size_t)j * k + rank] = topk_key_idx(key);
+                a.topk_logp[(size_t)j * k + rank] = topk_key_val(key) - lse;
+            }
+        }
+        return;
+    }
+    // heavily tied logits (more than SEL_CAP at or above T): k exact rounds of arg-max over every tile
+    unsigned long long prev = ~0ull;
+    for (int r = 0; r < k; ++r) {
+        unsigned long long best = 0ull;
+        for (int tile = wave; tile < ntiles; tile += 4) {
+            v4i A[KC];
+            float y[4], bb[4];
+            tile_loads(A, tile);
+            tile_bias(bb, tile);
+            tile_logits(A, bb, tile, y);
+            if (i == 0) {
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const int row = tile * OUT_TILE + 4 * g + rr;
+                    if (row < a.V) {
+                        const unsigned long long key = topk_key(y[rr], row);
+                        if (key < prev && key > best) best = key;
+                    }
+                }
+            }
+        }
+        best = wave_max_u64(best);
+        __syncthreads();
+        if (lane == 0) s_u[wave] = best;
+        __syncthreads();
+        best = s_u[0];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) best = s_u[w] > best ? s_u[w] : best;
+        if (tid == 0) {
+            a.topk_idx[(size_t)j * k + r] = topk_key_idx(best);
+            a.topk_logp[(size_t)j * k + r] = topk_key_val(best) - lse;
+        }
+        prev = best;
+    }
+}
+
 // =================================================================== host launcher ==
 
 int q8i_out_tiles(int V) { return (V + OUT_TILE - 1) / OUT_TILE; }
@@ -761,8 +978,17 @@ q8_status q8i_output_codes(q8_ctx *ctx, const q8_mat *W, const float *bias, cons
                            int32_t *tap_acc, float *part_max, double *part_sum)
 {
     q8_status st;
-    if (tiled && !tap_acc && q8i_vocab_panel_ok(W)) {
-        st = q8i_vocab_panel(ctx, W, bias, tq, tscale, n, logits, part_max, part_sum);
+    if (tiled && !tap_acc && q8i_vocab_panel_ok(W) && k <= 16) {
+        // no logits are kept: the selection computes those of the few tiles it needs again
+        st = q8i_vocab_panel(ctx, W, bias, tq, tscale, n, part_max, part_sum);
+        if (st) return st;
+        PanelSelectArgs s;
+        s.part_max = part_max; s.part_sum = part_sum; s.tiles = W->tiles; s.xq = tq; s.xscale = tscale; s.bias = bias;
+        s.lse = lse; s.topk_logp = topk_logp; s.topk_idx = topk_idx;
+        s.ntiles = q8i_out_tiles(W->rows); s.n = n; s.k = k; s.V = W->rows; s.w_scale = W->scale;
+        if (W->ld == 512) Q8_LAUNCH(ctx, Q8_KERNEL_SELECT, panel_select_kernel<8>, dim3(n), dim3(256), 0, s);
+        else Q8_LAUNCH(ctx, Q8_KERNEL_SELECT, panel_select_kernel<10>, dim3(n), dim3(256), 0, s);
+        return q8i_launch_check(ctx, "panel selection");
     } else {
         const q8i_gemm_job gj = {W, tq, tscale, bias, logits, W->rows, tap_acc, part_max, part_sum, tiled};
         st = q8i_gemm_jobs(ctx, &gj, 1, n);

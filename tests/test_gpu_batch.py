@@ -235,6 +235,26 @@ def test_output_layer_panel_persistent_kernel(q, ctx, oracle, V, R, n, k):
         assert_close(r["lse"][j:j + 1], np.array([lse]), "lse")
 
 
+def test_output_layer_panel_persistent_kernel_ties(q, ctx, oracle):
+    """The panel path keeps no logits and computes those of the qualifying tiles a second time.  With
+    nearly all logits equal every tile qualifies and the survivors overflow their list: the exact
+    fallback (k rounds over all tiles) has to give the raised entries first, then the lowest indices."""
+    V, R, n = 4100, 512, 11
+    W = np.zeros((V, R), np.float32); W[:, 0] = 1.0
+    b = np.zeros(V, np.float32)
+    raised = [7, 130, 131, 2047, 4099]
+    b[raised] = 2.0
+    t = np.zeros((n, R), np.float32); t[:, 0] = 0.5
+    Wm = q.q8_pack_tiles(ctx, q.q8_quantize_matrix(ctx, W, ld_out=512))
+    L = oracle.QLinear(W, b)
+    r = q.output_logits_q8(ctx, None, Wm, ctx.f32(b), t_in=ctx.f32(t), k=12, want_logits=False)
+    for j in range(n):
+        lse, lp, idx = oracle.logsoftmax_topk(L.gemv(t[j]), 12)
+        assert idx.tolist() == raised + [0, 1, 2, 3, 4, 5, 6]
+        assert_same(r["topk_idx"][j], idx); assert_close(r["topk_logp"][j], lp)
+        assert_close(r["lse"][j:j + 1], np.array([lse]), "lse")
+
+
 @pytest.mark.parametrize("dims,S,beam,l", [(dict(), 4, 5, 7), (dict(), 30, 5, 30), (dict(), 3, 3, 5),
                                            (dict(V=33658, E=620, H=1000, A=1000, R=620), 4, 5, 9),
                                            (dict(V=50, E=32, H=48, A=40, R=24, w_std=0.3), 6, 2, 5)])
