@@ -1145,7 +1145,7 @@ q8_status q8_beam_init_batch(q8_ctx *ctx, void *states, int n_sent, int beam, in
         H <= 0 || C < H)
         return q8_fail(ctx, Q8_ERR_SHAPE, "q8_beam_init_batch: bad sizes");
     return q8i_beam_batch(ctx, 1, states, q8i_beam_state_bytes(max_steps), n_sent, beam, 0, max_steps, nullptr, nullptr,
-                          nullptr, E_tgt, E, H, y_emb, s, done, enc_h, sent_off, C);
+                          nullptr, E_tgt, E, H, y_emb, s, done, enc_h, sent_off, C, 0);
 }
 
 q8_status q8_beam_update_batch(q8_ctx *ctx, void *states, int n_sent, int beam, int k, int max_steps,
@@ -1160,7 +1160,7 @@ q8_status q8_beam_update_batch(q8_ctx *ctx, void *states, int n_sent, int beam, 
         return q8_fail(ctx, Q8_ERR_SHAPE, "q8_beam_update_batch: bad sizes");
     if (s_next == s_step) return q8_fail(ctx, Q8_ERR_SHAPE, "s_next must not alias s_step");
     return q8i_beam_batch(ctx, 0, states, q8i_beam_state_bytes(max_steps), n_sent, beam, k, max_steps, topk_logp, topk_idx,
-                          s_step, E_tgt, E, H, y_emb, s_next, done, nullptr, nullptr, 0);
+                          s_step, E_tgt, E, H, y_emb, s_next, done, nullptr, nullptr, 0, 0);
 }
 
 q8_status q8_beam_result_batch(q8_ctx *ctx, const void *states, int n_sent, int max_steps, int32_t *tokens_host,
@@ -1276,8 +1276,9 @@ q8_status q8_translate_batch(q8_ctx *ctx, const q8_model *m, const int32_t *src_
         }
         if (!st) st = output_impl(ctx, &m->ro, &m->W_out, m->b_out, sv[cur ^ 1], y, cvec, nullptr, n, k, nullptr, nullptr, lp,
                                   idx, nullptr, nullptr, nullptr, &yc, &cc, &sc);
-        if (!st) st = q8_beam_update_batch(ctx, states, n_sent, beam, k, max_steps, lp, idx, sv[cur ^ 1], H, m->E_tgt, E, y,
-                                           sv[cur], done);
+        // (the table's height goes along: a token id outside it, which takes non-finite logits, is replaced by 0)
+        if (!st) st = q8i_beam_batch(ctx, 0, states, q8i_beam_state_bytes(max_steps), n_sent, beam, k, max_steps, lp, idx,
+                                     sv[cur ^ 1], m->E_tgt, E, H, y, sv[cur], done, nullptr, nullptr, 0, m->V_tgt);
         if (!st && (t % 8 == 7)) {
             hipError_t e = hipMemcpyAsync(done_host, done, sizeof(int32_t) * n_sent, hipMemcpyDeviceToHost, ctx->stream);
             if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);

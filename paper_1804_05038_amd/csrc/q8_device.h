@@ -691,6 +691,12 @@ __device__ __forceinline__ double quad_rows_sum(double v)
     return __hiloint2double((int)rh[0], (int)rl[0]) + __hiloint2double((int)rh[1], (int)rl[1]);
 }
 
+// e^x for x <= 0 (a logit minus the maximum of its group) by the hardware's 2^x on x log2(e), the
+// product and the 2^x that the fast library exponential takes for results in the normal range;
+// without its rescaling of denormal results (four more instructions per value): below 2^-126 this
+// returns zero, which a sum that also holds e^0 = 1 cannot tell from the denormal value.
+__device__ __forceinline__ float exp_le0(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896340736f); }
+
 // fp32 nonlinearities of the gates, evaluated in double and rounded once (q8_math.h).
 __device__ __forceinline__ float sigmoid_rn(float a) { return q8_sigmoid_rn(a); }
 __device__ __forceinline__ float tanh_rn(float a) { return q8_tanh_rn(a); }

@@ -108,7 +108,7 @@ __global__ __launch_bounds__(256) void logit_stats_kernel(const float *__restric
     double sd = 0.0;
 #pragma unroll
     for (int r = 0; r < 16; ++r)
-        if (v[r] > -INFINITY) sd += (double)__expf(v[r] - m);
+        if (v[r] > -INFINITY) sd += (double)exp_le0(v[r] - m);
     part_max[idx] = m;
     part_sum[idx] = sd;
 }

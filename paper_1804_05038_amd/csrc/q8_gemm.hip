@@ -232,7 +232,7 @@ __global__ __launch_bounds__(256) void gemm_block_kernel(GemmJobs jobs)
                 sd[t] = 0.0;
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    if (y[t][r] > -INFINITY) sd[t] += (double)__expf(y[t][r] - m[t]);
+                    if (y[t][r] > -INFINITY) sd[t] += (double)exp_le0(y[t][r] - m[t]);
             }
 #pragma unroll
             for (int t = 0; t < NT; ++t) sd[t] += __shfl_xor(sd[t], 16, 64);
@@ -367,21 +367,104 @@ struct PanelArgs {
     float w_scale;
 };
 
-#define VP_WAVES 16
+#define VP_WAVES 16        // at most; the launch picks the number of waves that divides the row tiles most evenly
 #define VP_MAX_NT 16
 
-template <int KC>      // 64-byte k steps per row: ld = 64 KC
+// One row tile against U column tiles starting at column tile t0: U independent accumulation
+// chains keep the matrix core busy (a single chain waits ~44 cycles per step) and their
+// epilogues interleave.  FULL: all 16 rows and all 16 U columns exist, nothing is masked (the
+// masked form costs about twice the vector instructions, which are what bounds this kernel:
+// per result tile 8 matrix-core steps stand against some 50 vector instructions).
+template <int KC, int U, bool FULL>
+__device__ __forceinline__ void panel_tiles(const PanelArgs &a, const v4i (&A)[KC], const int8_t *bt, int pitch, const float *s_c,
+                                            int tile, int t0, int nt, int cols, int c_base, float4 b, int i, int g)
+{
+    v4i acc[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc[u] = (v4i){0, 0, 0, 0};
+#pragma unroll
+    for (int s = 0; s < KC; ++s)
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            // column tiles past the panel read the first tile of the group again (in bounds); their results are dropped
+            const v4i bv = *(const v4i *)(bt + ((FULL || t0 + u < nt) ? u : 0) * 16 * pitch + 64 * s);
+            acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[s], bv, acc[u], 0, 0, 0);
+        }
+    const int row0 = tile * 16 + 4 * g;
+    const float bias[4] = {b.x, b.y, b.z, b.w};
+    float y[U][4], m[U];
+    double sd[U];
+    if (FULL) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const float c = s_c[16 * (t0 + u) + i];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) y[u][r] = (float)acc[u][r] * c;
+            if (a.bias) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) y[u][r] = y[u][r] + bias[r];
+            }
+            m[u] = fmaxf(fmaxf(y[u][0], y[u][1]), fmaxf(y[u][2], y[u][3]));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) m[u] = quad_rows_max(m[u]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            sd[u] = (double)exp_le0(y[u][0] - m[u]);
+#pragma unroll
+            for (int r = 1; r < 4; ++r) sd[u] += (double)exp_le0(y[u][r] - m[u]);
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int colr = 16 * (t0 + u) + i;                  // column within the panel
+            const bool col_ok = t0 + u < nt && colr < cols;
+            const float c = col_ok ? s_c[colr] : 0.0f;
+            m[u] = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                y[u][r] = -INFINITY;
+                if (col_ok && row0 + r < a.rows) {
+                    y[u][r] = (float)acc[u][r] * c;
+                    if (a.bias) y[u][r] = y[u][r] + bias[r];
+                }
+                m[u] = fmaxf(m[u], y[u][r]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) m[u] = quad_rows_max(m[u]);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            sd[u] = 0.0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (y[u][r] > -INFINITY) sd[u] += (double)exp_le0(y[u][r] - m[u]);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) sd[u] = quad_rows_sum(sd[u]);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int colr = 16 * (t0 + u) + i;
+        if ((FULL || (t0 + u < nt && colr < cols)) && g == 0) {
+            a.part_max[(size_t)(c_base + colr) * a.ntiles + tile] = m[u];
+            a.part_sum[(size_t)(c_base + colr) * a.ntiles + tile] = sd[u];
+        }
+    }
+}
+
+template <int KC, int U>      // 64-byte k steps per row: ld = 64 KC; column tiles per inner step
 __global__ __launch_bounds__(64 * VP_WAVES) void vocab_panel_kernel(PanelArgs a)
 {
     extern __shared__ __align__(16) int8_t s_x[];        // [cols x pitch]
     constexpr int ld = 64 * KC, pitch = ld + 16;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthr = blockDim.x, nwave = nthr >> 6;
     const int i = lane & 15, g = lane >> 4;
     const int n = a.n, c_base = blockIdx.y * a.cols_per_group;
     const int cols = min(a.cols_per_group, n - c_base);       // > 0 by construction of the grid
     const int nt = (cols + 15) >> 4;
     // this wave's row tiles: gw, gw + stride, ...
-    const int gw = blockIdx.x * VP_WAVES + wave, stride = gridDim.x * VP_WAVES;
+    const int gw = blockIdx.x * nwave + wave, stride = gridDim.x * nwave;
 
     v4i A0[KC], A1[KC];
     auto load_tile = [&](v4i (&A)[KC], int tile) {
@@ -396,29 +479,31 @@ __global__ __launch_bounds__(64 * VP_WAVES) void vocab_panel_kernel(PanelArgs a)
     {
         const __amdgpu_buffer_rsrc_t rx = q8_rsrc(a.xq + (size_t)c_base * ld, (size_t)cols * ld);
         const int total = nt * 16 * (ld / 16);
-        for (int p0 = 0; p0 < total; p0 += 8 * 64 * VP_WAVES) {
+        for (int p0 = 0; p0 < total; p0 += 8 * nthr) {
             v4i v[8];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int p = p0 + u * 64 * VP_WAVES + tid;      // piece p: slot p / (ld / 16), bytes 16 (p % (ld / 16)) ..
+                const int p = p0 + u * nthr + tid;               // piece p: slot p / (ld / 16), bytes 16 (p % (ld / 16)) ..
                 v[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(p < total ? (unsigned)p * 16u : Q8_OOB), 0, 0));
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                const int p = p0 + u * 64 * VP_WAVES + tid;
+                const int p = p0 + u * nthr + tid;
                 const int col = p / (ld / 16), ch = p - col * (ld / 16);
                 if (p < total) *(v4i *)(s_x + col * pitch + ch * 16) = v[u];
             }
         }
     }
     float *s_c = (float *)(s_x + (size_t)a.cols_per_group * pitch);      // dequantization factor of every slot
-    for (int c = tid; c < nt * 16; c += 64 * VP_WAVES) s_c[c] = c < cols ? a.w_scale * a.xscale[c_base + c] : 0.0f;
+    for (int c = tid; c < nt * 16; c += nthr) s_c[c] = c < cols ? a.w_scale * a.xscale[c_base + c] : 0.0f;
     __syncthreads();
 
     const bool bias_vec = (((uintptr_t)a.bias) & 15) == 0;
     const int8_t *bp = s_x + i * pitch + 16 * g;
+    const int nt_full = cols >> 4;                           // column tiles without a missing slot
     auto do_tile = [&](const v4i (&A)[KC], int tile) {
         const int row0 = tile * 16 + 4 * g;
+        const bool rows_full = tile * 16 + 16 <= a.rows;
         float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
         if (a.bias) {
             if (bias_vec && row0 + 3 < a.rows) {
@@ -430,58 +515,10 @@ __global__ __launch_bounds__(64 * VP_WAVES) void vocab_panel_kernel(PanelArgs a)
                 if (row0 + 3 < a.rows) b.w = a.bias[row0 + 3];
             }
         }
-        // four column tiles at a time: four independent accumulation chains keep the matrix core
-        // busy (a single chain waits ~44 cycles per step), and their epilogues interleave
-        for (int t0 = 0; t0 < nt; t0 += 4) {
-            v4i acc[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) acc[u] = (v4i){0, 0, 0, 0};
+        for (int t0 = 0; t0 < nt; t0 += U) {
             const int8_t *bt = bp + t0 * 16 * pitch;
-#pragma unroll
-            for (int s = 0; s < KC; ++s)
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    // column tiles past the panel read the last tile again (in bounds); their results are dropped
-                    const v4i bv = *(const v4i *)(bt + (t0 + u < nt ? u : 0) * 16 * pitch + 64 * s);
-                    acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(A[s], bv, acc[u], 0, 0, 0);
-                }
-            float y[4][4], m[4];
-            double sd[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int colr = 16 * (t0 + u) + i;                  // column within the panel
-                const bool col_ok = t0 + u < nt && colr < cols;
-                const float c = col_ok ? s_c[colr] : 0.0f;
-                m[u] = -INFINITY;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    y[u][r] = -INFINITY;
-                    if (col_ok && row0 + r < a.rows) {
-                        y[u][r] = (float)acc[u][r] * c;
-                        if (a.bias) y[u][r] = y[u][r] + (r == 0 ? b.x : r == 1 ? b.y : r == 2 ? b.z : b.w);
-                    }
-                    m[u] = fmaxf(m[u], y[u][r]);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) m[u] = quad_rows_max(m[u]);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                sd[u] = 0.0;
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (y[u][r] > -INFINITY) sd[u] += (double)__expf(y[u][r] - m[u]);
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) sd[u] = quad_rows_sum(sd[u]);
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int colr = 16 * (t0 + u) + i;
-                if (t0 + u < nt && colr < cols && g == 0) {
-                    a.part_max[(size_t)(c_base + colr) * a.ntiles + tile] = m[u];
-                    a.part_sum[(size_t)(c_base + colr) * a.ntiles + tile] = sd[u];
-                }
-            }
+            if (rows_full && t0 + U <= nt_full) panel_tiles<KC, U, true>(a, A, bt, pitch, s_c, tile, t0, nt, cols, c_base, b, i, g);
+            else panel_tiles<KC, U, false>(a, A, bt, pitch, s_c, tile, t0, nt, cols, c_base, b, i, g);
         }
     };
     for (int tile = gw; tile < a.ntiles; tile += 2 * stride) {
@@ -512,20 +549,31 @@ q8_status q8i_vocab_panel(q8_ctx *ctx, const q8_mat *W, const float *bias, const
     a.cols_per_group = ((n + ngroups - 1) / ngroups + 15) & ~15;
     int gx = 256 / ngroups;
     if (gx < 1) gx = 1;
-    if (gx * VP_WAVES > a.ntiles) gx = (a.ntiles + VP_WAVES - 1) / VP_WAVES;
+    if (gx * 8 > a.ntiles) gx = (a.ntiles + 7) / 8;
     const int gy = (n + a.cols_per_group - 1) / a.cols_per_group;
+    // waves per block (8..16): the count for which the busiest wave's row tiles exceed the average least
+    int nw = 8;
+    double best = 1e30;
+    for (int w = 8; w <= VP_WAVES; ++w) {
+        const int waves = gx * w, most = (a.ntiles + waves - 1) / waves;
+        const double ratio = (double)most * waves / a.ntiles;
+        if (ratio < best - 1e-9) { best = ratio; nw = w; }
+    }
     const size_t smem = (size_t)a.cols_per_group * (W->ld + 16 + 4);
-    static bool attr_set[2] = {false, false};
-    const int which = W->ld == 512 ? 0 : 1;
+    // column tiles per inner step: five when they divide the group's tiles and four do not (rows of 512
+    // bytes only: with ten k steps per row five chains no longer fit the registers of 16 waves)
+    const int ntg = a.cols_per_group / 16;
+    const bool five = W->ld == 512 && ntg % 5 == 0 && ntg % 4 != 0;
+    typedef void (*kern_t)(PanelArgs);
+    const kern_t kern = W->ld == 512 ? (five ? vocab_panel_kernel<8, 5> : vocab_panel_kernel<8, 4>) : vocab_panel_kernel<10, 4>;
+    static bool attr_set[3] = {false, false, false};
+    const int which = W->ld == 512 ? (five ? 1 : 0) : 2;
     if (!attr_set[which]) {
-        const hipError_t e = which == 0
-            ? hipFuncSetAttribute((const void *)vocab_panel_kernel<8>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024)
-            : hipFuncSetAttribute((const void *)vocab_panel_kernel<10>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        const hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "vocabulary panel kernel: %s", hipGetErrorString(e));
         attr_set[which] = true;
     }
-    if (which == 0) Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, vocab_panel_kernel<8>, dim3(gx, gy), dim3(64 * VP_WAVES), smem, a);
-    else Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, vocab_panel_kernel<10>, dim3(gx, gy), dim3(64 * VP_WAVES), smem, a);
+    Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, kern, dim3(gx, gy), dim3(64 * nw), smem, a);
     return q8i_launch_check(ctx, "vocabulary panel");
 }
 

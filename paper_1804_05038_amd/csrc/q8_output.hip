@@ -236,7 +236,7 @@ __device__ __forceinline__ void out_logits_body(const OutArgs &a)
         double sd = 0.0;
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            if (y[r] > -INFINITY) sd += (double)__expf(y[r] - m);
+            if (y[r] > -INFINITY) sd += (double)exp_le0(y[r] - m);
         sd += __shfl_xor(sd, 16, 64);
         sd += __shfl_xor(sd, 32, 64);
         if (i < n && g == 0) {
@@ -396,7 +396,7 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 8))) voi
     double sd = 0.0;
 #pragma unroll
     for (int r = 0; r < 4; ++r)
-        if (y[r] > -INFINITY) sd += (double)__expf(y[r] - m);
+        if (y[r] > -INFINITY) sd += (double)exp_le0(y[r] - m);
     sd = quad_rows_sum(sd);
     if (i < n && g == 0) {
         a.part_max[(size_t)i * a.ntiles + tile] = m;
@@ -423,6 +423,9 @@ struct SelectArgs {
 // Top-k entry `o` of the output tables; device-coherent when another block will read it.
 __device__ __forceinline__ void put_topk(const SelectArgs &a, size_t o, int idx, float logp)
 {
+    // (a round of the exact fallback that finds no candidate, which takes non-finite logits, decodes to an
+    // index past the table; whoever gathers an embedding row by it must find a row)
+    idx = (unsigned)idx < (unsigned)a.V ? idx : 0;
     if (a.fuse_update) {
         __hip_atomic_store(a.topk_idx + o, idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(a.topk_logp + o, logp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -501,7 +504,7 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     double S = 0.0;
 #pragma unroll
     for (int t = 0; t < OUT_SB; ++t)
-        if (pm[t] > -INFINITY) S += ps[t] * (double)__expf(pm[t] - m);
+        if (pm[t] > -INFINITY) S += ps[t] * (double)exp_le0(pm[t] - m);
     S = wave_sum_d(S);
     if (lane == 0) s_d[wave] = S;
     // ---- logits >= T of the qualifying tiles
@@ -714,7 +717,7 @@ __global__ __launch_bounds__(256) void panel_select_kernel(PanelSelectArgs a)
         double S = 0.0;
 #pragma unroll
         for (int t = 0; t < OUT_SB; ++t)
-            if (pm[t] > -INFINITY) S += ps[t] * (double)__expf(pm[t] - m);
+            if (pm[t] > -INFINITY) S += ps[t] * (double)exp_le0(pm[t] - m);
         S = wave_sum_d(S);
         if (lane == 0) s_d[wave] = S;
     };
@@ -804,7 +807,8 @@ __global__ __launch_bounds__(256) void panel_select_kernel(PanelSelectArgs a)
 #pragma unroll
         for (int w = 1; w < 4; ++w) best = s_u[w] > best ? s_u[w] : best;
         if (tid == 0) {
-            a.topk_idx[(size_t)j * k + r] = topk_key_idx(best);
+            const int idx = topk_key_idx(best);              // past the table if the round found no candidate (non-finite logits)
+            a.topk_idx[(size_t)j * k + r] = (unsigned)idx < (unsigned)a.V ? idx : 0;
             a.topk_logp[(size_t)j * k + r] = topk_key_val(best) - lse;
         }
         prev = best;
@@ -879,7 +883,7 @@ __global__ __launch_bounds__(256) void ensemble_combine_kernel(CombineArgs a)
     double sd = 0.0;
 #pragma unroll
     for (int r = 0; r < OUT_TILE; ++r)
-        if (r < rows) sd += (double)__expf(c[r] - mx);
+        if (r < rows) sd += (double)exp_le0(c[r] - mx);
     a.part_max[(size_t)j * a.ntiles + tile] = mx;
     a.part_sum[(size_t)j * a.ntiles + tile] = sd;
 }

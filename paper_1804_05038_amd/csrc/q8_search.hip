@@ -86,6 +86,7 @@ struct BeamBatchArgs {
     const float *enc_h;          // initialization: encoder states, sentence s starts at row sent_off[s]
     const int *sent_off;
     int beam, k, E, H, C, max_steps;
+    int V;                       // rows of E_tgt when known (token ids are then kept inside the table), else 0
 };
 
 __global__ __launch_bounds__(256) void beam_update_batch_kernel(BeamBatchArgs b)
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(256) void beam_update_batch_kernel(BeamBatchArgs b)
     const int s = blockIdx.x;
     const size_t slot = (size_t)s * b.beam;
     BeamUpdateArgs a = {(BeamState *)(b.states + (size_t)s * b.stride), b.topk_logp + slot * b.k, b.topk_idx + slot * b.k,
-                        b.s_step + slot * b.H, b.E_tgt, b.y_emb + slot * b.E, b.s_next + slot * b.H, b.beam, b.k, b.E, b.H};
+                        b.s_step + slot * b.H, b.E_tgt, b.y_emb + slot * b.E, b.s_next + slot * b.H, b.beam, b.k, b.E, b.H, b.V};
     beam_update_body<false>(a);
     __syncthreads();
     if (threadIdx.x == 0) b.done[s] = a.st->done;
@@ -136,10 +137,10 @@ q8_status q8i_beam_update(q8_ctx *ctx, void *state, const float *topk_logp, cons
 
 q8_status q8i_beam_batch(q8_ctx *ctx, int init, void *states, size_t stride, int S, int beam, int k, int max_steps,
                          const float *topk_logp, const int *topk_idx, const float *s_step, const float *E_tgt, int E,
-                         int H, float *y_emb, float *s_next, int *done, const float *enc_h, const int *sent_off, int C)
+                         int H, float *y_emb, float *s_next, int *done, const float *enc_h, const int *sent_off, int C, int V)
 {
     BeamBatchArgs b = {(char *)states, stride, topk_logp, topk_idx, s_step, E_tgt, y_emb, s_next, done, enc_h, sent_off,
-                       beam, k, E, H, C, max_steps};
+                       beam, k, E, H, C, max_steps, V};
     if (init) hipLaunchKernelGGL(beam_init_batch_kernel, dim3(S), dim3(256), 0, ctx->stream, b);
     else hipLaunchKernelGGL(beam_update_batch_kernel, dim3(S), dim3(256), 0, ctx->stream, b);
     return q8i_launch_check(ctx, init ? "beam init (batch)" : "beam update (batch)");
