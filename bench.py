@@ -24,12 +24,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# From the committed profile profiles/decode_step_beam5_kernels.txt (rocprofv3 runs of this file with --quick):
+# From the committed profile profiles/decode_step_beam5_kernels.txt (rocprofv3 runs of this file with --quick and --counters):
 # HBM-side bytes of one launch of the vocabulary kernel (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00 with the L2 serialized away),
 # its average duration on the kernel trace's clock, and the 25.6 MB read probe's on the same clock
 VOCAB_KERNEL_TRAFFIC_BYTES = 28.15e6
-VOCAB_KERNEL_TRACE_US = 5.92
-READ_PROBE_TRACE_US = 2.68
+VOCAB_KERNEL_TRACE_US = 5.85
+READ_PROBE_TRACE_US = 2.65
 L, BEAM, TOPK, MAX_STEPS = 30, 5, 12, 100
 
 
@@ -705,7 +705,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "out_logits8_kernel<2, 8, true> (50000x512 int8 vocabulary matrix, 5 hypotheses)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": VOCAB_KERNEL_TRAFFIC_BYTES, "traffic_unit": "bytes per launch",
-                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE (x2.00) + WRITE_SIZE (x1.00) of bench.py --quick (dispatches serialized by "
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE (x2.00) + WRITE_SIZE (x1.00) of bench.py --counters (dispatches serialized by "
                                        "the counter run: no reuse of the L2 between steps), profiles/decode_step_beam5_kernels.txt",
                      "bytes_per_launch": out_bytes, "kernel_us": k_ms * 1e3, "samples": k_n,
                      "clock": "HIP event pair on the kernel's dispatch, measured live in the running decoder loop (includes the dispatch: "
