@@ -217,7 +217,8 @@ def test_output_layer_panel_ties(q, ctx, oracle):
 
 
 @pytest.mark.parametrize("V,R,n,k", [(50000, 512, 20, 12), (3001, 512, 300, 12), (2000, 620, 250, 5), (777, 512, 9, 16),
-                                     (5000, 640, 1000, 12)])
+                                     (5000, 640, 1000, 12), (100, 512, 12, 12), (3001, 512, 40, 1), (16, 512, 9, 16),
+                                     (4097, 640, 161, 7)])
 def test_output_layer_panel_persistent_kernel(q, ctx, oracle, V, R, n, k):
     """Tile-packed vocabulary matrix and no logits requested: the panel kernel that keeps the slots'
     codes in LDS and streams weight tiles (rows of 512 or 640 bytes)."""
