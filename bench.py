@@ -227,10 +227,18 @@ def gemv_bandwidth(torch, q, ctx, rng):
             q.q8_gemv(ctx, mats[it[0] % copies], x, None, y)
             it[0] += 1
         cold = median_of(torch, cold_call, inner=copies, warmup=copies)
+        # the kernel alone, by event pairs on its dispatches (the wall time of a small product is the host's launch rate)
+        reps = 200 if rows <= 50000 else 20
+        q.q8_profile_begin(ctx, "gemv", reps)
+        for _ in range(reps):
+            q.q8_gemv(ctx, M, x, None, y)
+        k_ms, k_n = q.q8_profile_end(ctx)
         out[name] = {"bytes": nbytes,
                      "warm_us": warm[0], "warm_GBps": nbytes / warm[0] / 1e3,
                      "cold_us": cold[0], "cold_GBps": nbytes / cold[0] / 1e3, "cold_copies": copies,
-                     "note": "wall time of back-to-back calls, launch included"}
+                     "warm_kernel_us_event_pairs": k_ms * 1e3, "warm_kernel_GBps": nbytes / (k_ms * 1e3) / 1e3,
+                     "note": "warm_us / cold_us: wall time of back-to-back calls, launch included (for the 3 MB product "
+                             "that is the host's launch rate, which differs between machines); warm_kernel_us: event pairs"}
         del mats
     return out
 

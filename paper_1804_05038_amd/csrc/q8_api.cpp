@@ -563,7 +563,9 @@ static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8
     // the selection reads the logits back; a panel's logits that stay in the workspace are kept
     // tile by tile (contiguous stores from the matrix cores' result layout)
     const int tiled = (n > kMaxNarrow && !logits) ? 1 : 0;
-    float *lg = logits ? logits : cv.take<float>(tiled ? ngrp * 16 * n : (size_t)n * V);
+    // (where the panel kernel runs nothing is kept at all: the selection computes the logits it needs again)
+    const bool none_kept = tiled && !(taps4 && taps4[3].acc) && q8i_output_codes_keeps_no_logits(W_out, k);
+    float *lg = logits ? logits : (none_kept ? nullptr : cv.take<float>(tiled ? ngrp * 16 * n : (size_t)n * V));
     if (n > kMaxNarrow) {
         // panel path: codes of t from the combine kernel (or from t_in), then the blocked product
         int8_t *tq = cv.take<int8_t>((size_t)n * W_out->ld);

@@ -130,6 +130,7 @@ struct q8i_gemm_job {           // Y [n x ldy] = dequantize(W . xq) + bias on th
 q8_status q8i_quantize_jobs(q8_ctx *ctx, const q8i_quant_job *d, int njobs, int n);   // njobs <= 3
 q8_status q8i_gemm_jobs(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n);        // njobs <= 3
 bool q8i_vocab_panel_ok(const q8_mat *W);
+bool q8i_output_codes_keeps_no_logits(const q8_mat *W, int k);
 q8_status q8i_vocab_panel(q8_ctx *ctx, const q8_mat *W, const float *bias, const int8_t *xq, const float *xscale, int n,
                           float *part_max, double *part_sum);
 q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode);

@@ -974,6 +974,9 @@ q8_status q8i_output(q8_ctx *ctx, const q8_mat *W, const float *bias, const floa
     return launch_select(ctx, part_max, part_sum, logits, 0, a.V, n, k, lse, topk_logp, topk_idx, beam);
 }
 
+// Whether q8i_output_codes, asked for tiled logits and no taps, runs the panel kernel and keeps no logits.
+bool q8i_output_codes_keeps_no_logits(const q8_mat *W, int k) { return q8i_vocab_panel_ok(W) && k <= 16; }
+
 // Vocabulary layer for more than 8 hypotheses, from the codes of t: the blocked matrix-core
 // product (which also leaves the per-tile softmax statistics), then the same selection.
 // tiled: the logits go to the workspace tile by tile (see GemmArgs) instead of row-major.
@@ -982,7 +985,7 @@ q8_status q8i_output_codes(q8_ctx *ctx, const q8_mat *W, const float *bias, cons
                            int32_t *tap_acc, float *part_max, double *part_sum)
 {
     q8_status st;
-    if (tiled && !tap_acc && q8i_vocab_panel_ok(W) && k <= 16) {
+    if (tiled && !tap_acc && q8i_output_codes_keeps_no_logits(W, k)) {
         // no logits are kept: the selection computes those of the few tiles it needs again
         st = q8i_vocab_panel(ctx, W, bias, tq, tscale, n, part_max, part_sum);
         if (st) return st;
