@@ -39,6 +39,7 @@ __device__ __forceinline__ int att_sentence(const AttArgs &a, int b, const float
 // with device-coherent stores): softmax over the energies in one wave, then the context
 // vector H_t (Eq. 5), a thread owning two adjacent columns and walking the source positions
 // in order.  Sums run in double; every stored value is rounded once.
+template <bool HANDOFF>
 __device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const float *enc_h, double *s_alpha)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nt = blockDim.x;
@@ -46,7 +47,9 @@ __device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const
         const float *e = a.e + (size_t)b * a.lde;
         float mx = -INFINITY;
         for (int t = lane; t < l; t += 64) {
-            const float ev = __hip_atomic_load(e + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // (inside the energy kernel the energies were written by other blocks of the same launch: device-coherent
+            // loads; in a launch of its own they are ordinary data)
+            const float ev = HANDOFF ? __hip_atomic_load(e + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : e[t];
             s_alpha[t] = (double)ev;
             mx = fmaxf(mx, ev);
         }
@@ -63,7 +66,7 @@ __device__ __forceinline__ void att_finish(const AttArgs &a, int b, int l, const
             s_alpha[t] = (double)al;          // the weight as the context sum uses it: converted once, not per column
             if (a.alpha) a.alpha[(size_t)b * a.lde + t] = al;
         }
-        if (lane == 0) __hip_atomic_store(&a.counters[b * a.cstride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (HANDOFF && lane == 0) __hip_atomic_store(&a.counters[b * a.cstride], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (a.ctx_q) {
@@ -161,7 +164,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
     }
     __syncthreads();
     if (!s_last) return;
-    att_finish(a, b, l, enc_h, s_alpha);
+    att_finish<true>(a, b, l, enc_h, s_alpha);
 }
 
 // Many hypotheses (sentences side by side): throughput matters, not the latency of one
@@ -223,7 +226,7 @@ __global__ __launch_bounds__(ATT_MAX_THREADS) void attention_finish_kernel(AttAr
     if (b >= n) return;
     const float *P, *enc_h;
     const int l = att_sentence(a, b, P, enc_h);
-    att_finish(a, b, l, enc_h, s_alpha);
+    att_finish<false>(a, b, l, enc_h, s_alpha);
 }
 
 // ========================================================================== readout ==
