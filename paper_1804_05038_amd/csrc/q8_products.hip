@@ -261,6 +261,94 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
     }
 }
 
+// ================================================== one pass over a large matrix ==
+// Rows of 256, 512 or 1024 bytes (LPR = 16, 32, 64 lanes per row), a matrix of several MB, one
+// product, no taps: nothing loops.  A wave takes 8 KB of consecutive rows (8 wave-wide loads of
+// one contiguous KiB each, 64 / LPR rows per load), so the whole matrix is requested in the
+// kernel's first microsecond, as in the vocabulary kernel; the lane's 16 code bytes of every
+// vector stay in registers; the 8 N partial sums per lane are totalled over the LPR lanes of a
+// row by the transposed reduction restricted to its first log2(LPR) stages, staged in LDS and
+// finished (scale, bias, store) by consecutive lanes for consecutive rows.
+#define GEMV1_LOADS 8
+template <int N, int LPR>
+__global__ __launch_bounds__(256) void gemv_onepass_kernel(GemvJobs jobs)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    __shared__ float s_scale[8];
+    __shared__ float s_red[8 * 4];
+    constexpr int RPL = 64 / LPR, RW = GEMV1_LOADS * RPL;          // rows per load, rows per wave
+    constexpr int CNT = GEMV1_LOADS * N, M = t_pow2(CNT), LG = t_log2(LPR);
+    constexpr int KEEP = M > LPR ? M / LPR : 1;                    // totals a lane is left with
+    __shared__ int s_t[4][RW * N];
+    const GemvJob &J = jobs.j[0];
+    const int ld = J.ld, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int r0 = ((int)blockIdx.x * 4 + wave) * RW;
+
+    XRegs<N, 1> xr;
+    x_load<N, 1>(xr, J.X, N, J.cols, J.ldx);
+    const __amdgpu_buffer_rsrc_t rw = q8_rsrc(J.W, (size_t)J.rows * ld);
+    v4i w[GEMV1_LOADS];
+    {
+        const size_t base = (size_t)r0 * ld + (size_t)lane * 16;   // below 2^31 (checked by the launcher)
+#pragma unroll
+        for (int l = 0; l < GEMV1_LOADS; ++l) {
+            const size_t off = base + (size_t)l * 1024;
+            w[l] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rw, (int)(r0 < J.rows ? (unsigned)off : Q8_OOB), 0, 0));
+        }
+    }
+    // the bias of row r0 + lane % RW: the row this lane finishes in every pass of the epilogue
+    const __amdgpu_buffer_rsrc_t rb = q8_rsrc(J.bias, J.bias ? (size_t)J.rows * sizeof(float) : 0);
+    const int my_row = r0 + (lane & (RW - 1));
+    const float bias = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, (int)(my_row < J.rows ? (unsigned)my_row * 4u : Q8_OOB), 0, 0));
+    x_finish<N, 1>(xr, N, ld, smem, s_scale, s_red);
+
+    const int lir = lane & (LPR - 1), g = lane / LPR;
+    int v[M];
+#pragma unroll
+    for (int e = 0; e < M; ++e) v[e] = 0;
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+        const v4i x = *(const v4i *)(smem + (size_t)j * ld + lir * 16);
+#pragma unroll
+        for (int l = 0; l < GEMV1_LOADS; ++l) v[l * N + j] = dot16(w[l], x, 0);
+    }
+    // totals over the LPR lanes of a row group: the stages that pair lanes within 16, 32 or 64
+    t_stage<0, M, TSumI>(v, lane);
+    t_stage<1, M, TSumI>(v, lane);
+    t_stage<2, M, TSumI>(v, lane);
+    t_stage<3, M, TSumI>(v, lane);
+    if constexpr (LG > 4) t_stage<4, M, TSumI>(v, lane);
+    if constexpr (LG > 5) t_stage<5, M, TSumI>(v, lane);
+    // the lane now holds values first .. first + KEEP - 1; lanes that differ only in bits no splitting stage used hold copies
+    int first = 0, used = 0;
+#pragma unroll
+    for (int st = 0; st < (t_log2(M) < LG ? t_log2(M) : LG); ++st) {
+        first |= ((lane >> t_bit(st)) & 1) * (M >> (st + 1));
+        used |= 1 << t_bit(st);
+    }
+    const bool owner = (lir & ~used) == 0;
+#pragma unroll
+    for (int i = 0; i < KEEP; ++i) {
+        const int e = first + i;                                   // e = l * N + j
+        if (owner && e < CNT) {
+            const int l = e / N, j = e - l * N;
+            s_t[wave][(l * RPL + g) * N + j] = v[i];
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    const bool has_bias = J.bias != nullptr;
+#pragma unroll
+    for (int o0 = 0; o0 < RW * N; o0 += 64) {
+        const int o = o0 + lane, j = o / RW, rr = o & (RW - 1);     // consecutive lanes, consecutive rows (rr = lane % RW)
+        if (o < RW * N && r0 + rr < J.rows) {
+            const int a = s_t[wave][rr * N + j];
+            float y = (float)a * (J.w_scale * s_scale[j]);
+            if (has_bias) y = y + bias;
+            J.Y[(size_t)j * J.ldy + r0 + rr] = y;
+        }
+    }
+}
+
 // ================================================ narrow product on the matrix cores ==
 
 // ==================================================================== read probe ==
@@ -345,6 +433,32 @@ q8_status q8i_fill_u32(q8_ctx *ctx, void *p, int n, unsigned v)
     return q8i_launch_check(ctx, "fill");
 }
 
+template <int N>
+static void launch_gemv_onepass_n(q8_ctx *ctx, const GemvJobs &jobs, size_t smem)
+{
+    const int ld = jobs.j[0].ld, rw = GEMV1_LOADS * 1024 / ld;                 // rows per wave
+    const int blocks = (jobs.j[0].rows + 4 * rw - 1) / (4 * rw);
+    if (ld == 256) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_onepass_kernel<N, 16>), dim3(blocks), dim3(256), smem, jobs);
+    else if (ld == 512) Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_onepass_kernel<N, 32>), dim3(blocks), dim3(256), smem, jobs);
+    else Q8_LAUNCH(ctx, Q8_KERNEL_GEMV, (gemv_onepass_kernel<N, 64>), dim3(blocks), dim3(256), smem, jobs);
+}
+
+static bool launch_gemv_onepass(q8_ctx *ctx, const GemvJobs &jobs, int n, size_t smem)
+{
+    switch (n) {
+    case 1: launch_gemv_onepass_n<1>(ctx, jobs, smem); break;
+    case 2: launch_gemv_onepass_n<2>(ctx, jobs, smem); break;
+    case 3: launch_gemv_onepass_n<3>(ctx, jobs, smem); break;
+    case 4: launch_gemv_onepass_n<4>(ctx, jobs, smem); break;
+    case 5: launch_gemv_onepass_n<5>(ctx, jobs, smem); break;
+    case 6: launch_gemv_onepass_n<6>(ctx, jobs, smem); break;
+    case 7: launch_gemv_onepass_n<7>(ctx, jobs, smem); break;
+    case 8: launch_gemv_onepass_n<8>(ctx, jobs, smem); break;
+    default: return false;
+    }
+    return true;
+}
+
 template <int N, bool ROWS, int U, bool STREAM>
 static void launch_gemv_nu(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t smem, int ch)
 {
@@ -384,6 +498,8 @@ q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
     if (with_rows != 0 && with_rows != njobs) fast = false;         // mixed launches run on the general kernel
     const bool rows = with_rows != 0;
     const int ch = fast ? q8_fast_ch(max_ld) : 0;
+    size_t all_bytes = 0;
+    for (int t = 0; t < njobs; ++t) all_bytes += (size_t)jobs.j[t].rows * jobs.j[t].ld;
     const int u = 2;                              // rows per wave and pass of the fast kernel
     int blocks = 0;
     for (int t = 0; t < njobs; ++t) {
@@ -398,6 +514,10 @@ q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
         blocks += (J.rows + rpb - 1) / rpb;
     }
     const size_t smem = (size_t)n * max_ld;
+    // one product over a matrix of several MB with rows of 256, 512 or 1024 bytes: the kernel without a loop
+    if (fast && njobs == 1 && !rows && !jobs.j[0].tap_xq && !jobs.j[0].tap_xscale && !jobs.j[0].tap_acc && all_bytes >= ((size_t)8 << 20) &&
+        (max_ld == 256 || max_ld == 512 || max_ld == 1024) && launch_gemv_onepass(ctx, jobs, n, smem))
+        return q8i_launch_check(ctx, "gemv");
     size_t bytes = 0;
     for (int t = 0; t < njobs; ++t) bytes += (size_t)jobs.j[t].rows * jobs.j[t].ld;
     const bool stream = bytes < ((size_t)8 << 20);          // the products inside a decoder step

@@ -101,6 +101,25 @@ def test_gemm_narrow_streaming(q, ctx, oracle, rows, cols, n):
     assert_same(y0, np_(Y)[0], "column 0 vs gemv")
 
 
+@pytest.mark.parametrize("rows,cols", [(50000, 512), (9001, 1024), (8300, 1012), (40003, 252), (17000, 500)])
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_gemm_narrow_one_pass_over_a_large_matrix(q, ctx, oracle, rows, cols, n):
+    """One product without taps over a matrix of more than 8 MB with rows of 256, 512 or 1024 bytes runs on the
+    kernel without a loop (8 KB of consecutive rows per wave, totals over 16, 32 or 64 lanes per row): identical
+    to the oracle and to the looping kernel (which the taps select)."""
+    rng = np.random.default_rng(rows + cols + n)
+    W = _w(rng, rows, cols)
+    b = (rng.standard_normal(rows) * 0.01).astype(np.float32)
+    X = rng.standard_normal((n, cols)).astype(np.float32) * rng.uniform(0.1, 10, (n, 1)).astype(np.float32)
+    L, M = oracle.QLinear(W, b), q.q8_quantize_matrix(ctx, W)
+    assert M.data.shape[0] * M.data.shape[1] >= 8 << 20 and M.data.shape[1] in (256, 512, 1024)
+    Y_ref = L.gemm_narrow(X)
+    assert_same(q.q8_gemm_narrow(ctx, M, ctx.f32(X), ctx.f32(b)), Y_ref, "Y, with bias")
+    Y_taps, _ = q.q8_gemm_narrow(ctx, M, ctx.f32(X), ctx.f32(b), taps=True)
+    assert_same(Y_taps, Y_ref, "Y from the looping kernel")
+    assert_same(q.q8_gemm_narrow(ctx, M, ctx.f32(X)), oracle.QLinear(W).gemm_narrow(X), "Y, no bias")
+
+
 @pytest.mark.parametrize("rows,cols,n", [(3072, 512, 50), (1024, 2048, 30), (1000, 620, 13), (100, 48, 9),
                                          (3072, 512, 60), (77, 1000, 70), (3072, 1024, 320), (130, 272, 129),
                                          (9000, 512, 130), (50000, 512, 40), (8200, 144, 257)])
