@@ -263,7 +263,7 @@ __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
 
 // ================================================== one pass over a large matrix ==
 // Rows of 256, 512 or 1024 bytes (LPR = 16, 32, 64 lanes per row), a matrix of several MB, one
-// product, no taps: nothing loops.  A wave takes 8 KB of consecutive rows (8 wave-wide loads of
+// product (one weight scale per matrix or per row), no taps: nothing loops.  A wave takes 8 KB of consecutive rows (8 wave-wide loads of
 // one contiguous KiB each, 64 / LPR rows per load), so the whole matrix is requested in the
 // kernel's first microsecond, as in the vocabulary kernel; the lane's 16 code bytes of every
 // vector stay in registers; the 8 N partial sums per lane are totalled over the LPR lanes of a
@@ -300,6 +300,9 @@ __global__ __launch_bounds__(256) void gemv_onepass_kernel(GemvJobs jobs)
     const __amdgpu_buffer_rsrc_t rb = q8_rsrc(J.bias, J.bias ? (size_t)J.rows * sizeof(float) : 0);
     const int my_row = r0 + (lane & (RW - 1));
     const float bias = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, (int)(my_row < J.rows ? (unsigned)my_row * 4u : Q8_OOB), 0, 0));
+    // ... and its weight scale where there is one per row (an absent array reads as zero and is not used)
+    const __amdgpu_buffer_rsrc_t rs = q8_rsrc(J.row_scale, J.row_scale ? (size_t)J.rows * sizeof(float) : 0);
+    const float row_scale = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(my_row < J.rows ? (unsigned)my_row * 4u : Q8_OOB), 0, 0));
     x_finish<N, 1>(xr, N, ld, smem, s_scale, s_red);
 
     const int lir = lane & (LPR - 1), g = lane / LPR;
@@ -336,13 +339,13 @@ __global__ __launch_bounds__(256) void gemv_onepass_kernel(GemvJobs jobs)
         }
     }
     __builtin_amdgcn_wave_barrier();
-    const bool has_bias = J.bias != nullptr;
+    const bool has_bias = J.bias != nullptr, has_rows = J.row_scale != nullptr;
 #pragma unroll
     for (int o0 = 0; o0 < RW * N; o0 += 64) {
         const int o = o0 + lane, j = o / RW, rr = o & (RW - 1);     // consecutive lanes, consecutive rows (rr = lane % RW)
         if (o < RW * N && r0 + rr < J.rows) {
             const int a = s_t[wave][rr * N + j];
-            float y = (float)a * (J.w_scale * s_scale[j]);
+            float y = (float)a * ((has_rows ? row_scale : J.w_scale) * s_scale[j]);
             if (has_bias) y = y + bias;
             J.Y[(size_t)j * J.ldy + r0 + rr] = y;
         }
@@ -515,7 +518,7 @@ q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)
     }
     const size_t smem = (size_t)n * max_ld;
     // one product over a matrix of several MB with rows of 256, 512 or 1024 bytes: the kernel without a loop
-    if (fast && njobs == 1 && !rows && !jobs.j[0].tap_xq && !jobs.j[0].tap_xscale && !jobs.j[0].tap_acc && all_bytes >= ((size_t)8 << 20) &&
+    if (fast && njobs == 1 && !jobs.j[0].tap_xq && !jobs.j[0].tap_xscale && !jobs.j[0].tap_acc && all_bytes >= ((size_t)8 << 20) &&
         (max_ld == 256 || max_ld == 512 || max_ld == 1024) && launch_gemv_onepass(ctx, jobs, n, smem))
         return q8i_launch_check(ctx, "gemv");
     size_t bytes = 0;

@@ -118,6 +118,10 @@ def test_gemm_narrow_one_pass_over_a_large_matrix(q, ctx, oracle, rows, cols, n)
     Y_taps, _ = q.q8_gemm_narrow(ctx, M, ctx.f32(X), ctx.f32(b), taps=True)
     assert_same(Y_taps, Y_ref, "Y from the looping kernel")
     assert_same(q.q8_gemm_narrow(ctx, M, ctx.f32(X)), oracle.QLinear(W).gemm_narrow(X), "Y, no bias")
+    if n in (1, 5, 8):
+        # the variant with one weight scale per row takes the same kernel
+        R, rs = q.q8_quantize_matrix_rows(ctx, W)
+        assert_same(q.q8_gemm_narrow_rows(ctx, R, rs, ctx.f32(X), ctx.f32(b)), oracle.QLinearRows(W, b).gemm_narrow(X), "Y, row scales")
 
 
 @pytest.mark.parametrize("rows,cols,n", [(3072, 512, 50), (1024, 2048, 30), (1000, 620, 13), (100, 48, 9),
