@@ -237,6 +237,8 @@ def gemv_bandwidth(torch, q, ctx, rng):
                      "warm_us": warm[0], "warm_GBps": nbytes / warm[0] / 1e3,
                      "cold_us": cold[0], "cold_GBps": nbytes / cold[0] / 1e3, "cold_copies": copies,
                      "warm_kernel_us_event_pairs": k_ms * 1e3, "warm_kernel_GBps": nbytes / (k_ms * 1e3) / 1e3,
+                     "warm_kernel_frac_of_hbm_peak": nbytes / (k_ms * 1e3) / 1e3 / HBM_PEAK_GBS,
+                     "cold_frac_of_hbm_peak": nbytes / cold[0] / 1e3 / HBM_PEAK_GBS,
                      "note": "warm_us / cold_us: wall time of back-to-back calls, launch included (for the 3 MB product "
                              "that is the host's launch rate, which differs between machines); warm_kernel_us: event pairs"}
         del mats
