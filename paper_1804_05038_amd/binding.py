@@ -678,7 +678,11 @@ def q8_translate_batch(ctx, model, sentences, beam=5, k=12, max_steps=100):
     off = np.zeros(S + 1, dtype=np.int32)
     off[1:] = np.cumsum([len(x) for x in sentences])
     V_src = model.E_src.shape[0]
-    src = torch.cat([source_ids(x, V_src, ctx.device) for x in sentences])
+    if any(isinstance(x, torch.Tensor) and x.is_cuda for x in sentences):
+        src = torch.cat([source_ids(x, V_src, ctx.device) for x in sentences])
+    else:
+        # ids that arrive on the host: checked here, then one transfer for all sentences (not one per sentence)
+        src = torch.cat([source_ids(x, V_src) for x in sentences]).to(ctx.device)
     out = (C.c_int32 * (max_steps * S))()
     n, steps, score = (C.c_int * S)(), (C.c_int * S)(), (C.c_float * S)()
     ctx.check(ctx.lib.q8_translate_batch(ctx.handle, C.byref(model.c), _ptr(src), off.ctypes.data_as(C.POINTER(C.c_int)), S,
