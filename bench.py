@@ -509,6 +509,7 @@ def main():
     ap.add_argument("--quick", action="store_true", help="beam-5 timed region and kernel timing only (profiling runs)")
     ap.add_argument("--sentences", type=int, default=20)
     ap.add_argument("--batched", action="store_true", help="only the batched decoder step at 64 sentences (profiling runs)")
+    ap.add_argument("--gemv", action="store_true", help="only the streaming product's section and the read probes (profiling runs)")
     ap.add_argument("--counters", action="store_true",
                     help="short workload for hardware-counter runs: 300 decoder steps at beam 5, the vocabulary kernel 200 times back "
                          "to back on one matrix and on 24 copies in turn, the two matrix-core products of a sentence, 20 batched steps")
@@ -553,6 +554,11 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"counters_workload": "done"}))
+        return
+    if args.gemv:
+        print(json.dumps({"gemv": gemv_bandwidth(torch, q, ctx, rng),
+                          "read_stream_ceiling": {"25.6MB_warm": read_ceiling(torch, q, ctx, 25600000, cold=False),
+                                                  "25.6MB_cold": read_ceiling(torch, q, ctx, 25600000, cold=True)}}))
         return
     if args.batched:
         print(json.dumps({"batched_decoding": batched_decoding(torch, q, m, rng, args.steps // 10, sizes=(64,), translate=False)}))
