@@ -468,6 +468,13 @@ q8_status q8_profile_end(q8_ctx *ctx, float *avg_ms_host, int *samples_host);
  * ceiling the streaming kernels are compared with.  Uses 8 KiB of the workspace. */
 q8_status q8_probe_read(q8_ctx *ctx, const void *buf, size_t bytes);
 
+/* Verification aid: evaluates the library's own device functions for the float parts of the
+ * model (Section 3 keeps sigmoid, tanh and the exponentials in floating point) on an array of
+ * n values, so that they can be compared with a reference on the device they run on.
+ * fn = 0: tanh, 1: sigmoid (x, y: n floats); fn = 2: exp for |x| <= 700 (x, y: n doubles).
+ * x, y: device pointers, y may equal x.  Enqueues one launch on the context's stream. */
+q8_status q8_math_eval(q8_ctx *ctx, int fn, const void *x, void *y, size_t n);
+
 #ifdef __cplusplus
 }
 #endif

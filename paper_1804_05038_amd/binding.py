@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 __all__ = ["Q8Error", "Context", "Mat", "Codes", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
            "q8_quantize_matrix", "q8_quantize_matrix_rows", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "q8_gemm_narrow_rows", "q8_attention_states_q8", "q8_attention_q8", "gru_step_q8", "cgru_decoder_step_q8",
            "output_logits_q8", "output_logits_beam_q8", "q8_encode", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
-           "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "MatF", "GruWeightsF32", "CgruWeightsF32", "ReadoutWeightsF32", "q8_gemv_f32",
+           "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "q8_math_eval", "MatF", "GruWeightsF32", "CgruWeightsF32", "ReadoutWeightsF32", "q8_gemv_f32",
            "cgru_decoder_step_f32", "output_logits_f32", "q8_translate_ensemble", "q8_translate_ensemble_bytes", "cgru_decoder_step_batch_q8", "q8_encode_batch", "q8_encode_batch_bytes", "q8_beam_init_batch",
            "q8_beam_update_batch", "q8_beam_result_batch", "q8_translate_batch", "q8_translate_batch_bytes",
            "KERNEL_CLASSES", "LIB_PATH", "source_ids",
@@ -114,6 +114,7 @@ def load_library():
         lib.q8_translate.argtypes = [vp, C.POINTER(_Model), vp, ci, ci, ci, ci, vp, ip, C.POINTER(C.c_float), ip]
         lib.q8_profile_begin.argtypes = [vp, ci, ci]
         lib.q8_probe_read.argtypes = [vp, vp, C.c_size_t]
+        lib.q8_math_eval.argtypes = [vp, ci, vp, vp, C.c_size_t]
         lib.cgru_decoder_step_batch_q8.argtypes = [vp, C.POINTER(_Cgru), vp, vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp]
         lib.cgru_decoder_step_batch_codes_q8.argtypes = lib.cgru_decoder_step_batch_q8.argtypes + [C.POINTER(_Codes)] * 3
         lib.output_logits_codes_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, ci, ci,
@@ -537,6 +538,17 @@ def q8_encode_batch(ctx, fwd, bwd, X, lengths, enc_h=None):
 
 def q8_profile_begin(ctx, kernel_class, max_samples):
     ctx.check(ctx.lib.q8_profile_begin(ctx.handle, KERNEL_CLASSES[kernel_class], max_samples))
+
+
+def q8_math_eval(ctx, fn, x):
+    """The device's own tanh ("tanh"), sigmoid ("sigmoid") (float32 tensors) or exp ("exp", float64) of x."""
+    code = {"tanh": 0, "sigmoid": 1, "exp": 2}[fn]
+    want = torch.float64 if code == 2 else torch.float32
+    if x.dtype != want or not x.is_contiguous():
+        raise ValueError("q8_math_eval(%s) takes a contiguous %s tensor" % (fn, want))
+    y = torch.empty_like(x)
+    ctx.check(ctx.lib.q8_math_eval(ctx.handle, code, _ptr(x), _ptr(y), x.numel()))
+    return y
 
 
 def q8_probe_read(ctx, buf):

@@ -225,6 +225,14 @@ q8_status q8_probe_read(q8_ctx *ctx, const void *buf, size_t bytes)
     return q8i_probe_read(ctx, buf, bytes);
 }
 
+q8_status q8_math_eval(q8_ctx *ctx, int fn, const void *x, void *y, size_t n)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    if (!x || !y) return q8_fail(ctx, Q8_ERR_NULL, "q8_math_eval: NULL buffer");
+    if (fn < 0 || fn > 2 || n == 0 || n > ((size_t)1 << 31)) return q8_fail(ctx, Q8_ERR_SHAPE, "q8_math_eval: fn in 0..2, 1 <= n <= 2^31");
+    return q8i_math_eval(ctx, fn, x, y, n);
+}
+
 size_t q8_tiles_bytes(int rows, int ld)
 {
     if (rows <= 0 || ld <= 0) return 0;

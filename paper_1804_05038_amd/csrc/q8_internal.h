@@ -169,6 +169,7 @@ q8_status q8i_beam_read_batch(q8_ctx *ctx, const void *states, size_t stride, in
 q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,
                       float *t_out, const q8_taps *taps3, const q8_codes *y_codes = nullptr, const q8_codes *c_codes = nullptr);
 q8_status q8i_probe_read(q8_ctx *ctx, const void *buf, size_t bytes);
+q8_status q8i_math_eval(q8_ctx *ctx, int fn, const void *x, void *y, size_t n);
 int q8i_out_tiles(int V);
 size_t q8i_tiles_bytes(int rows, int ld);
 q8_status q8i_pack_tiles(q8_ctx *ctx, const q8_mat *W, int8_t *tiles);

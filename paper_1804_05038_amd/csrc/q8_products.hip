@@ -380,6 +380,25 @@ __global__ __launch_bounds__(256) void read_probe_kernel(const int4 *buf, size_t
     if (r == 0x9e3779b9u) sink[blockIdx.x] = r;    // keeps the loads alive; practically never taken
 }
 
+// ============================================================ device math, evaluated ==
+// Verification aid: the device's own sigmoid / tanh (float in, float out) and exp (double in, double
+// out) on an array, so that the functions the kernels call can be compared with a reference value by
+// value on the device they run on.
+__global__ __launch_bounds__(256) void math_eval_kernel(int fn, const void *x, void *y, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    if (fn == 0) ((float *)y)[i] = q8_tanh_rn(((const float *)x)[i]);
+    else if (fn == 1) ((float *)y)[i] = q8_sigmoid_rn(((const float *)x)[i]);
+    else ((double *)y)[i] = q8_exp_d(((const double *)x)[i]);
+}
+
+q8_status q8i_math_eval(q8_ctx *ctx, int fn, const void *x, void *y, size_t n)
+{
+    hipLaunchKernelGGL(math_eval_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream, fn, x, y, n);
+    return q8i_launch_check(ctx, "math eval");
+}
+
 // =================================================================== host launchers ==
 
 q8_status q8i_probe_read(q8_ctx *ctx, const void *buf, size_t bytes)
