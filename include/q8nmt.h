@@ -236,8 +236,11 @@ q8_status q8_attention_q8(q8_ctx *ctx, const q8_mat *v, const q8_mat *hT, const 
  * lse [n] and t_out [n x R] may be NULL.  taps4: NULL or four entries for the products
  * W_s(s), W_y(y), W_c(ctx), W_out(t) (the first three unused when ro == NULL).
  * n_beam <= 8: streaming kernels.  8 < n_beam <= 1024 (hypotheses of many sentences): every
- * product on the matrix cores; the [n x rows] logits are then always materialized (in
- * the workspace when logits == NULL, which must have room for them). */
+ * product on the matrix cores.  With logits == NULL, a tile-packed W_out with rows of 512 or
+ * 640 bytes, k <= 16 and no taps, no logits are kept anywhere: only each 16-row tile's
+ * (max, sum of exp) per hypothesis, and the selection computes the logits of the few tiles
+ * that can hold one of the k best a second time (same results).  Otherwise the [n x rows]
+ * logits are materialized, in the workspace when logits == NULL (it must have room for them). */
 q8_status output_logits_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
                            const float *s, const float *y_emb, const float *ctx_vec, const float *t_in,
                            int n_beam, int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx,
