@@ -386,11 +386,12 @@ def batched_decoding(torch, q, m, rng, steps, sizes=(16, 64, 200), translate=Tru
                 c2.launch()
             ms, cnt = q.q8_profile_end(ctx)          # two launches per call: readout products, vocabulary
             r["output_layer_matrix_core_kernels_avg_us"] = ms * 1e3
-            q.q8_profile_begin(ctx, "attention", 50)
+            q.q8_profile_begin(ctx, "attention", 4 * 50)
             for _ in range(50):
                 c1.launch()
-            ms, cnt = q.q8_profile_end(ctx)
-            r["attention_us"] = ms * 1e3
+            ms, cnt = q.q8_profile_end(ctx)          # two launches per step: energies, then softmax + context
+            r["attention_us_per_step"] = ms * 1e3 * cnt / 50
+            r["attention_launches_per_step"] = cnt / 50
         out["%d_sentences" % S] = r
     if not translate:
         return out
