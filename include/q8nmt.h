@@ -277,6 +277,19 @@ q8_status cgru_decoder_step_batch_q8(q8_ctx *ctx, const q8_cgru_weights *w, cons
 q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights *bwd,
                     const float *X, int l, float *enc_h);
 
+/* How q8_encode runs the recurrence.  one_launch != 0 (the default): all positions in one
+ * launch where the shape is covered (H % 8 == 0, H <= 2048, rows of Wh of at most 2048 bytes,
+ * not under stream capture) and the device can hold 2 H / 8 blocks of 512 threads at once;
+ * otherwise, and with one_launch == 0, one launch per position.  Both give the same bits.
+ * Inside the one-launch kernel blocks wait for each other's results; every such wait gives up
+ * after spin_limit polls (<= 0: the default, 2^20) and the kernel then still ends, leaving enc_h
+ * invalid and a flag in the workspace that q8_encode_check reports.  The grid fits the device,
+ * so every block runs and the waits end; the bound is a safety net.
+ * q8_encode_check waits for the stream and returns Q8_ERR_DEVICE if an encoder launch since the
+ * last check gave up (q8_translate and q8_translate_ensemble call it themselves). */
+q8_status q8_encoder_options(q8_ctx *ctx, int one_launch, int spin_limit);
+q8_status q8_encode_check(q8_ctx *ctx);
+
 /* ---- search (Section 3 only says the beam is smaller than 8; these are the rules) ----
  * Token 0 is both begin- and end-of-sentence.  A search starts with one live hypothesis
  * (score 0, previous token 0) and `beam` slots.  Each step every live hypothesis offers its

@@ -142,6 +142,8 @@ q8_status q8_create(q8_ctx **out, void *hip_stream, void *workspace, size_t work
     c->prof_cap = c->prof_n = 0;
     c->prof_kind = Q8_KERNEL_VOCAB;
     c->ws_reserved_top = 0;
+    c->enc_one_launch = 1;
+    c->enc_spin_limit = Q8_ENC_SPIN_DEFAULT;
     q8_status st = q8i_fill_u32(c, c->ws, Q8_WS_HEADER / 4, 0u);
     if (st) { delete c; return st; }
     *out = c;
@@ -698,7 +700,17 @@ q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights
                                     {&bwd->Wx, xq, xs, bwd->bx, gxb, 3 * H, nullptr, nullptr, nullptr, 0}};
         TRY(q8i_gemm_jobs(ctx, gj, 2, l));
     }
-    // l sequential recurrent steps, both directions in each launch
+    // the recurrence: one launch for all positions where the device can hold its blocks at once ...
+    if (ctx->enc_one_launch) {
+        unsigned long long *xchg = cv.take<unsigned long long>((size_t)4 * H);
+        if (cv.ok) {
+            int launched = 0;
+            TRY(q8i_encode_persistent(ctx, fwd, bwd, gxf, gxb, l, enc_h, xchg, (unsigned *)(ctx->ws + Q8_WS_ENC_ERR),
+                                      ctx->enc_spin_limit, &launched));
+            if (launched) return Q8_OK;
+        }
+    }
+    // ... else l sequential launches, both directions in each
     for (int t = 0; t < l; ++t) {
         const int pf = t, pb = l - 1 - t;
         q8i_gru_desc d[2];
@@ -707,6 +719,28 @@ q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights
         d[1] = {bwd, nullptr, 0, t == 0 ? zero : enc_h + (size_t)(pb + 1) * C, H, gxb + (size_t)pb * 3 * H, 3 * H,
                 enc_h + (size_t)pb * C, H, nullptr};
         TRY(q8i_gru(ctx, d, 2, 1, Q8I_GRU_GX_PRE));
+    }
+    return Q8_OK;
+}
+
+q8_status q8_encoder_options(q8_ctx *ctx, int one_launch, int spin_limit)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    ctx->enc_one_launch = one_launch ? 1 : 0;
+    ctx->enc_spin_limit = spin_limit > 0 ? spin_limit : Q8_ENC_SPIN_DEFAULT;
+    return Q8_OK;
+}
+
+q8_status q8_encode_check(q8_ctx *ctx)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    unsigned flag = 0;
+    hipError_t e = hipMemcpyAsync(&flag, ctx->ws + Q8_WS_ENC_ERR, sizeof(flag), hipMemcpyDeviceToHost, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
+    if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "q8_encode_check: %s", hipGetErrorString(e));
+    if (flag) {
+        q8i_fill_u32(ctx, ctx->ws + Q8_WS_ENC_ERR, 1, 0u);
+        return q8_fail(ctx, Q8_ERR_DEVICE, "q8_encode: a wait inside the one-launch recurrence gave up; enc_h is not valid");
     }
     return Q8_OK;
 }
@@ -884,6 +918,7 @@ q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens
             st = q8i_beam_read(ctx, state, max_steps, nullptr, nullptr, nullptr, nullptr, &done);
     }
     if (!st) st = q8i_beam_read(ctx, state, max_steps, tokens_host, len_host, score_host, steps_host, nullptr);
+    if (!st) st = q8_encode_check(ctx);                       // (the stream is idle here: one word read back)
     ctx->ws_reserved_top = 0;
     return st;
 }
@@ -1138,6 +1173,7 @@ q8_status q8_translate_ensemble(q8_ctx *ctx, const q8_model *const *models, int 
             st = q8i_beam_read(ctx, state, max_steps, nullptr, nullptr, nullptr, nullptr, &done);
     }
     if (!st) st = q8i_beam_read(ctx, state, max_steps, tokens_host, len_host, score_host, steps_host, nullptr);
+    if (!st) st = q8_encode_check(ctx);                       // (the stream is idle here: one word read back)
     ctx->ws_reserved_top = 0;
     return st;
 }

@@ -431,6 +431,155 @@ __global__ __launch_bounds__(256) void enc_gates_kernel(EncStepArgs a, int S)
     a.enc_h[(size_t)pos * 2 * H + col] = gru_gates(xv, hv, hp);
 }
 
+// ============================================= encoder recurrence in one launch ==
+// Eq. 1 for one sentence, both directions, all l positions in ONE launch whose blocks are all
+// resident at once (the launcher checks that the device can hold them; otherwise the caller
+// launches per position).  Block b
+// of 512 threads owns eight hidden units of one direction, a wave one unit: its three recurrent
+// weight rows stay in registers for the whole sentence.  Per position every block needs the whole
+// previous state of its direction (H floats from all blocks of that direction).  There is no grid
+// barrier: a unit's new value is published as one 8-byte word (float, step tag) with a
+// device-coherent store into a double-buffered exchange array, and a consumer polls the words it
+// needs with device-coherent loads until their tags are this step's.  Buffer t & 1 can only be
+// overwritten (at step t + 2) by a block that has read all of step t + 1, which no block has written
+// before it had read all of step t: two buffers suffice.  Every wait is bounded: after spin_limit
+// polls (or as soon as another block has given up) a block sets the error word and goes on with
+// what it has, so the kernel always ends; the error word is the caller's to check.
+// Arithmetic per unit and position as in gru_fast_kernel<1, GRU_GX_PRE>: max-abs codes of the
+// previous state, exact int32 sums, one scale product, bias, gates in fp32 with the double-precision
+// sigmoid / tanh.  H % 8 == 0, H <= 2048, ld <= 2048, the exchange array zeroed before the launch.
+struct EncPArgs {
+    const int8_t *Wh[2];
+    const float *bh[2];
+    const float *gx[2];                  // [l x 3H] input pre-activations, biases included
+    float *enc_h;                        // [l x 2H]: backward state in columns [0, H), forward in [H, 2H)
+    unsigned long long *xchg;            // [2 buffers][2 directions][H] (value bits | tag << 32)
+    unsigned *err;
+    int l, H, ld, spin_limit;
+    float sh_w[2];
+};
+
+#define ENCP_THREADS 512
+template <int CH>           // 1024-byte chunks per weight row
+__global__ __launch_bounds__(ENCP_THREADS) void encoder_persistent_kernel(EncPArgs a)
+{
+    __shared__ __align__(16) int8_t s_q[2048 + 16];
+    __shared__ float s_max[ENCP_THREADS / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int H = a.H, bpd = H / 8;                       // blocks per direction
+    const int d = (int)blockIdx.x / bpd, u = ((int)blockIdx.x - d * bpd) * 8 + wave;
+    const int col0 = d == 0 ? H : 0;
+
+    // this wave's rows r, z, n of unit u, for the whole sentence
+    v4i w[3][CH];
+    {
+        const int row[3] = {u, H + u, 2 * H + u};
+        rows_load<3, CH, false>(w, q8_rsrc(a.Wh[d], (size_t)3 * H * a.ld), row, a.ld, lane);
+    }
+    float bh[3] = {0.f, 0.f, 0.f};
+    if (a.bh[d]) {
+#pragma unroll
+        for (int g = 0; g < 3; ++g) bh[g] = a.bh[d][g * H + u];
+    }
+    float h_prev = 0.0f;
+
+    for (int t = 0; t < a.l; ++t) {
+        const int pos = d == 0 ? t : a.l - 1 - t;
+        // the unit's input pre-activations of this position: lanes 0..2, requested before the wait
+        const float gxl = lane < 3 ? a.gx[d][(size_t)pos * 3 * H + lane * H + u] : 0.0f;
+        float scale = 1.0f;
+        if (t > 0) {
+            // previous state of this direction: thread tid takes units 2 tid, 2 tid + 1 (and + 1024 for H > 1024)
+            const unsigned want = (unsigned)t;
+            float v[CH][2], m = 0.0f;
+            // A poll that comes too early costs a whole round trip to the device-coherent level and its loads
+            // (2 per thread, 256 blocks) slow the stores everybody is waiting for.  The new values need about as
+            // long to become visible as this pause of 8 x 64 cycles; measured at 50 positions: no pause 161 us,
+            // 2: 143, 4: 108, 6: 102, 8: 102, 10: 105, 12: 108, 16: 112, 24: 123 (a pause between failed polls
+            // instead: 193 us).
+            __builtin_amdgcn_s_sleep(8);
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const int i0 = c * 2 * ENCP_THREADS + 2 * tid;
+                v[c][0] = v[c][1] = 0.0f;
+                if (i0 < H) {
+                    const unsigned long long *src = a.xchg + (size_t)(((t - 1) & 1) * 2 + d) * H + i0;
+                    int spins = 0;
+                    for (;;) {
+                        // two published words, each read whole by an 8-byte device-coherent load
+                        const unsigned long long r0 = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        const unsigned long long r1 = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        v[c][0] = __uint_as_float((unsigned)r0);
+                        v[c][1] = __uint_as_float((unsigned)r1);
+                        if ((unsigned)(r0 >> 32) == want && (unsigned)(r1 >> 32) == want) break;
+                        if (++spins >= a.spin_limit ||
+                            ((spins & 63) == 0 && __hip_atomic_load(a.err, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
+                            __hip_atomic_store(a.err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            break;
+                        }
+                    }
+                }
+                m = fmaxf(m, fmaxf(fabsf(v[c][0]), fabsf(v[c][1])));
+            }
+            m = wave_max_f(m);
+            if (lane == 0) s_max[wave] = m;
+            __syncthreads();                     // (also: every wave has finished reading the previous step's codes)
+            m = s_max[0];
+#pragma unroll
+            for (int ww = 1; ww < ENCP_THREADS / 64; ++ww) m = fmaxf(m, s_max[ww]);
+            float inv;
+            q8_scale_of(m, scale, inv);
+#pragma unroll
+            for (int c = 0; c < CH; ++c)         // codes of the units this thread read; zero past H
+                *(short *)(s_q + c * 2 * ENCP_THREADS + 2 * tid) = (short)q8_pack2(v[c][0], v[c][1], inv);
+            __syncthreads();
+        }
+        int acc[3] = {0, 0, 0};
+        if (t > 0) {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) {
+                const v4i x = *(const v4i *)(s_q + (c * 64 + lane) * 16);
+#pragma unroll
+                for (int g = 0; g < 3; ++g) acc[g] = dot16(w[g][c], x, acc[g]);
+            }
+#pragma unroll
+            for (int g = 0; g < 3; ++g) acc[g] = group_sum_i(acc[g], 64);
+        }
+        float gx[3], gh[3];
+        const float ch = a.sh_w[d] * scale;
+#pragma unroll
+        for (int g = 0; g < 3; ++g) {
+            gx[g] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(gxl), g));
+            float y = (float)acc[g] * ch;
+            if (a.bh[d]) y = y + bh[g];
+            gh[g] = y;
+        }
+        // the gates of gru_gates, operation by operation, with the two sigmoids evaluated side by side in lanes 0 and 1
+        const float pr = gx[0] + gh[0], pz = gx[1] + gh[1];
+        const float sg = sigmoid_rn(lane == 1 ? pz : pr);
+        const float r = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sg), 0));
+        const float z = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(sg), 1));
+        const float rn = r * gh[2];
+        const float pn = gx[2] + rn;
+        const float nn = tanh_rn(pn);
+        const float omz = 1.0f - z;
+        const float t1 = omz * nn;
+        const float t2 = z * h_prev;
+        const float h_new = t1 + t2;
+        if (lane == 0) {
+            // published first: the other blocks are waiting for it
+            const unsigned long long word = (unsigned long long)__float_as_uint(h_new) | ((unsigned long long)(unsigned)(t + 1) << 32);
+            __hip_atomic_store(a.xchg + (size_t)((t & 1) * 2 + d) * H + u, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            a.enc_h[(size_t)pos * 2 * H + col0 + u] = h_new;
+        }
+        h_prev = h_new;                          // (the same value in every lane of the wave)
+        // The block's waves start to poll together.  Without this barrier the waves that are done early poll
+        // while the last one still computes, and the extra device-coherent loads of 256 blocks slow every
+        // exchange down (measured before the pause above was added: 217 us for 50 positions against 153 us).
+        __syncthreads();
+    }
+}
+
 // =================================================================== host launchers ==
 
 q8_status q8i_enc_step(q8_ctx *ctx, int phase, const int *sent_off, int S, int t, int H, int ld, float *enc_h,
@@ -552,4 +701,47 @@ q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode
     default: launch_gru_n<8>(ctx, jobs, njobs, mode, blocks, smem, ch, xpre); break;
     }
     return q8i_launch_check(ctx, "gru");
+}
+
+// The encoder recurrence of one sentence in one launch.  Returns Q8_OK with *launched = 0
+// when the shape is not covered or the device cannot hold all blocks at once (the caller then
+// launches per position).  xchg: 4 H words of 8 bytes, zeroed here; err: one word, set to 1 by the
+// kernel if a wait gave up.
+q8_status q8i_encode_persistent(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights *bwd, const float *gxf,
+                                const float *gxb, int l, float *enc_h, unsigned long long *xchg, unsigned *err,
+                                int spin_limit, int *launched)
+{
+    *launched = 0;
+    const int H = fwd->Wh.cols, ld = fwd->Wh.ld;
+    if (H % 8 || H > 2048 || ld > 2048 || bwd->Wh.ld != ld || bwd->Wh.cols != H || l < 1) return Q8_OK;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(ctx->stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return Q8_OK;
+    const int ch = ld <= 1024 ? 1 : 2;
+    const void *kern = ch == 1 ? (const void *)encoder_persistent_kernel<1> : (const void *)encoder_persistent_kernel<2>;
+    const int blocks = 2 * (H / 8);
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, ENCP_THREADS, 0) != hipSuccess ||
+        (long long)per_cu * cus < blocks) {
+        (void)hipGetLastError();
+        return Q8_OK;
+    }
+    // (the error word is zero between calls: the workspace header starts zeroed and q8_encode_check clears it)
+    q8_status st = q8i_fill_u32(ctx, xchg, 4 * H * 2, 0u);
+    if (st) return st;
+    EncPArgs a;
+    a.Wh[0] = fwd->Wh.data; a.Wh[1] = bwd->Wh.data; a.bh[0] = fwd->bh; a.bh[1] = bwd->bh;
+    a.gx[0] = gxf; a.gx[1] = gxb; a.enc_h = enc_h; a.xchg = xchg; a.err = err;
+    a.l = l; a.H = H; a.ld = ld; a.spin_limit = spin_limit;
+    a.sh_w[0] = fwd->Wh.scale; a.sh_w[1] = bwd->Wh.scale;
+    // An ordinary launch: the grid fits the device (checked above), earlier work of this stream has ended when
+    // it starts, and work of other streams ends without needing this kernel, so every block becomes resident;
+    // a cooperative launch, which promises that, costs about 15 us more per call here.
+    if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_GRU, encoder_persistent_kernel<1>, dim3(blocks), dim3(ENCP_THREADS), 0, a);
+    else Q8_LAUNCH(ctx, Q8_KERNEL_GRU, encoder_persistent_kernel<2>, dim3(blocks), dim3(ENCP_THREADS), 0, a);
+    st = q8i_launch_check(ctx, "encoder recurrence");
+    if (st) return st;
+    *launched = 1;
+    return Q8_OK;
 }

@@ -23,6 +23,8 @@
 #define Q8_WS_HEADER 8192
 #define Q8_WS_SELECT_COUNTER 4096
 #define Q8_WS_SCRATCH_SLOT 6144
+#define Q8_WS_ENC_ERR 6208          // set to 1 by the one-launch encoder if a wait gave up (zeroed before each such launch)
+#define Q8_ENC_SPIN_DEFAULT (1 << 20)
 
 struct q8_ctx {
     hipStream_t stream;
@@ -35,6 +37,9 @@ struct q8_ctx {
     // bytes at the top of the workspace held by a composite call (q8_translate) while it
     // issues other calls, which carve from the bottom
     size_t ws_reserved_top;
+    // q8_encode: the recurrence in one cooperative launch where possible (q8_encoder_options), and the
+    // bound of its internal waits in polls
+    int enc_one_launch, enc_spin_limit;
 };
 
 // Launch of a kernel of class `kind` (a Q8_KERNEL_* value).  While a profile of that class
@@ -151,6 +156,9 @@ bool q8i_gru_gates_q_ok(int H, int ldh, int ldo, int ld1, int ld2);
 q8_status q8i_gru_gates_q(q8_ctx *ctx, const float *gx, const float *gh, const float *h_prev, int ldh, float *h_out,
                           int ldo, int H, int n, int8_t *q1, int ld1, float *s1, int8_t *q2, int ld2, float *s2);
 // one time step of the batched encoder: phase 0 quantizes the previous states, phase 1 applies the gates
+q8_status q8i_encode_persistent(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights *bwd, const float *gxf,
+                                const float *gxb, int l, float *enc_h, unsigned long long *xchg, unsigned *err,
+                                int spin_limit, int *launched);
 q8_status q8i_enc_step(q8_ctx *ctx, int phase, const int *sent_off, int S, int t, int H, int ld, float *enc_h,
                        const float *gxf, const float *gxb, float *ghf, float *ghb, int8_t *hqf, int8_t *hqb, float *hsf,
                        float *hsb);

@@ -205,6 +205,47 @@ def test_encoder(q, ctx, oracle, l, E, H):
     assert_close(enc, ref, "encoder states (free-running)")
 
 
+@pytest.mark.parametrize("l,E,H", [(50, 512, 1024), (1, 512, 1024), (2, 512, 1024), (5, 36, 40), (11, 100, 64), (60, 620, 1000),
+                                   (7, 64, 1032)])
+def test_encoder_in_one_launch_equals_one_launch_per_position(q, ctx, oracle, l, E, H):
+    """The recurrence of Eq. 1 as one cooperative launch (blocks hand the new state to each other through
+    tagged words) and as l launches: the same bits; the one-launch form reports no abandoned wait."""
+    p = synth.encoder(seed=3, l=l, E=E, H=H)
+    fwd, bwd = gpu_gru(q, ctx, p, "enc_fwd"), gpu_gru(q, ctx, p, "enc_bwd")
+    X = ctx.f32(p["X"])
+    try:
+        q.q8_encoder_options(ctx, one_launch=False)
+        per_position = np_(q.q8_encode(ctx, fwd, bwd, X))
+        q.q8_encoder_options(ctx, one_launch=True)
+        for _ in range(3):                                   # the exchange buffers are reused from call to call
+            one = np_(q.q8_encode(ctx, fwd, bwd, X))
+            q.q8_encode_check(ctx)
+            assert_same(one, per_position, "encoder states")
+    finally:
+        q.q8_encoder_options(ctx, one_launch=True)
+    assert_close(one, oracle.OracleModel(p).encode(p["X"]), "encoder states (free-running)")
+
+
+def test_encoder_wait_that_gives_up_ends_the_kernel_and_is_reported(q, ctx):
+    """With a bound of one poll per wait some block gives up at once: the kernel still ends normally,
+    q8_encode_check reports it, and the next call with the default bound is good again."""
+    p = synth.encoder(seed=3, l=20, E=512, H=1024)
+    fwd, bwd = gpu_gru(q, ctx, p, "enc_fwd"), gpu_gru(q, ctx, p, "enc_bwd")
+    X = ctx.f32(p["X"])
+    good = np_(q.q8_encode(ctx, fwd, bwd, X))
+    q.q8_encode_check(ctx)
+    try:
+        q.q8_encoder_options(ctx, one_launch=True, spin_limit=1)
+        q.q8_encode(ctx, fwd, bwd, X)
+        with pytest.raises(q.Q8Error):
+            q.q8_encode_check(ctx)
+    finally:
+        q.q8_encoder_options(ctx, one_launch=True, spin_limit=0)
+    again = np_(q.q8_encode(ctx, fwd, bwd, X))
+    q.q8_encode_check(ctx)
+    assert_same(again, good, "encoder states after the abandoned run")
+
+
 def test_output_layer_all_logits_equal_takes_the_exact_fallback(q, ctx, oracle):
     """Every logit ties: the survivor list of the pruned selection overflows and the exact rounds run."""
     V, R = 5000, 32
