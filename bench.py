@@ -688,6 +688,11 @@ def main():
                            ctx.f32(p4["enc_bwd.bx"]), ctx.f32(p4["enc_bwd.bh"]))
         X4, eo = ctx.f32(p4["X"]), ctx.empty(50, 2048)
         extra["calls_us_median_min"]["encoder_l50"] = median_of(torch, lambda: q.q8_encode(ctx, fwd, bwd, X4, eo), inner=10, warmup=3)
+        q.q8_encode_check(ctx)
+        q.q8_encoder_options(ctx, one_launch=False)
+        extra["calls_us_median_min"]["encoder_l50_one_launch_per_position"] = median_of(
+            torch, lambda: q.q8_encode(ctx, fwd, bwd, X4, eo), inner=10, warmup=3)
+        q.q8_encoder_options(ctx, one_launch=True)
         extra["gemv"] = gemv_bandwidth(torch, q, ctx, rng)
         extra["read_stream_ceiling"] = {"25.6MB_warm": ceil_warm,
                                         "25.6MB_cold": read_ceiling(torch, q, ctx, 25600000, cold=True),
