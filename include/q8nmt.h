@@ -123,8 +123,9 @@ size_t q8_workspace_bytes(int max_n, int max_l, int max_rows, int max_ld);
 
 /* Creates a context bound to hip_stream (a hipStream_t; NULL = the default stream)
  * and to the caller's device workspace (256-byte aligned).  Allocates host memory
- * only.  The first 4 KiB of the workspace are zeroed on the stream here and are kept
- * zero between calls by the kernels that use them as arrival counters. */
+ * only.  The first 32 KiB of the workspace (at least that many bytes are required) are
+ * zeroed on the stream here and are left zero after every call by the kernels that use
+ * them as arrival counters and exchange words. */
 q8_status q8_create(q8_ctx **out, void *hip_stream, void *workspace, size_t workspace_bytes);
 q8_status q8_destroy(q8_ctx *ctx);
 const char *q8_last_error(const q8_ctx *ctx);
@@ -289,6 +290,20 @@ q8_status q8_encode(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights
  * last check gave up (q8_translate and q8_translate_ensemble call it themselves). */
 q8_status q8_encoder_options(q8_ctx *ctx, int one_launch, int spin_limit);
 q8_status q8_encode_check(q8_ctx *ctx);
+
+/* How the attention block of cgru_decoder_step_q8 / _codes_q8 (Eq. 5-6, one sentence, n_beam <= 8)
+ * runs.  Both forms launch one kernel of l x n_beam blocks, one energy each, and give the same bits.
+ * exchange != 0 (the default): every block publishes its energy, waits for the other l - 1 of its
+ * hypothesis, and then sums and quantizes its own slice of the context vector (the slices' largest
+ * magnitudes are exchanged the same way); used where l <= 128, C <= 4096 and the device holds all
+ * l n_beam blocks of 1024 threads at once.  exchange == 0, and every other shape: the last block
+ * of a hypothesis to arrive computes the whole context vector.  The waits of the first form give
+ * up after spin_limit polls (<= 0: the default, 2^20); the kernel then still ends, its results and
+ * those of later calls are not valid until q8_encode_check (above) has reported it, once, and put
+ * the exchange words in the workspace header back to zero.  The same bound and the same report
+ * cover the one wait of output_logits_beam_q8, whose selection kernel hands every hypothesis' k
+ * best to the block that runs the search step. */
+q8_status q8_attention_options(q8_ctx *ctx, int exchange, int spin_limit);
 
 /* ---- search (Section 3 only says the beam is smaller than 8; these are the rules) ----
  * Token 0 is both begin- and end-of-sentence.  A search starts with one live hypothesis

@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 
 __all__ = ["Q8Error", "Context", "Mat", "Codes", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
            "q8_quantize_matrix", "q8_quantize_matrix_rows", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "q8_gemm_narrow_rows", "q8_attention_states_q8", "q8_attention_q8", "gru_step_q8", "cgru_decoder_step_q8",
-           "output_logits_q8", "output_logits_beam_q8", "q8_encode", "q8_encoder_options", "q8_encode_check", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
+           "output_logits_q8", "output_logits_beam_q8", "q8_encode", "q8_encoder_options", "q8_encode_check", "q8_attention_options", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
            "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "q8_math_eval", "MatF", "GruWeightsF32", "CgruWeightsF32", "ReadoutWeightsF32", "q8_gemv_f32",
            "cgru_decoder_step_f32", "output_logits_f32", "q8_translate_ensemble", "q8_translate_ensemble_bytes", "cgru_decoder_step_batch_q8", "q8_encode_batch", "q8_encode_batch_bytes", "q8_beam_init_batch",
            "q8_beam_update_batch", "q8_beam_result_batch", "q8_translate_batch", "q8_translate_batch_bytes",
@@ -102,6 +102,7 @@ def load_library():
         lib.q8_encode.argtypes = [vp, C.POINTER(_Gru), C.POINTER(_Gru), vp, ci, vp]
         lib.q8_encoder_options.argtypes = [vp, ci, ci]
         lib.q8_encode_check.argtypes = [vp]
+        lib.q8_attention_options.argtypes = [vp, ci, ci]
         lib.q8_beam_state_bytes.restype = C.c_size_t
         lib.q8_beam_state_bytes.argtypes = [ci]
         lib.q8_beam_init.argtypes = [vp, vp, ci, ci, vp, vp, ci, ci, vp, vp]
@@ -517,6 +518,10 @@ def q8_encoder_options(ctx, one_launch=True, spin_limit=0):
 
 def q8_encode_check(ctx):
     ctx.check(ctx.lib.q8_encode_check(ctx.handle))
+
+
+def q8_attention_options(ctx, exchange=True, spin_limit=0):
+    ctx.check(ctx.lib.q8_attention_options(ctx.handle, int(exchange), spin_limit))
 
 
 def q8_encode(ctx, fwd, bwd, X, enc_h=None):

@@ -144,6 +144,10 @@ q8_status q8_create(q8_ctx **out, void *hip_stream, void *workspace, size_t work
     c->ws_reserved_top = 0;
     c->enc_one_launch = 1;
     c->enc_spin_limit = Q8_ENC_SPIN_DEFAULT;
+    c->att_split = 1;
+    c->att_spin_limit = Q8_ENC_SPIN_DEFAULT;
+    c->att_capacity = -1;
+    c->att_words_set = 0;
     q8_status st = q8i_fill_u32(c, c->ws, Q8_WS_HEADER / 4, 0u);
     if (st) { delete c; return st; }
     *out = c;
@@ -448,7 +452,14 @@ q8_status cgru_decoder_step_codes_q8(q8_ctx *ctx, const q8_cgru_weights *w, cons
     q8i_gru_desc dq = {&w->q, ctx_out, C, s_mid, H, ghq, 3 * H, s_out, H, taps5 ? tq : nullptr,
                        have_codes ? cq : nullptr, have_codes ? cqs : nullptr};
     if (have_codes && codes_usable(ctx_codes, w->q.Wx.ld)) ctx_codes->valid = 1;
-    return q8i_gru(ctx, &dq, 1, n, Q8I_GRU_GH_PRE);
+    // (the attention kernel whose blocks exchange words leaves them set: this GRU zeroes them on its way out)
+    if (ctx->att_words_set) {
+        dq.clear = (unsigned long long *)(ctx->ws + Q8_WS_ATT_XCHG);
+        dq.clear_words = n * (Q8_WS_ATT_XCHG_PER_HYP / 8);
+    }
+    const q8_status st = q8i_gru(ctx, &dq, 1, n, Q8I_GRU_GH_PRE);
+    if (!st && dq.clear) ctx->att_words_set = 0;
+    return st;
 }
 
 q8_status cgru_decoder_step_batch_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h,
@@ -734,14 +745,29 @@ q8_status q8_encoder_options(q8_ctx *ctx, int one_launch, int spin_limit)
 q8_status q8_encode_check(q8_ctx *ctx)
 {
     if (!ctx) return Q8_ERR_NULL;
-    unsigned flag = 0;
-    hipError_t e = hipMemcpyAsync(&flag, ctx->ws + Q8_WS_ENC_ERR, sizeof(flag), hipMemcpyDeviceToHost, ctx->stream);
+    static_assert(Q8_WS_ATT_ERR == Q8_WS_ENC_ERR + 4, "the two flags are read together");
+    unsigned flag[2] = {0, 0};
+    hipError_t e = hipMemcpyAsync(flag, ctx->ws + Q8_WS_ENC_ERR, sizeof(flag), hipMemcpyDeviceToHost, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);
     if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "q8_encode_check: %s", hipGetErrorString(e));
-    if (flag) {
-        q8i_fill_u32(ctx, ctx->ws + Q8_WS_ENC_ERR, 1, 0u);
-        return q8_fail(ctx, Q8_ERR_DEVICE, "q8_encode: a wait inside the one-launch recurrence gave up; enc_h is not valid");
+    if (flag[0] || flag[1]) {
+        q8i_fill_u32(ctx, ctx->ws + Q8_WS_ENC_ERR, 2, 0u);
+        // (blocks that were not waited for may have left exchange words set after their reader cleared them)
+        q8i_fill_u32(ctx, ctx->ws + Q8_WS_ATT_XCHG, (Q8_WS_HEADER - Q8_WS_ATT_XCHG) / 4, 0u);
+        ctx->att_words_set = 0;
+        if (flag[0])
+            return q8_fail(ctx, Q8_ERR_DEVICE, "q8_encode: a wait inside the one-launch recurrence gave up; enc_h is not valid");
+        return q8_fail(ctx, Q8_ERR_DEVICE, "decoder step: a wait between the blocks of the attention or of the selection kernel gave up; "
+                                           "the results since the last check are not valid");
     }
+    return Q8_OK;
+}
+
+q8_status q8_attention_options(q8_ctx *ctx, int exchange, int spin_limit)
+{
+    if (!ctx) return Q8_ERR_NULL;
+    ctx->att_split = exchange ? 1 : 0;
+    ctx->att_spin_limit = spin_limit > 0 ? spin_limit : Q8_ENC_SPIN_DEFAULT;
     return Q8_OK;
 }
 

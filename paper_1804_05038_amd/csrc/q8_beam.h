@@ -39,6 +39,15 @@ __device__ __forceinline__ unsigned long long cand_key(float score, int parent, 
 }
 
 __device__ __forceinline__ void beam_gather(const BeamUpdateArgs &a, const int *s_parent, const int *s_token);
+template <bool GIVEN>
+__device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a, const float (&lp_in)[2], const int (&tk_in)[2]);
+// The tables as they lie in memory (written by an earlier kernel).
+__device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
+{
+    const float no_lp[2] = {0.0f, 0.0f};
+    const int no_tk[2] = {0, 0};
+    beam_update_body<false>(a, no_lp, no_tk);
+}
 
 // One block of at least 64 threads.  The decisions of a search step are taken by the block's first
 // wave alone, without barriers: lane L holds candidates L and L + 64 of the (at most 128) n_live x k
@@ -46,10 +55,11 @@ __device__ __forceinline__ void beam_gather(const BeamUpdateArgs &a, const int *
 // best b_live of them, in order, to lanes 0, 1, ...; ballots over those lanes give every survivor its
 // slot, the number of hypotheses that ended and the best of them; lane q then writes slot q of the
 // state.  Only then does the block meet, and all threads gather the surviving decoder states and the
-// embeddings of the new tokens.  COHERENT: the top-k tables were written by other blocks of the same
-// kernel with device-coherent stores and are read with device-coherent loads.
-template <bool COHERENT>
-__device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
+// embeddings of the new tokens.  GIVEN: lanes of the first wave bring their two candidates (entries
+// lane and lane + 64 of the top-k tables, the last entry repeated past the end) in lp_in / tk_in,
+// and the tables are not read.
+template <bool GIVEN>
+__device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a, const float (&lp_in)[2], const int (&tk_in)[2])
 {
     __shared__ int s_parent[Q8_MAX_BEAM], s_token[Q8_MAX_BEAM];
     __shared__ int s_skip;
@@ -64,8 +74,8 @@ __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int c = min(lane + 64 * u, nk - 1);      // (a lane past the tables reads their last entry and drops it)
-            lp[u] = COHERENT ? __hip_atomic_load(a.topk_logp + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.topk_logp[c];
-            tk[u] = COHERENT ? __hip_atomic_load(a.topk_idx + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : a.topk_idx[c];
+            lp[u] = GIVEN ? lp_in[u] : a.topk_logp[c];
+            tk[u] = GIVEN ? tk_in[u] : a.topk_idx[c];
         }
         const float sc_slot = st->score[lane & (Q8_MAX_BEAM - 1)];      // lane q < 8: score of slot q
         const int n_live = st->n_live, b_live = st->b_live, step = st->step, max_steps = st->max_steps;

@@ -19,6 +19,13 @@ struct AttArgs {
     int8_t *ctx_q;
     float *ctx_qscale;
     int ldq;
+    // attention_split_kernel: per hypothesis ATTS_L tagged energies then ATTS_L tagged slice maxima
+    // (8-byte words: value bits below, 1 above when present), zero on entry and left set; the flag a
+    // wait that gave up sets, the bound of a wait in polls, column pairs per block and its reciprocal
+    unsigned long long *xchg;
+    unsigned *wait_err;
+    int spin_limit, ppb;
+    float inv_ppb;
 };
 
 // Rows of P and enc_h that hypothesis b attends over, and how many.
@@ -165,6 +172,173 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
     __syncthreads();
     if (!s_last) return;
     att_finish<true>(a, b, l, enc_h, s_alpha);
+}
+
+// The same result without the single finishing block: every block needs all l energies of its
+// hypothesis anyway, so each publishes its own as a tagged 8-byte word (value, "present") with one
+// device-coherent store and polls the l words; each then derives the attention weights itself and
+// sums its own slice of ceil(C / 2 / l) column pairs of the context vector (Eq. 5).  The slice's
+// encoder states are requested while the energies are exchanged; once the weights are known, the
+// thread that fetched an entry forms its two products (exact in double), and one thread per
+// column adds them up over the positions in order, exactly the sum att_finish forms.  The scale
+// of the vector's codes needs its largest magnitude: the slices' maxima are exchanged the same
+// way, and every block quantizes its own slice.  Nobody pulls the l x C states through one
+// compute unit, and an exchange costs a store and a poll (0.6-0.8 us) instead of store, wait,
+// atomic, and a block that starts from nothing.  Timeline at l = 30, beam 5 (us after the first
+// block starts): energies summed 0.9, published 1.6, all 30 seen 2.7, weights 3.2, products in
+// LDS 3.6, columns summed 4.3, maxima published 4.5, seen 5.3, codes stored and last block gone
+// 6.0 (the kernel with the finishing block: 8.6-8.9).
+// The words stay set when the kernel ends (a block cannot know when the others have read them
+// without another exchange, which would cost a microsecond at the end): the next kernel of the
+// decoder step zeroes them, and the host keeps track that one does before this kernel runs again.
+// All l blocks of a hypothesis must be resident together (the host checks that the whole grid is);
+// every wait is bounded, a wait that gives up sets *wait_err and the block goes on with what it has
+// (finite values, wrong result).  Measured and not kept: a pause before the first poll (it helped
+// while the column sums were slower, 0.3 us, and does nothing now), requesting the slice before
+// the energies (the first barrier then waits for those loads), a departure count with the last
+// block clearing the words (+ 1.2 us at the kernel's end).
+#define ATTS_L 128            // source positions at most
+static_assert(2 * ATTS_L * 8 == Q8_WS_ATT_XCHG_PER_HYP, "energies and maxima of a hypothesis fill its part of the header");
+#define ATTS_SLICE 2304       // entries of LDS for a block's slice: l ceil(C / 2 / l) < C / 2 + l
+#define ATTS_SLICE_LOADS 3    // ceil(ATTS_SLICE / ATT_THREADS)
+__device__ __forceinline__ void atts_poll(const unsigned long long *w, int l, int lane, int limit, unsigned *wait_err,
+                                          float &v0, float &v1)
+{
+    unsigned long long x0 = 0ull, x1 = 0ull;
+    bool ok = false;
+    for (int spin = 0; spin < limit; ++spin) {
+        x0 = __hip_atomic_load(w + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);        // 128 words per hypothesis: in range
+        if (l > 64) x1 = __hip_atomic_load(w + 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool mine = (lane >= l || (x0 >> 32) != 0ull) && (lane + 64 >= l || (x1 >> 32) != 0ull);
+        if (__all(mine)) { ok = true; break; }
+        __builtin_amdgcn_s_sleep(1);
+    }
+    if (!ok && lane == 0) __hip_atomic_store(wait_err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v0 = __uint_as_float((unsigned)x0);
+    v1 = __uint_as_float((unsigned)x1);
+}
+
+__global__ __launch_bounds__(ATT_THREADS) void attention_split_kernel(AttArgs a)
+{
+    __shared__ double s_red[ATT_THREADS / 64];
+    __shared__ double s_alpha[ATTS_L];
+    __shared__ double2 s_p[ATTS_SLICE];
+    __shared__ float s_m[ATT_THREADS / 64];
+    __shared__ float s_sc[2];
+    const int i = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l = a.l, ppb = a.ppb, C = a.C;
+    unsigned long long *xe = a.xchg + (size_t)b * (Q8_WS_ATT_XCHG_PER_HYP / 8), *xm = xe + ATTS_L;
+
+    // Eq. 6: e[b, i] = sum_j v_j tanh(P[i, j] + a[b, j])
+    const float *Pi = a.P + (size_t)i * a.A;
+    const float *ab = a.a + (size_t)b * a.A;
+    double acc = 0.0;
+    for (int j = tid; j < a.A; j += ATT_THREADS) acc += (double)a.v[j] * (double)tanh_rn(Pi[j] + ab[j]);
+    acc = wave_sum_d(acc);
+    if (lane == 0) s_red[wave] = acc;
+    __syncthreads();
+    // This block's slice of the encoder states: entry e = t ppb + q is position t, column pair i ppb + q.
+    // Requested after the barrier (a barrier waits for the loads in flight) and, in the wave that
+    // publishes, after the energy is on its way; needed when the weights are known.
+    float2 hv[ATTS_SLICE_LOADS];
+    int tv[ATTS_SLICE_LOADS];
+    auto slice_request = [&]() {
+        const __amdgpu_buffer_rsrc_t rh = q8_rsrc(a.enc_h, (size_t)l * C * sizeof(float));
+#pragma unroll
+        for (int u = 0; u < ATTS_SLICE_LOADS; ++u) {
+            const int e = u * ATT_THREADS + tid;
+            const int t = (int)(((float)e + 0.5f) * a.inv_ppb);      // e / ppb: exact, both far below 2^12
+            const int c = 2 * (i * ppb + (e - t * ppb));
+            const unsigned off = (t < l && c < C) ? ((unsigned)t * (unsigned)C + (unsigned)c) * 4u : Q8_OOB;
+            hv[u] = __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(rh, (int)off, 0, 0));
+            tv[u] = min(t, l - 1);
+        }
+    };
+    if (wave != 0) slice_request();
+    if (wave == 0) {
+        if (lane == 0) {
+            double tot = 0.0;
+#pragma unroll
+            for (int w = 0; w < ATT_THREADS / 64; ++w) tot += s_red[w];
+            const float ev = (float)tot;
+            __hip_atomic_store(xe + i, (1ull << 32) | (unsigned long long)__float_as_uint(ev), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+            a.e[(size_t)b * a.lde + i] = ev;
+        }
+        slice_request();
+        float e0, e1;
+        atts_poll(xe, l, lane, a.spin_limit, a.wait_err, e0, e1);
+        // softmax over the l energies, as in att_finish
+        if (lane < l) s_alpha[lane] = (double)e0;
+        if (lane + 64 < l) s_alpha[lane + 64] = (double)e1;
+        float mx = -INFINITY;
+        for (int t = lane; t < l; t += 64) mx = fmaxf(mx, (float)s_alpha[t]);
+        mx = wave_max_f(mx);
+        double Z = 0.0, ex0 = 0.0;
+        for (int t = lane; t < l; t += 64) {
+            const double ex = q8_exp_d(fmax(s_alpha[t] - (double)mx, -700.0));
+            if (t == lane) ex0 = ex;
+            Z += ex;
+        }
+        Z = wave_sum_d(Z);
+        for (int t = lane; t < l; t += 64) {
+            const float al = (float)((t == lane ? ex0 : q8_exp_d(fmax(s_alpha[t] - (double)mx, -700.0))) / Z);
+            s_alpha[t] = (double)al;
+            if (a.alpha && i == 0) a.alpha[(size_t)b * a.lde + t] = al;
+        }
+    }
+    __syncthreads();
+    // Eq. 5.  The products alpha_t h of every entry, by the thread that fetched it (exact in double: 24 x 24
+    // bits), so that the sum over the positions, which has to run in order, is additions alone ...
+#pragma unroll
+    for (int u = 0; u < ATTS_SLICE_LOADS; ++u) {
+        const int e = u * ATT_THREADS + tid;
+        const double al = s_alpha[tv[u]];
+        if (e < ATTS_SLICE) s_p[e] = make_double2(al * (double)hv[u].x, al * (double)hv[u].y);
+    }
+    __syncthreads();
+    // ... by thread c < 2 ppb for column 2 i ppb + c, positions in order as att_finish adds them
+    const int c = 2 * i * ppb + tid;
+    const bool own = tid < 2 * ppb && c < C;
+    float f = 0.0f;
+    if (own) {
+        const double *pc = (const double *)s_p + tid;
+        double sum = 0.0;
+#pragma unroll 8
+        for (int t = 0; t < l; ++t) sum += pc[(size_t)t * 2 * ppb];
+        f = (float)sum;
+        a.ctx[(size_t)b * C + c] = f;
+    }
+    float m = wave_max_f(fabsf(f));
+    if (lane == 0) s_m[wave] = m;
+    __syncthreads();
+    if (wave == 0) {
+        if (lane == 0) {
+            m = 0.0f;
+#pragma unroll
+            for (int w = 0; w < ATT_THREADS / 64; ++w) m = fmaxf(m, s_m[w]);
+            __hip_atomic_store(xm + i, (1ull << 32) | (unsigned long long)__float_as_uint(m), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        }
+        float m0, m1;
+        atts_poll(xm, l, lane, a.spin_limit, a.wait_err, m0, m1);
+        m = fmaxf(lane < l ? m0 : 0.0f, lane + 64 < l ? m1 : 0.0f);
+        m = wave_max_f(m);
+        float scale, inv;
+        q8_scale_of(m, scale, inv);
+        if (lane == 0) {
+            s_sc[0] = scale;
+            s_sc[1] = inv;
+            if (i == 0) a.ctx_qscale[b] = scale;
+        }
+    }
+    __syncthreads();
+    {
+        const float inv = s_sc[1];
+        if (own) a.ctx_q[(size_t)b * a.ldq + c] = (int8_t)(q8_pack2(f, 0.0f, inv) & 0xff);
+        if (i == 0)                                               // pad bytes [C, ldq) are zero
+            for (int z = C + 2 * tid; z < a.ldq; z += 2 * ATT_THREADS) *(short *)(a.ctx_q + (size_t)b * a.ldq + z) = 0;
+    }
 }
 
 // Many hypotheses (sentences side by side): throughput matters, not the latency of one
@@ -462,7 +636,39 @@ q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, 
     const bool panel = n > Q8_MAX_BEAM;
     const bool codes = ctx_q && ctx_qscale && C % 2 == 0 && ldq >= C && ldq % 2 == 0 && ldq <= 2 * ATT_PAIRS * ATT_THREADS;
     t.ctx_q = codes ? ctx_q : nullptr; t.ctx_qscale = ctx_qscale; t.ldq = ldq;
+    t.xchg = nullptr; t.wait_err = nullptr; t.spin_limit = 0; t.ppb = 0; t.inv_ppb = 0.0f;
     if (codes_written) *codes_written = codes ? 1 : 0;
+    // One sentence: the form whose blocks exchange their energies and finish their own slices, where
+    // its shape limits hold, the consumer takes the codes, and the device holds the whole grid at once
+    // (its blocks wait for each other).
+    if (!panel && !sent_off && codes && ctx->att_split && l <= ATTS_L && C <= 4096) {
+        if (ctx->att_capacity < 0) {
+            int dev = 0, cus = 0, per_cu = 0;
+            if (hipGetDevice(&dev) == hipSuccess &&
+                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+                hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)attention_split_kernel, ATT_THREADS, 0) == hipSuccess)
+                ctx->att_capacity = per_cu * cus;
+            else {
+                (void)hipGetLastError();
+                ctx->att_capacity = 0;
+            }
+        }
+        const int ppb = (C / 2 + l - 1) / l;
+        if ((long long)l * n <= ctx->att_capacity && 2 * ppb <= ATT_THREADS && l * ppb <= ATTS_SLICE) {
+            t.xchg = (unsigned long long *)(ctx->ws + Q8_WS_ATT_XCHG);
+            if (ctx->att_words_set) {          // nobody cleared the last launch's words (its step ended early): do it now
+                const q8_status st = q8i_fill_u32(ctx, t.xchg, Q8_MAX_BEAM * (Q8_WS_ATT_XCHG_PER_HYP / 4), 0u);
+                if (st) return st;
+            }
+            ctx->att_words_set = 1;
+            t.wait_err = (unsigned *)(ctx->ws + Q8_WS_ATT_ERR);
+            t.spin_limit = ctx->att_spin_limit;
+            t.ppb = ppb;
+            t.inv_ppb = 1.0f / (float)ppb;
+            Q8_LAUNCH(ctx, Q8_KERNEL_ATTENTION, attention_split_kernel, dim3(l, n), dim3(ATT_THREADS), 0, t);
+            return q8i_launch_check(ctx, "attention");
+        }
+    }
     if (panel) {
         Q8_LAUNCH(ctx, Q8_KERNEL_ATTENTION, attention_panel_kernel, dim3((l + ATTP_POS - 1) / ATTP_POS, n), dim3(256), 0, t);
         // (block numbers are dealt to sentences in groups of eight, see the kernel: the grid covers whole groups)

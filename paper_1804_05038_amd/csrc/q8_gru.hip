@@ -23,7 +23,18 @@ struct GruJob {
 };
 struct GruJobs {
     GruJob j[2];
+    // 8-byte words that an earlier kernel of the step left set and wants zero at its next launch (NULL: none)
+    unsigned long long *clear;
+    int clear_words;
 };
+
+// The grid's first row of blocks zeroes them, as the last thing it does (nothing waits for the stores).
+__device__ __forceinline__ void gru_clear_words(const GruJobs &jobs)
+{
+    if (jobs.clear && blockIdx.y == 0)
+        for (unsigned w = blockIdx.x * 256u + threadIdx.x; w < (unsigned)jobs.clear_words; w += gridDim.x * 256u)
+            jobs.clear[w] = 0ull;
+}
 
 template <int N, int MODE>
 __device__ __forceinline__ void gru_x_taps(const GruJob &J, const int8_t *xq, const int8_t *hq, const float *s_scale)
@@ -138,6 +149,7 @@ __global__ __launch_bounds__(256) void gru_kernel(GruJobs jobs)
             J.h_out[(size_t)j * J.ldo + unit] = gru_gates(gx, gh, J.h_prev[(size_t)j * J.ldh + unit]);
         }
     }
+    gru_clear_words(jobs);
 }
 
 // Rows of at most 1024 * CH bytes, I % 4 == 0, H % 4 == 0, one hidden unit per wave
@@ -299,6 +311,7 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
         }
         J.h_out[(size_t)j * J.ldo + unit] = gru_gates(gx, gh, hp);
     }
+    gru_clear_words(jobs);
 }
 
 // Gates alone, for panels of more than 8 vectors whose two products came from the matrix
@@ -653,6 +666,8 @@ static void launch_gru_n(q8_ctx *ctx, const GruJobs &jobs, int njobs, int mode, 
 q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode)
 {
     GruJobs jobs;
+    jobs.clear = d[0].clear;
+    jobs.clear_words = d[0].clear ? d[0].clear_words : 0;
     size_t smem = 0;
     int max_ld = 0, maxH = 0;
     bool fast = true, xpre = mode == GRU_GH_PRE;      // codes of x: only if every job brings them

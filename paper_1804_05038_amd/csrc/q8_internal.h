@@ -16,14 +16,20 @@
 #include "q8_device.h"
 #endif
 
-// Workspace header: one attention arrival counter per hypothesis [0, 4096), the counter of
-// the fused selection + beam update at 4096, scratch slots (max bits, scale) at 6144.
+// Workspace header, zeroed by q8_create and zero again after every call that uses it: one attention
+// arrival counter per hypothesis in [0, 2048), 256 bytes apart; scratch slots (max bits, scale) at
+// 6144; the flags of waits that gave up; from 8192 the exchange words of the attention kernel without
+// a finishing block (2 KiB per hypothesis), at 24576 those of the selection kernel that runs the
+// search step.
 #define Q8_MAX_BEAM 8
 #define Q8_MAX_COLS 1024            // vectors of one batched call
-#define Q8_WS_HEADER 8192
-#define Q8_WS_SELECT_COUNTER 4096
+#define Q8_WS_HEADER 32768
 #define Q8_WS_SCRATCH_SLOT 6144
 #define Q8_WS_ENC_ERR 6208          // set to 1 by the one-launch encoder if a wait gave up (zeroed before each such launch)
+#define Q8_WS_ATT_ERR 6212          // the same for the attention kernel whose blocks wait for each other
+#define Q8_WS_ATT_XCHG 8192
+#define Q8_WS_ATT_XCHG_PER_HYP 2048
+#define Q8_WS_SELECT_XCHG 24576      // 128 words: the top-k entries on their way to the search step
 #define Q8_ENC_SPIN_DEFAULT (1 << 20)
 
 struct q8_ctx {
@@ -40,6 +46,13 @@ struct q8_ctx {
     // q8_encode: the recurrence in one cooperative launch where possible (q8_encoder_options), and the
     // bound of its internal waits in polls
     int enc_one_launch, enc_spin_limit;
+    // attention of one sentence: the form whose blocks exchange energies and finish their own slices
+    // (q8_attention_options), the bound of its waits in polls, and how many of its blocks the device
+    // holds at once (-1: not asked yet)
+    int att_split, att_spin_limit, att_capacity;
+    // that form leaves its exchange words set; the GRU that follows it in the step clears them.  1 while
+    // a launch's words are waiting for that (the next attention launch would clear them itself first).
+    int att_words_set;
 };
 
 // Launch of a kernel of class `kind` (a Q8_KERNEL_* value).  While a profile of that class
@@ -92,6 +105,9 @@ struct q8i_gru_desc {
     // not GX_PRE, may be NULL: where the codes [n x Wx.ld] and scales [n] of x are left for a later consumer
     int8_t *xq_out;
     float *xs_out;
+    // of the first job, may be NULL: 8-byte words the kernel zeroes on its way out
+    unsigned long long *clear;
+    int clear_words;
 };
 
 // beam update run by the last block of the selection kernel (NULL = none)

@@ -85,6 +85,7 @@ q8_status cgru_decoder_step_noalloc_q8(q8_ctx *ctx, const q8_cgru_weights *w, co
     view.ws = p;
     view.ws_bytes = Q8_STATIC_SCRATCH_BYTES;
     view.ws_reserved_top = 0;
+    view.att_split = 0;                      // (its waits report through a flag in the context's own workspace)
     st = cgru_decoder_step_q8(&view, w, P, enc_h, l, y_emb, s_prev, n_beam, s_out, ctx_out, alpha_out, s_mid_out, nullptr);
     ctx->prof_n = view.prof_n;               // event pairs of an open profile were taken from the shared list
     if (st) memcpy(ctx->err, view.err, sizeof(ctx->err));

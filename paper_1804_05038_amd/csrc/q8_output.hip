@@ -413,27 +413,16 @@ struct SelectArgs {
     int ntiles, n, k, V, ldl;
     int tiled;              // logits kept as [ntiles][n][16] instead of [n][ldl]
     int normalized;         // the "logits" are log-probabilities already: nothing is subtracted
-    int fuse_update;        // 1: the last block to finish also runs the beam update
-    unsigned *counter;      // arrival counter for that, zero on entry and on exit
+    int fuse_update;        // 1: block 0 also runs the beam update, once every block's k best are there
+    // for that: n k 8-byte words, one per top-k entry (bit 63 "present", token id, log-probability), zero on
+    // entry and on exit; the flag a wait that gave up sets; the bound of the wait in polls
+    unsigned long long *xw;
+    unsigned *wait_err;
+    int spin_limit;
     BeamUpdateArgs bu;
 };
 
 #define SEL_CAP 2048          // survivors held in LDS
-
-// Top-k entry `o` of the output tables; device-coherent when another block will read it.
-__device__ __forceinline__ void put_topk(const SelectArgs &a, size_t o, int idx, float logp)
-{
-    // (a round of the exact fallback that finds no candidate, which takes non-finite logits, decodes to an
-    // index past the table; whoever gathers an embedding row by it must find a row)
-    idx = (unsigned)idx < (unsigned)a.V ? idx : 0;
-    if (a.fuse_update) {
-        __hip_atomic_store(a.topk_idx + o, idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(a.topk_logp + o, logp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    } else {
-        a.topk_idx[o] = idx;
-        a.topk_logp[o] = logp;
-    }
-}
 
 // One block of 256 threads per hypothesis; thread t owns tiles t, t + 256, ... (up to 16).
 // (1) log-sum-exp from the tile partials.  (2) Each wave sorts its 64 threads' maxima; the
@@ -442,7 +431,14 @@ __device__ __forceinline__ void put_topk(const SelectArgs &a, size_t o, int idx,
 // a tile whose maximum is >= T.  (3) Those tiles are read back, logits >= T
 // collected (a few dozen unless many logits tie) and ranked by (value descending, index
 // ascending).  If ties overflow the survivor list, k exact rounds of arg-max over the
-// whole row run instead.
+// whole row run instead.  The k results are collected in LDS (a rank that found no candidate,
+// which takes non-finite logits, keeps an entry of token 0 with log-probability -inf) and stored
+// by k threads.
+// With the search step fused in, every block also publishes its k entries as tagged 8-byte words
+// with device-coherent stores and is done; block 0 polls the n k words (two per lane of one wave),
+// clears them for the next launch (it is their only reader) and goes on with the values in
+// registers: one store and a poll between "ranked" and "keys formed", where a count of arrivals
+// (stores performed, atomic, the last block reading the tables back) took 1.7 us.
 __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
 {
     __shared__ unsigned short s_q[OUT_MAX_TILES];
@@ -452,9 +448,11 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     __shared__ unsigned long long s_u[4];
     __shared__ float s_t4[4];
     __shared__ int s_nq, s_ns;
+    __shared__ unsigned long long s_top[16];
     const int j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = a.n, k = a.k;
     const int ntiles = a.ntiles;
     if (tid == 0) { s_nq = 0; s_ns = 0; }
+    if (tid < 16) s_top[tid] = topk_key(-INFINITY, 0);
 
     float pm[OUT_SB];
     double ps[OUT_SB];
@@ -557,7 +555,7 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
                 const ulonglong2 p0 = *(const ulonglong2 *)&s_key[u], p1 = *(const ulonglong2 *)&s_key[u + 2];
                 rank += (p0.x > key) + (p0.y > key) + (p1.x > key) + (p1.y > key);
             }
-            if (rank < k) put_topk(a, (size_t)j * k + rank, topk_key_idx(key), topk_key_val(key) - lse);
+            if (rank < k) s_top[rank] = key;
         }
     } else {
     // ---- heavily tied logits: k exact rounds of arg-max over the whole row
@@ -575,26 +573,48 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
         best = s_u[0];
 #pragma unroll
         for (int w = 1; w < 4; ++w) best = s_u[w] > best ? s_u[w] : best;
-        if (tid == 0) put_topk(a, (size_t)j * k + r, topk_key_idx(best), topk_key_val(best) - lse);
+        if (tid == 0) s_top[r] = best;
         prev = best;
     }
     }
-
-    if (!a.fuse_update) return;
-    // ---- the block that finishes last continues with the beam update.  Every thread waits
-    // until its own (device-coherent) top-k stores have been performed, then one thread
-    // counts the block's arrival with a device-coherent atomic.
-    __shared__ int s_is_last;
-    q8_stores_performed();
     __syncthreads();
-    if (tid == 0) {
-        const unsigned prev_cnt = __hip_atomic_fetch_add(a.counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_is_last = (prev_cnt == (unsigned)n - 1u);
-        if (s_is_last) __hip_atomic_store(a.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid < k) {
+        const unsigned long long key = s_top[tid];
+        // (a round of the exact fallback that finds no candidate decodes to an index past the table;
+        // whoever gathers an embedding row by it must find a row)
+        int idx = topk_key_idx(key);
+        idx = (unsigned)idx < (unsigned)a.V ? idx : 0;
+        const float logp = topk_key_val(key) - lse;
+        const size_t o = (size_t)j * k + tid;
+        a.topk_idx[o] = idx;
+        a.topk_logp[o] = logp;
+        if (a.fuse_update)
+            __hip_atomic_store(a.xw + o, (1ull << 63) | ((unsigned long long)(unsigned)idx << 32) | __float_as_uint(logp),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    __syncthreads();
-    if (!s_is_last) return;
-    beam_update_body<true>(a.bu);
+
+    if (!a.fuse_update || j != 0) return;
+    // ---- block 0 continues with the search step once all n k entries are there
+    float lp[2] = {0.0f, 0.0f};
+    int tk[2] = {0, 0};
+    if (tid < 64) {
+        const int nk = n * k;                      // at most 128
+        const int c0 = min(lane, nk - 1), c1 = min(lane + 64, nk - 1);
+        unsigned long long x0 = 0ull, x1 = 0ull;
+        bool ok = false;
+        for (int spin = 0; spin < a.spin_limit; ++spin) {
+            x0 = __hip_atomic_load(a.xw + c0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            x1 = __hip_atomic_load(a.xw + c1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (__all((x0 >> 63) != 0ull && (x1 >> 63) != 0ull)) { ok = true; break; }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        if (!ok && lane == 0) __hip_atomic_store(a.wait_err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        lp[0] = __uint_as_float((unsigned)x0); tk[0] = (int)((x0 >> 32) & 0x7fffffffull);
+        lp[1] = __uint_as_float((unsigned)x1); tk[1] = (int)((x1 >> 32) & 0x7fffffffull);
+        if (lane < nk) a.xw[lane] = 0ull;
+        if (lane + 64 < nk) a.xw[lane + 64] = 0ull;
+    }
+    beam_update_body<true>(a.bu, lp, tk);
 }
 
 // ========================================== selection for panels, logits recomputed ==
@@ -912,7 +932,9 @@ static q8_status launch_select(q8_ctx *ctx, const float *part_max, const double 
     s.lse = lse; s.topk_logp = topk_logp; s.topk_idx = topk_idx;
     s.ntiles = q8i_out_tiles(V); s.n = n; s.k = k; s.V = V; s.ldl = V; s.tiled = tiled; s.normalized = normalized;
     s.fuse_update = beam ? 1 : 0;
-    s.counter = (unsigned *)(ctx->ws + Q8_WS_SELECT_COUNTER);
+    s.xw = (unsigned long long *)(ctx->ws + Q8_WS_SELECT_XCHG);
+    s.wait_err = (unsigned *)(ctx->ws + Q8_WS_ATT_ERR);
+    s.spin_limit = ctx->att_spin_limit;
     if (beam) {
         BeamUpdateArgs bu = {(BeamState *)beam->state, topk_logp, topk_idx, beam->s_step, beam->E_tgt, beam->y_emb,
                              beam->s_next, n, k, beam->E, beam->H, V};

@@ -19,7 +19,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const float *__restric
 
 __global__ __launch_bounds__(256) void beam_update_kernel(BeamUpdateArgs a)
 {
-    beam_update_body<false>(a);
+    beam_update_body(a);
 }
 
 size_t q8i_beam_state_bytes(int max_steps)
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256) void beam_update_batch_kernel(BeamBatchArgs b)
     const size_t slot = (size_t)s * b.beam;
     BeamUpdateArgs a = {(BeamState *)(b.states + (size_t)s * b.stride), b.topk_logp + slot * b.k, b.topk_idx + slot * b.k,
                         b.s_step + slot * b.H, b.E_tgt, b.y_emb + slot * b.E, b.s_next + slot * b.H, b.beam, b.k, b.E, b.H, b.V};
-    beam_update_body<false>(a);
+    beam_update_body(a);
     __syncthreads();
     if (threadIdx.x == 0) b.done[s] = a.st->done;
 }

@@ -104,6 +104,63 @@ def test_cgru_decoder_step(q, ctx, oracle, E, H, A, l, n):
         assert_same(r2["s"], s, "repeat s"); assert_same(r2["ctx"], ctxv, "repeat ctx")
 
 
+def _step_with_codes(q, ctx, w, P, enc_h, y, s_prev, n):
+    codes = (q.Codes(ctx, n, w.r.Wx.ld), q.Codes(ctx, n, w.q.Wx.ld))
+    codes[1].q.fill_(77)        # pad bytes past C must come out zero whatever was there
+    r = q.cgru_decoder_step_q8(ctx, w, P, enc_h, y, s_prev, codes=codes)
+    assert codes[1].valid
+    return {k: np_(r[k]) for k in ("s", "ctx", "alpha", "s_mid")} | {"cq": np_(codes[1].q), "cs": np_(codes[1].scale)}
+
+
+@pytest.mark.parametrize("E,H,A,l,n", [(512, 1024, 1024, 30, 5), (512, 1024, 1024, 30, 1), (512, 1024, 1024, 1, 2), (512, 1024, 1024, 2, 3),
+                                       (512, 1024, 1024, 10, 8), (512, 1024, 1024, 64, 5), (512, 1024, 1024, 65, 3),
+                                       (512, 1024, 1024, 128, 2), (36, 40, 28, 7, 3), (64, 64, 64, 100, 4),
+                                       (620, 1000, 1000, 60, 8), (64, 2048, 64, 3, 2)])
+def test_attention_blocks_that_exchange_equal_the_finishing_block(q, ctx, oracle, E, H, A, l, n):
+    """Eq. 5-6: the attention kernel whose blocks exchange energies and finish their own slices of the
+    context vector gives the bits of the kernel whose last block per hypothesis finishes alone
+    (weights, context vector, its codes and scale, the new state), call after call."""
+    p = synth.cgru_step(seed=11, E=E, H=H, A=A, l=l, n_beam=n)
+    _, w = _decoder(q, ctx, oracle, p)
+    P = q.q8_gemm_narrow(ctx, gpu_mat(q, ctx, p["att.W"]), ctx.f32(p["enc_h"]), ctx.f32(p["att.b"]))
+    enc_h, y, s_prev = ctx.f32(p["enc_h"]), ctx.f32(p["y_emb"]), ctx.f32(p["s_prev"])
+    try:
+        q.q8_attention_options(ctx, exchange=False)
+        ref = _step_with_codes(q, ctx, w, P, enc_h, y, s_prev, n)
+    finally:
+        q.q8_attention_options(ctx, exchange=True)
+    for rep in range(3):
+        got = _step_with_codes(q, ctx, w, P, enc_h, y, s_prev, n)
+        for key in ref:
+            assert_same(got[key], ref[key], "%s (call %d)" % (key, rep))
+    q.q8_encode_check(ctx)
+    assert not ref["cq"][:, 2 * H:].any()
+
+
+def test_attention_wait_that_gives_up_ends_the_kernel_and_is_reported(q, ctx, oracle):
+    """With a bound of one poll per wait some block gives up at once: the kernel still ends normally,
+    q8_encode_check reports it once, and the next call with the default bound is good again (the
+    exchange words were cleared by the abandoned run too)."""
+    p = synth.cgru_step(seed=12, E=512, H=1024, A=1024, l=30, n_beam=5)
+    _, w = _decoder(q, ctx, oracle, p)
+    P = q.q8_gemm_narrow(ctx, gpu_mat(q, ctx, p["att.W"]), ctx.f32(p["enc_h"]), ctx.f32(p["att.b"]))
+    enc_h, y, s_prev = ctx.f32(p["enc_h"]), ctx.f32(p["y_emb"]), ctx.f32(p["s_prev"])
+    good = _step_with_codes(q, ctx, w, P, enc_h, y, s_prev, 5)
+    q.q8_encode_check(ctx)
+    try:
+        q.q8_attention_options(ctx, exchange=True, spin_limit=1)
+        _step_with_codes(q, ctx, w, P, enc_h, y, s_prev, 5)
+        with pytest.raises(q.Q8Error):
+            q.q8_encode_check(ctx)
+    finally:
+        q.q8_attention_options(ctx, exchange=True, spin_limit=0)
+    q.q8_encode_check(ctx)
+    again = _step_with_codes(q, ctx, w, P, enc_h, y, s_prev, 5)
+    q.q8_encode_check(ctx)
+    for key in good:
+        assert_same(again[key], good[key], key + " after the abandoned run")
+
+
 def test_cgru_uniform_attention_special_case(q, ctx, oracle):
     p = synth.cgru_step(seed=5, E=64, H=64, A=32, l=9, n_beam=2)
     m, w = _decoder(q, ctx, oracle, p)

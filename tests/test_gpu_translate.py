@@ -172,9 +172,10 @@ def _decode_loop(q, c, m, P, enc_h, n, s0, T):
 
 
 def test_non_finite_logits_keep_the_search_inside_its_tables(q, ctx):
-    """A NaN bias makes every logit NaN: none qualifies for the top-k tables, which keep what
-    they held before (here: ids far outside the vocabulary).  The fused search step must still
-    gather only rows of E_tgt and of the decoder states."""
+    """A NaN bias makes every logit NaN: none qualifies for the top-k tables, whose entries then
+    carry token 0 and a non-finite log-probability whatever they held before (here: ids far outside
+    the vocabulary).  The fused search step must still gather only rows of E_tgt and of the
+    decoder states."""
     V, E, H, A, R, n, T = 500, 64, 128, 64, 64, 4, 6
     p = synth.full_model(seed=22, V=V, E=E, H=H, A=A, R=R, w_std=0.2, b_std=0.1)
     m = q.Model.from_params(ctx, p)
@@ -245,6 +246,47 @@ def test_fused_tail_equals_separate_calls_and_graph_replays(q, ctx, oracle):
         assert got[0].tolist() == ref[0].tolist() and got[1] == ref[1] and got[2:] == ref[2:], rep
         q.q8_gemv(ctx, m.att_W, enc_h[0])          # unrelated eager work between replays
         torch.cuda.synchronize()
+
+
+def test_search_step_wait_that_gives_up_is_reported_and_the_next_search_is_good(q, ctx, oracle):
+    """With a bound of one poll the block that runs the search step inside the selection kernel may
+    stop waiting for the other hypotheses' k best: the kernel still ends normally, q8_encode_check
+    reports it once and clears the exchange words, and the same search run again gives the result
+    of the separate calls."""
+    V, E, H, A, R, n, T = 500, 64, 128, 64, 64, 4, 12
+    p = synth.full_model(seed=21, V=V, E=E, H=H, A=A, R=R, w_std=0.2, b_std=0.1)
+    m = q.Model.from_params(ctx, p)
+    rng = np.random.default_rng(3)
+    enc_h = ctx.f32(rng.standard_normal((9, 2 * H)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    s0 = ctx.f32(rng.standard_normal(H).astype(np.float32))
+    st, c0, c1, c2 = _decode_loop(q, ctx, m, P, enc_h, n, s0, T)
+
+    def search():
+        c0.launch()
+        for _ in range(T):
+            c1.launch(); c2.launch()
+        return q.q8_beam_result(ctx, st, T)
+
+    good = search()
+    q.q8_encode_check(ctx)
+    gave_up = False
+    try:
+        q.q8_attention_options(ctx, exchange=True, spin_limit=1)
+        for _ in range(5):                         # (a single poll can succeed when the other blocks are quick)
+            search()
+            try:
+                q.q8_encode_check(ctx)
+            except q.Q8Error:
+                gave_up = True
+                break
+    finally:
+        q.q8_attention_options(ctx, exchange=True, spin_limit=0)
+    assert gave_up
+    q.q8_encode_check(ctx)
+    again = search()
+    q.q8_encode_check(ctx)
+    assert again[0].tolist() == good[0].tolist() and again[1:] == good[1:]
 
 
 def test_two_contexts_on_two_streams(q, ctx, oracle):
