@@ -157,35 +157,46 @@ __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a, const 
 // Gathers the surviving decoder states and the embeddings of the new tokens: slot q of the
 // next step continues slot s_parent[q] with token s_token[q] (slots beyond the survivors
 // repeat survivor 0).  All loads of a thread are issued before its stores.
+// Thread tid moves 16-byte piece tid (+ 256 per pass) of every row: ROWS state rows and ROWS
+// embedding rows per pass, rows past n repeating row n - 1 and pieces past a row's end repeating
+// its last piece (same value to the same place).  So there is no division in the addressing and no
+// branch around a load or a store: inside a branch the compiler waits for each of them on the
+// spot, and a thread's loads and stores become as many memory round trips in a row.
+// (Moved as plain 16-byte vectors: nothing here looks inside the values.)
+template <int ROWS>
+__device__ __forceinline__ void beam_gather_rows(const BeamUpdateArgs &a, const int *s_parent, const int *s_token)
+{
+    const int tid = threadIdx.x;
+    const int H4 = a.H >> 2, E4 = a.E >> 2;
+    const v4i *s4 = (const v4i *)a.s_step, *e4 = (const v4i *)a.E_tgt;
+    v4i *sn4 = (v4i *)a.s_next, *y4 = (v4i *)a.y_emb;
+    for (int c0 = 0; c0 < max(H4, E4); c0 += 256) {
+        const int ch = min(c0 + tid, H4 - 1), ce = min(c0 + tid, E4 - 1);
+        v4i vs[ROWS], ve[ROWS];
+#pragma unroll
+        for (int q = 0; q < ROWS; ++q) {
+            const int qq = min(q, a.n - 1);
+            vs[q] = s4[(size_t)s_parent[qq] * H4 + ch];
+            ve[q] = e4[(size_t)s_token[qq] * E4 + ce];
+        }
+#pragma unroll
+        for (int q = 0; q < ROWS; ++q) {
+            const int qq = min(q, a.n - 1);
+            sn4[(size_t)qq * H4 + ch] = vs[q];
+            y4[(size_t)qq * E4 + ce] = ve[q];
+        }
+    }
+}
+
 __device__ __forceinline__ void beam_gather(const BeamUpdateArgs &a, const int *s_parent, const int *s_token)
 {
     const int tid = threadIdx.x;
     if (((a.H | a.E) & 3) == 0) {
-        // Thread tid moves 16-byte piece tid (+ 256 per pass) of every row: eight state rows and eight
-        // embedding rows per pass, rows past n repeating row n - 1 and pieces past a row's end repeating
-        // its last piece (same value to the same place).  So there is no division in the addressing and no
-        // branch around a load or a store: inside a branch the compiler waits for each of them on the
-        // spot, and a thread's loads and stores become as many memory round trips in a row.
-        // (Moved as plain 16-byte vectors: nothing here looks inside the values.)
-        const int H4 = a.H >> 2, E4 = a.E >> 2;
-        const v4i *s4 = (const v4i *)a.s_step, *e4 = (const v4i *)a.E_tgt;
-        v4i *sn4 = (v4i *)a.s_next, *y4 = (v4i *)a.y_emb;
-        for (int c0 = 0; c0 < max(H4, E4); c0 += 256) {
-            const int ch = min(c0 + tid, H4 - 1), ce = min(c0 + tid, E4 - 1);
-            v4i vs[Q8_MAX_BEAM], ve[Q8_MAX_BEAM];
-#pragma unroll
-            for (int q = 0; q < Q8_MAX_BEAM; ++q) {
-                const int qq = min(q, a.n - 1);
-                vs[q] = s4[(size_t)s_parent[qq] * H4 + ch];
-                ve[q] = e4[(size_t)s_token[qq] * E4 + ce];
-            }
-#pragma unroll
-            for (int q = 0; q < Q8_MAX_BEAM; ++q) {
-                const int qq = min(q, a.n - 1);
-                sn4[(size_t)qq * H4 + ch] = vs[q];
-                y4[(size_t)qq * E4 + ce] = ve[q];
-            }
-        }
+        // (a compute unit moves these rows at about 50 GB/s: rows that only repeat the last one cost as much
+        // as the others, so the row count follows the beam in three steps)
+        if (a.n <= 4) beam_gather_rows<4>(a, s_parent, s_token);
+        else if (a.n <= 6) beam_gather_rows<6>(a, s_parent, s_token);
+        else beam_gather_rows<Q8_MAX_BEAM>(a, s_parent, s_token);
     } else {
         for (int e = tid; e < a.n * a.H; e += blockDim.x) {
             const int q = e / a.H, c = e - q * a.H;
