@@ -73,12 +73,18 @@ class DecodeLoop:
         self.t = 0
         # a search is re-started every MAX_STEPS steps, as for a new sentence of the same length
         self.c0 = q.q8_beam_init(ctx, self.state, n, MAX_STEPS, self.s0, m.E_tgt, self.y, self.s, bind=True)
-        # the codes of y and of the context vectors travel from the step to the output layer's first layer
-        codes = None if os.environ.get("Q8_BENCH_NO_CODES") else (q.Codes(ctx, n, m.dec.r.Wx.ld), q.Codes(ctx, n, m.dec.q.Wx.ld))
+        # the codes of y and of the context vectors travel from the step to the output layer's first layer, and
+        # those of the rows the search step gathers (new embeddings, surviving states) to the next step's GRU r
+        codes = None if os.environ.get("Q8_BENCH_NO_CODES") else (q.Codes(ctx, n, m.dec.r.Wx.ld), q.Codes(ctx, n, m.dec.q.Wx.ld),
+                                                                   q.Codes(ctx, n, m.dec.r.Wh.ld))
+        if codes and os.environ.get("Q8_BENCH_NO_HANDOVER"):      # (codes inside a step only, none from step to step)
+            codes = codes[:2]
+        self.codes = codes if codes and len(codes) == 3 else None
         self.c1 = q.cgru_decoder_step_q8(ctx, m.dec, P, enc_h, self.y, self.s, bind=True, codes=codes)
-        # output layer + top-k + beam update (the update runs in the selection kernel's last block)
+        # output layer + top-k + beam update (the update runs in block 0 of the selection kernel)
         self.c2 = q.output_logits_beam_q8(ctx, m.ro, m.W_out, m.b_out, self.c1.out["s"], self.y, self.c1.out["ctx"],
-                                          self.state, m.E_tgt, self.s, k=TOPK, bind=True, codes=codes)
+                                          self.state, m.E_tgt, self.s, k=TOPK, bind=True, codes=codes,
+                                          E_codes=m.E_tgt_codes if codes and len(codes) == 3 else None)
         # the two calls it fuses, for the per-call timings
         self.c2a = q.output_logits_q8(ctx, m.ro, m.W_out, m.b_out, s=self.c1.out["s"], y_emb=self.y,
                                       ctx_vec=self.c1.out["ctx"], k=TOPK, want_logits=False, bind=True)
@@ -88,6 +94,8 @@ class DecodeLoop:
     def step(self):
         if self.t % MAX_STEPS == 0:
             self.c0.launch()
+            if self.codes:                      # (a new search: y and s are not what the codes were made of)
+                self.codes[0].invalidate(); self.codes[2].invalidate()
         self.t += 1
         self.c1.launch()
         self.c2.launch()

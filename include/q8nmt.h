@@ -360,6 +360,39 @@ q8_status output_logits_beam_codes_q8(q8_ctx *ctx, const q8_readout_weights *ro,
                                       float *topk_logp, int32_t *topk_idx, const q8_codes *y_codes,
                                       const q8_codes *ctx_codes);
 
+/* The same pair for a decoding loop, in which the search step's outputs are the next decoder
+ * step's inputs: the rows it gathers (embeddings of the new tokens into y_emb, surviving states
+ * into s_next) are rows that were, or can be, quantized before (Section 3: a vector's codes
+ * depend on the vector alone), so their codes are gathered with them and GRU r of the next step
+ * (Eq. 3) multiplies without quantizing.
+ * q8_row_codes: every row of the embedding table quantized on its own maximum, once, by
+ * q8_quantize_matrix_rows(E_tgt, V, E, E, q, ld, scale) with ld = r.Wx.ld (= the readout's W_y.ld).
+ * output_logits_beam_loop_q8 is output_logits_beam_codes_q8 (y_codes with valid == 1 and ctx_codes
+ * are this step's, for the readout) and, given E_codes, y_codes and s_next_codes with the pitches of
+ * W_y and W_s and E / 4 + W_y.ld / 16 + W_s.ld / 16 <= 256, leaves the codes of the new y_emb in
+ * y_codes and those of s_next (copies of the codes the readout made of s) in s_next_codes, both with
+ * valid = 2; otherwise valid = 0.  cgru_decoder_step_loop_q8 is cgru_decoder_step_codes_q8 and takes
+ * y_codes and s_prev_codes with valid == 2 (pitches r.Wx.ld, r.Wh.ld; no taps) as the codes of
+ * y_emb and s_prev; on return y_codes is valid (1) for the readout as before and s_prev_codes is
+ * spent (0).  A caller that changes y_emb or s_prev itself (q8_beam_init does) sets valid = 0.
+ * Bit-identical to the plain calls. */
+typedef struct {
+    const int8_t *q;       /* [rows x ld], pad bytes zero */
+    const float *scale;    /* [rows] */
+    int ld;
+} q8_row_codes;
+q8_status cgru_decoder_step_loop_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h,
+                                    int l, const float *y_emb, const float *s_prev, int n_beam,
+                                    float *s_out, float *ctx_out, float *alpha_out, float *s_mid_out,
+                                    const q8_taps *taps5, q8_codes *y_codes, q8_codes *ctx_codes,
+                                    q8_codes *s_prev_codes);
+q8_status output_logits_beam_loop_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out,
+                                     const float *b_out, const float *s, float *y_emb, const float *ctx_vec,
+                                     int n_beam, int k, void *state, const float *E_tgt, int E, float *s_next,
+                                     float *topk_logp, int32_t *topk_idx, q8_codes *y_codes,
+                                     const q8_codes *ctx_codes, q8_codes *s_next_codes,
+                                     const q8_row_codes *E_codes);
+
 /* The same for panels of hypothesis slots: cgru_decoder_step_batch_codes_q8 is
  * cgru_decoder_step_batch_q8 and also leaves the codes of y_emb (pitch r.Wx.ld), of the context
  * vectors (pitch q.Wx.ld) and of the new states s_out (any pitch ld >= H that is a multiple of

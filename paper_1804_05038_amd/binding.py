@@ -12,7 +12,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 
-__all__ = ["Q8Error", "Context", "Mat", "Codes", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
+__all__ = ["Q8Error", "Context", "Mat", "Codes", "RowCodes", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
            "q8_quantize_matrix", "q8_quantize_matrix_rows", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "q8_gemm_narrow_rows", "q8_attention_states_q8", "q8_attention_q8", "gru_step_q8", "cgru_decoder_step_q8",
            "output_logits_q8", "output_logits_beam_q8", "q8_encode", "q8_encoder_options", "q8_encode_check", "q8_attention_options", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
            "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "q8_math_eval", "MatF", "GruWeightsF32", "CgruWeightsF32", "ReadoutWeightsF32", "q8_gemv_f32",
@@ -34,6 +34,10 @@ class Q8Error(RuntimeError):
 class _Mat(C.Structure):
     _fields_ = [("data", C.c_void_p), ("rows", C.c_int), ("cols", C.c_int), ("ld", C.c_int), ("scale", C.c_float),
                 ("tiles", C.c_void_p)]
+
+
+class _RowCodes(C.Structure):
+    _fields_ = [("q", C.c_void_p), ("scale", C.c_void_p), ("ld", C.c_int)]
 
 
 class _Codes(C.Structure):
@@ -93,6 +97,7 @@ def load_library():
         lib.gru_step_q8.argtypes = [vp, C.POINTER(_Gru), vp, vp, ci, vp, C.POINTER(_Taps)]
         lib.cgru_decoder_step_q8.argtypes = [vp, C.POINTER(_Cgru), vp, vp, ci, vp, vp, ci, vp, vp, vp, vp, C.POINTER(_Taps)]
         lib.cgru_decoder_step_codes_q8.argtypes = lib.cgru_decoder_step_q8.argtypes + [C.POINTER(_Codes), C.POINTER(_Codes)]
+        lib.cgru_decoder_step_loop_q8.argtypes = lib.cgru_decoder_step_q8.argtypes + [C.POINTER(_Codes)] * 3
         lib.cgru_decoder_step_noalloc_q8.argtypes = lib.cgru_decoder_step_q8.argtypes[:-1]
         lib.q8_noalloc_setup.argtypes = [vp]
         lib.q8_noalloc_scratch_bytes.restype = C.c_size_t
@@ -112,6 +117,7 @@ def load_library():
         lib.output_logits_beam_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, ci, ci, vp,
                                               vp, ci, vp, vp, vp]
         lib.output_logits_beam_codes_q8.argtypes = lib.output_logits_beam_q8.argtypes + [C.POINTER(_Codes), C.POINTER(_Codes)]
+        lib.output_logits_beam_loop_q8.argtypes = lib.output_logits_beam_q8.argtypes + [C.POINTER(_Codes)] * 3 + [C.POINTER(_RowCodes)]
         lib.q8_translate_bytes.restype = C.c_size_t
         lib.q8_translate_bytes.argtypes = [C.POINTER(_Model), ci, ci, ci, ci]
         lib.q8_translate.argtypes = [vp, C.POINTER(_Model), vp, ci, ci, ci, ci, vp, ip, C.POINTER(C.c_float), ip]
@@ -269,6 +275,19 @@ class Codes:
     def valid(self):
         return bool(self.c.valid)
 
+    def invalidate(self):
+        """To be called by whoever changes the vectors these codes belong to."""
+        self.c.valid = 0
+
+
+class RowCodes:
+    """q8_row_codes: every row of a table (the target embeddings) quantized on its own maximum, at pitch ld."""
+
+    def __init__(self, ctx, table, ld):
+        mat, self.scale = q8_quantize_matrix_rows(ctx, table, ld_out=ld)
+        self.q = mat.data
+        self.c = _RowCodes(self.q.data_ptr(), self.scale.data_ptr(), ld)
+
 
 class _Bound:
     """A call with its arguments already marshalled: launch() re-issues it on the same
@@ -400,7 +419,9 @@ def gru_step_q8(ctx, g, x, h_prev, h_out=None, taps=False):
 
 def cgru_decoder_step_q8(ctx, w, P, enc_h, y_emb, s_prev, out=None, taps=False, bind=False, codes=None):
     """Returns dict(s, ctx, alpha, s_mid) (+ 'taps': five entries).  codes = (y, ctx) Codes objects:
-    cgru_decoder_step_codes_q8, which also leaves the codes of y_emb and of the context vectors there."""
+    cgru_decoder_step_codes_q8, which also leaves the codes of y_emb and of the context vectors there;
+    codes = (y, ctx, s_prev): cgru_decoder_step_loop_q8, which also takes the codes of y_emb and s_prev
+    that output_logits_beam_q8(codes=(y, ctx, s_next), E_codes=...) left (valid == 2)."""
     n, l = y_emb.shape[0], P.shape[0]
     H, Cd = w.r.H, w.q.Wx.cols
     o = out or {}
@@ -421,8 +442,8 @@ def cgru_decoder_step_q8(ctx, w, P, enc_h, y_emb, s_prev, out=None, taps=False, 
         r["taps"] = ts.t
     fn = ctx.lib.cgru_decoder_step_q8
     if codes is not None:
-        fn = ctx.lib.cgru_decoder_step_codes_q8
-        args = args + (C.byref(codes[0].c), C.byref(codes[1].c))
+        fn = ctx.lib.cgru_decoder_step_codes_q8 if len(codes) == 2 else ctx.lib.cgru_decoder_step_loop_q8
+        args = args + tuple(C.byref(c.c) for c in codes)
     if bind:
         r["keep"] = (w, P, enc_h, y_emb, s_prev, codes)
         return _Bound(ctx, fn, args, r)
@@ -600,8 +621,11 @@ class Model:
         out_W = q8_quantize_matrix(ctx, p["out.W"], ld_out=(R + 63) // 64 * 64 if R >= 256 else None)
         if out_W.ld % 64 == 0:
             out_W = q8_pack_tiles(ctx, out_W)
-        return cls(ctx.f32(p["E_src"]), ctx.f32(p["E_tgt"]), gru("enc_fwd"), gru("enc_bwd"), mat("att.W"),
-                   ctx.f32(p["att.b"]), dec, ro, out_W, ctx.f32(p["out.b"]))
+        m = cls(ctx.f32(p["E_src"]), ctx.f32(p["E_tgt"]), gru("enc_fwd"), gru("enc_bwd"), mat("att.W"),
+                ctx.f32(p["att.b"]), dec, ro, out_W, ctx.f32(p["out.b"]))
+        # the target embeddings' codes, row by row, for decoding loops that hand codes from step to step
+        m.E_tgt_codes = RowCodes(ctx, m.E_tgt, dec.r.Wx.ld)
+        return m
 
 
 def source_ids(ids, V_src, device=None):
@@ -776,9 +800,12 @@ def q8_beam_result(ctx, state, max_steps):
     return np.array(out[:n.value], dtype=np.int32), np.float32(score.value), steps.value, bool(done.value)
 
 
-def output_logits_beam_q8(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, state, E_tgt, s_next, k=12, bind=False, codes=None):
+def output_logits_beam_q8(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, state, E_tgt, s_next, k=12, bind=False, codes=None,
+                          E_codes=None):
     """Output layer + top-k + beam update; returns dict(topk_logp, topk_idx).  codes = (y, ctx) Codes
-    objects filled by cgru_decoder_step_q8(codes=...): output_logits_beam_codes_q8."""
+    objects filled by cgru_decoder_step_q8(codes=...): output_logits_beam_codes_q8.  codes = (y, ctx,
+    s_next) with E_codes (RowCodes of E_tgt): output_logits_beam_loop_q8, which also leaves the codes
+    of the new y_emb and of s_next for the next decoder step."""
     n = s.shape[0]
     lp = ctx.empty(n, k)
     idx = ctx.empty(n, k, dtype=torch.int32)
@@ -786,11 +813,14 @@ def output_logits_beam_q8(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, state, E_tgt
             _ptr(state), _ptr(E_tgt), E_tgt.shape[1], _ptr(s_next), _ptr(lp), _ptr(idx))
     r = {"topk_logp": lp, "topk_idx": idx}
     fn = ctx.lib.output_logits_beam_q8
-    if codes is not None:
+    if codes is not None and len(codes) == 3:
+        fn = ctx.lib.output_logits_beam_loop_q8
+        args = args + tuple(C.byref(c.c) for c in codes) + (C.byref(E_codes.c) if E_codes is not None else None,)
+    elif codes is not None:
         fn = ctx.lib.output_logits_beam_codes_q8
         args = args + (C.byref(codes[0].c), C.byref(codes[1].c))
     if bind:
-        r["keep"] = (ro, W_out, b_out, s, y_emb, ctx_vec, state, E_tgt, s_next, codes)
+        r["keep"] = (ro, W_out, b_out, s, y_emb, ctx_vec, state, E_tgt, s_next, codes, E_codes)
         return _Bound(ctx, fn, args, r)
     ctx.check(fn(*args))
     return r

@@ -402,8 +402,21 @@ q8_status cgru_decoder_step_codes_q8(q8_ctx *ctx, const q8_cgru_weights *w, cons
                                      float *alpha_out, float *s_mid_out, const q8_taps *taps5, q8_codes *y_codes,
                                      q8_codes *ctx_codes)
 {
+    if (y_codes) y_codes->valid = 0;                           // (whatever they held is not taken as an input here)
+    return cgru_decoder_step_loop_q8(ctx, w, P, enc_h, l, y_emb, s_prev, n_beam, s_out, ctx_out, alpha_out, s_mid_out, taps5,
+                                     y_codes, ctx_codes, nullptr);
+}
+
+q8_status cgru_decoder_step_loop_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h, int l,
+                                    const float *y_emb, const float *s_prev, int n_beam, float *s_out, float *ctx_out,
+                                    float *alpha_out, float *s_mid_out, const q8_taps *taps5, q8_codes *y_codes,
+                                    q8_codes *ctx_codes, q8_codes *s_prev_codes)
+{
+    // codes that the search step left for this call: both inputs of GRU r or neither
+    const bool y_in = y_codes && y_codes->valid == 2, s_in = s_prev_codes && s_prev_codes->valid == 2;
     if (y_codes) y_codes->valid = 0;
     if (ctx_codes) ctx_codes->valid = 0;
+    if (s_prev_codes) s_prev_codes->valid = 0;
     if (!ctx) return Q8_ERR_NULL;
     if (!w) return q8_fail(ctx, Q8_ERR_NULL, "weights: NULL");
     TRY(check_gru(ctx, &w->r, "r"));
@@ -432,10 +445,15 @@ q8_status cgru_decoder_step_codes_q8(q8_ctx *ctx, const q8_cgru_weights *w, cons
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "cgru_decoder_step_q8: workspace too small");
     if (codes_usable(ctx_codes, w->q.Wx.ld)) { cq = ctx_codes->q; cqs = ctx_codes->scale; }    // the caller keeps them
     const bool y_out = codes_usable(y_codes, w->r.Wx.ld);
+    const bool given = y_in && s_in && y_out && codes_usable(s_prev_codes, w->r.Wh.ld) && !taps5;
 
     // Eq. 3: s' = r(y, s_prev)
     q8i_gru_desc dr = {&w->r, y_emb, E, s_prev, H, nullptr, 0, s_mid, H, taps5, nullptr, nullptr,
                        y_out ? y_codes->q : nullptr, y_out ? y_codes->scale : nullptr};
+    if (given) {
+        dr.xq_pre = y_codes->q; dr.xs_pre = y_codes->scale; dr.xq_out = nullptr; dr.xs_out = nullptr;
+        dr.hq_pre = s_prev_codes->q; dr.hs_pre = s_prev_codes->scale;
+    }
     TRY(q8i_gru(ctx, &dr, 1, n, Q8I_GRU_FULL));
     if (y_out) y_codes->valid = 1;
     // everything that depends on s' alone: u(s') of Eq. 6 and the recurrent half of GRU q
@@ -544,7 +562,7 @@ q8_status cgru_decoder_step_batch_codes_q8(q8_ctx *ctx, const q8_cgru_weights *w
 static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
                              const float *s, const float *y_emb, const float *ctx_vec, const float *t_in, int n_beam,
                              int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx, float *t_out,
-                             const q8_taps *taps4, const q8i_beam_desc *beam, const q8_codes *y_codes = nullptr,
+                             const q8_taps *taps4, q8i_beam_desc *beam, const q8_codes *y_codes = nullptr,
                              const q8_codes *ctx_codes = nullptr, const q8_codes *s_codes = nullptr)
 {
     if (!ctx) return Q8_ERR_NULL;
@@ -622,8 +640,20 @@ static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8
     }
     if (ro) {
         float *t = t_out ? t_out : cv.take<float>((size_t)n * R);
+        // the search step hands the codes of the surviving states on: the readout leaves those of s for it
+        int8_t *sq = nullptr;
+        float *ss = nullptr;
+        if (beam && beam->Eq) {
+            sq = cv.take<int8_t>((size_t)n * ro->W_s.ld);
+            ss = cv.take<float>(n);
+        }
         if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
-        TRY(q8i_readout(ctx, ro, s, y_emb, ctx_vec, n, t, taps4, y_codes, ctx_codes));
+        int exported = 0;
+        TRY(q8i_readout(ctx, ro, s, y_emb, ctx_vec, n, t, taps4, y_codes, ctx_codes, sq, ss, &exported));
+        if (beam && beam->Eq) {
+            if (exported) { beam->sq_in = sq; beam->ss_in = ss; }
+            else beam->Eq = nullptr;                               // (this readout kernel keeps its codes to itself)
+        }
         T = t;
     }
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
@@ -656,6 +686,22 @@ q8_status output_logits_beam_codes_q8(q8_ctx *ctx, const q8_readout_weights *ro,
                                       const float *E_tgt, int E, float *s_next, float *topk_logp, int32_t *topk_idx,
                                       const q8_codes *y_codes, const q8_codes *ctx_codes)
 {
+    q8_codes y = {nullptr, nullptr, 0, 0};
+    if (y_codes) y = *y_codes;
+    return output_logits_beam_loop_q8(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, n_beam, k, state, E_tgt, E, s_next, topk_logp,
+                                      topk_idx, y_codes ? &y : nullptr, ctx_codes, nullptr, nullptr);
+}
+
+q8_status output_logits_beam_loop_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                                     const float *s, float *y_emb, const float *ctx_vec, int n_beam, int k, void *state,
+                                     const float *E_tgt, int E, float *s_next, float *topk_logp, int32_t *topk_idx,
+                                     q8_codes *y_codes, const q8_codes *ctx_codes, q8_codes *s_next_codes,
+                                     const q8_row_codes *E_codes)
+{
+    // y_codes as an input: the codes of this step's y_emb for the readout (valid == 1)
+    q8_codes y_in = {nullptr, nullptr, 0, 0};
+    if (y_codes) { y_in = *y_codes; y_in.valid = y_codes->valid == 1; y_codes->valid = 0; }
+    if (s_next_codes) s_next_codes->valid = 0;
     if (!ctx) return Q8_ERR_NULL;
     if (!ro || !state || !E_tgt || !s_next || !s || !y_emb)
         return q8_fail(ctx, Q8_ERR_NULL, "output_logits_beam_q8: NULL argument");
@@ -664,8 +710,21 @@ q8_status output_logits_beam_codes_q8(q8_ctx *ctx, const q8_readout_weights *ro,
     if (!aligned16(E_tgt) || !aligned16(s_next)) return q8_fail(ctx, Q8_ERR_ALIGN, "fp32 buffers need 16-byte alignment");
     if (E != ro->W_y.cols) return q8_fail(ctx, Q8_ERR_SHAPE, "E does not match the readout's embedding width");
     q8i_beam_desc bd = {state, s, E_tgt, y_emb, s_next, E, ro->W_s.cols};
-    return output_impl(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, nullptr, n_beam, k, nullptr, nullptr, topk_logp,
-                       topk_idx, nullptr, nullptr, &bd, y_codes, ctx_codes);
+    // The codes of the rows that the search step gathers travel with them where everything fits: the table of
+    // embedding codes at the pitch of the matrices that multiply y (the readout's W_y here, GRU r's Wx in the next
+    // step), code buffers of the caller at those pitches, and a gather whose pass of 256 16-byte pieces has room.
+    const int H = ro->W_s.cols, ldy = ro->W_y.ld, lds = ro->W_s.ld;
+    const bool hand_on = E_codes && E_codes->q && E_codes->scale && E_codes->ld == ldy && aligned16(E_codes->q) &&
+                         codes_usable(y_codes, ldy) && codes_usable(s_next_codes, lds) && n_beam <= kMaxNarrow &&
+                         E % 4 == 0 && H % 4 == 0 && E / 4 + ldy / 16 + lds / 16 <= 256;
+    if (hand_on) {
+        bd.Eq = E_codes->q; bd.Es = E_codes->scale; bd.ldy = ldy; bd.lds = lds;
+        bd.yq_out = y_codes->q; bd.ys_out = y_codes->scale; bd.sq_out = s_next_codes->q; bd.ss_out = s_next_codes->scale;
+    }
+    const q8_status st = output_impl(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, nullptr, n_beam, k, nullptr, nullptr, topk_logp,
+                                     topk_idx, nullptr, nullptr, &bd, y_codes ? &y_in : nullptr, ctx_codes);
+    if (!st && hand_on && bd.Eq) { y_codes->valid = 2; s_next_codes->valid = 2; }
+    return st;
 }
 
 q8_status output_logits_beam_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,

@@ -28,6 +28,15 @@ struct BeamUpdateArgs {
     float *y_emb, *s_next;
     int n, k, E, H;
     int V;                  // rows of E_tgt when known (token ids are then kept inside the table), else 0
+    // Optional (all or none; E / 4 + ldy / 16 + lds / 16 <= 256): the codes of the gathered rows travel with
+    // them, so that the next decoder step need not quantize its inputs again.  Eq [V x ldy], Es [V]: every
+    // embedding row quantized on its own maximum; sq_in [n x lds], ss_in [n]: the codes of s_step as the readout
+    // quantized them.  Out: yq_out [n x ldy], ys_out [n] for y_emb; sq_out [n x lds], ss_out [n] for s_next.
+    const int8_t *Eq, *sq_in;
+    const float *Es, *ss_in;
+    int8_t *yq_out, *sq_out;
+    float *ys_out, *ss_out;
+    int ldy, lds;
 };
 
 // key: larger score first, then lower parent, then lower token id
@@ -168,23 +177,47 @@ __device__ __forceinline__ void beam_gather_rows(const BeamUpdateArgs &a, const 
 {
     const int tid = threadIdx.x;
     const int H4 = a.H >> 2, E4 = a.E >> 2;
-    const v4i *s4 = (const v4i *)a.s_step, *e4 = (const v4i *)a.E_tgt;
-    v4i *sn4 = (v4i *)a.s_next, *y4 = (v4i *)a.y_emb;
+    const v4i *s4 = (const v4i *)a.s_step;
+    v4i *sn4 = (v4i *)a.s_next;
+    // The embedding rows are shorter than a pass of 256 pieces; the threads past their end move the rows'
+    // codes instead (first pass only): pieces [E4, E4 + ldy / 16) of a "row" are the embedding row's codes,
+    // the next lds / 16 the codes of the parent's state.  Each thread has one source and one destination
+    // (base, pieces per row, piece) and, per row, the index its source is gathered by.
+    const int Y16 = a.Eq ? a.ldy >> 4 : 0, S16 = a.Eq ? a.lds >> 4 : 0;
+    const bool is_y = tid >= E4 && tid < E4 + Y16, is_s = tid >= E4 + Y16 && tid < E4 + Y16 + S16;
+    const v4i *src0 = is_y ? (const v4i *)a.Eq : is_s ? (const v4i *)a.sq_in : (const v4i *)a.E_tgt;
+    v4i *dst0 = is_y ? (v4i *)a.yq_out : is_s ? (v4i *)a.sq_out : (v4i *)a.y_emb;
+    const int pitch0 = is_y ? Y16 : is_s ? S16 : E4;
+    const int piece0 = is_y ? tid - E4 : is_s ? tid - E4 - Y16 : min(tid, E4 - 1);
+    // their scales: thread q & 7 of every wave fetches those of row q (the same words for all waves), thread q stores them
+    // (unconditional loads: without codes they read the first floats of the tables and drop them)
+    const int qs = min(tid & 7, a.n - 1);
+    const float ys = *(a.Eq ? a.Es + s_token[qs] : a.E_tgt), ss = *(a.Eq ? a.ss_in + s_parent[qs] : a.s_step);
     for (int c0 = 0; c0 < max(H4, E4); c0 += 256) {
-        const int ch = min(c0 + tid, H4 - 1), ce = min(c0 + tid, E4 - 1);
+        const int ch = min(c0 + tid, H4 - 1);
+        const bool first = c0 == 0;
+        const v4i *src = first ? src0 : (const v4i *)a.E_tgt;
+        v4i *dst = first ? dst0 : (v4i *)a.y_emb;
+        const int pitch = first ? pitch0 : E4, piece = first ? piece0 : min(c0 + tid, E4 - 1);
+        const bool by_parent = first && is_s;
         v4i vs[ROWS], ve[ROWS];
 #pragma unroll
         for (int q = 0; q < ROWS; ++q) {
             const int qq = min(q, a.n - 1);
-            vs[q] = s4[(size_t)s_parent[qq] * H4 + ch];
-            ve[q] = e4[(size_t)s_token[qq] * E4 + ce];
+            const int par = s_parent[qq], tok = s_token[qq];
+            vs[q] = s4[(size_t)par * H4 + ch];
+            ve[q] = src[(size_t)(by_parent ? par : tok) * pitch + piece];
         }
 #pragma unroll
         for (int q = 0; q < ROWS; ++q) {
             const int qq = min(q, a.n - 1);
             sn4[(size_t)qq * H4 + ch] = vs[q];
-            y4[(size_t)qq * E4 + ce] = ve[q];
+            dst[(size_t)qq * pitch + piece] = ve[q];
         }
+    }
+    if (a.Eq && tid < a.n) {
+        a.ys_out[tid] = ys;
+        a.ss_out[tid] = ss;
     }
 }
 

@@ -418,6 +418,10 @@ struct ReadoutArgs {
     // fast kernel with PRE: codes [n x ldy], [n x ldc] (pad bytes zero) and scales [n] of y and c from their producers
     const int8_t *yq_pre, *cq_pre;
     const float *ys_pre, *cs_pre;
+    // fast kernel, may be NULL: where block 0 leaves the codes [n x lds] and scales [n] of s (the search step hands
+    // the survivors' on to the next decoder step)
+    int8_t *sq_out;
+    float *ss_out;
 };
 
 template <int N>
@@ -550,6 +554,10 @@ __global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
         x_finish_multi<N, CH, 3>(rin, lds3, dst, s_scale, s_red);
     }
     if (blockIdx.x == 0) readout_x_taps<N>(a, sq, yq, cq, s_scale);
+    if (blockIdx.x == 0 && a.sq_out) {
+        for (int p = threadIdx.x; p < N * a.lds / 16; p += 256) *(v4i *)(a.sq_out + 16 * p) = *(const v4i *)(sq + 16 * p);
+        if (threadIdx.x < N) a.ss_out[threadIdx.x] = s_scale[threadIdx.x];
+    }
 
     // the three rows' partial sums against their vectors, totalled over the wave in one pass;
     // lane j < N receives the totals of hypothesis j
@@ -692,9 +700,11 @@ static void launch_readout_n(q8_ctx *ctx, const ReadoutArgs &a, int blocks, size
 }
 
 q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,
-                      float *t_out, const q8_taps *taps3, const q8_codes *y_codes, const q8_codes *c_codes)
+                      float *t_out, const q8_taps *taps3, const q8_codes *y_codes, const q8_codes *c_codes,
+                      int8_t *sq_out, float *ss_out, int *s_exported)
 {
     ReadoutArgs a;
+    if (s_exported) *s_exported = 0;
     // codes from the producers: both or neither, and only in the layout the kernel copies (the matrices' own pitches)
     const bool pre = y_codes && c_codes && y_codes->valid && c_codes->valid && y_codes->q && c_codes->q && y_codes->scale &&
                      c_codes->scale && y_codes->ld == ro->W_y.ld && c_codes->ld == ro->W_c.ld;
@@ -717,6 +727,9 @@ q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s,
     const int upb = ch ? 4 : 4 * (64 / a.lpr);
     const int blocks = (a.R + upb - 1) / upb;
     const size_t smem = (size_t)n * (a.lds + a.ldy + a.ldc);
+    const bool exporting = ch != 0 && sq_out && ss_out;             // (the general kernel does not export)
+    a.sq_out = exporting ? sq_out : nullptr; a.ss_out = ss_out;
+    if (s_exported) *s_exported = exporting ? 1 : 0;
     switch (n) {
     case 1: launch_readout_n<1>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
     case 2: launch_readout_n<2>(ctx, a, blocks, smem, ch, pre && ch != 0); break;

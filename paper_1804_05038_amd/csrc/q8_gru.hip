@@ -12,8 +12,10 @@ struct GruJob {
     const int8_t *Wx, *Wh;
     const float *bx, *bh;
     const float *x, *h_prev, *g_pre;
-    const int8_t *xq_pre;      // GH_PRE, kernels with XPRE: codes [N x ldwx] and scales [N] of x from its producer
+    const int8_t *xq_pre;      // kernels with XPRE: codes [N x ldwx] and scales [N] of x from its producer
     const float *xs_pre;
+    const int8_t *hq_pre;      // GRU_FULL kernels with XPRE: the same for h_prev, [N x ldwh]
+    const float *hs_pre;
     int8_t *xq_out;            // may be NULL: where block 0 leaves the codes [N x ldwx] and scales [N] of x for a later consumer
     float *xs_out;
     float *h_out;
@@ -154,12 +156,14 @@ __global__ __launch_bounds__(256) void gru_kernel(GruJobs jobs)
 
 // Rows of at most 1024 * CH bytes, I % 4 == 0, H % 4 == 0, one hidden unit per wave
 // (grid.x * 4 >= H).  Activations, the unit's six (or three) weight rows and the
-// epilogue's operands are all requested before the block first waits.  XPRE (with
-// GRU_GH_PRE): x arrives as codes and scales, which are copied to LDS instead of quantized.
+// epilogue's operands are all requested before the block first waits.  XPRE: the vectors
+// that are multiplied here arrive as codes and scales from whoever produced them (x with
+// GRU_GH_PRE; x and h_prev with GRU_FULL) and are copied to LDS instead of quantized.
 template <int N, int MODE, int CH, bool XPRE = false>
 __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
 {
-    static_assert(!XPRE || MODE == GRU_GH_PRE, "codes are taken for the input of GRU_GH_PRE only");
+    static_assert(!XPRE || MODE != GRU_GX_PRE, "codes are taken for x, or for x and h_prev");
+    constexpr bool HPRE = XPRE && MODE == GRU_FULL;
     extern __shared__ __align__(16) int8_t smem[];
     __shared__ float s_scale[16];
     __shared__ float s_red[2 * 8 * 4];
@@ -177,19 +181,27 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
     // XPRE: N * ldwx code bytes in 16-byte pieces, thread tid takes pieces tid, tid + 256, ...; a piece
     // past the end is read through the descriptor as zero, so the loads need no branch
     constexpr int NPRE = XPRE ? (N * CH * 64 + 255) / 256 : 1;
-    v4i pre_q[NPRE];
-    float pre_s = 0.0f;                      // XPRE: scale of vector tid, requested first so that it is not waited for behind the weights
+    v4i pre_q[NPRE], pre_hq[HPRE ? NPRE : 1];
+    float pre_s = 0.0f, pre_hs = 0.0f;       // XPRE: scales of vector tid, requested first so that they are not waited for behind the weights
     if (XPRE) {
-        pre_s = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-            q8_rsrc(J.xs_pre, (size_t)N * sizeof(float)), (int)(threadIdx.x < N ? threadIdx.x * 4u : Q8_OOB), 0, 0));
+        const int so = (int)(threadIdx.x < N ? threadIdx.x * 4u : Q8_OOB);
+        pre_s = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(q8_rsrc(J.xs_pre, (size_t)N * sizeof(float)), so, 0, 0));
+        if (HPRE)
+            pre_hs = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(q8_rsrc(J.hs_pre, (size_t)N * sizeof(float)), so, 0, 0));
         const __amdgpu_buffer_rsrc_t rq = q8_rsrc(J.xq_pre, (size_t)N * J.ldwx);
 #pragma unroll
         for (int t = 0; t < NPRE; ++t)
             pre_q[t] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rq, (t * 256 + (int)threadIdx.x) * 16, 0, 0));
+        if (HPRE) {
+            const __amdgpu_buffer_rsrc_t rhq = q8_rsrc(J.hq_pre, (size_t)N * J.ldwh);
+#pragma unroll
+            for (int t = 0; t < NPRE; ++t)
+                pre_hq[t] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rhq, (t * 256 + (int)threadIdx.x) * 16, 0, 0));
+        }
         __builtin_amdgcn_sched_barrier(0);
     }
     if (MODE != GRU_GX_PRE && !XPRE) x_load<N, CH>(xr, J.x, N, J.I, J.ldx);
-    if (MODE != GRU_GH_PRE) x_load<N, CH>(hr, J.h_prev, N, H, J.ldh);
+    if (MODE != GRU_GH_PRE && !HPRE) x_load<N, CH>(hr, J.h_prev, N, H, J.ldh);
     v4i wx[3][CH], wh[3][CH];
     {
         int row[3];
@@ -233,25 +245,29 @@ __global__ __launch_bounds__(256) void gru_fast_kernel(GruJobs jobs)
         }
     }
 
-    if (MODE == GRU_FULL) {
-        const int lds[2] = {J.ldwx, J.ldwh};
-        int8_t *const dst[2] = {xq, hq};
-        x_finish_multi<N, CH, 2>(xh, lds, dst, s_scale, s_red);
-    } else if (XPRE) {
+    if (XPRE) {
 #pragma unroll
         for (int t = 0; t < NPRE; ++t) {
             const int o = (t * 256 + (int)threadIdx.x) * 16;
             if (o < N * J.ldwx) *(v4i *)(xq + o) = pre_q[t];
+            if (HPRE && o < N * J.ldwh) *(v4i *)(hq + o) = pre_hq[t];
         }
-        if (threadIdx.x < N) s_scale[threadIdx.x] = pre_s;
+        if (threadIdx.x < N) {
+            s_scale[threadIdx.x] = pre_s;
+            if (HPRE) s_scale[8 + threadIdx.x] = pre_hs;
+        }
         __syncthreads();
+    } else if (MODE == GRU_FULL) {
+        const int lds[2] = {J.ldwx, J.ldwh};
+        int8_t *const dst[2] = {xq, hq};
+        x_finish_multi<N, CH, 2>(xh, lds, dst, s_scale, s_red);
     } else if (MODE == GRU_GH_PRE) {
         x_finish<N, CH>(xr, N, J.ldwx, xq, s_scale, s_red);
     } else {
         x_finish<N, CH>(hr, N, J.ldwh, hq, s_scale + 8, s_red);
     }
     if (blockIdx.x == 0) gru_x_taps<N, MODE>(J, xq, hq, s_scale);
-    if (blockIdx.x == 0 && MODE != GRU_GX_PRE) gru_x_export<N>(J, xq, s_scale);
+    if (blockIdx.x == 0 && MODE != GRU_GX_PRE && !XPRE) gru_x_export<N>(J, xq, s_scale);
 
     // partial sums of the unit's rows against every vector, totalled over the wave in one pass;
     // lane j < N receives the totals of vector j: [0, 3) input product, [3, 6) recurrent product
@@ -643,10 +659,10 @@ template <int N, int MODE>
 static void launch_gru_nm(q8_ctx *ctx, const GruJobs &jobs, int njobs, int blocks, size_t smem, int ch, bool xpre)
 {
     dim3 grid(blocks, njobs);
-    if constexpr (MODE == GRU_GH_PRE) {
+    if constexpr (MODE != GRU_GX_PRE) {
         if (xpre && (ch == 1 || ch == 2)) {
-            if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_GRU, (gru_fast_kernel<N, GRU_GH_PRE, 1, true>), grid, dim3(256), smem, jobs);
-            else Q8_LAUNCH(ctx, Q8_KERNEL_GRU, (gru_fast_kernel<N, GRU_GH_PRE, 2, true>), grid, dim3(256), smem, jobs);
+            if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_GRU, (gru_fast_kernel<N, MODE, 1, true>), grid, dim3(256), smem, jobs);
+            else Q8_LAUNCH(ctx, Q8_KERNEL_GRU, (gru_fast_kernel<N, MODE, 2, true>), grid, dim3(256), smem, jobs);
             return;
         }
     }
@@ -658,7 +674,7 @@ static void launch_gru_nm(q8_ctx *ctx, const GruJobs &jobs, int njobs, int block
 template <int N>
 static void launch_gru_n(q8_ctx *ctx, const GruJobs &jobs, int njobs, int mode, int blocks, size_t smem, int ch, bool xpre)
 {
-    if (mode == GRU_FULL) launch_gru_nm<N, GRU_FULL>(ctx, jobs, njobs, blocks, smem, ch, false);
+    if (mode == GRU_FULL) launch_gru_nm<N, GRU_FULL>(ctx, jobs, njobs, blocks, smem, ch, xpre);
     else if (mode == GRU_GX_PRE) launch_gru_nm<N, GRU_GX_PRE>(ctx, jobs, njobs, blocks, smem, ch, false);
     else launch_gru_nm<N, GRU_GH_PRE>(ctx, jobs, njobs, blocks, smem, ch, xpre);
 }
@@ -670,15 +686,18 @@ q8_status q8i_gru(q8_ctx *ctx, const q8i_gru_desc *d, int njobs, int n, int mode
     jobs.clear_words = d[0].clear ? d[0].clear_words : 0;
     size_t smem = 0;
     int max_ld = 0, maxH = 0;
-    bool fast = true, xpre = mode == GRU_GH_PRE;      // codes of x: only if every job brings them
+    // codes in place of the vectors that are multiplied here (x; with both products also h_prev): only if every job brings them
+    bool fast = true, xpre = mode != GRU_GX_PRE;
     for (int t = 0; t < njobs; ++t) {
         GruJob &J = jobs.j[t];
         const q8_gru_weights *g = d[t].g;
         J.Wx = g->Wx.data; J.Wh = g->Wh.data; J.bx = g->bx; J.bh = g->bh;
         J.x = d[t].x; J.h_prev = d[t].h_prev; J.g_pre = d[t].g_pre; J.h_out = d[t].h_out;
         J.xq_pre = d[t].xq_pre; J.xs_pre = d[t].xs_pre;
+        J.hq_pre = d[t].hq_pre; J.hs_pre = d[t].hs_pre;
         J.xq_out = d[t].xs_out ? d[t].xq_out : nullptr; J.xs_out = d[t].xs_out;
         if (!J.xq_pre || !J.xs_pre) xpre = false;
+        if (mode == GRU_FULL && (!J.hq_pre || !J.hs_pre)) xpre = false;
         q8_taps none = {nullptr, nullptr, nullptr};
         J.tx = d[t].taps ? d[t].taps[0] : none;
         J.th = d[t].taps ? d[t].taps[1] : none;

@@ -99,7 +99,8 @@ struct q8i_gru_desc {
     const float *g_pre;  int ldg;
     float *h_out;        int ldo;
     const q8_taps *taps; // NULL or [2]
-    // GH_PRE only, may be NULL: codes [n x Wx.ld] (pad bytes zero) and scales [n] of x, left by its producer
+    // may be NULL: codes [n x Wx.ld] (pad bytes zero) and scales [n] of x, left by its producer: used with
+    // GH_PRE, and with FULL if hq_pre / hs_pre (the same for h_prev, [n x Wh.ld]) are there too
     const int8_t *xq_pre;
     const float *xs_pre;
     // not GX_PRE, may be NULL: where the codes [n x Wx.ld] and scales [n] of x are left for a later consumer
@@ -108,6 +109,8 @@ struct q8i_gru_desc {
     // of the first job, may be NULL: 8-byte words the kernel zeroes on its way out
     unsigned long long *clear;
     int clear_words;
+    const int8_t *hq_pre;
+    const float *hs_pre;
 };
 
 // beam update run by the last block of the selection kernel (NULL = none)
@@ -116,6 +119,12 @@ struct q8i_beam_desc {
     const float *s_step, *E_tgt;
     float *y_emb, *s_next;
     int E, H;
+    // optional, all or none: the codes of the gathered rows travel with them (see BeamUpdateArgs)
+    const int8_t *Eq, *sq_in;
+    const float *Es, *ss_in;
+    int8_t *yq_out, *sq_out;
+    float *ys_out, *ss_out;
+    int ldy, lds;
 };
 
 enum { Q8I_GRU_FULL = 0, Q8I_GRU_GX_PRE = 1, Q8I_GRU_GH_PRE = 2 };
@@ -191,7 +200,8 @@ q8_status q8i_beam_read_batch(q8_ctx *ctx, const void *states, size_t stride, in
 // y_codes / c_codes (may be NULL): codes of y and c left by their producers; used when both are valid and laid out
 // with the pitches of W_y and W_c
 q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,
-                      float *t_out, const q8_taps *taps3, const q8_codes *y_codes = nullptr, const q8_codes *c_codes = nullptr);
+                      float *t_out, const q8_taps *taps3, const q8_codes *y_codes = nullptr, const q8_codes *c_codes = nullptr,
+                      int8_t *sq_out = nullptr, float *ss_out = nullptr, int *s_exported = nullptr);
 q8_status q8i_probe_read(q8_ctx *ctx, const void *buf, size_t bytes);
 q8_status q8i_math_eval(q8_ctx *ctx, int fn, const void *x, void *y, size_t n);
 int q8i_out_tiles(int V);

@@ -938,6 +938,11 @@ static q8_status launch_select(q8_ctx *ctx, const float *part_max, const double 
     if (beam) {
         BeamUpdateArgs bu = {(BeamState *)beam->state, topk_logp, topk_idx, beam->s_step, beam->E_tgt, beam->y_emb,
                              beam->s_next, n, k, beam->E, beam->H, V};
+        if (beam->Eq) {
+            bu.Eq = beam->Eq; bu.Es = beam->Es; bu.sq_in = beam->sq_in; bu.ss_in = beam->ss_in;
+            bu.yq_out = beam->yq_out; bu.ys_out = beam->ys_out; bu.sq_out = beam->sq_out; bu.ss_out = beam->ss_out;
+            bu.ldy = beam->ldy; bu.lds = beam->lds;
+        }
         s.bu = bu;
     } else {
         memset(&s.bu, 0, sizeof(s.bu));

@@ -248,6 +248,65 @@ def test_fused_tail_equals_separate_calls_and_graph_replays(q, ctx, oracle):
         torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("dims", [dict(V=50000, E=512, H=1024, A=1024, R=512), dict(V=500, E=64, H=128, A=64, R=64),
+                                  dict(V=700, E=620, H=1000, A=1000, R=620), dict(V=300, E=36, H=40, A=28, R=24)])
+@pytest.mark.parametrize("n", [5, 1, 8])
+def test_codes_handed_from_the_search_step_to_the_next_decoder_step(q, ctx, oracle, dims, n):
+    """A decoding loop in which the search step gathers the codes of the rows it gathers (embedding rows
+    quantized once, the readout's codes of the surviving states) and GRU r of the next step takes them
+    (Eq. 3, Section 3: a vector's codes depend on the vector alone) against the loop that quantizes
+    again: every state, context vector, top-k table, gathered row and code buffer bit for bit, step by
+    step.  At 620 / 1000 the gather has no room for the codes and the loop quantizes as before."""
+    T = 7
+    p = synth.full_model(seed=31, **dims, **(dict(w_std=0.2, b_std=0.1) if dims["V"] < 1000 else {}))
+    m = q.Model.from_params(ctx, p)
+    E, H = dims["E"], dims["H"]
+    rng = np.random.default_rng(5)
+    enc_h = ctx.f32(rng.standard_normal((11, 2 * H)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    s0 = ctx.f32(rng.standard_normal(H).astype(np.float32))
+
+    def loop(hand_on):
+        state = torch.zeros(q.q8_beam_state_bytes(T), dtype=torch.uint8, device=ctx.device)
+        y, s = ctx.empty(n, E), ctx.empty(n, H)
+        codes = [q.Codes(ctx, n, m.dec.r.Wx.ld), q.Codes(ctx, n, m.dec.q.Wx.ld)]
+        if hand_on:
+            codes.append(q.Codes(ctx, n, m.dec.r.Wh.ld))
+        q.q8_beam_init(ctx, state, n, T, s0, m.E_tgt, y, s)
+        trace, used = [], 0
+        for _ in range(T):
+            given = hand_on and codes[0].c.valid == 2 and codes[2].c.valid == 2
+            used += bool(given)
+            if given:          # what GRU r is about to take: the codes of y and s as they are now
+                trace += [np_(codes[0].q), np_(codes[0].scale), np_(codes[2].q), np_(codes[2].scale)]
+            r = q.cgru_decoder_step_q8(ctx, m.dec, P, enc_h, y, s, codes=codes)
+            o = q.output_logits_beam_q8(ctx, m.ro, m.W_out, m.b_out, r["s"], y, r["ctx"], state, m.E_tgt, s, k=12,
+                                        codes=codes, E_codes=m.E_tgt_codes if hand_on else None)
+            trace += [np_(r[k]) for k in ("s", "ctx", "alpha", "s_mid")] + [np_(o["topk_logp"]), np_(o["topk_idx"]), np_(y), np_(s)]
+        return trace, used, q.q8_beam_result(ctx, state, T)
+
+    ref, _, ref_res = loop(False)
+    got, used, got_res = loop(True)
+    fits = E // 4 + m.dec.r.Wx.ld // 16 + m.dec.r.Wh.ld // 16 <= 256
+    assert used == (T - 1 if fits else 0)
+    # the code buffers in `got` have no counterpart in `ref`: check them against the oracle's quantization of the rows
+    gi = iter(got)
+    for step in range(T):
+        if fits and step > 0:
+            yq, ys, sq, ss = next(gi), next(gi), next(gi), next(gi)
+            y_rows, s_rows = ref[8 * (step - 1) + 6], ref[8 * (step - 1) + 7]
+            for j in range(n):
+                cq, cs = oracle.quantize(y_rows[j])
+                assert_same(yq[j, :E], cq, "codes of y"); assert_same(ys[j:j + 1], np.array([cs], np.float32), "scale of y")
+                assert not yq[j, E:].any()
+                cq, cs = oracle.quantize(s_rows[j])
+                assert_same(sq[j, :H], cq, "codes of s"); assert_same(ss[j:j + 1], np.array([cs], np.float32), "scale of s")
+                assert not sq[j, H:].any()
+        for i in range(8):
+            assert_same(next(gi), ref[8 * step + i], "step %d, output %d" % (step, i))
+    assert got_res[0].tolist() == ref_res[0].tolist() and got_res[1:] == ref_res[1:]
+
+
 def test_search_step_wait_that_gives_up_is_reported_and_the_next_search_is_good(q, ctx, oracle):
     """With a bound of one poll the block that runs the search step inside the selection kernel may
     stop waiting for the other hypotheses' k best: the kernel still ends normally, q8_encode_check
