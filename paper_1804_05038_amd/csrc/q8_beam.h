@@ -47,15 +47,31 @@ __device__ __forceinline__ unsigned long long cand_key(float score, int parent, 
     return ((unsigned long long)u << 32) | ((unsigned)(15 - parent) << 20) | (unsigned)(0xFFFFF - token);
 }
 
+// What a search step reads of the state before it decides (lane q & 7 holds the score of slot q).
+struct BeamStateRead {
+    float sc_slot, fin_score;
+    int n_live, b_live, step, max_steps, done, have_fin;
+};
+__device__ __forceinline__ BeamStateRead beam_state_read(const BeamState *st, int lane)
+{
+    BeamStateRead r;
+    r.sc_slot = st->score[lane & (Q8_MAX_BEAM - 1)];
+    r.n_live = st->n_live; r.b_live = st->b_live; r.step = st->step; r.max_steps = st->max_steps;
+    r.done = st->done; r.have_fin = st->have_fin; r.fin_score = st->fin_score;
+    return r;
+}
+
 __device__ __forceinline__ void beam_gather(const BeamUpdateArgs &a, const int *s_parent, const int *s_token);
 template <bool GIVEN>
-__device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a, const float (&lp_in)[2], const int (&tk_in)[2]);
+__device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a, const float (&lp_in)[2], const int (&tk_in)[2],
+                                                 const BeamStateRead &pre);
 // The tables as they lie in memory (written by an earlier kernel).
 __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
 {
     const float no_lp[2] = {0.0f, 0.0f};
     const int no_tk[2] = {0, 0};
-    beam_update_body<false>(a, no_lp, no_tk);
+    const BeamStateRead none = {};
+    beam_update_body<false>(a, no_lp, no_tk, none);
 }
 
 // One block of at least 64 threads.  The decisions of a search step are taken by the block's first
@@ -65,10 +81,12 @@ __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a)
 // slot, the number of hypotheses that ended and the best of them; lane q then writes slot q of the
 // state.  Only then does the block meet, and all threads gather the surviving decoder states and the
 // embeddings of the new tokens.  GIVEN: lanes of the first wave bring their two candidates (entries
-// lane and lane + 64 of the top-k tables, the last entry repeated past the end) in lp_in / tk_in,
-// and the tables are not read.
+// lane and lane + 64 of the top-k tables, the last entry repeated past the end) in lp_in / tk_in
+// and what beam_state_read returned (requested while they waited for the candidates), and
+// neither the tables nor the state are read here.
 template <bool GIVEN>
-__device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a, const float (&lp_in)[2], const int (&tk_in)[2])
+__device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a, const float (&lp_in)[2], const int (&tk_in)[2],
+                                                 const BeamStateRead &pre)
 {
     __shared__ int s_parent[Q8_MAX_BEAM], s_token[Q8_MAX_BEAM];
     __shared__ int s_skip;
@@ -86,11 +104,12 @@ __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a, const 
             lp[u] = GIVEN ? lp_in[u] : a.topk_logp[c];
             tk[u] = GIVEN ? tk_in[u] : a.topk_idx[c];
         }
-        const float sc_slot = st->score[lane & (Q8_MAX_BEAM - 1)];      // lane q < 8: score of slot q
-        const int n_live = st->n_live, b_live = st->b_live, step = st->step, max_steps = st->max_steps;
-        const bool skip = st->done != 0;
-        const int have_fin0 = st->have_fin;
-        const float fin_score0 = st->fin_score;
+        const BeamStateRead sr = GIVEN ? pre : beam_state_read(st, lane);
+        const float sc_slot = sr.sc_slot;                                // lane q < 8: score of slot q
+        const int n_live = sr.n_live, b_live = sr.b_live, step = sr.step, max_steps = sr.max_steps;
+        const bool skip = sr.done != 0;
+        const int have_fin0 = sr.have_fin;
+        const float fin_score0 = sr.fin_score;
         const int ncand = skip ? 0 : n_live * a.k;
         const int take = min(b_live, ncand);
         // candidate c = parent * k + rank in the parent's list; parent = floor((c + 0.5) / k) in float

@@ -597,7 +597,9 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     // ---- block 0 continues with the search step once all n k entries are there
     float lp[2] = {0.0f, 0.0f};
     int tk[2] = {0, 0};
+    BeamStateRead sr = {};
     if (tid < 64) {
+        sr = beam_state_read(a.bu.st, lane);       // (on its way while the candidates are waited for)
         const int nk = n * k;                      // at most 128
         const int c0 = min(lane, nk - 1), c1 = min(lane + 64, nk - 1);
         unsigned long long x0 = 0ull, x1 = 0ull;
@@ -614,7 +616,7 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
         if (lane < nk) a.xw[lane] = 0ull;
         if (lane + 64 < nk) a.xw[lane + 64] = 0ull;
     }
-    beam_update_body<true>(a.bu, lp, tk);
+    beam_update_body<true>(a.bu, lp, tk, sr);
 }
 
 // ========================================== selection for panels, logits recomputed ==
