@@ -427,6 +427,8 @@ typedef struct {
     q8_readout_weights ro;           /* Eq. 2, first layer */
     q8_mat W_out;                    /* Eq. 2, second layer [V_tgt x R] */
     const float *b_out;
+    q8_row_codes E_tgt_codes;        /* optional (q == NULL: none): E_tgt row by row at pitch dec.r.Wx.ld; q8_translate
+                                        then hands codes from the search step to the next decoder step */
 } q8_model;
 
 /* Workspace bytes that q8_translate needs on top of q8_workspace_bytes(beam, max_l, ...). */

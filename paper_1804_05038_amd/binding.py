@@ -63,7 +63,7 @@ class _Readout(C.Structure):
 class _Model(C.Structure):
     _fields_ = [("E_src", C.c_void_p), ("E_tgt", C.c_void_p), ("V_src", C.c_int), ("V_tgt", C.c_int), ("E", C.c_int),
                 ("enc_fwd", _Gru), ("enc_bwd", _Gru), ("att_W", _Mat), ("att_b", C.c_void_p),
-                ("dec", _Cgru), ("ro", _Readout), ("W_out", _Mat), ("b_out", C.c_void_p)]
+                ("dec", _Cgru), ("ro", _Readout), ("W_out", _Mat), ("b_out", C.c_void_p), ("E_tgt_codes", _RowCodes)]
 
 
 _lib = None
@@ -625,6 +625,7 @@ class Model:
                 ctx.f32(p["att.b"]), dec, ro, out_W, ctx.f32(p["out.b"]))
         # the target embeddings' codes, row by row, for decoding loops that hand codes from step to step
         m.E_tgt_codes = RowCodes(ctx, m.E_tgt, dec.r.Wx.ld)
+        m.c.E_tgt_codes = m.E_tgt_codes.c
         return m
 
 

@@ -927,7 +927,7 @@ q8_status q8_beam_result(q8_ctx *ctx, const void *state, int max_steps, int32_t 
 
 namespace {
 struct TranslateBufs {
-    size_t X, enc_h, P, y, s0, s1, cv, lp, idx, tok, state, yq, ys, cq, cs, total;
+    size_t X, enc_h, P, y, s0, s1, cv, lp, idx, tok, state, yq, ys, cq, cs, sq, ss, total;
 };
 TranslateBufs translate_layout(const q8_model *m, int l, int beam, int k, int max_steps)
 {
@@ -943,6 +943,8 @@ TranslateBufs translate_layout(const q8_model *m, int l, int beam, int k, int ma
     // codes of y and of the context vectors, handed from the decoder step to the output layer
     b.yq = take((size_t)beam * m->dec.r.Wx.ld); b.ys = take((size_t)beam * 4);
     b.cq = take((size_t)beam * m->dec.q.Wx.ld); b.cs = take((size_t)beam * 4);
+    // codes of the surviving states, handed from the search step to the next decoder step
+    b.sq = take((size_t)beam * m->dec.r.Wh.ld); b.ss = take((size_t)beam * 4);
     b.total = o;
     return b;
 }
@@ -984,6 +986,8 @@ q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens
     void *state = top + b.state;
     q8_codes yc = {(int8_t *)(top + b.yq), (float *)(top + b.ys), m->dec.r.Wx.ld, 0};
     q8_codes cc = {(int8_t *)(top + b.cq), (float *)(top + b.cs), m->dec.q.Wx.ld, 0};
+    q8_codes sc = {(int8_t *)(top + b.sq), (float *)(top + b.ss), m->dec.r.Wh.ld, 0};
+    const q8_row_codes *Ec = m->E_tgt_codes.q ? &m->E_tgt_codes : nullptr;
     ctx->ws_reserved_top = ctx->ws_bytes - (size_t)(top - ctx->ws);
 
     q8_status st = q8i_gather_rows(ctx, m->E_src, src_tokens, l, E, m->V_src, X);                        // x_i of Eq. 1
@@ -993,12 +997,13 @@ q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens
     if (!st) st = q8i_beam_init(ctx, state, beam, max_steps, enc_h, m->E_tgt, E, H, y, s[0]);
     int cur = 0, done = 0;
     for (int t = 0; t < max_steps && !st && !done; ++t) {
-        st = cgru_decoder_step_codes_q8(ctx, &m->dec, P, enc_h, l, y, s[cur], beam, s[cur ^ 1], cv, nullptr, nullptr, nullptr,
-                                        &yc, &cc);
-        // output layer, top-k and (in the selection kernel's last block) the beam update, which
-        // gathers the surviving states from s[cur ^ 1] into s[cur] and the new embeddings into y
-        if (!st) st = output_logits_beam_codes_q8(ctx, &m->ro, &m->W_out, m->b_out, s[cur ^ 1], y, cv, beam, k, state,
-                                                  m->E_tgt, E, s[cur], lp, idx, &yc, &cc);
+        st = cgru_decoder_step_loop_q8(ctx, &m->dec, P, enc_h, l, y, s[cur], beam, s[cur ^ 1], cv, nullptr, nullptr, nullptr,
+                                       &yc, &cc, &sc);
+        // output layer, top-k and (in block 0 of the selection kernel) the beam update, which gathers the
+        // surviving states from s[cur ^ 1] into s[cur] and the new embeddings into y, with their codes
+        // where the model brings its embeddings' codes
+        if (!st) st = output_logits_beam_loop_q8(ctx, &m->ro, &m->W_out, m->b_out, s[cur ^ 1], y, cv, beam, k, state,
+                                                 m->E_tgt, E, s[cur], lp, idx, &yc, &cc, &sc, Ec);
         if (!st && (t % 8 == 7))
             st = q8i_beam_read(ctx, state, max_steps, nullptr, nullptr, nullptr, nullptr, &done);
     }

@@ -195,7 +195,7 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(AttArgs a)
 // every wait is bounded, a wait that gives up sets *wait_err and the block goes on with what it has
 // (finite values, wrong result).  Measured and not kept: a pause before the first poll (it helped
 // while the column sums were slower, 0.3 us, and does nothing now), requesting the slice before
-// the energies (the first barrier then waits for those loads), a departure count with the last
+// the energies (they are then published 0.3 us later), a departure count with the last
 // block clearing the words (+ 1.2 us at the kernel's end).
 #define ATTS_L 128            // source positions at most
 static_assert(2 * ATTS_L * 8 == Q8_WS_ATT_XCHG_PER_HYP, "energies and maxima of a hypothesis fill its part of the header");
@@ -238,8 +238,9 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_split_kernel(AttArgs a)
     if (lane == 0) s_red[wave] = acc;
     __syncthreads();
     // This block's slice of the encoder states: entry e = t ppb + q is position t, column pair i ppb + q.
-    // Requested after the barrier (a barrier waits for the loads in flight) and, in the wave that
-    // publishes, after the energy is on its way; needed when the weights are known.
+    // Requested after the energy's barrier and, in the wave that publishes, after the energy is on its
+    // way (the requests' address arithmetic ahead of the energy delayed it by 0.3 us); needed when the
+    // weights are known.
     float2 hv[ATTS_SLICE_LOADS];
     int tv[ATTS_SLICE_LOADS];
     auto slice_request = [&]() {

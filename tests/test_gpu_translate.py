@@ -307,6 +307,23 @@ def test_codes_handed_from_the_search_step_to_the_next_decoder_step(q, ctx, orac
     assert got_res[0].tolist() == ref_res[0].tolist() and got_res[1:] == ref_res[1:]
 
 
+def test_translate_with_and_without_the_embedding_codes(q, ctx, oracle):
+    """q8_translate hands codes from the search step to the next decoder step when the model brings its
+    embeddings' codes; without them it quantizes in every step.  Same tokens, score bits and step count."""
+    p = synth.full_model(seed=33, V=900, E=64, H=128, A=64, R=64, w_std=0.2, b_std=0.1)
+    m = q.Model.from_params(ctx, p)
+    srcs = synth.sentences(seed=8, n=4, V=900, min_len=3, max_len=12)
+    with_codes = [q.q8_translate(ctx, m, src, beam=5, k=8, max_steps=20) for src in srcs]
+    keep = m.c.E_tgt_codes
+    m.c.E_tgt_codes = type(keep)()
+    try:
+        without = [q.q8_translate(ctx, m, src, beam=5, k=8, max_steps=20) for src in srcs]
+    finally:
+        m.c.E_tgt_codes = keep
+    for a, b in zip(with_codes, without):
+        assert a[0].tolist() == b[0].tolist() and np.float32(a[1]).tobytes() == np.float32(b[1]).tobytes() and a[2] == b[2]
+
+
 def test_search_step_wait_that_gives_up_is_reported_and_the_next_search_is_good(q, ctx, oracle):
     """With a bound of one poll the block that runs the search step inside the selection kernel may
     stop waiting for the other hypotheses' k best: the kernel still ends normally, q8_encode_check
