@@ -370,19 +370,26 @@ def batched_decoding(torch, q, m, rng, steps, sizes=(16, 64, 200), translate=Tru
         y, s = ctx.empty(n, 512), ctx.empty(n, 1024)
         done = torch.zeros(S, dtype=torch.int32, device=ctx.device)
         c0 = q.q8_beam_init_batch(ctx, states, S, BEAM, MAX_STEPS, enc_h, off, m.E_tgt, y, s, done, bind=True)
-        # codes of y, of the context vectors and of the new states travel from the step to the output layer
+        # codes of y, of the context vectors and of the new states travel from the step to the output layer, and
+        # those of the rows the search step gathers to the next step (which then has no quantization launch)
         codes = None if os.environ.get("Q8_BENCH_NO_CODES") else (
             q.Codes(ctx, n, m.dec.r.Wx.ld), q.Codes(ctx, n, m.dec.q.Wx.ld), q.Codes(ctx, n, m.ro.W_s.ld))
-        c1 = q.cgru_decoder_step_batch_q8(ctx, m.dec, P, enc_h, off, BEAM, L, y, s, bind=True, codes=codes)
+        hand_on = codes is not None and not os.environ.get("Q8_BENCH_NO_HANDOVER")
+        sp = q.Codes(ctx, n, m.dec.r.Wh.ld) if hand_on else None
+        c1 = q.cgru_decoder_step_batch_q8(ctx, m.dec, P, enc_h, off, BEAM, L, y, s, bind=True,
+                                          codes=codes + (sp,) if hand_on else codes)
         c2 = q.output_logits_q8(ctx, m.ro, m.W_out, m.b_out, s=c1.out["s"], y_emb=y, ctx_vec=c1.out["ctx"], k=TOPK,
                                 want_logits=False, bind=True, codes=codes)
         c3 = q.q8_beam_update_batch(ctx, states, S, BEAM, MAX_STEPS, c2.out["topk_logp"], c2.out["topk_idx"],
-                                    c1.out["s"], m.E_tgt, y, s, done, bind=True)
+                                    c1.out["s"], m.E_tgt, y, s, done, bind=True,
+                                    codes=(codes[2], codes[0], sp) if hand_on else None, E_codes=m.E_tgt_codes if hand_on else None)
         t = [0]
 
         def step():
             if t[0] % MAX_STEPS == 0:
                 c0.launch()
+                if hand_on:                         # (a new search: y and s are not what the codes were made of)
+                    codes[0].invalidate(); sp.invalidate()
             t[0] += 1
             c1.launch(); c2.launch(); c3.launch()
         per = time_loop(torch, step, steps, max(steps // 10, 10))

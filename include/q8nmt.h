@@ -410,6 +410,24 @@ q8_status output_logits_codes_q8(q8_ctx *ctx, const q8_readout_weights *ro, cons
                                  float *logits, float *lse, float *topk_logp, int32_t *topk_idx, float *t_out,
                                  const q8_codes *s_codes, const q8_codes *y_codes, const q8_codes *ctx_codes);
 
+/* The loop forms for panels (see cgru_decoder_step_loop_q8): q8_beam_update_batch_loop is q8_beam_update_batch
+ * with the height V of E_tgt (token ids are kept inside it) and, given E_codes, the codes s_codes of s_step
+ * (valid == 1, as cgru_decoder_step_batch_codes_q8 left them) and y_next_codes / s_next_codes with the pitches of
+ * E_codes and s_codes (s_next_codes not the buffers of s_codes), it leaves the codes of the new y_emb and of s_next
+ * there with valid = 2 (where E / 4 + E_codes->ld / 16 + s_codes->ld / 16 <= 256; otherwise valid = 0).
+ * cgru_decoder_step_batch_loop_q8 is cgru_decoder_step_batch_codes_q8 and takes y_codes and s_prev_codes with
+ * valid == 2 (pitches r.Wx.ld, r.Wh.ld) in place of quantizing y_emb and s_prev.  Bit-identical results. */
+q8_status cgru_decoder_step_batch_loop_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h,
+                                          const int32_t *sent_off, int n_sent, int beam, int max_l,
+                                          const float *y_emb, const float *s_prev, float *s_out, float *ctx_out,
+                                          float *alpha_out, float *s_mid_out, q8_codes *y_codes,
+                                          q8_codes *ctx_codes, q8_codes *s_codes, q8_codes *s_prev_codes);
+q8_status q8_beam_update_batch_loop(q8_ctx *ctx, void *states, int n_sent, int beam, int k, int max_steps,
+                                    const float *topk_logp, const int32_t *topk_idx, const float *s_step, int H,
+                                    const float *E_tgt, int E, int V, float *y_emb, float *s_next, int32_t *done,
+                                    const q8_row_codes *E_codes, const q8_codes *s_codes, q8_codes *y_next_codes,
+                                    q8_codes *s_next_codes);
+
 /* Waits for the stream and copies the result to the host: tokens (without the final
  * token 0), their number, the cumulative log-probability, the steps made, and whether
  * the search is over.  Host pointers; any may be NULL. */

@@ -126,6 +126,7 @@ def load_library():
         lib.q8_math_eval.argtypes = [vp, ci, vp, vp, C.c_size_t]
         lib.cgru_decoder_step_batch_q8.argtypes = [vp, C.POINTER(_Cgru), vp, vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp]
         lib.cgru_decoder_step_batch_codes_q8.argtypes = lib.cgru_decoder_step_batch_q8.argtypes + [C.POINTER(_Codes)] * 3
+        lib.cgru_decoder_step_batch_loop_q8.argtypes = lib.cgru_decoder_step_batch_q8.argtypes + [C.POINTER(_Codes)] * 4
         lib.output_logits_codes_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, ci, ci,
                                                vp, vp, vp, vp, vp] + [C.POINTER(_Codes)] * 3
         lib.q8_gemv_f32.argtypes = [vp, C.POINTER(_MatF), vp, ci, ci, vp, vp, ci]
@@ -139,6 +140,8 @@ def load_library():
         lib.q8_encode_batch.argtypes = [vp, C.POINTER(_Gru), C.POINTER(_Gru), vp, vp, ip, ci, vp]
         lib.q8_beam_init_batch.argtypes = [vp, vp, ci, ci, ci, vp, vp, ci, vp, ci, ci, vp, vp, vp]
         lib.q8_beam_update_batch.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, ci, vp, ci, vp, vp, vp]
+        lib.q8_beam_update_batch_loop.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, ci, vp, ci, ci, vp, vp, vp,
+                                                  C.POINTER(_RowCodes), C.POINTER(_Codes), C.POINTER(_Codes), C.POINTER(_Codes)]
         lib.q8_beam_result_batch.argtypes = [vp, vp, ci, ci, vp, ip, C.POINTER(C.c_float), ip]
         lib.q8_translate_batch_bytes.restype = C.c_size_t
         lib.q8_translate_batch_bytes.argtypes = [C.POINTER(_Model), ci, ci, ci, ci, ci]
@@ -471,7 +474,9 @@ def cgru_decoder_step_noalloc_q8(ctx, w, P, enc_h, y_emb, s_prev, out):
 def cgru_decoder_step_batch_q8(ctx, w, P, enc_h, sent_off, beam, max_l, y_emb, s_prev, out=None, bind=False, codes=None):
     """Decoder step for len(sent_off) - 1 sentences side by side; sent_off: device int32 offsets
     into P / enc_h.  Returns dict(s, ctx, alpha [n x max_l], s_mid).  codes = (y, ctx, s) Codes objects:
-    cgru_decoder_step_batch_codes_q8, which leaves the three sets of codes there."""
+    cgru_decoder_step_batch_codes_q8, which leaves the three sets of codes there; codes = (y, ctx, s, s_prev):
+    cgru_decoder_step_batch_loop_q8, which also takes the codes of y_emb and s_prev that
+    q8_beam_update_batch(codes=..., E_codes=...) left."""
     n = y_emb.shape[0]
     S = sent_off.shape[0] - 1
     assert n == S * beam
@@ -486,7 +491,7 @@ def cgru_decoder_step_batch_q8(ctx, w, P, enc_h, sent_off, beam, max_l, y_emb, s
     r = {"s": s_out, "ctx": c_out, "alpha": alpha, "s_mid": s_mid}
     fn = ctx.lib.cgru_decoder_step_batch_q8
     if codes is not None:
-        fn = ctx.lib.cgru_decoder_step_batch_codes_q8
+        fn = ctx.lib.cgru_decoder_step_batch_codes_q8 if len(codes) == 3 else ctx.lib.cgru_decoder_step_batch_loop_q8
         args = args + tuple(C.byref(c.c) for c in codes)
     if bind:
         r["keep"] = (w, P, enc_h, sent_off, y_emb, s_prev, codes)
@@ -752,14 +757,21 @@ def q8_beam_init_batch(ctx, states, n_sent, beam, max_steps, enc_h, sent_off, E_
 
 
 def q8_beam_update_batch(ctx, states, n_sent, beam, max_steps, topk_logp, topk_idx, s_step, E_tgt, y_emb, s_next, done,
-                         bind=False):
+                         bind=False, codes=None, E_codes=None):
+    """codes = (s, y_next, s_next) Codes objects with E_codes (RowCodes of E_tgt): q8_beam_update_batch_loop, which
+    gathers the codes of s_step's rows (s) and of the new tokens' embeddings into s_next / y_next."""
     k = topk_logp.shape[1]
     args = (ctx.handle, _ptr(states), n_sent, beam, k, max_steps, _ptr(topk_logp), _ptr(topk_idx), _ptr(s_step),
-            s_step.shape[1], _ptr(E_tgt), E_tgt.shape[1], _ptr(y_emb), _ptr(s_next), _ptr(done))
+            s_step.shape[1], _ptr(E_tgt), E_tgt.shape[1])
+    fn = ctx.lib.q8_beam_update_batch
+    if codes is not None:
+        fn = ctx.lib.q8_beam_update_batch_loop
+        args = args + (E_tgt.shape[0], _ptr(y_emb), _ptr(s_next), _ptr(done), C.byref(E_codes.c)) + tuple(C.byref(c.c) for c in codes)
+    else:
+        args = args + (_ptr(y_emb), _ptr(s_next), _ptr(done))
     if bind:
-        return _Bound(ctx, ctx.lib.q8_beam_update_batch, args,
-                      {"keep": (states, topk_logp, topk_idx, s_step, E_tgt, y_emb, s_next, done)})
-    ctx.check(ctx.lib.q8_beam_update_batch(*args))
+        return _Bound(ctx, fn, args, {"keep": (states, topk_logp, topk_idx, s_step, E_tgt, y_emb, s_next, done, codes, E_codes)})
+    ctx.check(fn(*args))
 
 
 def q8_beam_result_batch(ctx, states, n_sent, max_steps):

@@ -80,11 +80,24 @@ bool codes_usable(const q8_codes *c, int ld)
 }
 
 // xq_pre / xs_pre (with gh_pre only): x arrives quantized.  out: the gates kernel also quantizes h_out.
+// x_keep: x's codes are written to the caller's buffers; with h_given (no gh_pre, no taps) they are there
+// already, like those of h_prev in h_given, and nothing is quantized.
 q8_status gru_panel(q8_ctx *ctx, Carver &cv, const q8_gru_weights *g, const float *x, const float *h_prev, int n,
                     const float *gh_pre, float *h_out, const q8_taps *taps2, const int8_t *xq_pre = nullptr,
-                    const float *xs_pre = nullptr, const PanelCodesOut *out = nullptr, const q8_codes *x_keep = nullptr)
+                    const float *xs_pre = nullptr, const PanelCodesOut *out = nullptr, const q8_codes *x_keep = nullptr,
+                    const q8_codes *h_given = nullptr)
 {
     const int I = g->Wx.cols, H = g->Wh.cols;
+    if (h_given && x_keep && !gh_pre && !taps2) {
+        float *gx = cv.take<float>((size_t)n * 3 * H), *gh = cv.take<float>((size_t)n * 3 * H);
+        if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "GRU panel: workspace too small");
+        const q8i_gemm_job gj[2] = {{&g->Wx, x_keep->q, x_keep->scale, g->bx, gx, 3 * H, nullptr, nullptr, nullptr, 0},
+                                    {&g->Wh, h_given->q, h_given->scale, g->bh, gh, 3 * H, nullptr, nullptr, nullptr, 0}};
+        TRY(q8i_gemm_jobs(ctx, gj, 2, n));
+        if (out)
+            return q8i_gru_gates_q(ctx, gx, gh, h_prev, H, h_out, H, H, n, out->q1, out->ld1, out->s1, out->q2, out->ld2, out->s2);
+        return q8i_gru_gates(ctx, gx, gh, h_prev, H, h_out, H, H, n);
+    }
     const bool have_x = gh_pre && xq_pre && xs_pre && !taps2;
     int8_t *xq = have_x ? nullptr : cv.take<int8_t>((size_t)n * g->Wx.ld), *hq = gh_pre ? nullptr : cv.take<int8_t>((size_t)n * g->Wh.ld);
     float *xs = have_x ? nullptr : cv.take<float>(n), *hs = cv.take<float>(n);
@@ -493,9 +506,23 @@ q8_status cgru_decoder_step_batch_codes_q8(q8_ctx *ctx, const q8_cgru_weights *w
                                            const float *s_prev, float *s_out, float *ctx_out, float *alpha_out,
                                            float *s_mid_out, q8_codes *y_codes, q8_codes *ctx_codes, q8_codes *s_codes)
 {
+    if (y_codes) y_codes->valid = 0;                           // (whatever they held is not taken as an input here)
+    return cgru_decoder_step_batch_loop_q8(ctx, w, P, enc_h, sent_off, n_sent, beam, max_l, y_emb, s_prev, s_out, ctx_out,
+                                           alpha_out, s_mid_out, y_codes, ctx_codes, s_codes, nullptr);
+}
+
+q8_status cgru_decoder_step_batch_loop_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h,
+                                          const int32_t *sent_off, int n_sent, int beam, int max_l, const float *y_emb,
+                                          const float *s_prev, float *s_out, float *ctx_out, float *alpha_out,
+                                          float *s_mid_out, q8_codes *y_codes, q8_codes *ctx_codes, q8_codes *s_codes,
+                                          q8_codes *s_prev_codes)
+{
+    // codes that the search step left for this call: both inputs of GRU r or neither
+    const bool y_in = y_codes && y_codes->valid == 2, s_in = s_prev_codes && s_prev_codes->valid == 2;
     if (y_codes) y_codes->valid = 0;
     if (ctx_codes) ctx_codes->valid = 0;
     if (s_codes) s_codes->valid = 0;
+    if (s_prev_codes) s_prev_codes->valid = 0;
     if (!ctx) return Q8_ERR_NULL;
     if (!w) return q8_fail(ctx, Q8_ERR_NULL, "weights: NULL");
     TRY(check_gru(ctx, &w->r, "r"));
@@ -527,13 +554,14 @@ q8_status cgru_decoder_step_batch_codes_q8(q8_ctx *ctx, const q8_cgru_weights *w
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "cgru_decoder_step_batch_q8: workspace too small");
     if (codes_usable(ctx_codes, w->q.Wx.ld)) { cq = ctx_codes->q; cqs = ctx_codes->scale; }    // the caller keeps them
     const bool y_keep = codes_usable(y_codes, w->r.Wx.ld);
+    const bool given = y_in && s_in && y_keep && codes_usable(s_prev_codes, w->r.Wh.ld);
     // Eq. 3: s' = r(y, s_prev); the gates kernel leaves s' quantized for the two products below
     const bool fused_codes = q8i_gru_gates_q_ok(H, H, H, w->att_U.ld, w->q.Wh.ld);
     {
         Carver sub = cv;
         const PanelCodesOut out = {mq_u, w->att_U.ld, ms_u, mq_h, w->q.Wh.ld, ms_h};
         TRY(gru_panel(ctx, sub, &w->r, y_emb, s_prev, n, nullptr, s_mid, nullptr, nullptr, nullptr, fused_codes ? &out : nullptr,
-                      y_keep ? y_codes : nullptr));
+                      y_keep ? y_codes : nullptr, given ? s_prev_codes : nullptr));
         if (y_keep) y_codes->valid = 1;
     }
     // everything that depends on s' alone: u(s') of Eq. 6 and the recurrent half of GRU q
@@ -1299,6 +1327,50 @@ q8_status q8_beam_update_batch(q8_ctx *ctx, void *states, int n_sent, int beam, 
                           s_step, E_tgt, E, H, y_emb, s_next, done, nullptr, nullptr, 0, 0);
 }
 
+namespace {
+// The search step's gather takes the codes of its rows along where there is room for them in its pass
+// (see output_logits_beam_loop_q8): fills the descriptor and says whether it did.
+bool batch_hand_on(q8i_beam_desc *bd, const q8_row_codes *E_codes, const q8_codes *s_codes, q8_codes *y_next, q8_codes *s_next,
+                   int E, int H)
+{
+    if (!E_codes || !E_codes->q || !E_codes->scale || !aligned16(E_codes->q) || !s_codes || s_codes->valid != 1 || !y_next || !s_next)
+        return false;
+    const int ldy = E_codes->ld, lds = s_codes->ld;
+    if (!codes_usable(s_codes, lds) || !codes_usable(y_next, ldy) || !codes_usable(s_next, lds) || s_next->q == s_codes->q)
+        return false;
+    if (E % 4 || H % 4 || ldy % 16 || lds % 16 || ldy < E || lds < H || E / 4 + ldy / 16 + lds / 16 > 256) return false;
+    bd->Eq = E_codes->q; bd->Es = E_codes->scale; bd->ldy = ldy; bd->lds = lds;
+    bd->sq_in = s_codes->q; bd->ss_in = s_codes->scale;
+    bd->yq_out = y_next->q; bd->ys_out = y_next->scale; bd->sq_out = s_next->q; bd->ss_out = s_next->scale;
+    return true;
+}
+}  // namespace
+
+q8_status q8_beam_update_batch_loop(q8_ctx *ctx, void *states, int n_sent, int beam, int k, int max_steps,
+                                    const float *topk_logp, const int32_t *topk_idx, const float *s_step, int H,
+                                    const float *E_tgt, int E, int V, float *y_emb, float *s_next, int32_t *done,
+                                    const q8_row_codes *E_codes, const q8_codes *s_codes, q8_codes *y_next_codes,
+                                    q8_codes *s_next_codes)
+{
+    if (y_next_codes) y_next_codes->valid = 0;
+    if (s_next_codes) s_next_codes->valid = 0;
+    if (!ctx) return Q8_ERR_NULL;
+    if (!states || !topk_logp || !topk_idx || !s_step || !E_tgt || !y_emb || !s_next || !done)
+        return q8_fail(ctx, Q8_ERR_NULL, "q8_beam_update_batch: NULL argument");
+    if (n_sent <= 0 || beam <= 0 || beam > Q8_MAX_BEAM || (long long)n_sent * beam > kMaxMfmaN || k < beam || k > kMaxK ||
+        max_steps <= 0 || E <= 0 || H <= 0 || V < 0)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "q8_beam_update_batch: bad sizes");
+    if (s_next == s_step) return q8_fail(ctx, Q8_ERR_SHAPE, "s_next must not alias s_step");
+    q8i_beam_desc bd = {};
+    // (codes are gathered by token id: only with the table's height known, so that every id stays inside it)
+    const bool hand_on = V > 0 && batch_hand_on(&bd, E_codes, s_codes, y_next_codes, s_next_codes, E, H);
+    const q8_status st = q8i_beam_batch(ctx, 0, states, q8i_beam_state_bytes(max_steps), n_sent, beam, k, max_steps, topk_logp,
+                                        topk_idx, s_step, E_tgt, E, H, y_emb, s_next, done, nullptr, nullptr, 0, V,
+                                        hand_on ? &bd : nullptr);
+    if (!st && hand_on) { y_next_codes->valid = 2; s_next_codes->valid = 2; }
+    return st;
+}
+
 q8_status q8_beam_result_batch(q8_ctx *ctx, const void *states, int n_sent, int max_steps, int32_t *tokens_host,
                                int *len_host, float *score_host, int *steps_host)
 {
@@ -1310,7 +1382,7 @@ q8_status q8_beam_result_batch(q8_ctx *ctx, const void *states, int n_sent, int 
 
 namespace {
 struct BatchBufs {
-    size_t X, enc_h, P, off, y, s0, s1, cv, lp, idx, done, states, yq, ys, cq, cs, sq, ss, total;
+    size_t X, enc_h, P, off, y, s0, s1, cv, lp, idx, done, states, yq, ys, cq, cs, sq, ss, pq, ps, total;
 };
 BatchBufs batch_layout(const q8_model *m, int total_l, int n_sent, int beam, int k, int max_steps)
 {
@@ -1328,6 +1400,8 @@ BatchBufs batch_layout(const q8_model *m, int total_l, int n_sent, int beam, int
     b.yq = take(n * m->dec.r.Wx.ld); b.ys = take(n * 4);
     b.cq = take(n * m->dec.q.Wx.ld); b.cs = take(n * 4);
     b.sq = take(n * m->ro.W_s.ld); b.ss = take(n * 4);
+    // codes of the surviving states, handed from the search step to the next decoder step
+    b.pq = take(n * m->dec.r.Wh.ld); b.ps = take(n * 4);
     b.total = o;
     return b;
 }
@@ -1383,6 +1457,8 @@ q8_status q8_translate_batch(q8_ctx *ctx, const q8_model *m, const int32_t *src_
     q8_codes yc = {(int8_t *)(top + b.yq), (float *)(top + b.ys), m->dec.r.Wx.ld, 0};
     q8_codes cc = {(int8_t *)(top + b.cq), (float *)(top + b.cs), m->dec.q.Wx.ld, 0};
     q8_codes sc = {(int8_t *)(top + b.sq), (float *)(top + b.ss), m->ro.W_s.ld, 0};
+    q8_codes pc = {(int8_t *)(top + b.pq), (float *)(top + b.ps), m->dec.r.Wh.ld, 0};
+    const q8_row_codes *Ec = m->E_tgt_codes.q ? &m->E_tgt_codes : nullptr;
     ctx->ws_reserved_top = ctx->ws_bytes - (size_t)(top - ctx->ws);
 
     q8_status st = Q8_OK;
@@ -1407,14 +1483,21 @@ q8_status q8_translate_batch(q8_ctx *ctx, const q8_model *m, const int32_t *src_
                                             nullptr, &yc, &cc);
             sc.valid = 0;
         } else {
-            st = cgru_decoder_step_batch_codes_q8(ctx, &m->dec, P, enc_h, off, n_sent, beam, max_l, y, sv[cur], sv[cur ^ 1],
-                                                  cvec, nullptr, nullptr, &yc, &cc, &sc);
+            st = cgru_decoder_step_batch_loop_q8(ctx, &m->dec, P, enc_h, off, n_sent, beam, max_l, y, sv[cur], sv[cur ^ 1],
+                                                 cvec, nullptr, nullptr, &yc, &cc, &sc, &pc);
         }
         if (!st) st = output_impl(ctx, &m->ro, &m->W_out, m->b_out, sv[cur ^ 1], y, cvec, nullptr, n, k, nullptr, nullptr, lp,
                                   idx, nullptr, nullptr, nullptr, &yc, &cc, &sc);
-        // (the table's height goes along: a token id outside it, which takes non-finite logits, is replaced by 0)
+        // (the table's height goes along: a token id outside it, which takes non-finite logits, is replaced by 0;
+        // where the model brings its embeddings' codes, the codes of the gathered rows go to the next step)
+        q8i_beam_desc bd = {};
+        const bool hand_on = !st && batch_hand_on(&bd, Ec, &sc, &yc, &pc, E, H);
+        yc.valid = 0;
+        pc.valid = 0;
         if (!st) st = q8i_beam_batch(ctx, 0, states, q8i_beam_state_bytes(max_steps), n_sent, beam, k, max_steps, lp, idx,
-                                     sv[cur ^ 1], m->E_tgt, E, H, y, sv[cur], done, nullptr, nullptr, 0, m->V_tgt);
+                                     sv[cur ^ 1], m->E_tgt, E, H, y, sv[cur], done, nullptr, nullptr, 0, m->V_tgt,
+                                     hand_on ? &bd : nullptr);
+        if (!st && hand_on) { yc.valid = 2; pc.valid = 2; }
         if (!st && (t % 8 == 7)) {
             hipError_t e = hipMemcpyAsync(done_host, done, sizeof(int32_t) * n_sent, hipMemcpyDeviceToHost, ctx->stream);
             if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);

@@ -194,7 +194,8 @@ q8_status q8i_output_codes(q8_ctx *ctx, const q8_mat *W, const float *bias, cons
                            int32_t *tap_acc, float *part_max, double *part_sum);
 q8_status q8i_beam_batch(q8_ctx *ctx, int init, void *states, size_t stride, int S, int beam, int k, int max_steps,
                          const float *topk_logp, const int *topk_idx, const float *s_step, const float *E_tgt, int E,
-                         int H, float *y_emb, float *s_next, int *done, const float *enc_h, const int *sent_off, int C, int V);
+                         int H, float *y_emb, float *s_next, int *done, const float *enc_h, const int *sent_off, int C, int V,
+                         const struct q8i_beam_desc *codes = nullptr);
 q8_status q8i_beam_read_batch(q8_ctx *ctx, const void *states, size_t stride, int S, int max_steps, int32_t *tokens_host,
                               int *len_host, float *score_host, int *steps_host);
 // y_codes / c_codes (may be NULL): codes of y and c left by their producers; used when both are valid and laid out

@@ -288,3 +288,64 @@ def test_codes_travel_from_the_batched_step_to_the_output_layer(q, ctx, oracle, 
         res.append((r1["s"], r1["ctx"], r2["t"], r2["logits"], r2["lse"], r2["topk_logp"], r2["topk_idx"]))
     for a, b, what in zip(res[0], res[1], ("s", "ctx", "t", "logits", "lse", "topk_logp", "topk_idx")):
         assert_same(b, np_(a), what + ": with codes against without")
+
+
+@pytest.mark.parametrize("dims,S,beam,l", [(dict(), 6, 5, 9), (dict(V=500, E=64, H=128, A=64, R=64, w_std=0.2, b_std=0.1), 20, 3, 5),
+                                           (dict(V=700, E=620, H=1000, A=1000, R=620, w_std=0.2, b_std=0.1), 3, 5, 6)])
+def test_codes_handed_from_the_batched_search_step_to_the_next_step(q, ctx, oracle, dims, S, beam, l):
+    """A batched decoding loop in which q8_beam_update_batch_loop gathers the codes of the rows it gathers and
+    cgru_decoder_step_batch_loop_q8 takes them in place of its quantization launch, against the loop that
+    quantizes again: every state, context vector, top-k table and gathered row bit for bit at every step; the
+    handed codes against the oracle's quantization of the rows.  At 620 / 1000 the gather has no room for them."""
+    T = 6
+    p = synth.full_model(seed=41, **dims)
+    m = q.Model.from_params(ctx, p)
+    E, H = m.E_tgt.shape[1], m.dec.r.H
+    n = S * beam
+    rng = np.random.default_rng(S + l)
+    enc_h = ctx.f32(rng.standard_normal((S * l, 2 * H)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    off = torch.arange(0, (S + 1) * l, l, dtype=torch.int32, device=ctx.device)
+
+    def loop(hand_on):
+        states = torch.zeros(q.q8_beam_state_bytes(T) * S, dtype=torch.uint8, device=ctx.device)
+        y, s = ctx.empty(n, E), ctx.empty(n, H)
+        done = torch.zeros(S, dtype=torch.int32, device=ctx.device)
+        q.q8_beam_init_batch(ctx, states, S, beam, T, enc_h, off, m.E_tgt, y, s, done)
+        codes = [q.Codes(ctx, n, m.dec.r.Wx.ld), q.Codes(ctx, n, m.dec.q.Wx.ld), q.Codes(ctx, n, m.ro.W_s.ld)]
+        if hand_on:
+            codes.append(q.Codes(ctx, n, m.dec.r.Wh.ld))
+        trace, used = [], 0
+        for _ in range(T):
+            given = hand_on and codes[0].c.valid == 2 and codes[3].c.valid == 2
+            used += bool(given)
+            if given:
+                trace += [np_(codes[0].q), np_(codes[0].scale), np_(codes[3].q), np_(codes[3].scale)]
+            r = q.cgru_decoder_step_batch_q8(ctx, m.dec, P, enc_h, off, beam, l, y, s, codes=codes)
+            o = q.output_logits_q8(ctx, m.ro, m.W_out, m.b_out, s=r["s"], y_emb=y, ctx_vec=r["ctx"], k=8, want_logits=False,
+                                   codes=codes[:3])
+            q.q8_beam_update_batch(ctx, states, S, beam, T, o["topk_logp"], o["topk_idx"], r["s"], m.E_tgt, y, s, done,
+                                   codes=(codes[2], codes[0], codes[3]) if hand_on else None,
+                                   E_codes=m.E_tgt_codes if hand_on else None)
+            trace += [np_(r["s"]), np_(r["ctx"]), np_(o["topk_logp"]), np_(o["topk_idx"]), np_(y), np_(s)]
+        return trace, used, q.q8_beam_result_batch(ctx, states, S, T)
+
+    ref, _, ref_res = loop(False)
+    got, used, got_res = loop(True)
+    fits = E // 4 + m.dec.r.Wx.ld // 16 + m.ro.W_s.ld // 16 <= 256
+    assert used == (T - 1 if fits else 0)
+    gi = iter(got)
+    for step in range(T):
+        if fits and step > 0:
+            yq, ys, sq, ss = next(gi), next(gi), next(gi), next(gi)
+            y_rows, s_rows = ref[6 * (step - 1) + 4], ref[6 * (step - 1) + 5]
+            for j in (0, n // 2, n - 1):
+                cq, cs = oracle.quantize(y_rows[j])
+                assert_same(yq[j, :E], cq, "codes of y"); assert_same(ys[j:j + 1], np.array([cs], np.float32), "scale of y")
+                cq, cs = oracle.quantize(s_rows[j])
+                assert_same(sq[j, :H], cq, "codes of s"); assert_same(ss[j:j + 1], np.array([cs], np.float32), "scale of s")
+                assert not yq[j, E:].any() and not sq[j, H:].any()
+        for i in range(6):
+            assert_same(next(gi), ref[6 * step + i], "step %d, output %d" % (step, i))
+    for a, b in zip(got_res, ref_res):
+        assert a[0].tolist() == b[0].tolist() and a[1:] == b[1:]
