@@ -635,10 +635,14 @@ def main():
     if not args.no_graph and not args.quick:
         try:
             lanes = []
-            for _ in range(4):
+            for lane in range(4):
                 st = torch.cuda.Stream()
                 with torch.cuda.stream(st):
                     c = q.Context("cuda:0", stream=st)
+                    # The blocks of the attention kernel's exchange form wait for each other, so the grids of kernels
+                    # that may run at the same time must fit the device together (150 blocks of 1024 threads each
+                    # here, 512 fit): two lanes use it, the other two the form whose last block finishes.
+                    q.q8_attention_options(c, exchange=lane < 2)
                     lp = DecodeLoop(q, c, m, P, enc_h, BEAM, rng)
                     lp.step()
                     st.synchronize()

@@ -302,7 +302,12 @@ q8_status q8_encode_check(q8_ctx *ctx);
  * those of later calls are not valid until q8_encode_check (above) has reported it, once, and put
  * the exchange words in the workspace header back to zero.  The same bound and the same report
  * cover the one wait of output_logits_beam_q8, whose selection kernel hands every hypothesis' k
- * best to the block that runs the search step. */
+ * best to the block that runs the search step.
+ * Contexts whose decoder steps may run at the same time on one device (different streams): the
+ * blocks of the exchange form wait for each other, so the attention grids that can be in flight
+ * together must fit the device together (l n_beam blocks of 1024 threads each, two per compute
+ * unit); give the contexts beyond that exchange = 0.  The same holds for q8_encoder_options'
+ * one-launch recurrence (2 H / 8 blocks of 512 threads). */
 q8_status q8_attention_options(q8_ctx *ctx, int exchange, int spin_limit);
 
 /* ---- search (Section 3 only says the beam is smaller than 8; these are the rules) ----
