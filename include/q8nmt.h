@@ -560,7 +560,9 @@ q8_status q8_probe_read(q8_ctx *ctx, const void *buf, size_t bytes);
 /* Verification aid: evaluates the library's own device functions for the float parts of the
  * model (Section 3 keeps sigmoid, tanh and the exponentials in floating point) on an array of
  * n values, so that they can be compared with a reference on the device they run on.
- * fn = 0: tanh, 1: sigmoid (x, y: n floats); fn = 2: exp for |x| <= 700 (x, y: n doubles).
+ * fn = 0: tanh, 1: sigmoid (x, y: n floats); fn = 2: exp for |x| <= 700 (x, y: n doubles);
+ * fn = 3: every group of 64 consecutive floats sorted in descending order (the wave-wide sort
+ * from which the top-k selection derives its threshold; n a multiple of 256).
  * x, y: device pointers, y may equal x.  Enqueues one launch on the context's stream. */
 q8_status q8_math_eval(q8_ctx *ctx, int fn, const void *x, void *y, size_t n);
 

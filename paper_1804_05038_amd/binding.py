@@ -582,8 +582,9 @@ def q8_profile_begin(ctx, kernel_class, max_samples):
 
 
 def q8_math_eval(ctx, fn, x):
-    """The device's own tanh ("tanh"), sigmoid ("sigmoid") (float32 tensors) or exp ("exp", float64) of x."""
-    code = {"tanh": 0, "sigmoid": 1, "exp": 2}[fn]
+    """The device's own tanh ("tanh"), sigmoid ("sigmoid") (float32 tensors) or exp ("exp", float64) of x;
+    "sort64": every 64 consecutive floats in descending order (a multiple of 256 values)."""
+    code = {"tanh": 0, "sigmoid": 1, "exp": 2, "sort64": 3}[fn]
     want = torch.float64 if code == 2 else torch.float32
     if x.dtype != want or not x.is_contiguous():
         raise ValueError("q8_math_eval(%s) takes a contiguous %s tensor" % (fn, want))

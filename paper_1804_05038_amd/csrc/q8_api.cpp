@@ -248,7 +248,8 @@ q8_status q8_math_eval(q8_ctx *ctx, int fn, const void *x, void *y, size_t n)
 {
     if (!ctx) return Q8_ERR_NULL;
     if (!x || !y) return q8_fail(ctx, Q8_ERR_NULL, "q8_math_eval: NULL buffer");
-    if (fn < 0 || fn > 2 || n == 0 || n > ((size_t)1 << 31)) return q8_fail(ctx, Q8_ERR_SHAPE, "q8_math_eval: fn in 0..2, 1 <= n <= 2^31");
+    if (fn < 0 || fn > 3 || n == 0 || n > ((size_t)1 << 31)) return q8_fail(ctx, Q8_ERR_SHAPE, "q8_math_eval: fn in 0..3, 1 <= n <= 2^31");
+    if (fn == 3 && n % 256) return q8_fail(ctx, Q8_ERR_SHAPE, "q8_math_eval: the sort takes a multiple of 256 values");
     return q8i_math_eval(ctx, fn, x, y, n);
 }
 

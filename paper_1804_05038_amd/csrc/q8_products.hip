@@ -383,11 +383,15 @@ __global__ __launch_bounds__(256) void read_probe_kernel(const int4 *buf, size_t
 // ============================================================ device math, evaluated ==
 // Verification aid: the device's own sigmoid / tanh (float in, float out) and exp (double in, double
 // out) on an array, so that the functions the kernels call can be compared with a reference value by
-// value on the device they run on.
+// value on the device they run on; and the wave-wide sort of the selection's threshold on groups of 64.
 __global__ __launch_bounds__(256) void math_eval_kernel(int fn, const void *x, void *y, size_t n)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n) return;
+    if (fn == 3) {                                   // (n is a multiple of 256: every wave is complete)
+        ((float *)y)[i] = wave_sort_desc_f(((const float *)x)[i], threadIdx.x & 63);
+        return;
+    }
     if (fn == 0) ((float *)y)[i] = q8_tanh_rn(((const float *)x)[i]);
     else if (fn == 1) ((float *)y)[i] = q8_sigmoid_rn(((const float *)x)[i]);
     else ((double *)y)[i] = q8_exp_d(((const double *)x)[i]);

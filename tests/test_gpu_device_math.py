@@ -77,3 +77,18 @@ def test_device_and_host_forms_agree(q, ctx):
         fn(x.ctypes.data, host.ctypes.data, x.size)
         dev = q.q8_math_eval(ctx, name, torch.from_numpy(x).to(ctx.device)).cpu().numpy()
         assert (host == dev).all(), (name, int((host != dev).sum()))
+
+
+def test_wave_sort_orders_every_group_of_64(q, ctx):
+    """The wave-wide sort behind the top-k threshold (cross-lane moves only): random values, many equal
+    values, infinities and already sorted input, against numpy's sort."""
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal(64 * 4096).astype(np.float32)
+    x[: 64 * 512] = rng.integers(-3, 4, 64 * 512).astype(np.float32)          # heavy ties
+    x[64 * 512: 64 * 520] = np.tile(np.arange(64, dtype=np.float32), 8)        # ascending
+    x[64 * 520: 64 * 528] = np.tile(np.arange(64, dtype=np.float32)[::-1], 8)  # descending
+    x[64 * 528: 64 * 536: 3] = -np.inf
+    x[64 * 536] = np.inf
+    y = q.q8_math_eval(ctx, "sort64", torch.from_numpy(x).to(ctx.device)).cpu().numpy()
+    ref = -np.sort(-x.reshape(-1, 64), axis=1)
+    assert (y.reshape(-1, 64) == ref).all()
