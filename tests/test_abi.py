@@ -70,3 +70,40 @@ def test_source_token_ids_are_range_checked_on_the_host():
             q.source_ids(bad, 10)
     with pytest.raises(ValueError):
         q.source_ids(torch.tensor([1, 20]), 10)
+
+
+def test_loop_forms_without_a_context_return_the_null_code_and_drop_the_codes(lib):
+    """The forms that hand codes from step to step mark every code set they were given as not
+    valid before anything else, so a call that fails leaves nothing that a later call could
+    mistake for this step's codes."""
+    from paper_1804_05038_amd.binding import _Codes
+    import ctypes as C
+
+    def given(v):
+        c = _Codes(None, None, 0, v)
+        return c, C.byref(c)
+
+    def nulls(fn, n_tail):              # NULL or 0 for every argument before the code sets
+        head = fn.argtypes[:len(fn.argtypes) - n_tail]
+        return [None if t is C.c_void_p or hasattr(t, "contents") else 0 for t in head]
+
+    assert lib.q8_attention_options(None, 1, 0) == 1
+    y, py = given(2); cx, pcx = given(1); sp, psp = given(2)
+    args = nulls(lib.cgru_decoder_step_loop_q8, 3)
+    assert lib.cgru_decoder_step_loop_q8(*args, py, pcx, psp) == 1
+    assert (y.valid, cx.valid, sp.valid) == (0, 0, 0)
+
+    y, py = given(1); cx, pcx = given(1); sn, psn = given(2)
+    args = nulls(lib.output_logits_beam_loop_q8, 4)
+    assert lib.output_logits_beam_loop_q8(*args, py, pcx, psn, None) == 1
+    assert (y.valid, sn.valid) == (0, 0) and cx.valid == 1      # the context's codes are an input only
+
+    y, py = given(2); cx, pcx = given(1); s, ps = given(1); sp, psp = given(2)
+    args = nulls(lib.cgru_decoder_step_batch_loop_q8, 4)
+    assert lib.cgru_decoder_step_batch_loop_q8(*args, py, pcx, ps, psp) == 1
+    assert (y.valid, cx.valid, s.valid, sp.valid) == (0, 0, 0, 0)
+
+    s, ps = given(1); yn, pyn = given(2); sn, psn = given(2)
+    args = nulls(lib.q8_beam_update_batch_loop, 4)
+    assert lib.q8_beam_update_batch_loop(*args, None, ps, pyn, psn) == 1
+    assert (yn.valid, sn.valid) == (0, 0) and s.valid == 1
