@@ -617,7 +617,11 @@ class Model:
     @classmethod
     def from_params(cls, ctx, p):
         """Quantizes a dict of fp32 arrays (keys as in workloads.synth.full_model) on the device."""
-        mat = lambda k: q8_quantize_matrix(ctx, p[k])
+        def mat(k):
+            # rows of whole 64-byte k steps are also kept tile-packed: the matrix-core products of panels read
+            # that copy (one contiguous KiB per operand)
+            W = q8_quantize_matrix(ctx, p[k])
+            return q8_pack_tiles(ctx, W) if W.ld % 64 == 0 else W
         gru = lambda pre: GruWeights(mat(pre + ".Wx"), mat(pre + ".Wh"), ctx.f32(p[pre + ".bx"]), ctx.f32(p[pre + ".bh"]))
         dec = CgruWeights(gru("dec_r"), mat("att.U"), ctx.f32(p["att.v"]), gru("dec_q"))
         ro = ReadoutWeights(mat("ro.Ws"), mat("ro.Wy"), mat("ro.Wc"), ctx.f32(p["ro.b"]))

@@ -85,10 +85,17 @@ bool codes_usable(const q8_codes *c, int ld)
 q8_status gru_panel(q8_ctx *ctx, Carver &cv, const q8_gru_weights *g, const float *x, const float *h_prev, int n,
                     const float *gh_pre, float *h_out, const q8_taps *taps2, const int8_t *xq_pre = nullptr,
                     const float *xs_pre = nullptr, const PanelCodesOut *out = nullptr, const q8_codes *x_keep = nullptr,
-                    const q8_codes *h_given = nullptr)
+                    const q8_codes *h_given = nullptr, int region = 0)
 {
     const int I = g->Wx.cols, H = g->Wh.cols;
+    // products, gates and codes in one launch where the shape allows (no pre-activations in memory)
+    const bool one_launch = !taps2 && q8i_gru_panel_ok(ctx, g, gh_pre != nullptr, n, H, H, out != nullptr, out ? out->ld1 : 0, out ? out->ld2 : 0, out && out->q2);
+    auto panel = [&](const int8_t *xq_, const float *xs_, const int8_t *hq_, const float *hs_) {
+        return q8i_gru_panel(ctx, g, xq_, xs_, hq_, hs_, gh_pre, h_prev, H, h_out, H, n, out ? out->q1 : nullptr, out ? out->ld1 : 0,
+                             out ? out->s1 : nullptr, out ? out->q2 : nullptr, out ? out->ld2 : 0, out ? out->s2 : nullptr, region);
+    };
     if (h_given && x_keep && !gh_pre && !taps2) {
+        if (one_launch) return panel(x_keep->q, x_keep->scale, h_given->q, h_given->scale);
         float *gx = cv.take<float>((size_t)n * 3 * H), *gh = cv.take<float>((size_t)n * 3 * H);
         if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "GRU panel: workspace too small");
         const q8i_gemm_job gj[2] = {{&g->Wx, x_keep->q, x_keep->scale, g->bx, gx, 3 * H, nullptr, nullptr, nullptr, 0},
@@ -102,12 +109,14 @@ q8_status gru_panel(q8_ctx *ctx, Carver &cv, const q8_gru_weights *g, const floa
     int8_t *xq = have_x ? nullptr : cv.take<int8_t>((size_t)n * g->Wx.ld), *hq = gh_pre ? nullptr : cv.take<int8_t>((size_t)n * g->Wh.ld);
     float *xs = have_x ? nullptr : cv.take<float>(n), *hs = cv.take<float>(n);
     if (!have_x && x_keep) { xq = x_keep->q; xs = x_keep->scale; }       // x's codes stay with the caller (pitch checked there)
-    float *gx = cv.take<float>((size_t)n * 3 * H), *gh = gh_pre ? nullptr : cv.take<float>((size_t)n * 3 * H);
+    float *gx = one_launch ? nullptr : cv.take<float>((size_t)n * 3 * H);
+    float *gh = gh_pre || one_launch ? nullptr : cv.take<float>((size_t)n * 3 * H);
     if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "GRU panel: workspace too small");
     if (!have_x) {
         const q8i_quant_job qj[2] = {{x, I, I, g->Wx.ld, xq, xs, taps2}, {h_prev, H, H, g->Wh.ld, hq, hs, taps2 ? taps2 + 1 : nullptr}};
         TRY(q8i_quantize_jobs(ctx, qj, gh_pre ? 1 : 2, n));
     }
+    if (one_launch) return panel(have_x ? xq_pre : xq, have_x ? xs_pre : xs, hq, hs);
     const q8i_gemm_job gj[2] = {{&g->Wx, have_x ? xq_pre : xq, have_x ? xs_pre : xs, g->bx, gx, 3 * H, taps2 ? taps2[0].acc : nullptr, nullptr, nullptr, 0},
                                 {&g->Wh, hq, hs, g->bh, gh, 3 * H, taps2 ? taps2[1].acc : nullptr, nullptr, nullptr, 0}};
     TRY(q8i_gemm_jobs(ctx, gj, gh_pre ? 1 : 2, n));
@@ -161,6 +170,7 @@ q8_status q8_create(q8_ctx **out, void *hip_stream, void *workspace, size_t work
     c->att_spin_limit = Q8_ENC_SPIN_DEFAULT;
     c->att_capacity = -1;
     c->att_words_set = 0;
+    c->grup_used[0] = c->grup_used[1] = 0;
     q8_status st = q8i_fill_u32(c, c->ws, Q8_WS_HEADER / 4, 0u);
     if (st) { delete c; return st; }
     *out = c;
@@ -583,7 +593,7 @@ q8_status cgru_decoder_step_batch_loop_q8(q8_ctx *ctx, const q8_cgru_weights *w,
                         q8i_gru_gates_q_ok(H, H, H, s_codes->ld, s_codes->ld);
     const PanelCodesOut s_out_codes = {s_keep ? s_codes->q : nullptr, s_keep ? s_codes->ld : 0, s_keep ? s_codes->scale : nullptr, nullptr, 0, nullptr};
     q8_status st = gru_panel(ctx, sub, &w->q, ctx_out, s_mid, n, ghq, s_out, nullptr, have_codes ? cq : nullptr,
-                             have_codes ? cqs : nullptr, s_keep ? &s_out_codes : nullptr);
+                             have_codes ? cqs : nullptr, s_keep ? &s_out_codes : nullptr, nullptr, nullptr, 1);
     if (!st && s_keep) s_codes->valid = 1;
     return st;
 }
@@ -843,9 +853,10 @@ q8_status q8_encode_check(q8_ctx *ctx)
         // (blocks that were not waited for may have left exchange words set after their reader cleared them)
         q8i_fill_u32(ctx, ctx->ws + Q8_WS_ATT_XCHG, (Q8_WS_HEADER - Q8_WS_ATT_XCHG) / 4, 0u);
         ctx->att_words_set = 0;
+        ctx->grup_used[0] = ctx->grup_used[1] = 0;
         if (flag[0])
             return q8_fail(ctx, Q8_ERR_DEVICE, "q8_encode: a wait inside the one-launch recurrence gave up; enc_h is not valid");
-        return q8_fail(ctx, Q8_ERR_DEVICE, "decoder step: a wait between the blocks of the attention or of the selection kernel gave up; "
+        return q8_fail(ctx, Q8_ERR_DEVICE, "decoder step: a wait between the blocks of the attention, the selection or the panel GRU kernel gave up; "
                                            "the results since the last check are not valid");
     }
     return Q8_OK;

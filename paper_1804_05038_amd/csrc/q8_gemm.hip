@@ -7,6 +7,9 @@
 
 struct GemmArgs {
     const int8_t *W;       // [rows x ld] int8
+    const int8_t *Wt;      // the same matrix tile-packed (q8_pack_tiles), or NULL: every matrix-core operand of 16 rows x 64 k
+                           // bytes is then one contiguous KiB instead of 16 pieces of rows that lie ld bytes apart, which the
+                           // memory system delivers about 2.5 times as fast (measured: 192 KB per block, 2.1 against 5.3 us)
     const int8_t *xq;      // [n x ld] int8 codes of the n vectors
     const float *xscale;   // [n]
     const float *bias;     // [rows] or NULL
@@ -68,7 +71,13 @@ __global__ __launch_bounds__(256) void gemm_block_kernel(GemmJobs jobs)
         const int row = r0 + 16 * rt + i;
         row_ok[rt] = row < rows;
         wp[rt] = a.W + (size_t)(row_ok[rt] ? row : rows - 1) * ld;
+        if (a.Wt) {            // this lane's 16 bytes of the row tile's first k step (tiles past the matrix: the last one, dropped below)
+            const int tile = min((r0 + 16 * rt) >> 4, a.ntiles - 1);
+            wp[rt] = a.Wt + (size_t)tile * (ld >> 6) * 1024 + lane * 16;
+        }
     }
+    const bool tiled = a.Wt != nullptr;
+    const int kc_last = (ld >> 6) - 1;
     const int8_t *bp_g[PIECES];
     bool col_ok[PIECES];
 #pragma unroll
@@ -96,7 +105,7 @@ __global__ __launch_bounds__(256) void gemm_block_kernel(GemmJobs jobs)
         for (int u = 0; u < PIECES; ++u) R.b[u] = *(const v4i *)(bp_g[u] + kB);
 #pragma unroll
         for (int kc = 0; kc < 2; ++kc) {
-            const int kA = min(k0 + 64 * kc + 16 * g, klast);
+            const int kA = tiled ? min((k0 >> 6) + kc, kc_last) * 1024 : min(k0 + 64 * kc + 16 * g, klast);
 #pragma unroll
             for (int rt = 0; rt < RT; ++rt) R.a[rt][kc] = *(const v4i *)(wp[rt] + kA);
         }
@@ -282,13 +291,16 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(GemmJobs jobs)
         bq[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rx, (int)off, 0, 0));
     }
     // this wave's 16 rows
-    const __amdgpu_buffer_rsrc_t rw = q8_rsrc(a.W, (size_t)rows * ld);
+    const bool tiled = a.Wt != nullptr;
+    const __amdgpu_buffer_rsrc_t rw = tiled ? q8_rsrc(a.Wt, (size_t)a.ntiles * 16 * ld) : q8_rsrc(a.W, (size_t)rows * ld);
     const int row = r0 + i;
     v4i av[KS];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
         const int k = 64 * s + 16 * g;
-        const unsigned off = (row < rows && k < ld) ? (unsigned)row * (unsigned)ld + (unsigned)k : Q8_OOB;
+        unsigned off = (row < rows && k < ld) ? (unsigned)row * (unsigned)ld + (unsigned)k : Q8_OOB;
+        // tile-packed: operand (row tile, k step) is one KiB, lane by lane (rows past the matrix are zero in it)
+        if (tiled) off = (r0 < rows && 64 * s < ld) ? (((unsigned)(r0 >> 4) * (unsigned)(ld >> 6) + (unsigned)s) << 10) + 16u * lane : Q8_OOB;
         av[s] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rw, (int)off, 0, 0));
     }
     // epilogue operands: dequantization factors and biases
@@ -629,7 +641,7 @@ q8_status q8i_gemm_jobs(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n)
     for (int t = 0; t < GEMM_MAX_JOBS; ++t) {
         const q8i_gemm_job &q = d[t < njobs ? t : 0];
         GemmArgs &a = jobs.j[t];
-        a.W = q.W->data; a.xq = q.xq; a.xscale = q.xscale; a.bias = q.bias; a.Y = q.Y; a.tap_acc = q.tap_acc;
+        a.W = q.W->data; a.Wt = (q.W->tiles && q.W->ld % 64 == 0) ? q.W->tiles : nullptr; a.xq = q.xq; a.xscale = q.xscale; a.bias = q.bias; a.Y = q.Y; a.tap_acc = q.tap_acc;
         a.part_max = q.part_max; a.part_sum = q.part_sum;
         a.rows = q.W->rows; a.ld = q.W->ld; a.n = n; a.ldy = q.ldy; a.ntiles = (q.W->rows + 15) / 16;
         a.tiled = q.tiled;
@@ -643,7 +655,7 @@ q8_status q8i_gemm_jobs(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n)
     int max_ld = 0;
     for (int t = 0; t < njobs; ++t) {
         const GemmArgs &a = jobs.j[t];
-        if (a.ld > 1024 || a.tap_acc || a.tiled || (size_t)a.rows * a.ld >= (1u << 31) || (size_t)n * a.ld >= (1u << 31)) resident = false;
+        if (a.ld > 1024 || a.tap_acc || a.tiled || (size_t)a.ntiles * 16 * a.ld >= (1u << 31) || (size_t)n * a.ld >= (1u << 31)) resident = false;
         if (a.ld > max_ld) max_ld = a.ld;
     }
     if (resident) {

@@ -655,6 +655,335 @@ q8_status q8i_gru_gates_q(q8_ctx *ctx, const float *gx, const float *gh, const f
     return q8i_launch_check(ctx, "gru gates + codes");
 }
 
+// ================================= products and gates of a panel in one launch ==
+// One GRU transition (Eq. 1, 3, 4) for a panel of hypothesis slots without the two [n x 3H] arrays
+// of pre-activations ever reaching memory: the matrix-core products of the block kernels above and
+// the gates of gru_gates_q_kernel, value for value, in one kernel.  Block (ug, cg) of twelve waves
+// owns hidden units 32 ug .. 32 ug + 31 and slots 48 cg .. 48 cg + 47.  Wave (rt, kp), rt = 2 gate +
+// unit tile, kp = 0 / 1, multiplies the 16 weight rows of its gate and unit tile over one part of
+// the k range against the block's slots (codes parked in LDS, 48 slots whole):
+//   both products here (GH_PRE false): kp = 0 is W_x (KS0 k steps of 64 bytes), kp = 1 is W_h (KS1);
+//   recurrent product given (GH_PRE true): W_x alone, kp = 0 its first KS0 k steps, kp = 1 the next
+//   KS1; the two exact int32 partial sums are added before the one dequantization.
+// The accumulators cross to the threads that apply the gates through LDS; thread -> (slot, unit)
+// with consecutive threads on consecutive units, two pairs per thread.
+// The codes of the new state need max |h| over all H units of a slot, which the H / 32 blocks of a
+// column group hold between them.  Each block publishes its 48 partial maxima as 4-byte words
+// (float bits + 1, so that zero means "not there yet") with device-coherent stores and polls the
+// group's words; with all of them it quantizes the values it still holds in registers.  The waits
+// are bounded (a wait that gives up raises the context's flag and the kernel still ends), and the
+// launcher checks that the device holds all blocks at once.  Words must be zero on entry: two regions
+// take turns (GRU r of a decoder step uses one, GRU q the other) and every launch clears the region it
+// does not use, which the launch before it has finished with; the host keeps track and clears by
+// a fill where that order is broken.
+#define GP_UNITS 32
+#define GP_SLOTS 48
+#define GP_WAVES 12
+#define GP_MAX_CG 7          // column groups of a launch whose blocks exchange maxima (336 slots)
+#define GP_REGION_WORDS (GP_MAX_CG * 32 * GP_SLOTS)
+struct GruPanelArgs {
+    const int8_t *Wx, *Wh;      // [3H x ldx], [3H x ldh] (Wh unused with GH_PRE)
+    const int8_t *Wxt, *Wht;    // the same tile-packed (q8_pack_tiles) or NULL: one contiguous KiB per matrix-core operand
+    const float *bx, *bh;       // [3H] or NULL
+    const int8_t *xq, *hq;      // codes [n x ldx], [n x ldh]
+    const float *xs, *hs;       // [n]
+    const float *gh_pre;        // GH_PRE: [n x 3H], bias included
+    const float *h_prev;        // [n x ldp]
+    float *h_out;               // [n x ldo]
+    int8_t *q1, *q2;            // codes of h_out [n x ld1], [n x ld2] (q2 may be NULL), pad bytes zero
+    float *s1, *s2;
+    unsigned *xw;               // exchange words [2 regions][GP_MAX_CG][32 unit groups][48 slots]
+    unsigned *wait_err;
+    int region, spin_limit;
+    int H, n, ldx, ldh, ldp, ldo, ld1, ld2;
+    float wx_scale, wh_scale;
+};
+
+template <int KS0, int KS1, bool GH_PRE>
+__global__ __launch_bounds__(64 * GP_WAVES) void gru_panel_kernel(GruPanelArgs a)
+{
+    extern __shared__ __align__(16) int8_t s_gp[];
+    __shared__ float s_mx[2 * 64 * GP_WAVES];          // the column group's maxima [unit group][slot]
+    constexpr int KSM = KS0 > KS1 ? KS0 : KS1;
+    constexpr int NT = 64 * GP_WAVES;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);          // wave-uniform, and known to be
+    const int i = lane & 15, g = lane >> 4;
+    const int ug = blockIdx.x, cg = blockIdx.y;
+    const int H = a.H, n = a.n, c0 = cg * GP_SLOTS, u0 = ug * GP_UNITS;
+    constexpr int ldx = GH_PRE ? 64 * (KS0 + KS1) : 64 * KS0, ldh = GH_PRE ? 0 : 64 * KS1;     // the launcher checks a.ldx, a.ldh
+    constexpr int px = ldx + 16, ph = ldh + 16;                  // LDS pitches of the two code regions
+    int8_t *s_x = s_gp, *s_h = s_gp + GP_SLOTS * px;
+    int *s_e = (int *)(s_gp + GP_SLOTS * px + (GH_PRE ? 0 : GP_SLOTS * ph));     // [12 waves][3 tiles][16 slots][16 units]
+    // the exchange words of the region this launch does not use, for this block's unit group: its own
+    // column group, and the last column group also those beyond the grid
+    if (a.q1 && tid < GP_SLOTS) {
+        unsigned *other = a.xw + (size_t)(1 - a.region) * GP_REGION_WORDS + ug * GP_SLOTS + tid;
+        const int last = cg == (int)gridDim.y - 1 ? GP_MAX_CG : cg + 1;
+        for (int c2 = cg; c2 < last; ++c2) other[(size_t)c2 * 32 * GP_SLOTS] = 0u;
+    }
+
+    // ---- every load of the products, requested before the first wait (outside the arrays: zero) ----
+    // the slots' codes in 16-byte pieces: UX rounds of the block's threads for x, UH for h
+    constexpr int PCX = ldx / 16, PCH = ldh / 16, UX = GP_SLOTS * PCX / NT, UH = GP_SLOTS * PCH / NT;
+    static_assert(GP_SLOTS * PCX % NT == 0 && GP_SLOTS * PCH % NT == 0, "pieces divide among the threads");
+    const __amdgpu_buffer_rsrc_t rxq = q8_rsrc(a.xq, (size_t)n * ldx);
+    const __amdgpu_buffer_rsrc_t rhq = q8_rsrc(GH_PRE ? a.xq : a.hq, GH_PRE ? 0 : (size_t)n * ldh);
+    v4i bqx[UX], bqh[UH > 0 ? UH : 1];
+#pragma unroll
+    for (int u = 0; u < UX; ++u) {
+        const int p = u * NT + tid, slot = p / PCX, piece = p - slot * PCX;
+        const unsigned off = c0 + slot < n ? (unsigned)(c0 + slot) * (unsigned)ldx + 16u * piece : Q8_OOB;
+        bqx[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rxq, (int)off, 0, 0));
+    }
+#pragma unroll
+    for (int u = 0; u < UH; ++u) {
+        const int p = u * NT + tid, slot = p / (PCH > 0 ? PCH : 1), piece = p - slot * PCH;
+        const unsigned off = c0 + slot < n ? (unsigned)(c0 + slot) * (unsigned)ldh + 16u * piece : Q8_OOB;
+        bqh[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rhq, (int)off, 0, 0));
+    }
+    // this wave's 16 weight rows over its part of the k range
+    const int rt = wave % 6, kp = wave / 6, gate = rt >> 1, ut = rt & 1;
+    const bool from_h = !GH_PRE && kp == 1;
+    const int ks = kp == 0 ? KS0 : KS1;                           // k steps of this wave
+    const int kbase = GH_PRE && kp == 1 ? 64 * KS0 : 0;           // first k byte within the matrix's rows
+    const int ldw = from_h ? ldh : ldx;
+    const int8_t *wt = from_h ? a.Wht : a.Wxt;
+    const __amdgpu_buffer_rsrc_t rw = q8_rsrc(wt ? wt : (from_h ? a.Wh : a.Wx), (size_t)3 * H * ldw);
+    const int row0 = gate * H + u0 + 16 * ut, row = row0 + i;             // H % 16 == 0: row0 starts a tile
+    v4i av[KSM];
+#pragma unroll
+    for (int s = 0; s < KSM; ++s) {
+        const int k = kbase + 64 * s + 16 * g;
+        unsigned off = (s < ks && k < ldw) ? (unsigned)row * (unsigned)ldw + (unsigned)k : Q8_OOB;
+        if (wt) off = s < ks ? (((unsigned)(row0 >> 4) * (unsigned)(ldw >> 6) + (unsigned)((kbase >> 6) + s)) << 10) + 16u * lane : Q8_OOB;
+        av[s] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rw, (int)off, 0, 0));
+    }
+    // what the gates need per (slot, unit) pair: pairs tid and tid + NT of 48 x 32
+    const __amdgpu_buffer_rsrc_t rxs = q8_rsrc(a.xs, (size_t)n * 4), rhs = q8_rsrc(GH_PRE ? a.xs : a.hs, GH_PRE ? 0 : (size_t)n * 4);
+    const __amdgpu_buffer_rsrc_t rbx = q8_rsrc(a.bx, a.bx ? (size_t)3 * H * 4 : 0), rbh = q8_rsrc(a.bh, (!GH_PRE && a.bh) ? (size_t)3 * H * 4 : 0);
+    const __amdgpu_buffer_rsrc_t rgh = q8_rsrc(a.gh_pre, GH_PRE ? (size_t)n * 3 * H * 4 : 0);
+    const __amdgpu_buffer_rsrc_t rhp = q8_rsrc(a.h_prev, ((size_t)(n - 1) * a.ldp + H) * 4);
+    float xsv[2], hsv[2], hpv[2], bxv[2][3], bhv[2][3];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int pr = e * NT + tid, c = pr >> 5, u = pr & 31, col = c0 + c, unit = u0 + u;
+        const bool ok = col < n;
+        xsv[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rxs, (int)(ok ? (unsigned)col * 4u : Q8_OOB), 0, 0));
+        hsv[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rhs, (int)(ok ? (unsigned)col * 4u : Q8_OOB), 0, 0));
+        hpv[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rhp, (int)(ok ? ((unsigned)col * (unsigned)a.ldp + (unsigned)unit) * 4u : Q8_OOB), 0, 0));
+#pragma unroll
+        for (int gt = 0; gt < 3; ++gt) {
+            const unsigned r4 = (unsigned)(gt * H + unit) * 4u;
+            bxv[e][gt] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rbx, (int)r4, 0, 0));
+            // GH_PRE: the given recurrent pre-activation takes the place of (product, bias)
+            bhv[e][gt] = GH_PRE ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rgh, (int)(ok ? ((unsigned)col * 3u * (unsigned)H) * 4u + r4 : Q8_OOB), 0, 0))
+                                : __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rbh, (int)r4, 0, 0));
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- codes into LDS ----
+#pragma unroll
+    for (int u = 0; u < UX; ++u) {
+        const int p = u * NT + tid, slot = p / PCX, piece = p - slot * PCX;
+        *(v4i *)(s_x + slot * px + 16 * piece) = bqx[u];
+    }
+#pragma unroll
+    for (int u = 0; u < UH; ++u) {
+        const int p = u * NT + tid, slot = p / (PCH > 0 ? PCH : 1), piece = p - slot * PCH;
+        *(v4i *)(s_h + slot * ph + 16 * piece) = bqh[u];
+    }
+    __syncthreads();
+
+    // ---- products: three column tiles, independent accumulation chains ----
+    v4i acc[3];
+#pragma unroll
+    for (int t = 0; t < 3; ++t) acc[t] = (v4i){0, 0, 0, 0};
+    {
+        const int8_t *bp = (from_h ? s_h + i * ph : s_x + i * px + kbase) + 16 * g;
+        const int pitch = from_h ? ph : px;
+#pragma unroll
+        for (int s = 0; s < KSM; ++s) {
+            if (s < ks) {                                           // wave-uniform
+#pragma unroll
+                for (int t = 0; t < 3; ++t) {
+                    const v4i bv = *(const v4i *)(bp + t * 16 * pitch + 64 * s);
+                    acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[s], bv, acc[t], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // lane (i, g) holds units 4 g + r, r = 0..3, of slot i of each tile
+#pragma unroll
+    for (int t = 0; t < 3; ++t) *(v4i *)(s_e + (((wave * 3 + t) * 16 + i) * 16 + 4 * g)) = acc[t];
+    __syncthreads();
+
+    // ---- gates ----
+    float hn[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int pr = e * NT + tid, c = pr >> 5, u = pr & 31, col = c0 + c, unit = u0 + u;
+        const float cx = a.wx_scale * xsv[e], ch = a.wh_scale * hsv[e];
+        float gx[3], gh[3];
+#pragma unroll
+        for (int gt = 0; gt < 3; ++gt) {
+            const int w0 = gt * 2 + (u >> 4);
+            const int e0 = s_e[(((w0 * 3 + (c >> 4)) * 16 + (c & 15)) * 16 + (u & 15))];
+            const int e1 = s_e[((((6 + w0) * 3 + (c >> 4)) * 16 + (c & 15)) * 16 + (u & 15))];
+            if (GH_PRE) {
+                float y = (float)(e0 + e1) * cx;
+                if (a.bx) y = y + bxv[e][gt];
+                gx[gt] = y;
+                gh[gt] = bhv[e][gt];
+            } else {
+                float y = (float)e0 * cx;
+                if (a.bx) y = y + bxv[e][gt];
+                gx[gt] = y;
+                float z = (float)e1 * ch;
+                if (a.bh) z = z + bhv[e][gt];
+                gh[gt] = z;
+            }
+        }
+        hn[e] = gru_gates(gx, gh, hpv[e]);
+        if (col < n) a.h_out[(size_t)col * a.ldo + unit] = hn[e];
+    }
+    if (!a.q1) return;
+
+    // ---- codes: this block's maxima out, the column group's in ----
+    unsigned *mine = a.xw + (size_t)a.region * GP_REGION_WORDS + (size_t)cg * 32 * GP_SLOTS;
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int pr = e * NT + tid, c = pr >> 5, col = c0 + c;
+        float m = col < n ? fmaxf(0.0f, fabsf(hn[e])) : 0.0f;
+        // over the 32 lanes that share the slot
+        m = fmaxf(m, __int_as_float(dpp_mov_i<DPP_XOR1>(__float_as_int(m))));
+        m = fmaxf(m, __int_as_float(dpp_mov_i<DPP_XOR2>(__float_as_int(m))));
+        m = fmaxf(m, __int_as_float(dpp_mov_i<DPP_HALF_MIRROR>(__float_as_int(m))));
+        m = fmaxf(m, __int_as_float(dpp_mov_i<DPP_MIRROR>(__float_as_int(m))));
+        m = fmaxf(m, __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(m), SWZ_XOR16)));
+        if ((lane & 31) == 0)
+            __hip_atomic_store(mine + ug * GP_SLOTS + c, __float_as_uint(m) + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    {
+        // thread t polls words t and t + NT of the group's gridDim.x * 48
+        const int nw = (int)gridDim.x * GP_SLOTS;
+        unsigned w0 = tid < nw ? 0u : 1u, w1 = tid + NT < nw ? 0u : 1u;
+        bool ok = false;
+        for (int spin = 0; spin < a.spin_limit; ++spin) {
+            if (!w0) w0 = __hip_atomic_load(mine + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (!w1) w1 = __hip_atomic_load(mine + NT + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (w0 && w1) { ok = true; break; }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        if (!ok) __hip_atomic_store(a.wait_err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_mx[tid] = w0 ? __uint_as_float(w0 - 1u) : 0.0f;
+        s_mx[NT + tid] = w1 ? __uint_as_float(w1 - 1u) : 0.0f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int pr = e * NT + tid, c = pr >> 5, u = pr & 31, col = c0 + c, unit = u0 + u;
+        float m = 0.0f;
+        for (int g2 = 0; g2 < (int)gridDim.x; ++g2) m = fmaxf(m, s_mx[g2 * GP_SLOTS + c]);
+        float scale, inv;
+        q8_scale_of(m, scale, inv);
+        const int8_t code = (int8_t)(q8_pack2(hn[e], 0.0f, inv) & 0xff);
+        if (col < n) {
+            a.q1[(size_t)col * a.ld1 + unit] = code;
+            if (a.q2) a.q2[(size_t)col * a.ld2 + unit] = code;
+            if (ug == 0 && u == 0) {
+                a.s1[col] = scale;
+                if (a.q2) a.s2[col] = scale;
+            }
+        }
+    }
+}
+
+// Whether the one-launch panel GRU takes this shape (rows of 512 + 1024 bytes for both products, or rows of
+// 2048 bytes for the input product alone; H a multiple of 32, at most 1024; code rows of exactly H bytes), and,
+// where codes are wanted (its blocks then wait for each other), whether the context allows such kernels
+// and the device holds the whole grid at once.
+bool q8i_gru_panel_ok(q8_ctx *ctx, const q8_gru_weights *g, bool gh_pre, int n, int ldp, int ldo, bool codes, int ld1, int ld2, bool have_q2)
+{
+    const int H = g->Wh.cols;
+    if (H % GP_UNITS || H > 1024 || n < 1 || n > Q8_MAX_COLS) return false;
+    if (ldp % 4 || ldo % 4) return false;
+    if (g->Wx.rows != 3 * H || (size_t)3 * H * g->Wx.ld >= (1u << 31) || (size_t)n * g->Wx.ld >= (1u << 31)) return false;
+    if (gh_pre ? g->Wx.ld != 2048 : (g->Wx.ld != 512 || g->Wh.ld != 1024 || g->Wh.rows != 3 * H)) return false;
+    if (!codes) return true;
+    if (ld1 != H || (have_q2 && ld2 != H) || !ctx->att_split) return false;
+    const int ncg = (n + GP_SLOTS - 1) / GP_SLOTS;
+    if (ncg > GP_MAX_CG) return false;
+    static int capacity[2] = {-1, -1};
+    const int v = gh_pre ? 1 : 0;
+    if (capacity[v] < 0) {
+        int per_cu = 0, dev = 0, cus = 0;
+        const size_t smem = (size_t)GP_SLOTS * (gh_pre ? 2048 + 16 : 512 + 16 + 1024 + 16) + (size_t)GP_WAVES * 3 * 256 * sizeof(int);
+        hipError_t e = gh_pre ? hipFuncSetAttribute((const void *)gru_panel_kernel<16, 16, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem)
+                              : hipFuncSetAttribute((const void *)gru_panel_kernel<8, 16, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e == hipSuccess)
+            e = gh_pre ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gru_panel_kernel<16, 16, true>, 64 * GP_WAVES, smem)
+                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gru_panel_kernel<8, 16, false>, 64 * GP_WAVES, smem);
+        if (e == hipSuccess) e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) { (void)hipGetLastError(); return false; }
+        capacity[v] = per_cu * cus;
+    }
+    return (H / GP_UNITS) * ncg <= capacity[v];
+}
+
+// region: which of the two sets of exchange words this launch uses (0: GRU r of a decoder step and single
+// transitions, 1: GRU q), the other being cleared by it.
+q8_status q8i_gru_panel(q8_ctx *ctx, const q8_gru_weights *g, const int8_t *xq, const float *xs, const int8_t *hq,
+                        const float *hs, const float *gh_pre, const float *h_prev, int ldp, float *h_out, int ldo, int n,
+                        int8_t *q1, int ld1, float *s1, int8_t *q2, int ld2, float *s2, int region)
+{
+    GruPanelArgs a;
+    a.Wx = g->Wx.data; a.Wh = g->Wh.data; a.bx = g->bx; a.bh = g->bh;
+    a.Wxt = g->Wx.tiles; a.Wht = g->Wh.tiles;
+    a.xq = xq; a.hq = hq; a.xs = xs; a.hs = hs; a.gh_pre = gh_pre; a.h_prev = h_prev; a.h_out = h_out;
+    a.q1 = q1; a.q2 = q2; a.s1 = s1; a.s2 = s2;
+    a.xw = (unsigned *)(ctx->ws + Q8_WS_GRUP_XCHG);
+    a.wait_err = (unsigned *)(ctx->ws + Q8_WS_ATT_ERR);
+    a.region = region ? 1 : 0; a.spin_limit = ctx->att_spin_limit;
+    a.H = g->Wh.cols; a.n = n; a.ldx = g->Wx.ld; a.ldh = g->Wh.ld; a.ldp = ldp; a.ldo = ldo; a.ld1 = ld1; a.ld2 = q2 ? ld2 : 0;
+    a.wx_scale = g->Wx.scale; a.wh_scale = g->Wh.scale;
+    const dim3 grid(a.H / GP_UNITS, (n + GP_SLOTS - 1) / GP_SLOTS);
+    if (q1) {
+        // the region this launch uses must be clear, and the launch clears the other one for its own unit
+        // groups: anything beyond that (a launch before this one with more unit groups, or two launches in
+        // a row on one region) is cleared here
+        const int r = a.region, ugs = (int)grid.x;
+        q8_status st = Q8_OK;
+        if (ctx->grup_used[r]) st = q8i_fill_u32(ctx, a.xw + (size_t)r * GP_REGION_WORDS, GP_REGION_WORDS, 0u);
+        if (!st && ctx->grup_used[1 - r] > ugs) st = q8i_fill_u32(ctx, a.xw + (size_t)(1 - r) * GP_REGION_WORDS, GP_REGION_WORDS, 0u);
+        if (st) return st;
+        ctx->grup_used[1 - r] = 0;
+        ctx->grup_used[r] = ugs;
+    }
+    const size_t e_bytes = (size_t)GP_WAVES * 3 * 256 * sizeof(int);
+    static bool attr_set[2] = {false, false};
+    if (gh_pre) {
+        const size_t smem = (size_t)GP_SLOTS * (a.ldx + 16) + e_bytes;
+        if (!attr_set[1]) {
+            const hipError_t e = hipFuncSetAttribute((const void *)gru_panel_kernel<16, 16, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "panel GRU kernel: %s", hipGetErrorString(e));
+            attr_set[1] = true;
+        }
+        Q8_LAUNCH(ctx, Q8_KERNEL_GRU, (gru_panel_kernel<16, 16, true>), grid, dim3(64 * GP_WAVES), smem, a);
+    } else {
+        const size_t smem = (size_t)GP_SLOTS * (a.ldx + 16 + a.ldh + 16) + e_bytes;
+        if (!attr_set[0]) {
+            const hipError_t e = hipFuncSetAttribute((const void *)gru_panel_kernel<8, 16, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "panel GRU kernel: %s", hipGetErrorString(e));
+            attr_set[0] = true;
+        }
+        Q8_LAUNCH(ctx, Q8_KERNEL_GRU, (gru_panel_kernel<8, 16, false>), grid, dim3(64 * GP_WAVES), smem, a);
+    }
+    return q8i_launch_check(ctx, "panel GRU");
+}
+
 template <int N, int MODE>
 static void launch_gru_nm(q8_ctx *ctx, const GruJobs &jobs, int njobs, int blocks, size_t smem, int ch, bool xpre)
 {

@@ -17,19 +17,19 @@
 #endif
 
 // Workspace header, zeroed by q8_create and zero again after every call that uses it: one attention
-// arrival counter per hypothesis in [0, 2048), 256 bytes apart; scratch slots (max bits, scale) at
-// 6144; the flags of waits that gave up; from 8192 the exchange words of the attention kernel without
+// arrival counter per hypothesis in [0, 4096); scratch slots (max bits, scale) at 6144; the flags of waits that gave up; from 8192 the exchange words of the attention kernel without
 // a finishing block (2 KiB per hypothesis), at 24576 those of the selection kernel that runs the
-// search step.
+// search step, from 32768 those of the one-launch panel GRU.
 #define Q8_MAX_BEAM 8
 #define Q8_MAX_COLS 1024            // vectors of one batched call
-#define Q8_WS_HEADER 32768
+#define Q8_WS_HEADER 131072
 #define Q8_WS_SCRATCH_SLOT 6144
 #define Q8_WS_ENC_ERR 6208          // set to 1 by the one-launch encoder if a wait gave up (zeroed before each such launch)
 #define Q8_WS_ATT_ERR 6212          // the same for the attention kernel whose blocks wait for each other
 #define Q8_WS_ATT_XCHG 8192
 #define Q8_WS_ATT_XCHG_PER_HYP 2048
 #define Q8_WS_SELECT_XCHG 24576      // 128 words: the top-k entries on their way to the search step
+#define Q8_WS_GRUP_XCHG 32768        // 2 x 10752 words: partial maxima of the one-launch panel GRU (two regions that take turns)
 #define Q8_ENC_SPIN_DEFAULT (1 << 20)
 
 struct q8_ctx {
@@ -53,6 +53,9 @@ struct q8_ctx {
     // that form leaves its exchange words set; the GRU that follows it in the step clears them.  1 while
     // a launch's words are waiting for that (the next attention launch would clear them itself first).
     int att_words_set;
+    // one-launch panel GRU: unit groups whose exchange words a launch has left set in each of the two regions
+    // (0: the region is clear); the launch after it clears them, see q8i_gru_panel
+    int grup_used[2];
 };
 
 // Launch of a kernel of class `kind` (a Q8_KERNEL_* value).  While a profile of that class
@@ -180,6 +183,13 @@ q8_status q8i_gru_gates(q8_ctx *ctx, const float *gx, const float *gh, const flo
 bool q8i_gru_gates_q_ok(int H, int ldh, int ldo, int ld1, int ld2);
 q8_status q8i_gru_gates_q(q8_ctx *ctx, const float *gx, const float *gh, const float *h_prev, int ldh, float *h_out,
                           int ldo, int H, int n, int8_t *q1, int ld1, float *s1, int8_t *q2, int ld2, float *s2);
+// products, gates and the codes of the new states in one launch (panels; shapes: q8i_gru_panel_ok).  gh_pre NULL:
+// both products from the codes xq / hq; else the input product alone, the recurrent pre-activations given.
+// q1 NULL: no codes.  region 0 or 1: see the launcher.
+bool q8i_gru_panel_ok(q8_ctx *ctx, const q8_gru_weights *g, bool gh_pre, int n, int ldp, int ldo, bool codes, int ld1, int ld2, bool have_q2);
+q8_status q8i_gru_panel(q8_ctx *ctx, const q8_gru_weights *g, const int8_t *xq, const float *xs, const int8_t *hq,
+                        const float *hs, const float *gh_pre, const float *h_prev, int ldp, float *h_out, int ldo, int n,
+                        int8_t *q1, int ld1, float *s1, int8_t *q2, int ld2, float *s2, int region);
 // one time step of the batched encoder: phase 0 quantizes the previous states, phase 1 applies the gates
 q8_status q8i_encode_persistent(q8_ctx *ctx, const q8_gru_weights *fwd, const q8_gru_weights *bwd, const float *gxf,
                                 const float *gxb, int l, float *enc_h, unsigned long long *xchg, unsigned *err,

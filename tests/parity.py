@@ -31,12 +31,15 @@ def np_(t):
     return t.detach().cpu().numpy()
 
 
-def gpu_mat(q, ctx, W):
-    return q.q8_quantize_matrix(ctx, W)
+def gpu_mat(q, ctx, W, tiled=False):
+    """The quantized matrix; tiled: also its tile-packed copy, which the matrix-core products of
+    panels read when it is there (rows of whole 64-byte k steps only)."""
+    M = q.q8_quantize_matrix(ctx, W)
+    return q.q8_pack_tiles(ctx, M) if tiled and M.ld % 64 == 0 else M
 
 
-def gpu_gru(q, ctx, p, prefix):
-    return q.GruWeights(gpu_mat(q, ctx, p[prefix + ".Wx"]), gpu_mat(q, ctx, p[prefix + ".Wh"]),
+def gpu_gru(q, ctx, p, prefix, tiled=False):
+    return q.GruWeights(gpu_mat(q, ctx, p[prefix + ".Wx"], tiled), gpu_mat(q, ctx, p[prefix + ".Wh"], tiled),
                         ctx.f32(p[prefix + ".bx"]), ctx.f32(p[prefix + ".bh"]))
 
 

@@ -35,13 +35,14 @@ def _check_product(oracle, L, x_gpu, tap, j, what):
     return oracle.dequantize(acc, L.scale, xs, L.bias)
 
 
-@pytest.mark.parametrize("I,H,n", [(512, 1024, 9), (512, 1024, 70), (2048, 1024, 33), (36, 20, 12), (620, 1000, 17),
-                                   (256, 256, 130)])
-def test_gru_step_panel(q, ctx, oracle, I, H, n):
+@pytest.mark.parametrize("I,H,n,tiled", [(512, 1024, 9, False), (512, 1024, 70, False), (2048, 1024, 33, False), (36, 20, 12, False),
+                                         (620, 1000, 17, False), (256, 256, 130, False), (512, 1024, 70, True), (512, 1024, 145, True),
+                                         (2048, 1024, 33, True), (256, 256, 130, True), (1024, 1000, 20, True)])
+def test_gru_step_panel(q, ctx, oracle, I, H, n, tiled):
     p = synth.gru_cell(seed=0, I=I, H=H, n_batch=n)
     p["x"] = p["x"] * np.random.default_rng(n).uniform(0.1, 10, (n, 1)).astype(np.float32)
     g = oracle.QGru(p["Wx"], p["Wh"], p["bx"], p["bh"])
-    G = q.GruWeights(gpu_mat(q, ctx, p["Wx"]), gpu_mat(q, ctx, p["Wh"]), ctx.f32(p["bx"]), ctx.f32(p["bh"]))
+    G = q.GruWeights(gpu_mat(q, ctx, p["Wx"], tiled), gpu_mat(q, ctx, p["Wh"], tiled), ctx.f32(p["bx"]), ctx.f32(p["bh"]))
     x, h0 = ctx.f32(p["x"]), ctx.f32(p["h_prev"])
     h, taps = q.gru_step_q8(ctx, G, x, h0, taps=True)
     for j in range(0, n, max(1, n // 7)):
@@ -109,13 +110,18 @@ def test_output_layer_panel_with_readout(q, ctx, oracle):
     assert_same(r5["topk_idx"], np_(r["topk_idx"])[:5]); assert_same(r5["topk_logp"], np_(r["topk_logp"])[:5])
 
 
-@pytest.mark.parametrize("E,H,A,lens,beam", [(512, 1024, 1024, (30, 11, 50), 5), (36, 40, 28, (7, 1, 3, 12), 3),
-                                             (64, 64, 64, (5, 300), 2), (512, 1024, 1024, (9,) * 26, 5)])
-def test_cgru_decoder_step_batch(q, ctx, oracle, E, H, A, lens, beam):
+@pytest.mark.parametrize("E,H,A,lens,beam,tiled", [(512, 1024, 1024, (30, 11, 50), 5, False), (36, 40, 28, (7, 1, 3, 12), 3, False),
+                                                   (64, 64, 64, (5, 300), 2, True), (512, 1024, 1024, (9,) * 26, 5, False),
+                                                   (512, 1024, 1024, (9,) * 26, 5, True), (512, 1024, 1024, (30, 11, 50), 5, True),
+                                                   (512, 1024, 1024, (4,) * 67, 3, True)])
+def test_cgru_decoder_step_batch(q, ctx, oracle, E, H, A, lens, beam, tiled):
+    """tiled: the weights also carry their tile-packed copies, which the panel's matrix-core kernels read;
+    the single-sentence calls it is compared with read the rows."""
     S, L, n = len(lens), sum(lens), len(lens) * beam
     p = synth.cgru_step(seed=1, E=E, H=H, A=A, l=L, n_beam=n)
     m = oracle.OracleModel(p)
-    w = q.CgruWeights(gpu_gru(q, ctx, p, "dec_r"), gpu_mat(q, ctx, p["att.U"]), ctx.f32(p["att.v"]), gpu_gru(q, ctx, p, "dec_q"))
+    w = q.CgruWeights(gpu_gru(q, ctx, p, "dec_r", tiled), gpu_mat(q, ctx, p["att.U"], tiled), ctx.f32(p["att.v"]),
+                      gpu_gru(q, ctx, p, "dec_q", tiled))
     enc_h = ctx.f32(p["enc_h"])
     P = q.q8_gemm_narrow(ctx, gpu_mat(q, ctx, p["att.W"]), enc_h, ctx.f32(p["att.b"]))
     P_ref = m.attention_precompute(p["enc_h"])
