@@ -355,3 +355,70 @@ def test_codes_handed_from_the_batched_search_step_to_the_next_step(q, ctx, orac
             assert_same(next(gi), ref[6 * step + i], "step %d, output %d" % (step, i))
     for a, b in zip(got_res, ref_res):
         assert a[0].tolist() == b[0].tolist() and a[1:] == b[1:]
+
+
+def _batched_step_with_codes(q, ctx, m, P, enc_h, off, beam, l, y, s):
+    n = y.shape[0]
+    codes = (q.Codes(ctx, n, m.dec.r.Wx.ld), q.Codes(ctx, n, m.dec.q.Wx.ld), q.Codes(ctx, n, m.ro.W_s.ld))
+    r = q.cgru_decoder_step_batch_q8(ctx, m.dec, P, enc_h, off, beam, l, y, s, codes=codes)
+    return {"s_mid": np_(r["s_mid"]), "s": np_(r["s"]), "ctx": np_(r["ctx"]), "alpha": np_(r["alpha"]),
+            "sq": np_(codes[2].q), "ss": np_(codes[2].scale), "cq": np_(codes[1].q), "cs": np_(codes[1].scale)}
+
+
+def _panel_case(q, ctx, S, beam, l, seed=31):
+    p = synth.full_model(seed=seed)
+    m = q.Model.from_params(ctx, p)
+    E, H = m.E_tgt.shape[1], m.dec.r.H
+    n = S * beam
+    rng = np.random.default_rng(S + l)
+    enc_h = ctx.f32(rng.standard_normal((S * l, 2 * H)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    off = torch.arange(0, (S + 1) * l, l, dtype=torch.int32, device=ctx.device)
+    y = ctx.f32(rng.standard_normal((n, E)).astype(np.float32))
+    s = ctx.f32((rng.standard_normal((n, H)) * rng.uniform(0.05, 3.0, (n, 1))).astype(np.float32))
+    return m, P, enc_h, off, y, s
+
+
+@pytest.mark.parametrize("S,beam,l", [(2, 5, 6), (64, 5, 12), (67, 5, 4), (12, 8, 9), (70, 5, 3)])
+def test_panel_gru_in_one_launch_equals_products_and_gates_apart(q, ctx, oracle, S, beam, l):
+    """The transitions of a batched step as one kernel each, whose blocks exchange their partial maxima for the
+    codes of the new states (the default where the grid fits the device: up to 336 slots), against the same
+    step with that form switched off (matrix-core products, then a gates kernel): the same bits, states and
+    codes.  70 sentences x 5 = 350 slots is past the limit and runs the second form either way."""
+    m, P, enc_h, off, y, s = _panel_case(q, ctx, S, beam, l)
+    one = _batched_step_with_codes(q, ctx, m, P, enc_h, off, beam, l, y, s)
+    again = _batched_step_with_codes(q, ctx, m, P, enc_h, off, beam, l, y, s)
+    try:
+        q.q8_attention_options(ctx, exchange=False)
+        apart = _batched_step_with_codes(q, ctx, m, P, enc_h, off, beam, l, y, s)
+    finally:
+        q.q8_attention_options(ctx, exchange=True)
+    q.q8_encode_check(ctx)
+    for key in one:
+        assert_same(one[key], apart[key], key + ": one launch against products and gates apart")
+        assert_same(again[key], one[key], key + ": second call (exchange words cleared by the launch between)")
+    j = one["s"].shape[0] - 1
+    sq, ss = oracle.quantize(one["s"][j])
+    assert_same(one["sq"][j, :sq.shape[0]], sq, "codes of the last slot's new state")
+    assert float(one["ss"][j]) == float(ss)
+
+
+def test_panel_gru_wait_that_gives_up_is_reported_and_the_next_step_is_good(q, ctx, oracle):
+    """With a bound of one poll a block of the one-launch panel GRU gives up at once: the kernel still ends,
+    q8_encode_check reports it once and clears the exchange words, and the next step with the default bound
+    gives the first one's bits again."""
+    m, P, enc_h, off, y, s = _panel_case(q, ctx, 40, 5, 5)
+    good = _batched_step_with_codes(q, ctx, m, P, enc_h, off, 5, 5, y, s)
+    q.q8_encode_check(ctx)
+    try:
+        q.q8_attention_options(ctx, exchange=True, spin_limit=1)
+        _batched_step_with_codes(q, ctx, m, P, enc_h, off, 5, 5, y, s)
+        with pytest.raises(q.Q8Error):
+            q.q8_encode_check(ctx)
+    finally:
+        q.q8_attention_options(ctx, exchange=True, spin_limit=0)
+    q.q8_encode_check(ctx)
+    again = _batched_step_with_codes(q, ctx, m, P, enc_h, off, 5, 5, y, s)
+    q.q8_encode_check(ctx)
+    for key in good:
+        assert_same(again[key], good[key], key + " after the abandoned run")
