@@ -69,7 +69,10 @@ typedef struct q8_ctx q8_ctx;
 
 /* An int8 weight matrix: device data, host-side scale (known at load time).  `tiles` is
  * an optional second copy of the same codes in the matrix-core streaming order made by
- * q8_pack_tiles (NULL = none); output_logits_q8 reads it instead of `data` when present. */
+ * q8_pack_tiles (NULL = none).  Where it is present the matrix-core kernels read it instead of
+ * `data`: output_logits_q8, and every product of a panel of more than 8 vectors (GRU, attention
+ * and readout products of batched decoding, the encoder's input products).  The kernels for at
+ * most 8 vectors always read `data`, so a matrix used both ways keeps both copies. */
 typedef struct {
     const int8_t *data;
     int rows, cols, ld;
@@ -123,7 +126,7 @@ size_t q8_workspace_bytes(int max_n, int max_l, int max_rows, int max_ld);
 
 /* Creates a context bound to hip_stream (a hipStream_t; NULL = the default stream)
  * and to the caller's device workspace (256-byte aligned).  Allocates host memory
- * only.  The first 32 KiB of the workspace (at least that many bytes are required) are
+ * only.  The first 128 KiB of the workspace (at least that many bytes are required) are
  * zeroed on the stream here and are left zero after every call by the kernels that use
  * them as arrival counters and exchange words. */
 q8_status q8_create(q8_ctx **out, void *hip_stream, void *workspace, size_t workspace_bytes);
@@ -136,11 +139,12 @@ const char *q8_last_error(const q8_ctx *ctx);
 q8_status q8_quantize_matrix(q8_ctx *ctx, const float *W, int rows, int cols, int ld_in,
                              int8_t *Wq_out, int ld_out, float *scale_out_host);
 
-/* Load-time re-ordering of a quantized matrix for the vocabulary layer (a layout choice of
+/* Load-time re-ordering of a quantized matrix for the matrix-core kernels (a layout choice of
  * this library, not an operation of the paper): rows are grouped in tiles of 16 and each
  * 16 x 64-byte block is stored as one contiguous KiB in the lane order of
  * v_mfma_i32_16x16x64_i8's A operand (lane = 16 * (k / 16 % 4) + row % 16, 16 bytes per lane),
- * so that every wave-wide load of the streaming pass is one contiguous KiB.  Rows past
+ * so that every wave-wide load of a matrix-core operand is one contiguous KiB (16 pieces of
+ * rows that lie ld bytes apart arrive about 2.5 times more slowly).  Rows past
  * `rows` in the last tile are zero.  Requires ld % 64 == 0; tiles_out holds
  * q8_tiles_bytes(rows, ld) bytes, 16-byte aligned.  Enqueued on the stream. */
 size_t q8_tiles_bytes(int rows, int ld);
@@ -302,12 +306,17 @@ q8_status q8_encode_check(q8_ctx *ctx);
  * those of later calls are not valid until q8_encode_check (above) has reported it, once, and put
  * the exchange words in the workspace header back to zero.  The same bound and the same report
  * cover the one wait of output_logits_beam_q8, whose selection kernel hands every hypothesis' k
- * best to the block that runs the search step.
+ * best to the block that runs the search step, and the GRU transitions of
+ * cgru_decoder_step_batch_q8 at up to 336 hypothesis slots (rows of 512 / 1024 / 2048 bytes, H a
+ * multiple of 32 up to 1024): with exchange != 0 each is one kernel (products, gates, codes of the
+ * new states) whose blocks exchange the largest magnitudes of their parts of a state; with
+ * exchange == 0, and for every other shape, products and gates are separate launches.  Same bits.
  * Contexts whose decoder steps may run at the same time on one device (different streams): the
  * blocks of the exchange form wait for each other, so the attention grids that can be in flight
  * together must fit the device together (l n_beam blocks of 1024 threads each, two per compute
  * unit); give the contexts beyond that exchange = 0.  The same holds for q8_encoder_options'
- * one-launch recurrence (2 H / 8 blocks of 512 threads). */
+ * one-launch recurrence (2 H / 8 blocks of 512 threads) and for the batched step's one-kernel
+ * GRU (H / 32 x ceil(slots / 48) blocks of 768 threads, one per compute unit). */
 q8_status q8_attention_options(q8_ctx *ctx, int exchange, int spin_limit);
 
 /* ---- search (Section 3 only says the beam is smaller than 8; these are the rules) ----

@@ -667,7 +667,8 @@ static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8
             }
             if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
             if (!have_pre) TRY(q8i_quantize_jobs(ctx, qj, 3, n));
-            TRY(q8i_gemm_jobs(ctx, gj, 3, n));
+            if (q8i_gemm_ksplit3_ok(gj, n)) TRY(q8i_gemm_ksplit3(ctx, gj, n));
+            else TRY(q8i_gemm_jobs(ctx, gj, 3, n));
             TRY(q8i_readout_combine(ctx, gj[0].Y, gj[1].Y, gj[2].Y, ro->b_t, R, n, t, W_out->ld, tq, tsc, taps4 ? taps4 + 3 : nullptr));
         } else {
             if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");

@@ -360,6 +360,178 @@ __global__ __launch_bounds__(256) void gemm_resident_kernel(GemmJobs jobs)
     }
 }
 
+// ===================================================== three products, k split over waves ==
+// The readout's three partial products (Eq. 2's first layer: W_s q(s), W_y q(y), W_c q(H_t), 512 rows
+// each, rows of 1024 / 512 / 2048 bytes) for a panel of slots in one K-resident launch.  The block
+// kernel above needs ten staged steps for the longest rows and fills 120 blocks (10 us); here block
+// (rg, cg) owns rows 32 rg .. 32 rg + 31 of all three matrices and slots 32 cg .. 32 cg + 31, whose codes
+// for all three products sit in LDS (3632 bytes per slot), and the 3584 k bytes are cut into seven
+// chunks of 512: wave (ut, chunk) multiplies one tile of 16 rows over one chunk against the two slot
+// tiles, every load requested up front.  The exact int32 partial sums of a product's chunks meet in LDS
+// and are dequantized once, as the block kernel does it.  Rows of other lengths take the block kernel.
+#define KS3_ROWS 32
+#define KS3_SLOTS 32
+#define KS3_WAVES 14
+struct Ksplit3Args {
+    const int8_t *W[3], *Wt[3];    // [R x ld], and tile-packed or NULL
+    const int8_t *xq[3];           // codes [n x ld]
+    const float *xs[3];            // [n]
+    float *Y[3];                   // [n x ldy]
+    float w_scale[3];
+    int R, n, ldy;
+};
+
+__global__ __launch_bounds__(64 * KS3_WAVES) void gemm_ksplit3_kernel(Ksplit3Args a)
+{
+    extern __shared__ __align__(16) int8_t s_k3[];
+    constexpr int NT = 64 * KS3_WAVES;
+    constexpr int LD0 = 1024, LD1 = 512, LD2 = 2048;
+    constexpr int P0 = LD0 + 16, P1 = LD1 + 16, P2 = LD2 + 16;           // LDS pitches
+    int8_t *s_x0 = s_k3, *s_x1 = s_x0 + KS3_SLOTS * P0, *s_x2 = s_x1 + KS3_SLOTS * P1;
+    int *s_e = (int *)(s_x2 + KS3_SLOTS * P2);                           // [14 waves][2 slot tiles][16 slots][16 rows]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i = lane & 15, g = lane >> 4;
+    const int rg = blockIdx.x, cg = blockIdx.y, n = a.n, c0 = cg * KS3_SLOTS, r0 = rg * KS3_ROWS;
+
+    // ---- all loads up front (outside the arrays: zero) ----
+    constexpr int U0 = (KS3_SLOTS * LD0 / 16 + NT - 1) / NT, U1 = (KS3_SLOTS * LD1 / 16 + NT - 1) / NT, U2 = (KS3_SLOTS * LD2 / 16 + NT - 1) / NT;
+    const __amdgpu_buffer_rsrc_t rq0 = q8_rsrc(a.xq[0], (size_t)n * LD0), rq1 = q8_rsrc(a.xq[1], (size_t)n * LD1), rq2 = q8_rsrc(a.xq[2], (size_t)n * LD2);
+    v4i b0[U0], b1[U1], b2[U2];
+#pragma unroll
+    for (int u = 0; u < U0; ++u) {
+        const int p = u * NT + tid, slot = p / (LD0 / 16), piece = p - slot * (LD0 / 16);
+        const unsigned off = (p < KS3_SLOTS * LD0 / 16 && c0 + slot < n) ? (unsigned)(c0 + slot) * LD0 + 16u * piece : Q8_OOB;
+        b0[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rq0, (int)off, 0, 0));
+    }
+#pragma unroll
+    for (int u = 0; u < U1; ++u) {
+        const int p = u * NT + tid, slot = p / (LD1 / 16), piece = p - slot * (LD1 / 16);
+        const unsigned off = (p < KS3_SLOTS * LD1 / 16 && c0 + slot < n) ? (unsigned)(c0 + slot) * LD1 + 16u * piece : Q8_OOB;
+        b1[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rq1, (int)off, 0, 0));
+    }
+#pragma unroll
+    for (int u = 0; u < U2; ++u) {
+        const int p = u * NT + tid, slot = p / (LD2 / 16), piece = p - slot * (LD2 / 16);
+        const unsigned off = (p < KS3_SLOTS * LD2 / 16 && c0 + slot < n) ? (unsigned)(c0 + slot) * LD2 + 16u * piece : Q8_OOB;
+        b2[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rq2, (int)off, 0, 0));
+    }
+    // this wave: row tile ut, chunk ch -> product j, first k byte kbase
+    const int ut = wave / 7, ch = wave % 7;
+    const int j = ch < 2 ? 0 : ch == 2 ? 1 : 2;
+    const int kbase = 512 * (ch < 2 ? ch : ch == 2 ? 0 : ch - 3);
+    const int ldw = j == 0 ? LD0 : j == 1 ? LD1 : LD2;
+    const int8_t *wt = a.Wt[j];
+    const __amdgpu_buffer_rsrc_t rw = q8_rsrc(wt ? wt : a.W[j], (size_t)a.R * ldw);
+    const int row0 = r0 + 16 * ut;                                       // R % 32 == 0: a whole tile inside the matrix
+    v4i av[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        unsigned off = (unsigned)(row0 + i) * (unsigned)ldw + (unsigned)(kbase + 64 * s + 16 * g);
+        if (wt) off = (((unsigned)(row0 >> 4) * (unsigned)(ldw >> 6) + (unsigned)((kbase >> 6) + s)) << 10) + 16u * lane;
+        av[s] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rw, (int)off, 0, 0));
+    }
+    // dequantization factors of the (slot, row) pairs tid and tid + NT of 32 x 32
+    const __amdgpu_buffer_rsrc_t rs0 = q8_rsrc(a.xs[0], (size_t)n * 4), rs1 = q8_rsrc(a.xs[1], (size_t)n * 4), rs2 = q8_rsrc(a.xs[2], (size_t)n * 4);
+    float xs[2][3];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int pr = e * NT + tid, col = c0 + (pr >> 5);
+        const int off = (int)((pr < KS3_SLOTS * KS3_ROWS && col < n) ? (unsigned)col * 4u : Q8_OOB);
+        xs[e][0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs0, off, 0, 0));
+        xs[e][1] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs1, off, 0, 0));
+        xs[e][2] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs2, off, 0, 0));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- codes into LDS ----
+#pragma unroll
+    for (int u = 0; u < U0; ++u) {
+        const int p = u * NT + tid, slot = p / (LD0 / 16), piece = p - slot * (LD0 / 16);
+        if (p < KS3_SLOTS * LD0 / 16) *(v4i *)(s_x0 + slot * P0 + 16 * piece) = b0[u];
+    }
+#pragma unroll
+    for (int u = 0; u < U1; ++u) {
+        const int p = u * NT + tid, slot = p / (LD1 / 16), piece = p - slot * (LD1 / 16);
+        if (p < KS3_SLOTS * LD1 / 16) *(v4i *)(s_x1 + slot * P1 + 16 * piece) = b1[u];
+    }
+#pragma unroll
+    for (int u = 0; u < U2; ++u) {
+        const int p = u * NT + tid, slot = p / (LD2 / 16), piece = p - slot * (LD2 / 16);
+        if (p < KS3_SLOTS * LD2 / 16) *(v4i *)(s_x2 + slot * P2 + 16 * piece) = b2[u];
+    }
+    __syncthreads();
+
+    // ---- products ----
+    v4i acc[2] = {(v4i){0, 0, 0, 0}, (v4i){0, 0, 0, 0}};
+    {
+        const int pitch = j == 0 ? P0 : j == 1 ? P1 : P2;
+        const int8_t *bp = (j == 0 ? s_x0 : j == 1 ? s_x1 : s_x2) + i * pitch + kbase + 16 * g;
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const v4i bv = *(const v4i *)(bp + t * 16 * pitch + 64 * s);
+                acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[s], bv, acc[t], 0, 0, 0);
+            }
+    }
+    // lane (i, g) holds rows 4 g + r, r = 0..3, of slot i of each tile
+#pragma unroll
+    for (int t = 0; t < 2; ++t) *(v4i *)(s_e + (((wave * 2 + t) * 16 + i) * 16 + 4 * g)) = acc[t];
+    __syncthreads();
+
+    // ---- chunks summed, dequantized, stored: consecutive threads, consecutive rows of a slot ----
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int pr = e * NT + tid;
+        if (pr >= KS3_SLOTS * KS3_ROWS) break;
+        const int c = pr >> 5, r = pr & 31, col = c0 + c;
+        const int at = ((c >> 4) * 16 + (c & 15)) * 16 + (r & 15), w0 = (r >> 4) * 7;        // wave (ut, chunk) = 7 ut + chunk
+        const int e0 = s_e[(w0 + 0) * 512 + at] + s_e[(w0 + 1) * 512 + at];
+        const int e1 = s_e[(w0 + 2) * 512 + at];
+        const int e2 = ((s_e[(w0 + 3) * 512 + at] + s_e[(w0 + 4) * 512 + at]) + s_e[(w0 + 5) * 512 + at]) + s_e[(w0 + 6) * 512 + at];
+        if (col < n) {
+            const size_t o = (size_t)col * a.ldy + r0 + r;
+            a.Y[0][o] = (float)e0 * (a.w_scale[0] * xs[e][0]);
+            a.Y[1][o] = (float)e1 * (a.w_scale[1] * xs[e][1]);
+            a.Y[2][o] = (float)e2 * (a.w_scale[2] * xs[e][2]);
+        }
+    }
+}
+
+// Whether the three products W[u] . xq[u] (no bias, no taps, plain output at pitch ldy) take the kernel above.
+bool q8i_gemm_ksplit3_ok(const q8i_gemm_job *d, int n)
+{
+    const int R = d[0].W->rows;
+    if (R % KS3_ROWS || n < 1 || (R / KS3_ROWS) * ((n + KS3_SLOTS - 1) / KS3_SLOTS) > 256) return false;
+    static const int want[3] = {1024, 512, 2048};
+    for (int u = 0; u < 3; ++u) {
+        if (d[u].W->rows != R || d[u].W->ld != want[u] || d[u].bias || d[u].tap_acc || d[u].part_max || d[u].tiled || d[u].row_scale ||
+            d[u].ldy != d[0].ldy || (size_t)n * want[u] >= (1u << 31))
+            return false;
+    }
+    return true;
+}
+
+q8_status q8i_gemm_ksplit3(q8_ctx *ctx, const q8i_gemm_job *d, int n)
+{
+    Ksplit3Args a;
+    for (int u = 0; u < 3; ++u) {
+        a.W[u] = d[u].W->data; a.Wt[u] = d[u].W->tiles; a.xq[u] = d[u].xq; a.xs[u] = d[u].xscale; a.Y[u] = d[u].Y;
+        a.w_scale[u] = d[u].W->scale;
+    }
+    a.R = d[0].W->rows; a.n = n; a.ldy = d[0].ldy;
+    const size_t smem = (size_t)KS3_SLOTS * (1024 + 16 + 512 + 16 + 2048 + 16) + (size_t)KS3_WAVES * 2 * 1024;
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute((const void *)gemm_ksplit3_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "three-product kernel: %s", hipGetErrorString(e));
+        attr_set = true;
+    }
+    Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, gemm_ksplit3_kernel, dim3(a.R / KS3_ROWS, (n + KS3_SLOTS - 1) / KS3_SLOTS), dim3(64 * KS3_WAVES), smem, a);
+    return q8i_launch_check(ctx, "three products");
+}
+
 // ================================================================ vocabulary panel ==
 // The vocabulary product for a panel of hypothesis slots (many sentences side by side).  Unlike
 // the block kernel above, a block keeps its share of the vectors' codes in LDS for its whole

@@ -113,7 +113,8 @@ def test_output_layer_panel_with_readout(q, ctx, oracle):
 @pytest.mark.parametrize("E,H,A,lens,beam,tiled", [(512, 1024, 1024, (30, 11, 50), 5, False), (36, 40, 28, (7, 1, 3, 12), 3, False),
                                                    (64, 64, 64, (5, 300), 2, True), (512, 1024, 1024, (9,) * 26, 5, False),
                                                    (512, 1024, 1024, (9,) * 26, 5, True), (512, 1024, 1024, (30, 11, 50), 5, True),
-                                                   (512, 1024, 1024, (4,) * 67, 3, True)])
+                                                   (512, 1024, 1024, (4,) * 67, 3, True), (512, 1024, 1024, (3, 5, 2) * 20, 5, True),
+                                                   (64, 64, 64, (2, 7, 1) * 30, 3, False), (64, 64, 64, (3,) * 130, 7, False)])
 def test_cgru_decoder_step_batch(q, ctx, oracle, E, H, A, lens, beam, tiled):
     """tiled: the weights also carry their tile-packed copies, which the panel's matrix-core kernels read;
     the single-sentence calls it is compared with read the rows."""
