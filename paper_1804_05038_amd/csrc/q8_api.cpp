@@ -582,7 +582,8 @@ q8_status cgru_decoder_step_batch_loop_q8(q8_ctx *ctx, const q8_cgru_weights *w,
     }
     const q8i_gemm_job gj[2] = {{&w->att_U, mq_u, ms_u, nullptr, a, A, nullptr, nullptr, nullptr, 0},
                                 {&w->q.Wh, mq_h, ms_h, w->q.bh, ghq, 3 * H, nullptr, nullptr, nullptr, 0}};
-    TRY(q8i_gemm_jobs(ctx, gj, 2, n));
+    if (q8i_gemm_ksplit2_ok(gj, 2, n)) TRY(q8i_gemm_ksplit2(ctx, gj, 2, n));
+    else TRY(q8i_gemm_jobs(ctx, gj, 2, n));
     // Eq. 5-6 per hypothesis, against the positions of its own sentence
     int have_codes = 0;
     TRY(q8i_attention(ctx, P, enc_h, max_l, A, C, a, w->att_v, n, e, alpha_out, ctx_out, sent_off, beam, cq, cqs, w->q.Wx.ld, &have_codes));

@@ -532,6 +532,136 @@ q8_status q8i_gemm_ksplit3(q8_ctx *ctx, const q8i_gemm_job *d, int n)
     return q8i_launch_check(ctx, "three products");
 }
 
+// ============================================ rows of 1024 bytes, k split over two waves ==
+// Products with rows of exactly 1024 bytes over a panel of at most 336 slots (u(s') of Eq. 6 and the
+// recurrent product of GRU q, which share a launch): block (rg, cg, job) owns 128 rows and 48 slots;
+// wave (row tile, half) multiplies 16 rows over 512 k bytes against the three slot tiles, the two exact
+// int32 halves meet in LDS and are dequantized once, and a slot's 128 results leave as 512 contiguous
+// bytes.  Against the 64 x 64 blocks of gemm_resident_kernel a compute unit takes in 178 KB instead of
+// 2 x 128 KB, and the results leave in whole lines.
+#define KS2_ROWS 128
+#define KS2_SLOTS 48
+struct Ksplit2Args {
+    GemmArgs j[2];
+};
+
+__global__ __launch_bounds__(1024) void gemm_ksplit2_kernel(Ksplit2Args jobs)
+{
+    extern __shared__ __align__(16) int8_t s_k2[];
+    constexpr int NT = 1024, LD = 1024, PITCH = LD + 16;
+    const GemmArgs &a = jobs.j[blockIdx.z];
+    if ((int)blockIdx.x * KS2_ROWS >= a.rows) return;            // the grid is sized for the larger job
+    int8_t *s_x = s_k2;
+    int *s_e = (int *)(s_k2 + KS2_SLOTS * PITCH);                // [16 waves][3 slot tiles][16 slots][16 rows]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i = lane & 15, g = lane >> 4;
+    const int n = a.n, c0 = (int)blockIdx.y * KS2_SLOTS, r0 = (int)blockIdx.x * KS2_ROWS;
+
+    // ---- all loads up front ----
+    constexpr int UX = KS2_SLOTS * (LD / 16) / NT;              // 3 pieces per thread
+    static_assert(KS2_SLOTS * (LD / 16) % NT == 0, "pieces divide among the threads");
+    const __amdgpu_buffer_rsrc_t rq = q8_rsrc(a.xq, (size_t)n * LD);
+    v4i bq[UX];
+#pragma unroll
+    for (int u = 0; u < UX; ++u) {
+        const int p = u * NT + tid, slot = p / (LD / 16), piece = p - slot * (LD / 16);
+        const unsigned off = c0 + slot < n ? (unsigned)(c0 + slot) * LD + 16u * piece : Q8_OOB;
+        bq[u] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rq, (int)off, 0, 0));
+    }
+    const int rt = wave >> 1, half = wave & 1, kbase = 512 * half;
+    const __amdgpu_buffer_rsrc_t rw = q8_rsrc(a.Wt ? a.Wt : a.W, (size_t)a.rows * LD);      // rows % 128 == 0
+    const int row0 = r0 + 16 * rt;
+    v4i av[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+        unsigned off = (unsigned)(row0 + i) * (unsigned)LD + (unsigned)(kbase + 64 * s + 16 * g);
+        if (a.Wt) off = (((unsigned)(row0 >> 4) * (unsigned)(LD >> 6) + (unsigned)((kbase >> 6) + s)) << 10) + 16u * lane;
+        av[s] = __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(rw, (int)off, 0, 0));
+    }
+    // per (slot, row) pair tid + 1024 e, e = 0..5: row = pair % 128 is the same for all six
+    const int row = r0 + (tid & 127);
+    const __amdgpu_buffer_rsrc_t rs = q8_rsrc(a.xscale, (size_t)n * 4), rb = q8_rsrc(a.bias, a.bias ? (size_t)a.rows * 4 : 0);
+    const float bias = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, (int)((unsigned)row * 4u), 0, 0));
+    float xs[6];
+#pragma unroll
+    for (int e = 0; e < 6; ++e) {
+        const int col = c0 + ((e * NT + tid) >> 7);
+        xs[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, (int)(col < n ? (unsigned)col * 4u : Q8_OOB), 0, 0));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+#pragma unroll
+    for (int u = 0; u < UX; ++u) {
+        const int p = u * NT + tid, slot = p / (LD / 16), piece = p - slot * (LD / 16);
+        *(v4i *)(s_x + slot * PITCH + 16 * piece) = bq[u];
+    }
+    __syncthreads();
+
+    v4i acc[3] = {(v4i){0, 0, 0, 0}, (v4i){0, 0, 0, 0}, (v4i){0, 0, 0, 0}};
+    {
+        const int8_t *bp = s_x + i * PITCH + kbase + 16 * g;
+#pragma unroll
+        for (int s = 0; s < 8; ++s)
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {
+                const v4i bv = *(const v4i *)(bp + t * 16 * PITCH + 64 * s);
+                acc[t] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av[s], bv, acc[t], 0, 0, 0);
+            }
+    }
+#pragma unroll
+    for (int t = 0; t < 3; ++t) *(v4i *)(s_e + (((wave * 3 + t) * 16 + i) * 16 + 4 * g)) = acc[t];
+    __syncthreads();
+
+#pragma unroll
+    for (int e = 0; e < 6; ++e) {
+        const int pr = e * NT + tid, c = pr >> 7, r = pr & 127, col = c0 + c;
+        const int at = ((c >> 4) * 16 + (c & 15)) * 16 + (r & 15), w0 = (r >> 4) * 2;        // wave (row tile, half) = 2 rt + half
+        const int sum = s_e[w0 * 768 + at] + s_e[(w0 + 1) * 768 + at];
+        float y = (float)sum * (a.w_scale * xs[e]);
+        if (a.bias) y = y + bias;
+        if (col < n) a.Y[(size_t)col * a.ldy + row] = y;
+    }
+}
+
+// Whether the products d[0 .. njobs) (njobs <= 2; plain output, no taps) take the kernel above.
+bool q8i_gemm_ksplit2_ok(const q8i_gemm_job *d, int njobs, int n)
+{
+    if (njobs < 1 || njobs > 2 || n < 1 || (n + KS2_SLOTS - 1) / KS2_SLOTS > 7) return false;
+    int blocks = 0;
+    for (int u = 0; u < njobs; ++u) {
+        if (d[u].W->ld != 1024 || d[u].W->rows % KS2_ROWS || d[u].tap_acc || d[u].part_max || d[u].tiled || d[u].row_scale ||
+            (size_t)d[u].W->rows * 1024 >= (1u << 31))
+            return false;
+        blocks += d[u].W->rows / KS2_ROWS;
+    }
+    return blocks * ((n + KS2_SLOTS - 1) / KS2_SLOTS) <= 256;
+}
+
+q8_status q8i_gemm_ksplit2(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n)
+{
+    Ksplit2Args jobs;
+    int max_rows = 0;
+    for (int t = 0; t < 2; ++t) {
+        const q8i_gemm_job &q = d[t < njobs ? t : 0];
+        GemmArgs &a = jobs.j[t];
+        a.W = q.W->data; a.Wt = q.W->tiles; a.xq = q.xq; a.xscale = q.xscale; a.bias = q.bias; a.Y = q.Y; a.tap_acc = nullptr;
+        a.part_max = nullptr; a.part_sum = nullptr;
+        a.rows = q.W->rows; a.ld = q.W->ld; a.n = n; a.ldy = q.ldy; a.ntiles = (q.W->rows + 15) / 16; a.tiled = 0;
+        a.w_scale = q.W->scale; a.row_scale = nullptr;
+        if (a.rows > max_rows) max_rows = a.rows;
+    }
+    const size_t smem = (size_t)KS2_SLOTS * (1024 + 16) + (size_t)16 * 3 * 1024;
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute((const void *)gemm_ksplit2_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return q8_fail(ctx, Q8_ERR_DEVICE, "k-split product kernel: %s", hipGetErrorString(e));
+        attr_set = true;
+    }
+    Q8_LAUNCH(ctx, Q8_KERNEL_MFMA, gemm_ksplit2_kernel, dim3(max_rows / KS2_ROWS, (n + KS2_SLOTS - 1) / KS2_SLOTS, njobs), dim3(1024), smem, jobs);
+    return q8i_launch_check(ctx, "k-split products");
+}
+
 // ================================================================ vocabulary panel ==
 // The vocabulary product for a panel of hypothesis slots (many sentences side by side).  Unlike
 // the block kernel above, a block keeps its share of the vectors' codes in LDS for its whole

@@ -165,6 +165,9 @@ q8_status q8i_gemm_jobs(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n);  
 // three products with rows of 1024 / 512 / 2048 bytes (the readout's) over the same vectors in one K-resident launch
 bool q8i_gemm_ksplit3_ok(const q8i_gemm_job *d, int n);
 q8_status q8i_gemm_ksplit3(q8_ctx *ctx, const q8i_gemm_job *d, int n);
+// up to two products with rows of 1024 bytes over at most 336 vectors, k split over pairs of waves
+bool q8i_gemm_ksplit2_ok(const q8i_gemm_job *d, int njobs, int n);
+q8_status q8i_gemm_ksplit2(q8_ctx *ctx, const q8i_gemm_job *d, int njobs, int n);
 bool q8i_vocab_panel_ok(const q8_mat *W);
 bool q8i_output_codes_keeps_no_logits(const q8_mat *W, int k);
 q8_status q8i_vocab_panel(q8_ctx *ctx, const q8_mat *W, const float *bias, const int8_t *xq, const float *xscale, int n,
