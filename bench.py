@@ -28,8 +28,8 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side bytes of one launch of the vocabulary kernel (FETCH_SIZE x 2.00 + WRITE_SIZE x 1.00 with the L2 serialized away),
 # its average duration on the kernel trace's clock, and the 25.6 MB read probe's on the same clock
 VOCAB_KERNEL_TRAFFIC_BYTES = 28.15e6
-VOCAB_KERNEL_TRACE_US = 5.55
-READ_PROBE_TRACE_US = 2.65
+VOCAB_KERNEL_TRACE_US = 5.56
+READ_PROBE_TRACE_US = 2.60
 L, BEAM, TOPK, MAX_STEPS = 30, 5, 12, 100
 
 
