@@ -59,3 +59,49 @@ def test_decoder_step_and_search_step_are_bit_reproducible(setup, n, l, reps, ha
         got = run()
         for i, (a, b) in enumerate(zip(got, ref)):
             assert torch.equal(a, b), "repetition %d: output %d differs from the first run" % (rep, i)
+
+
+@pytest.mark.parametrize("S,l,reps", [(64, 8, 150), (13, 5, 100)])
+def test_batched_step_is_bit_reproducible(setup, S, l, reps):
+    """The batched decoder step with codes handed on (GRU r and GRU q as one kernel each, whose blocks exchange
+    their partial maxima through two regions of words that take turns), the panel output layer and the batched
+    search step: two steps of a search from its start, the same bits in every repetition."""
+    q, ctx0, m = setup
+    ctx = q.Context("cuda:0", workspace_bytes=q.q8_workspace_bytes(max_n=S * 5, max_l=64, max_rows=50000, max_ld=2048) + (256 << 20))
+    beam, T, n = 5, 4, S * 5
+    E, H = m.E_tgt.shape[1], m.dec.r.H
+    rng = np.random.default_rng(7 + S)
+    enc_h = ctx.f32(rng.standard_normal((S * l, 2 * H)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    off = torch.arange(0, (S + 1) * l, l, dtype=torch.int32, device=ctx.device)
+    states = torch.zeros(q.q8_beam_state_bytes(T) * S, dtype=torch.uint8, device=ctx.device)
+    y, s = ctx.empty(n, E), ctx.empty(n, H)
+    done = torch.zeros(S, dtype=torch.int32, device=ctx.device)
+    codes = (q.Codes(ctx, n, m.dec.r.Wx.ld), q.Codes(ctx, n, m.dec.q.Wx.ld), q.Codes(ctx, n, m.ro.W_s.ld))
+    sp = q.Codes(ctx, n, m.dec.r.Wh.ld)
+    c0 = q.q8_beam_init_batch(ctx, states, S, beam, T, enc_h, off, m.E_tgt, y, s, done, bind=True)
+    c1 = q.cgru_decoder_step_batch_q8(ctx, m.dec, P, enc_h, off, beam, l, y, s, bind=True, codes=codes + (sp,))
+    c2 = q.output_logits_q8(ctx, m.ro, m.W_out, m.b_out, s=c1.out["s"], y_emb=y, ctx_vec=c1.out["ctx"], k=12,
+                            want_logits=False, bind=True, codes=codes)
+    c3 = q.q8_beam_update_batch(ctx, states, S, beam, T, c2.out["topk_logp"], c2.out["topk_idx"], c1.out["s"], m.E_tgt, y, s,
+                                done, bind=True, codes=(codes[2], codes[0], sp), E_codes=m.E_tgt_codes)
+
+    def run():
+        c0.launch()
+        codes[0].invalidate(); sp.invalidate()
+        outs = []
+        for _ in range(2):
+            c1.launch(); c2.launch(); c3.launch()
+            outs += [c1.out["s"].clone(), c1.out["ctx"].clone(), c1.out["s_mid"].clone(), codes[1].q.clone(), codes[2].q.clone(),
+                     codes[2].scale.clone(), c2.out["topk_logp"].clone(), c2.out["topk_idx"].clone(), y.clone(), s.clone(),
+                     codes[0].q.clone(), sp.q.clone(), sp.scale.clone()]
+        outs.append(states.clone())
+        return outs
+
+    ref = run()
+    assert all(torch.isfinite(t).all() for t in ref if t.is_floating_point())
+    for rep in range(reps):
+        got = run()
+        for i, (a, b) in enumerate(zip(got, ref)):
+            assert torch.equal(a, b), "repetition %d: output %d differs from the first run" % (rep, i)
+    q.q8_encode_check(ctx)
