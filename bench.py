@@ -357,7 +357,7 @@ def batched_decoding(torch, q, m, rng, steps, sizes=(16, 64, 200), translate=Tru
     from workloads import synth
     """Section 6's batching: S sentences decoded side by side (S x beam hypothesis slots per
     step), every product on the int8 matrix cores.  A step is cgru_decoder_step_batch_q8 +
-    output_logits_q8 (panel path) + q8_beam_update_batch; the rate is in sentence-steps."""
+    output_logits_beam_batch_q8 (panel path, search steps included); the rate is in sentence-steps."""
     wsb = q.q8_workspace_bytes(max_n=1024, max_l=64, max_rows=50000, max_ld=2048) + (1024 << 20)
     ctx = q.Context("cuda:0", workspace_bytes=wsb)
     out = {}
@@ -378,11 +378,20 @@ def batched_decoding(torch, q, m, rng, steps, sizes=(16, 64, 200), translate=Tru
         sp = q.Codes(ctx, n, m.dec.r.Wh.ld) if hand_on else None
         c1 = q.cgru_decoder_step_batch_q8(ctx, m.dec, P, enc_h, off, BEAM, L, y, s, bind=True,
                                           codes=codes + (sp,) if hand_on else codes)
-        c2 = q.output_logits_q8(ctx, m.ro, m.W_out, m.b_out, s=c1.out["s"], y_emb=y, ctx_vec=c1.out["ctx"], k=TOPK,
-                                want_logits=False, bind=True, codes=codes)
-        c3 = q.q8_beam_update_batch(ctx, states, S, BEAM, MAX_STEPS, c2.out["topk_logp"], c2.out["topk_idx"],
-                                    c1.out["s"], m.E_tgt, y, s, done, bind=True,
-                                    codes=(codes[2], codes[0], sp) if hand_on else None, E_codes=m.E_tgt_codes if hand_on else None)
+        # (output layer and the sentences' search steps in one call: the selection kernel's launch runs them)
+        if codes is not None and not os.environ.get("Q8_BENCH_SEARCH_APART"):
+            c2 = q.output_logits_beam_batch_q8(ctx, m.ro, m.W_out, m.b_out, c1.out["s"], y, c1.out["ctx"], states, S, BEAM,
+                                               MAX_STEPS, m.E_tgt, s, done, k=TOPK, bind=True,
+                                               codes=(codes[2], codes[0], codes[1]), s_next_codes=sp,
+                                               E_codes=m.E_tgt_codes if hand_on else None)
+            c3 = None
+        else:
+            c2 = q.output_logits_q8(ctx, m.ro, m.W_out, m.b_out, s=c1.out["s"], y_emb=y, ctx_vec=c1.out["ctx"], k=TOPK,
+                                    want_logits=False, bind=True, codes=codes)
+            c3 = q.q8_beam_update_batch(ctx, states, S, BEAM, MAX_STEPS, c2.out["topk_logp"], c2.out["topk_idx"],
+                                        c1.out["s"], m.E_tgt, y, s, done, bind=True,
+                                        codes=(codes[2], codes[0], sp) if hand_on else None,
+                                        E_codes=m.E_tgt_codes if hand_on else None)
         t = [0]
 
         def step():
@@ -391,7 +400,9 @@ def batched_decoding(torch, q, m, rng, steps, sizes=(16, 64, 200), translate=Tru
                 if hand_on:                         # (a new search: y and s are not what the codes were made of)
                     codes[0].invalidate(); sp.invalidate()
             t[0] += 1
-            c1.launch(); c2.launch(); c3.launch()
+            c1.launch(); c2.launch()
+            if c3 is not None:
+                c3.launch()
         per = time_loop(torch, step, steps, max(steps // 10, 10))
         r = {"us_per_step": per * 1e6, "sentence_steps_per_s": S / per, "hypothesis_slots": n}
         if S == 64:

@@ -442,6 +442,23 @@ q8_status q8_beam_update_batch_loop(q8_ctx *ctx, void *states, int n_sent, int b
                                     const q8_row_codes *E_codes, const q8_codes *s_codes, q8_codes *y_next_codes,
                                     q8_codes *s_next_codes);
 
+/* output_logits_codes_q8 for a panel of n_sent beams followed by q8_beam_update_batch_loop (V = W_out->rows), as
+ * output_logits_beam_loop_q8 is for one sentence (Eq. 2, then the search rules above): logits of the decoder states
+ * s [n_sent beam x H] of this step, their k best entries into topk_logp / topk_idx [n_sent beam x k] (device, not
+ * NULL), then every sentence's search step, which writes s_next (must not alias s), overwrites y_emb with the
+ * embeddings of the new tokens and sets done [n_sent].  With tile-packed W_out of pitch 512 or 640 and more than 8
+ * slots the search steps run inside the selection kernel's launch (the block of a sentence's last slot waits for the
+ * k best of the sentence's other slots; the wait is bounded and reported as q8_attention_options says); every other
+ * shape runs the two calls one after the other.  s_codes / y_codes / ctx_codes: this step's codes for the readout
+ * (any may be NULL or not valid: quantized here); given E_codes, s_codes with valid == 1, y_codes and s_next_codes
+ * (pitches of E_codes and s_codes, s_next_codes not the buffers of s_codes), the codes of the new y_emb and of
+ * s_next are left in y_codes and s_next_codes with valid = 2 (otherwise valid = 0).  Bit-identical to the two calls. */
+q8_status output_logits_beam_batch_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                                      const float *s, float *y_emb, const float *ctx_vec, int n_sent, int beam, int k,
+                                      int max_steps, void *states, const float *E_tgt, int E, float *s_next, int32_t *done,
+                                      float *topk_logp, int32_t *topk_idx, const q8_codes *s_codes, q8_codes *y_codes,
+                                      const q8_codes *ctx_codes, q8_codes *s_next_codes, const q8_row_codes *E_codes);
+
 /* Waits for the stream and copies the result to the host: tokens (without the final
  * token 0), their number, the cumulative log-probability, the steps made, and whether
  * the search is over.  Host pointers; any may be NULL. */

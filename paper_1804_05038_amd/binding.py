@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 
 __all__ = ["Q8Error", "Context", "Mat", "Codes", "RowCodes", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
            "q8_quantize_matrix", "q8_quantize_matrix_rows", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "q8_gemm_narrow_rows", "q8_attention_states_q8", "q8_attention_q8", "gru_step_q8", "cgru_decoder_step_q8",
-           "output_logits_q8", "output_logits_beam_q8", "q8_encode", "q8_encoder_options", "q8_encode_check", "q8_attention_options", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
+           "output_logits_q8", "output_logits_beam_q8", "output_logits_beam_batch_q8", "q8_encode", "q8_encoder_options", "q8_encode_check", "q8_attention_options", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
            "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "q8_math_eval", "MatF", "GruWeightsF32", "CgruWeightsF32", "ReadoutWeightsF32", "q8_gemv_f32",
            "cgru_decoder_step_f32", "output_logits_f32", "q8_translate_ensemble", "q8_translate_ensemble_bytes", "cgru_decoder_step_batch_q8", "q8_encode_batch", "q8_encode_batch_bytes", "q8_beam_init_batch",
            "q8_beam_update_batch", "q8_beam_result_batch", "q8_translate_batch", "q8_translate_batch_bytes",
@@ -142,6 +142,9 @@ def load_library():
         lib.q8_beam_update_batch.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, ci, vp, ci, vp, vp, vp]
         lib.q8_beam_update_batch_loop.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, ci, vp, ci, ci, vp, vp, vp,
                                                   C.POINTER(_RowCodes), C.POINTER(_Codes), C.POINTER(_Codes), C.POINTER(_Codes)]
+        lib.output_logits_beam_batch_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, ci, ci, ci, ci, vp,
+                                                    vp, ci, vp, vp, vp, vp, C.POINTER(_Codes), C.POINTER(_Codes),
+                                                    C.POINTER(_Codes), C.POINTER(_Codes), C.POINTER(_RowCodes)]
         lib.q8_beam_result_batch.argtypes = [vp, vp, ci, ci, vp, ip, C.POINTER(C.c_float), ip]
         lib.q8_translate_batch_bytes.restype = C.c_size_t
         lib.q8_translate_batch_bytes.argtypes = [C.POINTER(_Model), ci, ci, ci, ci, ci]
@@ -777,6 +780,28 @@ def q8_beam_update_batch(ctx, states, n_sent, beam, max_steps, topk_logp, topk_i
     if bind:
         return _Bound(ctx, fn, args, {"keep": (states, topk_logp, topk_idx, s_step, E_tgt, y_emb, s_next, done, codes, E_codes)})
     ctx.check(fn(*args))
+
+
+def output_logits_beam_batch_q8(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, states, n_sent, beam, max_steps, E_tgt, s_next,
+                                done, k=12, bind=False, codes=None, s_next_codes=None, E_codes=None):
+    """Output layer of a panel of n_sent beams, top-k and every sentence's search step; returns
+    dict(topk_logp, topk_idx).  codes = (s, y, ctx) Codes objects of this step (as for output_logits_q8);
+    with s_next_codes and E_codes (RowCodes of E_tgt) the codes of the new y_emb (in y) and of s_next go
+    to the next decoder step."""
+    n = s.shape[0]
+    lp = ctx.empty(n, k)
+    idx = ctx.empty(n, k, dtype=torch.int32)
+    by = lambda c: C.byref(c.c) if c is not None else None
+    sc, yc, cc = codes if codes is not None else (None, None, None)
+    args = (ctx.handle, C.byref(ro.c), C.byref(W_out.c), _ptr(b_out), _ptr(s), _ptr(y_emb), _ptr(ctx_vec), n_sent, beam, k,
+            max_steps, _ptr(states), _ptr(E_tgt), E_tgt.shape[1], _ptr(s_next), _ptr(done), _ptr(lp), _ptr(idx),
+            by(sc), by(yc), by(cc), by(s_next_codes), by(E_codes))
+    r = {"topk_logp": lp, "topk_idx": idx}
+    if bind:
+        r["keep"] = (ro, W_out, b_out, s, y_emb, ctx_vec, states, E_tgt, s_next, done, codes, s_next_codes, E_codes)
+        return _Bound(ctx, ctx.lib.output_logits_beam_batch_q8, args, r)
+    ctx.check(ctx.lib.output_logits_beam_batch_q8(*args))
+    return r
 
 
 def q8_beam_result_batch(ctx, states, n_sent, max_steps):

@@ -603,8 +603,10 @@ static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8
                              const float *s, const float *y_emb, const float *ctx_vec, const float *t_in, int n_beam,
                              int k, float *logits, float *lse, float *topk_logp, int32_t *topk_idx, float *t_out,
                              const q8_taps *taps4, q8i_beam_desc *beam, const q8_codes *y_codes = nullptr,
-                             const q8_codes *ctx_codes = nullptr, const q8_codes *s_codes = nullptr)
+                             const q8_codes *ctx_codes = nullptr, const q8_codes *s_codes = nullptr,
+                             const BeamBatchArgs *search = nullptr, int *search_fused = nullptr)
 {
+    if (search_fused) *search_fused = 0;
     if (!ctx) return Q8_ERR_NULL;
     TRY(check_mat(ctx, W_out, "W_out"));
     const int n = n_beam, R = W_out->cols, V = W_out->rows;
@@ -677,7 +679,7 @@ static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8
             TRY(q8i_quantize_jobs(ctx, &qj, 1, n));
         }
         return q8i_output_codes(ctx, W_out, b_out, tq, tsc, n, k, lg, tiled, lse, topk_logp, topk_idx,
-                                taps4 ? taps4[3].acc : nullptr, pm, ps);
+                                taps4 ? taps4[3].acc : nullptr, pm, ps, search, search_fused);
     }
     if (ro) {
         float *t = t_out ? t_out : cv.take<float>((size_t)n * R);
@@ -1385,6 +1387,57 @@ q8_status q8_beam_update_batch_loop(q8_ctx *ctx, void *states, int n_sent, int b
     return st;
 }
 
+namespace {
+// Output layer of a panel and the sentences' search steps: one launch fewer where the panel selection can run
+// the search steps itself, the two calls one after the other everywhere else.  Same results either way.
+q8_status output_and_search_batch(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                                  const float *s, float *y_emb, const float *ctx_vec, int n_sent, int beam, int k,
+                                  int max_steps, void *states, const float *E_tgt, int E, int H, float *s_next, int32_t *done,
+                                  float *topk_logp, int32_t *topk_idx, const q8_codes *s_codes, const q8_codes *y_codes,
+                                  const q8_codes *ctx_codes, const q8i_beam_desc *hand_on)
+{
+    const int n = n_sent * beam, V = W_out->rows;
+    const BeamBatchArgs bb = q8i_beam_batch_args(states, q8i_beam_state_bytes(max_steps), beam, k, max_steps, topk_logp, topk_idx, s,
+                                                 E_tgt, E, H, y_emb, s_next, done, nullptr, nullptr, 0, V, hand_on);
+    int fused = 0;
+    TRY(output_impl(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, nullptr, n, k, nullptr, nullptr, topk_logp, topk_idx, nullptr,
+                    nullptr, nullptr, y_codes, ctx_codes, s_codes, &bb, &fused));
+    if (fused) return Q8_OK;
+    return q8i_beam_batch(ctx, 0, states, q8i_beam_state_bytes(max_steps), n_sent, beam, k, max_steps, topk_logp, topk_idx, s,
+                          E_tgt, E, H, y_emb, s_next, done, nullptr, nullptr, 0, V, hand_on);
+}
+}  // namespace
+
+q8_status output_logits_beam_batch_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                                      const float *s, float *y_emb, const float *ctx_vec, int n_sent, int beam, int k,
+                                      int max_steps, void *states, const float *E_tgt, int E, float *s_next, int32_t *done,
+                                      float *topk_logp, int32_t *topk_idx, const q8_codes *s_codes, q8_codes *y_codes,
+                                      const q8_codes *ctx_codes, q8_codes *s_next_codes, const q8_row_codes *E_codes)
+{
+    // y_codes as an input: the codes of this step's y_emb for the readout (valid != 0)
+    q8_codes y_in = {nullptr, nullptr, 0, 0};
+    if (y_codes) { y_in = *y_codes; y_codes->valid = 0; }
+    if (s_next_codes) s_next_codes->valid = 0;
+    if (!ctx) return Q8_ERR_NULL;
+    if (!ro || !W_out || !states || !E_tgt || !s_next || !s || !y_emb || !ctx_vec || !done || !topk_logp || !topk_idx)
+        return q8_fail(ctx, Q8_ERR_NULL, "output_logits_beam_batch_q8: NULL argument");
+    if (n_sent <= 0 || beam <= 0 || beam > Q8_MAX_BEAM || (long long)n_sent * beam > kMaxMfmaN || k < beam || k > kMaxK ||
+        max_steps <= 0 || E <= 0)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "output_logits_beam_batch_q8: bad sizes");
+    if (s_next == s) return q8_fail(ctx, Q8_ERR_SHAPE, "s_next must not alias s");
+    if (!aligned16(E_tgt) || !aligned16(s_next)) return q8_fail(ctx, Q8_ERR_ALIGN, "fp32 buffers need 16-byte alignment");
+    if (E != ro->W_y.cols) return q8_fail(ctx, Q8_ERR_SHAPE, "E does not match the readout's embedding width");
+    const int H = ro->W_s.cols;
+    q8i_beam_desc bd = {};
+    // (the codes of s for the gather are the caller's: valid == 1, as cgru_decoder_step_batch_codes_q8 left them)
+    const bool hand_on = batch_hand_on(&bd, E_codes, s_codes, y_codes, s_next_codes, E, H);
+    const q8_status st = output_and_search_batch(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, n_sent, beam, k, max_steps, states, E_tgt,
+                                                 E, H, s_next, done, topk_logp, topk_idx, s_codes, y_codes ? &y_in : nullptr,
+                                                 ctx_codes, hand_on ? &bd : nullptr);
+    if (!st && hand_on) { y_codes->valid = 2; s_next_codes->valid = 2; }
+    return st;
+}
+
 q8_status q8_beam_result_batch(q8_ctx *ctx, const void *states, int n_sent, int max_steps, int32_t *tokens_host,
                                int *len_host, float *score_host, int *steps_host)
 {
@@ -1500,17 +1553,15 @@ q8_status q8_translate_batch(q8_ctx *ctx, const q8_model *m, const int32_t *src_
             st = cgru_decoder_step_batch_loop_q8(ctx, &m->dec, P, enc_h, off, n_sent, beam, max_l, y, sv[cur], sv[cur ^ 1],
                                                  cvec, nullptr, nullptr, &yc, &cc, &sc, &pc);
         }
-        if (!st) st = output_impl(ctx, &m->ro, &m->W_out, m->b_out, sv[cur ^ 1], y, cvec, nullptr, n, k, nullptr, nullptr, lp,
-                                  idx, nullptr, nullptr, nullptr, &yc, &cc, &sc);
         // (the table's height goes along: a token id outside it, which takes non-finite logits, is replaced by 0;
         // where the model brings its embeddings' codes, the codes of the gathered rows go to the next step)
         q8i_beam_desc bd = {};
         const bool hand_on = !st && batch_hand_on(&bd, Ec, &sc, &yc, &pc, E, H);
+        const q8_codes y_in = yc;
         yc.valid = 0;
         pc.valid = 0;
-        if (!st) st = q8i_beam_batch(ctx, 0, states, q8i_beam_state_bytes(max_steps), n_sent, beam, k, max_steps, lp, idx,
-                                     sv[cur ^ 1], m->E_tgt, E, H, y, sv[cur], done, nullptr, nullptr, 0, m->V_tgt,
-                                     hand_on ? &bd : nullptr);
+        if (!st) st = output_and_search_batch(ctx, &m->ro, &m->W_out, m->b_out, sv[cur ^ 1], y, cvec, n_sent, beam, k, max_steps,
+                                              states, m->E_tgt, E, H, sv[cur], done, lp, idx, &sc, &y_in, &cc, hand_on ? &bd : nullptr);
         if (!st && hand_on) { yc.valid = 2; pc.valid = 2; }
         if (!st && (t % 8 == 7)) {
             hipError_t e = hipMemcpyAsync(done_host, done, sizeof(int32_t) * n_sent, hipMemcpyDeviceToHost, ctx->stream);

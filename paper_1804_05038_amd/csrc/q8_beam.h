@@ -260,3 +260,18 @@ __device__ __forceinline__ void beam_gather(const BeamUpdateArgs &a, const int *
         }
     }
 }
+
+// The search step's arguments for sentence s of a panel.
+__device__ __forceinline__ BeamUpdateArgs beam_batch_sentence(const BeamBatchArgs &b, int s)
+{
+    const size_t slot = (size_t)s * b.beam;
+    BeamUpdateArgs a = {(BeamState *)(b.states + (size_t)s * b.stride), b.topk_logp + slot * b.k, b.topk_idx + slot * b.k,
+                        b.s_step + slot * b.H, b.E_tgt, b.y_emb + slot * b.E, b.s_next + slot * b.H, b.beam, b.k, b.E, b.H, b.V};
+    if (b.Eq) {
+        a.Eq = b.Eq; a.Es = b.Es; a.ldy = b.ldy; a.lds = b.lds;
+        a.sq_in = b.sq_in + slot * b.lds; a.ss_in = b.ss_in + slot;
+        a.yq_out = b.yq_out + slot * b.ldy; a.ys_out = b.ys_out + slot;
+        a.sq_out = b.sq_out + slot * b.lds; a.ss_out = b.ss_out + slot;
+    }
+    return a;
+}

@@ -22,7 +22,7 @@
 // search step, from 32768 those of the one-launch panel GRU.
 #define Q8_MAX_BEAM 8
 #define Q8_MAX_COLS 1024            // vectors of one batched call
-#define Q8_WS_HEADER 131072
+#define Q8_WS_HEADER 262144
 #define Q8_WS_SCRATCH_SLOT 6144
 #define Q8_WS_ENC_ERR 6208          // set to 1 by the one-launch encoder if a wait gave up (zeroed before each such launch)
 #define Q8_WS_ATT_ERR 6212          // the same for the attention kernel whose blocks wait for each other
@@ -30,6 +30,7 @@
 #define Q8_WS_ATT_XCHG_PER_HYP 2048
 #define Q8_WS_SELECT_XCHG 24576      // 128 words: the top-k entries on their way to the search step
 #define Q8_WS_GRUP_XCHG 32768        // 2 x 10752 words: partial maxima of the one-launch panel GRU (two regions that take turns)
+#define Q8_WS_PSEL_XCHG 131072       // 1024 x 16 8-byte words: the same hand-over for a panel of slots (sentences side by side)
 #define Q8_ENC_SPIN_DEFAULT (1 << 20)
 
 struct q8_ctx {
@@ -130,6 +131,29 @@ struct q8i_beam_desc {
     int ldy, lds;
 };
 
+// Search steps of several sentences side by side: sentence s owns slots [s beam, (s + 1) beam) of every
+// per-hypothesis table.
+struct BeamBatchArgs {
+    char *states;
+    size_t stride;               // bytes between the states of consecutive sentences
+    const float *topk_logp;
+    const int *topk_idx;
+    const float *s_step, *E_tgt;
+    float *y_emb, *s_next;
+    int *done;                   // [S]: 1 once the sentence's search is over
+    const float *enc_h;          // initialization: encoder states, sentence s starts at row sent_off[s]
+    const int *sent_off;
+    int beam, k, E, H, C, max_steps;
+    int V;                       // rows of E_tgt when known (token ids are then kept inside the table), else 0
+    // optional, all or none (see BeamUpdateArgs): the codes of the gathered rows travel with them; the per-slot
+    // tables are those of all sentences, slot-major like y_emb and s_next
+    const int8_t *Eq, *sq_in;
+    const float *Es, *ss_in;
+    int8_t *yq_out, *sq_out;
+    float *ys_out, *ss_out;
+    int ldy, lds;
+};
+
 enum { Q8I_GRU_FULL = 0, Q8I_GRU_GX_PRE = 1, Q8I_GRU_GH_PRE = 2 };
 
 q8_status q8i_fill_u32(q8_ctx *ctx, void *p, int n, unsigned v);   // fill kernel (safe under graph capture)
@@ -207,7 +231,12 @@ q8_status q8i_readout_combine(q8_ctx *ctx, const float *ts, const float *ty, con
                               int n, float *t_out, int ld, int8_t *tq, float *tscale, const q8_taps *tap);
 q8_status q8i_output_codes(q8_ctx *ctx, const q8_mat *W, const float *bias, const int8_t *tq, const float *tscale, int n,
                            int k, float *logits, int tiled, float *lse, float *topk_logp, int32_t *topk_idx,
-                           int32_t *tap_acc, float *part_max, double *part_sum);
+                           int32_t *tap_acc, float *part_max, double *part_sum, const BeamBatchArgs *search = nullptr,
+                           int *search_fused = nullptr);
+BeamBatchArgs q8i_beam_batch_args(void *states, size_t stride, int beam, int k, int max_steps, const float *topk_logp,
+                                  const int *topk_idx, const float *s_step, const float *E_tgt, int E, int H, float *y_emb,
+                                  float *s_next, int *done, const float *enc_h, const int *sent_off, int C, int V,
+                                  const struct q8i_beam_desc *codes);
 q8_status q8i_beam_batch(q8_ctx *ctx, int init, void *states, size_t stride, int S, int beam, int k, int max_steps,
                          const float *topk_logp, const int *topk_idx, const float *s_step, const float *E_tgt, int E,
                          int H, float *y_emb, float *s_next, int *done, const float *enc_h, const int *sent_off, int C, int V,

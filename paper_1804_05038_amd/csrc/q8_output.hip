@@ -637,13 +637,26 @@ struct PanelSelectArgs {
     int *topk_idx;
     int ntiles, n, k, V;
     float w_scale;
+    // FUSE: the search steps of the sentences run in this launch (see the kernel); xw: n k 8-byte words, zero
+    // on entry and on exit; the flag a wait that gave up sets; the bound of the wait in polls
+    unsigned long long *xw;
+    unsigned *wait_err;
+    int spin_limit;
+    BeamBatchArgs bb;
 };
 
 #define PSEL_BATCH 4          // tiles per wave whose weights are requested together
 
-template <int KC>
+// FUSE: the search step of every sentence runs here too, as in out_select_kernel: each block publishes its
+// k entries as tagged 8-byte words (present bit, token id, log-probability) with device-coherent stores; the
+// block of a sentence's last slot polls the beam k words of its sentence (two per lane of one wave), clears
+// them (it is their only reader) and runs the sentence's search step with the candidates in registers.  The
+// blocks it waits for have lower indices and were dispatched before it, so the wait ends whatever the
+// device holds at once; it is bounded all the same, and a wait that gives up sets wait_err.
+template <int KC, bool FUSE>
 __global__ __launch_bounds__(256) void panel_select_kernel(PanelSelectArgs a)
 {
+    __shared__ unsigned long long s_best[16];
     __shared__ unsigned short s_q[OUT_MAX_TILES];
     __shared__ __align__(16) unsigned long long s_key[SEL_CAP + 4];
     __shared__ float s_f[4];
@@ -658,6 +671,7 @@ __global__ __launch_bounds__(256) void panel_select_kernel(PanelSelectArgs a)
     const int ntiles = a.ntiles;
     if (tid == 0) { s_nq = 0; s_ns = 0; }
     if (tid < 64) s_top[tid] = -INFINITY;
+    if (FUSE && tid < 16) s_best[tid] = topk_key(-INFINITY, 0);
 
     // the slot's codes as second operand: column 0 carries them, columns 1..15 are zero
     v4i bv[KC];
@@ -794,12 +808,16 @@ __global__ __launch_bounds__(256) void panel_select_kernel(PanelSelectArgs a)
                 rank += (p0.x > key) + (p0.y > key) + (p1.x > key) + (p1.y > key);
             }
             if (rank < k) {
-                a.topk_idx[(size_t)j * k + rank] = topk_key_idx(key);
-                a.topk_logp[(size_t)j * k + rank] = topk_key_val(key) - lse;
+                if (FUSE) {
+                    s_best[rank] = key;
+                } else {
+                    a.topk_idx[(size_t)j * k + rank] = topk_key_idx(key);
+                    a.topk_logp[(size_t)j * k + rank] = topk_key_val(key) - lse;
+                }
             }
         }
-        return;
-    }
+        if (!FUSE) return;
+    } else {
     // heavily tied logits (more than SEL_CAP at or above T): k exact rounds of arg-max over every tile
     unsigned long long prev = ~0ull;
     for (int r = 0; r < k; ++r) {
@@ -830,11 +848,58 @@ __global__ __launch_bounds__(256) void panel_select_kernel(PanelSelectArgs a)
         for (int w = 1; w < 4; ++w) best = s_u[w] > best ? s_u[w] : best;
         if (tid == 0) {
             const int idx = topk_key_idx(best);              // past the table if the round found no candidate (non-finite logits)
-            a.topk_idx[(size_t)j * k + r] = (unsigned)idx < (unsigned)a.V ? idx : 0;
-            a.topk_logp[(size_t)j * k + r] = topk_key_val(best) - lse;
+            if (FUSE) {
+                s_best[r] = best;
+            } else {
+                a.topk_idx[(size_t)j * k + r] = (unsigned)idx < (unsigned)a.V ? idx : 0;
+                a.topk_logp[(size_t)j * k + r] = topk_key_val(best) - lse;
+            }
         }
         prev = best;
     }
+    }
+    if (!FUSE) return;
+    // ---- the k entries: stored, and published for the block that runs this sentence's search step
+    __syncthreads();
+    if (tid < k) {
+        const unsigned long long key = s_best[tid];
+        int idx = topk_key_idx(key);
+        idx = (unsigned)idx < (unsigned)a.V ? idx : 0;       // (a rank without a candidate: token 0 at -inf)
+        const float logp = topk_key_val(key) - lse;
+        const size_t o = (size_t)j * k + tid;
+        a.topk_idx[o] = idx;
+        a.topk_logp[o] = logp;
+        __hip_atomic_store(a.xw + o, (1ull << 63) | ((unsigned long long)(unsigned)idx << 32) | __float_as_uint(logp),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    const int beam = a.bb.beam, sent = j / beam;
+    if (j != sent * beam + beam - 1) return;
+    const BeamUpdateArgs bu = beam_batch_sentence(a.bb, sent);
+    float lp[2] = {0.0f, 0.0f};
+    int tk[2] = {0, 0};
+    BeamStateRead sr = {};
+    if (tid < 64) {
+        sr = beam_state_read(bu.st, lane);                   // (on its way while the candidates are waited for)
+        const int nk = beam * k;                             // at most 128
+        unsigned long long *xw = a.xw + (size_t)sent * nk;
+        const int c0 = min(lane, nk - 1), c1 = min(lane + 64, nk - 1);
+        unsigned long long x0 = 0ull, x1 = 0ull;
+        bool ok = false;
+        for (int spin = 0; spin < a.spin_limit; ++spin) {
+            x0 = __hip_atomic_load(xw + c0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            x1 = __hip_atomic_load(xw + c1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (__all((x0 >> 63) != 0ull && (x1 >> 63) != 0ull)) { ok = true; break; }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        if (!ok && lane == 0) __hip_atomic_store(a.wait_err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        lp[0] = __uint_as_float((unsigned)x0); tk[0] = (int)((x0 >> 32) & 0x7fffffffull);
+        lp[1] = __uint_as_float((unsigned)x1); tk[1] = (int)((x1 >> 32) & 0x7fffffffull);
+        if (lane < nk) xw[lane] = 0ull;
+        if (lane + 64 < nk) xw[lane + 64] = 0ull;
+    }
+    beam_update_body<true>(bu, lp, tk, sr);
+    __syncthreads();
+    if (tid == 0) a.bb.done[sent] = bu.st->done;
 }
 
 // =================================================================== host launcher ==
@@ -1011,9 +1076,10 @@ bool q8i_output_codes_keeps_no_logits(const q8_mat *W, int k) { return q8i_vocab
 // tiled: the logits go to the workspace tile by tile (see GemmArgs) instead of row-major.
 q8_status q8i_output_codes(q8_ctx *ctx, const q8_mat *W, const float *bias, const int8_t *tq, const float *tscale, int n,
                            int k, float *logits, int tiled, float *lse, float *topk_logp, int32_t *topk_idx,
-                           int32_t *tap_acc, float *part_max, double *part_sum)
+                           int32_t *tap_acc, float *part_max, double *part_sum, const BeamBatchArgs *search, int *search_fused)
 {
     q8_status st;
+    if (search_fused) *search_fused = 0;
     if (tiled && !tap_acc && q8i_output_codes_keeps_no_logits(W, k)) {
         // no logits are kept: the selection computes those of the few tiles it needs again
         st = q8i_vocab_panel(ctx, W, bias, tq, tscale, n, part_max, part_sum);
@@ -1022,8 +1088,23 @@ q8_status q8i_output_codes(q8_ctx *ctx, const q8_mat *W, const float *bias, cons
         s.part_max = part_max; s.part_sum = part_sum; s.tiles = W->tiles; s.xq = tq; s.xscale = tscale; s.bias = bias;
         s.lse = lse; s.topk_logp = topk_logp; s.topk_idx = topk_idx;
         s.ntiles = q8i_out_tiles(W->rows); s.n = n; s.k = k; s.V = W->rows; s.w_scale = W->scale;
-        if (W->ld == 512) Q8_LAUNCH(ctx, Q8_KERNEL_SELECT, panel_select_kernel<8>, dim3(n), dim3(256), 0, s);
-        else Q8_LAUNCH(ctx, Q8_KERNEL_SELECT, panel_select_kernel<10>, dim3(n), dim3(256), 0, s);
+        s.xw = (unsigned long long *)(ctx->ws + Q8_WS_PSEL_XCHG);
+        s.wait_err = (unsigned *)(ctx->ws + Q8_WS_ATT_ERR);
+        s.spin_limit = ctx->att_spin_limit;
+        // the sentences' search steps in the same launch: n = whole beams of at most 8, beam k <= 128 candidates
+        const bool fuse = search && search->beam >= 1 && search->beam <= Q8_MAX_BEAM && n % search->beam == 0 &&
+                          search->beam * k <= 128 && (size_t)n * k * 8 <= Q8_WS_HEADER - Q8_WS_PSEL_XCHG;
+        if (fuse) {
+            s.bb = *search;
+            s.bb.topk_logp = topk_logp; s.bb.topk_idx = topk_idx; s.bb.k = k;
+            if (W->ld == 512) Q8_LAUNCH(ctx, Q8_KERNEL_SELECT, (panel_select_kernel<8, true>), dim3(n), dim3(256), 0, s);
+            else Q8_LAUNCH(ctx, Q8_KERNEL_SELECT, (panel_select_kernel<10, true>), dim3(n), dim3(256), 0, s);
+            if (search_fused) *search_fused = 1;
+        } else {
+            memset(&s.bb, 0, sizeof(s.bb));
+            if (W->ld == 512) Q8_LAUNCH(ctx, Q8_KERNEL_SELECT, (panel_select_kernel<8, false>), dim3(n), dim3(256), 0, s);
+            else Q8_LAUNCH(ctx, Q8_KERNEL_SELECT, (panel_select_kernel<10, false>), dim3(n), dim3(256), 0, s);
+        }
         return q8i_launch_check(ctx, "panel selection");
     } else {
         const q8i_gemm_job gj = {W, tq, tscale, bias, logits, W->rows, tap_acc, part_max, part_sum, tiled};

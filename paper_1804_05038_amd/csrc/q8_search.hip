@@ -73,41 +73,11 @@ __global__ __launch_bounds__(256) void beam_regather_kernel(BeamUpdateArgs a)
     beam_gather(a, s_parent, s_token);
 }
 
-// Several sentences side by side: block s runs sentence s, whose beam occupies slots
-// [s beam, (s + 1) beam) of every per-hypothesis table.
-struct BeamBatchArgs {
-    char *states;
-    size_t stride;               // bytes between the states of consecutive sentences
-    const float *topk_logp;
-    const int *topk_idx;
-    const float *s_step, *E_tgt;
-    float *y_emb, *s_next;
-    int *done;                   // [S]: 1 once the sentence's search is over
-    const float *enc_h;          // initialization: encoder states, sentence s starts at row sent_off[s]
-    const int *sent_off;
-    int beam, k, E, H, C, max_steps;
-    int V;                       // rows of E_tgt when known (token ids are then kept inside the table), else 0
-    // optional, all or none (see BeamUpdateArgs): the codes of the gathered rows travel with them; the per-slot
-    // tables are those of all sentences, slot-major like y_emb and s_next
-    const int8_t *Eq, *sq_in;
-    const float *Es, *ss_in;
-    int8_t *yq_out, *sq_out;
-    float *ys_out, *ss_out;
-    int ldy, lds;
-};
-
+// Several sentences side by side: block s runs sentence s (BeamBatchArgs).
 __global__ __launch_bounds__(256) void beam_update_batch_kernel(BeamBatchArgs b)
 {
     const int s = blockIdx.x;
-    const size_t slot = (size_t)s * b.beam;
-    BeamUpdateArgs a = {(BeamState *)(b.states + (size_t)s * b.stride), b.topk_logp + slot * b.k, b.topk_idx + slot * b.k,
-                        b.s_step + slot * b.H, b.E_tgt, b.y_emb + slot * b.E, b.s_next + slot * b.H, b.beam, b.k, b.E, b.H, b.V};
-    if (b.Eq) {
-        a.Eq = b.Eq; a.Es = b.Es; a.ldy = b.ldy; a.lds = b.lds;
-        a.sq_in = b.sq_in + slot * b.lds; a.ss_in = b.ss_in + slot;
-        a.yq_out = b.yq_out + slot * b.ldy; a.ys_out = b.ys_out + slot;
-        a.sq_out = b.sq_out + slot * b.lds; a.ss_out = b.ss_out + slot;
-    }
+    const BeamUpdateArgs a = beam_batch_sentence(b, s);
     beam_update_body(a);
     __syncthreads();
     if (threadIdx.x == 0) b.done[s] = a.st->done;
@@ -148,10 +118,10 @@ q8_status q8i_beam_update(q8_ctx *ctx, void *state, const float *topk_logp, cons
     return q8i_launch_check(ctx, "beam_update");
 }
 
-q8_status q8i_beam_batch(q8_ctx *ctx, int init, void *states, size_t stride, int S, int beam, int k, int max_steps,
-                         const float *topk_logp, const int *topk_idx, const float *s_step, const float *E_tgt, int E,
-                         int H, float *y_emb, float *s_next, int *done, const float *enc_h, const int *sent_off, int C, int V,
-                         const q8i_beam_desc *codes)
+BeamBatchArgs q8i_beam_batch_args(void *states, size_t stride, int beam, int k, int max_steps, const float *topk_logp,
+                                  const int *topk_idx, const float *s_step, const float *E_tgt, int E, int H, float *y_emb,
+                                  float *s_next, int *done, const float *enc_h, const int *sent_off, int C, int V,
+                                  const q8i_beam_desc *codes)
 {
     BeamBatchArgs b = {(char *)states, stride, topk_logp, topk_idx, s_step, E_tgt, y_emb, s_next, done, enc_h, sent_off,
                        beam, k, E, H, C, max_steps, V};
@@ -160,6 +130,16 @@ q8_status q8i_beam_batch(q8_ctx *ctx, int init, void *states, size_t stride, int
         b.yq_out = codes->yq_out; b.ys_out = codes->ys_out; b.sq_out = codes->sq_out; b.ss_out = codes->ss_out;
         b.ldy = codes->ldy; b.lds = codes->lds;
     }
+    return b;
+}
+
+q8_status q8i_beam_batch(q8_ctx *ctx, int init, void *states, size_t stride, int S, int beam, int k, int max_steps,
+                         const float *topk_logp, const int *topk_idx, const float *s_step, const float *E_tgt, int E,
+                         int H, float *y_emb, float *s_next, int *done, const float *enc_h, const int *sent_off, int C, int V,
+                         const q8i_beam_desc *codes)
+{
+    const BeamBatchArgs b = q8i_beam_batch_args(states, stride, beam, k, max_steps, topk_logp, topk_idx, s_step, E_tgt, E, H, y_emb,
+                                                s_next, done, enc_h, sent_off, C, V, codes);
     if (init) hipLaunchKernelGGL(beam_init_batch_kernel, dim3(S), dim3(256), 0, ctx->stream, b);
     else hipLaunchKernelGGL(beam_update_batch_kernel, dim3(S), dim3(256), 0, ctx->stream, b);
     return q8i_launch_check(ctx, init ? "beam init (batch)" : "beam update (batch)");

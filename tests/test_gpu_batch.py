@@ -423,3 +423,97 @@ def test_panel_gru_wait_that_gives_up_is_reported_and_the_next_step_is_good(q, c
     q.q8_encode_check(ctx)
     for key in good:
         assert_same(again[key], good[key], key + " after the abandoned run")
+
+
+def _batched_search(q, ctx, m, P, enc_h, off, S, beam, l, T, fused, hand_on, k=8):
+    """T steps of a batched search from its start; fused: output_logits_beam_batch_q8, else the output layer and
+    q8_beam_update_batch apart.  Returns every step's states, contexts, top-k tables and gathered rows, and the result."""
+    E, H = m.E_tgt.shape[1], m.dec.r.H
+    n = S * beam
+    states = torch.zeros(q.q8_beam_state_bytes(T) * S, dtype=torch.uint8, device=ctx.device)
+    y, s = ctx.empty(n, E), ctx.empty(n, H)
+    done = torch.zeros(S, dtype=torch.int32, device=ctx.device)
+    q.q8_beam_init_batch(ctx, states, S, beam, T, enc_h, off, m.E_tgt, y, s, done)
+    codes = [q.Codes(ctx, n, m.dec.r.Wx.ld), q.Codes(ctx, n, m.dec.q.Wx.ld), q.Codes(ctx, n, m.ro.W_s.ld)]
+    if hand_on:
+        codes.append(q.Codes(ctx, n, m.dec.r.Wh.ld))
+    trace, used = [], 0
+    for _ in range(T):
+        used += bool(hand_on and codes[0].c.valid == 2 and codes[3].c.valid == 2)
+        r = q.cgru_decoder_step_batch_q8(ctx, m.dec, P, enc_h, off, beam, l, y, s, codes=codes)
+        if fused:
+            o = q.output_logits_beam_batch_q8(ctx, m.ro, m.W_out, m.b_out, r["s"], y, r["ctx"], states, S, beam, T, m.E_tgt, s,
+                                              done, k=k, codes=(codes[2], codes[0], codes[1]),
+                                              s_next_codes=codes[3] if hand_on else None,
+                                              E_codes=m.E_tgt_codes if hand_on else None)
+        else:
+            o = q.output_logits_q8(ctx, m.ro, m.W_out, m.b_out, s=r["s"], y_emb=y, ctx_vec=r["ctx"], k=k, want_logits=False,
+                                   codes=codes[:3])
+            q.q8_beam_update_batch(ctx, states, S, beam, T, o["topk_logp"], o["topk_idx"], r["s"], m.E_tgt, y, s, done,
+                                   codes=(codes[2], codes[0], codes[3]) if hand_on else None,
+                                   E_codes=m.E_tgt_codes if hand_on else None)
+        trace += [np_(r["s"]), np_(r["ctx"]), np_(o["topk_logp"]), np_(o["topk_idx"]), np_(y), np_(s), np_(done)]
+    return trace, used, q.q8_beam_result_batch(ctx, states, S, T)
+
+
+@pytest.mark.parametrize("dims,S,beam,l,k,hand_on", [
+    (dict(), 6, 5, 9, 12, True), (dict(), 64, 5, 7, 12, True), (dict(), 200, 5, 3, 12, True), (dict(), 2, 8, 5, 16, False),
+    (dict(), 40, 1, 4, 3, True), (dict(V=700, E=620, H=1000, A=1000, R=620, w_std=0.2, b_std=0.1), 3, 5, 6, 8, True),
+    (dict(V=500, E=64, H=128, A=64, R=64, w_std=0.2, b_std=0.1), 20, 3, 5, 8, True), (dict(), 1, 5, 6, 12, False)])
+def test_search_steps_inside_the_panel_selection(q, ctx, oracle, dims, S, beam, l, k, hand_on):
+    """output_logits_beam_batch_q8 (the sentences' search steps run in the selection kernel's launch where the
+    vocabulary matrix is tile-packed with rows of 512 or 640 bytes and there are more than 8 slots; the other
+    shapes here take its two-call path) against output layer and q8_beam_update_batch apart: every state,
+    context vector, top-k table, gathered row and done flag bit for bit at every step, the same results, and
+    as many steps that took their codes from the search step."""
+    T = 5
+    p = synth.full_model(seed=43, **dims)
+    m = q.Model.from_params(ctx, p)
+    H = m.dec.r.H
+    rng = np.random.default_rng(S + l)
+    enc_h = ctx.f32(rng.standard_normal((S * l, 2 * H)).astype(np.float32))
+    P = torch.cat([q.q8_gemm_narrow(ctx, m.att_W, enc_h[o:o + 1000].contiguous(), m.att_b) for o in range(0, S * l, 1000)])
+    off = torch.arange(0, (S + 1) * l, l, dtype=torch.int32, device=ctx.device)
+    ref, ref_used, ref_res = _batched_search(q, ctx, m, P, enc_h, off, S, beam, l, T, False, hand_on, k)
+    for rep in range(2):                              # (the second run finds the exchange words as the first left them)
+        got, used, got_res = _batched_search(q, ctx, m, P, enc_h, off, S, beam, l, T, True, hand_on, k)
+        q.q8_encode_check(ctx)
+        assert used == ref_used
+        for i, (a, b) in enumerate(zip(got, ref)):
+            assert_same(a, b, "run %d, step %d, output %d" % (rep, i // 7, i % 7))
+        for a, b in zip(got_res, ref_res):
+            assert a[0].tolist() == b[0].tolist() and a[1:] == b[1:]
+
+
+def test_panel_search_wait_that_gives_up_is_reported_and_the_next_search_is_good(q, ctx, oracle):
+    """With a bound of one poll the block that runs a sentence's search step inside the panel selection may stop
+    waiting for the sentence's other slots: the kernel still ends normally, q8_encode_check reports it once and
+    clears the exchange words, and the same search run again gives the first result."""
+    S, beam, l, T = 12, 5, 4, 4
+    m = q.Model.from_params(ctx, synth.full_model(seed=43))
+    rng = np.random.default_rng(5)
+    enc_h = ctx.f32(rng.standard_normal((S * l, 2 * m.dec.r.H)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    off = torch.arange(0, (S + 1) * l, l, dtype=torch.int32, device=ctx.device)
+    good = _batched_search(q, ctx, m, P, enc_h, off, S, beam, l, T, True, True)
+    q.q8_encode_check(ctx)
+    gave_up = False
+    try:
+        q.q8_attention_options(ctx, exchange=True, spin_limit=1)
+        for _ in range(5):                            # (a single poll can succeed when the other blocks are quick)
+            _batched_search(q, ctx, m, P, enc_h, off, S, beam, l, T, True, True)
+            try:
+                q.q8_encode_check(ctx)
+            except q.Q8Error:
+                gave_up = True
+                break
+    finally:
+        q.q8_attention_options(ctx, exchange=True, spin_limit=0)
+    assert gave_up
+    q.q8_encode_check(ctx)
+    again = _batched_search(q, ctx, m, P, enc_h, off, S, beam, l, T, True, True)
+    q.q8_encode_check(ctx)
+    for a, b in zip(again[0], good[0]):
+        assert_same(a, b, "after the abandoned run")
+    for a, b in zip(again[2], good[2]):
+        assert a[0].tolist() == b[0].tolist() and a[1:] == b[1:]
