@@ -407,6 +407,31 @@ q8_status output_logits_beam_loop_q8(q8_ctx *ctx, const q8_readout_weights *ro, 
                                      const q8_codes *ctx_codes, q8_codes *s_next_codes,
                                      const q8_row_codes *E_codes);
 
+/* The decoding loop of one sentence with GRU r (Eq. 3) taken off the chain of dependent launches.  s' of the next
+ * step is r(E_tgt[token], s[parent]) for the token and parent the search step picks.  Its two products do not
+ * depend on that decision (Section 3: a vector's codes, and so its 8-bit products, depend on the vector alone):
+ * W_x^r q(E_tgt[v]) + b_x is a function of the token, kept as a table gx_table [V x 3H] (device, fp32; made once
+ * per model with q8_gemm_narrow over the rows of E_tgt: 614 MB at V = 50000, H = 1024), and W_h^r q(s_j) + b_h of
+ * every state s_j of this step is multiplied in the readout's launch.  What is left for after the decision are
+ * the gates.
+ * cgru_decoder_step_ahead_q8: Eq. 4-6 from a given s' (s_mid [n_beam x H]): writes s_out, ctx_out (alpha_out, ctx_codes
+ * as in cgru_decoder_step_codes_q8).
+ * output_logits_beam_ahead_q8: output_logits_beam_loop_q8 whose search step moves no state rows; r: the weights of
+ * GRU r (r->Wh, r->bh are used; rows of W_h^r of at most 1024 bytes ride in the readout's launch, longer ones take a
+ * launch of their own); blocks of the selection kernel wait (bounded, reported as q8_attention_options says) for
+ * the search step's decision and write s_mid_next [n_beam x H] = gates(gx_table[token], W_h^r q(s[parent]) + b_h,
+ * s[parent]), the s' of the next step.  y_codes: in, the codes of this step's y_emb (valid != 0; else quantized
+ * here); out, with E_codes, those of the new y_emb (valid = 2).  The first s' of a search is
+ * gru_step_q8(r, y_emb, s).  Bit-identical to cgru_decoder_step_q8 + output_logits_beam_q8. */
+q8_status cgru_decoder_step_ahead_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h, int l,
+                                     const float *s_mid, int n_beam, float *s_out, float *ctx_out, float *alpha_out,
+                                     q8_codes *ctx_codes);
+q8_status output_logits_beam_ahead_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                                      const float *s, float *y_emb, const float *ctx_vec, int n_beam, int k, void *state,
+                                      const float *E_tgt, int E, float *topk_logp, int32_t *topk_idx, q8_codes *y_codes,
+                                      const q8_codes *ctx_codes, const q8_row_codes *E_codes, const q8_gru_weights *r,
+                                      const float *gx_table, float *s_mid_next);
+
 /* The same for panels of hypothesis slots: cgru_decoder_step_batch_codes_q8 is
  * cgru_decoder_step_batch_q8 and also leaves the codes of y_emb (pitch r.Wx.ld), of the context
  * vectors (pitch q.Wx.ld) and of the new states s_out (any pitch ld >= H that is a multiple of

@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "libq8nmt.so")
 
 __all__ = ["Q8Error", "Context", "Mat", "Codes", "RowCodes", "GruWeights", "CgruWeights", "ReadoutWeights", "load_library",
            "q8_quantize_matrix", "q8_quantize_matrix_rows", "q8_pack_tiles", "q8_gemv", "q8_gemm_narrow", "q8_gemm_narrow_rows", "q8_attention_states_q8", "q8_attention_q8", "gru_step_q8", "cgru_decoder_step_q8",
-           "output_logits_q8", "output_logits_beam_q8", "output_logits_beam_batch_q8", "q8_encode", "q8_encoder_options", "q8_encode_check", "q8_attention_options", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
+           "output_logits_q8", "output_logits_beam_q8", "output_logits_beam_batch_q8", "cgru_decoder_step_ahead_q8", "output_logits_beam_ahead_q8", "gru_input_table", "q8_encode", "q8_encoder_options", "q8_encode_check", "q8_attention_options", "q8_workspace_bytes", "Model", "q8_translate", "q8_translate_bytes",
            "q8_beam_state_bytes", "q8_beam_init", "q8_beam_update", "q8_beam_result", "q8_profile_begin", "q8_profile_end", "q8_probe_read", "q8_math_eval", "MatF", "GruWeightsF32", "CgruWeightsF32", "ReadoutWeightsF32", "q8_gemv_f32",
            "cgru_decoder_step_f32", "output_logits_f32", "q8_translate_ensemble", "q8_translate_ensemble_bytes", "cgru_decoder_step_batch_q8", "q8_encode_batch", "q8_encode_batch_bytes", "q8_beam_init_batch",
            "q8_beam_update_batch", "q8_beam_result_batch", "q8_translate_batch", "q8_translate_batch_bytes",
@@ -142,6 +142,10 @@ def load_library():
         lib.q8_beam_update_batch.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, ci, vp, ci, vp, vp, vp]
         lib.q8_beam_update_batch_loop.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp, vp, ci, vp, ci, ci, vp, vp, vp,
                                                   C.POINTER(_RowCodes), C.POINTER(_Codes), C.POINTER(_Codes), C.POINTER(_Codes)]
+        lib.cgru_decoder_step_ahead_q8.argtypes = [vp, C.POINTER(_Cgru), vp, vp, ci, vp, ci, vp, vp, vp, C.POINTER(_Codes)]
+        lib.output_logits_beam_ahead_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, ci, ci, vp, vp, ci,
+                                                    vp, vp, C.POINTER(_Codes), C.POINTER(_Codes), C.POINTER(_RowCodes),
+                                                    C.POINTER(_Gru), vp, vp]
         lib.output_logits_beam_batch_q8.argtypes = [vp, C.POINTER(_Readout), C.POINTER(_Mat), vp, vp, vp, vp, ci, ci, ci, ci, vp,
                                                     vp, ci, vp, vp, vp, vp, C.POINTER(_Codes), C.POINTER(_Codes),
                                                     C.POINTER(_Codes), C.POINTER(_Codes), C.POINTER(_RowCodes)]
@@ -415,10 +419,13 @@ class ReadoutWeights:
         self.c = _Readout(W_s.c, W_y.c, W_c.c, b_t.data_ptr() if b_t is not None else None)
 
 
-def gru_step_q8(ctx, g, x, h_prev, h_out=None, taps=False):
+def gru_step_q8(ctx, g, x, h_prev, h_out=None, taps=False, bind=False):
     n = x.shape[0]
     h_out = ctx.empty(n, g.H) if h_out is None else h_out
     ts = _TapSet(ctx, [(n, g.Wx.cols, g.Wx.rows), (n, g.Wh.cols, g.Wh.rows)]) if taps else None
+    if bind:
+        return _Bound(ctx, ctx.lib.gru_step_q8, (ctx.handle, C.byref(g.c), _ptr(x), _ptr(h_prev), n, _ptr(h_out), None),
+                      {"h": h_out, "keep": (g, x, h_prev)})
     ctx.check(ctx.lib.gru_step_q8(ctx.handle, C.byref(g.c), _ptr(x), _ptr(h_prev), n, _ptr(h_out), ts.arr if ts else None))
     return (h_out, ts.t) if taps else h_out
 
@@ -640,6 +647,57 @@ class Model:
         m.E_tgt_codes = RowCodes(ctx, m.E_tgt, dec.r.Wx.ld)
         m.c.E_tgt_codes = m.E_tgt_codes.c
         return m
+
+
+def gru_input_table(ctx, g, E, rows=1024):
+    """W_x q(E[v]) + b_x for every row v of the embedding table E: [V x 3H] fp32 on the device (the table
+    cgru_decoder_step_ahead_q8 / output_logits_beam_ahead_q8 gather GRU r's input half from), made with
+    q8_gemm_narrow in panels of `rows` rows on a context of its own (a panel needs a larger workspace)."""
+    tmp = Context(ctx.device, workspace_bytes=q8_workspace_bytes(max_n=rows, max_ld=max(2048, g.Wx.ld)), stream=ctx.stream)
+    V = E.shape[0]
+    G = torch.empty(V, g.Wx.rows, dtype=torch.float32, device=ctx.device)
+    for o in range(0, V, rows):
+        q8_gemm_narrow(tmp, g.Wx, E[o:o + rows], g.bx, Y=G[o:o + rows])
+    torch.cuda.synchronize(ctx.device)
+    tmp.close()
+    return G
+
+
+def cgru_decoder_step_ahead_q8(ctx, w, P, enc_h, s_mid, out=None, bind=False, ctx_codes=None):
+    """The decoder step from a given s' (Eq. 4-6); returns dict(s, ctx, alpha)."""
+    n, l = s_mid.shape[0], P.shape[0]
+    H, Cd = w.r.H, w.q.Wx.cols
+    o = out or {}
+    s_out = o["s"] if "s" in o else ctx.empty(n, H)
+    c_out = o["ctx"] if "ctx" in o else ctx.empty(n, Cd)
+    alpha = o["alpha"] if "alpha" in o else ctx.empty(n, l)
+    args = (ctx.handle, C.byref(w.c), _ptr(P), _ptr(enc_h), l, _ptr(s_mid), n, _ptr(s_out), _ptr(c_out), _ptr(alpha),
+            C.byref(ctx_codes.c) if ctx_codes is not None else None)
+    r = {"s": s_out, "ctx": c_out, "alpha": alpha}
+    if bind:
+        r["keep"] = (w, P, enc_h, s_mid, ctx_codes)
+        return _Bound(ctx, ctx.lib.cgru_decoder_step_ahead_q8, args, r)
+    ctx.check(ctx.lib.cgru_decoder_step_ahead_q8(*args))
+    return r
+
+
+def output_logits_beam_ahead_q8(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, state, E_tgt, gru_r, gx_table, s_mid_next, k=12,
+                                bind=False, y_codes=None, ctx_codes=None, E_codes=None):
+    """Output layer + top-k + search step + GRU r of the next step (its recurrent product in the readout's launch,
+    its gates in the selection kernel's: s_mid_next); returns dict(topk_logp, topk_idx)."""
+    n = s.shape[0]
+    lp = ctx.empty(n, k)
+    idx = ctx.empty(n, k, dtype=torch.int32)
+    by = lambda c: C.byref(c.c) if c is not None else None
+    args = (ctx.handle, C.byref(ro.c), C.byref(W_out.c), _ptr(b_out), _ptr(s), _ptr(y_emb), _ptr(ctx_vec), n, k,
+            _ptr(state), _ptr(E_tgt), E_tgt.shape[1], _ptr(lp), _ptr(idx), by(y_codes), by(ctx_codes), by(E_codes),
+            C.byref(gru_r.c), _ptr(gx_table), _ptr(s_mid_next))
+    r = {"topk_logp": lp, "topk_idx": idx}
+    if bind:
+        r["keep"] = (ro, W_out, b_out, s, y_emb, ctx_vec, state, E_tgt, gru_r, gx_table, s_mid_next, y_codes, ctx_codes, E_codes)
+        return _Bound(ctx, ctx.lib.output_logits_beam_ahead_q8, args, r)
+    ctx.check(ctx.lib.output_logits_beam_ahead_q8(*args))
+    return r
 
 
 def source_ids(ids, V_src, device=None):

@@ -171,6 +171,7 @@ q8_status q8_create(q8_ctx **out, void *hip_stream, void *workspace, size_t work
     c->att_capacity = -1;
     c->att_words_set = 0;
     c->grup_used[0] = c->grup_used[1] = 0;
+    c->gate_pause = Q8_GATE_PAUSE_DEFAULT;
     q8_status st = q8i_fill_u32(c, c->ws, Q8_WS_HEADER / 4, 0u);
     if (st) { delete c; return st; }
     *out = c;
@@ -431,6 +432,12 @@ q8_status cgru_decoder_step_codes_q8(q8_ctx *ctx, const q8_cgru_weights *w, cons
                                      y_codes, ctx_codes, nullptr);
 }
 
+namespace {
+q8_status cgru_after_r(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h, int l, const float *s_mid,
+                       int n, float *s_out, float *ctx_out, float *alpha_out, const q8_taps *taps5, q8_codes *ctx_codes,
+                       float *a, float *ghq, float *e, int8_t *cq, float *cqs);
+}
+
 q8_status cgru_decoder_step_loop_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h, int l,
                                     const float *y_emb, const float *s_prev, int n_beam, float *s_out, float *ctx_out,
                                     float *alpha_out, float *s_mid_out, const q8_taps *taps5, q8_codes *y_codes,
@@ -480,6 +487,16 @@ q8_status cgru_decoder_step_loop_q8(q8_ctx *ctx, const q8_cgru_weights *w, const
     }
     TRY(q8i_gru(ctx, &dr, 1, n, Q8I_GRU_FULL));
     if (y_out) y_codes->valid = 1;
+    return cgru_after_r(ctx, w, P, enc_h, l, s_mid, n, s_out, ctx_out, alpha_out, taps5, ctx_codes, a, ghq, e, cq, cqs);
+}
+
+namespace {
+// The decoder step from s' on (Eq. 4-6); a, ghq, e, cq, cqs: scratch of the sizes cgru_decoder_step_loop_q8 takes.
+q8_status cgru_after_r(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h, int l, const float *s_mid,
+                       int n, float *s_out, float *ctx_out, float *alpha_out, const q8_taps *taps5, q8_codes *ctx_codes,
+                       float *a, float *ghq, float *e, int8_t *cq, float *cqs)
+{
+    const int H = w->r.Wh.cols, C = w->q.Wx.cols, A = w->att_U.rows;
     // everything that depends on s' alone: u(s') of Eq. 6 and the recurrent half of GRU q
     q8_mat qWh = w->q.Wh;
     q8i_gemv_desc dj[2] = {{&w->att_U, s_mid, H, nullptr, a, A, taps5 ? taps5 + 2 : nullptr},
@@ -502,6 +519,41 @@ q8_status cgru_decoder_step_loop_q8(q8_ctx *ctx, const q8_cgru_weights *w, const
     const q8_status st = q8i_gru(ctx, &dq, 1, n, Q8I_GRU_GH_PRE);
     if (!st && dq.clear) ctx->att_words_set = 0;
     return st;
+}
+
+}  // namespace
+
+q8_status cgru_decoder_step_ahead_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h, int l,
+                                     const float *s_mid, int n_beam, float *s_out, float *ctx_out, float *alpha_out,
+                                     q8_codes *ctx_codes)
+{
+    if (ctx_codes) ctx_codes->valid = 0;
+    if (!ctx) return Q8_ERR_NULL;
+    if (!w) return q8_fail(ctx, Q8_ERR_NULL, "weights: NULL");
+    TRY(check_gru(ctx, &w->r, "r"));
+    TRY(check_gru(ctx, &w->q, "q"));
+    TRY(check_mat(ctx, &w->att_U, "att_U"));
+    const int n = n_beam, H = w->r.Wh.cols, C = w->q.Wx.cols, A = w->att_U.rows;
+    if (n <= 0 || n > kMaxNarrow) return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam = %d outside [1, %d]", n, kMaxNarrow);
+    if (l <= 0 || l > kMaxL) return q8_fail(ctx, Q8_ERR_SHAPE, "l = %d outside [1, %d]", l, kMaxL);
+    if (w->q.Wh.cols != H || w->att_U.cols != H) return q8_fail(ctx, Q8_ERR_SHAPE, "hidden sizes of r, q and att_U differ");
+    if (H % 4 || C % 4 || A % 4) return q8_fail(ctx, Q8_ERR_ALIGN, "H, C, A must be multiples of 4");
+    if (!w->att_v || !P || !enc_h || !s_mid || !s_out || !ctx_out)
+        return q8_fail(ctx, Q8_ERR_NULL, "cgru_decoder_step_ahead_q8: NULL argument");
+    if (!aligned16(w->att_v) || !aligned16(P) || !aligned16(enc_h) || !aligned16(s_mid) || !aligned16(s_out) || !aligned16(ctx_out))
+        return q8_fail(ctx, Q8_ERR_ALIGN, "cgru_decoder_step_ahead_q8: fp32 buffers need 16-byte alignment");
+    if (s_out == s_mid) return q8_fail(ctx, Q8_ERR_SHAPE, "s_out must not alias s_mid");
+    if ((size_t)n * w->r.Wh.ld > 65536 || (size_t)n * w->q.Wx.ld > 65536)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "n_beam * row length exceeds 65536");
+    Carver cv(ctx);
+    float *a = cv.take<float>((size_t)n * A);
+    float *ghq = cv.take<float>((size_t)n * 3 * H);
+    float *e = cv.take<float>((size_t)n * l);
+    int8_t *cq = cv.take<int8_t>((size_t)n * w->q.Wx.ld);
+    float *cqs = cv.take<float>(n);
+    if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "cgru_decoder_step_ahead_q8: workspace too small");
+    if (codes_usable(ctx_codes, w->q.Wx.ld)) { cq = ctx_codes->q; cqs = ctx_codes->scale; }
+    return cgru_after_r(ctx, w, P, enc_h, l, s_mid, n, s_out, ctx_out, alpha_out, nullptr, ctx_codes, a, ghq, e, cq, cqs);
 }
 
 q8_status cgru_decoder_step_batch_q8(q8_ctx *ctx, const q8_cgru_weights *w, const float *P, const float *enc_h,
@@ -686,14 +738,27 @@ static q8_status output_impl(q8_ctx *ctx, const q8_readout_weights *ro, const q8
         // the search step hands the codes of the surviving states on: the readout leaves those of s for it
         int8_t *sq = nullptr;
         float *ss = nullptr;
-        if (beam && beam->Eq) {
+        if (beam && beam->Eq && beam->lds > 0) {
             sq = cv.take<int8_t>((size_t)n * ro->W_s.ld);
             ss = cv.take<float>(n);
         }
         if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
         int exported = 0;
+        if (beam && beam->gx_table) {
+            // the recurrent half of the next step's GRU r, W_h^r q(s_j) + b_h for every state of this step: in the
+            // readout's launch where both run on their fast kernels, else in a launch of its own
+            const q8_gru_weights *g = beam->gru_r;
+            float *gh = cv.take<float>((size_t)n * g->Wh.rows);
+            if (!cv.ok) return q8_fail(ctx, Q8_ERR_WORKSPACE, "output_logits_q8: workspace too small");
+            q8_mat rWh = g->Wh;
+            const q8i_gemv_desc xd = {&rWh, s, g->Wh.cols, g->bh, gh, g->Wh.rows, nullptr};
+            int xdone = 0;
+            TRY(q8i_readout(ctx, ro, s, y_emb, ctx_vec, n, t, taps4, y_codes, ctx_codes, sq, ss, &exported, &xd, &xdone));
+            if (!xdone) TRY(q8i_gemv_jobs(ctx, &xd, 1, n));
+            beam->gh_r = gh;
+        } else
         TRY(q8i_readout(ctx, ro, s, y_emb, ctx_vec, n, t, taps4, y_codes, ctx_codes, sq, ss, &exported));
-        if (beam && beam->Eq) {
+        if (beam && beam->Eq && beam->lds > 0) {
             if (exported) { beam->sq_in = sq; beam->ss_in = ss; }
             else beam->Eq = nullptr;                               // (this readout kernel keeps its codes to itself)
         }
@@ -767,6 +832,44 @@ q8_status output_logits_beam_loop_q8(q8_ctx *ctx, const q8_readout_weights *ro, 
     const q8_status st = output_impl(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, nullptr, n_beam, k, nullptr, nullptr, topk_logp,
                                      topk_idx, nullptr, nullptr, &bd, y_codes ? &y_in : nullptr, ctx_codes);
     if (!st && hand_on && bd.Eq) { y_codes->valid = 2; s_next_codes->valid = 2; }
+    return st;
+}
+
+q8_status output_logits_beam_ahead_q8(q8_ctx *ctx, const q8_readout_weights *ro, const q8_mat *W_out, const float *b_out,
+                                      const float *s, float *y_emb, const float *ctx_vec, int n_beam, int k, void *state,
+                                      const float *E_tgt, int E, float *topk_logp, int32_t *topk_idx, q8_codes *y_codes,
+                                      const q8_codes *ctx_codes, const q8_row_codes *E_codes, const q8_gru_weights *r,
+                                      const float *gx_table, float *s_mid_next)
+{
+    // y_codes as an input: the codes of this step's y_emb for the readout (left by this call a step earlier, or by
+    // cgru_decoder_step_codes_q8 in the search's first step)
+    q8_codes y_in = {nullptr, nullptr, 0, 0};
+    if (y_codes) { y_in = *y_codes; y_codes->valid = 0; }
+    if (!ctx) return Q8_ERR_NULL;
+    if (!ro || !W_out || !state || !E_tgt || !s || !y_emb || !r || !gx_table || !s_mid_next)
+        return q8_fail(ctx, Q8_ERR_NULL, "output_logits_beam_ahead_q8: NULL argument");
+    TRY(check_gru(ctx, r, "r"));
+    if (r->Wh.cols != ro->W_s.cols || r->Wx.cols != E)
+        return q8_fail(ctx, Q8_ERR_SHAPE, "output_logits_beam_ahead_q8: GRU r does not match the readout's H and E");
+    if (k < n_beam) return q8_fail(ctx, Q8_ERR_SHAPE, "output_logits_beam_ahead_q8: need k >= n_beam");
+    if (n_beam > kMaxNarrow) return q8_fail(ctx, Q8_ERR_SHAPE, "output_logits_beam_ahead_q8: at most %d hypotheses", kMaxNarrow);
+    if (!aligned16(E_tgt) || !aligned16(gx_table) || !aligned16(s_mid_next))
+        return q8_fail(ctx, Q8_ERR_ALIGN, "fp32 buffers need 16-byte alignment");
+    if (E != ro->W_y.cols) return q8_fail(ctx, Q8_ERR_SHAPE, "E does not match the readout's embedding width");
+    if (W_out->rows >= (1 << 24)) return q8_fail(ctx, Q8_ERR_SHAPE, "output_logits_beam_ahead_q8: vocabulary of 2^24 or more");
+    const int H = ro->W_s.cols, ldy = ro->W_y.ld;
+    q8i_beam_desc bd = {state, s, E_tgt, y_emb, nullptr, E, H};
+    bd.gx_table = gx_table; bd.gru_r = r; bd.s_mid_next = s_mid_next;
+    // (the codes of the new embedding rows travel with them where the gather's pass has room; no state rows move)
+    const bool hand_on = E_codes && E_codes->q && E_codes->scale && E_codes->ld == ldy && aligned16(E_codes->q) &&
+                         codes_usable(y_codes, ldy) && E % 4 == 0 && E / 4 + ldy / 16 <= 256;
+    if (hand_on) {
+        bd.Eq = E_codes->q; bd.Es = E_codes->scale; bd.ldy = ldy; bd.lds = 0;
+        bd.yq_out = y_codes->q; bd.ys_out = y_codes->scale;
+    }
+    const q8_status st = output_impl(ctx, ro, W_out, b_out, s, y_emb, ctx_vec, nullptr, n_beam, k, nullptr, nullptr, topk_logp,
+                                     topk_idx, nullptr, nullptr, &bd, y_codes && y_in.valid ? &y_in : nullptr, ctx_codes);
+    if (!st && hand_on && bd.Eq) y_codes->valid = 2;
     return st;
 }
 

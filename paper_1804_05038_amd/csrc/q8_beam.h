@@ -37,6 +37,12 @@ struct BeamUpdateArgs {
     int8_t *yq_out, *sq_out;
     float *ys_out, *ss_out;
     int ldy, lds;
+    // Optional: the decision goes to blocks that compute GRU r of the next step from it (see out_select_kernel).
+    // xg: gate_blocks x 8 8-byte words, zero on entry; word 8 b + q = (present bit, parent slot, token) of slot q
+    // for block b, which clears it.  s_next may then be NULL (no state rows are gathered), and with Eq given
+    // sq_in / sq_out may be NULL (lds = 0: only the embedding rows' codes travel).
+    unsigned long long *xg;
+    int gate_blocks;
 };
 
 // key: larger score first, then lower parent, then lower token id
@@ -176,6 +182,18 @@ __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a, const 
             s_parent[lane] = parent0;
             s_token[lane] = token0;
         }
+        if (a.xg) {
+            // (the entries of s_parent / s_token were written by lanes of this wave)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            for (int w = lane; w < a.gate_blocks * Q8_MAX_BEAM; w += 64) {
+                const int q = w & (Q8_MAX_BEAM - 1);
+                const int par = skip ? 0 : s_parent[q], tok = skip ? 0 : s_token[q];
+                if (q < a.n)
+                    __hip_atomic_store(a.xg + w, (1ull << 63) | ((unsigned long long)(unsigned)par << 32) | (unsigned)tok,
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
     }
     __syncthreads();
     if (s_skip) return;
@@ -191,7 +209,7 @@ __device__ __forceinline__ void beam_update_body(const BeamUpdateArgs &a, const 
 // branch around a load or a store: inside a branch the compiler waits for each of them on the
 // spot, and a thread's loads and stores become as many memory round trips in a row.
 // (Moved as plain 16-byte vectors: nothing here looks inside the values.)
-template <int ROWS>
+template <int ROWS, bool STATES>
 __device__ __forceinline__ void beam_gather_rows(const BeamUpdateArgs &a, const int *s_parent, const int *s_token)
 {
     const int tid = threadIdx.x;
@@ -211,8 +229,8 @@ __device__ __forceinline__ void beam_gather_rows(const BeamUpdateArgs &a, const 
     // their scales: thread q & 7 of every wave fetches those of row q (the same words for all waves), thread q stores them
     // (unconditional loads: without codes they read the first floats of the tables and drop them)
     const int qs = min(tid & 7, a.n - 1);
-    const float ys = *(a.Eq ? a.Es + s_token[qs] : a.E_tgt), ss = *(a.Eq ? a.ss_in + s_parent[qs] : a.s_step);
-    for (int c0 = 0; c0 < max(H4, E4); c0 += 256) {
+    const float ys = *(a.Eq ? a.Es + s_token[qs] : a.E_tgt), ss = *(a.Eq && a.ss_in ? a.ss_in + s_parent[qs] : a.s_step);
+    for (int c0 = 0; c0 < (STATES ? max(H4, E4) : E4); c0 += 256) {
         const int ch = min(c0 + tid, H4 - 1);
         const bool first = c0 == 0;
         const v4i *src = first ? src0 : (const v4i *)a.E_tgt;
@@ -224,19 +242,19 @@ __device__ __forceinline__ void beam_gather_rows(const BeamUpdateArgs &a, const 
         for (int q = 0; q < ROWS; ++q) {
             const int qq = min(q, a.n - 1);
             const int par = s_parent[qq], tok = s_token[qq];
-            vs[q] = s4[(size_t)par * H4 + ch];
+            if (STATES) vs[q] = s4[(size_t)par * H4 + ch];
             ve[q] = src[(size_t)(by_parent ? par : tok) * pitch + piece];
         }
 #pragma unroll
         for (int q = 0; q < ROWS; ++q) {
             const int qq = min(q, a.n - 1);
-            sn4[(size_t)qq * H4 + ch] = vs[q];
+            if (STATES) sn4[(size_t)qq * H4 + ch] = vs[q];
             dst[(size_t)qq * pitch + piece] = ve[q];
         }
     }
     if (a.Eq && tid < a.n) {
         a.ys_out[tid] = ys;
-        a.ss_out[tid] = ss;
+        if (a.ss_out) a.ss_out[tid] = ss;
     }
 }
 
@@ -246,11 +264,15 @@ __device__ __forceinline__ void beam_gather(const BeamUpdateArgs &a, const int *
     if (((a.H | a.E) & 3) == 0) {
         // (a compute unit moves these rows at about 50 GB/s: rows that only repeat the last one cost as much
         // as the others, so the row count follows the beam in three steps)
-        if (a.n <= 4) beam_gather_rows<4>(a, s_parent, s_token);
-        else if (a.n <= 6) beam_gather_rows<6>(a, s_parent, s_token);
-        else beam_gather_rows<Q8_MAX_BEAM>(a, s_parent, s_token);
+        if (!a.s_next) {
+            if (a.n <= 4) beam_gather_rows<4, false>(a, s_parent, s_token);
+            else if (a.n <= 6) beam_gather_rows<6, false>(a, s_parent, s_token);
+            else beam_gather_rows<Q8_MAX_BEAM, false>(a, s_parent, s_token);
+        } else if (a.n <= 4) beam_gather_rows<4, true>(a, s_parent, s_token);
+        else if (a.n <= 6) beam_gather_rows<6, true>(a, s_parent, s_token);
+        else beam_gather_rows<Q8_MAX_BEAM, true>(a, s_parent, s_token);
     } else {
-        for (int e = tid; e < a.n * a.H; e += blockDim.x) {
+        for (int e = tid; a.s_next && e < a.n * a.H; e += blockDim.x) {
             const int q = e / a.H, c = e - q * a.H;
             a.s_next[e] = a.s_step[(size_t)s_parent[q] * a.H + c];
         }

@@ -1,6 +1,7 @@
 // q8_decoder.hip -- the float part of the attention of Eq. 5-6 and the first layer of the
 // output network g of Eq. 2 ("Pieces of Eight: 8-bit Neural Machine Translation").
 #include "q8_internal.h"
+#include "q8_gemv_fast.h"
 
 // ======================================================================== attention ==
 
@@ -496,15 +497,14 @@ __global__ __launch_bounds__(256) void readout_kernel(ReadoutArgs a)
 // their producers left (the GRU that multiplied y at the start of the step, the attention block
 // that finished c); they are copied into LDS and s alone is quantized here.
 template <int N, int CH, bool PRE>
-__global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
+__device__ __forceinline__ void readout_fast_body(const ReadoutArgs &a, int bid, int8_t *smem)
 {
-    extern __shared__ __align__(16) int8_t smem[];
     __shared__ float s_scale[24];
     __shared__ float s_red[3 * 8 * 4];
     __shared__ int s_t[4][3 * N];
     int8_t *sq = smem, *yq = sq + N * a.lds, *cq = yq + N * a.ldy;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int unit = blockIdx.x * 4 + wave;
+    const int unit = bid * 4 + wave;
     const bool ok = unit < a.R;
 
     // PRE: the codes as 16-byte pieces (thread tid takes pieces tid, tid + 256, ... of each input; a piece
@@ -554,8 +554,8 @@ __global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
         int8_t *const dst[3] = {sq, yq, cq};
         x_finish_multi<N, CH, 3>(rin, lds3, dst, s_scale, s_red);
     }
-    if (blockIdx.x == 0) readout_x_taps<N>(a, sq, yq, cq, s_scale);
-    if (blockIdx.x == 0 && a.sq_out) {
+    if (bid == 0) readout_x_taps<N>(a, sq, yq, cq, s_scale);
+    if (bid == 0 && a.sq_out) {
         for (int p = threadIdx.x; p < N * a.lds / 16; p += 256) *(v4i *)(a.sq_out + 16 * p) = *(const v4i *)(sq + 16 * p);
         if (threadIdx.x < N) a.ss_out[threadIdx.x] = s_scale[threadIdx.x];
     }
@@ -588,6 +588,24 @@ __global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
         if (a.ty.acc) a.ty.acc[(size_t)lane * a.R + unit] = vy;
         if (a.tc.acc) a.tc.acc[(size_t)lane * a.R + unit] = vc;
     }
+}
+
+template <int N, int CH, bool PRE>
+__global__ __launch_bounds__(256) void readout_fast_kernel(ReadoutArgs a)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    readout_fast_body<N, CH, PRE>(a, blockIdx.x, smem);
+}
+
+// The readout and, in the blocks after its own, a streaming product that reads the same new states: the
+// recurrent half of the next step's GRU r, W_h^r q(s) + b_h (rows of at most 1024 bytes), which then costs no
+// launch of its own on the chain of dependent launches.
+template <int N, int CH, bool PRE>
+__global__ __launch_bounds__(256) void readout_with_product_kernel(ReadoutArgs a, GemvJobs jobs, int readout_blocks)
+{
+    extern __shared__ __align__(16) int8_t smem[];
+    if ((int)blockIdx.x < readout_blocks) readout_fast_body<N, CH, PRE>(a, blockIdx.x, smem);
+    else gemv_fast_body<N, 1, false, 2, true>(jobs, (int)blockIdx.x - readout_blocks, smem);
 }
 
 // Panels of more than 8 hypotheses: the three products of g's first layer came from the
@@ -691,8 +709,18 @@ q8_status q8i_attention(q8_ctx *ctx, const float *P, const float *enc_h, int l, 
 }
 
 template <int N>
-static void launch_readout_n(q8_ctx *ctx, const ReadoutArgs &a, int blocks, size_t smem, int ch, bool pre)
+static void launch_readout_n(q8_ctx *ctx, const ReadoutArgs &a, int blocks, size_t smem, int ch, bool pre, const GemvJobs *extra,
+                             int extra_blocks, size_t extra_smem)
 {
+    if (extra) {
+        const size_t sm = smem > extra_smem ? smem : extra_smem;
+        const dim3 grid(blocks + extra_blocks);
+        if (ch == 1 && pre) Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_with_product_kernel<N, 1, true>), grid, dim3(256), sm, a, *extra, blocks);
+        else if (ch == 2 && pre) Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_with_product_kernel<N, 2, true>), grid, dim3(256), sm, a, *extra, blocks);
+        else if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_with_product_kernel<N, 1, false>), grid, dim3(256), sm, a, *extra, blocks);
+        else Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_with_product_kernel<N, 2, false>), grid, dim3(256), sm, a, *extra, blocks);
+        return;
+    }
     if (ch == 1 && pre) Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_fast_kernel<N, 1, true>), dim3(blocks), dim3(256), smem, a);
     else if (ch == 2 && pre) Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_fast_kernel<N, 2, true>), dim3(blocks), dim3(256), smem, a);
     else if (ch == 1) Q8_LAUNCH(ctx, Q8_KERNEL_READOUT, (readout_fast_kernel<N, 1, false>), dim3(blocks), dim3(256), smem, a);
@@ -702,10 +730,11 @@ static void launch_readout_n(q8_ctx *ctx, const ReadoutArgs &a, int blocks, size
 
 q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,
                       float *t_out, const q8_taps *taps3, const q8_codes *y_codes, const q8_codes *c_codes,
-                      int8_t *sq_out, float *ss_out, int *s_exported)
+                      int8_t *sq_out, float *ss_out, int *s_exported, const q8i_gemv_desc *extra, int *extra_done)
 {
     ReadoutArgs a;
     if (s_exported) *s_exported = 0;
+    if (extra_done) *extra_done = 0;
     // codes from the producers: both or neither, and only in the layout the kernel copies (the matrices' own pitches)
     const bool pre = y_codes && c_codes && y_codes->valid && c_codes->valid && y_codes->q && c_codes->q && y_codes->scale &&
                      c_codes->scale && y_codes->ld == ro->W_y.ld && c_codes->ld == ro->W_c.ld;
@@ -731,15 +760,22 @@ q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s,
     const bool exporting = ch != 0 && sq_out && ss_out;             // (the general kernel does not export)
     a.sq_out = exporting ? sq_out : nullptr; a.ss_out = ss_out;
     if (s_exported) *s_exported = exporting ? 1 : 0;
+    // a product of the same states in the blocks after the readout's own (fast kernels of both, rows of <= 1024 bytes)
+    GemvJobs xj;
+    int xblocks = 0;
+    size_t xsmem = 0;
+    const bool with_extra = extra && (ch == 1 || ch == 2) && q8i_gemv_fast_setup(extra, n, &xj, &xblocks, &xsmem);
+    if (with_extra && extra_done) *extra_done = 1;
+    const GemvJobs *xp = with_extra ? &xj : nullptr;
     switch (n) {
-    case 1: launch_readout_n<1>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
-    case 2: launch_readout_n<2>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
-    case 3: launch_readout_n<3>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
-    case 4: launch_readout_n<4>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
-    case 5: launch_readout_n<5>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
-    case 6: launch_readout_n<6>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
-    case 7: launch_readout_n<7>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
-    default: launch_readout_n<8>(ctx, a, blocks, smem, ch, pre && ch != 0); break;
+    case 1: launch_readout_n<1>(ctx, a, blocks, smem, ch, pre && ch != 0, xp, xblocks, xsmem); break;
+    case 2: launch_readout_n<2>(ctx, a, blocks, smem, ch, pre && ch != 0, xp, xblocks, xsmem); break;
+    case 3: launch_readout_n<3>(ctx, a, blocks, smem, ch, pre && ch != 0, xp, xblocks, xsmem); break;
+    case 4: launch_readout_n<4>(ctx, a, blocks, smem, ch, pre && ch != 0, xp, xblocks, xsmem); break;
+    case 5: launch_readout_n<5>(ctx, a, blocks, smem, ch, pre && ch != 0, xp, xblocks, xsmem); break;
+    case 6: launch_readout_n<6>(ctx, a, blocks, smem, ch, pre && ch != 0, xp, xblocks, xsmem); break;
+    case 7: launch_readout_n<7>(ctx, a, blocks, smem, ch, pre && ch != 0, xp, xblocks, xsmem); break;
+    default: launch_readout_n<8>(ctx, a, blocks, smem, ch, pre && ch != 0, xp, xblocks, xsmem); break;
     }
     return q8i_launch_check(ctx, "readout");
 }

@@ -731,3 +731,20 @@ __device__ __forceinline__ float exp_le0(float x) { return __builtin_amdgcn_exp2
 // fp32 nonlinearities of the gates, evaluated in double and rounded once (q8_math.h).
 __device__ __forceinline__ float sigmoid_rn(float a) { return q8_sigmoid_rn(a); }
 __device__ __forceinline__ float tanh_rn(float a) { return q8_tanh_rn(a); }
+
+// Gates of one hidden unit from its six pre-activations (fp32, one operation per
+// statement, transcendental functions in double rounded once).
+__device__ __forceinline__ float gru_gates(const float (&gx)[3], const float (&gh)[3], float h_prev)
+{
+    const float pr = gx[0] + gh[0];
+    const float r = sigmoid_rn(pr);
+    const float pz = gx[1] + gh[1];
+    const float z = sigmoid_rn(pz);
+    const float rn = r * gh[2];
+    const float pn = gx[2] + rn;
+    const float nn = tanh_rn(pn);
+    const float omz = 1.0f - z;
+    const float t1 = omz * nn;
+    const float t2 = z * h_prev;
+    return t1 + t2;
+}

@@ -62,23 +62,6 @@ __device__ __forceinline__ void gru_x_export(const GruJob &J, const int8_t *xq, 
     if (threadIdx.x < N) J.xs_out[threadIdx.x] = s_scale[threadIdx.x];
 }
 
-// Gates of one hidden unit from its six pre-activations (fp32, one operation per
-// statement, transcendental functions in double rounded once).
-__device__ __forceinline__ float gru_gates(const float (&gx)[3], const float (&gh)[3], float h_prev)
-{
-    const float pr = gx[0] + gh[0];
-    const float r = sigmoid_rn(pr);
-    const float pz = gx[1] + gh[1];
-    const float z = sigmoid_rn(pz);
-    const float rn = r * gh[2];
-    const float pn = gx[2] + rn;
-    const float nn = tanh_rn(pn);
-    const float omz = 1.0f - z;
-    const float t1 = omz * nn;
-    const float t2 = z * h_prev;
-    return t1 + t2;
-}
-
 // General shapes.
 template <int N, int MODE>
 __global__ __launch_bounds__(256) void gru_kernel(GruJobs jobs)

@@ -23,6 +23,7 @@
 #define Q8_MAX_BEAM 8
 #define Q8_MAX_COLS 1024            // vectors of one batched call
 #define Q8_WS_HEADER 262144
+#define Q8_GATE_PAUSE_DEFAULT 10     // short sleeps of the blocks that wait for the search step's decision before their first poll
 #define Q8_WS_SCRATCH_SLOT 6144
 #define Q8_WS_ENC_ERR 6208          // set to 1 by the one-launch encoder if a wait gave up (zeroed before each such launch)
 #define Q8_WS_ATT_ERR 6212          // the same for the attention kernel whose blocks wait for each other
@@ -30,6 +31,7 @@
 #define Q8_WS_ATT_XCHG_PER_HYP 2048
 #define Q8_WS_SELECT_XCHG 24576      // 128 words: the top-k entries on their way to the search step
 #define Q8_WS_GRUP_XCHG 32768        // 2 x 10752 words: partial maxima of the one-launch panel GRU (two regions that take turns)
+#define Q8_WS_GATES_XCHG 118784      // 64 x 8 words: the search step's decision on its way to the blocks that compute the next GRU r
 #define Q8_WS_PSEL_XCHG 131072       // 1024 x 16 8-byte words: the same hand-over for a panel of slots (sentences side by side)
 #define Q8_ENC_SPIN_DEFAULT (1 << 20)
 
@@ -57,6 +59,9 @@ struct q8_ctx {
     // one-launch panel GRU: unit groups whose exchange words a launch has left set in each of the two regions
     // (0: the region is clear); the launch after it clears them, see q8i_gru_panel
     int grup_used[2];
+    // the decoding loop whose GRU r runs ahead (output_logits_beam_ahead_q8): short sleeps of the blocks that
+    // wait for the search step's decision before their first poll
+    int gate_pause;
 };
 
 // Launch of a kernel of class `kind` (a Q8_KERNEL_* value).  While a profile of that class
@@ -129,6 +134,13 @@ struct q8i_beam_desc {
     int8_t *yq_out, *sq_out;
     float *ys_out, *ss_out;
     int ldy, lds;
+    // optional, all or none: GRU r of the next step (Eq. 3) computed in the selection kernel's launch from the
+    // decision (see out_select_kernel): W_x^r q(E_tgt[v]) + b_x for every token [V x 3H]; the weights of GRU r, whose
+    // recurrent product W_h^r q(s_step[j]) + b_h [n x 3H] the readout's launch makes (gh_r: where it is, set by the
+    // output layer); and where s' of the next step goes [n x H]
+    const float *gx_table, *gh_r;
+    const q8_gru_weights *gru_r;
+    float *s_mid_next;
 };
 
 // Search steps of several sentences side by side: sentence s owns slots [s beam, (s + 1) beam) of every
@@ -247,7 +259,12 @@ q8_status q8i_beam_read_batch(q8_ctx *ctx, const void *states, size_t stride, in
 // with the pitches of W_y and W_c
 q8_status q8i_readout(q8_ctx *ctx, const q8_readout_weights *ro, const float *s, const float *y, const float *c, int n,
                       float *t_out, const q8_taps *taps3, const q8_codes *y_codes = nullptr, const q8_codes *c_codes = nullptr,
-                      int8_t *sq_out = nullptr, float *ss_out = nullptr, int *s_exported = nullptr);
+                      int8_t *sq_out = nullptr, float *ss_out = nullptr, int *s_exported = nullptr,
+                      const struct q8i_gemv_desc *extra = nullptr, int *extra_done = nullptr);
+// One product with rows of at most 1024 bytes on the streaming product's fast kernel body, as blocks of another
+// kernel (see readout_with_product_kernel): fills the job, its block count and LDS bytes; false if it does not fit.
+struct GemvJobs;
+bool q8i_gemv_fast_setup(const struct q8i_gemv_desc *d, int n, struct GemvJobs *jobs, int *blocks, size_t *smem);
 q8_status q8i_probe_read(q8_ctx *ctx, const void *buf, size_t bytes);
 q8_status q8i_math_eval(q8_ctx *ctx, int fn, const void *x, void *y, size_t n);
 int q8i_out_tiles(int V);

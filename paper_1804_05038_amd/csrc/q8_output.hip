@@ -420,9 +420,55 @@ struct SelectArgs {
     unsigned *wait_err;
     int spin_limit;
     BeamUpdateArgs bu;
+    // with bu.xg: blocks n .. n + bu.gate_blocks - 1 compute s' of the next step (Eq. 3) once block 0 has decided
+    const float *gx_table, *gh_r;
+    float *s_mid_next;
+    int gate_pause;         // short sleeps before the first poll for the decision
 };
 
-#define SEL_CAP 2048          // survivors held in LDS
+#define SEL_CAP 2048
+#define SEL_GATE_BLOCKS_MAX 64
+
+// GRU r of the next decoder step (Eq. 3) ahead of its launch.  Its two products do not wait for the search
+// step's decision: W_x^r q(y) + b_x depends on the token alone (a table over the vocabulary, gx_table), and
+// W_h^r q(s) + b_h of every state of this step was computed in the readout's launch (gh_r).  What is left, the
+// gates of slot q from row token[q] of the one and row parent[q] of the other, is done here, by blocks of the
+// selection kernel that wait for the decision: block 0 publishes it as tagged words, eight per gate block,
+// and each block clears its own.  The wait is bounded; a block that gives up sets wait_err and goes on with
+// indices kept inside the tables.
+__device__ __forceinline__ void ahead_gates_block(const SelectArgs &a)
+{
+    __shared__ int s_par[Q8_MAX_BEAM], s_tok[Q8_MAX_BEAM];
+    const int gb = blockIdx.x - a.n, tid = threadIdx.x, n = a.n, H = a.bu.H;
+    if (tid < 64) {
+        unsigned long long *xg = a.bu.xg + gb * Q8_MAX_BEAM;
+        // (polls that come long before the decision only disturb the blocks that work towards it)
+        for (int i = 0; i < a.gate_pause; ++i) __builtin_amdgcn_s_sleep(16);
+        const int q = min(tid, n - 1);
+        unsigned long long x = 0ull;
+        bool ok = false;
+        for (int spin = 0; spin < a.spin_limit; ++spin) {
+            x = __hip_atomic_load(xg + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (__all((x >> 63) != 0ull)) { ok = true; break; }
+            __builtin_amdgcn_s_sleep(4);
+        }
+        if (!ok && tid == 0) __hip_atomic_store(a.wait_err, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid < n) {
+            const int par = (int)((x >> 32) & 0xFull), tok = (int)(x & 0xFFFFFFull);
+            s_par[tid] = par < n ? par : 0;
+            s_tok[tid] = tok < a.V ? tok : 0;
+            xg[tid] = 0ull;
+        }
+    }
+    __syncthreads();
+    for (int e = gb * 256 + tid; e < n * H; e += a.bu.gate_blocks * 256) {
+        const int q = e / H, u = e - q * H;
+        const float *x = a.gx_table + (size_t)s_tok[q] * 3 * H + u, *h = a.gh_r + (size_t)s_par[q] * 3 * H + u;
+        const float xv[3] = {x[0], x[H], x[2 * H]}, hv[3] = {h[0], h[H], h[2 * H]};
+        a.s_mid_next[(size_t)q * H + u] = gru_gates(xv, hv, a.bu.s_step[(size_t)s_par[q] * H + u]);
+    }
+}
+          // survivors held in LDS
 
 // One block of 256 threads per hypothesis; thread t owns tiles t, t + 256, ... (up to 16).
 // (1) log-sum-exp from the tile partials.  (2) Each wave sorts its 64 threads' maxima; the
@@ -451,6 +497,7 @@ __global__ __launch_bounds__(256) void out_select_kernel(SelectArgs a)
     __shared__ unsigned long long s_top[16];
     const int j = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = a.n, k = a.k;
     const int ntiles = a.ntiles;
+    if (j >= n) { ahead_gates_block(a); return; }
     if (tid == 0) { s_nq = 0; s_ns = 0; }
     if (tid < 16) s_top[tid] = topk_key(-INFINITY, 0);
 
@@ -1014,7 +1061,16 @@ static q8_status launch_select(q8_ctx *ctx, const float *part_max, const double 
     } else {
         memset(&s.bu, 0, sizeof(s.bu));
     }
-    Q8_LAUNCH(ctx, Q8_KERNEL_SELECT, out_select_kernel, dim3(n), dim3(256), 0, s);
+    int gate_blocks = 0;
+    s.gx_table = nullptr; s.gh_r = nullptr; s.s_mid_next = nullptr; s.gate_pause = ctx->gate_pause;
+    if (beam && beam->gx_table) {
+        gate_blocks = (n * beam->H + 255) / 256;
+        if (gate_blocks > SEL_GATE_BLOCKS_MAX) gate_blocks = SEL_GATE_BLOCKS_MAX;
+        s.gx_table = beam->gx_table; s.gh_r = beam->gh_r; s.s_mid_next = beam->s_mid_next;
+        s.bu.xg = (unsigned long long *)(ctx->ws + Q8_WS_GATES_XCHG);
+        s.bu.gate_blocks = gate_blocks;
+    }
+    Q8_LAUNCH(ctx, Q8_KERNEL_SELECT, out_select_kernel, dim3(n + gate_blocks), dim3(256), 0, s);
     return q8i_launch_check(ctx, "output");
 }
 

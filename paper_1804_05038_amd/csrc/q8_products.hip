@@ -3,6 +3,7 @@
 // product (16-byte loads, 4-way int8 dots, DPP reductions), and the narrow product on the
 // int8 matrix cores for more than 8 vectors.
 #include "q8_internal.h"
+#include "q8_gemv_fast.h"
 
 // =============================================================== weight quantization ==
 
@@ -75,43 +76,6 @@ __global__ void fill_u32_kernel(unsigned *p, int n, unsigned v)
 
 // ====================================================== streaming matrix x vector(s) ==
 
-struct GemvJob {
-    const int8_t *W;
-    const float *X;
-    const float *bias;
-    float *Y;
-    int8_t *tap_xq;
-    float *tap_xscale;
-    int32_t *tap_acc;
-    int rows, cols, ld, ldx, ldy, lpr, block0, rpb;
-    float w_scale;
-    const float *row_scale;     // NULL, or one weight scale per row in place of w_scale
-};
-#define Q8_MAX_JOBS 3
-struct GemvJobs {
-    GemvJob j[Q8_MAX_JOBS];
-    int njobs;
-};
-
-__device__ __forceinline__ int pick_job(const GemvJobs &jobs)
-{
-    int ji = 0;
-    for (int t = 1; t < jobs.njobs; ++t)
-        if ((int)blockIdx.x >= jobs.j[t].block0) ji = t;
-    return ji;
-}
-
-template <int N>
-__device__ __forceinline__ void write_x_taps(const GemvJob &J, const int8_t *xq, const float *s_scale)
-{
-    if (J.tap_xq)
-        for (int e = threadIdx.x; e < N * J.cols; e += blockDim.x) {
-            const int j = e / J.cols, k = e - j * J.cols;
-            J.tap_xq[e] = xq[j * J.ld + k];
-        }
-    if (J.tap_xscale && threadIdx.x < N) J.tap_xscale[threadIdx.x] = s_scale[threadIdx.x];
-}
-
 // General shapes.  Up to Q8_MAX_JOBS independent products in one launch, each with
 // N <= 8 vectors.  A block belongs to one job, quantizes that job's vectors into LDS
 // and streams its slice of rows.
@@ -121,7 +85,7 @@ __global__ __launch_bounds__(256) void gemv_jobs_kernel(GemvJobs jobs)
     extern __shared__ __align__(16) int8_t smem[];
     __shared__ float s_scale[8];
     __shared__ float s_red[8 * 4];
-    const GemvJob &J = jobs.j[pick_job(jobs)];
+    const GemvJob &J = jobs.j[pick_job(jobs, blockIdx.x)];
     const int blk = blockIdx.x - J.block0;
     const int ld = J.ld;
 
@@ -161,104 +125,11 @@ __global__ __launch_bounds__(256) void gemv_jobs_kernel(GemvJobs jobs)
     }
 }
 
-// The lane's partial sums of U staged rows against the N quantized vectors in LDS, without a
-// branch: a lane whose 16 bytes lie past the row holds zeros (the loader read them from nowhere)
-// and multiplies them with the row's last 16 codes.
-template <int N, int U, int CH>
-__device__ __forceinline__ void rows_dot_part_nb(const v4i (&w)[U][CH], int ld, int lane, const int8_t *xq, int (&acc)[U][N])
-{
-#pragma unroll
-    for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int j = 0; j < N; ++j) acc[u][j] = 0;
-#pragma unroll
-    for (int c = 0; c < CH; ++c) {
-        const int off = min((c * 64 + lane) * 16, ld - 16);
-#pragma unroll
-        for (int j = 0; j < N; ++j) {
-            const v4i x = *(const v4i *)(xq + (size_t)j * ld + off);
-#pragma unroll
-            for (int u = 0; u < U; ++u) acc[u][j] = dot16(w[u][c], x, acc[u][j]);
-        }
-    }
-}
-
-// Rows of at most 1024 * CH bytes and cols % 4 == 0: activations and the first U rows of every
-// wave are requested before anything is waited for; after that two register sets take turns, one
-// pass's rows being multiplied while the next pass's are in flight (U rows per wave and pass).
-// ROWS: every job has one weight scale per row (requested with the row's bias).
-// STREAM: small matrices (a decoder step's) are read with the non-temporal hint, large ones plainly,
-// so that a matrix of the size of the L2 that is multiplied again and again stays there.
 template <int N, int CH, bool ROWS, int U, bool STREAM>
 __global__ __launch_bounds__(256) void gemv_fast_kernel(GemvJobs jobs)
 {
     extern __shared__ __align__(16) int8_t smem[];
-    __shared__ float s_scale[8];
-    __shared__ float s_red[8 * 4];
-    __shared__ int s_t[4][U * N];
-    const GemvJob &J = jobs.j[pick_job(jobs)];
-    const int blk = blockIdx.x - J.block0;
-    const int ld = J.ld;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int r_begin = blk * J.rpb;
-    const int r_end = min(J.rows, r_begin + J.rpb);
-
-    XRegs<N, CH> xr;
-    x_load<N, CH>(xr, J.X, N, J.cols, J.ldx);
-    int r = r_begin + wave * U;
-    const __amdgpu_buffer_rsrc_t rw = q8_rsrc(J.W, (size_t)J.rows * ld);
-    const __amdgpu_buffer_rsrc_t rb = q8_rsrc(J.bias, J.bias ? (size_t)J.rows * sizeof(float) : 0);
-    const __amdgpu_buffer_rsrc_t rs = q8_rsrc(J.row_scale, ROWS ? (size_t)J.rows * sizeof(float) : 0);
-    const int last_row = J.rows - 1;
-    // A pass's rows, their biases and (ROWS) their scales, all requested without a branch: rows past
-    // the block's end read from nowhere (zeros); the per-row floats take one load instruction per
-    // pass, lane u reading row u's (from a clamped row; absent arrays read as zero): a load
-    // instruction per row would double the kernel's count of them.
-    auto request = [&](v4i (&wr)[U][CH], float (&b)[2], int r0) {
-        int row[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) row[u] = r0 + u < r_end ? r0 + u : -1;
-        rows_load<U, CH, STREAM>(wr, rw, row, ld, lane);
-        const int off = min(r0 + (lane & (U - 1)), last_row) * 4;
-        b[0] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rb, off, 0, 0));
-        b[1] = ROWS ? __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rs, off, 0, 0)) : 0.0f;
-    };
-    v4i w[U][CH], w2[U][CH];
-    float bw[2], bw2[2];
-    request(w, bw, r);
-    x_finish<N, CH>(xr, N, ld, smem, s_scale, s_red);
-    if (blk == 0) write_x_taps<N>(J, smem, s_scale);
-    float cj = 0.0f, sxj = 0.0f;
-    if (lane < N) { sxj = s_scale[lane]; cj = J.w_scale * sxj; }
-    const bool has_bias = J.bias != nullptr;
-
-    auto finish = [&](const v4i (&wr)[U][CH], const float (&b)[2], int r0) {
-        int part[U][N], mine[U];
-        rows_dot_part_nb<N, U, CH>(wr, ld, lane, smem, part);
-        sums_to_lanes<N, U>(part, lane, s_t[wave], mine);      // lane j < N: the totals of vector j
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int a = mine[u];
-            const float bu = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(b[0]), u));
-            const float su = ROWS ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(b[1]), u)) : 0.0f;
-            float y = (float)a * (ROWS ? su * sxj : cj);
-            const float yb = y + bu;
-            y = has_bias ? yb : y;
-            if (lane < N && r0 + u < r_end) {
-                J.Y[(size_t)lane * J.ldy + r0 + u] = y;
-                if (J.tap_acc) J.tap_acc[(size_t)lane * J.rows + r0 + u] = a;
-            }
-        }
-    };
-    while (r < r_end) {
-        request(w2, bw2, r + 4 * U);
-        finish(w, bw, r);
-        r += 4 * U;
-        if (r >= r_end) break;
-        request(w, bw, r + 4 * U);
-        finish(w2, bw2, r);
-        r += 4 * U;
-    }
+    gemv_fast_body<N, CH, ROWS, U, STREAM>(jobs, blockIdx.x, smem);
 }
 
 // ================================================== one pass over a large matrix ==
@@ -500,6 +371,27 @@ static void launch_gemv_n(q8_ctx *ctx, const GemvJobs &jobs, int blocks, size_t 
     else if (rows) launch_gemv_nu<N, true, 2, false>(ctx, jobs, blocks, smem, ch);
     else if (stream) launch_gemv_nu<N, false, 2, true>(ctx, jobs, blocks, smem, ch);
     else launch_gemv_nu<N, false, 2, false>(ctx, jobs, blocks, smem, ch);
+}
+
+bool q8i_gemv_fast_setup(const q8i_gemv_desc *d, int n, GemvJobs *jobs, int *blocks, size_t *smem)
+{
+    if (d->row_scale || d->taps || d->W->cols % 4 != 0 || (size_t)d->W->rows * d->W->ld >= (1u << 31) || q8_fast_ch(d->W->ld) != 1)
+        return false;
+    memset(jobs, 0, sizeof(*jobs));
+    jobs->njobs = 1;
+    GemvJob &J = jobs->j[0];
+    J.W = d->W->data; J.X = d->X; J.bias = d->bias; J.Y = d->Y;
+    J.rows = d->W->rows; J.cols = d->W->cols; J.ld = d->W->ld;
+    J.ldx = d->ldx; J.ldy = d->ldy; J.w_scale = d->W->scale;
+    J.lpr = q8_lanes_per_row(J.ld);
+    const int pass = 4 * 2;                       // rows per block and pass of the fast kernel (four waves, two rows each)
+    int rpb = (J.rows + 2047) / 2048;
+    rpb = (rpb + pass - 1) / pass * pass;
+    J.rpb = rpb;
+    J.block0 = 0;
+    *blocks = (J.rows + rpb - 1) / rpb;
+    *smem = (size_t)n * J.ld;
+    return true;
 }
 
 q8_status q8i_gemv_jobs(q8_ctx *ctx, const q8i_gemv_desc *d, int njobs, int n)

@@ -467,3 +467,64 @@ def test_codes_travel_from_the_decoder_step_to_the_output_layer(q, ctx, oracle, 
     r1 = q.cgru_decoder_step_q8(ctx, m.dec, P, enc_h, y.clone(), s.clone(), codes=bad)
     assert not bad[0].valid and not bad[1].valid
     assert_same(r1["s"], np_(res[0][0]), "s with unusable code buffers")
+
+
+def _ahead_search(q, c, m, P, enc_h, n, s0, T, gx, codes, k=6):
+    """A search of T steps with GRU r taken off the chain (cgru_decoder_step_ahead_q8 +
+    output_logits_beam_ahead_q8); returns every step's s', s, context, top-k tables and y, and the result."""
+    E, H = m.E_tgt.shape[1], m.dec.r.H
+    state = torch.zeros(q.q8_beam_state_bytes(T), dtype=torch.uint8, device=c.device)
+    y, s = c.empty(n, E), c.empty(n, H)
+    q.q8_beam_init(c, state, n, T, s0, m.E_tgt, y, s)
+    s_mid = [q.gru_step_q8(c, m.dec.r, y, s), c.empty(n, H)]
+    yc = q.Codes(c, n, m.dec.r.Wx.ld) if codes else None
+    cc = q.Codes(c, n, m.dec.q.Wx.ld) if codes else None
+    trace = []
+    for t in range(T):
+        r = q.cgru_decoder_step_ahead_q8(c, m.dec, P, enc_h, s_mid[t & 1], ctx_codes=cc)
+        o = q.output_logits_beam_ahead_q8(c, m.ro, m.W_out, m.b_out, r["s"], y, r["ctx"], state, m.E_tgt, m.dec.r, gx,
+                                          s_mid[(t + 1) & 1], k=k, y_codes=yc, ctx_codes=cc,
+                                          E_codes=m.E_tgt_codes if codes else None)
+        trace += [np_(s_mid[t & 1]), np_(r["s"]), np_(r["ctx"]), np_(o["topk_logp"]), np_(o["topk_idx"]), np_(y)]
+    return trace, q.q8_beam_result(c, state, T)
+
+
+@pytest.mark.parametrize("dims,n,l,T,codes", [
+    (dict(V=500, E=64, H=128, A=64, R=64, w_std=0.2, b_std=0.1), 4, 9, 12, True),
+    (dict(V=13, E=16, H=32, A=16, R=16, w_std=0.5, b_std=0.3), 3, 5, 15, False),
+    (dict(V=60, E=32, H=64, A=32, R=32, w_std=0.4, b_std=0.2), 8, 7, 15, True),
+    (dict(V=700, E=620, H=1000, A=1000, R=620, w_std=0.2, b_std=0.1), 5, 6, 6, True),
+    (dict(), 5, 30, 8, True), (dict(), 1, 11, 5, False)])
+def test_decoding_loop_with_gru_r_ahead_of_the_decision(q, ctx, oracle, dims, n, l, T, codes):
+    """cgru_decoder_step_ahead_q8 + output_logits_beam_ahead_q8 (the next step's s' from a table of the input
+    products over the vocabulary, the recurrent products made in the readout's launch, and gates computed by
+    blocks of the selection kernel once the search step has decided) against cgru_decoder_step_q8 +
+    output_logits_beam_q8: every s', state, context vector, top-k table and embedding row bit for bit at every
+    step, over searches in which hypotheses end and slots die, twice in a row (exchange words left clear)."""
+    p = synth.full_model(seed=27, **dims)
+    m = q.Model.from_params(ctx, p)
+    E, H = m.E_tgt.shape[1], m.dec.r.H
+    rng = np.random.default_rng(n + l)
+    enc_h = ctx.f32(rng.standard_normal((l, 2 * H)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    s0 = ctx.f32(rng.standard_normal(H).astype(np.float32))
+    gx = q.gru_input_table(ctx, m.dec.r, m.E_tgt)
+    # the table against the plain product of a few rows
+    rows = [0, m.E_tgt.shape[0] // 2, m.E_tgt.shape[0] - 1]
+    assert_same(gx[rows], np_(q.q8_gemm_narrow(ctx, m.dec.r.Wx, m.E_tgt[rows].contiguous(), m.dec.r.bx)), "table rows")
+
+    state = torch.zeros(q.q8_beam_state_bytes(T), dtype=torch.uint8, device=ctx.device)
+    y, s = ctx.empty(n, E), ctx.empty(n, H)
+    q.q8_beam_init(ctx, state, n, T, s0, m.E_tgt, y, s)
+    ref = []
+    for t in range(T):
+        r = q.cgru_decoder_step_q8(ctx, m.dec, P, enc_h, y, s)
+        o = q.output_logits_beam_q8(ctx, m.ro, m.W_out, m.b_out, r["s"], y, r["ctx"], state, m.E_tgt, s, k=max(6, n))
+        ref += [np_(r["s_mid"]), np_(r["s"]), np_(r["ctx"]), np_(o["topk_logp"]), np_(o["topk_idx"]), np_(y)]
+    ref_res = q.q8_beam_result(ctx, state, T)
+    for rep in range(2):
+        got, res = _ahead_search(q, ctx, m, P, enc_h, n, s0, T, gx, codes, k=max(6, n))
+        q.q8_encode_check(ctx)
+        for i, (a, b) in enumerate(zip(got, ref)):
+            assert_same(a, b, "run %d, step %d, output %d" % (rep, i // 6, i % 6))
+        assert res[0].tolist() == ref_res[0].tolist() and res[1:] == ref_res[1:]
