@@ -622,7 +622,7 @@ def main():
     # The timed loops take GRU r off the chain of dependent launches (see DecodeLoop); the loops above, the plain
     # cgru_decoder_step_q8 + output_logits_beam_q8, serve the per-call timings.  The table of GRU r's input products
     # over the vocabulary, W_x^r q(E_tgt[v]) + b_x [50000 x 3072] fp32, is part of the model like its int8 weights.
-    gx = None if os.environ.get("Q8_BENCH_NO_AHEAD") else q.gru_input_table(ctx, m.dec.r, m.E_tgt)
+    gx = None if os.environ.get("Q8_BENCH_NO_AHEAD") else m.gx_r
     hloop5 = DecodeLoop(q, ctx, m, P, enc_h, BEAM, rng, gx=gx) if gx is not None else loop5
     hloop1 = DecodeLoop(q, ctx, m, P, enc_h, 1, rng, gx=gx) if gx is not None else loop1
 

@@ -503,6 +503,8 @@ typedef struct {
     const float *b_out;
     q8_row_codes E_tgt_codes;        /* optional (q == NULL: none): E_tgt row by row at pitch dec.r.Wx.ld; q8_translate
                                         then hands codes from the search step to the next decoder step */
+    const float *gx_r;               /* optional (NULL: none): the table of cgru_decoder_step_ahead_q8, W_x^r q(E_tgt[v]) + b_x
+                                        [V_tgt x 3H] fp32; q8_translate then decodes with GRU r off the chain of launches */
 } q8_model;
 
 /* Workspace bytes that q8_translate needs on top of q8_workspace_bytes(beam, max_l, ...). */

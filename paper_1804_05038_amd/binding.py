@@ -63,7 +63,8 @@ class _Readout(C.Structure):
 class _Model(C.Structure):
     _fields_ = [("E_src", C.c_void_p), ("E_tgt", C.c_void_p), ("V_src", C.c_int), ("V_tgt", C.c_int), ("E", C.c_int),
                 ("enc_fwd", _Gru), ("enc_bwd", _Gru), ("att_W", _Mat), ("att_b", C.c_void_p),
-                ("dec", _Cgru), ("ro", _Readout), ("W_out", _Mat), ("b_out", C.c_void_p), ("E_tgt_codes", _RowCodes)]
+                ("dec", _Cgru), ("ro", _Readout), ("W_out", _Mat), ("b_out", C.c_void_p), ("E_tgt_codes", _RowCodes),
+                ("gx_r", C.c_void_p)]
 
 
 _lib = None
@@ -625,8 +626,10 @@ class Model:
                         dec.c, ro.c, W_out.c, b_out.data_ptr() if b_out is not None else None)
 
     @classmethod
-    def from_params(cls, ctx, p):
-        """Quantizes a dict of fp32 arrays (keys as in workloads.synth.full_model) on the device."""
+    def from_params(cls, ctx, p, gx_table=True):
+        """Quantizes a dict of fp32 arrays (keys as in workloads.synth.full_model) on the device.  gx_table: also
+        make the table of GRU r's input products over the target vocabulary (12 H bytes per token), with which
+        q8_translate keeps GRU r off the chain of dependent launches."""
         def mat(k):
             # rows of whole 64-byte k steps are also kept tile-packed: the matrix-core products of panels read
             # that copy (one contiguous KiB per operand)
@@ -646,6 +649,8 @@ class Model:
         # the target embeddings' codes, row by row, for decoding loops that hand codes from step to step
         m.E_tgt_codes = RowCodes(ctx, m.E_tgt, dec.r.Wx.ld)
         m.c.E_tgt_codes = m.E_tgt_codes.c
+        m.gx_r = gru_input_table(ctx, dec.r, m.E_tgt) if gx_table else None
+        m.c.gx_r = m.gx_r.data_ptr() if gx_table else None
         return m
 
 

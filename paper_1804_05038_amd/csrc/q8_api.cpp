@@ -1074,7 +1074,7 @@ q8_status q8_beam_result(q8_ctx *ctx, const void *state, int max_steps, int32_t 
 
 namespace {
 struct TranslateBufs {
-    size_t X, enc_h, P, y, s0, s1, cv, lp, idx, tok, state, yq, ys, cq, cs, sq, ss, total;
+    size_t X, enc_h, P, y, s0, s1, cv, lp, idx, tok, state, yq, ys, cq, cs, sq, ss, sm0, sm1, total;
 };
 TranslateBufs translate_layout(const q8_model *m, int l, int beam, int k, int max_steps)
 {
@@ -1092,6 +1092,8 @@ TranslateBufs translate_layout(const q8_model *m, int l, int beam, int k, int ma
     b.cq = take((size_t)beam * m->dec.q.Wx.ld); b.cs = take((size_t)beam * 4);
     // codes of the surviving states, handed from the search step to the next decoder step
     b.sq = take((size_t)beam * m->dec.r.Wh.ld); b.ss = take((size_t)beam * 4);
+    // s' of this step and of the next (the loop with GRU r ahead)
+    b.sm0 = take((size_t)beam * H * 4); b.sm1 = take((size_t)beam * H * 4);
     b.total = o;
     return b;
 }
@@ -1143,7 +1145,19 @@ q8_status q8_translate(q8_ctx *ctx, const q8_model *m, const int32_t *src_tokens
     // initial decoder state: the backward encoder state at the first source position
     if (!st) st = q8i_beam_init(ctx, state, beam, max_steps, enc_h, m->E_tgt, E, H, y, s[0]);
     int cur = 0, done = 0;
-    for (int t = 0; t < max_steps && !st && !done; ++t) {
+    // With the table of GRU r's input products the loop keeps GRU r off the chain of dependent launches: s' of a step
+    // is made by the step before it (the first by a plain GRU call), the states stay where GRU q wrote them.
+    float *sm[2] = {(float *)(top + b.sm0), (float *)(top + b.sm1)};
+    const bool ahead = m->gx_r != nullptr && aligned16(m->gx_r) && m->V_tgt < (1 << 24);
+    if (ahead && !st) st = gru_step_q8(ctx, &m->dec.r, y, s[0], beam, sm[0], nullptr);                  // Eq. 3, first step
+    for (int t = 0; ahead && t < max_steps && !st && !done; ++t) {
+        st = cgru_decoder_step_ahead_q8(ctx, &m->dec, P, enc_h, l, sm[t & 1], beam, s[1], cv, nullptr, &cc);
+        if (!st) st = output_logits_beam_ahead_q8(ctx, &m->ro, &m->W_out, m->b_out, s[1], y, cv, beam, k, state, m->E_tgt, E, lp,
+                                                  idx, &yc, &cc, Ec, &m->dec.r, m->gx_r, sm[(t + 1) & 1]);
+        if (!st && (t % 8 == 7))
+            st = q8i_beam_read(ctx, state, max_steps, nullptr, nullptr, nullptr, nullptr, &done);
+    }
+    for (int t = 0; !ahead && t < max_steps && !st && !done; ++t) {
         st = cgru_decoder_step_loop_q8(ctx, &m->dec, P, enc_h, l, y, s[cur], beam, s[cur ^ 1], cv, nullptr, nullptr, nullptr,
                                        &yc, &cc, &sc);
         // output layer, top-k and (in block 0 of the selection kernel) the beam update, which gathers the

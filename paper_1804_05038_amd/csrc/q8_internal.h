@@ -23,7 +23,8 @@
 #define Q8_MAX_BEAM 8
 #define Q8_MAX_COLS 1024            // vectors of one batched call
 #define Q8_WS_HEADER 262144
-#define Q8_GATE_PAUSE_DEFAULT 10     // short sleeps of the blocks that wait for the search step's decision before their first poll
+#define Q8_GATE_PAUSE_DEFAULT 8      // sleeps of about 0.45 us of the blocks that wait for the search step's decision, before their first poll
+                                     // (0 to 14 measured alike; later than that the first poll comes after the decision)
 #define Q8_WS_SCRATCH_SLOT 6144
 #define Q8_WS_ENC_ERR 6208          // set to 1 by the one-launch encoder if a wait gave up (zeroed before each such launch)
 #define Q8_WS_ATT_ERR 6212          // the same for the attention kernel whose blocks wait for each other

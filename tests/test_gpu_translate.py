@@ -508,7 +508,7 @@ def test_decoding_loop_with_gru_r_ahead_of_the_decision(q, ctx, oracle, dims, n,
     enc_h = ctx.f32(rng.standard_normal((l, 2 * H)).astype(np.float32))
     P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
     s0 = ctx.f32(rng.standard_normal(H).astype(np.float32))
-    gx = q.gru_input_table(ctx, m.dec.r, m.E_tgt)
+    gx = m.gx_r
     # the table against the plain product of a few rows
     rows = [0, m.E_tgt.shape[0] // 2, m.E_tgt.shape[0] - 1]
     assert_same(gx[rows], np_(q.q8_gemm_narrow(ctx, m.dec.r.Wx, m.E_tgt[rows].contiguous(), m.dec.r.bx)), "table rows")
@@ -528,3 +528,24 @@ def test_decoding_loop_with_gru_r_ahead_of_the_decision(q, ctx, oracle, dims, n,
         for i, (a, b) in enumerate(zip(got, ref)):
             assert_same(a, b, "run %d, step %d, output %d" % (rep, i // 6, i % 6))
         assert res[0].tolist() == ref_res[0].tolist() and res[1:] == ref_res[1:]
+
+
+@pytest.mark.parametrize("dims,beam,k,T", [(dict(V=13, E=16, H=32, A=16, R=16, w_std=0.5, b_std=0.3), 3, 5, 15),
+                                           (dict(V=500, E=64, H=128, A=64, R=64, w_std=0.2, b_std=0.1), 5, 8, 14),
+                                           (dict(), 5, 12, 10)])
+def test_translate_with_and_without_the_table_of_input_products(q, ctx, oracle, dims, beam, k, T):
+    """q8_translate on a model that brings the table of GRU r's input products (the loop with GRU r ahead of the
+    decision) and on the same model without it (the plain loop): the same tokens, score and step count, and
+    both equal to the oracle's."""
+    p = synth.full_model(seed=29, **dims)
+    with_table = q.Model.from_params(ctx, p)
+    without = q.Model.from_params(ctx, p, gx_table=False)
+    assert with_table.gx_r is not None and without.gx_r is None
+    m_ref = oracle.OracleModel(p)
+    V = p["E_src"].shape[0]
+    for seed, l in ((1, 4), (2, 9), (3, 17)):
+        src = np.random.default_rng(seed).integers(1, V, size=l).astype(np.int32)
+        a = q.q8_translate(ctx, with_table, src, beam=beam, k=k, max_steps=T)
+        b = q.q8_translate(ctx, without, src, beam=beam, k=k, max_steps=T)
+        assert a[0].tolist() == b[0].tolist() and a[1:] == b[1:]
+        _check_sentence(q, ctx, with_table, m_ref, src, beam, k, T)
