@@ -105,3 +105,83 @@ def test_batched_step_is_bit_reproducible(setup, S, l, reps):
         for i, (a, b) in enumerate(zip(got, ref)):
             assert torch.equal(a, b), "repetition %d: output %d differs from the first run" % (rep, i)
     q.q8_encode_check(ctx)
+
+
+def _ahead_calls(q, ctx, m, P, enc_h, n, s0, T):
+    """Bound calls of the loop with GRU r ahead: init, the first s', and the two calls for either parity of the step."""
+    E, H = m.E_tgt.shape[1], m.dec.r.H
+    state = torch.zeros(q.q8_beam_state_bytes(T), dtype=torch.uint8, device=ctx.device)
+    y, s = ctx.empty(n, E), ctx.empty(n, H)
+    s_mid = [ctx.empty(n, H), ctx.empty(n, H)]
+    yc, cc = q.Codes(ctx, n, m.dec.r.Wx.ld), q.Codes(ctx, n, m.dec.q.Wx.ld)
+    c0 = q.q8_beam_init(ctx, state, n, T, s0, m.E_tgt, y, s, bind=True)
+    cr = q.gru_step_q8(ctx, m.dec.r, y, s, h_out=s_mid[0], bind=True)
+    c1, c2, out = [], [], None
+    for i in (0, 1):
+        c = q.cgru_decoder_step_ahead_q8(ctx, m.dec, P, enc_h, s_mid[i], out=out, bind=True, ctx_codes=cc)
+        out = c.out
+        c1.append(c)
+        c2.append(q.output_logits_beam_ahead_q8(ctx, m.ro, m.W_out, m.b_out, out["s"], y, out["ctx"], state, m.E_tgt, m.dec.r, m.gx_r,
+                                                s_mid[1 - i], k=12, bind=True, y_codes=yc, ctx_codes=cc, E_codes=m.E_tgt_codes))
+
+    def run(steps=3):
+        c0.launch()
+        yc.invalidate()
+        cr.launch()
+        outs = []
+        for t in range(steps):
+            c1[t & 1].launch()
+            c2[t & 1].launch()
+            outs += [s_mid[t & 1].clone(), out["s"].clone(), out["ctx"].clone(), c2[t & 1].out["topk_logp"].clone(),
+                     c2[t & 1].out["topk_idx"].clone(), y.clone(), yc.q.clone(), s_mid[1 - (t & 1)].clone()]
+        outs.append(state.clone())
+        return outs
+    return run
+
+
+@pytest.mark.parametrize("n,l,reps", [(5, 30, 300), (8, 60, 100), (1, 7, 100)])
+def test_loop_with_gru_r_ahead_is_bit_reproducible(setup, n, l, reps):
+    """Three steps of a search with GRU r ahead of the decision (blocks of the selection kernel wait for the search
+    step's decision and compute the next s'; the readout's launch carries the recurrent product), the same bits
+    in every repetition."""
+    q, ctx, m = setup
+    H = m.dec.r.H
+    rng = np.random.default_rng(200 + n)
+    enc_h = ctx.f32(rng.standard_normal((l, 2 * H)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    s0 = ctx.f32(rng.standard_normal(H).astype(np.float32))
+    run = _ahead_calls(q, ctx, m, P, enc_h, n, s0, 4)
+    ref = run()
+    assert all(torch.isfinite(t).all() for t in ref if t.is_floating_point())
+    for rep in range(reps):
+        got = run()
+        for i, (a, b) in enumerate(zip(got, ref)):
+            assert torch.equal(a, b), "repetition %d: output %d differs from the first run" % (rep, i)
+    q.q8_encode_check(ctx)
+
+
+def test_wait_for_the_decision_that_gives_up_is_reported_and_the_next_search_is_good(setup):
+    """With a bound of one poll the blocks that wait for the search step's decision give up at once (it comes
+    microseconds later): the kernel still ends normally with every index inside its table, q8_encode_check
+    reports it and clears the exchange words, and the same search run again gives the first run's bits."""
+    q, ctx, m = setup
+    H = m.dec.r.H
+    rng = np.random.default_rng(9)
+    enc_h = ctx.f32(rng.standard_normal((12, 2 * H)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    s0 = ctx.f32(rng.standard_normal(H).astype(np.float32))
+    run = _ahead_calls(q, ctx, m, P, enc_h, 5, s0, 4)
+    good = run()
+    q.q8_encode_check(ctx)
+    try:
+        q.q8_attention_options(ctx, exchange=True, spin_limit=1)
+        run()
+        with pytest.raises(q.Q8Error):
+            q.q8_encode_check(ctx)
+    finally:
+        q.q8_attention_options(ctx, exchange=True, spin_limit=0)
+    q.q8_encode_check(ctx)
+    again = run()
+    q.q8_encode_check(ctx)
+    for i, (a, b) in enumerate(zip(again, good)):
+        assert torch.equal(a, b), "output %d after the abandoned run" % i
