@@ -316,7 +316,10 @@ q8_status q8_encode_check(q8_ctx *ctx);
  * together must fit the device together (l n_beam blocks of 1024 threads each, two per compute
  * unit); give the contexts beyond that exchange = 0.  The same holds for q8_encoder_options'
  * one-launch recurrence (2 H / 8 blocks of 512 threads) and for the batched step's one-kernel
- * GRU (H / 32 x ceil(slots / 48) blocks of 768 threads, one per compute unit). */
+ * GRU (H / 32 x ceil(slots / 48) blocks of 768 threads, one per compute unit).  The waits inside the
+ * selection kernels (output_logits_beam_q8 and its forms, output_logits_beam_ahead_q8's blocks that
+ * compute the next GRU r, output_logits_beam_batch_q8) are for blocks of lower index in the same
+ * launch, which the device has started before the block that waits: they end whatever else runs. */
 q8_status q8_attention_options(q8_ctx *ctx, int exchange, int spin_limit);
 
 /* ---- search (Section 3 only says the beam is smaller than 8; these are the rules) ----
