@@ -185,3 +185,37 @@ def test_wait_for_the_decision_that_gives_up_is_reported_and_the_next_search_is_
     q.q8_encode_check(ctx)
     for i, (a, b) in enumerate(zip(again, good)):
         assert torch.equal(a, b), "output %d after the abandoned run" % i
+
+
+def test_loop_with_gru_r_ahead_replayed_from_a_graph(setup):
+    """The launch mode of the benchmark's headline: one HIP graph holds a whole search of the loop with GRU r ahead
+    (full-size model, beam 5); it is replayed four times with eager work and synchronizations between the replays,
+    and every replay's outputs and search state equal the eager run's bit for bit."""
+    q, ctx, m = setup
+    H, T = m.dec.r.H, 6
+    rng = np.random.default_rng(31)
+    enc_h = ctx.f32(rng.standard_normal((30, 2 * H)).astype(np.float32))
+    P = q.q8_gemm_narrow(ctx, m.att_W, enc_h, m.att_b)
+    s0 = ctx.f32(rng.standard_normal(H).astype(np.float32))
+    ref = _ahead_calls(q, ctx, m, P, enc_h, 5, s0, T)(steps=T)
+    q.q8_encode_check(ctx)
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        gctx = q.Context("cuda:0", stream=side)
+        run = _ahead_calls(q, gctx, m, P, enc_h, 5, s0, T)
+        run(steps=T)
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            captured = run(steps=T)          # (the clones it returns are made inside the graph: they hold every step's outputs)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        g.replay()
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(captured, ref)):
+            assert torch.equal(a, b), "replay %d: output %d differs from the eager run" % (rep, i)
+        q.q8_gemv(ctx, m.att_W, enc_h[0])    # unrelated eager work between replays
+        for t in captured:
+            t.zero_()                        # (a replay must write every output again)
+        torch.cuda.synchronize()
+    q.q8_encode_check(gctx)
