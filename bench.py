@@ -670,6 +670,42 @@ def main():
         except Exception as e:  # graph capture only changes how the launches reach the GPU
             graph_us = "unavailable: %s" % (str(e).splitlines()[0][:120])
 
+    # ---- the same step with the plain calls (cgru_decoder_step_q8 + output_logits_beam_q8: GRU r multiplies W_x^r by
+    # the gathered embedding rows inside the step, seven launches), same protocol, reported beside the value
+    plain = None
+    if gx is not None and not args.quick:
+        plain = {"calls": "cgru_decoder_step_q8 + output_logits_beam_q8 (codes handed from step to step), seven launches per step",
+                 "steps_per_s_beam5_eager": 1.0 / time_loop(torch, loop5.step, args.steps, args.warmup)}
+        if not args.no_graph:
+            try:
+                side = torch.cuda.Stream()
+                with torch.cuda.stream(side):
+                    pctx = q.Context("cuda:0", stream=side)
+                    ploop = DecodeLoop(q, pctx, m, P, enc_h, BEAM, rng)
+                    ploop.step()
+                    side.synchronize()
+                    ploop.t = 0
+                    pg = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(pg, stream=side):
+                        for _ in range(MAX_STEPS):
+                            ploop.step()
+                torch.cuda.synchronize()
+                for _ in range(3):
+                    pg.replay()
+                reps = []
+                for _ in range(9):
+                    torch.cuda.synchronize()
+                    t0 = time.perf_counter()
+                    for _ in range(10):
+                        pg.replay()
+                    torch.cuda.synchronize()
+                    reps.append((time.perf_counter() - t0) / (10 * MAX_STEPS))
+                plain["steps_per_s_beam5"] = 1.0 / float(np.median(reps))
+                plain["median_us_per_step"] = float(np.median(reps)) * 1e6
+                plain["int8_weight_bytes_per_step"] = 15204352 + 1835008 + 25600000
+            except Exception as e:
+                plain["graph"] = "unavailable: %s" % (str(e).splitlines()[0][:120])
+
     eager1 = time_loop(torch, hloop1.step, args.steps, args.warmup) if not args.quick else float("nan")
 
     # ---- several sentences at once: one context, stream and captured 100-step search each.  A
@@ -787,11 +823,14 @@ def main():
         "config": {"workload": "full decoder step for one sentence: conditional-GRU step + output layer + beam update "
                                "(embedding 512, hidden 1024, attention 1024, vocabulary 50000, source length 30), "
                                "beam 5, top-12", "launch_mode": mode, "int8_weight_bytes_per_step": weights_per_step,
-                   "loop": ("cgru_decoder_step_ahead_q8 + output_logits_beam_ahead_q8: GRU r's input products from a table over the "
-                            "vocabulary (614 MB fp32), its recurrent products in the readout's launch, its gates in "
-                            "blocks of the selection kernel; same bits as the plain calls") if gx is not None else
+                   "loop": ("cgru_decoder_step_ahead_q8 + output_logits_beam_ahead_q8, the loop q8_translate runs: every product, "
+                            "activation and search step of the plain calls is computed in every step except W_x^r q(y) of GRU r "
+                            "(1.5 of the step's 42.6 MB of weights), which is a function of the token alone and is read from a table "
+                            "over the vocabulary made by the same 8-bit product at model load (614 MB fp32); GRU r's recurrent "
+                            "products run in the readout's launch, its gates in blocks of the selection kernel; six launches per "
+                            "step, every output bit-identical to the plain calls, whose rate is in plain_calls") if gx is not None else
                            "cgru_decoder_step_q8 + output_logits_beam_q8"},
-        "steps_per_s_beam5_eager": 1.0 / eager5, "us_per_step_graph": graph_us,
+        "steps_per_s_beam5_eager": 1.0 / eager5, "us_per_step_graph": graph_us, "plain_calls": plain,
         "concurrent_sentences": concurrent,
         "weights_GBps_whole_step": weights_per_step / best5 / 1e9,
         "roofline": {"bound": "hbm", "kernel": "out_logits8_kernel<2, 8, true> (50000x512 int8 vocabulary matrix, 5 hypotheses)",
