@@ -107,3 +107,19 @@ def test_loop_forms_without_a_context_return_the_null_code_and_drop_the_codes(li
     args = nulls(lib.q8_beam_update_batch_loop, 4)
     assert lib.q8_beam_update_batch_loop(*args, None, ps, pyn, psn) == 1
     assert (yn.valid, sn.valid) == (0, 0) and s.valid == 1
+
+    # the loop with GRU r ahead of the decision, and the panel output layer with the search steps in its launch
+    cx, pcx = given(1)
+    args = nulls(lib.cgru_decoder_step_ahead_q8, 1)
+    assert lib.cgru_decoder_step_ahead_q8(*args, pcx) == 1
+    assert cx.valid == 0
+
+    y, py = given(2); cx, pcx = given(1)
+    args = nulls(lib.output_logits_beam_ahead_q8, 6)
+    assert lib.output_logits_beam_ahead_q8(*args, py, pcx, None, None, None, None) == 1
+    assert y.valid == 0 and cx.valid == 1
+
+    s, ps = given(1); y, py = given(1); cx, pcx = given(1); sn, psn = given(2)
+    args = nulls(lib.output_logits_beam_batch_q8, 5)
+    assert lib.output_logits_beam_batch_q8(*args, ps, py, pcx, psn, None) == 1
+    assert (y.valid, sn.valid) == (0, 0) and (s.valid, cx.valid) == (1, 1)
